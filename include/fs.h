@@ -1,0 +1,244 @@
+/*
+ * fs.h — C ABI of the stitched-kernel executor for AMD MI355X (gfx950).
+ *
+ * The library executes a *fusion plan*: a DAG of typed, fine-grained, memory-bound
+ * tensor ops (elementwise, broadcast, transpose, row/column reduction) on 2-D
+ * row-major tensors.  Each fused group of the plan runs as ONE stitched GPU kernel:
+ * elementwise producers are composed into their consumers in registers (the paper's
+ * "thread composition", Section 1 / Figure 2(a)), and ops that need a different
+ * parallel loop - reductions and the ops that consume a reduction result - are
+ * composed through on-chip shared memory inside the same kernel ("block
+ * composition" / stitching, Section 1 / Figure 2(b), Section 5.2 / Algorithm 2).
+ *
+ * Conventions
+ *   - Every function returns fs_status.  Nothing throws or aborts across the ABI.
+ *     fs_last_error() returns a thread-local, human-readable message for the last
+ *     non-FS_OK status returned on the calling thread.
+ *   - "host" pointers are ordinary CPU memory; "device" pointers are HIP device
+ *     memory of the current device.  The caller owns every device buffer (inputs,
+ *     outputs, workspace) and the stream; the library owns only fs_plan objects
+ *     (host memory plus loaded code objects).
+ *   - Tensors are dense, contiguous, row-major [rows, cols].  FS_F32 is IEEE
+ *     binary32, FS_BF16 is bfloat16 (raw uint16 bits), FS_U8 is a predicate byte
+ *     holding 0 or 1.  Every device tensor pointer must be 16-byte aligned.
+ *   - A plan is immutable after fs_plan_create.  fs_plan_run may be called
+ *     concurrently on one plan only with distinct workspaces.
+ */
+#ifndef FS_H_
+#define FS_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FS_ABI_VERSION 1u
+
+typedef struct fs_plan fs_plan; /* opaque */
+
+typedef enum {
+  FS_OK = 0,
+  FS_ERR_INVALID_ARG = 1, /* null pointer, bad abi_version, misaligned device pointer ... */
+  FS_ERR_BAD_GRAPH = 2,   /* operand id >= node id (cycle / dangling id), bad arity, bad output id */
+  FS_ERR_SHAPE = 3,       /* operand / result shapes inconsistent with the opcode */
+  FS_ERR_DTYPE = 4,       /* operand / result dtypes inconsistent with the opcode */
+  FS_ERR_UNSUPPORTED = 5, /* valid graph, but a caller-given grouping cannot be one stitched kernel */
+  FS_ERR_LDS_BUDGET = 6,  /* a caller-given group needs more LDS than lds_budget_bytes */
+  FS_ERR_WORKSPACE = 7,   /* workspace null, misaligned or smaller than fs_plan_workspace_bytes */
+  FS_ERR_COMPILE = 8,     /* run-time compilation of a group's kernel failed */
+  FS_ERR_HIP = 9,         /* a HIP runtime call failed (message holds the HIP error string) */
+  FS_ERR_OOM = 10         /* host allocation failed */
+} fs_status;
+
+typedef enum { FS_F32 = 0, FS_BF16 = 1, FS_U8 = 2 } fs_dtype;
+
+/*
+ * Opcodes.  The four op classes of the paper's problem statement (Section 2.1):
+ * elementwise, shape modulation (here: the two broadcasts and Transpose - with
+ * 2-D row-major tensors Reshape/Bitcast have nothing to do), Reduction
+ * (sum/max/min/mean, Section 1) and - deliberately absent - BatchMatMul.
+ */
+typedef enum {
+  FS_INPUT = 0,  /* external tensor; the k-th FS_INPUT node (in id order) is inputs[k] of fs_plan_run */
+  FS_CONST = 1,  /* tensor of the declared shape filled with attr_f; never materialised */
+  /* unary elementwise, shape and arity (1): out[i,j] = f(in0[i,j]) */
+  FS_NEG = 2,
+  FS_ABS = 3,
+  FS_EXP = 4,
+  FS_LOG = 5,
+  FS_TANH = 6,
+  FS_SIGMOID = 7,   /* 1 / (1 + exp(-x)) */
+  FS_SQRT = 8,
+  FS_RSQRT = 9,     /* 1 / sqrt(x) */
+  FS_RCP = 10,      /* 1 / x */
+  FS_GELU_TANH = 11,/* 0.5 x (1 + tanh(sqrt(2/pi) (x + 0.044715 x^3))) */
+  FS_CONVERT = 12,  /* value-preserving change of dtype (round to nearest even when narrowing) */
+  /* binary elementwise, arity 2, all three shapes equal */
+  FS_ADD = 13,
+  FS_SUB = 14,
+  FS_MUL = 15,
+  FS_DIV = 16,
+  FS_MAX = 17,      /* IEEE maxNum */
+  FS_MIN = 18,      /* IEEE minNum */
+  /* predicates */
+  FS_CMP = 19,      /* arity 2, result FS_U8: attr_i is an fs_cmp */
+  FS_SELECT = 20,   /* arity 3: in0 is FS_U8; out = in0 ? in1 : in2 (bits of the chosen operand) */
+  /* shape modulation; broadcasts are never materialised (the paper inlines such
+   * trivial ops by thread composition, Section 4.3) */
+  FS_BCAST_ROWVEC = 21, /* in0 [1,C] -> out [R,C]: out[i,j] = in0[0,j] */
+  FS_BCAST_COLVEC = 22, /* in0 [R,1] -> out [R,C]: out[i,j] = in0[i,0] */
+  FS_TRANSPOSE = 23,    /* in0 [R,C] -> out [C,R]: out[j,i] = in0[i,j] */
+  /* reductions; attr_i is an fs_reduce_kind */
+  FS_REDUCE_ROW = 24,   /* in0 [R,C] -> out [R,1], reduces over the columns of each row */
+  FS_REDUCE_COL = 25,   /* in0 [R,C] -> out [1,C], reduces over the rows of each column */
+  FS_NUM_OPCODES = 26
+} fs_opcode;
+
+typedef enum { FS_CMP_GT = 0, FS_CMP_GE = 1, FS_CMP_LT = 2, FS_CMP_LE = 3, FS_CMP_EQ = 4, FS_CMP_NE = 5 } fs_cmp;
+typedef enum { FS_RED_SUM = 0, FS_RED_MAX = 1, FS_RED_MIN = 2, FS_RED_MEAN = 3 } fs_reduce_kind;
+
+/*
+ * One node of the DAG.  The node id is its index in fs_graph_desc.nodes, and the
+ * array must be topologically ordered: every in[k] < id.  rows/cols/dtype declare
+ * the node's OUTPUT tensor and are checked against the opcode's rule.
+ * Arithmetic is done in fp32 and the value is rounded once to the node's dtype, so
+ * a FS_BF16 node holds a bf16-representable value even when it never leaves registers.
+ */
+typedef struct {
+  int32_t opcode; /* fs_opcode */
+  int32_t dtype;  /* fs_dtype of the result */
+  int32_t rows;
+  int32_t cols;
+  int32_t num_in; /* 0..3 */
+  int32_t in[3];  /* operand node ids; unused entries ignored */
+  int32_t attr_i; /* fs_cmp for FS_CMP, fs_reduce_kind for FS_REDUCE_*, else 0 */
+  float attr_f;   /* value of FS_CONST, else 0 */
+} fs_node;
+
+/* Execution mode. */
+#define FS_MODE_STITCHED 0u /* fused groups, one kernel launch per group */
+#define FS_MODE_UNFUSED 1u  /* one launch per compute node, every intermediate in HBM; the
+                               comparison executor for launch count and HBM traffic
+                               (the role of the per-op baseline in Section 6.3) */
+
+/*
+ * Optional schedule override, applied to every group it is legal for (0 = let the
+ * scheduler decide).  In the paper's terms (Section 4.1) every group runs a Row
+ * schedule with split_dim = 0: `max_workgroups` bounds `blocks`; lanes_per_row
+ * says how many lanes cooperate on one row (a power of two, 1..1024, the analogue
+ * of reduce_warps in Section 4.4); wg_threads is the workgroup size (multiple of 64,
+ * <= 1024).  max_workgroups = 1 gives the always-valid single-block schedule of
+ * Section 4.3.
+ */
+typedef struct {
+  int32_t lanes_per_row;
+  int32_t wg_threads;
+  int32_t max_workgroups;
+  int32_t reserved;
+} fs_sched_hint;
+
+typedef struct {
+  uint32_t abi_version;          /* FS_ABI_VERSION */
+  int32_t num_nodes;
+  const fs_node* nodes;          /* host; copied by fs_plan_create */
+  int32_t num_outputs;
+  const int32_t* outputs;        /* host; node ids that are plan outputs (not INPUT/CONST/BCAST_*), distinct */
+  const int32_t* group_of_node;  /* host; NULL => the library groups greedily.  Else one group id >= 0 per
+                                    node (ignored for INPUT/CONST/BCAST_* nodes, which are inlined into
+                                    each consumer): the caller's fusion plan.  Ignored in FS_MODE_UNFUSED. */
+  uint32_t mode;                 /* FS_MODE_* */
+  int32_t lds_budget_bytes;      /* per-workgroup LDS limit for one group; 0 => 32768 */
+  const fs_sched_hint* hint;     /* host; may be NULL */
+} fs_graph_desc;
+
+/* What the scheduler decided for one group (one kernel launch). */
+typedef struct {
+  int32_t num_nodes;        /* compute nodes executed by this kernel */
+  int32_t dom_rows;         /* the group's work space [dom_rows, dom_cols] (Section 4.1: output shape of the root) */
+  int32_t dom_cols;
+  int32_t lanes_per_row;    /* lanes that share one row */
+  int32_t vec_elems;        /* elements per vector memory access (16 bytes when shapes allow) */
+  int32_t elems_per_lane;   /* columns held by one lane for each [R,C] value */
+  int32_t wg_threads;       /* workgroup size */
+  int32_t rows_per_iter;    /* rows a workgroup processes per loop trip = wg_threads / lanes_per_row */
+  int32_t grid;             /* workgroups launched = `blocks` of Section 4.1 */
+  int32_t lds_bytes;        /* static LDS the kernel uses */
+  int32_t num_row_reduces;  /* stitched row reductions */
+  int32_t num_col_reduces;  /* two-stage column reductions */
+  int32_t num_ext_inputs;   /* tensors read from HBM */
+  int32_t num_ext_outputs;  /* tensors written to HBM */
+  uint64_t min_hbm_bytes;   /* external inputs once + outputs once */
+  uint64_t scratch_bytes;   /* column-reduction partials + tickets inside the plan workspace */
+} fs_group_info;
+
+/*
+ * fs_plan_create: validate the DAG (ids, arity, shapes, dtypes), form groups
+ * (given or greedy; a cut-down of the paper's Algorithm 1 with its SchdConsistent
+ * checks, Section 3.2), pick each group's schedule (Section 4) and LDS plan
+ * (Section 5.1), generate and compile each group's kernel for gfx950
+ * (Section 5.2 / Algorithm 2).  Host-only: needs no GPU.  desc and everything it points
+ * to may be freed after the call.  *out_plan is set only on FS_OK.
+ */
+fs_status fs_plan_create(const fs_graph_desc* desc, fs_plan** out_plan);
+
+/* Frees the plan and unloads its code objects.  NULL is FS_OK. */
+fs_status fs_plan_destroy(fs_plan* plan);
+
+/* Bytes of device workspace fs_plan_run needs: tensors that cross group boundaries,
+ * column-reduction partials and ticket counters.  May be 0. */
+fs_status fs_plan_workspace_bytes(const fs_plan* plan, size_t* bytes);
+
+/*
+ * fs_plan_run: enqueue the plan's launches on `hip_stream` (a hipStream_t; NULL = the
+ * null stream) of the current device.  Asynchronous: no allocation, no
+ * synchronisation, no host<->device copy.
+ *   inputs   host array of device pointers, one per FS_INPUT node in id order
+ *   outputs  host array of device pointers, one per entry of desc.outputs, same order
+ *   workspace / workspace_bytes  device buffer of >= fs_plan_workspace_bytes bytes,
+ *            256-byte aligned; may be NULL when 0 bytes are needed.  The ticket
+ *            counters inside it must be zero before the FIRST run on that buffer
+ *            (fs_plan_workspace_init does it); every run leaves them zero again.
+ * Inputs must not alias outputs or the workspace.  The first run on a device loads
+ * the plan's code objects onto it.
+ */
+fs_status fs_plan_run(fs_plan* plan, const void* const* inputs, void* const* outputs,
+                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Enqueue a fill kernel on `hip_stream` that zeroes the ticket counters of a fresh workspace. */
+fs_status fs_plan_workspace_init(fs_plan* plan, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Plan-level figures for the metric: groups (= launches per run in stitched mode),
+ * launches per run, minimal HBM bytes of the whole plan (plan inputs once + plan
+ * outputs once) and the bytes this plan's launches move (sum over groups of
+ * external inputs + outputs).  Any out pointer may be NULL. */
+fs_status fs_plan_stats(const fs_plan* plan, int32_t* num_groups, int32_t* num_launches,
+                        uint64_t* min_hbm_bytes, uint64_t* launched_hbm_bytes);
+
+fs_status fs_plan_group_info(const fs_plan* plan, int32_t group, fs_group_info* out_info);
+
+/* The group each node was assigned to (-1 for INPUT/CONST/BCAST_*). out has room for num_nodes entries. */
+fs_status fs_plan_node_groups(const fs_plan* plan, int32_t* out, int32_t num_nodes);
+
+/* The generated HIP source of one group's kernel (owned by the plan; valid until destroy). */
+fs_status fs_plan_group_source(const fs_plan* plan, int32_t group, const char** out_src);
+
+/* Name of the kernel symbol of one group (for matching profiler output). */
+fs_status fs_plan_group_kernel_name(const fs_plan* plan, int32_t group, const char** out_name);
+
+/*
+ * fs_copy_probe: a plain streaming copy of `bytes` bytes (multiple of 16) from src
+ * to dst (both device, 16-byte aligned) with 128-bit accesses, enqueued on
+ * `hip_stream`.  It exists to measure the achievable HBM streaming rate of the
+ * device (the practical ceiling under the 8 TB/s datasheet peak) and to calibrate
+ * profiler byte counters against a kernel of known traffic.
+ */
+fs_status fs_copy_probe(const void* src, void* dst, size_t bytes, void* hip_stream);
+
+const char* fs_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FS_H_ */

@@ -1,0 +1,74 @@
+/*
+ * fso.h - CPU ORACLE for the stitched-kernel executor.  TEST INFRASTRUCTURE ONLY.
+ *
+ * A plain, slow, one-op-at-a-time interpreter of a fusion plan (a DAG of
+ * elementwise / broadcast / transpose / reduction ops on 2-D row-major tensors, the
+ * op classes of the paper's Section 2.1).  Fusion changes where intermediates live, not
+ * what is computed (Section 4.1 names footprint and launch count as the objectives;
+ * Section 5.1.1 recomputes "to ensure correctness"), so the reference result of a fused
+ * kernel is simply the op-by-op evaluation of its DAG: that is all this file does.
+ *
+ * Only tests, the smoke check and the benchmark's cpu_baseline leg may call it.
+ * It shares no code, header or table with the GPU library: the structs below are
+ * this library's own declaration of the plan layout.
+ *
+ * Parity pins (tests/test_oracle_pins.py): closed forms, invariants, brute force
+ * in pure Python, numpy.float32 bit-equality of the basic arithmetic, torch CPU
+ * fp64 softmax / layer_norm / gelu.  The paper prints no numerical example, so no
+ * pin comes from paper-printed values.
+ */
+#ifndef FSO_H_
+#define FSO_H_
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { FSO_F32 = 0, FSO_BF16 = 1, FSO_U8 = 2 };
+
+enum {
+  FSO_INPUT = 0, FSO_CONST = 1,
+  FSO_NEG = 2, FSO_ABS = 3, FSO_EXP = 4, FSO_LOG = 5, FSO_TANH = 6, FSO_SIGMOID = 7, FSO_SQRT = 8,
+  FSO_RSQRT = 9, FSO_RCP = 10, FSO_GELU_TANH = 11, FSO_CONVERT = 12,
+  FSO_ADD = 13, FSO_SUB = 14, FSO_MUL = 15, FSO_DIV = 16, FSO_MAX = 17, FSO_MIN = 18,
+  FSO_CMP = 19, FSO_SELECT = 20,
+  FSO_BCAST_ROWVEC = 21, FSO_BCAST_COLVEC = 22, FSO_TRANSPOSE = 23,
+  FSO_REDUCE_ROW = 24, FSO_REDUCE_COL = 25
+};
+enum { FSO_GT = 0, FSO_GE = 1, FSO_LT = 2, FSO_LE = 3, FSO_EQ = 4, FSO_NE = 5 };
+enum { FSO_SUM = 0, FSO_MAX_ = 1, FSO_MIN_ = 2, FSO_MEAN = 3 };
+
+typedef struct {
+  int32_t opcode, dtype, rows, cols, num_in, in[3], attr_i;
+  float attr_f;
+} fso_node;
+
+typedef struct {
+  int32_t num_nodes;
+  const fso_node* nodes;   /* topological: every operand id < node id */
+  int32_t num_outputs;
+  const int32_t* outputs;
+} fso_graph;
+
+/*
+ * Evaluate the DAG on host buffers.
+ *   host_in[k]   the k-th FSO_INPUT node's tensor in its dtype (f32 / bf16 bits as uint16 / u8)
+ *   host_out[k]  buffer for outputs[k] in that node's dtype
+ *   num_threads  OpenMP threads for the independent outer loop of each op (>= 1)
+ *   round_nodes  1: every node is rounded to its declared dtype before any consumer
+ *                   reads it (the reference of record);
+ *                0: nodes stay in fp64, rounding only at plan outputs (a companion
+ *                   used to flag ill-conditioned elements, never the pass/fail reference).
+ * Returns 0, or a negative code: -1 bad argument, -2 bad graph, -3 out of memory.
+ */
+int fso_run(const fso_graph* g, const void* const* host_in, void* const* host_out, int num_threads, int round_nodes);
+
+/* The two roundings, exported so tests can pin them on their own. */
+double fso_round_f32(double x);
+double fso_round_bf16(double x);
+
+#ifdef __cplusplus
+}
+#endif
+#endif
