@@ -1,0 +1,323 @@
+// fs_codegen.cpp - emits the HIP source of one fused group's stitched kernel.
+//
+// Structure of the emitted kernel (the realisation of Algorithm 2, Section 5.2):
+//   - an op that is neither a root, nor a reduction, nor kept in shared memory is emitted
+//     inline, element by element, into the registers of the lane that owns the element
+//     (the ElementalIrEmitter branch: thread composition);
+//   - a row reduction ends a stage: lanes fold their own elements, the wavefront folds by
+//     lane permutes, wavefronts of one row meet in LDS (EmitWriteSharedArray), and the
+//     consumers of the result continue in the same kernel (block composition);
+//   - roots are written to global memory as soon as they exist (EmitWriteOutputArray).
+// The body is straight-line code over the building blocks of fs_device.h; names are local
+// indices, so two groups with the same structure produce the same text and share a binary.
+#include <algorithm>
+#include <cstring>
+#include <sstream>
+
+#include "fs_internal.h"
+
+namespace fs {
+
+namespace {
+
+struct Emitter {
+  const Graph& g;
+  GroupPlan& gp;
+  std::ostringstream os;
+  std::map<int, int> local;  // node id -> local index
+  std::vector<char> in_set;
+
+  Emitter(const Graph& g_, GroupPlan& gp_) : g(g_), gp(gp_), in_set(g_.n(), 0) {}
+
+  int loc(int node) {
+    auto it = local.find(node);
+    if (it != local.end()) return it->second;
+    const int idx = (int)local.size();
+    local[node] = idx;
+    return idx;
+  }
+  static const char* prefix(Kind k) { return k == KIND_FULL ? "v" : k == KIND_COLV ? "s" : "r"; }
+  std::string name(int node, Kind k) { return std::string(prefix(k)) + std::to_string(loc(node)); }
+
+  static std::string literal(float f, int dtype) {
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    char buf[96];
+    snprintf(buf, sizeof(buf), "fs_round<%d>(fs_lit(0x%08xu /* %.9g */))", dtype, u, (double)f);
+    return buf;
+  }
+
+  Kind classify(const fs_node& n) const {
+    if (n.rows == gp.R && n.cols == gp.C) return KIND_FULL;
+    if (n.rows == gp.R && n.cols == 1) return KIND_COLV;
+    if (n.rows == 1 && n.cols == gp.C) return KIND_ROWV;
+    return KIND_NONE;
+  }
+
+  // expression for element e of operand `o` (indexable by `e` inside an unrolled loop)
+  std::string ref(int o) {
+    const fs_node& n = g.nodes[o];
+    if (n.opcode == FS_CONST) return literal(n.attr_f, n.dtype);
+    int src = o;
+    if (n.opcode == FS_BCAST_ROWVEC || n.opcode == FS_BCAST_COLVEC) {
+      src = n.in[0];
+      if (g.nodes[src].opcode == FS_CONST) return literal(g.nodes[src].attr_f, g.nodes[src].dtype);
+    }
+    const Kind k = gp.kind.at(src);
+    if (k == KIND_COLV) return name(src, k);
+    return name(src, k) + "[e]";
+  }
+
+  std::string expr(const fs_node& n) {
+    auto A = [&]() { return ref(n.in[0]); };
+    auto B = [&]() { return ref(n.in[1]); };
+    auto Cc = [&]() { return ref(n.in[2]); };
+    switch (n.opcode) {
+      case FS_NEG: return "-(" + A() + ")";
+      case FS_ABS: return "__builtin_fabsf(" + A() + ")";
+      case FS_EXP: return "fs_exp(" + A() + ")";
+      case FS_LOG: return "fs_log(" + A() + ")";
+      case FS_TANH: return "fs_tanh(" + A() + ")";
+      case FS_SIGMOID: return "fs_sigmoid(" + A() + ")";
+      case FS_SQRT: return "fs_sqrt(" + A() + ")";
+      case FS_RSQRT: return "fs_rsqrt(" + A() + ")";
+      case FS_RCP: return "fs_rcp(" + A() + ")";
+      case FS_GELU_TANH: return "fs_gelu_tanh(" + A() + ")";
+      case FS_CONVERT: return "(" + A() + ")";
+      case FS_ADD: return "(" + A() + " + " + B() + ")";
+      case FS_SUB: return "(" + A() + " - " + B() + ")";
+      case FS_MUL: return "(" + A() + " * " + B() + ")";
+      case FS_DIV: return "fs_div(" + A() + ", " + B() + ")";
+      case FS_MAX: return "fs_max(" + A() + ", " + B() + ")";
+      case FS_MIN: return "fs_min(" + A() + ", " + B() + ")";
+      case FS_CMP: {
+        static const char* ops[] = {">", ">=", "<", "<=", "==", "!="};
+        return "((" + A() + " " + ops[n.attr_i] + " " + B() + ") ? 1.0f : 0.0f)";
+      }
+      case FS_SELECT: return "((" + A() + " != 0.0f) ? " + B() + " : " + Cc() + ")";
+      case FS_REDUCE_ROW:  // degenerate (one column): the value itself
+      case FS_REDUCE_COL:  // degenerate (one row)
+        return "(" + A() + ")";
+    }
+    return "0.0f";
+  }
+
+  std::string tmpl_row() const {  // template arguments shared by the row load/store/reduce blocks
+    std::ostringstream t;
+    t << "V, NVL, L, NV, RAGGED";
+    return t.str();
+  }
+
+  // an array holding operand `o` as a full slice (needed by reductions / transposed stores)
+  std::string as_array(int o, const std::string& tag) {
+    const fs_node& n = g.nodes[o];
+    if (!op_is_free(n.opcode) || n.opcode == FS_INPUT) {
+      const Kind k = gp.kind.at(o);
+      if (k != KIND_COLV) return name(o, k);
+    }
+    const std::string t = "t" + tag;
+    os << "    float " << t << "[E];\n    _Pragma(\"unroll\") for (int e = 0; e < E; ++e) " << t << "[e] = " << ref(o) << ";\n";
+    return t;
+  }
+
+  void emit_store(const ExtTensor& e, const std::string& indent) {
+    const std::string nm = name(e.node, gp.kind.at(e.node));
+    if (e.transposed) return;  // emitted with the node
+    if (e.kind == KIND_FULL)
+      os << indent << "fs_store_row<" << e.dtype << ", " << tmpl_row() << ">(" << nm << ", a.p[" << e.arg << "], row0, lir, rok);\n";
+    else if (e.kind == KIND_COLV)
+      os << indent << "if (rok && lir == 0) fs_store1<" << e.dtype << ">(a.p[" << e.arg << "], row, " << nm << ");\n";
+  }
+
+  const ExtTensor* find_out(int node) const {
+    for (const ExtTensor& e : gp.ext_out)
+      if (e.node == node) return &e;
+    return nullptr;
+  }
+
+  void run(const std::string& kname) {
+    const Schedule& s = gp.s;
+    for (int m : gp.members) in_set[m] = 1;
+    const int R = gp.R, C = gp.C;
+    const int NP = (int)(gp.ext_in.size() + gp.ext_out.size());
+    const int K = (int)gp.col_reduces.size();
+    const int WPR = s.L > 64 ? s.L / 64 : 1;
+    const int KB = std::max(1, gp.max_batched_reduces);
+    const bool xwave = !gp.row_reduces.empty() && s.L > 64;
+
+    // fixed local numbering: external inputs first, then members
+    for (const ExtTensor& e : gp.ext_in) loc(e.node);
+    for (int m : gp.members) loc(m);
+
+    os << "// work space [R," << C << "], " << s.L << " lanes/row, " << s.E << " elements/lane, workgroup " << s.WG << "\n";
+    os << "struct " << kname << "_args { void* p[" << NP << "]; float* part; fs_u32* tickets; int R; int n_iters; };\n";
+    if (K > 0) {
+      os << "struct " << kname << "_kinds { static FS_DEV float op(int k, float a, float b) { switch (k) {";
+      for (int k = 0; k < K; ++k)
+        os << " case " << k << ": return fs_red_op<" << g.nodes[gp.col_reduces[k]].attr_i << ">(a, b);";
+      os << " } return a; } };\n";
+    }
+    os << "extern \"C\" __global__ void __launch_bounds__(" << s.WG << ") " << kname << "(const " << kname << "_args a) {\n";
+    os << "  constexpr int V = " << s.V << ", NVL = " << s.NVL << ", L = " << s.L << ", NV = " << s.NV << ", E = NVL * V, WG = " << s.WG
+       << ", G = WG / L, C = " << C << ";\n";
+    os << "  constexpr bool RAGGED = " << (s.ragged ? "true" : "false") << ";\n";
+    os << "  const int tid = (int)threadIdx.x, lir = tid & (L - 1), rg = tid / L;\n";
+    os << "  const long R = a.R;\n";
+    os << "  (void)lir; (void)rg; (void)R; (void)C; (void)G;\n";
+    if (xwave) os << "  __shared__ float lds_rr[2 * G * " << WPR << " * " << KB << "];\n  int parity = 0;\n";
+    if (K > 0) os << "  __shared__ float lds_col[G * C];\n  __shared__ fs_u32 lds_flag;\n";
+
+    // ---- prologue: per-column values are loaded / computed once per workgroup ----
+    for (const ExtTensor& e : gp.ext_in)
+      if (e.kind == KIND_ROWV) {
+        os << "  float " << name(e.node, KIND_ROWV) << "[E];\n";
+        os << "  fs_load_row<" << e.dtype << ", " << tmpl_row() << ">(" << name(e.node, KIND_ROWV) << ", a.p[" << e.arg << "], 0, lir, true);\n";
+      }
+    for (int m : gp.members) {
+      if (gp.level.at(m) >= 0) continue;
+      const fs_node& n = g.nodes[m];
+      const std::string nm = name(m, KIND_ROWV);
+      os << "  float " << nm << "[E];\n  _Pragma(\"unroll\") for (int e = 0; e < E; ++e) " << nm << "[e] = fs_round<" << n.dtype << ">("
+         << expr(n) << ");\n";
+      if (const ExtTensor* e = find_out(m))
+        os << "  if (blockIdx.x == 0 && rg == 0) fs_store_row<" << e->dtype << ", " << tmpl_row() << ">(" << nm << ", a.p[" << e->arg
+           << "], 0, lir, true);\n";
+    }
+    for (int k = 0; k < K; ++k) {
+      const int m = gp.col_reduces[k];
+      os << "  float ca" << loc(m) << "[E];\n  _Pragma(\"unroll\") for (int e = 0; e < E; ++e) ca" << loc(m) << "[e] = fs_red_identity<"
+         << g.nodes[m].attr_i << ">();\n";
+    }
+
+    // ---- the row loop ----
+    os << "  for (int it = (int)blockIdx.x; it < a.n_iters; it += (int)gridDim.x) {\n";
+    os << "    const long row = (long)it * G + rg;\n    const bool rok = row < R;\n    const long row0 = row * C;\n    (void)row0;\n";
+    for (const ExtTensor& e : gp.ext_in) {
+      if (e.kind == KIND_FULL) {
+        os << "    float " << name(e.node, KIND_FULL) << "[E];\n";
+        os << "    fs_load_row<" << e.dtype << ", " << tmpl_row() << ">(" << name(e.node, KIND_FULL) << ", a.p[" << e.arg << "], row0, lir, rok);\n";
+      } else if (e.kind == KIND_COLV) {
+        os << "    const float " << name(e.node, KIND_COLV) << " = rok ? fs_load1<" << e.dtype << ">(a.p[" << e.arg << "], row) : 0.0f;\n";
+      }
+    }
+
+    // members in stage order; the row reductions of a stage come last and share one exchange
+    std::vector<int> order;
+    for (int m : gp.members)
+      if (gp.level.at(m) >= 0) order.push_back(m);
+    auto is_rr = [&](int m) { return std::find(gp.row_reduces.begin(), gp.row_reduces.end(), m) != gp.row_reduces.end(); };
+    std::stable_sort(order.begin(), order.end(), [&](int x, int y) {
+      const int lx = gp.level.at(x), ly = gp.level.at(y);
+      if (lx != ly) return lx < ly;
+      return (int)is_rr(x) < (int)is_rr(y);
+    });
+
+    size_t i = 0;
+    while (i < order.size()) {
+      const int m = order[i];
+      const fs_node& n = g.nodes[m];
+      if (is_rr(m)) {
+        // batch: every row reduction of this stage
+        std::vector<int> batch;
+        const int lvl = gp.level.at(m);
+        while (i < order.size() && is_rr(order[i]) && gp.level.at(order[i]) == lvl) batch.push_back(order[i++]);
+        for (int b : batch) {
+          const fs_node& bn = g.nodes[b];
+          const std::string arr = as_array(bn.in[0], std::to_string(loc(b)));
+          os << "    float q" << loc(b) << " = fs_lane_reduce<" << bn.attr_i << ", " << tmpl_row() << ">(" << arr << ", lir);\n";
+          os << "    q" << loc(b) << " = fs_segment_allreduce<" << bn.attr_i << ", (L < 64 ? L : 64)>(q" << loc(b) << ");\n";
+        }
+        if (xwave) {
+          os << "    {\n      const fs_xwave<" << KB << ", " << WPR << "> xw{lds_rr + (parity * G + rg) * " << WPR * KB
+             << ", lir >> 6, (tid & 63) == 0};\n";
+          for (size_t k = 0; k < batch.size(); ++k) os << "      xw.put(" << k << ", q" << loc(batch[k]) << ");\n";
+          os << "      fs_lds_barrier();\n";
+          for (size_t k = 0; k < batch.size(); ++k)
+            os << "      q" << loc(batch[k]) << " = xw.get<" << g.nodes[batch[k]].attr_i << ">(" << k << ");\n";
+          os << "      parity ^= 1;\n    }\n";
+        }
+        for (int b : batch) {
+          const fs_node& bn = g.nodes[b];
+          os << "    const float " << name(b, KIND_COLV) << " = fs_round<" << bn.dtype << ">("
+             << (bn.attr_i == FS_RED_MEAN ? "q" + std::to_string(loc(b)) + " / (float)C" : "q" + std::to_string(loc(b))) << ");\n";
+          if (const ExtTensor* e = find_out(b)) emit_store(*e, "    ");
+        }
+        continue;
+      }
+      ++i;
+      if (n.opcode == FS_REDUCE_COL && R > 1) {
+        os << "    _Pragma(\"unroll\") for (int e = 0; e < E; ++e) ca" << loc(m) << "[e] = rok ? fs_red_op<" << n.attr_i << ">(ca" << loc(m)
+           << "[e], " << ref(n.in[0]) << ") : ca" << loc(m) << "[e];\n";
+        continue;
+      }
+      if (n.opcode == FS_TRANSPOSE) {
+        const ExtTensor* e = find_out(m);
+        const std::string arr = as_array(n.in[0], std::to_string(loc(m)));
+        if (e)
+          os << "    fs_store_row_transposed<" << e->dtype << ", " << tmpl_row() << ">(" << arr << ", a.p[" << e->arg << "], R, row, lir, rok);\n";
+        continue;
+      }
+      const Kind k = gp.kind.at(m);
+      if (k == KIND_COLV) {
+        os << "    const float " << name(m, k) << " = fs_round<" << n.dtype << ">(" << expr(n) << ");\n";
+      } else {
+        os << "    float " << name(m, k) << "[E];\n    _Pragma(\"unroll\") for (int e = 0; e < E; ++e) " << name(m, k) << "[e] = fs_round<"
+           << n.dtype << ">(" << expr(n) << ");\n";
+      }
+      if (const ExtTensor* e = find_out(m)) emit_store(*e, "    ");
+    }
+    os << "  }\n";
+
+    // ---- epilogue: finish the column reductions ----
+    if (K > 0) {
+      os << "  {\n    constexpr int CPT = (C + WG - 1) / WG;\n    float cv[" << K << "][CPT];\n";
+      for (int k = 0; k < K; ++k) {
+        const int m = gp.col_reduces[k];
+        os << "    fs_colred_fold_wg<" << g.nodes[m].attr_i << ", V, NVL, L, NV, C, WG, CPT>(ca" << loc(m) << ", cv[" << k << "], lds_col, lir, rg);\n";
+      }
+      os << "    if (fs_colred_fold_grid<" << K << ", C, WG, CPT, " << s.fan_in << ", " << kname
+         << "_kinds>(cv, a.part, a.tickets, &lds_flag)) {\n";
+      os << "      _Pragma(\"unroll\") for (int i = 0; i < CPT; ++i) {\n        const int col = tid + i * WG;\n        if (col < C) {\n";
+      for (int k = 0; k < K; ++k) {
+        const int m = gp.col_reduces[k];
+        const ExtTensor* e = find_out(m);
+        if (!e) continue;
+        const fs_node& n = g.nodes[m];
+        os << "          fs_store1<" << e->dtype << ">(a.p[" << e->arg << "], col, fs_round<" << n.dtype << ">(cv[" << k << "][i]"
+           << (n.attr_i == FS_RED_MEAN ? " / (float)a.R" : "") << "));\n";
+      }
+      os << "        }\n      }\n    }\n  }\n";
+    }
+    os << "}\n";
+  }
+};
+
+uint64_t fnv1a(const std::string& s) {
+  uint64_t h = 1469598103934665603ull;
+  for (unsigned char c : s) {
+    h ^= c;
+    h *= 1099511628211ull;
+  }
+  return h;
+}
+
+}  // namespace
+
+fs_status generate_kernel(const Graph& g, GroupPlan* gp, int /*group_index*/) {
+  // first pass with a placeholder name to hash the structure, second pass with the real name
+  std::string text;
+  {
+    Emitter e(g, *gp);
+    e.run("FSK");
+    text = e.os.str();
+  }
+  char nm[64];
+  snprintf(nm, sizeof(nm), "fs_k_%016llx", (unsigned long long)fnv1a(text));
+  Emitter e(g, *gp);
+  e.run(nm);
+  gp->kernel_name = nm;
+  gp->source = e.os.str();
+  return FS_OK;
+}
+
+}  // namespace fs

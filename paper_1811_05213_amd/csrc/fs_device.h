@@ -1,0 +1,374 @@
+// fs_device.h - device-side building blocks of stitched kernels for gfx950 (CDNA4, wave64).
+//
+// A stitched kernel is a generated straight-line body that calls the pieces below.  The
+// body is the paper's thread composition (Section 1, Figure 2(a)): every elementwise node of
+// the fused group is evaluated in registers on the lane's slice of a row.  Nodes that need
+// another parallel loop - reductions and whatever consumes them - are joined inside the same
+// kernel through on-chip memory, the paper's block composition (Section 1, Figure 2(b);
+// Section 5.2, Algorithm 2).  On this hardware a 64-lane wavefront exchanges values through
+// DPP / lane-permute instructions without touching LDS at all, so LDS is only needed when a
+// row spans several wavefronts, for column partials and for transposing stores.
+//
+// Work decomposition (a Row schedule with split_dim = 0 in the terms of Section 4.1): a
+// workgroup of WG lanes is split into G = WG / L row-groups of L lanes.  Per loop trip a
+// row-group owns one row; lane `lir` of the row-group owns the 16-byte vectors
+// j*L + lir (j = 0..NVL-1) of that row, i.e. E = NVL*V elements that stay in VGPRs for the
+// whole body.  Consecutive lanes touch consecutive 16-byte vectors: every wave-wide memory
+// instruction is fully coalesced.
+//
+// This header is compiled two ways: ahead of time with hipcc (to check it and for the
+// probe kernels) and at run time as the prefix of every generated kernel.
+#ifndef FS_DEVICE_H_
+#define FS_DEVICE_H_
+
+#define FS_DEV __device__ __forceinline__
+
+// dtype tags (values match the host enum fs_dtype)
+#define FS_DT_F32 0
+#define FS_DT_BF16 1
+#define FS_DT_U8 2
+// reduction kinds (values match fs_reduce_kind)
+#define FS_K_SUM 0
+#define FS_K_MAX 1
+#define FS_K_MIN 2
+#define FS_K_MEAN 3
+
+typedef unsigned int fs_u32;
+typedef unsigned short fs_u16;
+typedef unsigned char fs_u8;
+
+template <int DT> struct fs_elem;
+template <> struct fs_elem<FS_DT_F32> { typedef float type; };
+template <> struct fs_elem<FS_DT_BF16> { typedef fs_u16 type; };
+template <> struct fs_elem<FS_DT_U8> { typedef fs_u8 type; };
+
+template <typename T, int N> struct fs_vec { typedef T type __attribute__((ext_vector_type(N))); };
+template <typename T> struct fs_vec<T, 1> { typedef T type; };
+
+// ------------------------------------------------------------------------------------------
+// scalar conversions
+// ------------------------------------------------------------------------------------------
+FS_DEV constexpr float fs_lit(fs_u32 bits) { return __builtin_bit_cast(float, bits); }  // exact literal
+FS_DEV float fs_bf16_bits_to_f32(fs_u16 h) { return __builtin_bit_cast(float, (fs_u32)h << 16); }
+// round-to-nearest-even fp32 -> bf16 (v_cvt_pk_bf16_f32 on gfx950)
+FS_DEV fs_u16 fs_f32_to_bf16_bits(float f) { return __builtin_bit_cast(fs_u16, (__bf16)f); }
+
+template <int DT> FS_DEV float fs_to_f32(typename fs_elem<DT>::type x);
+template <> FS_DEV float fs_to_f32<FS_DT_F32>(float x) { return x; }
+template <> FS_DEV float fs_to_f32<FS_DT_BF16>(fs_u16 x) { return fs_bf16_bits_to_f32(x); }
+template <> FS_DEV float fs_to_f32<FS_DT_U8>(fs_u8 x) { return x ? 1.0f : 0.0f; }
+
+template <int DT> FS_DEV typename fs_elem<DT>::type fs_from_f32(float x);
+template <> FS_DEV float fs_from_f32<FS_DT_F32>(float x) { return x; }
+template <> FS_DEV fs_u16 fs_from_f32<FS_DT_BF16>(float x) { return fs_f32_to_bf16_bits(x); }
+template <> FS_DEV fs_u8 fs_from_f32<FS_DT_U8>(float x) { return x != 0.0f ? (fs_u8)1 : (fs_u8)0; }
+
+// A node's value is rounded once to its declared dtype even when it never leaves registers.
+template <int DT> FS_DEV float fs_round(float x) { return x; }
+template <> FS_DEV float fs_round<FS_DT_BF16>(float x) { return fs_bf16_bits_to_f32(fs_f32_to_bf16_bits(x)); }
+
+// ------------------------------------------------------------------------------------------
+// elementwise math.  + - * / sqrt max min are the IEEE operations (the translation unit is
+// compiled without contraction), so values that feed a predicate are reproducible bit for bit.
+// exp/log/tanh/sigmoid/gelu/rsqrt/rcp are built on the hardware's 1-ulp transcendental
+// instructions (v_exp_f32, v_log_f32, v_rcp_f32, v_rsq_f32).
+// ------------------------------------------------------------------------------------------
+#define FS_LOG2E 1.4426950408889634f
+#define FS_LN2 0.6931471805599453f
+
+// exp(x) = 2^(x*log2e).  The product is carried in two floats (t + r) so its rounding error
+// does not grow with |x|: 2^(t+r) = 2^t * (1 + r ln2 + ...).
+FS_DEV float fs_exp(float x) {
+  const float t = x * FS_LOG2E;
+  float r = __builtin_fmaf(x, FS_LOG2E, -t);
+  r = __builtin_fmaf(x, 1.925963033500494e-8f /* log2(e) - float(log2(e)) */, r);
+  const float p = __builtin_amdgcn_exp2f(t);
+  return __builtin_fmaf(p, r * FS_LN2, p);
+}
+FS_DEV float fs_log(float x) { return __builtin_amdgcn_logf(x) * FS_LN2; }
+FS_DEV float fs_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
+FS_DEV float fs_rsqrt(float x) { return __builtin_amdgcn_rsqf(x); }
+FS_DEV float fs_sqrt(float x) { return __builtin_sqrtf(x); }
+FS_DEV float fs_div(float a, float b) { return a / b; }
+FS_DEV float fs_max(float a, float b) { return __builtin_fmaxf(a, b); }
+FS_DEV float fs_min(float a, float b) { return __builtin_fminf(a, b); }
+
+// sigmoid(x) = 1 / (1 + 2^(-x log2e)); saturates cleanly to 0 and 1.
+FS_DEV float fs_sigmoid(float x) {
+  const float e = __builtin_amdgcn_exp2f(x * -FS_LOG2E);
+  return __builtin_amdgcn_rcpf(1.0f + e);
+}
+
+// tanh: for |x| >= 1/4, 1 - 2/(e^{2|x|}+1) (no cancellation there); below, the odd Maclaurin
+// polynomial through x^9 (truncation < 1e-8 relative at 1/4).  Both sides are evaluated and
+// selected, so a wave never diverges.
+FS_DEV float fs_tanh(float x) {
+  const float ax = __builtin_fabsf(x);
+  const float e = __builtin_amdgcn_exp2f(ax * (2.0f * FS_LOG2E));
+  const float big = __builtin_fmaf(-2.0f, __builtin_amdgcn_rcpf(e + 1.0f), 1.0f);
+  const float x2 = x * x;
+  float p = __builtin_fmaf(x2, 0.021869488536155203f, -0.053968253968253971f);
+  p = __builtin_fmaf(x2, p, 0.13333333333333333f);
+  p = __builtin_fmaf(x2, p, -0.33333333333333331f);
+  const float small = __builtin_fmaf(ax * x2, p, ax);
+  return __builtin_copysignf(ax < 0.25f ? small : big, x);
+}
+
+// tanh-GeLU: 0.5 z (1 + tanh(u)) with u = sqrt(2/pi) (z + 0.044715 z^3).  Since
+// (1 + tanh u)/2 = sigmoid(2u), it is evaluated as z * sigmoid(2u): no cancellation in the
+// negative tail, one exp and one rcp per element.
+FS_DEV float fs_gelu_tanh(float z) {
+  const float z2 = z * z;
+  const float u2 = (2.0f * 0.7978845608028654f) * z * __builtin_fmaf(0.044715f, z2, 1.0f);
+  return z * fs_sigmoid(u2);
+}
+
+// ------------------------------------------------------------------------------------------
+// vector memory access: V elements of dtype DT per access (16 bytes for the widest dtype of
+// the group).  Invalid rows / columns load zeros and store nothing.
+// ------------------------------------------------------------------------------------------
+template <int DT, int V> FS_DEV void fs_load_vec(float* dst, const void* base, long elem_index) {
+  typedef typename fs_elem<DT>::type T;
+  typedef typename fs_vec<T, V>::type VT;
+  const VT raw = *reinterpret_cast<const VT*>(static_cast<const T*>(base) + elem_index);
+  if constexpr (V == 1) {
+    dst[0] = fs_to_f32<DT>(raw);
+  } else {
+#pragma unroll
+    for (int k = 0; k < V; ++k) dst[k] = fs_to_f32<DT>(raw[k]);
+  }
+}
+
+template <int DT, int V> FS_DEV void fs_store_vec(const float* src, void* base, long elem_index) {
+  typedef typename fs_elem<DT>::type T;
+  typedef typename fs_vec<T, V>::type VT;
+  VT raw;
+  if constexpr (V == 1) {
+    raw = fs_from_f32<DT>(src[0]);
+  } else {
+#pragma unroll
+    for (int k = 0; k < V; ++k) raw[k] = fs_from_f32<DT>(src[k]);
+  }
+  *reinterpret_cast<VT*>(static_cast<T*>(base) + elem_index) = raw;
+}
+
+// Load the lane's slice of one row: vectors j*L + lir, j < NVL.  `row_elem0` is the element
+// index of the row's first column.  NV = vectors per row; RAGGED says NV % L != 0.
+template <int DT, int V, int NVL, int L, int NV, bool RAGGED>
+FS_DEV void fs_load_row(float (&dst)[NVL * V], const void* base, long row_elem0, int lir, bool rok) {
+#pragma unroll
+  for (int j = 0; j < NVL; ++j) {
+    const int vi = j * L + lir;
+    const bool ok = rok && (!RAGGED || j < NVL - 1 || vi < NV);
+    if (ok) {
+      fs_load_vec<DT, V>(&dst[j * V], base, row_elem0 + (long)vi * V);
+    } else {
+#pragma unroll
+      for (int k = 0; k < V; ++k) dst[j * V + k] = 0.0f;
+    }
+  }
+}
+
+template <int DT, int V, int NVL, int L, int NV, bool RAGGED>
+FS_DEV void fs_store_row(const float (&src)[NVL * V], void* base, long row_elem0, int lir, bool rok) {
+#pragma unroll
+  for (int j = 0; j < NVL; ++j) {
+    const int vi = j * L + lir;
+    const bool ok = rok && (!RAGGED || j < NVL - 1 || vi < NV);
+    if (ok) fs_store_vec<DT, V>(&src[j * V], base, row_elem0 + (long)vi * V);
+  }
+}
+
+// Transposing store of the lane's slice of row `row` of a [R,C] value into a [C,R] tensor.
+template <int DT, int V, int NVL, int L, int NV, bool RAGGED>
+FS_DEV void fs_store_row_transposed(const float (&src)[NVL * V], void* base, long R, long row, int lir, bool rok) {
+  typedef typename fs_elem<DT>::type T;
+#pragma unroll
+  for (int j = 0; j < NVL; ++j) {
+    const int vi = j * L + lir;
+    const bool ok = rok && (!RAGGED || j < NVL - 1 || vi < NV);
+    if (ok) {
+#pragma unroll
+      for (int k = 0; k < V; ++k) static_cast<T*>(base)[(long)(vi * V + k) * R + row] = fs_from_f32<DT>(src[j * V + k]);
+    }
+  }
+}
+
+template <int DT> FS_DEV float fs_load1(const void* base, long i) {
+  return fs_to_f32<DT>(static_cast<const typename fs_elem<DT>::type*>(base)[i]);
+}
+template <int DT> FS_DEV void fs_store1(void* base, long i, float x) {
+  static_cast<typename fs_elem<DT>::type*>(base)[i] = fs_from_f32<DT>(x);
+}
+
+// ------------------------------------------------------------------------------------------
+// reductions
+// ------------------------------------------------------------------------------------------
+template <int KIND> FS_DEV float fs_red_identity() {
+  return KIND == FS_K_MAX ? -__builtin_inff() : KIND == FS_K_MIN ? __builtin_inff() : 0.0f;
+}
+template <int KIND> FS_DEV float fs_red_op(float a, float b) {
+  return KIND == FS_K_MAX ? __builtin_fmaxf(a, b) : KIND == FS_K_MIN ? __builtin_fminf(a, b) : a + b;
+}
+
+// Serial reduction of the lane's own E elements (masked columns contribute the identity).
+template <int KIND, int V, int NVL, int L, int NV, bool RAGGED>
+FS_DEV float fs_lane_reduce(const float (&v)[NVL * V], int lir) {
+  float acc = fs_red_identity<KIND>();
+#pragma unroll
+  for (int j = 0; j < NVL; ++j) {
+    const bool ok = !RAGGED || j < NVL - 1 || (j * L + lir) < NV;
+#pragma unroll
+    for (int k = 0; k < V; ++k) acc = fs_red_op<KIND>(acc, ok ? v[j * V + k] : fs_red_identity<KIND>());
+  }
+  return acc;
+}
+
+template <int CTRL> FS_DEV float fs_dpp(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+
+// All-reduce inside aligned segments of W lanes of a wavefront (W = 1,2,4,...,64).  Every
+// lane of a segment ends with the same bits.  Steps 1..8 are DPP lane permutes inside a row
+// of 16 lanes (quad_perm, row_half_mirror, row_mirror), fused into the arithmetic
+// instruction.  Across the four rows of a wavefront the row totals are read into scalar
+// registers (v_readlane) and folded there in a fixed order.  No LDS traffic.
+template <int KIND, int W> FS_DEV float fs_segment_allreduce(float v) {
+  if constexpr (W >= 2) v = fs_red_op<KIND>(v, fs_dpp<0xB1>(v));   // quad_perm [1,0,3,2]
+  if constexpr (W >= 4) v = fs_red_op<KIND>(v, fs_dpp<0x4E>(v));   // quad_perm [2,3,0,1]
+  if constexpr (W >= 8) v = fs_red_op<KIND>(v, fs_dpp<0x141>(v));  // row_half_mirror
+  if constexpr (W >= 16) v = fs_red_op<KIND>(v, fs_dpp<0x140>(v)); // row_mirror
+  if constexpr (W >= 32) {
+    const int b = __builtin_bit_cast(int, v);
+    const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 0));
+    const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 16));
+    const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 32));
+    const float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 48));
+    const float lo = fs_red_op<KIND>(r0, r1), hi = fs_red_op<KIND>(r2, r3);
+    if constexpr (W >= 64) v = fs_red_op<KIND>(lo, hi);
+    else v = (__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u)) < 32u) ? lo : hi;
+  }
+  return v;
+}
+
+// Workgroup barrier that orders LDS traffic only: outstanding global loads/stores of the
+// streaming body are not waited for.
+FS_DEV void fs_lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// Cross-wave step of a row reduction when a row spans WPR = L/64 wavefronts: wave leaders
+// publish their partial in LDS, one barrier, every lane folds the WPR partials in fixed order
+// (so all lanes of the row hold identical bits).  `slot` points at this row-group's WPR*K
+// floats inside the current ping-pong half; K reductions of one stage share the barrier.
+template <int K, int WPR> struct fs_xwave {
+  float* slot;
+  int wir;     // wave index inside the row
+  bool leader; // lane 0 of its wavefront
+  FS_DEV void put(int k, float v) const {
+    if (leader) slot[wir * K + k] = v;
+  }
+  template <int KIND> FS_DEV float get(int k) const {
+    float acc = slot[k];
+#pragma unroll
+    for (int w = 1; w < WPR; ++w) acc = fs_red_op<KIND>(acc, slot[w * K + k]);
+    return acc;
+  }
+};
+
+// ------------------------------------------------------------------------------------------
+// column reductions: two stages, no atomics on data, bitwise deterministic.
+//   stage 1  every lane accumulates its columns over the rows its workgroup visits; the G
+//            row-groups of the workgroup are folded through LDS in row-group order.
+//   stage 2  the workgroup's partial goes to the workspace; a ticket per fan-in group tells
+//            the last arriver to fold that group's partials in index order, and it moves up
+//            one level.  The only atomic is the ticket.  The survivor of the top level holds
+//            the result.
+// ------------------------------------------------------------------------------------------
+
+// Stage 1, in-workgroup fold.  acc: the lane's per-column accumulators in the row layout.
+// On return thread t holds columns t, t+WG, ... (CPT of them) in `mine`.
+template <int KIND, int V, int NVL, int L, int NV, int C, int WG, int CPT>
+FS_DEV void fs_colred_fold_wg(const float (&acc)[NVL * V], float (&mine)[CPT], float* lds /* G*C floats */, int lir, int rg) {
+  constexpr int G = WG / L;
+  __syncthreads(); // LDS area may still be in use by the previous fold
+#pragma unroll
+  for (int j = 0; j < NVL; ++j) {
+    const int vi = j * L + lir;
+    if (vi < NV) {
+#pragma unroll
+      for (int k = 0; k < V; ++k) lds[rg * C + vi * V + k] = acc[j * V + k];
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < CPT; ++i) {
+    const int col = (int)threadIdx.x + i * WG;
+    float a = fs_red_identity<KIND>();
+    if (col < C) {
+      a = lds[col];
+      for (int g = 1; g < G; ++g) a = fs_red_op<KIND>(a, lds[g * C + col]);
+    }
+    mine[i] = a;
+  }
+}
+
+template <int KIND> FS_DEV float fs_red_op_dyn(float a, float b) { return fs_red_op<KIND>(a, b); }
+
+// Stage 2, grid-wide fold of K*C values per workgroup with fan-in F.
+//   part     workspace, sum over levels of n_level*K*C floats
+//   tickets  workspace, one zero-initialised u32 per fan-in group per level; left zero on exit
+//   flag     one u32 of LDS
+// Returns true in exactly one workgroup, whose `vals` then hold the final values.
+template <int K, int C, int WG, int CPT, int F, typename KINDS>
+FS_DEV bool fs_colred_fold_grid(float (&vals)[K][CPT], float* part, fs_u32* tickets, fs_u32* flag) {
+  fs_u32 idx = blockIdx.x, n = gridDim.x;
+  const int t = (int)threadIdx.x;
+  while (n > 1) {
+    float* mine = part + (long)idx * (K * C);
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+#pragma unroll
+      for (int i = 0; i < CPT; ++i) {
+        const int col = t + i * WG;
+        if (col < C) mine[k * C + col] = vals[k][i];
+      }
+    }
+    __threadfence();  // release: this lane's partial is visible device-wide before the ticket
+    __syncthreads();
+    const fs_u32 grp = idx / F, first = grp * F;
+    const fs_u32 cnt = (n - first) < (fs_u32)F ? (n - first) : (fs_u32)F;
+    if (t == 0) {
+      const fs_u32 old = __hip_atomic_fetch_add(&tickets[grp], 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+      const bool last = old == cnt - 1;
+      if (last) __hip_atomic_store(&tickets[grp], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      *flag = last ? 1u : 0u;
+    }
+    __syncthreads();
+    if (*flag == 0u) return false;
+    __threadfence();  // acquire: the other workgroups' partials
+    const float* gp = part + (long)first * (K * C);
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+#pragma unroll
+      for (int i = 0; i < CPT; ++i) {
+        const int col = t + i * WG;
+        if (col < C) {
+          float a = gp[k * C + col];
+          for (fs_u32 j = 1; j < cnt; ++j) a = KINDS::op(k, a, gp[(long)j * (K * C) + k * C + col]);
+          vals[k][i] = a;
+        }
+      }
+    }
+    part += (long)n * (K * C);
+    const fs_u32 groups = (n + F - 1) / F;
+    tickets += groups;
+    idx = grp;
+    n = groups;
+  }
+  return true;
+}
+
+#endif  // FS_DEVICE_H_

@@ -1,0 +1,134 @@
+// fs_graph.cpp - ingestion and validation of a fusion plan (ids, arity, shapes, dtypes).
+#include <cstring>
+
+#include "fs_internal.h"
+
+namespace fs {
+
+static thread_local std::string g_error;
+std::string& error_buffer() { return g_error; }
+
+void set_error(const char* fmt, ...) {
+  char buf[1024];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof(buf), fmt, ap);
+  va_end(ap);
+  g_error = buf;
+}
+
+int op_arity(int op) {
+  if (op == FS_INPUT || op == FS_CONST) return 0;
+  if (op_is_unary(op)) return 1;
+  if (op_is_binary(op) || op == FS_CMP) return 2;
+  if (op == FS_SELECT) return 3;
+  if (op == FS_BCAST_ROWVEC || op == FS_BCAST_COLVEC || op == FS_TRANSPOSE || op == FS_REDUCE_ROW || op == FS_REDUCE_COL)
+    return 1;
+  return -1;
+}
+
+const char* op_name(int op) {
+  static const char* names[FS_NUM_OPCODES] = {
+      "input", "const", "neg", "abs", "exp", "log", "tanh", "sigmoid", "sqrt", "rsqrt", "rcp", "gelu_tanh", "convert",
+      "add", "sub", "mul", "div", "max", "min", "cmp", "select", "bcast_rowvec", "bcast_colvec", "transpose",
+      "reduce_row", "reduce_col"};
+  return (op >= 0 && op < FS_NUM_OPCODES) ? names[op] : "?";
+}
+
+static bool is_float_dtype(int dt) { return dt == FS_F32 || dt == FS_BF16; }
+
+fs_status build_graph(const fs_graph_desc* desc, Graph* g) {
+  if (!desc) FS_FAIL(FS_ERR_INVALID_ARG, "desc is NULL");
+  if (desc->abi_version != FS_ABI_VERSION)
+    FS_FAIL(FS_ERR_INVALID_ARG, "abi_version %u, library speaks %u", desc->abi_version, FS_ABI_VERSION);
+  if (desc->num_nodes <= 0 || !desc->nodes) FS_FAIL(FS_ERR_INVALID_ARG, "no nodes");
+  if (desc->num_outputs <= 0 || !desc->outputs) FS_FAIL(FS_ERR_INVALID_ARG, "no outputs");
+  if (desc->mode != FS_MODE_STITCHED && desc->mode != FS_MODE_UNFUSED) FS_FAIL(FS_ERR_INVALID_ARG, "unknown mode %u", desc->mode);
+  if (desc->lds_budget_bytes < 0 || desc->lds_budget_bytes > 65536)
+    FS_FAIL(FS_ERR_INVALID_ARG, "lds_budget_bytes %d outside [0, 65536]", desc->lds_budget_bytes);
+
+  const int N = desc->num_nodes;
+  g->nodes.assign(desc->nodes, desc->nodes + N);
+  g->users.assign(N, {});
+  g->input_index.assign(N, -1);
+  g->output_index.assign(N, -1);
+  g->input_ids.clear();
+
+  for (int id = 0; id < N; ++id) {
+    const fs_node& n = g->nodes[id];
+    const int ar = op_arity(n.opcode);
+    if (ar < 0) FS_FAIL(FS_ERR_BAD_GRAPH, "node %d: unknown opcode %d", id, n.opcode);
+    if (n.num_in != ar) FS_FAIL(FS_ERR_BAD_GRAPH, "node %d (%s): arity %d, expected %d", id, op_name(n.opcode), n.num_in, ar);
+    if (n.dtype != FS_F32 && n.dtype != FS_BF16 && n.dtype != FS_U8) FS_FAIL(FS_ERR_DTYPE, "node %d: unknown dtype %d", id, n.dtype);
+    if (n.rows < 1 || n.cols < 1) FS_FAIL(FS_ERR_SHAPE, "node %d: shape [%d,%d]", id, n.rows, n.cols);
+    if ((int64_t)n.rows * n.cols > ((int64_t)1 << 40)) FS_FAIL(FS_ERR_SHAPE, "node %d: too large", id);
+    for (int k = 0; k < ar; ++k) {
+      if (n.in[k] < 0 || n.in[k] >= id)
+        FS_FAIL(FS_ERR_BAD_GRAPH, "node %d (%s): operand %d is node %d; ids must be topological (operand id < node id)", id,
+                op_name(n.opcode), k, n.in[k]);
+    }
+    const fs_node* a = ar > 0 ? &g->nodes[n.in[0]] : nullptr;
+    const fs_node* b = ar > 1 ? &g->nodes[n.in[1]] : nullptr;
+    const fs_node* c = ar > 2 ? &g->nodes[n.in[2]] : nullptr;
+    auto same_shape = [&](const fs_node* x) { return x->rows == n.rows && x->cols == n.cols; };
+    const int op = n.opcode;
+
+    if (op == FS_INPUT) {
+      g->input_index[id] = (int)g->input_ids.size();
+      g->input_ids.push_back(id);
+    } else if (op == FS_CONST) {
+      if (!is_float_dtype(n.dtype)) FS_FAIL(FS_ERR_DTYPE, "node %d (const): dtype must be f32 or bf16", id);
+    } else if (op == FS_CONVERT) {
+      if (!same_shape(a)) FS_FAIL(FS_ERR_SHAPE, "node %d (convert): shape differs from operand", id);
+      if (!is_float_dtype(n.dtype)) FS_FAIL(FS_ERR_DTYPE, "node %d (convert): target must be f32 or bf16", id);
+    } else if (op_is_unary(op)) {
+      if (!same_shape(a)) FS_FAIL(FS_ERR_SHAPE, "node %d (%s): shape differs from operand", id, op_name(op));
+      if (!is_float_dtype(n.dtype) || !is_float_dtype(a->dtype)) FS_FAIL(FS_ERR_DTYPE, "node %d (%s): needs f32/bf16", id, op_name(op));
+    } else if (op_is_binary(op)) {
+      if (!same_shape(a) || !same_shape(b)) FS_FAIL(FS_ERR_SHAPE, "node %d (%s): operand shapes differ from result", id, op_name(op));
+      if (!is_float_dtype(n.dtype) || !is_float_dtype(a->dtype) || !is_float_dtype(b->dtype))
+        FS_FAIL(FS_ERR_DTYPE, "node %d (%s): needs f32/bf16", id, op_name(op));
+    } else if (op == FS_CMP) {
+      if (!same_shape(a) || !same_shape(b)) FS_FAIL(FS_ERR_SHAPE, "node %d (cmp): operand shapes differ from result", id);
+      if (n.dtype != FS_U8) FS_FAIL(FS_ERR_DTYPE, "node %d (cmp): result must be u8", id);
+      if (!is_float_dtype(a->dtype) || !is_float_dtype(b->dtype)) FS_FAIL(FS_ERR_DTYPE, "node %d (cmp): operands must be f32/bf16", id);
+      if (n.attr_i < FS_CMP_GT || n.attr_i > FS_CMP_NE) FS_FAIL(FS_ERR_BAD_GRAPH, "node %d (cmp): kind %d", id, n.attr_i);
+    } else if (op == FS_SELECT) {
+      if (!same_shape(a) || !same_shape(b) || !same_shape(c)) FS_FAIL(FS_ERR_SHAPE, "node %d (select): operand shapes differ", id);
+      if (a->dtype != FS_U8) FS_FAIL(FS_ERR_DTYPE, "node %d (select): predicate must be u8", id);
+      if (b->dtype != n.dtype || c->dtype != n.dtype) FS_FAIL(FS_ERR_DTYPE, "node %d (select): branches must have the result dtype", id);
+    } else if (op == FS_BCAST_ROWVEC) {
+      if (a->rows != 1 || a->cols != n.cols) FS_FAIL(FS_ERR_SHAPE, "node %d (bcast_rowvec): operand must be [1,%d]", id, n.cols);
+      if (a->dtype != n.dtype) FS_FAIL(FS_ERR_DTYPE, "node %d (bcast_rowvec): dtype differs from operand", id);
+      if (op_is_free(a->opcode) && a->opcode != FS_INPUT && a->opcode != FS_CONST)
+        FS_FAIL(FS_ERR_BAD_GRAPH, "node %d: broadcast of a broadcast", id);
+    } else if (op == FS_BCAST_COLVEC) {
+      if (a->cols != 1 || a->rows != n.rows) FS_FAIL(FS_ERR_SHAPE, "node %d (bcast_colvec): operand must be [%d,1]", id, n.rows);
+      if (a->dtype != n.dtype) FS_FAIL(FS_ERR_DTYPE, "node %d (bcast_colvec): dtype differs from operand", id);
+      if (op_is_free(a->opcode) && a->opcode != FS_INPUT && a->opcode != FS_CONST)
+        FS_FAIL(FS_ERR_BAD_GRAPH, "node %d: broadcast of a broadcast", id);
+    } else if (op == FS_TRANSPOSE) {
+      if (a->rows != n.cols || a->cols != n.rows) FS_FAIL(FS_ERR_SHAPE, "node %d (transpose): result must be [%d,%d]", id, a->cols, a->rows);
+      if (a->dtype != n.dtype) FS_FAIL(FS_ERR_DTYPE, "node %d (transpose): dtype differs from operand", id);
+    } else if (op == FS_REDUCE_ROW || op == FS_REDUCE_COL) {
+      if (op == FS_REDUCE_ROW && (a->rows != n.rows || n.cols != 1)) FS_FAIL(FS_ERR_SHAPE, "node %d (reduce_row): result must be [%d,1]", id, a->rows);
+      if (op == FS_REDUCE_COL && (a->cols != n.cols || n.rows != 1)) FS_FAIL(FS_ERR_SHAPE, "node %d (reduce_col): result must be [1,%d]", id, a->cols);
+      if (!is_float_dtype(n.dtype) || !is_float_dtype(a->dtype)) FS_FAIL(FS_ERR_DTYPE, "node %d (reduce): needs f32/bf16", id);
+      if (n.attr_i < FS_RED_SUM || n.attr_i > FS_RED_MEAN) FS_FAIL(FS_ERR_BAD_GRAPH, "node %d (reduce): kind %d", id, n.attr_i);
+    }
+    for (int k = 0; k < ar; ++k) g->users[n.in[k]].push_back(id);
+  }
+
+  g->outputs.clear();
+  for (int k = 0; k < desc->num_outputs; ++k) {
+    const int o = desc->outputs[k];
+    if (o < 0 || o >= N) FS_FAIL(FS_ERR_BAD_GRAPH, "output %d: node id %d out of range", k, o);
+    if (op_is_free(g->nodes[o].opcode)) FS_FAIL(FS_ERR_BAD_GRAPH, "output %d: node %d (%s) is never materialised", k, o, op_name(g->nodes[o].opcode));
+    if (g->output_index[o] >= 0) FS_FAIL(FS_ERR_BAD_GRAPH, "output %d: node %d listed twice", k, o);
+    g->output_index[o] = k;
+    g->outputs.push_back(o);
+  }
+  return FS_OK;
+}
+
+}  // namespace fs

@@ -1,0 +1,443 @@
+// fs_group.cpp - fused-group analysis, schedule and LDS planning, and group formation.
+#include <algorithm>
+#include <functional>
+#include <set>
+
+#include "fs_internal.h"
+
+namespace fs {
+
+namespace {
+
+int pow2_ceil(int x) {
+  int p = 1;
+  while (p < x) p <<= 1;
+  return p;
+}
+
+struct Resolved {
+  bool literal = false;  // FS_CONST: no tensor behind it
+  int node = -1;         // the tensor actually read (bcasts looked through)
+  Kind kind = KIND_NONE; // its kind in the group's work space
+};
+
+struct Analyser {
+  const Graph& g;
+  GroupPlan& gp;
+  std::vector<char> in_set;
+  int R = 1, C = 1;
+
+  Analyser(const Graph& g_, GroupPlan& gp_) : g(g_), gp(gp_), in_set(g_.n(), 0) {}
+
+  Kind classify(int rows, int cols) const {
+    if (rows == R && cols == C) return KIND_FULL;
+    if (rows == R && cols == 1) return KIND_COLV;
+    if (rows == 1 && cols == C) return KIND_ROWV;
+    return KIND_NONE;
+  }
+  Kind classify(const fs_node& n) const { return classify(n.rows, n.cols); }
+
+  // A member whose value only exists after the grid-wide fold / is only stored transposed.
+  bool is_deferred(int id) const {
+    const fs_node& n = g.nodes[id];
+    return (n.opcode == FS_REDUCE_COL && R > 1) || n.opcode == FS_TRANSPOSE;
+  }
+  // A row reduction that needs lanes to exchange values (C == 1 degenerates to a copy).
+  bool is_cross_lane_reduce(int id) const { return g.nodes[id].opcode == FS_REDUCE_ROW && C > 1; }
+
+  // What a consumer expecting kind `want` sees when it reads operand node `o`.
+  bool resolve(int o, Kind want, Resolved* r) const {
+    const fs_node& n = g.nodes[o];
+    if (classify(n) != want) return false;
+    if (n.opcode == FS_CONST) {
+      r->literal = true;
+      return true;
+    }
+    if (n.opcode == FS_BCAST_ROWVEC || n.opcode == FS_BCAST_COLVEC) {
+      const int x = n.in[0];
+      const fs_node& xn = g.nodes[x];
+      if (xn.opcode == FS_CONST) {
+        r->literal = true;
+        return true;
+      }
+      const Kind kx = classify(xn);
+      if (kx == KIND_NONE) return false;
+      // a broadcast either widens a vector to the full work space or is the identity
+      const bool ok = kx == want || (want == KIND_FULL && kx == (n.opcode == FS_BCAST_ROWVEC ? KIND_ROWV : KIND_COLV));
+      if (!ok) return false;
+      r->node = x;
+      r->kind = kx;
+      return true;
+    }
+    r->node = o;
+    r->kind = want;
+    return true;
+  }
+};
+
+void add_ext_in(GroupPlan& gp, int node, Kind k, int dtype) {
+  for (const ExtTensor& e : gp.ext_in)
+    if (e.node == node) return;
+  ExtTensor e;
+  e.node = node;
+  e.kind = k;
+  e.dtype = dtype;
+  gp.ext_in.push_back(e);
+}
+
+}  // namespace
+
+// -------------------------------------------------------------------------------------------
+// Schedule and LDS plan of one group.
+//
+// Every group runs a Row schedule with split_dim = 0 (Section 4.1): the work space [R,C] is
+// cut along rows into `grid` blocks.  What is tuned is how many lanes cooperate on a row (L,
+// the role of reduce_warps in Section 4.4), the workgroup size and the block count.  Row
+// reductions want a row inside one wavefront (no LDS, no barrier); very long rows are spread
+// over several wavefronts and folded through LDS; small problems trade elements per lane
+// for more wavefronts so that the 256 CUs all get work.
+// -------------------------------------------------------------------------------------------
+static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPlan* gp) {
+  Schedule& s = gp->s;
+  const int R = gp->R, C = gp->C;
+  int max_es = 0, n_full = 0;
+  for (const ExtTensor& e : gp->ext_in)
+    if (e.kind == KIND_FULL) max_es = std::max(max_es, dtype_size(e.dtype)), ++n_full;
+  for (const ExtTensor& e : gp->ext_out)
+    if (e.kind == KIND_FULL) max_es = std::max(max_es, dtype_size(e.dtype)), ++n_full;
+  if (max_es == 0) max_es = 4;
+  int V = 16 / max_es;
+  while (C % V) V /= 2;
+  const int NV = C / V;
+  const bool rowred = !gp->row_reduces.empty();
+  const bool colred = !gp->col_reduces.empty();
+
+  // elements of one [R,C] value a lane may hold
+  int ecap = rowred ? 32 : 8;
+  if (n_full > 4) ecap /= 2;
+  ecap = std::max(ecap, V);
+  const int l_min = pow2_ceil((NV + ecap / V - 1) / (ecap / V));
+  const int l_max = std::min(1024, pow2_ceil(NV));
+  if (l_min > 1024) FS_FAIL(FS_ERR_UNSUPPORTED, "rows of %d columns are too long for one workgroup", C);
+  int L = rowred ? std::min(64, l_max) : std::min(256, l_max);
+  L = std::max(L, l_min);
+  // small problems: more lanes per row until the device has ~8 wavefronts per CU
+  while ((int64_t)R * L / 64 < 2048 && L < l_max) L *= 2;
+  if (opt.has_hint && opt.hint.lanes_per_row > 0) {
+    const int h = opt.hint.lanes_per_row;
+    if ((h & (h - 1)) == 0 && h >= l_min && h <= 1024) L = h;
+  }
+
+  int WG;
+  const int64_t total_waves = std::max<int64_t>(1, (int64_t)R * L / 64);
+  if (colred || total_waves > 1024) WG = std::max(256, L);
+  else WG = std::max(64, L);
+  if (opt.has_hint && opt.hint.wg_threads > 0) {
+    const int h = opt.hint.wg_threads;
+    if (h % 64 == 0 && h >= L && h <= 1024) WG = h;
+  }
+
+  s.V = V;
+  s.NV = NV;
+  s.L = L;
+  s.NVL = (NV + L - 1) / L;
+  s.E = s.NVL * V;
+  s.WG = WG;
+  s.G = WG / L;
+  s.ragged = (NV % L) != 0;
+  s.n_iters = (R + s.G - 1) / s.G;
+  int cap = colred ? 1024 : 2048;
+  if (opt.has_hint && opt.hint.max_workgroups > 0) cap = opt.hint.max_workgroups;
+  s.grid = std::max(1, std::min(s.n_iters, cap));
+
+  // LDS plan (Section 5.1).  Size requirements: cross-wave row-reduction partials (the "direct
+  // allocation" for a non-root Reduce) and the column-partial fold area.  Space sharing: all row
+  // reductions of the kernel reuse one ping-pong pair of slots instead of one buffer each (the
+  // Reduce.2-reuses-Reduce.1 case of Section 5.1.3); the column fold area is shared by all column
+  // reductions in turn.
+  int lds = 0;
+  if (rowred && L > 64) lds += 2 * s.G * (L / 64) * gp->max_batched_reduces * 4;
+  if (colred) lds += s.G * C * 4 + 16;
+  s.lds_bytes = lds;
+  if (lds > opt.lds_budget)
+    FS_FAIL(FS_ERR_LDS_BUDGET, "group needs %d bytes of LDS, budget is %d", lds, opt.lds_budget);
+
+  // grid-wide fold scratch
+  gp->n_tickets = 0;
+  gp->part_bytes = 0;
+  if (colred) {
+    const size_t kc = gp->col_reduces.size() * (size_t)C;
+    size_t floats = 0;
+    int n = s.grid;
+    while (n > 1) {
+      floats += (size_t)n * kc;
+      n = (n + s.fan_in - 1) / s.fan_in;
+      gp->n_tickets += n;
+    }
+    gp->part_bytes = floats * 4;
+  }
+  (void)g;
+  return FS_OK;
+}
+
+fs_status analyse_group(const Graph& g, const std::vector<int>& members, const std::vector<int>& /*group_of*/,
+                        int /*self_group*/, const PlanOptions& opt, GroupPlan* out) {
+  GroupPlan& gp = *out;
+  gp = GroupPlan();
+  gp.members = members;
+  std::sort(gp.members.begin(), gp.members.end());
+  Analyser a(g, gp);
+  for (int m : gp.members) a.in_set[m] = 1;
+
+  // work space: the largest extents seen (a transposed root contributes its operand's shape)
+  int R = 1, C = 1;
+  for (int m : gp.members) {
+    const fs_node& n = g.nodes[m];
+    if (n.opcode != FS_TRANSPOSE) R = std::max(R, n.rows), C = std::max(C, n.cols);
+    for (int k = 0; k < n.num_in; ++k) {
+      const fs_node& o = g.nodes[n.in[k]];
+      R = std::max(R, o.rows), C = std::max(C, o.cols);
+    }
+  }
+  a.R = gp.R = R;
+  a.C = gp.C = C;
+
+  for (int m : gp.members) {
+    const fs_node& n = g.nodes[m];
+    Kind result_kind = a.classify(n);
+    Kind operand_kind = result_kind;
+    if (n.opcode == FS_REDUCE_ROW || n.opcode == FS_REDUCE_COL || n.opcode == FS_TRANSPOSE) {
+      operand_kind = KIND_FULL;
+      if (n.opcode == FS_TRANSPOSE) result_kind = KIND_FULL;  // lives in the operand's layout, stored transposed
+    }
+    if (result_kind == KIND_NONE)
+      FS_FAIL(FS_ERR_UNSUPPORTED, "node %d [%d,%d] does not fit the group's work space [%d,%d]", m, n.rows, n.cols, R, C);
+    gp.kind[m] = result_kind;
+    int lvl = result_kind == KIND_ROWV && !a.is_deferred(m) ? -1 : 0;
+    for (int k = 0; k < n.num_in; ++k) {
+      Resolved r;
+      if (!a.resolve(n.in[k], operand_kind, &r))
+        FS_FAIL(FS_ERR_UNSUPPORTED, "node %d: operand %d does not fit the group's work space [%d,%d]", m, n.in[k], R, C);
+      if (r.literal) continue;
+      if (a.in_set[r.node]) {
+        if (a.is_deferred(r.node))
+          FS_FAIL(FS_ERR_UNSUPPORTED, "node %d consumes node %d, whose value only exists after the whole grid has run", m, r.node);
+        lvl = std::max(lvl, gp.level[r.node] + (a.is_cross_lane_reduce(r.node) ? 1 : 0));
+      } else {
+        add_ext_in(gp, r.node, r.kind, g.nodes[r.node].dtype);
+        gp.kind[r.node] = r.kind;
+      }
+    }
+    gp.level[m] = lvl;
+    if (a.is_cross_lane_reduce(m)) gp.row_reduces.push_back(m);
+    if (n.opcode == FS_REDUCE_COL && R > 1) gp.col_reduces.push_back(m);
+
+    // does the value leave the kernel?
+    bool leaves = g.output_index[m] >= 0;
+    std::function<void(int)> scan_users = [&](int id) {
+      for (int u : g.users[id]) {
+        const int uop = g.nodes[u].opcode;
+        if (uop == FS_BCAST_ROWVEC || uop == FS_BCAST_COLVEC) scan_users(u);
+        else if (!a.in_set[u]) leaves = true;
+      }
+    };
+    scan_users(m);
+    if (leaves) {
+      ExtTensor e;
+      e.node = m;
+      e.kind = n.opcode == FS_REDUCE_COL && R > 1 ? KIND_ROWV : result_kind;
+      e.dtype = n.dtype;
+      e.transposed = n.opcode == FS_TRANSPOSE;
+      e.deferred = n.opcode == FS_REDUCE_COL && R > 1;
+      gp.ext_out.push_back(e);
+    }
+  }
+  if (gp.ext_out.empty()) FS_FAIL(FS_ERR_UNSUPPORTED, "group produces nothing");
+  if (gp.ext_in.size() + gp.ext_out.size() > 48) FS_FAIL(FS_ERR_UNSUPPORTED, "group touches too many tensors");
+
+  // row reductions of one stage share one exchange
+  std::map<int, int> per_level;
+  for (int m : gp.row_reduces) gp.max_batched_reduces = std::max(gp.max_batched_reduces, ++per_level[gp.level[m]]);
+
+  int arg = 0;
+  for (ExtTensor& e : gp.ext_in) e.arg = arg++;
+  for (ExtTensor& e : gp.ext_out) e.arg = arg++;
+
+  gp.min_hbm_bytes = 0;
+  for (const ExtTensor& e : gp.ext_in) gp.min_hbm_bytes += (uint64_t)g.nodes[e.node].rows * g.nodes[e.node].cols * dtype_size(e.dtype);
+  for (const ExtTensor& e : gp.ext_out) gp.min_hbm_bytes += (uint64_t)g.nodes[e.node].rows * g.nodes[e.node].cols * dtype_size(e.dtype);
+
+  return choose_schedule(g, opt, &gp);
+}
+
+// -------------------------------------------------------------------------------------------
+// Group formation.
+//
+// Unfused mode: one group per compute node.  Caller-given plan: checked, not changed.
+// Otherwise a greedy producer/consumer fusion in the spirit of Algorithm 1 (Section 3.2):
+// nodes are visited from the outputs upwards (the order of decreasing span); a node joins the
+// group of one of its users when the three conditions of SchdConsistent hold:
+//   1. no dependence cycle between groups would appear (the paper's `giveup` test),
+//   2. it has a user in that group (producer/consumer fusion only),
+//   3. the merged group still has a valid schedule and fits the LDS budget (analyse_group).
+// -------------------------------------------------------------------------------------------
+namespace {
+
+struct Former {
+  const Graph& g;
+  const PlanOptions& opt;
+  std::vector<int> group_of;              // node -> group id, -1 unassigned/free
+  std::vector<std::vector<int>> members;  // group id -> nodes
+  std::vector<char> live;
+
+  Former(const Graph& g_, const PlanOptions& o) : g(g_), opt(o), group_of(g_.n(), -1), live(g_.n(), 0) {}
+
+  void mark_live() {
+    std::vector<int> stack(g.outputs.begin(), g.outputs.end());
+    while (!stack.empty()) {
+      const int id = stack.back();
+      stack.pop_back();
+      if (live[id]) continue;
+      live[id] = 1;
+      for (int k = 0; k < g.nodes[id].num_in; ++k) stack.push_back(g.nodes[id].in[k]);
+    }
+  }
+
+  // compute-node users of `id`, looking through broadcasts
+  void real_users(int id, std::vector<int>* out) const {
+    for (int u : g.users[id]) {
+      if (!live[u]) continue;
+      const int uop = g.nodes[u].opcode;
+      if (uop == FS_BCAST_ROWVEC || uop == FS_BCAST_COLVEC) real_users(u, out);
+      else out->push_back(u);
+    }
+  }
+
+  // is group `to` reachable from group `from` along producer -> consumer edges?
+  bool reaches(int from, int to) const {
+    std::vector<char> seen(members.size(), 0);
+    std::vector<int> stack{from};
+    while (!stack.empty()) {
+      const int grp = stack.back();
+      stack.pop_back();
+      if (grp == to) return true;
+      if (seen[grp]) continue;
+      seen[grp] = 1;
+      for (int m : members[grp]) {
+        std::vector<int> us;
+        real_users(m, &us);
+        for (int u : us)
+          if (group_of[u] >= 0 && group_of[u] != grp && !seen[group_of[u]]) stack.push_back(group_of[u]);
+      }
+    }
+    return false;
+  }
+
+  fs_status topo_order(std::vector<std::vector<int>>* ordered) const {
+    const int NG = (int)members.size();
+    std::vector<std::set<int>> succ(NG);
+    std::vector<int> indeg(NG, 0);
+    for (int grp = 0; grp < NG; ++grp)
+      for (int m : members[grp]) {
+        std::vector<int> us;
+        real_users(m, &us);
+        for (int u : us) {
+          const int h = group_of[u];
+          if (h >= 0 && h != grp && succ[grp].insert(h).second) ++indeg[h];
+        }
+      }
+    // Kahn, smallest first-member id first (stable, close to the caller's order)
+    auto key = [&](int grp) { return *std::min_element(members[grp].begin(), members[grp].end()); };
+    std::set<std::pair<int, int>> ready;
+    for (int grp = 0; grp < NG; ++grp)
+      if (!members[grp].empty() && indeg[grp] == 0) ready.insert({key(grp), grp});
+    size_t placed = 0, nonempty = 0;
+    for (int grp = 0; grp < NG; ++grp) nonempty += !members[grp].empty();
+    while (!ready.empty()) {
+      const int grp = ready.begin()->second;
+      ready.erase(ready.begin());
+      ordered->push_back(members[grp]);
+      ++placed;
+      for (int h : succ[grp])
+        if (--indeg[h] == 0) ready.insert({key(h), h});
+    }
+    if (placed != nonempty) FS_FAIL(FS_ERR_UNSUPPORTED, "the grouping has a dependence cycle between groups");
+    return FS_OK;
+  }
+};
+
+}  // namespace
+
+fs_status form_groups(const Graph& g, const fs_graph_desc* desc, const PlanOptions& opt, std::vector<int>* group_of,
+                      std::vector<std::vector<int>>* ordered) {
+  Former f(g, opt);
+  f.mark_live();
+  const int N = g.n();
+  GroupPlan scratch;
+
+  if (opt.mode == FS_MODE_UNFUSED) {
+    for (int id = 0; id < N; ++id)
+      if (f.live[id] && !op_is_free(g.nodes[id].opcode)) {
+        f.group_of[id] = (int)f.members.size();
+        f.members.push_back({id});
+      }
+  } else if (desc->group_of_node) {
+    std::map<int, int> remap;
+    for (int id = 0; id < N; ++id) {
+      if (!f.live[id] || op_is_free(g.nodes[id].opcode)) continue;
+      const int want = desc->group_of_node[id];
+      if (want < 0) FS_FAIL(FS_ERR_INVALID_ARG, "group_of_node[%d] = %d", id, want);
+      auto it = remap.find(want);
+      if (it == remap.end()) {
+        it = remap.insert({want, (int)f.members.size()}).first;
+        f.members.push_back({});
+      }
+      f.group_of[id] = it->second;
+      f.members[it->second].push_back(id);
+    }
+  } else {
+    for (int id = N - 1; id >= 0; --id) {
+      if (!f.live[id] || op_is_free(g.nodes[id].opcode)) continue;
+      std::vector<int> us;
+      f.real_users(id, &us);
+      // candidate groups: those of its users, most users first
+      std::map<int, int> votes;
+      for (int u : us)
+        if (f.group_of[u] >= 0) ++votes[f.group_of[u]];
+      std::vector<std::pair<int, int>> cands;
+      for (auto& kv : votes) cands.push_back({-kv.second, kv.first});
+      std::sort(cands.begin(), cands.end());
+      int joined = -1;
+      for (auto& cand : cands) {
+        const int grp = cand.second;
+        // condition 1: joining must not close a cycle through a user left outside
+        bool cycle = false;
+        for (int u : us) {
+          const int h = f.group_of[u];
+          if (h >= 0 && h != grp && f.reaches(h, grp)) {
+            cycle = true;
+            break;
+          }
+        }
+        if (cycle) continue;
+        // condition 3: schedule and LDS plan of the merged group
+        std::vector<int> merged = f.members[grp];
+        merged.push_back(id);
+        if ((int)merged.size() > 96) continue;
+        if (analyse_group(g, merged, f.group_of, grp, opt, &scratch) != FS_OK) continue;
+        joined = grp;
+        break;
+      }
+      if (joined < 0) {
+        joined = (int)f.members.size();
+        f.members.push_back({});
+      }
+      f.group_of[id] = joined;
+      f.members[joined].push_back(id);
+    }
+  }
+  *group_of = f.group_of;
+  return f.topo_order(ordered);
+}
+
+}  // namespace fs

@@ -1,0 +1,155 @@
+// fs_internal.h - host-side data structures of the stitched-kernel executor.
+#ifndef FS_INTERNAL_H_
+#define FS_INTERNAL_H_
+
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <map>
+#include <mutex>
+#include <string>
+#include <vector>
+
+#include "fs.h"
+
+namespace fs {
+
+// ---- errors --------------------------------------------------------------------------------
+void set_error(const char* fmt, ...) __attribute__((format(printf, 1, 2)));
+std::string& error_buffer();
+#define FS_FAIL(status, ...)       \
+  do {                             \
+    ::fs::set_error(__VA_ARGS__);  \
+    return (status);               \
+  } while (0)
+
+// ---- graph -----------------------------------------------------------------------------------
+inline bool op_is_free(int op) {  // never materialised, never a launch: inlined into consumers
+  return op == FS_INPUT || op == FS_CONST || op == FS_BCAST_ROWVEC || op == FS_BCAST_COLVEC;
+}
+inline bool op_is_unary(int op) { return op >= FS_NEG && op <= FS_CONVERT; }
+inline bool op_is_binary(int op) { return op >= FS_ADD && op <= FS_MIN; }
+inline bool op_is_approx(int op) {  // not bit-reproducible against a correctly rounded reference
+  return op == FS_EXP || op == FS_LOG || op == FS_TANH || op == FS_SIGMOID || op == FS_RSQRT || op == FS_RCP ||
+         op == FS_GELU_TANH;
+}
+int op_arity(int op);
+const char* op_name(int op);
+inline int dtype_size(int dt) { return dt == FS_F32 ? 4 : dt == FS_BF16 ? 2 : 1; }
+
+struct Graph {
+  std::vector<fs_node> nodes;
+  std::vector<int> outputs;              // plan outputs (node ids)
+  std::vector<int> input_ids;            // FS_INPUT nodes in id order
+  std::vector<int> input_index;          // node id -> index into inputs[] or -1
+  std::vector<int> output_index;         // node id -> index into outputs[] or -1
+  std::vector<std::vector<int>> users;   // direct users of each node
+  int n() const { return (int)nodes.size(); }
+};
+
+// Validates desc and fills g.  (Section 2.1: the op classes; this is the receiving end of a fusion plan.)
+fs_status build_graph(const fs_graph_desc* desc, Graph* g);
+
+// ---- groups ----------------------------------------------------------------------------------
+// How a tensor relates to its group's work space [R,C] (Section 4.1: the schedule is defined on
+// the root's output shape; operands get theirs by back-propagation, Section 4.2).
+enum Kind : int {
+  KIND_NONE = 0,
+  KIND_FULL = 1,  // [R,C]: E elements per lane, in VGPRs
+  KIND_COLV = 2,  // [R,1]: one value per row, replicated in the row's lanes
+  KIND_ROWV = 3   // [1,C]: one value per column, the lane's slice loaded once per workgroup
+};
+
+struct ExtTensor {
+  int node = -1;
+  Kind kind = KIND_NONE;
+  int dtype = 0;
+  bool transposed = false;  // output only: stored as [C,R]
+  bool deferred = false;    // output only: column-reduction result written by the last workgroup
+  int arg = -1;             // index into the kernel's pointer table
+};
+
+struct Schedule {
+  int V = 4;        // elements per vector access
+  int NV = 0;       // vectors per row = C / V
+  int L = 64;       // lanes per row (power of two)
+  int NVL = 1;      // vectors per lane = ceil(NV / L)
+  int E = 4;        // elements per lane = NVL * V
+  int WG = 256;     // workgroup size
+  int G = 4;        // row-groups per workgroup = WG / L
+  int n_iters = 0;  // ceil(R / G): loop trips over the whole grid
+  int grid = 0;     // workgroups (`blocks` of Section 4.1)
+  bool ragged = false;  // NV % L != 0
+  int lds_bytes = 0;
+  int fan_in = 32;  // column-reduction tree fan-in
+};
+
+struct GroupPlan {
+  std::vector<int> members;  // compute nodes, ascending id
+  int R = 0, C = 0;          // work space
+  std::map<int, Kind> kind;  // members and external tensors -> kind
+  std::map<int, int> level;  // members -> stage (number of row reductions upstream)
+  std::vector<ExtTensor> ext_in, ext_out;
+  std::vector<int> row_reduces;  // REDUCE_ROW members that need a cross-lane exchange
+  std::vector<int> col_reduces;  // REDUCE_COL members finished by the grid-wide fold
+  int max_batched_reduces = 0;   // largest number of row reductions sharing one exchange
+  Schedule s;
+  // workspace scratch (byte offsets inside the plan workspace)
+  size_t part_offset = 0, part_bytes = 0;
+  size_t ticket_offset = 0;
+  int n_tickets = 0;
+  uint64_t min_hbm_bytes = 0;
+  // generated kernel
+  std::string kernel_name, source;
+};
+
+struct PlanOptions {
+  uint32_t mode = FS_MODE_STITCHED;
+  int lds_budget = 32768;
+  fs_sched_hint hint = {0, 0, 0, 0};
+  bool has_hint = false;
+};
+
+// Analyse a candidate member set: work space, kinds, stages, external tensors, schedule, LDS plan.
+// Returns FS_OK, FS_ERR_UNSUPPORTED (cannot be one stitched kernel) or FS_ERR_LDS_BUDGET.
+// This is the schedule-consistency check of Section 3.2 (third condition of SchdConsistent)
+// together with the schedule and shared-memory planning of Sections 4 and 5.1.
+fs_status analyse_group(const Graph& g, const std::vector<int>& members, const std::vector<int>& group_of,
+                        int self_group, const PlanOptions& opt, GroupPlan* out);
+
+// Assign every compute node to a group.  group_of[node] = group id or -1 for free nodes.
+fs_status form_groups(const Graph& g, const fs_graph_desc* desc, const PlanOptions& opt, std::vector<int>* group_of,
+                      std::vector<std::vector<int>>* groups_in_launch_order);
+
+// Emit the HIP source of one group's kernel (Section 5.2, Algorithm 2 realised as a
+// straight-line body over hand-written device building blocks).
+fs_status generate_kernel(const Graph& g, GroupPlan* gp, int group_index);
+
+// Compile `source` for gfx950 (disk-cached).  No GPU needed.
+fs_status compile_kernel(const std::string& source, const std::string& name, std::vector<char>* code);
+
+const char* device_header_source();  // text of fs_device.h, embedded at build time
+
+}  // namespace fs
+
+struct fs_plan {
+  fs::Graph graph;
+  fs::PlanOptions opt;
+  std::vector<int> group_of;
+  std::vector<fs::GroupPlan> groups;  // in launch order
+  // workspace layout
+  std::map<int, size_t> ws_tensor_offset;  // node materialised in the workspace -> byte offset
+  size_t ticket_bytes = 0;                 // tickets live at the start of the workspace
+  size_t workspace_bytes = 0;
+  uint64_t min_hbm_bytes = 0, launched_hbm_bytes = 0;
+  std::vector<char> code;  // one gfx950 code object holding every kernel of the plan
+  // per-device loaded code
+  struct Loaded {
+    std::vector<void*> modules;    // hipModule_t per group
+    std::vector<void*> functions;  // hipFunction_t per group
+  };
+  std::mutex mu;
+  std::map<int, Loaded> loaded;
+};
+
+#endif  // FS_INTERNAL_H_

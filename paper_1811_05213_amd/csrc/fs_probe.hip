@@ -1,0 +1,83 @@
+// fs_probe.hip - ahead-of-time kernels: the streaming-copy probe and the workspace fill.
+// Also instantiates the building blocks of fs_device.h once, so that a plain hipcc build
+// checks the header that generated kernels are prefixed with.
+#include <hip/hip_runtime.h>
+
+#include "fs_device.h"
+
+typedef unsigned int fs_uint4 __attribute__((ext_vector_type(4)));
+
+// Plain copy, 16 bytes per lane per access, grid-stride: the reference point for "what fraction
+// of the HBM roofline does a memory-bound kernel reach on this device".
+__global__ void __launch_bounds__(256) fs_copy_probe_kernel(const fs_uint4* __restrict__ src, fs_uint4* __restrict__ dst, long n_vec) {
+  const long stride = (long)gridDim.x * 256;
+  for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < n_vec; i += stride) dst[i] = src[i];
+}
+
+__global__ void __launch_bounds__(256) fs_zero_u32_kernel(unsigned int* p, long n) {
+  const long i = (long)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = 0u;
+}
+
+// Exercises every building block (never launched by the library).
+struct fs_selftest_kinds {
+  static FS_DEV float op(int k, float a, float b) { return k == 0 ? fs_red_op<FS_K_SUM>(a, b) : fs_red_op<FS_K_MAX>(a, b); }
+};
+__global__ void __launch_bounds__(256) fs_device_selftest_kernel(const void* in, void* out, float* part, fs_u32* tickets, int R) {
+  constexpr int V = 8, NVL = 2, L = 128, NV = 200, WG = 256, G = WG / L, C = NV * V, E = NVL * V;
+  __shared__ float lds_rr[2 * G * 2 * 2];
+  __shared__ float lds_col[G * C];
+  __shared__ fs_u32 flag;
+  const int tid = threadIdx.x, lir = tid & (L - 1), rg = tid / L;
+  float ca[E], cb[E];
+  for (int e = 0; e < E; ++e) ca[e] = 0.f, cb[e] = fs_red_identity<FS_K_MAX>();
+  int parity = 0;
+  for (int it = blockIdx.x; it * G < R; it += gridDim.x) {
+    const long row = (long)it * G + rg;
+    const bool rok = row < R;
+    float v[E];
+    fs_load_row<FS_DT_BF16, V, NVL, L, NV, true>(v, in, row * C, lir, rok);
+    float q = fs_segment_allreduce<FS_K_SUM, 64>(fs_lane_reduce<FS_K_SUM, V, NVL, L, NV, true>(v, lir));
+    float m = fs_segment_allreduce<FS_K_MAX, 64>(fs_lane_reduce<FS_K_MAX, V, NVL, L, NV, true>(v, lir));
+    const fs_xwave<2, 2> xw{lds_rr + (parity * G + rg) * 4, lir >> 6, (tid & 63) == 0};
+    xw.put(0, q);
+    xw.put(1, m);
+    fs_lds_barrier();
+    q = xw.get<FS_K_SUM>(0);
+    m = xw.get<FS_K_MAX>(1);
+    parity ^= 1;
+    for (int e = 0; e < E; ++e) {
+      v[e] = fs_round<FS_DT_BF16>(fs_gelu_tanh(fs_tanh(fs_exp(v[e] - m)) / q) + fs_sigmoid(fs_log(fs_rsqrt(fs_rcp(fs_sqrt(v[e]))))));
+      ca[e] = rok ? ca[e] + v[e] : ca[e];
+      cb[e] = rok ? fs_max(cb[e], v[e]) : cb[e];
+    }
+    fs_store_row<FS_DT_BF16, V, NVL, L, NV, true>(v, out, row * C, lir, rok);
+    fs_store_row_transposed<FS_DT_F32, V, NVL, L, NV, true>(v, out, R, row, lir, rok);
+  }
+  constexpr int CPT = (C + WG - 1) / WG;
+  float cv[2][CPT];
+  fs_colred_fold_wg<FS_K_SUM, V, NVL, L, NV, C, WG, CPT>(ca, cv[0], lds_col, lir, rg);
+  fs_colred_fold_wg<FS_K_MAX, V, NVL, L, NV, C, WG, CPT>(cb, cv[1], lds_col, lir, rg);
+  if (fs_colred_fold_grid<2, C, WG, CPT, 32, fs_selftest_kinds>(cv, part, tickets, &flag))
+    for (int i = 0; i < CPT; ++i)
+      if (tid + i * WG < C) fs_store1<FS_DT_F32>(out, tid + i * WG, cv[0][i] + cv[1][i]);
+}
+
+namespace fs {
+
+int launch_copy_probe(const void* src, void* dst, size_t bytes, hipStream_t stream) {
+  const long n_vec = (long)(bytes / 16);
+  if (n_vec == 0) return 0;
+  long blocks = (n_vec + 255) / 256;
+  if (blocks > 256 * 32) blocks = 256 * 32;
+  hipLaunchKernelGGL(fs_copy_probe_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, (const fs_uint4*)src, (fs_uint4*)dst, n_vec);
+  return (int)hipGetLastError();
+}
+
+int launch_zero_u32(void* p, size_t count, hipStream_t stream) {
+  if (count == 0) return 0;
+  hipLaunchKernelGGL(fs_zero_u32_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, stream, (unsigned int*)p, (long)count);
+  return (int)hipGetLastError();
+}
+
+}  // namespace fs

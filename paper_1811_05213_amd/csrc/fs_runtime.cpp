@@ -1,0 +1,386 @@
+// fs_runtime.cpp - the C ABI: plan creation (group, schedule, generate, compile), launches,
+// introspection.  Kernels are compiled at plan creation with the HIP run-time compiler for
+// gfx950 only; compilation needs no GPU, loading and launching do.
+#include <dlfcn.h>
+#include <hip/hip_runtime_api.h>
+#include <hip/hiprtc.h>
+#include <sys/stat.h>
+#include <unistd.h>
+
+#include <cstdlib>
+#include <cstring>
+#include <fstream>
+#include <set>
+
+#include "fs_internal.h"
+
+namespace fs {
+int launch_copy_probe(const void* src, void* dst, size_t bytes, hipStream_t stream);
+int launch_zero_u32(void* p, size_t count, hipStream_t stream);
+
+namespace {
+
+uint64_t fnv1a(const std::string& s, uint64_t h = 1469598103934665603ull) {
+  for (unsigned char c : s) {
+    h ^= c;
+    h *= 1099511628211ull;
+  }
+  return h;
+}
+
+std::string cache_dir() {
+  if (const char* e = getenv("FS_KERNEL_CACHE")) return e;
+  Dl_info info;
+  if (dladdr((void*)&cache_dir, &info) && info.dli_fname) {
+    std::string p = info.dli_fname;
+    const size_t slash = p.rfind('/');
+    if (slash != std::string::npos) return p.substr(0, slash) + "/kcache";
+  }
+  return "";
+}
+
+const char* kCompileOptions[] = {"--offload-arch=gfx950", "-O3",      "-std=c++17",     "-ffp-contract=off",
+                                 "-Xclang",               "-target-feature", "-Xclang", "-packed-fp32-ops"};
+constexpr int kNumCompileOptions = 8;
+
+bool read_file(const std::string& path, std::vector<char>* out) {
+  std::ifstream f(path, std::ios::binary);
+  if (!f) return false;
+  f.seekg(0, std::ios::end);
+  const std::streamoff n = f.tellg();
+  if (n <= 0) return false;
+  out->resize((size_t)n);
+  f.seekg(0);
+  f.read(out->data(), n);
+  return (bool)f;
+}
+
+void write_file_atomic(const std::string& path, const std::vector<char>& data) {
+  const std::string tmp = path + ".tmp" + std::to_string((long)getpid());
+  {
+    std::ofstream f(tmp, std::ios::binary);
+    if (!f) return;
+    f.write(data.data(), (std::streamsize)data.size());
+    if (!f) {
+      unlink(tmp.c_str());
+      return;
+    }
+  }
+  if (rename(tmp.c_str(), path.c_str()) != 0) unlink(tmp.c_str());
+}
+
+}  // namespace
+
+fs_status compile_kernel(const std::string& source, const std::string& name, std::vector<char>* code) {
+  std::string key_text = source;
+  for (int i = 0; i < kNumCompileOptions; ++i) key_text += kCompileOptions[i];
+  int rtc_major = 0, rtc_minor = 0;
+  hiprtcVersion(&rtc_major, &rtc_minor);
+  key_text += std::to_string(rtc_major) + "." + std::to_string(rtc_minor);
+  char key[40];
+  snprintf(key, sizeof(key), "%016llx%016llx", (unsigned long long)fnv1a(key_text),
+           (unsigned long long)fnv1a(key_text, 0x9e3779b97f4a7c15ull));
+  const std::string dir = cache_dir();
+  const std::string path = dir.empty() ? "" : dir + "/" + key + ".hsaco";
+  if (!path.empty() && read_file(path, code)) return FS_OK;
+
+  hiprtcProgram prog;
+  if (hiprtcCreateProgram(&prog, source.c_str(), (name + ".hip").c_str(), 0, nullptr, nullptr) != HIPRTC_SUCCESS)
+    FS_FAIL(FS_ERR_COMPILE, "hiprtcCreateProgram failed");
+  const hiprtcResult rc = hiprtcCompileProgram(prog, kNumCompileOptions, kCompileOptions);
+  if (rc != HIPRTC_SUCCESS) {
+    size_t n = 0;
+    hiprtcGetProgramLogSize(prog, &n);
+    std::string log(n, '\0');
+    if (n) hiprtcGetProgramLog(prog, &log[0]);
+    hiprtcDestroyProgram(&prog);
+    if (const char* dump = getenv("FS_DUMP_FAILED_SOURCE")) {
+      std::ofstream f(dump);
+      f << source;
+    }
+    FS_FAIL(FS_ERR_COMPILE, "kernel compilation failed: %s\n%.800s", hiprtcGetErrorString(rc), log.c_str());
+  }
+  size_t n = 0;
+  hiprtcGetCodeSize(prog, &n);
+  code->resize(n);
+  hiprtcGetCode(prog, code->data());
+  hiprtcDestroyProgram(&prog);
+  if (!path.empty()) {
+    mkdir(dir.c_str(), 0755);
+    write_file_atomic(path, *code);
+  }
+  return FS_OK;
+}
+
+}  // namespace fs
+
+using namespace fs;
+
+static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+extern "C" {
+
+const char* fs_last_error(void) { return error_buffer().c_str(); }
+
+fs_status fs_plan_create(const fs_graph_desc* desc, fs_plan** out_plan) {
+  if (!out_plan) FS_FAIL(FS_ERR_INVALID_ARG, "out_plan is NULL");
+  *out_plan = nullptr;
+  fs_plan* plan = new (std::nothrow) fs_plan();
+  if (!plan) FS_FAIL(FS_ERR_OOM, "out of host memory");
+  fs_status st = build_graph(desc, &plan->graph);
+  if (st != FS_OK) {
+    delete plan;
+    return st;
+  }
+  plan->opt.mode = desc->mode;
+  plan->opt.lds_budget = desc->lds_budget_bytes > 0 ? desc->lds_budget_bytes : 32768;
+  if (desc->hint) {
+    plan->opt.hint = *desc->hint;
+    plan->opt.has_hint = true;
+    const fs_sched_hint& h = plan->opt.hint;
+    if (h.lanes_per_row < 0 || h.wg_threads < 0 || h.max_workgroups < 0) {
+      delete plan;
+      FS_FAIL(FS_ERR_INVALID_ARG, "negative schedule hint");
+    }
+  }
+
+  std::vector<std::vector<int>> ordered;
+  st = form_groups(plan->graph, desc, plan->opt, &plan->group_of, &ordered);
+  if (st != FS_OK) {
+    delete plan;
+    return st;
+  }
+  const Graph& g = plan->graph;
+  plan->groups.resize(ordered.size());
+  // group ids follow launch order
+  for (size_t gi = 0; gi < ordered.size(); ++gi)
+    for (int m : ordered[gi]) plan->group_of[m] = (int)gi;
+  for (size_t gi = 0; gi < ordered.size(); ++gi) {
+    st = analyse_group(g, ordered[gi], plan->group_of, (int)gi, plan->opt, &plan->groups[gi]);
+    if (st == FS_OK) st = generate_kernel(g, &plan->groups[gi], (int)gi);
+    if (st != FS_OK) {
+      delete plan;
+      return st;
+    }
+  }
+
+  // workspace: [tickets][tensors crossing group boundaries][column-reduction partials]
+  size_t off = 0;
+  for (GroupPlan& gp : plan->groups) {
+    gp.ticket_offset = off;
+    off += (size_t)gp.n_tickets * 4;
+  }
+  plan->ticket_bytes = align_up(off, 256);
+  off = plan->ticket_bytes;
+  for (GroupPlan& gp : plan->groups)
+    for (const ExtTensor& e : gp.ext_out)
+      if (g.output_index[e.node] < 0 && !plan->ws_tensor_offset.count(e.node)) {
+        plan->ws_tensor_offset[e.node] = off;
+        off = align_up(off + (size_t)g.nodes[e.node].rows * g.nodes[e.node].cols * dtype_size(e.dtype), 256);
+      }
+  for (GroupPlan& gp : plan->groups)
+    if (gp.part_bytes) {
+      gp.part_offset = off;
+      off = align_up(off + gp.part_bytes, 256);
+    }
+  plan->workspace_bytes = off;
+
+  plan->min_hbm_bytes = 0;
+  for (int id : g.input_ids) {
+    bool used = false;  // only inputs some live node reads
+    for (const GroupPlan& gp : plan->groups)
+      for (const ExtTensor& e : gp.ext_in) used |= e.node == id;
+    if (used) plan->min_hbm_bytes += (uint64_t)g.nodes[id].rows * g.nodes[id].cols * dtype_size(g.nodes[id].dtype);
+  }
+  for (int o : g.outputs) plan->min_hbm_bytes += (uint64_t)g.nodes[o].rows * g.nodes[o].cols * dtype_size(g.nodes[o].dtype);
+  plan->launched_hbm_bytes = 0;
+  for (const GroupPlan& gp : plan->groups) plan->launched_hbm_bytes += gp.min_hbm_bytes;
+
+  // one translation unit per plan: the building blocks once, then every distinct kernel body
+  std::string tu = device_header_source();
+  std::set<std::string> seen;
+  for (const GroupPlan& gp : plan->groups)
+    if (seen.insert(gp.kernel_name).second) tu += "\n" + gp.source;
+  st = compile_kernel(tu, "fs_plan", &plan->code);
+  if (st != FS_OK) {
+    delete plan;
+    return st;
+  }
+  *out_plan = plan;
+  return FS_OK;
+}
+
+fs_status fs_plan_destroy(fs_plan* plan) {
+  if (!plan) return FS_OK;
+  for (auto& kv : plan->loaded)
+    for (void* m : kv.second.modules)
+      if (m) (void)hipModuleUnload((hipModule_t)m);
+  delete plan;
+  return FS_OK;
+}
+
+fs_status fs_plan_workspace_bytes(const fs_plan* plan, size_t* bytes) {
+  if (!plan || !bytes) FS_FAIL(FS_ERR_INVALID_ARG, "NULL argument");
+  *bytes = plan->workspace_bytes;
+  return FS_OK;
+}
+
+static fs_status load_on_device(fs_plan* plan, int device, fs_plan::Loaded** out) {
+  std::lock_guard<std::mutex> lk(plan->mu);
+  auto it = plan->loaded.find(device);
+  if (it != plan->loaded.end()) {
+    *out = &it->second;
+    return FS_OK;
+  }
+  hipModule_t mod;
+  hipError_t e = hipModuleLoadData(&mod, plan->code.data());
+  if (e != hipSuccess) FS_FAIL(FS_ERR_HIP, "hipModuleLoadData: %s", hipGetErrorString(e));
+  fs_plan::Loaded ld;
+  ld.modules.push_back((void*)mod);
+  for (const GroupPlan& gp : plan->groups) {
+    hipFunction_t fn;
+    e = hipModuleGetFunction(&fn, mod, gp.kernel_name.c_str());
+    if (e != hipSuccess) {
+      (void)hipModuleUnload(mod);
+      FS_FAIL(FS_ERR_HIP, "hipModuleGetFunction(%s): %s", gp.kernel_name.c_str(), hipGetErrorString(e));
+    }
+    ld.functions.push_back((void*)fn);
+  }
+  *out = &(plan->loaded[device] = std::move(ld));
+  return FS_OK;
+}
+
+static fs_status check_workspace(const fs_plan* plan, const void* workspace, size_t workspace_bytes) {
+  if (plan->workspace_bytes == 0) return FS_OK;
+  if (!workspace) FS_FAIL(FS_ERR_WORKSPACE, "workspace is NULL but the plan needs %zu bytes", plan->workspace_bytes);
+  if (workspace_bytes < plan->workspace_bytes)
+    FS_FAIL(FS_ERR_WORKSPACE, "workspace has %zu bytes, the plan needs %zu", workspace_bytes, plan->workspace_bytes);
+  if (((uintptr_t)workspace & 255) != 0) FS_FAIL(FS_ERR_WORKSPACE, "workspace is not 256-byte aligned");
+  return FS_OK;
+}
+
+fs_status fs_plan_workspace_init(fs_plan* plan, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!plan) FS_FAIL(FS_ERR_INVALID_ARG, "plan is NULL");
+  fs_status st = check_workspace(plan, workspace, workspace_bytes);
+  if (st != FS_OK) return st;
+  if (plan->ticket_bytes == 0) return FS_OK;
+  const int e = launch_zero_u32(workspace, plan->ticket_bytes / 4, (hipStream_t)hip_stream);
+  if (e != 0) FS_FAIL(FS_ERR_HIP, "fill kernel launch: %s", hipGetErrorString((hipError_t)e));
+  return FS_OK;
+}
+
+fs_status fs_plan_run(fs_plan* plan, const void* const* inputs, void* const* outputs, void* workspace,
+                      size_t workspace_bytes, void* hip_stream) {
+  if (!plan || !outputs) FS_FAIL(FS_ERR_INVALID_ARG, "NULL argument");
+  const Graph& g = plan->graph;
+  if (!g.input_ids.empty() && !inputs) FS_FAIL(FS_ERR_INVALID_ARG, "inputs is NULL");
+  for (size_t k = 0; k < g.input_ids.size(); ++k)
+    if (!inputs[k] || ((uintptr_t)inputs[k] & 15)) FS_FAIL(FS_ERR_INVALID_ARG, "inputs[%zu] is NULL or not 16-byte aligned", k);
+  for (size_t k = 0; k < g.outputs.size(); ++k)
+    if (!outputs[k] || ((uintptr_t)outputs[k] & 15)) FS_FAIL(FS_ERR_INVALID_ARG, "outputs[%zu] is NULL or not 16-byte aligned", k);
+  fs_status st = check_workspace(plan, workspace, workspace_bytes);
+  if (st != FS_OK) return st;
+
+  int device = 0;
+  hipError_t e = hipGetDevice(&device);
+  if (e != hipSuccess) FS_FAIL(FS_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e));
+  fs_plan::Loaded* ld = nullptr;
+  st = load_on_device(plan, device, &ld);
+  if (st != FS_OK) return st;
+
+  char* ws = (char*)workspace;
+  auto tensor_ptr = [&](int node) -> void* {
+    if (g.input_index[node] >= 0) return const_cast<void*>(inputs[g.input_index[node]]);
+    if (g.output_index[node] >= 0) return outputs[g.output_index[node]];
+    return ws + plan->ws_tensor_offset.at(node);
+  };
+
+  for (size_t gi = 0; gi < plan->groups.size(); ++gi) {
+    const GroupPlan& gp = plan->groups[gi];
+    // kernarg block: { void* p[NP]; float* part; u32* tickets; int R; int n_iters; }
+    alignas(8) char buf[8 * 48 + 32];
+    size_t n = 0;
+    auto push_ptr = [&](void* p) {
+      memcpy(buf + n, &p, 8);
+      n += 8;
+    };
+    for (const ExtTensor& t : gp.ext_in) push_ptr(tensor_ptr(t.node));
+    for (const ExtTensor& t : gp.ext_out) push_ptr(tensor_ptr(t.node));
+    push_ptr(gp.part_bytes ? (void*)(ws + gp.part_offset) : nullptr);
+    push_ptr(gp.n_tickets ? (void*)(ws + gp.ticket_offset) : nullptr);
+    const int R = gp.R, iters = gp.s.n_iters;
+    memcpy(buf + n, &R, 4);
+    memcpy(buf + n + 4, &iters, 4);
+    n += 8;
+    size_t size = n;
+    void* config[] = {HIP_LAUNCH_PARAM_BUFFER_POINTER, buf, HIP_LAUNCH_PARAM_BUFFER_SIZE, &size, HIP_LAUNCH_PARAM_END};
+    e = hipModuleLaunchKernel((hipFunction_t)ld->functions[gi], (unsigned)gp.s.grid, 1, 1, (unsigned)gp.s.WG, 1, 1, 0,
+                              (hipStream_t)hip_stream, nullptr, config);
+    if (e != hipSuccess) FS_FAIL(FS_ERR_HIP, "launch of group %zu (%s): %s", gi, gp.kernel_name.c_str(), hipGetErrorString(e));
+  }
+  return FS_OK;
+}
+
+fs_status fs_plan_stats(const fs_plan* plan, int32_t* num_groups, int32_t* num_launches, uint64_t* min_hbm_bytes,
+                        uint64_t* launched_hbm_bytes) {
+  if (!plan) FS_FAIL(FS_ERR_INVALID_ARG, "plan is NULL");
+  if (num_groups) *num_groups = (int32_t)plan->groups.size();
+  if (num_launches) *num_launches = (int32_t)plan->groups.size();
+  if (min_hbm_bytes) *min_hbm_bytes = plan->min_hbm_bytes;
+  if (launched_hbm_bytes) *launched_hbm_bytes = plan->launched_hbm_bytes;
+  return FS_OK;
+}
+
+fs_status fs_plan_group_info(const fs_plan* plan, int32_t group, fs_group_info* o) {
+  if (!plan || !o) FS_FAIL(FS_ERR_INVALID_ARG, "NULL argument");
+  if (group < 0 || group >= (int)plan->groups.size()) FS_FAIL(FS_ERR_INVALID_ARG, "group %d out of range", group);
+  const GroupPlan& gp = plan->groups[group];
+  o->num_nodes = (int32_t)gp.members.size();
+  o->dom_rows = gp.R;
+  o->dom_cols = gp.C;
+  o->lanes_per_row = gp.s.L;
+  o->vec_elems = gp.s.V;
+  o->elems_per_lane = gp.s.E;
+  o->wg_threads = gp.s.WG;
+  o->rows_per_iter = gp.s.G;
+  o->grid = gp.s.grid;
+  o->lds_bytes = gp.s.lds_bytes;
+  o->num_row_reduces = (int32_t)gp.row_reduces.size();
+  o->num_col_reduces = (int32_t)gp.col_reduces.size();
+  o->num_ext_inputs = (int32_t)gp.ext_in.size();
+  o->num_ext_outputs = (int32_t)gp.ext_out.size();
+  o->min_hbm_bytes = gp.min_hbm_bytes;
+  o->scratch_bytes = gp.part_bytes + (uint64_t)gp.n_tickets * 4;
+  return FS_OK;
+}
+
+fs_status fs_plan_node_groups(const fs_plan* plan, int32_t* out, int32_t num_nodes) {
+  if (!plan || !out) FS_FAIL(FS_ERR_INVALID_ARG, "NULL argument");
+  if (num_nodes != plan->graph.n()) FS_FAIL(FS_ERR_INVALID_ARG, "num_nodes %d, plan has %d", num_nodes, plan->graph.n());
+  for (int i = 0; i < num_nodes; ++i) out[i] = plan->group_of[i];
+  return FS_OK;
+}
+
+fs_status fs_plan_group_source(const fs_plan* plan, int32_t group, const char** out_src) {
+  if (!plan || !out_src) FS_FAIL(FS_ERR_INVALID_ARG, "NULL argument");
+  if (group < 0 || group >= (int)plan->groups.size()) FS_FAIL(FS_ERR_INVALID_ARG, "group %d out of range", group);
+  *out_src = plan->groups[group].source.c_str();
+  return FS_OK;
+}
+
+fs_status fs_plan_group_kernel_name(const fs_plan* plan, int32_t group, const char** out_name) {
+  if (!plan || !out_name) FS_FAIL(FS_ERR_INVALID_ARG, "NULL argument");
+  if (group < 0 || group >= (int)plan->groups.size()) FS_FAIL(FS_ERR_INVALID_ARG, "group %d out of range", group);
+  *out_name = plan->groups[group].kernel_name.c_str();
+  return FS_OK;
+}
+
+fs_status fs_copy_probe(const void* src, void* dst, size_t bytes, void* hip_stream) {
+  if (!src || !dst || (bytes & 15) || ((uintptr_t)src & 15) || ((uintptr_t)dst & 15))
+    FS_FAIL(FS_ERR_INVALID_ARG, "copy probe needs 16-byte aligned pointers and a multiple of 16 bytes");
+  const int e = launch_copy_probe(src, dst, bytes, (hipStream_t)hip_stream);
+  if (e != 0) FS_FAIL(FS_ERR_HIP, "copy probe launch: %s", hipGetErrorString((hipError_t)e));
+  return FS_OK;
+}
+
+}  // extern "C"
