@@ -1,0 +1,203 @@
+#!/usr/bin/env python3
+"""Benchmark of the stitched-kernel hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 2] [--no-extras] [--no-cpu]
+
+A step is one fs_plan_run of the whole fused subgraph on one batch of seeded synthetic input
+already resident in HBM.  The headline line is workload 2 of the benchmark spec (LayerNorm + bias +
+tanh-GeLU, bf16 [16384,1024]); `value` is effective HBM GB/s = minimal bytes (every plan input
+read once + every plan output written once) / time per step.  Steps cycle through enough
+distinct buffer sets (>= 1.5 GiB in total) that the 256 MB last-level cache cannot serve them.
+Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import statistics
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def build_sets(plan, graph, host_inputs, device, total_bytes_target):
+    """Distinct device buffer sets of one workload (same seeded content, different addresses)."""
+    import torch
+    from paper_1811_05213_amd.runner import DeviceRun, to_device
+    from workloads import min_hbm_bytes
+    per_set = max(1, min_hbm_bytes(graph))
+    n_sets = max(1, min(64, -(-total_bytes_target // per_set)))
+    big_nodes = [graph.nodes[i] for i in graph.input_ids()]
+    first = DeviceRun(plan, device)
+    first.set_inputs(host_inputs)
+    runs = [first]
+    for _ in range(n_sets - 1):
+        r = DeviceRun(plan, device)
+        # small vectors are shared, large tensors get their own copy
+        r.set_device_inputs([t.clone() if n.rows * n.cols > 65536 else t for t, n in zip(first.inputs, big_nodes)])
+        runs.append(r)
+    torch.cuda.synchronize()
+    return runs
+
+
+def time_plan(runs, steps, warmup):
+    """Average ms per step over `steps` launches cycling through `runs`, via events on the launch stream."""
+    import torch
+    n = len(runs)
+    for i in range(warmup):
+        runs[i % n].launch()
+    torch.cuda.synchronize()
+    start, end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    start.record()
+    for i in range(steps):
+        runs[i % n].launch()
+    end.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    return start.elapsed_time(end) / steps, wall_ms / steps
+
+
+def time_copy_probe(nbytes, reps=20):
+    import torch
+    from paper_1811_05213_amd import copy_probe
+    n_sets = 4
+    srcs = [torch.empty(nbytes, dtype=torch.uint8, device="cuda:0").random_(0, 255) for _ in range(n_sets)]
+    dsts = [torch.empty(nbytes, dtype=torch.uint8, device="cuda:0") for _ in range(n_sets)]
+    stream = torch.cuda.current_stream().cuda_stream
+    for i in range(4):
+        copy_probe(srcs[i % n_sets].data_ptr(), dsts[i % n_sets].data_ptr(), nbytes, stream)
+    torch.cuda.synchronize()
+    s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    s.record()
+    for i in range(reps):
+        copy_probe(srcs[i % n_sets].data_ptr(), dsts[i % n_sets].data_ptr(), nbytes, stream)
+    e.record()
+    torch.cuda.synchronize()
+    ms = s.elapsed_time(e) / reps
+    return 2 * nbytes / ms / 1e6  # GB/s (read + write)
+
+
+def measure_workload(cfg, steps, warmup, with_unfused=True, rows=None):
+    import torch
+    from paper_1811_05213_amd import Plan, FS_MODE_UNFUSED
+    from workloads import workload, min_hbm_bytes
+    g, ins, name = workload(cfg, rows)
+    out = {"workload": name}
+    target = int(1.5 * 2 ** 30)
+    for mode, label in ((0, "stitched"),) + (((FS_MODE_UNFUSED, "unfused"),) if with_unfused else ()):
+        plan = Plan(g, mode=mode)
+        st = plan.stats()
+        runs = build_sets(plan, g, ins, "cuda:0", target if mode == 0 or st["launched_hbm_bytes"] < 2 ** 31 else 0)
+        ms, wall_ms = time_plan(runs, steps, warmup)
+        hot_ms, _ = time_plan(runs[:1], steps, 2)
+        out[label] = {"ms": ms, "ms_hot": hot_ms, "wall_ms": wall_ms, "launches": st["num_launches"],
+                      "launched_hbm_bytes": st["launched_hbm_bytes"], "buffer_sets": len(runs)}
+        if mode == 0:
+            out["min_hbm_bytes"] = st["min_hbm_bytes"]
+            out["gbs"] = st["min_hbm_bytes"] / ms / 1e6
+            out["frac_of_peak"] = out["gbs"] / HBM_PEAK_GBS
+            out["groups"] = [plan.group_info(i) for i in range(min(st["num_groups"], 4))]
+            out["kernel"] = plan.group_kernel_name(0)
+        del runs
+        plan.destroy()
+        torch.cuda.empty_cache()
+    if with_unfused:
+        out["speedup_vs_unfused"] = out["unfused"]["ms"] / out["stitched"]["ms"]
+        out["launch_ratio"] = out["stitched"]["launches"] / out["unfused"]["launches"]
+    assert min_hbm_bytes(g) == out["min_hbm_bytes"]
+    return out
+
+
+def cpu_baseline(cfg):
+    """The CPU oracle as it stands, timed on the host cores of this machine (a reference, not the target)."""
+    import oracle
+    from workloads import workload, min_hbm_bytes
+    g, ins, name = workload(cfg)
+    cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "0") or 0) or (os.cpu_count() or 1))
+    oracle.run(g, ins, cores)  # warm the pages
+    times = []
+    for _ in range(5):
+        t = time.perf_counter()
+        oracle.run(g, ins, cores)
+        times.append(time.perf_counter() - t)
+    dt = statistics.median(times)
+    return {"value": min_hbm_bytes(g) / dt / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
+            "sample": f"the whole workload ({name}), median of 5 runs, {dt * 1e3:.0f} ms each"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--workload", type=int, default=2, help="BASELINE.json config number (1-5) for the headline line")
+    ap.add_argument("--no-extras", action="store_true", help="skip the other workloads and the copy probe")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1")
+        sys.exit(2)
+
+    import torch
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible; the stitched kernels only run on a MI355X")
+        sys.exit(3)
+    from paper_1811_05213_amd import lib
+    lib()  # fails loudly if libfs.so is missing
+
+    head = measure_workload(args.workload, args.steps, args.warmup)
+    log("headline", json.dumps(head))
+    extras = {}
+    copy_gbs = None
+    if not args.no_extras:
+        copy_gbs = time_copy_probe(1 << 29)
+        for cfg in (1, 2, 3, 4, 5):
+            if cfg == args.workload:
+                continue
+            steps = {1: 400, 2: 400, 3: 30, 4: 200, 5: 50}[cfg]
+            extras[f"cfg{cfg}"] = measure_workload(cfg, steps, max(4, steps // 10))
+            log(f"cfg{cfg}", json.dumps(extras[f"cfg{cfg}"]))
+    cpu = None if args.no_cpu else cpu_baseline(args.workload)
+
+    ms = head["stitched"]["ms"]
+    line = {
+        "metric": "effective HBM GB/s (% of peak) per fused subgraph; fused vs unfused speedup",
+        "value": head["gbs"],
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": head["workload"], "mode": "stitched", "launches_per_step": head["stitched"]["launches"],
+                   "buffer_sets": head["stitched"]["buffer_sets"], "min_hbm_bytes": head["min_hbm_bytes"]},
+        "pct_of_hbm_peak": 100.0 * head["frac_of_peak"],
+        "speedup_vs_unfused": head.get("speedup_vs_unfused"),
+        "launch_ratio": head.get("launch_ratio"),
+        "unfused_ms_per_step": head.get("unfused", {}).get("ms"),
+        "roofline": {"bound": "hbm", "achieved": head["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": head["frac_of_peak"], "traffic": None, "kernel": head["kernel"],
+                     "algorithmic_bytes_per_launch": head["min_hbm_bytes"], "avg_launch_us": ms * 1e3},
+        "cpu_baseline": cpu,
+        "copy_probe_gbs": copy_gbs,
+        "other_workloads": extras,
+    }
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -152,10 +152,13 @@ struct Emitter {
     os << "// work space [R," << C << "], " << s.L << " lanes/row, " << s.E << " elements/lane, workgroup " << s.WG << "\n";
     os << "struct " << kname << "_args { void* p[" << NP << "]; float* part; fs_u32* tickets; int R; int n_iters; };\n";
     if (K > 0) {
-      os << "struct " << kname << "_kinds { static FS_DEV float op(int k, float a, float b) { switch (k) {";
+      os << "struct " << kname << "_kinds {\n  static FS_DEV float op(int k, float a, float b) { switch (k) {";
       for (int k = 0; k < K; ++k)
         os << " case " << k << ": return fs_red_op<" << g.nodes[gp.col_reduces[k]].attr_i << ">(a, b);";
-      os << " } return a; } };\n";
+      os << " } return a; }\n  static FS_DEV float identity(int k) { switch (k) {";
+      for (int k = 0; k < K; ++k)
+        os << " case " << k << ": return fs_red_identity<" << g.nodes[gp.col_reduces[k]].attr_i << ">();";
+      os << " } return 0.0f; }\n};\n";
     }
     os << "extern \"C\" __global__ void __launch_bounds__(" << s.WG << ") " << kname << "(const " << kname << "_args a) {\n";
     os << "  constexpr int V = " << s.V << ", NVL = " << s.NVL << ", L = " << s.L << ", NV = " << s.NV << ", E = NVL * V, WG = " << s.WG
@@ -270,21 +273,24 @@ struct Emitter {
 
     // ---- epilogue: finish the column reductions ----
     if (K > 0) {
-      os << "  {\n    constexpr int CPT = (C + WG - 1) / WG;\n    float cv[" << K << "][CPT];\n";
+      const int FV = C % 4 == 0 ? 4 : C % 2 == 0 ? 2 : 1;
+      os << "  {\n    constexpr int FV = " << FV << ";\n    typedef fs_colfold<" << K << ", C, WG, FV> S;\n    float cv[S::CPT][FV];\n";
       for (int k = 0; k < K; ++k) {
         const int m = gp.col_reduces[k];
-        os << "    fs_colred_fold_wg<" << g.nodes[m].attr_i << ", V, NVL, L, NV, C, WG, CPT>(ca" << loc(m) << ", cv[" << k << "], lds_col, lir, rg);\n";
+        os << "    fs_colred_fold_wg<" << g.nodes[m].attr_i << ", " << k << ", " << K << ", V, NVL, L, NV, C, WG, FV>(ca" << loc(m)
+           << ", cv, lds_col, lir, rg);\n";
       }
-      os << "    if (fs_colred_fold_grid<" << K << ", C, WG, CPT, " << s.fan_in << ", " << kname
+      os << "    if (fs_colred_fold_grid<" << K << ", C, WG, FV, " << s.fan_in << ", " << kname
          << "_kinds>(cv, a.part, a.tickets, &lds_flag)) {\n";
-      os << "      _Pragma(\"unroll\") for (int i = 0; i < CPT; ++i) {\n        const int col = tid + i * WG;\n        if (col < C) {\n";
+      os << "      _Pragma(\"unroll\") for (int i = 0; i < S::CPT; ++i) {\n        const int c = tid + i * WG;\n"
+         << "        if (c < S::NCH) {\n          const int k = c / S::CH, col0 = (c % S::CH) * FV;\n";
       for (int k = 0; k < K; ++k) {
         const int m = gp.col_reduces[k];
         const ExtTensor* e = find_out(m);
         if (!e) continue;
         const fs_node& n = g.nodes[m];
-        os << "          fs_store1<" << e->dtype << ">(a.p[" << e->arg << "], col, fs_round<" << n.dtype << ">(cv[" << k << "][i]"
-           << (n.attr_i == FS_RED_MEAN ? " / (float)a.R" : "") << "));\n";
+        os << "          if (k == " << k << ") { _Pragma(\"unroll\") for (int f = 0; f < FV; ++f) fs_store1<" << e->dtype << ">(a.p[" << e->arg
+           << "], col0 + f, fs_round<" << n.dtype << ">(cv[i][f]" << (n.attr_i == FS_RED_MEAN ? " / (float)a.R" : "") << ")); }\n";
       }
       os << "        }\n      }\n    }\n  }\n";
     }

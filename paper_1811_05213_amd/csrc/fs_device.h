@@ -286,14 +286,67 @@ template <int K, int WPR> struct fs_xwave {
 //            the last arriver to fold that group's partials in index order, and it moves up
 //            one level.  The only atomic is the ticket.  The survivor of the top level holds
 //            the result.
+// The K column reductions of a kernel travel together as one vector of K*C floats, cut into
+// chunks of FV floats (FV = 4 when C allows).  Thread t owns chunks t, t+WG, ...; chunk c
+// belongs to reduction c / (C/FV) and covers columns (c % (C/FV))*FV onwards.
 // ------------------------------------------------------------------------------------------
+template <int K, int C, int WG, int FV> struct fs_colfold {
+  static constexpr int CH = C / FV;                   // chunks per reduction
+  static constexpr int NCH = K * CH;                  // chunks per workgroup partial
+  static constexpr int CPT = (NCH + WG - 1) / WG;     // chunks per thread
+};
 
-// Stage 1, in-workgroup fold.  acc: the lane's per-column accumulators in the row layout.
-// On return thread t holds columns t, t+WG, ... (CPT of them) in `mine`.
-template <int KIND, int V, int NVL, int L, int NV, int C, int WG, int CPT>
-FS_DEV void fs_colred_fold_wg(const float (&acc)[NVL * V], float (&mine)[CPT], float* lds /* G*C floats */, int lir, int rg) {
+// 4/8/16-byte memory access that is coherent at device scope without fences: the sc1 bit makes a
+// store write through to, and a load read from, the level all 8 XCDs share.
+typedef fs_u32 fs_u32x2 __attribute__((ext_vector_type(2)));
+typedef fs_u32 fs_u32x4 __attribute__((ext_vector_type(4)));
+#define FS_AUX_SC1 0x10
+FS_DEV __amdgpu_buffer_rsrc_t fs_make_rsrc(const void* base, fs_u32 bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
+}
+template <int FV> FS_DEV void fs_load_dev(float (&dst)[FV], __amdgpu_buffer_rsrc_t r, fs_u32 byte_off) {
+  if constexpr (FV == 4) {
+    // (each element is copied to a scalar first: a bit_cast applied directly to a vector
+    // element expression reads element 0 with this compiler)
+    const fs_u32x4 u = __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, FS_AUX_SC1);
+#pragma unroll
+    for (int f = 0; f < 4; ++f) {
+      const fs_u32 w = u[f];
+      dst[f] = __builtin_bit_cast(float, w);
+    }
+  } else if constexpr (FV == 2) {
+    const fs_u32x2 u = __builtin_amdgcn_raw_buffer_load_b64(r, byte_off, 0, FS_AUX_SC1);
+    const fs_u32 w0 = u[0], w1 = u[1];
+    dst[0] = __builtin_bit_cast(float, w0);
+    dst[1] = __builtin_bit_cast(float, w1);
+  } else {
+    dst[0] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, byte_off, 0, FS_AUX_SC1));
+  }
+}
+template <int FV> FS_DEV void fs_store_dev(const float (&src)[FV], __amdgpu_buffer_rsrc_t r, fs_u32 byte_off) {
+  if constexpr (FV == 4) {
+    fs_u32x4 u;
+#pragma unroll
+    for (int f = 0; f < 4; ++f) u[f] = __builtin_bit_cast(fs_u32, src[f]);
+    __builtin_amdgcn_raw_buffer_store_b128(u, r, byte_off, 0, FS_AUX_SC1);
+  } else if constexpr (FV == 2) {
+    fs_u32x2 u;
+    u[0] = __builtin_bit_cast(fs_u32, src[0]);
+    u[1] = __builtin_bit_cast(fs_u32, src[1]);
+    __builtin_amdgcn_raw_buffer_store_b64(u, r, byte_off, 0, FS_AUX_SC1);
+  } else {
+    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(fs_u32, src[0]), r, byte_off, 0, FS_AUX_SC1);
+  }
+}
+
+// Stage 1, in-workgroup fold of reduction number KIDX.  acc: the lane's per-column accumulators
+// in the row layout.  Fills the chunks of `vals` that belong to reduction KIDX.
+template <int KIND, int KIDX, int K, int V, int NVL, int L, int NV, int C, int WG, int FV, int CPT>
+FS_DEV void fs_colred_fold_wg(const float (&acc)[NVL * V], float (&vals)[CPT][FV], float* lds /* G*C floats */, int lir, int rg) {
+  typedef fs_colfold<K, C, WG, FV> S;
+  static_assert(CPT == S::CPT, "chunks per thread");
   constexpr int G = WG / L;
-  __syncthreads(); // LDS area may still be in use by the previous fold
+  __syncthreads();  // the LDS area may still be read by the previous fold
 #pragma unroll
   for (int j = 0; j < NVL; ++j) {
     const int vi = j * L + lir;
@@ -304,65 +357,90 @@ FS_DEV void fs_colred_fold_wg(const float (&acc)[NVL * V], float (&mine)[CPT], f
   }
   __syncthreads();
 #pragma unroll
-  for (int i = 0; i < CPT; ++i) {
-    const int col = (int)threadIdx.x + i * WG;
-    float a = fs_red_identity<KIND>();
-    if (col < C) {
-      a = lds[col];
-      for (int g = 1; g < G; ++g) a = fs_red_op<KIND>(a, lds[g * C + col]);
+  for (int i = 0; i < S::CPT; ++i) {
+    const int c = (int)threadIdx.x + i * WG;
+    if (c >= KIDX * S::CH && c < (KIDX + 1) * S::CH) {
+      const int col0 = (c - KIDX * S::CH) * FV;
+#pragma unroll
+      for (int f = 0; f < FV; ++f) {
+        float a = lds[col0 + f];
+        for (int g = 1; g < G; ++g) a = fs_red_op<KIND>(a, lds[g * C + col0 + f]);
+        vals[i][f] = a;
+      }
     }
-    mine[i] = a;
   }
 }
 
-template <int KIND> FS_DEV float fs_red_op_dyn(float a, float b) { return fs_red_op<KIND>(a, b); }
-
-// Stage 2, grid-wide fold of K*C values per workgroup with fan-in F.
+// Stage 2, grid-wide fold with fan-in F.
 //   part     workspace, sum over levels of n_level*K*C floats
 //   tickets  workspace, one zero-initialised u32 per fan-in group per level; left zero on exit
 //   flag     one u32 of LDS
 // Returns true in exactly one workgroup, whose `vals` then hold the final values.
-template <int K, int C, int WG, int CPT, int F, typename KINDS>
-FS_DEV bool fs_colred_fold_grid(float (&vals)[K][CPT], float* part, fs_u32* tickets, fs_u32* flag) {
+//
+// Visibility across the 8 XCDs (each has its own L2) is obtained without device-scope fences,
+// which write back and invalidate a whole L2 and cost microseconds each: partials are written
+// with sc1 stores, every wavefront waits for its own stores to be acknowledged before the
+// workgroup barrier, lane 0 then bumps the ticket with an agent-scope atomic, and the folding
+// workgroup reads the partials with sc1 loads (never served by stale lines of its own L2).
+// The F loads of a chunk are independent and issued in batches, so a fold costs a few memory
+// round trips, not F of them; they are combined in index order, whichever workgroup folds.
+template <int K, int C, int WG, int FV, int F, typename KINDS, int CPT>
+FS_DEV bool fs_colred_fold_grid(float (&vals)[CPT][FV], float* part, fs_u32* tickets, fs_u32* flag) {
+  typedef fs_colfold<K, C, WG, FV> S;
+  static_assert(CPT == S::CPT, "chunks per thread");
+  constexpr int KC = K * C;
+  constexpr int FB = 8;  // loads in flight per chunk
   fs_u32 idx = blockIdx.x, n = gridDim.x;
   const int t = (int)threadIdx.x;
   while (n > 1) {
-    float* mine = part + (long)idx * (K * C);
+    {
+      const __amdgpu_buffer_rsrc_t mine = fs_make_rsrc(part + (long)idx * KC, KC * 4);
 #pragma unroll
-    for (int k = 0; k < K; ++k) {
-#pragma unroll
-      for (int i = 0; i < CPT; ++i) {
-        const int col = t + i * WG;
-        if (col < C) mine[k * C + col] = vals[k][i];
+      for (int i = 0; i < S::CPT; ++i) {
+        const int c = t + i * WG;
+        if (c < S::NCH) fs_store_dev<FV>(vals[i], mine, (fs_u32)c * (FV * 4));
       }
     }
-    __threadfence();  // release: this lane's partial is visible device-wide before the ticket
+    __builtin_amdgcn_s_waitcnt(0);  // this wavefront's partial stores are acknowledged
     __syncthreads();
     const fs_u32 grp = idx / F, first = grp * F;
     const fs_u32 cnt = (n - first) < (fs_u32)F ? (n - first) : (fs_u32)F;
     if (t == 0) {
-      const fs_u32 old = __hip_atomic_fetch_add(&tickets[grp], 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+      const fs_u32 old = __hip_atomic_fetch_add(&tickets[grp], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       const bool last = old == cnt - 1;
       if (last) __hip_atomic_store(&tickets[grp], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       *flag = last ? 1u : 0u;
     }
     __syncthreads();
     if (*flag == 0u) return false;
-    __threadfence();  // acquire: the other workgroups' partials
-    const float* gp = part + (long)first * (K * C);
+    const __amdgpu_buffer_rsrc_t theirs = fs_make_rsrc(part + (long)first * KC, cnt * (KC * 4));
 #pragma unroll
-    for (int k = 0; k < K; ++k) {
+    for (int i = 0; i < S::CPT; ++i) {
+      const int c = t + i * WG;
+      if (c < S::NCH) {
+        const int k = c / S::CH;
+        float a[FV];
 #pragma unroll
-      for (int i = 0; i < CPT; ++i) {
-        const int col = t + i * WG;
-        if (col < C) {
-          float a = gp[k * C + col];
-          for (fs_u32 j = 1; j < cnt; ++j) a = KINDS::op(k, a, gp[(long)j * (K * C) + k * C + col]);
-          vals[k][i] = a;
+        for (int f = 0; f < FV; ++f) a[f] = KINDS::identity(k);
+        for (fs_u32 jb = 0; jb < cnt; jb += FB) {
+          float tmp[FB][FV];
+#pragma unroll
+          for (int u = 0; u < FB; ++u) {
+            const fs_u32 j = (jb + u) < cnt ? (jb + u) : (cnt - 1);  // clamped: always a valid load
+            fs_load_dev<FV>(tmp[u], theirs, j * (KC * 4) + (fs_u32)c * (FV * 4));
+          }
+#pragma unroll
+          for (int u = 0; u < FB; ++u) {
+            const bool use = (jb + u) < cnt;
+#pragma unroll
+            for (int f = 0; f < FV; ++f) a[f] = use ? KINDS::op(k, a[f], tmp[u][f]) : a[f];
+          }
         }
+#pragma unroll
+        for (int f = 0; f < FV; ++f) vals[i][f] = a[f];
       }
     }
-    part += (long)n * (K * C);
+    part += (long)n * KC;
     const fs_u32 groups = (n + F - 1) / F;
     tickets += groups;
     idx = grp;

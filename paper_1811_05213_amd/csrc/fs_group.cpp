@@ -333,6 +333,69 @@ struct Former {
     return false;
   }
 
+  // direct producer -> consumer successors of a group
+  std::set<int> successors(int grp) const {
+    std::set<int> out;
+    for (int m : members[grp]) {
+      std::vector<int> us;
+      real_users(m, &us);
+      for (int u : us)
+        if (group_of[u] >= 0 && group_of[u] != grp) out.insert(group_of[u]);
+    }
+    return out;
+  }
+
+  // Second pass: fuse groups that are not (only) producer and consumer of each other.  This is
+  // the role of the paper's intra-layer ElementwiseFusion and of its multi-root computations
+  // (Sections 3.2 and 4.3): kernels over the same work space are merged when they read a common
+  // [R,C] tensor (one read instead of two) or when they are so small that the launch, not the
+  // traffic, is what they cost (the tunable footprint threshold of Section 3.2).
+  void merge_siblings() {
+    constexpr uint64_t kFootprintThreshold = 16ull << 20;
+    std::vector<GroupPlan> plan(members.size());
+    std::vector<char> valid(members.size(), 0);
+    auto analyse = [&](int grp) {
+      valid[grp] = !members[grp].empty() && analyse_group(g, members[grp], group_of, grp, opt, &plan[grp]) == FS_OK;
+    };
+    for (size_t grp = 0; grp < members.size(); ++grp) analyse((int)grp);
+    bool changed = true;
+    GroupPlan merged_plan;
+    while (changed) {
+      changed = false;
+      for (size_t a = 0; a < members.size() && !changed; ++a) {
+        if (!valid[a]) continue;
+        for (size_t b = a + 1; b < members.size() && !changed; ++b) {
+          if (!valid[b] || plan[a].R != plan[b].R || plan[a].C != plan[b].C) continue;
+          if (members[a].size() + members[b].size() > 96) continue;
+          // profitable?
+          bool share_full = false;
+          for (const ExtTensor& x : plan[a].ext_in)
+            for (const ExtTensor& y : plan[b].ext_in) share_full |= x.node == y.node && x.kind == KIND_FULL && y.kind == KIND_FULL;
+          for (const ExtTensor& x : plan[a].ext_out)
+            for (const ExtTensor& y : plan[b].ext_in) share_full |= x.node == y.node && y.kind == KIND_FULL;
+          for (const ExtTensor& x : plan[b].ext_out)
+            for (const ExtTensor& y : plan[a].ext_in) share_full |= x.node == y.node && y.kind == KIND_FULL;
+          const bool small = plan[a].min_hbm_bytes + plan[b].min_hbm_bytes <= kFootprintThreshold;
+          if (!share_full && !small) continue;
+          // a path a -> c -> ... -> b through a third group would become a cycle
+          bool cycle = false;
+          for (int c : successors((int)a)) cycle |= c != (int)b && reaches(c, (int)b);
+          for (int c : successors((int)b)) cycle |= c != (int)a && reaches(c, (int)a);
+          if (cycle) continue;
+          std::vector<int> merged = members[a];
+          merged.insert(merged.end(), members[b].begin(), members[b].end());
+          if (analyse_group(g, merged, group_of, (int)a, opt, &merged_plan) != FS_OK) continue;
+          for (int m : members[b]) group_of[m] = (int)a;
+          members[a] = merged;
+          members[b].clear();
+          valid[b] = 0;
+          plan[a] = merged_plan;
+          changed = true;
+        }
+      }
+    }
+  }
+
   fs_status topo_order(std::vector<std::vector<int>>* ordered) const {
     const int NG = (int)members.size();
     std::vector<std::set<int>> succ(NG);
@@ -435,6 +498,7 @@ fs_status form_groups(const Graph& g, const fs_graph_desc* desc, const PlanOptio
       f.group_of[id] = joined;
       f.members[joined].push_back(id);
     }
+    f.merge_siblings();
   }
   *group_of = f.group_of;
   return f.topo_order(ordered);

@@ -22,6 +22,7 @@ __global__ void __launch_bounds__(256) fs_zero_u32_kernel(unsigned int* p, long 
 // Exercises every building block (never launched by the library).
 struct fs_selftest_kinds {
   static FS_DEV float op(int k, float a, float b) { return k == 0 ? fs_red_op<FS_K_SUM>(a, b) : fs_red_op<FS_K_MAX>(a, b); }
+  static FS_DEV float identity(int k) { return k == 0 ? fs_red_identity<FS_K_SUM>() : fs_red_identity<FS_K_MAX>(); }
 };
 __global__ void __launch_bounds__(256) fs_device_selftest_kernel(const void* in, void* out, float* part, fs_u32* tickets, int R) {
   constexpr int V = 8, NVL = 2, L = 128, NV = 200, WG = 256, G = WG / L, C = NV * V, E = NVL * V;
@@ -54,13 +55,14 @@ __global__ void __launch_bounds__(256) fs_device_selftest_kernel(const void* in,
     fs_store_row<FS_DT_BF16, V, NVL, L, NV, true>(v, out, row * C, lir, rok);
     fs_store_row_transposed<FS_DT_F32, V, NVL, L, NV, true>(v, out, R, row, lir, rok);
   }
-  constexpr int CPT = (C + WG - 1) / WG;
-  float cv[2][CPT];
-  fs_colred_fold_wg<FS_K_SUM, V, NVL, L, NV, C, WG, CPT>(ca, cv[0], lds_col, lir, rg);
-  fs_colred_fold_wg<FS_K_MAX, V, NVL, L, NV, C, WG, CPT>(cb, cv[1], lds_col, lir, rg);
-  if (fs_colred_fold_grid<2, C, WG, CPT, 32, fs_selftest_kinds>(cv, part, tickets, &flag))
-    for (int i = 0; i < CPT; ++i)
-      if (tid + i * WG < C) fs_store1<FS_DT_F32>(out, tid + i * WG, cv[0][i] + cv[1][i]);
+  constexpr int FV = 4;
+  typedef fs_colfold<2, C, WG, FV> S;
+  float cv[S::CPT][FV];
+  fs_colred_fold_wg<FS_K_SUM, 0, 2, V, NVL, L, NV, C, WG, FV>(ca, cv, lds_col, lir, rg);
+  fs_colred_fold_wg<FS_K_MAX, 1, 2, V, NVL, L, NV, C, WG, FV>(cb, cv, lds_col, lir, rg);
+  if (fs_colred_fold_grid<2, C, WG, FV, 32, fs_selftest_kinds>(cv, part, tickets, &flag))
+    for (int i = 0; i < S::CPT; ++i)
+      if (tid + i * WG < S::NCH) fs_store1<FS_DT_F32>(out, (tid + i * WG) * FV, cv[i][0] + cv[i][3]);
 }
 
 namespace fs {
