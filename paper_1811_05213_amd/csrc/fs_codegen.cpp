@@ -124,9 +124,9 @@ struct Emitter {
     const std::string nm = name(e.node, gp.kind.at(e.node));
     if (e.transposed) return;  // emitted with the node
     if (e.kind == KIND_FULL)
-      os << indent << "fs_store_row<" << e.dtype << ", " << tmpl_row() << ">(" << nm << ", a.p[" << e.arg << "], row0, lir, rok);\n";
+      os << indent << "fs_store_row<" << e.dtype << ", " << tmpl_row() << ">(" << nm << ", a.p[" << e.arg << "], row0, lir, vbase, rok);\n";
     else if (e.kind == KIND_COLV)
-      os << indent << "if (rok && lir == 0) fs_store1<" << e.dtype << ">(a.p[" << e.arg << "], row, " << nm << ");\n";
+      os << indent << "if (rok && lir == 0 && vbase == 0) fs_store1<" << e.dtype << ">(a.p[" << e.arg << "], row, " << nm << ");\n";
   }
 
   const ExtTensor* find_out(int node) const {
@@ -162,30 +162,35 @@ struct Emitter {
     }
     os << "extern \"C\" __global__ void __launch_bounds__(" << s.WG << ") " << kname << "(const " << kname << "_args a) {\n";
     os << "  constexpr int V = " << s.V << ", NVL = " << s.NVL << ", L = " << s.L << ", NV = " << s.NV << ", E = NVL * V, WG = " << s.WG
-       << ", G = WG / L, C = " << C << ";\n";
+       << ", G = WG / L, C = " << C << ", CT = " << s.CT << ";\n";
     os << "  constexpr bool RAGGED = " << (s.ragged ? "true" : "false") << ";\n";
     os << "  const int tid = (int)threadIdx.x, lir = tid & (L - 1), rg = tid / L;\n";
     os << "  const long R = a.R;\n";
-    os << "  (void)lir; (void)rg; (void)R; (void)C; (void)G;\n";
+    os << "  (void)lir; (void)rg; (void)R; (void)C; (void)G; (void)CT;\n";
+    const bool tiled = s.CT > 1;  // per-column values depend on the tile: handled inside the loop
     if (xwave) os << "  __shared__ float lds_rr[2 * G * " << WPR << " * " << KB << "];\n  int parity = 0;\n";
     if (K > 0) os << "  __shared__ float lds_col[G * C];\n  __shared__ fs_u32 lds_flag;\n";
 
     // ---- prologue: per-column values are loaded / computed once per workgroup ----
-    for (const ExtTensor& e : gp.ext_in)
-      if (e.kind == KIND_ROWV) {
-        os << "  float " << name(e.node, KIND_ROWV) << "[E];\n";
-        os << "  fs_load_row<" << e.dtype << ", " << tmpl_row() << ">(" << name(e.node, KIND_ROWV) << ", a.p[" << e.arg << "], 0, lir, true);\n";
+    auto emit_rowv = [&](const std::string& ind, const std::string& vb, const std::string& store_cond) {
+      for (const ExtTensor& e : gp.ext_in)
+        if (e.kind == KIND_ROWV) {
+          os << ind << "float " << name(e.node, KIND_ROWV) << "[E];\n";
+          os << ind << "fs_load_row<" << e.dtype << ", " << tmpl_row() << ">(" << name(e.node, KIND_ROWV) << ", a.p[" << e.arg << "], 0, lir, " << vb
+             << ", true);\n";
+        }
+      for (int m : gp.members) {
+        if (gp.level.at(m) >= 0) continue;
+        const fs_node& n = g.nodes[m];
+        const std::string nm = name(m, KIND_ROWV);
+        os << ind << "float " << nm << "[E];\n" << ind << "_Pragma(\"unroll\") for (int e = 0; e < E; ++e) " << nm << "[e] = fs_round<" << n.dtype
+           << ">(" << expr(n) << ");\n";
+        if (const ExtTensor* e = find_out(m))
+          os << ind << "if (" << store_cond << ") fs_store_row<" << e->dtype << ", " << tmpl_row() << ">(" << nm << ", a.p[" << e->arg
+             << "], 0, lir, " << vb << ", true);\n";
       }
-    for (int m : gp.members) {
-      if (gp.level.at(m) >= 0) continue;
-      const fs_node& n = g.nodes[m];
-      const std::string nm = name(m, KIND_ROWV);
-      os << "  float " << nm << "[E];\n  _Pragma(\"unroll\") for (int e = 0; e < E; ++e) " << nm << "[e] = fs_round<" << n.dtype << ">("
-         << expr(n) << ");\n";
-      if (const ExtTensor* e = find_out(m))
-        os << "  if (blockIdx.x == 0 && rg == 0) fs_store_row<" << e->dtype << ", " << tmpl_row() << ">(" << nm << ", a.p[" << e->arg
-           << "], 0, lir, true);\n";
-    }
+    };
+    if (!tiled) emit_rowv("  ", "0", "blockIdx.x == 0 && rg == 0");
     for (int k = 0; k < K; ++k) {
       const int m = gp.col_reduces[k];
       os << "  float ca" << loc(m) << "[E];\n  _Pragma(\"unroll\") for (int e = 0; e < E; ++e) ca" << loc(m) << "[e] = fs_red_identity<"
@@ -194,11 +199,17 @@ struct Emitter {
 
     // ---- the row loop ----
     os << "  for (int it = (int)blockIdx.x; it < a.n_iters; it += (int)gridDim.x) {\n";
-    os << "    const long row = (long)it * G + rg;\n    const bool rok = row < R;\n    const long row0 = row * C;\n    (void)row0;\n";
+    if (!tiled) {
+      os << "    const long row = (long)it * G + rg;\n    constexpr int vbase = 0;\n";
+    } else {
+      os << "    const long unit = (long)it * G + rg;\n    const long row = unit / CT;\n    const int vbase = (int)(unit % CT) * (NVL * L);\n";
+    }
+    os << "    const bool rok = row < R;\n    const long row0 = row * C;\n    (void)row0; (void)vbase;\n";
+    if (tiled) emit_rowv("    ", "vbase", "row == 0");
     for (const ExtTensor& e : gp.ext_in) {
       if (e.kind == KIND_FULL) {
         os << "    float " << name(e.node, KIND_FULL) << "[E];\n";
-        os << "    fs_load_row<" << e.dtype << ", " << tmpl_row() << ">(" << name(e.node, KIND_FULL) << ", a.p[" << e.arg << "], row0, lir, rok);\n";
+        os << "    fs_load_row<" << e.dtype << ", " << tmpl_row() << ">(" << name(e.node, KIND_FULL) << ", a.p[" << e.arg << "], row0, lir, vbase, rok);\n";
       } else if (e.kind == KIND_COLV) {
         os << "    const float " << name(e.node, KIND_COLV) << " = rok ? fs_load1<" << e.dtype << ">(a.p[" << e.arg << "], row) : 0.0f;\n";
       }
@@ -257,7 +268,7 @@ struct Emitter {
         const ExtTensor* e = find_out(m);
         const std::string arr = as_array(n.in[0], std::to_string(loc(m)));
         if (e)
-          os << "    fs_store_row_transposed<" << e->dtype << ", " << tmpl_row() << ">(" << arr << ", a.p[" << e->arg << "], R, row, lir, rok);\n";
+          os << "    fs_store_row_transposed<" << e->dtype << ", " << tmpl_row() << ">(" << arr << ", a.p[" << e->arg << "], R, row, lir, vbase, rok);\n";
         continue;
       }
       const Kind k = gp.kind.at(m);

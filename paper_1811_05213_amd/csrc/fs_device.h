@@ -152,14 +152,15 @@ template <int DT, int V> FS_DEV void fs_store_vec(const float* src, void* base, 
   *reinterpret_cast<VT*>(static_cast<T*>(base) + elem_index) = raw;
 }
 
-// Load the lane's slice of one row: vectors j*L + lir, j < NVL.  `row_elem0` is the element
-// index of the row's first column.  NV = vectors per row; RAGGED says NV % L != 0.
+// Load the lane's slice of one row tile: vectors vbase + j*L + lir, j < NVL (vbase = 0 unless a
+// row is cut into several column tiles).  `row_elem0` is the element index of the row's first
+// column.  NV = vectors per row; RAGGED says some of those vector indices can fall beyond NV.
 template <int DT, int V, int NVL, int L, int NV, bool RAGGED>
-FS_DEV void fs_load_row(float (&dst)[NVL * V], const void* base, long row_elem0, int lir, bool rok) {
+FS_DEV void fs_load_row(float (&dst)[NVL * V], const void* base, long row_elem0, int lir, int vbase, bool rok) {
 #pragma unroll
   for (int j = 0; j < NVL; ++j) {
-    const int vi = j * L + lir;
-    const bool ok = rok && (!RAGGED || j < NVL - 1 || vi < NV);
+    const int vi = vbase + j * L + lir;
+    const bool ok = rok && (!RAGGED || vi < NV);
     if (ok) {
       fs_load_vec<DT, V>(&dst[j * V], base, row_elem0 + (long)vi * V);
     } else {
@@ -170,23 +171,23 @@ FS_DEV void fs_load_row(float (&dst)[NVL * V], const void* base, long row_elem0,
 }
 
 template <int DT, int V, int NVL, int L, int NV, bool RAGGED>
-FS_DEV void fs_store_row(const float (&src)[NVL * V], void* base, long row_elem0, int lir, bool rok) {
+FS_DEV void fs_store_row(const float (&src)[NVL * V], void* base, long row_elem0, int lir, int vbase, bool rok) {
 #pragma unroll
   for (int j = 0; j < NVL; ++j) {
-    const int vi = j * L + lir;
-    const bool ok = rok && (!RAGGED || j < NVL - 1 || vi < NV);
+    const int vi = vbase + j * L + lir;
+    const bool ok = rok && (!RAGGED || vi < NV);
     if (ok) fs_store_vec<DT, V>(&src[j * V], base, row_elem0 + (long)vi * V);
   }
 }
 
 // Transposing store of the lane's slice of row `row` of a [R,C] value into a [C,R] tensor.
 template <int DT, int V, int NVL, int L, int NV, bool RAGGED>
-FS_DEV void fs_store_row_transposed(const float (&src)[NVL * V], void* base, long R, long row, int lir, bool rok) {
+FS_DEV void fs_store_row_transposed(const float (&src)[NVL * V], void* base, long R, long row, int lir, int vbase, bool rok) {
   typedef typename fs_elem<DT>::type T;
 #pragma unroll
   for (int j = 0; j < NVL; ++j) {
-    const int vi = j * L + lir;
-    const bool ok = rok && (!RAGGED || j < NVL - 1 || vi < NV);
+    const int vi = vbase + j * L + lir;
+    const bool ok = rok && (!RAGGED || vi < NV);
     if (ok) {
 #pragma unroll
       for (int k = 0; k < V; ++k) static_cast<T*>(base)[(long)(vi * V + k) * R + row] = fs_from_f32<DT>(src[j * V + k]);
@@ -217,7 +218,7 @@ FS_DEV float fs_lane_reduce(const float (&v)[NVL * V], int lir) {
   float acc = fs_red_identity<KIND>();
 #pragma unroll
   for (int j = 0; j < NVL; ++j) {
-    const bool ok = !RAGGED || j < NVL - 1 || (j * L + lir) < NV;
+    const bool ok = !RAGGED || (j * L + lir) < NV;
 #pragma unroll
     for (int k = 0; k < V; ++k) acc = fs_red_op<KIND>(acc, ok ? v[j * V + k] : fs_red_identity<KIND>());
   }

@@ -116,9 +116,13 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   int ecap = rowred ? 32 : 8;
   if (n_full > 4) ecap /= 2;
   ecap = std::max(ecap, V);
-  const int l_min = pow2_ceil((NV + ecap / V - 1) / (ecap / V));
+  int l_min = pow2_ceil((NV + ecap / V - 1) / (ecap / V));
   const int l_max = std::min(1024, pow2_ceil(NV));
-  if (l_min > 1024) FS_FAIL(FS_ERR_UNSUPPORTED, "rows of %d columns are too long for one workgroup", C);
+  // Groups without reductions do not need a whole row in one workgroup: very long rows are cut
+  // into column tiles, each handled like a row of its own.
+  const bool tileable = !rowred && !colred;
+  if (l_min > 1024 && !tileable) FS_FAIL(FS_ERR_UNSUPPORTED, "rows of %d columns are too long for one workgroup", C);
+  if (tileable) l_min = std::min(l_min, 256);
   int L = rowred ? std::min(64, l_max) : std::min(256, l_max);
   L = std::max(L, l_min);
   // small problems: more lanes per row until the device has ~8 wavefronts per CU
@@ -127,9 +131,14 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
     const int h = opt.hint.lanes_per_row;
     if ((h & (h - 1)) == 0 && h >= l_min && h <= 1024) L = h;
   }
+  int NVL = (NV + L - 1) / L, CT = 1;
+  if (NVL * V > ecap && tileable) {
+    NVL = std::max(1, ecap / V);
+    CT = (NV + NVL * L - 1) / (NVL * L);
+  }
 
   int WG;
-  const int64_t total_waves = std::max<int64_t>(1, (int64_t)R * L / 64);
+  const int64_t total_waves = std::max<int64_t>(1, (int64_t)R * CT * L / 64);
   if (colred || total_waves > 1024) WG = std::max(256, L);
   else WG = std::max(64, L);
   if (opt.has_hint && opt.hint.wg_threads > 0) {
@@ -140,12 +149,13 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   s.V = V;
   s.NV = NV;
   s.L = L;
-  s.NVL = (NV + L - 1) / L;
+  s.NVL = NVL;
+  s.CT = CT;
   s.E = s.NVL * V;
   s.WG = WG;
   s.G = WG / L;
-  s.ragged = (NV % L) != 0;
-  s.n_iters = (R + s.G - 1) / s.G;
+  s.ragged = (int64_t)CT * NVL * L != NV;
+  s.n_iters = (int)(((int64_t)R * CT + s.G - 1) / s.G);
   int cap = colred ? 1024 : 2048;
   if (opt.has_hint && opt.hint.max_workgroups > 0) cap = opt.hint.max_workgroups;
   s.grid = std::max(1, std::min(s.n_iters, cap));

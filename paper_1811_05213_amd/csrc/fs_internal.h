@@ -77,9 +77,10 @@ struct Schedule {
   int E = 4;        // elements per lane = NVL * V
   int WG = 256;     // workgroup size
   int G = 4;        // row-groups per workgroup = WG / L
-  int n_iters = 0;  // ceil(R / G): loop trips over the whole grid
+  int CT = 1;       // column tiles per row (> 1 only for groups without reductions: very long rows)
+  int n_iters = 0;  // ceil(R * CT / G): loop trips over the whole grid
   int grid = 0;     // workgroups (`blocks` of Section 4.1)
-  bool ragged = false;  // NV % L != 0
+  bool ragged = false;  // some lane's vector index can fall beyond NV
   int lds_bytes = 0;
   int fan_in = 32;  // column-reduction tree fan-in
 };

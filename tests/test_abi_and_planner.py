@@ -1,0 +1,279 @@
+"""Host-side tests of the C-ABI library: symbols, validation errors, grouping, schedules, LDS plan.
+
+No GPU is needed: fs_plan_create is host-only (kernels are compiled for gfx950 by the run-time
+compiler, not loaded).  Compute entry points are not called here.
+"""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_1811_05213_amd as fs
+from paper_1811_05213_amd import binding
+from workloads import (Graph, elementwise20_graph, layernorm_gelu_graph, min_hbm_bytes, multi_reduce_graph,
+                       random_dag_graph, softmax_graph)
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module", autouse=True)
+def built_lib():
+    if not os.path.exists(fs.LIB_PATH):
+        from paper_1811_05213_amd import build
+        build.build()
+    return fs.lib()
+
+
+def test_library_exports_every_declared_symbol(built_lib):
+    text = open(os.path.join(ROOT, "include", "fs.h")).read()
+    declared = set(re.findall(r"\b(fs_[a-z_0-9]+)\s*\(", text))
+    declared -= {"fs_plan"}  # the opaque type
+    assert {"fs_plan_create", "fs_plan_run", "fs_plan_destroy", "fs_plan_workspace_bytes", "fs_last_error"} <= declared
+    raw = ctypes.CDLL(fs.LIB_PATH)
+    for name in sorted(declared):
+        assert hasattr(raw, name), f"libfs.so does not export {name}"
+
+
+def _status(graph, **kw):
+    try:
+        fs.Plan(graph, **kw).destroy()
+        return "FS_OK"
+    except fs.FsError as e:
+        return e.status_name
+
+
+def test_validation_errors():
+    # operand id not smaller than node id (dangling / cycle)
+    g = Graph()
+    x = g.input(4, 8)
+    y = g.unary("neg", x)
+    g.nodes[y].ins = (5,)
+    g.set_outputs([y])
+    assert _status(g) == "FS_ERR_BAD_GRAPH"
+    # arity
+    g = Graph()
+    x = g.input(4, 8)
+    y = g.binary("add", x, x)
+    g.nodes[y].ins = (x,)
+    g.set_outputs([y])
+    assert _status(g) == "FS_ERR_BAD_GRAPH"
+    # shape mismatch
+    g = Graph()
+    a, b = g.input(4, 8), g.input(4, 9)
+    y = g.binary("add", a, b)
+    g.set_outputs([y])
+    assert _status(g) == "FS_ERR_SHAPE"
+    g = Graph()
+    a = g.input(4, 8)
+    r = g.reduce_row("sum", a)
+    g.nodes[r].cols = 2
+    g.set_outputs([r])
+    assert _status(g) == "FS_ERR_SHAPE"
+    # dtype rules
+    g = Graph()
+    a, b = g.input(4, 8), g.input(4, 8)
+    c = g.cmp("gt", a, b)
+    g.nodes[c].dtype = "f32"
+    g.set_outputs([c])
+    assert _status(g) == "FS_ERR_DTYPE"
+    g = Graph()
+    a, b = g.input(4, 8), g.input(4, 8)
+    s = g.select(a, a, b)  # predicate is not u8
+    g.set_outputs([s])
+    assert _status(g) == "FS_ERR_DTYPE"
+    # outputs: a broadcast is never materialised; duplicates; out of range
+    g = Graph()
+    v = g.input(1, 8)
+    b = g.bcast_rowvec(v, 4)
+    g.set_outputs([b])
+    assert _status(g) == "FS_ERR_BAD_GRAPH"
+    g = softmax_graph(8, 64)
+    g.set_outputs(g.outputs * 2)
+    assert _status(g) == "FS_ERR_BAD_GRAPH"
+    g = softmax_graph(8, 64)
+    g.set_outputs([999])
+    assert _status(g) == "FS_ERR_BAD_GRAPH"
+
+
+def test_invalid_arguments(built_lib):
+    desc = binding.fs_graph_desc()
+    h = ctypes.c_void_p()
+    assert built_lib.fs_plan_create(None, ctypes.byref(h)) == 1
+    assert b"NULL" in built_lib.fs_last_error()
+    desc.abi_version = 77
+    assert built_lib.fs_plan_create(ctypes.byref(desc), ctypes.byref(h)) == 1
+    assert built_lib.fs_plan_destroy(None) == 0
+    n = ctypes.c_size_t()
+    assert built_lib.fs_plan_workspace_bytes(None, ctypes.byref(n)) == 1
+
+
+@pytest.mark.parametrize("name,graph,nodes", [
+    ("softmax", softmax_graph(256, 1024), 5),
+    ("layernorm", layernorm_gelu_graph(16384, 1024), 13),
+    ("elementwise20", elementwise20_graph(65536, 1024), 20),
+    ("multi_reduce", multi_reduce_graph(65536, 512), 5),
+])
+def test_workloads_1_to_4_are_one_stitched_kernel(name, graph, nodes):
+    p = fs.Plan(graph)
+    st = p.stats()
+    assert st["num_groups"] == 1 and st["num_launches"] == 1
+    assert st["min_hbm_bytes"] == min_hbm_bytes(graph) == st["launched_hbm_bytes"]
+    gi = p.group_info(0)
+    assert gi["num_nodes"] == nodes
+    assert gi["dom_rows"] == graph.nodes[0].rows and gi["dom_cols"] == graph.nodes[0].cols
+    # Section 4.4: thread block size is a multiple of the wavefront size, at most 1024
+    assert gi["wg_threads"] % 64 == 0 and 64 <= gi["wg_threads"] <= 1024
+    assert gi["lanes_per_row"] & (gi["lanes_per_row"] - 1) == 0
+    assert gi["wg_threads"] == gi["rows_per_iter"] * gi["lanes_per_row"]
+    assert gi["grid"] >= 1 and gi["lds_bytes"] <= 32768
+    # 128-bit accesses for the widest dtype
+    assert gi["vec_elems"] == (8 if name == "layernorm" else 4)
+    src = p.group_source(0)
+    assert p.group_kernel_name(0) in src and "__launch_bounds__" in src
+    # the unfused executor: one launch per compute node, more traffic
+    u = fs.Plan(graph, mode=fs.FS_MODE_UNFUSED)
+    su = u.stats()
+    assert su["num_launches"] == nodes and su["launched_hbm_bytes"] > st["launched_hbm_bytes"]
+    assert u.workspace_bytes() > 0
+    p.destroy()
+    u.destroy()
+
+
+def test_softmax_reductions_share_lds_slots():
+    # Section 5.1.3: Reduce.2 reuses the buffer of Reduce.1.  With a row spread over 4 wavefronts the
+    # two row reductions together use one ping-pong pair of 4-float slots, not one buffer each.
+    p = fs.Plan(softmax_graph(256, 1024), hint={"lanes_per_row": 256, "wg_threads": 256})
+    gi = p.group_info(0)
+    assert gi["num_row_reduces"] == 2
+    assert gi["lds_bytes"] == 2 * 1 * 4 * 1 * 4  # 2 halves x 1 row-group x 4 waves x 1 reduction x 4 B
+    p.destroy()
+    # a row inside one wavefront needs no LDS at all
+    p = fs.Plan(softmax_graph(65536, 1024))
+    assert p.group_info(0)["lanes_per_row"] == 64 and p.group_info(0)["lds_bytes"] == 0
+    p.destroy()
+
+
+def test_single_block_schedule_is_always_valid():
+    # Section 4.3: split_dim = 0, sword = 1 (one thread block) is valid for every fused computation
+    for g in (softmax_graph(300, 1000), layernorm_gelu_graph(77, 1024), multi_reduce_graph(1000, 512), elementwise20_graph(64, 1024)):
+        p = fs.Plan(g, hint={"max_workgroups": 1})
+        assert p.stats()["num_groups"] == 1 and p.group_info(0)["grid"] == 1
+        p.destroy()
+
+
+def test_lds_budget():
+    g = multi_reduce_graph(4096, 512)
+    # caller-given single group that cannot fit: distinct status, no abort
+    grp = [0] * len(g.nodes)
+    assert _status(g, group_of_node=grp, lds_budget_bytes=256) == "FS_ERR_LDS_BUDGET"
+    assert _status(g, group_of_node=grp) == "FS_OK"
+    # greedy grouping under the same budget cannot place the column reductions either
+    assert _status(g, lds_budget_bytes=256) == "FS_ERR_LDS_BUDGET"
+    # but row-only work still plans: the budget only removes what needs LDS
+    assert _status(softmax_graph(64, 1024), lds_budget_bytes=256) == "FS_OK"
+
+
+def test_caller_grouping_checked():
+    g = softmax_graph(64, 256)
+    ids = g.compute_ids()
+    ok = [0] * len(g.nodes)
+    assert _status(g, group_of_node=ok) == "FS_OK"
+    # m | d,e | s | y : legal chain of four groups
+    grp = [0] * len(g.nodes)
+    for k, i in enumerate(ids):
+        grp[i] = [0, 1, 1, 2, 3][k]
+    p = fs.Plan(g, group_of_node=grp)
+    assert p.stats()["num_groups"] == 4
+    p.destroy()
+    # y with m but without d,e,s: group {m,y} both feeds and consumes group {d,e,s} -> cycle
+    grp = [0] * len(g.nodes)
+    for k, i in enumerate(ids):
+        grp[i] = [0, 1, 1, 1, 0][k]
+    assert _status(g, group_of_node=grp) == "FS_ERR_UNSUPPORTED"
+    # a column reduction result cannot be consumed inside its own group
+    g = Graph()
+    x = g.input(64, 32)
+    c = g.reduce_col("sum", x)
+    y = g.binary("sub", x, g.bcast_rowvec(c, 64))
+    g.set_outputs([y])
+    assert _status(g, group_of_node=[0] * len(g.nodes)) == "FS_ERR_UNSUPPORTED"
+    p = fs.Plan(g)  # the greedy grouper cuts there instead
+    assert p.stats()["num_groups"] == 2
+    p.destroy()
+
+
+def _check_grouping(g, p):
+    """SchdConsistent conditions (Section 3.2) as properties of the result."""
+    grp = p.node_groups()
+    ngroups = p.stats()["num_groups"]
+    free = {"input", "const", "bcast_rowvec", "bcast_colvec"}
+    users = {i: [] for i in range(len(g.nodes))}
+    for i, n in enumerate(g.nodes):
+        for o in n.ins:
+            users[o].append(i)
+
+    def real_users(i):
+        out = []
+        for u in users[i]:
+            out += real_users(u) if g.nodes[u].op in ("bcast_rowvec", "bcast_colvec") else [u]
+        return out
+
+    def source(o):
+        return g.nodes[o].ins[0] if g.nodes[o].op in ("bcast_rowvec", "bcast_colvec") else o
+
+    for i, n in enumerate(g.nodes):
+        if n.op in free:
+            assert grp[i] == -1
+            continue
+        assert 0 <= grp[i] < ngroups
+        # launch order is a topological order of the groups: producers never come later
+        for o in n.ins:
+            s = source(o)
+            if g.nodes[s].op not in free:
+                assert grp[s] <= grp[i], f"node {i} in group {grp[i]} reads node {s} of later group {grp[s]}"
+    return grp
+
+
+def test_random_dag_grouping_properties():
+    g = random_dag_graph()
+    p = fs.Plan(g)
+    st = p.stats()
+    grp = _check_grouping(g, p)
+    assert st["num_groups"] < 40, "200 nodes should fuse into far fewer launches"
+    assert st["launched_hbm_bytes"] >= st["min_hbm_bytes"]
+    u = fs.Plan(g, mode=fs.FS_MODE_UNFUSED)
+    assert u.stats()["num_launches"] == len(g.compute_ids()) == 200
+    assert u.stats()["launched_hbm_bytes"] > st["launched_hbm_bytes"]
+    # transposes and column-direction results end their group: nobody in the same group reads them
+    for i, n in enumerate(g.nodes):
+        if n.op == "transpose":
+            for j, m in enumerate(g.nodes):
+                if i in m.ins:
+                    assert grp[j] != grp[i]
+    p.destroy()
+    u.destroy()
+
+
+def test_dead_nodes_are_not_executed():
+    g = Graph()
+    x = g.input(16, 64)
+    y = g.unary("tanh", x)
+    g.unary("exp", x)  # dead
+    g.set_outputs([y])
+    p = fs.Plan(g)
+    assert p.stats()["num_groups"] == 1 and p.group_info(0)["num_nodes"] == 1
+    assert p.node_groups()[2] == -1
+    p.destroy()
+
+
+def test_ragged_and_degenerate_shapes_plan():
+    for rows, cols in ((1, 1), (1, 777), (300, 1), (37, 1000), (5, 3), (3, 20000)):
+        g = softmax_graph(rows, cols)
+        p = fs.Plan(g)
+        gi = p.group_info(0)
+        assert gi["elems_per_lane"] * gi["lanes_per_row"] >= cols
+        p.destroy()
+    # rows too long for one workgroup's registers are refused cleanly
+    assert _status(softmax_graph(2, 1 << 20)) == "FS_ERR_UNSUPPORTED"

@@ -1,0 +1,278 @@
+"""GPU parity: the stitched kernels (through the C ABI) against the CPU oracle, element by element.
+
+Tolerances (see tests/parity.py): fp32 outputs 1e-5, bf16 outputs 1e-2, predicates bit-exact.
+Sizes span several workgroups, several loop trips and ragged tails; the five BASELINE workloads
+are also checked at their full sizes in the launch configuration bench.py times.
+"""
+import numpy as np
+import pytest
+
+import oracle
+import paper_1811_05213_amd as fs
+from paper_1811_05213_amd.runner import DeviceRun, run_graph
+from parity import check_all, check_output
+from workloads import (Graph, bf16_bits_to_f32, elementwise20_graph, elementwise20_inputs, f32_to_bf16_bits,
+                       layernorm_gelu_graph, layernorm_gelu_inputs, multi_reduce_graph, multi_reduce_inputs,
+                       random_dag_graph, random_dag_inputs, softmax_graph, softmax_inputs, workload)
+
+pytestmark = pytest.mark.gpu
+RNG = np.random.default_rng(20240607)
+THREADS = 16
+
+
+def both_modes(g, ins, what, rtol_scale=1.0, **kw):
+    ref = oracle.run(g, ins, THREADS)
+    out_s = run_graph(g, ins, mode=fs.FS_MODE_STITCHED, **kw)
+    check_all(g, out_s, ref, what + " stitched", rtol_scale)
+    out_u = run_graph(g, ins, mode=fs.FS_MODE_UNFUSED, **kw)
+    check_all(g, out_u, ref, what + " unfused", rtol_scale)
+    return ref, out_s, out_u
+
+
+# ------------------------------------------------------------------ single ops on awkward shapes
+SHAPES = [(1, 1), (5, 3), (37, 1000), (300, 1), (1, 777), (64, 64), (129, 258), (2, 4100)]
+UNARY_RANGES = {"neg": (-5, 5), "abs": (-5, 5), "exp": (-20, 20), "log": (1e-3, 50), "tanh": (-6, 6), "sigmoid": (-20, 20),
+                "sqrt": (0, 100), "rsqrt": (1e-3, 100), "rcp": (0.01, 100), "gelu_tanh": (-8, 8)}
+
+
+@pytest.mark.parametrize("op", sorted(UNARY_RANGES))
+def test_unary_ops(op):
+    lo, hi = UNARY_RANGES[op]
+    for rows, cols in SHAPES:
+        g = Graph()
+        x = g.input(rows, cols)
+        g.set_outputs([g.unary(op, x)])
+        both_modes(g, [RNG.uniform(lo, hi, (rows, cols)).astype(np.float32)], f"{op} {rows}x{cols}")
+
+
+@pytest.mark.parametrize("op", ["add", "sub", "mul", "div", "max", "min"])
+def test_binary_ops_bit_exact(op):
+    # correctly rounded IEEE ops: the GPU must agree with the oracle bit for bit
+    for rows, cols in SHAPES[:6]:
+        g = Graph()
+        a, b = g.input(rows, cols), g.input(rows, cols)
+        g.set_outputs([g.binary(op, a, b)])
+        ins = [(RNG.standard_normal((rows, cols)) * 10.0 ** RNG.integers(-3, 4, (rows, cols))).astype(np.float32) for _ in range(2)]
+        ref, out_s, out_u = both_modes(g, ins, f"{op} {rows}x{cols}")
+        np.testing.assert_array_equal(out_s[0].view(np.uint32), ref[0].view(np.uint32))
+        np.testing.assert_array_equal(out_u[0].view(np.uint32), ref[0].view(np.uint32))
+
+
+def test_transcendental_accuracy_wide_range():
+    """Pure relative error of the approximate ops over wide ranges (no rms slack): <= 1e-5."""
+    cases = {"exp": np.linspace(-85, 85, 20001), "tanh": np.concatenate([np.linspace(-12, 12, 20001), np.logspace(-8, 0, 2000)]),
+             "sigmoid": np.linspace(-30, 30, 20001), "log": np.logspace(-30, 30, 20001), "rsqrt": np.logspace(-30, 30, 20001),
+             "rcp": np.logspace(-30, 30, 20001), # (the definition 0.5 z (1 + tanh u) cancels even in fp64 for z << -5: the oracle itself loses digits there)
+             "gelu_tanh": np.concatenate([np.linspace(-5, 9, 20001), np.logspace(-8, 0, 2000)])}
+    for op, xs in cases.items():
+        x = xs.astype(np.float32).reshape(1, -1)
+        g = Graph()
+        i = g.input(*x.shape)
+        g.set_outputs([g.unary(op, i)])
+        ref = oracle.run(g, [x], THREADS)[0].astype(np.float64)
+        out = run_graph(g, [x])[0].astype(np.float64)
+        ok = np.abs(ref) > 1e-30
+        rel = np.abs(out[ok] - ref[ok]) / np.abs(ref[ok])
+        assert rel.max() <= 1e-5, f"{op}: max relative error {rel.max():.3g}"
+
+
+def test_cmp_select_and_u8_outputs():
+    rows, cols = 70, 300
+    a = RNG.integers(-3, 4, (rows, cols)).astype(np.float32)  # many ties
+    b = RNG.integers(-3, 4, (rows, cols)).astype(np.float32)
+    for kind in ("gt", "ge", "lt", "le", "eq", "ne"):
+        g = Graph()
+        ia, ib = g.input(rows, cols), g.input(rows, cols)
+        p = g.cmp(kind, ia, ib)
+        s = g.select(p, ia, ib)
+        g.set_outputs([p, s])
+        ref, out_s, out_u = both_modes(g, [a, b], f"cmp {kind}")
+        np.testing.assert_array_equal(out_s[0], ref[0])
+        np.testing.assert_array_equal(out_s[1].view(np.uint32), ref[1].view(np.uint32))
+    # a u8 tensor as plan input
+    g = Graph()
+    ip, ia, ib = g.input(rows, cols, "u8"), g.input(rows, cols), g.input(rows, cols)
+    g.set_outputs([g.select(ip, ia, ib)])
+    mask = RNG.integers(0, 2, (rows, cols)).astype(np.uint8)
+    ref, out_s, _ = both_modes(g, [mask, a, b], "select with u8 input")
+    np.testing.assert_array_equal(out_s[0], np.where(mask != 0, a, b))
+
+
+def test_bf16_nodes_and_convert():
+    rows, cols = 33, 520
+    x = RNG.standard_normal((rows, cols)).astype(np.float32)
+    g = Graph()
+    i = g.input(rows, cols, "bf16")
+    f = g.unary("convert", i, "f32")
+    sq = g.binary("mul", i, i, "bf16")       # bf16 node kept in registers: rounded once
+    y = g.binary("add", sq, f, "f32")
+    o = g.unary("convert", y, "bf16")
+    g.set_outputs([f, sq, y, o])
+    ref, out_s, out_u = both_modes(g, [f32_to_bf16_bits(x)], "bf16 chain")
+    # conversions and the exactly representable product are bit-exact
+    np.testing.assert_array_equal(out_s[0], ref[0])
+    np.testing.assert_array_equal(out_s[1], ref[1])
+
+
+# ------------------------------------------------------------------ reductions, broadcasts, transposes
+@pytest.mark.parametrize("kind", ["sum", "max", "min", "mean"])
+def test_row_and_col_reductions(kind):
+    for rows, cols in [(1, 1), (7, 5), (300, 1), (1, 777), (129, 258), (1000, 64), (40, 4100), (5000, 36)]:
+        g = Graph()
+        x = g.input(rows, cols)
+        g.set_outputs([g.reduce_row(kind, x), g.reduce_col(kind, x)])
+        both_modes(g, [RNG.standard_normal((rows, cols)).astype(np.float32)], f"reduce {kind} {rows}x{cols}")
+
+
+def test_row_reduce_across_wavefronts():
+    # rows long enough to be spread over 2..16 wavefronts with an LDS fold, ragged tails included
+    for rows, cols in [(9, 4096), (3, 20000), (2, 16385), (5, 32768)]:  # 32768 = the longest row one workgroup holds
+        g = softmax_graph(rows, cols)
+        p = fs.Plan(g)
+        assert p.group_info(0)["lanes_per_row"] > 64
+        p.destroy()
+        both_modes(g, [RNG.standard_normal((rows, cols)).astype(np.float32)], f"softmax {rows}x{cols}")
+
+
+def test_broadcasts_and_transpose():
+    rows, cols = 130, 72
+    g = Graph()
+    x, v, w = g.input(rows, cols), g.input(1, cols), g.input(rows, 1)
+    a = g.binary("mul", x, g.bcast_rowvec(v, rows))
+    b = g.binary("add", a, g.bcast_colvec(w, cols))
+    c = g.binary("sub", b, g.const(0.25, rows, cols))
+    t = g.transpose(c)
+    tt = g.unary("tanh", t)          # consumer in the transposed space: next group
+    r = g.reduce_row("sum", t)       # [cols,1]
+    back = g.transpose(tt)
+    g.set_outputs([c, t, tt, r, back])
+    ins = [RNG.standard_normal((rows, cols)).astype(np.float32), RNG.standard_normal((1, cols)).astype(np.float32),
+           RNG.standard_normal((rows, 1)).astype(np.float32)]
+    ref, out_s, _ = both_modes(g, ins, "bcast/transpose")
+    np.testing.assert_array_equal(out_s[1], out_s[0].T)  # a transpose moves bits, nothing else
+
+
+def test_vector_valued_members_and_constants():
+    # ops on [1,C] and [R,1] tensors inside a group with [R,C] work
+    rows, cols = 90, 200
+    g = Graph()
+    x, v = g.input(rows, cols), g.input(1, cols)
+    v2 = g.binary("mul", v, g.const(2.0, 1, cols))          # per-column value computed once per workgroup
+    m = g.reduce_row("max", x)
+    m2 = g.binary("add", m, g.const(1.0, rows, 1))          # per-row value
+    y = g.binary("div", g.binary("add", x, g.bcast_rowvec(v2, rows)), g.bcast_colvec(m2, cols))
+    g.set_outputs([y, v2, m2])
+    ins = [RNG.uniform(1, 2, (rows, cols)).astype(np.float32), RNG.uniform(1, 2, (1, cols)).astype(np.float32)]
+    both_modes(g, ins, "vector members")
+
+
+# ------------------------------------------------------------------ the five workloads
+@pytest.mark.parametrize("cfg,rows", [(1, 256), (1, 33), (1, 5000), (2, 512), (2, 77), (3, 256), (3, 1001), (4, 512), (4, 5000),
+                                      (4, 70001), (5, None), (5, 100)])
+def test_workloads_test_sizes(cfg, rows):
+    g, ins, name = workload(cfg, rows)
+    both_modes(g, ins, name)
+
+
+def test_layernorm_decomposed_gelu_variant():
+    g = layernorm_gelu_graph(300, 1024, decomposed_gelu=True)
+    ins = layernorm_gelu_inputs(300, 1024)
+    ref, out_s, _ = both_modes(g, ins, "layernorm decomposed gelu")
+    g2 = layernorm_gelu_graph(300, 1024)
+    out2 = run_graph(g2, ins)
+    check_output(out_s[0], out2[0], "bf16", "decomposed vs composite gelu")
+
+
+def test_full_size_softmax_layernorm_multireduce_randomdag():
+    for cfg in (1, 2, 4, 5):
+        g, ins, name = workload(cfg)
+        ref = oracle.run(g, ins, THREADS)
+        out = run_graph(g, ins)
+        check_all(g, out, ref, name + " full size")
+
+
+def test_full_size_elementwise20_on_sampled_rows():
+    # every op of workload 3 is row-independent, so the oracle evaluated on a sample of rows gives
+    # the exact expected values of those rows of the full-size run
+    rows, cols = 65536, 1024
+    g = elementwise20_graph(rows, cols)
+    ins = elementwise20_inputs(rows, cols)
+    out = run_graph(g, ins)
+    pick = np.unique(np.concatenate([[0, 1, 255, 256, rows - 2, rows - 1], RNG.integers(0, rows, 500)]))
+    gs = elementwise20_graph(len(pick), cols)
+    ref = oracle.run(gs, [a[pick] if a.shape[0] == rows else a for a in ins], THREADS)
+    check_all(gs, [o[pick] for o in out], ref, "elementwise20 full size, sampled rows")
+    assert all(np.isfinite(o).all() for o in out)
+
+
+def test_elementwise20_predicate_bit_exact():
+    rows = 300
+    g = elementwise20_graph(rows, 1024)
+    pid = next(i for i, n in enumerate(g.nodes) if n.op == "cmp")
+    g.set_outputs(g.outputs + [pid])
+    ins = elementwise20_inputs(rows, 1024)
+    ref, out_s, out_u = both_modes(g, ins, "elementwise20 + mask")
+    np.testing.assert_array_equal(out_s[2], ref[2])
+    np.testing.assert_array_equal(out_u[2], ref[2])
+
+
+# ------------------------------------------------------------------ determinism and schedule invariance
+def test_run_to_run_bit_identical():
+    for cfg, rows in ((4, 70001), (1, 5000), (5, None)):
+        g, ins, name = workload(cfg, rows)
+        plan = fs.Plan(g)
+        r = DeviceRun(plan)
+        r.set_inputs(ins)
+        r.launch()
+        first = [o.copy() for o in r.results()]
+        for _ in range(20):
+            r.launch()
+        for a, b in zip(first, r.results()):
+            assert a.tobytes() == b.tobytes(), name
+        plan.destroy()
+
+
+@pytest.mark.parametrize("cfg,rows", [(1, 300), (2, 300), (4, 3000), (3, 200)])
+def test_schedule_invariance(cfg, rows):
+    """The one-block schedule (Section 4.3) and other legal schedules give the tuned schedule's result."""
+    g, ins, name = workload(cfg, rows)
+    ref = oracle.run(g, ins, THREADS)
+    for hint in ({"max_workgroups": 1}, {"lanes_per_row": 256, "wg_threads": 256}, {"lanes_per_row": 1024, "wg_threads": 1024},
+                 {"lanes_per_row": 32, "wg_threads": 64, "max_workgroups": 7}, {"wg_threads": 512, "max_workgroups": 40}):
+        out = run_graph(g, ins, hint=hint)
+        check_all(g, out, ref, f"{name} hint {hint}")
+
+
+def test_caller_given_groups():
+    g = softmax_graph(200, 512)
+    ins = softmax_inputs(200, 1024)[0][:, :512].copy()
+    ref = oracle.run(g, [ins], THREADS)
+    grp = [0] * len(g.nodes)
+    for k, i in enumerate(g.compute_ids()):
+        grp[i] = [0, 1, 1, 2, 3][k]
+    out = run_graph(g, [ins], group_of_node=grp)
+    check_all(g, out, ref, "softmax in four caller-given groups")
+
+
+# ------------------------------------------------------------------ run-time argument errors (nothing is launched)
+def test_run_argument_errors():
+    g, ins, _ = workload(4, 512)
+    plan = fs.Plan(g)
+    r = DeviceRun(plan)
+    r.set_inputs(ins)
+    need = plan.workspace_bytes()
+    assert need > 0
+    ptrs_in = [t.data_ptr() for t in r.inputs]
+    ptrs_out = [t.data_ptr() for t in r.outputs]
+    with pytest.raises(fs.FsError) as e:
+        plan.run(ptrs_in, ptrs_out, 0, 0)
+    assert e.value.status_name == "FS_ERR_WORKSPACE"
+    with pytest.raises(fs.FsError) as e:
+        plan.run(ptrs_in, ptrs_out, r.workspace.data_ptr(), need - 1)
+    assert e.value.status_name == "FS_ERR_WORKSPACE"
+    with pytest.raises(fs.FsError) as e:
+        plan.run([ptrs_in[0] + 4], ptrs_out, r.workspace.data_ptr(), need)
+    assert e.value.status_name == "FS_ERR_INVALID_ARG"
+    r.launch()  # still usable afterwards
+    check_all(g, r.results(), oracle.run(g, ins, THREADS), "after argument errors")
+    plan.destroy()
