@@ -10,6 +10,14 @@
 //   - roots are written to global memory as soon as they exist (EmitWriteOutputArray).
 // The body is straight-line code over the building blocks of fs_device.h; names are local
 // indices, so two groups with the same structure produce the same text and share a binary.
+//
+// Two peephole rules keep the instruction count down (on this device 4 bytes of HBM traffic
+// pay for only ~20 scalar fp32 instructions, so arithmetic is never free):
+//   - a multiply whose only consumer is an add/sub (or a sum reduction) is contracted into an
+//     fma, unless one of the two feeds a predicate: predicates must see exactly the roundings
+//     the graph spells out;
+//   - a value that is only stored is not rounded to its dtype in registers first (the store
+//     rounds).
 #include <algorithm>
 #include <cstring>
 #include <sstream>
@@ -26,8 +34,10 @@ struct Emitter {
   std::ostringstream os;
   std::map<int, int> local;  // node id -> local index
   std::vector<char> in_set;
+  std::vector<int> uses;      // in-group operand slots reading each member (looking through broadcasts)
+  std::vector<char> folded;   // multiply emitted inside its single consumer
 
-  Emitter(const Graph& g_, GroupPlan& gp_) : g(g_), gp(gp_), in_set(g_.n(), 0) {}
+  Emitter(const Graph& g_, GroupPlan& gp_) : g(g_), gp(gp_), in_set(g_.n(), 0), uses(g_.n(), 0), folded(g_.n(), 0) {}
 
   int loc(int node) {
     auto it = local.find(node);
@@ -47,28 +57,40 @@ struct Emitter {
     return buf;
   }
 
-  Kind classify(const fs_node& n) const {
-    if (n.rows == gp.R && n.cols == gp.C) return KIND_FULL;
-    if (n.rows == gp.R && n.cols == 1) return KIND_COLV;
-    if (n.rows == 1 && n.cols == gp.C) return KIND_ROWV;
-    return KIND_NONE;
+  int source_of(int o) const {  // the tensor behind an operand, looking through a broadcast
+    const fs_node& n = g.nodes[o];
+    return (n.opcode == FS_BCAST_ROWVEC || n.opcode == FS_BCAST_COLVEC) ? n.in[0] : o;
+  }
+
+  const ExtTensor* find_out(int node) const {
+    for (const ExtTensor& e : gp.ext_out)
+      if (e.node == node) return &e;
+    return nullptr;
+  }
+
+  // may multiply `m` be emitted inside consumer `u` as part of an fma?
+  bool can_fold_mul(int m, int u) const {
+    if (m < 0 || !in_set[m]) return false;
+    const fs_node& mn = g.nodes[m];
+    const fs_node& un = g.nodes[u];
+    const bool reduce = un.opcode == FS_REDUCE_ROW || un.opcode == FS_REDUCE_COL;
+    return mn.opcode == FS_MUL && uses[m] == 1 && !find_out(m) && mn.dtype == FS_F32 && un.dtype == FS_F32 && !g.exact[m] &&
+           !g.exact[u] && gp.kind.at(m) == (reduce ? KIND_FULL : gp.kind.at(u));
   }
 
   // expression for element e of operand `o` (indexable by `e` inside an unrolled loop)
   std::string ref(int o) {
     const fs_node& n = g.nodes[o];
     if (n.opcode == FS_CONST) return literal(n.attr_f, n.dtype);
-    int src = o;
-    if (n.opcode == FS_BCAST_ROWVEC || n.opcode == FS_BCAST_COLVEC) {
-      src = n.in[0];
-      if (g.nodes[src].opcode == FS_CONST) return literal(g.nodes[src].attr_f, g.nodes[src].dtype);
-    }
+    const int src = source_of(o);
+    if (g.nodes[src].opcode == FS_CONST) return literal(g.nodes[src].attr_f, g.nodes[src].dtype);
     const Kind k = gp.kind.at(src);
     if (k == KIND_COLV) return name(src, k);
     return name(src, k) + "[e]";
   }
 
-  std::string expr(const fs_node& n) {
+  std::string expr(int id) {
+    const fs_node& n = g.nodes[id];
     auto A = [&]() { return ref(n.in[0]); };
     auto B = [&]() { return ref(n.in[1]); };
     auto Cc = [&]() { return ref(n.in[2]); };
@@ -84,8 +106,20 @@ struct Emitter {
       case FS_RCP: return "fs_rcp(" + A() + ")";
       case FS_GELU_TANH: return "fs_gelu_tanh(" + A() + ")";
       case FS_CONVERT: return "(" + A() + ")";
-      case FS_ADD: return "(" + A() + " + " + B() + ")";
-      case FS_SUB: return "(" + A() + " - " + B() + ")";
+      case FS_ADD:
+      case FS_SUB: {
+        const bool sub = n.opcode == FS_SUB;
+        for (int side = 0; side < 2; ++side) {
+          const int m = n.in[side];
+          if (!folded[m]) continue;
+          const fs_node& mn = g.nodes[m];
+          const std::string x = ref(mn.in[0]), y = ref(mn.in[1]), other = ref(n.in[1 - side]);
+          if (!sub) return "__builtin_fmaf(" + x + ", " + y + ", " + other + ")";
+          if (side == 0) return "__builtin_fmaf(" + x + ", " + y + ", -(" + other + "))";  // m - c
+          return "__builtin_fmaf(-(" + x + "), " + y + ", " + other + ")";                 // c - m
+        }
+        return "(" + A() + (sub ? " - " : " + ") + B() + ")";
+      }
       case FS_MUL: return "(" + A() + " * " + B() + ")";
       case FS_DIV: return "fs_div(" + A() + ", " + B() + ")";
       case FS_MAX: return "fs_max(" + A() + ", " + B() + ")";
@@ -102,21 +136,25 @@ struct Emitter {
     return "0.0f";
   }
 
-  std::string tmpl_row() const {  // template arguments shared by the row load/store/reduce blocks
-    std::ostringstream t;
-    t << "V, NVL, L, NV, RAGGED";
-    return t.str();
+  // value of node `id` rounded to its dtype, unless it is only stored (the store rounds)
+  std::string rounded(int id, const std::string& e) {
+    const fs_node& n = g.nodes[id];
+    if (n.dtype != FS_BF16 || (uses[id] == 0 && find_out(id))) return e;
+    return "fs_round<" + std::to_string(n.dtype) + ">(" + e + ")";
   }
 
-  // an array holding operand `o` as a full slice (needed by reductions / transposed stores)
+  static std::string tmpl_row() { return "V, NVL, L, NV, RAGGED"; }
+
+  // an array holding operand `o` as a full slice (needed by max/min reductions / transposed stores)
   std::string as_array(int o, const std::string& tag) {
     const fs_node& n = g.nodes[o];
-    if (!op_is_free(n.opcode) || n.opcode == FS_INPUT) {
+    if ((!op_is_free(n.opcode) || n.opcode == FS_INPUT) && !folded[o]) {
       const Kind k = gp.kind.at(o);
       if (k != KIND_COLV) return name(o, k);
     }
     const std::string t = "t" + tag;
-    os << "    float " << t << "[E];\n    _Pragma(\"unroll\") for (int e = 0; e < E; ++e) " << t << "[e] = " << ref(o) << ";\n";
+    os << "    float " << t << "[E];\n    _Pragma(\"unroll\") for (int e = 0; e < E; ++e) " << t << "[e] = "
+       << (folded[o] ? expr(o) : ref(o)) << ";\n";
     return t;
   }
 
@@ -124,26 +162,52 @@ struct Emitter {
     const std::string nm = name(e.node, gp.kind.at(e.node));
     if (e.transposed) return;  // emitted with the node
     if (e.kind == KIND_FULL)
-      os << indent << "fs_store_row<" << e.dtype << ", " << tmpl_row() << ">(" << nm << ", a.p[" << e.arg << "], row0, lir, vbase, rok);\n";
+      os << indent << "fs_store_row<" << e.dtype << ", " << tmpl_row() << ", " << (e.streaming ? "true" : "false") << ">(" << nm << ", a.p["
+         << e.arg << "], row0, lir, vbase, rok);\n";
     else if (e.kind == KIND_COLV)
       os << indent << "if (rok && lir == 0 && vbase == 0) fs_store1<" << e.dtype << ">(a.p[" << e.arg << "], row, " << nm << ");\n";
   }
 
-  const ExtTensor* find_out(int node) const {
-    for (const ExtTensor& e : gp.ext_out)
-      if (e.node == node) return &e;
-    return nullptr;
+  void count_uses() {
+    for (int m : gp.members) {
+      const fs_node& n = g.nodes[m];
+      for (int k = 0; k < n.num_in; ++k) {
+        const int src = source_of(n.in[k]);
+        if (in_set[src]) ++uses[src];
+      }
+    }
+    // decide which multiplies disappear into their consumer
+    for (int u : gp.members) {
+      const fs_node& un = g.nodes[u];
+      if (un.opcode == FS_ADD || un.opcode == FS_SUB) {
+        for (int side = 0; side < 2; ++side) {
+          const int m = un.in[side];  // direct operand only (a broadcast in between changes the kind)
+          if (can_fold_mul(m, u) && !folded[un.in[1 - side]]) {
+            folded[m] = 1;
+            break;
+          }
+        }
+      } else if ((un.opcode == FS_REDUCE_ROW || un.opcode == FS_REDUCE_COL) && (un.attr_i == FS_RED_SUM || un.attr_i == FS_RED_MEAN) &&
+                 gp.R > 1 && gp.C > 1) {
+        if (can_fold_mul(un.in[0], u)) folded[un.in[0]] = 1;
+      }
+    }
   }
 
   void run(const std::string& kname) {
     const Schedule& s = gp.s;
     for (int m : gp.members) in_set[m] = 1;
+    count_uses();
     const int R = gp.R, C = gp.C;
     const int NP = (int)(gp.ext_in.size() + gp.ext_out.size());
     const int K = (int)gp.col_reduces.size();
     const int WPR = s.L > 64 ? s.L / 64 : 1;
     const int KB = std::max(1, gp.max_batched_reduces);
     const bool xwave = !gp.row_reduces.empty() && s.L > 64;
+    // Per-column values ([1,C] tensors) are loaded into registers once per workgroup when the
+    // workgroup loops over many rows; with one trip per workgroup (or column tiles) they are
+    // simply read where the loop body needs them.
+    const bool rowv_in_loop = s.CT > 1 || s.grid >= s.n_iters;
 
     // fixed local numbering: external inputs first, then members
     for (const ExtTensor& e : gp.ext_in) loc(e.node);
@@ -167,11 +231,10 @@ struct Emitter {
     os << "  const int tid = (int)threadIdx.x, lir = tid & (L - 1), rg = tid / L;\n";
     os << "  const long R = a.R;\n";
     os << "  (void)lir; (void)rg; (void)R; (void)C; (void)G; (void)CT;\n";
-    const bool tiled = s.CT > 1;  // per-column values depend on the tile: handled inside the loop
     if (xwave) os << "  __shared__ float lds_rr[2 * G * " << WPR << " * " << KB << "];\n  int parity = 0;\n";
     if (K > 0) os << "  __shared__ float lds_col[G * C];\n  __shared__ fs_u32 lds_flag;\n";
 
-    // ---- prologue: per-column values are loaded / computed once per workgroup ----
+    // ---- per-column values ----
     auto emit_rowv = [&](const std::string& ind, const std::string& vb, const std::string& store_cond) {
       for (const ExtTensor& e : gp.ext_in)
         if (e.kind == KIND_ROWV) {
@@ -180,17 +243,16 @@ struct Emitter {
              << ", true);\n";
         }
       for (int m : gp.members) {
-        if (gp.level.at(m) >= 0) continue;
-        const fs_node& n = g.nodes[m];
+        if (gp.level.at(m) >= 0 || folded[m]) continue;
         const std::string nm = name(m, KIND_ROWV);
-        os << ind << "float " << nm << "[E];\n" << ind << "_Pragma(\"unroll\") for (int e = 0; e < E; ++e) " << nm << "[e] = fs_round<" << n.dtype
-           << ">(" << expr(n) << ");\n";
+        os << ind << "float " << nm << "[E];\n" << ind << "_Pragma(\"unroll\") for (int e = 0; e < E; ++e) " << nm << "[e] = "
+           << rounded(m, expr(m)) << ";\n";
         if (const ExtTensor* e = find_out(m))
           os << ind << "if (" << store_cond << ") fs_store_row<" << e->dtype << ", " << tmpl_row() << ">(" << nm << ", a.p[" << e->arg
              << "], 0, lir, " << vb << ", true);\n";
       }
     };
-    if (!tiled) emit_rowv("  ", "0", "blockIdx.x == 0 && rg == 0");
+    if (!rowv_in_loop) emit_rowv("  ", "0", "blockIdx.x == 0 && rg == 0");
     for (int k = 0; k < K; ++k) {
       const int m = gp.col_reduces[k];
       os << "  float ca" << loc(m) << "[E];\n  _Pragma(\"unroll\") for (int e = 0; e < E; ++e) ca" << loc(m) << "[e] = fs_red_identity<"
@@ -199,32 +261,34 @@ struct Emitter {
 
     // ---- the row loop ----
     os << "  for (int it = (int)blockIdx.x; it < a.n_iters; it += (int)gridDim.x) {\n";
-    if (!tiled) {
+    if (s.CT == 1) {
       os << "    const long row = (long)it * G + rg;\n    constexpr int vbase = 0;\n";
     } else {
       os << "    const long unit = (long)it * G + rg;\n    const long row = unit / CT;\n    const int vbase = (int)(unit % CT) * (NVL * L);\n";
     }
     os << "    const bool rok = row < R;\n    const long row0 = row * C;\n    (void)row0; (void)vbase;\n";
-    if (tiled) emit_rowv("    ", "vbase", "row == 0");
     for (const ExtTensor& e : gp.ext_in) {
       if (e.kind == KIND_FULL) {
         os << "    float " << name(e.node, KIND_FULL) << "[E];\n";
-        os << "    fs_load_row<" << e.dtype << ", " << tmpl_row() << ">(" << name(e.node, KIND_FULL) << ", a.p[" << e.arg << "], row0, lir, vbase, rok);\n";
+        os << "    fs_load_row<" << e.dtype << ", " << tmpl_row() << ", " << (e.streaming ? "true" : "false") << ">(" << name(e.node, KIND_FULL)
+           << ", a.p[" << e.arg << "], row0, lir, vbase, rok);\n";
       } else if (e.kind == KIND_COLV) {
         os << "    const float " << name(e.node, KIND_COLV) << " = rok ? fs_load1<" << e.dtype << ">(a.p[" << e.arg << "], row) : 0.0f;\n";
       }
     }
+    if (rowv_in_loop) emit_rowv("    ", "vbase", "row == 0 && rok");
 
     // members in stage order; the row reductions of a stage come last and share one exchange
     std::vector<int> order;
     for (int m : gp.members)
-      if (gp.level.at(m) >= 0) order.push_back(m);
+      if (gp.level.at(m) >= 0 && !folded[m]) order.push_back(m);
     auto is_rr = [&](int m) { return std::find(gp.row_reduces.begin(), gp.row_reduces.end(), m) != gp.row_reduces.end(); };
     std::stable_sort(order.begin(), order.end(), [&](int x, int y) {
       const int lx = gp.level.at(x), ly = gp.level.at(y);
       if (lx != ly) return lx < ly;
       return (int)is_rr(x) < (int)is_rr(y);
     });
+    const std::string col_ok = "(!RAGGED || ((e / V) * L + lir) < NV)";
 
     size_t i = 0;
     while (i < order.size()) {
@@ -237,9 +301,17 @@ struct Emitter {
         while (i < order.size() && is_rr(order[i]) && gp.level.at(order[i]) == lvl) batch.push_back(order[i++]);
         for (int b : batch) {
           const fs_node& bn = g.nodes[b];
-          const std::string arr = as_array(bn.in[0], std::to_string(loc(b)));
-          os << "    float q" << loc(b) << " = fs_lane_reduce<" << bn.attr_i << ", " << tmpl_row() << ">(" << arr << ", lir);\n";
-          os << "    q" << loc(b) << " = fs_segment_allreduce<" << bn.attr_i << ", (L < 64 ? L : 64)>(q" << loc(b) << ");\n";
+          const std::string q = "q" + std::to_string(loc(b));
+          if (folded[bn.in[0]]) {
+            // sum of products: one fma per element
+            const fs_node& mn = g.nodes[bn.in[0]];
+            os << "    float " << q << " = 0.0f;\n    _Pragma(\"unroll\") for (int e = 0; e < E; ++e) " << q << " = " << col_ok
+               << " ? __builtin_fmaf(" << ref(mn.in[0]) << ", " << ref(mn.in[1]) << ", " << q << ") : " << q << ";\n";
+          } else {
+            const std::string arr = as_array(bn.in[0], std::to_string(loc(b)));
+            os << "    float " << q << " = fs_lane_reduce<" << bn.attr_i << ", " << tmpl_row() << ">(" << arr << ", lir);\n";
+          }
+          os << "    " << q << " = fs_segment_allreduce<" << bn.attr_i << ", (L < 64 ? L : 64)>(" << q << ");\n";
         }
         if (xwave) {
           os << "    {\n      const fs_xwave<" << KB << ", " << WPR << "> xw{lds_rr + (parity * G + rg) * " << WPR * KB
@@ -252,16 +324,23 @@ struct Emitter {
         }
         for (int b : batch) {
           const fs_node& bn = g.nodes[b];
-          os << "    const float " << name(b, KIND_COLV) << " = fs_round<" << bn.dtype << ">("
-             << (bn.attr_i == FS_RED_MEAN ? "q" + std::to_string(loc(b)) + " / (float)C" : "q" + std::to_string(loc(b))) << ");\n";
+          const std::string q = "q" + std::to_string(loc(b));
+          os << "    const float " << name(b, KIND_COLV) << " = " << rounded(b, bn.attr_i == FS_RED_MEAN ? q + " / (float)C" : q) << ";\n";
           if (const ExtTensor* e = find_out(b)) emit_store(*e, "    ");
         }
         continue;
       }
       ++i;
       if (n.opcode == FS_REDUCE_COL && R > 1) {
-        os << "    _Pragma(\"unroll\") for (int e = 0; e < E; ++e) ca" << loc(m) << "[e] = rok ? fs_red_op<" << n.attr_i << ">(ca" << loc(m)
-           << "[e], " << ref(n.in[0]) << ") : ca" << loc(m) << "[e];\n";
+        const std::string ca = "ca" + std::to_string(loc(m));
+        if (folded[n.in[0]]) {
+          const fs_node& mn = g.nodes[n.in[0]];
+          os << "    _Pragma(\"unroll\") for (int e = 0; e < E; ++e) " << ca << "[e] = rok ? __builtin_fmaf(" << ref(mn.in[0]) << ", "
+             << ref(mn.in[1]) << ", " << ca << "[e]) : " << ca << "[e];\n";
+        } else {
+          os << "    _Pragma(\"unroll\") for (int e = 0; e < E; ++e) " << ca << "[e] = rok ? fs_red_op<" << n.attr_i << ">(" << ca << "[e], "
+             << ref(n.in[0]) << ") : " << ca << "[e];\n";
+        }
         continue;
       }
       if (n.opcode == FS_TRANSPOSE) {
@@ -273,10 +352,10 @@ struct Emitter {
       }
       const Kind k = gp.kind.at(m);
       if (k == KIND_COLV) {
-        os << "    const float " << name(m, k) << " = fs_round<" << n.dtype << ">(" << expr(n) << ");\n";
+        os << "    const float " << name(m, k) << " = " << rounded(m, expr(m)) << ";\n";
       } else {
-        os << "    float " << name(m, k) << "[E];\n    _Pragma(\"unroll\") for (int e = 0; e < E; ++e) " << name(m, k) << "[e] = fs_round<"
-           << n.dtype << ">(" << expr(n) << ");\n";
+        os << "    float " << name(m, k) << "[E];\n    _Pragma(\"unroll\") for (int e = 0; e < E; ++e) " << name(m, k) << "[e] = "
+           << rounded(m, expr(m)) << ";\n";
       }
       if (const ExtTensor* e = find_out(m)) emit_store(*e, "    ");
     }
@@ -301,7 +380,7 @@ struct Emitter {
         if (!e) continue;
         const fs_node& n = g.nodes[m];
         os << "          if (k == " << k << ") { _Pragma(\"unroll\") for (int f = 0; f < FV; ++f) fs_store1<" << e->dtype << ">(a.p[" << e->arg
-           << "], col0 + f, fs_round<" << n.dtype << ">(cv[i][f]" << (n.attr_i == FS_RED_MEAN ? " / (float)a.R" : "") << ")); }\n";
+           << "], col0 + f, cv[i][f]" << (n.attr_i == FS_RED_MEAN ? " / (float)a.R" : "") << "); }\n";
       }
       os << "        }\n      }\n    }\n  }\n";
     }

@@ -115,22 +115,26 @@ FS_DEV float fs_tanh(float x) {
 }
 
 // tanh-GeLU: 0.5 z (1 + tanh(u)) with u = sqrt(2/pi) (z + 0.044715 z^3).  Since
-// (1 + tanh u)/2 = sigmoid(2u), it is evaluated as z * sigmoid(2u): no cancellation in the
-// negative tail, one exp and one rcp per element.
+// (1 + tanh u)/2 = sigmoid(2u), it is evaluated as z / (1 + 2^(-2u log2e)): no cancellation in
+// the negative tail, one exp and one rcp per element.  The constants of u and of the base-2
+// exponent are folded into one odd polynomial: -2u log2e = z (c2 + c1 z^2).
 FS_DEV float fs_gelu_tanh(float z) {
-  const float z2 = z * z;
-  const float u2 = (2.0f * 0.7978845608028654f) * z * __builtin_fmaf(0.044715f, z2, 1.0f);
-  return z * fs_sigmoid(u2);
+  constexpr float c2 = -2.0f * 0.7978845608028654f * FS_LOG2E;
+  constexpr float c1 = 0.044715f * c2;
+  const float t = __builtin_fmaf(c1, z * z, c2);
+  const float e = __builtin_amdgcn_exp2f(z * t);
+  return z * __builtin_amdgcn_rcpf(1.0f + e);
 }
 
 // ------------------------------------------------------------------------------------------
 // vector memory access: V elements of dtype DT per access (16 bytes for the widest dtype of
 // the group).  Invalid rows / columns load zeros and store nothing.
 // ------------------------------------------------------------------------------------------
-template <int DT, int V> FS_DEV void fs_load_vec(float* dst, const void* base, long elem_index) {
+template <int DT, int V, bool NT = false> FS_DEV void fs_load_vec(float* dst, const void* base, long elem_index) {
   typedef typename fs_elem<DT>::type T;
   typedef typename fs_vec<T, V>::type VT;
-  const VT raw = *reinterpret_cast<const VT*>(static_cast<const T*>(base) + elem_index);
+  const VT* p = reinterpret_cast<const VT*>(static_cast<const T*>(base) + elem_index);
+  const VT raw = NT ? __builtin_nontemporal_load(p) : *p;
   if constexpr (V == 1) {
     dst[0] = fs_to_f32<DT>(raw);
   } else {
@@ -139,7 +143,7 @@ template <int DT, int V> FS_DEV void fs_load_vec(float* dst, const void* base, l
   }
 }
 
-template <int DT, int V> FS_DEV void fs_store_vec(const float* src, void* base, long elem_index) {
+template <int DT, int V, bool NT = false> FS_DEV void fs_store_vec(const float* src, void* base, long elem_index) {
   typedef typename fs_elem<DT>::type T;
   typedef typename fs_vec<T, V>::type VT;
   VT raw;
@@ -149,20 +153,22 @@ template <int DT, int V> FS_DEV void fs_store_vec(const float* src, void* base, 
 #pragma unroll
     for (int k = 0; k < V; ++k) raw[k] = fs_from_f32<DT>(src[k]);
   }
-  *reinterpret_cast<VT*>(static_cast<T*>(base) + elem_index) = raw;
+  VT* p = reinterpret_cast<VT*>(static_cast<T*>(base) + elem_index);
+  if constexpr (NT) __builtin_nontemporal_store(raw, p);
+  else *p = raw;
 }
 
 // Load the lane's slice of one row tile: vectors vbase + j*L + lir, j < NVL (vbase = 0 unless a
 // row is cut into several column tiles).  `row_elem0` is the element index of the row's first
 // column.  NV = vectors per row; RAGGED says some of those vector indices can fall beyond NV.
-template <int DT, int V, int NVL, int L, int NV, bool RAGGED>
+template <int DT, int V, int NVL, int L, int NV, bool RAGGED, bool NT = false>
 FS_DEV void fs_load_row(float (&dst)[NVL * V], const void* base, long row_elem0, int lir, int vbase, bool rok) {
 #pragma unroll
   for (int j = 0; j < NVL; ++j) {
     const int vi = vbase + j * L + lir;
     const bool ok = rok && (!RAGGED || vi < NV);
     if (ok) {
-      fs_load_vec<DT, V>(&dst[j * V], base, row_elem0 + (long)vi * V);
+      fs_load_vec<DT, V, NT>(&dst[j * V], base, row_elem0 + (long)vi * V);
     } else {
 #pragma unroll
       for (int k = 0; k < V; ++k) dst[j * V + k] = 0.0f;
@@ -170,13 +176,13 @@ FS_DEV void fs_load_row(float (&dst)[NVL * V], const void* base, long row_elem0,
   }
 }
 
-template <int DT, int V, int NVL, int L, int NV, bool RAGGED>
+template <int DT, int V, int NVL, int L, int NV, bool RAGGED, bool NT = false>
 FS_DEV void fs_store_row(const float (&src)[NVL * V], void* base, long row_elem0, int lir, int vbase, bool rok) {
 #pragma unroll
   for (int j = 0; j < NVL; ++j) {
     const int vi = vbase + j * L + lir;
     const bool ok = rok && (!RAGGED || vi < NV);
-    if (ok) fs_store_vec<DT, V>(&src[j * V], base, row_elem0 + (long)vi * V);
+    if (ok) fs_store_vec<DT, V, NT>(&src[j * V], base, row_elem0 + (long)vi * V);
   }
 }
 

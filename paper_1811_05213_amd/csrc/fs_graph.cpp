@@ -119,6 +119,15 @@ fs_status build_graph(const fs_graph_desc* desc, Graph* g) {
     for (int k = 0; k < ar; ++k) g->users[n.in[k]].push_back(id);
   }
 
+  // every ancestor of a predicate operand must be computed with exactly the roundings the graph
+  // spells out, or the predicate would not be reproducible bit for bit
+  g->exact.assign(N, 0);
+  for (int id = N - 1; id >= 0; --id) {
+    const fs_node& n = g->nodes[id];
+    if (n.opcode == FS_CMP || g->exact[id])
+      for (int k = 0; k < n.num_in; ++k) g->exact[n.in[k]] = 1;
+  }
+
   g->outputs.clear();
   for (int k = 0; k < desc->num_outputs; ++k) {
     const int o = desc->outputs[k];

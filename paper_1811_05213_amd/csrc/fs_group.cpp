@@ -156,7 +156,11 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   s.G = WG / L;
   s.ragged = (int64_t)CT * NVL * L != NV;
   s.n_iters = (int)(((int64_t)R * CT + s.G - 1) / s.G);
-  int cap = colred ? 1024 : 2048;
+  // Streaming groups launch one workgroup per row tile: the hardware hands tiles out in memory
+  // order and a fresh wavefront issues its loads at once, which measures faster on this device
+  // than persistent workgroups looping with a grid stride.  Column reductions keep a bounded
+  // grid because every workgroup leaves a partial to fold.
+  int cap = colred ? 1024 : (1 << 30);
   if (opt.has_hint && opt.hint.max_workgroups > 0) cap = opt.hint.max_workgroups;
   s.grid = std::max(1, std::min(s.n_iters, cap));
 
@@ -272,6 +276,12 @@ fs_status analyse_group(const Graph& g, const std::vector<int>& members, const s
   int arg = 0;
   for (ExtTensor& e : gp.ext_in) e.arg = arg++;
   for (ExtTensor& e : gp.ext_out) e.arg = arg++;
+  // tensors far larger than the caches are read / written once: keep them out of the way
+  auto big = [&](const ExtTensor& e) {
+    return e.kind == KIND_FULL && (uint64_t)g.nodes[e.node].rows * g.nodes[e.node].cols * dtype_size(e.dtype) >= (32ull << 20);
+  };
+  for (ExtTensor& e : gp.ext_in) e.streaming = big(e);
+  for (ExtTensor& e : gp.ext_out) e.streaming = big(e) && !e.transposed;
 
   gp.min_hbm_bytes = 0;
   for (const ExtTensor& e : gp.ext_in) gp.min_hbm_bytes += (uint64_t)g.nodes[e.node].rows * g.nodes[e.node].cols * dtype_size(e.dtype);

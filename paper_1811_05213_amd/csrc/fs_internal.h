@@ -44,6 +44,7 @@ struct Graph {
   std::vector<int> input_index;          // node id -> index into inputs[] or -1
   std::vector<int> output_index;         // node id -> index into outputs[] or -1
   std::vector<std::vector<int>> users;   // direct users of each node
+  std::vector<char> exact;               // node feeds a predicate: its bits must be reproducible (no contraction)
   int n() const { return (int)nodes.size(); }
 };
 
@@ -66,6 +67,7 @@ struct ExtTensor {
   int dtype = 0;
   bool transposed = false;  // output only: stored as [C,R]
   bool deferred = false;    // output only: column-reduction result written by the last workgroup
+  bool streaming = false;   // large tensor touched once: non-temporal loads / stores
   int arg = -1;             // index into the kernel's pointer table
 };
 
