@@ -53,14 +53,16 @@ def time_plan(runs, steps, warmup):
     """Average ms per step over `steps` launches cycling through `runs`, via events on the launch stream."""
     import torch
     n = len(runs)
+    launchers = [r.prepare() for r in runs]
     for i in range(warmup):
-        runs[i % n].launch()
+        launchers[i % n]()
     torch.cuda.synchronize()
     start, end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    order = [launchers[i % n] for i in range(steps)]
     t0 = time.perf_counter()
     start.record()
-    for i in range(steps):
-        runs[i % n].launch()
+    for launch in order:
+        launch()
     end.record()
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3

@@ -145,6 +145,7 @@ class Plan:
             h = fs_sched_hint(hint.get("lanes_per_row", 0), hint.get("wg_threads", 0), hint.get("max_workgroups", 0), 0)
             desc.hint = ctypes.pointer(h)
         self._h = ctypes.c_void_p()
+        self._run = lib().fs_plan_run
         _check(lib().fs_plan_create(ctypes.byref(desc), ctypes.byref(self._h)))
 
     def destroy(self) -> None:
@@ -195,9 +196,21 @@ class Plan:
 
     def run(self, input_ptrs: Sequence[int], output_ptrs: Sequence[int], workspace_ptr: int, workspace_bytes: int,
             stream: int = 0) -> None:
+        ins, outs = self.pointer_tables(input_ptrs, output_ptrs)
+        _check(lib().fs_plan_run(self._h, ins, outs, workspace_ptr, workspace_bytes, stream))
+
+    @staticmethod
+    def pointer_tables(input_ptrs: Sequence[int], output_ptrs: Sequence[int]):
+        """The two host arrays of device pointers fs_plan_run takes (build once, reuse per launch)."""
         ins = (ctypes.c_void_p * max(1, len(input_ptrs)))(*input_ptrs)
         outs = (ctypes.c_void_p * max(1, len(output_ptrs)))(*output_ptrs)
-        _check(lib().fs_plan_run(self._h, ins, outs, workspace_ptr, workspace_bytes, stream))
+        return ins, outs
+
+    def run_tables(self, ins, outs, workspace_ptr: int, workspace_bytes: int, stream: int = 0) -> None:
+        """fs_plan_run with pointer tables made by pointer_tables(): the cheapest call path from Python."""
+        status = self._run(self._h, ins, outs, workspace_ptr, workspace_bytes, stream)
+        if status != 0:
+            _check(status)
 
 
 def copy_probe(src_ptr: int, dst_ptr: int, nbytes: int, stream: int = 0) -> None:

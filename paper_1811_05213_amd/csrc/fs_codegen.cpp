@@ -233,15 +233,33 @@ struct Emitter {
     os << "  (void)lir; (void)rg; (void)R; (void)C; (void)G; (void)CT;\n";
     if (xwave) os << "  __shared__ float lds_rr[2 * G * " << WPR << " * " << KB << "];\n  int parity = 0;\n";
     if (K > 0) os << "  __shared__ float lds_col[G * C];\n  __shared__ fs_u32 lds_flag;\n";
+    if (s.stage_rowv) {
+      int n_rowv = 0;
+      for (const ExtTensor& e : gp.ext_in) n_rowv += e.kind == KIND_ROWV;
+      os << "  __shared__ float lds_rowv[" << n_rowv << " * C];\n";
+    }
 
     // ---- per-column values ----
     auto emit_rowv = [&](const std::string& ind, const std::string& vb, const std::string& store_cond) {
-      for (const ExtTensor& e : gp.ext_in)
-        if (e.kind == KIND_ROWV) {
-          os << ind << "float " << name(e.node, KIND_ROWV) << "[E];\n";
-          os << ind << "fs_load_row<" << e.dtype << ", " << tmpl_row() << ">(" << name(e.node, KIND_ROWV) << ", a.p[" << e.arg << "], 0, lir, " << vb
-             << ", true);\n";
-        }
+      if (s.stage_rowv) {
+        int k = 0;
+        for (const ExtTensor& e : gp.ext_in)
+          if (e.kind == KIND_ROWV) os << ind << "fs_stage_rowvec<" << e.dtype << ", C, WG>(lds_rowv + " << (k++) << " * C, a.p[" << e.arg << "]);\n";
+        os << ind << "__syncthreads();\n";
+        k = 0;
+        for (const ExtTensor& e : gp.ext_in)
+          if (e.kind == KIND_ROWV) {
+            os << ind << "float " << name(e.node, KIND_ROWV) << "[E];\n";
+            os << ind << "fs_read_staged<" << tmpl_row() << ">(" << name(e.node, KIND_ROWV) << ", lds_rowv + " << (k++) << " * C, lir, " << vb << ");\n";
+          }
+      } else {
+        for (const ExtTensor& e : gp.ext_in)
+          if (e.kind == KIND_ROWV) {
+            os << ind << "float " << name(e.node, KIND_ROWV) << "[E];\n";
+            os << ind << "fs_load_row<" << e.dtype << ", " << tmpl_row() << ">(" << name(e.node, KIND_ROWV) << ", a.p[" << e.arg << "], 0, lir, " << vb
+               << ");\n";
+          }
+      }
       for (int m : gp.members) {
         if (gp.level.at(m) >= 0 || folded[m]) continue;
         const std::string nm = name(m, KIND_ROWV);
@@ -266,14 +284,15 @@ struct Emitter {
     } else {
       os << "    const long unit = (long)it * G + rg;\n    const long row = unit / CT;\n    const int vbase = (int)(unit % CT) * (NVL * L);\n";
     }
-    os << "    const bool rok = row < R;\n    const long row0 = row * C;\n    (void)row0; (void)vbase;\n";
+    // rows beyond R are clamped for loads (never predicated) and masked at stores / accumulations
+    os << "    const bool rok = row < R;\n    const long row_ld = rok ? row : R - 1;\n    const long row0 = row_ld * C;\n    (void)row0; (void)vbase;\n";
     for (const ExtTensor& e : gp.ext_in) {
       if (e.kind == KIND_FULL) {
         os << "    float " << name(e.node, KIND_FULL) << "[E];\n";
         os << "    fs_load_row<" << e.dtype << ", " << tmpl_row() << ", " << (e.streaming ? "true" : "false") << ">(" << name(e.node, KIND_FULL)
-           << ", a.p[" << e.arg << "], row0, lir, vbase, rok);\n";
+           << ", a.p[" << e.arg << "], row0, lir, vbase);\n";
       } else if (e.kind == KIND_COLV) {
-        os << "    const float " << name(e.node, KIND_COLV) << " = rok ? fs_load1<" << e.dtype << ">(a.p[" << e.arg << "], row) : 0.0f;\n";
+        os << "    const float " << name(e.node, KIND_COLV) << " = fs_load1<" << e.dtype << ">(a.p[" << e.arg << "], row_ld);\n";
       }
     }
     if (rowv_in_loop) emit_rowv("    ", "vbase", "row == 0 && rok");

@@ -159,20 +159,18 @@ template <int DT, int V, bool NT = false> FS_DEV void fs_store_vec(const float* 
 }
 
 // Load the lane's slice of one row tile: vectors vbase + j*L + lir, j < NVL (vbase = 0 unless a
-// row is cut into several column tiles).  `row_elem0` is the element index of the row's first
-// column.  NV = vectors per row; RAGGED says some of those vector indices can fall beyond NV.
+// row is cut into several column tiles).  `row_elem0` is the element index of the first column
+// of a VALID row (callers clamp the row index instead of predicating the load).  NV = vectors
+// per row; RAGGED says some of those vector indices can fall beyond NV: they are clamped too.
+// Nothing here branches, so all loads of a body are issued back to back and waited for once;
+// lanes outside the tensor hold duplicates that are never stored and never reduced.
 template <int DT, int V, int NVL, int L, int NV, bool RAGGED, bool NT = false>
-FS_DEV void fs_load_row(float (&dst)[NVL * V], const void* base, long row_elem0, int lir, int vbase, bool rok) {
+FS_DEV void fs_load_row(float (&dst)[NVL * V], const void* base, long row_elem0, int lir, int vbase) {
 #pragma unroll
   for (int j = 0; j < NVL; ++j) {
-    const int vi = vbase + j * L + lir;
-    const bool ok = rok && (!RAGGED || vi < NV);
-    if (ok) {
-      fs_load_vec<DT, V, NT>(&dst[j * V], base, row_elem0 + (long)vi * V);
-    } else {
-#pragma unroll
-      for (int k = 0; k < V; ++k) dst[j * V + k] = 0.0f;
-    }
+    int vi = vbase + j * L + lir;
+    if (RAGGED) vi = vi < NV ? vi : NV - 1;
+    fs_load_vec<DT, V, NT>(&dst[j * V], base, row_elem0 + (long)vi * V);
   }
 }
 
@@ -198,6 +196,32 @@ FS_DEV void fs_store_row_transposed(const float (&src)[NVL * V], void* base, lon
 #pragma unroll
       for (int k = 0; k < V; ++k) static_cast<T*>(base)[(long)(vi * V + k) * R + row] = fs_from_f32<DT>(src[j * V + k]);
     }
+  }
+}
+
+// Per-column vectors ([1,C] operands) shared by every row of the workgroup are staged once in
+// LDS as fp32: one cooperative pass of the whole workgroup instead of every wavefront pulling
+// its own copy through the vector cache (which is the narrower path: 64 B/clk against 128).
+template <int DT, int C, int WG> FS_DEV void fs_stage_rowvec(float* lds, const void* src) {
+  typedef typename fs_elem<DT>::type T;
+  constexpr int SV = (C % 4 == 0) ? 4 : 1;
+  for (int i = (int)threadIdx.x * SV; i < C; i += WG * SV) {
+    float tmp[SV];
+    fs_load_vec<DT, SV>(tmp, src, i);
+#pragma unroll
+    for (int k = 0; k < SV; ++k) lds[i + k] = tmp[k];
+  }
+  (void)sizeof(T);
+}
+// The lane's slice of a staged vector (same element ownership as fs_load_row).
+template <int V, int NVL, int L, int NV, bool RAGGED>
+FS_DEV void fs_read_staged(float (&dst)[NVL * V], const float* lds, int lir, int vbase) {
+#pragma unroll
+  for (int j = 0; j < NVL; ++j) {
+    const int vi = vbase + j * L + lir;
+    const bool ok = !RAGGED || vi < NV;
+#pragma unroll
+    for (int k = 0; k < V; ++k) dst[j * V + k] = ok ? lds[vi * V + k] : 0.0f;
   }
 }
 

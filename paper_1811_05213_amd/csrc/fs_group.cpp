@@ -172,6 +172,15 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   int lds = 0;
   if (rowred && L > 64) lds += 2 * s.G * (L / 64) * gp->max_batched_reduces * 4;
   if (colred) lds += s.G * C * 4 + 16;
+  // [1,C] inputs shared by all rows of a workgroup: with one trip per workgroup they are staged in
+  // LDS by the whole workgroup when several rows share them and the budget allows
+  int n_rowv = 0;
+  for (const ExtTensor& e : gp->ext_in) n_rowv += e.kind == KIND_ROWV;
+  s.stage_rowv = false;
+  if (n_rowv > 0 && CT == 1 && s.grid >= s.n_iters && s.G >= 4 && R > 1 && lds + n_rowv * C * 4 <= opt.lds_budget) {
+    s.stage_rowv = true;
+    lds += n_rowv * C * 4;
+  }
   s.lds_bytes = lds;
   if (lds > opt.lds_budget)
     FS_FAIL(FS_ERR_LDS_BUDGET, "group needs %d bytes of LDS, budget is %d", lds, opt.lds_budget);

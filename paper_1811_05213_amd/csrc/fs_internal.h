@@ -85,6 +85,7 @@ struct Schedule {
   bool ragged = false;  // some lane's vector index can fall beyond NV
   int lds_bytes = 0;
   int fan_in = 32;  // column-reduction tree fan-in
+  bool stage_rowv = false;  // [1,C] inputs are staged once per workgroup in LDS
 };
 
 struct GroupPlan {

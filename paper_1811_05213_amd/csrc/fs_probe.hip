@@ -37,7 +37,7 @@ __global__ void __launch_bounds__(256) fs_device_selftest_kernel(const void* in,
     const long row = (long)it * G + rg;
     const bool rok = row < R;
     float v[E];
-    fs_load_row<FS_DT_BF16, V, NVL, L, NV, true>(v, in, row * C, lir, 0, rok);
+    fs_load_row<FS_DT_BF16, V, NVL, L, NV, true>(v, in, (rok ? row : 0) * C, lir, 0);
     float q = fs_segment_allreduce<FS_K_SUM, 64>(fs_lane_reduce<FS_K_SUM, V, NVL, L, NV, true>(v, lir));
     float m = fs_segment_allreduce<FS_K_MAX, 64>(fs_lane_reduce<FS_K_MAX, V, NVL, L, NV, true>(v, lir));
     const fs_xwave<2, 2> xw{lds_rr + (parity * G + rg) * 4, lir >> 6, (tid & 63) == 0};

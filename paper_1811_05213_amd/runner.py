@@ -59,6 +59,15 @@ class DeviceRun:
         self.plan.run([t.data_ptr() for t in self.inputs], [t.data_ptr() for t in self.outputs],
                       self.workspace.data_ptr() if self.ws_bytes else 0, self.ws_bytes, stream)
 
+    def prepare(self):
+        """Freeze the pointer tables and the stream; returns a zero-argument launcher for timing loops."""
+        ins, outs = self.plan.pointer_tables([t.data_ptr() for t in self.inputs], [t.data_ptr() for t in self.outputs])
+        ws = self.workspace.data_ptr() if self.ws_bytes else 0
+        stream = torch.cuda.current_stream(self.device).cuda_stream
+        run, nbytes = self.plan.run_tables, self.ws_bytes
+        self._frozen = (ins, outs)  # keep the tables alive
+        return lambda: run(ins, outs, ws, nbytes, stream)
+
     def results(self) -> List[np.ndarray]:
         torch.cuda.synchronize(self.device)
         return [to_host(t, n.dtype) for t, n in zip(self.outputs, self.out_nodes)]
