@@ -120,6 +120,19 @@ def measure_workload(cfg, steps, warmup, with_unfused=True, rows=None):
     return out
 
 
+def measured_traffic(workload_name):
+    """HBM bytes per launch of the workload's stitched kernel, from the committed rocprofv3 counter summary
+    (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, scale factors calibrated on the copy probe), or None."""
+    path = os.path.join(ROOT, "profiles", workload_name + "_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(cfg):
     """The CPU oracle as it stands, timed on the host cores of this machine (a reference, not the target)."""
     import oracle
@@ -143,7 +156,7 @@ def main():
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--workload", type=int, default=2, help="BASELINE.json config number (1-5) for the headline line")
-    ap.add_argument("--no-extras", action="store_true", help="skip the other workloads and the copy probe")
+    ap.add_argument("--no-extras", action="store_true", help="skip the other four workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -160,9 +173,8 @@ def main():
     head = measure_workload(args.workload, args.steps, args.warmup)
     log("headline", json.dumps(head))
     extras = {}
-    copy_gbs = None
+    copy_gbs = time_copy_probe(1 << 29)
     if not args.no_extras:
-        copy_gbs = time_copy_probe(1 << 29)
         for cfg in (1, 2, 3, 4, 5):
             if cfg == args.workload:
                 continue
@@ -192,7 +204,7 @@ def main():
         "launch_ratio": head.get("launch_ratio"),
         "unfused_ms_per_step": head.get("unfused", {}).get("ms"),
         "roofline": {"bound": "hbm", "achieved": head["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": head["frac_of_peak"], "traffic": None, "kernel": head["kernel"],
+                     "frac": head["frac_of_peak"], "traffic": measured_traffic(head["workload"]), "kernel": head["kernel"],
                      "algorithmic_bytes_per_launch": head["min_hbm_bytes"], "avg_launch_us": ms * 1e3},
         "cpu_baseline": cpu,
         "copy_probe_gbs": copy_gbs,

@@ -236,7 +236,7 @@ struct Emitter {
     if (s.stage_rowv) {
       int n_rowv = 0;
       for (const ExtTensor& e : gp.ext_in) n_rowv += e.kind == KIND_ROWV;
-      os << "  __shared__ float lds_rowv[" << n_rowv << " * C];\n";
+      os << "  constexpr int SLOT = NVL * L * V;\n  __shared__ float lds_rowv[" << n_rowv << " * SLOT];\n";
     }
 
     // ---- per-column values ----
@@ -244,13 +244,14 @@ struct Emitter {
       if (s.stage_rowv) {
         int k = 0;
         for (const ExtTensor& e : gp.ext_in)
-          if (e.kind == KIND_ROWV) os << ind << "fs_stage_rowvec<" << e.dtype << ", C, WG>(lds_rowv + " << (k++) << " * C, a.p[" << e.arg << "]);\n";
+          if (e.kind == KIND_ROWV)
+            os << ind << "fs_stage_rowvec<" << e.dtype << ", V, L, C, WG>(lds_rowv + " << (k++) << " * SLOT, a.p[" << e.arg << "]);\n";
         os << ind << "__syncthreads();\n";
         k = 0;
         for (const ExtTensor& e : gp.ext_in)
           if (e.kind == KIND_ROWV) {
             os << ind << "float " << name(e.node, KIND_ROWV) << "[E];\n";
-            os << ind << "fs_read_staged<" << tmpl_row() << ">(" << name(e.node, KIND_ROWV) << ", lds_rowv + " << (k++) << " * C, lir, " << vb << ");\n";
+            os << ind << "fs_read_staged<" << tmpl_row() << ">(" << name(e.node, KIND_ROWV) << ", lds_rowv + " << (k++) << " * SLOT, lir);\n";
           }
       } else {
         for (const ExtTensor& e : gp.ext_in)

@@ -202,26 +202,55 @@ FS_DEV void fs_store_row_transposed(const float (&src)[NVL * V], void* base, lon
 // Per-column vectors ([1,C] operands) shared by every row of the workgroup are staged once in
 // LDS as fp32: one cooperative pass of the whole workgroup instead of every wavefront pulling
 // its own copy through the vector cache (which is the narrower path: 64 B/clk against 128).
-template <int DT, int C, int WG> FS_DEV void fs_stage_rowvec(float* lds, const void* src) {
-  typedef typename fs_elem<DT>::type T;
-  constexpr int SV = (C % 4 == 0) ? 4 : 1;
-  for (int i = (int)threadIdx.x * SV; i < C; i += WG * SV) {
-    float tmp[SV];
-    fs_load_vec<DT, SV>(tmp, src, i);
+// The staged copy is laid out in the order lanes read it: the 4-float chunk q of vector
+// vi = j*L + lir sits at chunk index (j*(V/4) + q)*L + lir, so a 128-bit LDS read by
+// consecutive lanes touches consecutive 16-byte chunks (no bank conflicts).  SLOT = NVL*L*V
+// floats per vector.
+template <int DT, int V, int L, int C, int WG> FS_DEV void fs_stage_rowvec(float* lds, const void* src) {
+  if constexpr (V % 4 == 0) {
+    constexpr int Q = V / 4;
+    for (int chunk = (int)threadIdx.x; chunk < C / 4; chunk += WG) {
+      float tmp[4];
+      fs_load_vec<DT, 4>(tmp, src, chunk * 4);
+      const int vi = chunk / Q, q = chunk % Q, j = vi / L, l = vi % L;
+      float* d = lds + ((j * Q + q) * L + l) * 4;
 #pragma unroll
-    for (int k = 0; k < SV; ++k) lds[i + k] = tmp[k];
+      for (int k = 0; k < 4; ++k) d[k] = tmp[k];
+    }
+  } else {
+    for (int i = (int)threadIdx.x; i < C; i += WG) {
+      float tmp[1];
+      fs_load_vec<DT, 1>(tmp, src, i);
+      lds[i] = tmp[0];
+    }
   }
-  (void)sizeof(T);
 }
 // The lane's slice of a staged vector (same element ownership as fs_load_row).
 template <int V, int NVL, int L, int NV, bool RAGGED>
-FS_DEV void fs_read_staged(float (&dst)[NVL * V], const float* lds, int lir, int vbase) {
+FS_DEV void fs_read_staged(float (&dst)[NVL * V], const float* lds, int lir) {
+  if constexpr (V % 4 == 0) {
+    constexpr int Q = V / 4;
+    typedef float f4 __attribute__((ext_vector_type(4)));
 #pragma unroll
-  for (int j = 0; j < NVL; ++j) {
-    const int vi = vbase + j * L + lir;
-    const bool ok = !RAGGED || vi < NV;
+    for (int j = 0; j < NVL; ++j) {
 #pragma unroll
-    for (int k = 0; k < V; ++k) dst[j * V + k] = ok ? lds[vi * V + k] : 0.0f;
+      for (int q = 0; q < Q; ++q) {
+        const f4 x = *reinterpret_cast<const f4*>(lds + ((j * Q + q) * L + lir) * 4);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const float xk = x[k];
+          dst[j * V + q * 4 + k] = xk;
+        }
+      }
+    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < NVL; ++j) {
+      int vi = j * L + lir;
+      if (RAGGED) vi = vi < NV ? vi : NV - 1;
+#pragma unroll
+      for (int k = 0; k < V; ++k) dst[j * V + k] = lds[vi * V + k];
+    }
   }
 }
 

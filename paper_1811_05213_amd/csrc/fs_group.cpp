@@ -177,9 +177,10 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   int n_rowv = 0;
   for (const ExtTensor& e : gp->ext_in) n_rowv += e.kind == KIND_ROWV;
   s.stage_rowv = false;
-  if (n_rowv > 0 && CT == 1 && s.grid >= s.n_iters && s.G >= 4 && R > 1 && lds + n_rowv * C * 4 <= opt.lds_budget) {
+  const int slot_bytes = s.NVL * s.L * V * 4;
+  if (n_rowv > 0 && CT == 1 && s.grid >= s.n_iters && s.G >= 4 && R > 1 && lds + n_rowv * slot_bytes <= opt.lds_budget) {
     s.stage_rowv = true;
-    lds += n_rowv * C * 4;
+    lds += n_rowv * slot_bytes;
   }
   s.lds_bytes = lds;
   if (lds > opt.lds_budget)
