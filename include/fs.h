@@ -149,7 +149,7 @@ typedef struct {
                                     node (ignored for INPUT/CONST/BCAST_* nodes, which are inlined into
                                     each consumer): the caller's fusion plan.  Ignored in FS_MODE_UNFUSED. */
   uint32_t mode;                 /* FS_MODE_* */
-  int32_t lds_budget_bytes;      /* per-workgroup LDS limit for one group; 0 => 32768 */
+  int32_t lds_budget_bytes;      /* per-workgroup LDS limit for one group; 0 => 65536 (of 160 KB per CU) */
   const fs_sched_hint* hint;     /* host; may be NULL */
 } fs_graph_desc;
 

@@ -232,7 +232,7 @@ struct Emitter {
     os << "  const long R = a.R;\n";
     os << "  (void)lir; (void)rg; (void)R; (void)C; (void)G; (void)CT;\n";
     if (xwave) os << "  __shared__ float lds_rr[2 * G * " << WPR << " * " << KB << "];\n  int parity = 0;\n";
-    if (K > 0) os << "  __shared__ float lds_col[G * C];\n  __shared__ fs_u32 lds_flag;\n";
+    if (K > 0) os << "  __shared__ float lds_col[(L < 64 ? WG / 64 : G) * C];\n  __shared__ fs_u32 lds_flag;\n";
     if (s.stage_rowv) {
       int n_rowv = 0;
       for (const ExtTensor& e : gp.ext_in) n_rowv += e.kind == KIND_ROWV;
@@ -279,21 +279,33 @@ struct Emitter {
     }
 
     // ---- the row loop ----
-    os << "  for (int it = (int)blockIdx.x; it < a.n_iters; it += (int)gridDim.x) {\n";
-    if (s.CT == 1) {
-      os << "    const long row = (long)it * G + rg;\n    constexpr int vbase = 0;\n";
+    // A looping kernel handles U row tiles per trip: the loads of all U tiles are issued first,
+    // then the U bodies run one after the other (more bytes in flight per wavefront).
+    const int U = (rowv_in_loop || s.CT > 1) ? 1 : std::max(1, s.U);
+    if (U == 1) {
+      os << "  for (int it = (int)blockIdx.x; it < a.n_iters; it += (int)gridDim.x) {\n";
     } else {
-      os << "    const long unit = (long)it * G + rg;\n    const long row = unit / CT;\n    const int vbase = (int)(unit % CT) * (NVL * L);\n";
+      os << "  for (int it0 = (int)blockIdx.x * " << U << "; it0 < a.n_iters; it0 += (int)gridDim.x * " << U << ") {\n";
     }
-    // rows beyond R are clamped for loads (never predicated) and masked at stores / accumulations
-    os << "    const bool rok = row < R;\n    const long row_ld = rok ? row : R - 1;\n    const long row0 = row_ld * C;\n    (void)row0; (void)vbase;\n";
-    for (const ExtTensor& e : gp.ext_in) {
-      if (e.kind == KIND_FULL) {
-        os << "    float " << name(e.node, KIND_FULL) << "[E];\n";
-        os << "    fs_load_row<" << e.dtype << ", " << tmpl_row() << ", " << (e.streaming ? "true" : "false") << ">(" << name(e.node, KIND_FULL)
-           << ", a.p[" << e.arg << "], row0, lir, vbase);\n";
-      } else if (e.kind == KIND_COLV) {
-        os << "    const float " << name(e.node, KIND_COLV) << " = fs_load1<" << e.dtype << ">(a.p[" << e.arg << "], row_ld);\n";
+    for (int u = 0; u < U; ++u) {
+      const std::string x = U == 1 ? "" : "_" + std::to_string(u);
+      if (U > 1) os << "    const int it" << x << " = it0 + " << u << ";\n";
+      if (s.CT == 1) {
+        os << "    const long row" << x << " = (long)it" << x << " * G + rg;\n    constexpr int vbase" << x << " = 0;\n";
+      } else {
+        os << "    const long unit = (long)it * G + rg;\n    const long row = unit / CT;\n    const int vbase = (int)(unit % CT) * (NVL * L);\n";
+      }
+      // rows beyond R are clamped for loads (never predicated) and masked at stores / accumulations
+      os << "    const bool rok" << x << " = row" << x << " < R;\n    const long row_ld" << x << " = rok" << x << " ? row" << x
+         << " : R - 1;\n    const long row0" << x << " = row_ld" << x << " * C;\n    (void)row0" << x << "; (void)vbase" << x << ";\n";
+      for (const ExtTensor& e : gp.ext_in) {
+        if (e.kind == KIND_FULL) {
+          os << "    float " << name(e.node, KIND_FULL) << x << "[E];\n";
+          os << "    fs_load_row<" << e.dtype << ", " << tmpl_row() << ", " << (e.streaming ? "true" : "false") << ">(" << name(e.node, KIND_FULL)
+             << x << ", a.p[" << e.arg << "], row0" << x << ", lir, vbase" << x << ");\n";
+        } else if (e.kind == KIND_COLV) {
+          os << "    const float " << name(e.node, KIND_COLV) << x << " = fs_load1<" << e.dtype << ">(a.p[" << e.arg << "], row_ld" << x << ");\n";
+        }
       }
     }
     if (rowv_in_loop) emit_rowv("    ", "vbase", "row == 0 && rok");
@@ -310,7 +322,17 @@ struct Emitter {
     });
     const std::string col_ok = "(!RAGGED || ((e / V) * L + lir) < NV)";
 
-    size_t i = 0;
+    for (int u = 0; u < U; ++u) {
+      if (U > 1) {
+        const std::string x = "_" + std::to_string(u);
+        os << "    {\n    const long row = row" << x << "; const bool rok = rok" << x << "; const long row0 = row0" << x
+           << "; constexpr int vbase = 0; (void)row; (void)rok; (void)row0; (void)vbase;\n";
+        for (const ExtTensor& e : gp.ext_in) {
+          if (e.kind == KIND_FULL) os << "    float (&" << name(e.node, KIND_FULL) << ")[E] = " << name(e.node, KIND_FULL) << x << ";\n";
+          else if (e.kind == KIND_COLV) os << "    const float " << name(e.node, KIND_COLV) << " = " << name(e.node, KIND_COLV) << x << ";\n";
+        }
+      }
+      size_t i = 0;
     while (i < order.size()) {
       const int m = order[i];
       const fs_node& n = g.nodes[m];
@@ -378,6 +400,8 @@ struct Emitter {
            << rounded(m, expr(m)) << ";\n";
       }
       if (const ExtTensor* e = find_out(m)) emit_store(*e, "    ");
+    }
+      if (U > 1) os << "    }\n";
     }
     os << "  }\n";
 

@@ -399,20 +399,48 @@ template <int FV> FS_DEV void fs_store_dev(const float (&src)[FV], __amdgpu_buff
   }
 }
 
+FS_DEV int fs_lane_id() { return (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u)); }
+// value of lane (lane ^ mask) of the same wavefront (LDS crossbar, no LDS memory)
+FS_DEV float fs_shfl_xor(float v, int mask) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute((fs_lane_id() ^ mask) << 2, __builtin_bit_cast(int, v)));
+}
+
 // Stage 1, in-workgroup fold of reduction number KIDX.  acc: the lane's per-column accumulators
-// in the row layout.  Fills the chunks of `vals` that belong to reduction KIDX.
+// in the row layout.  Fills the chunks of `vals` that belong to reduction KIDX.  When several
+// row-groups share a wavefront (L < 64) they are folded inside the wavefront first (lanes l,
+// l+L, l+2L, ... own the same columns), so the LDS area holds one row of C floats per wavefront
+// (GL = WG/64 rows), not one per row-group.
 template <int KIND, int KIDX, int K, int V, int NVL, int L, int NV, int C, int WG, int FV, int CPT>
-FS_DEV void fs_colred_fold_wg(const float (&acc)[NVL * V], float (&vals)[CPT][FV], float* lds /* G*C floats */, int lir, int rg) {
+FS_DEV void fs_colred_fold_wg(const float (&acc_in)[NVL * V], float (&vals)[CPT][FV], float* lds /* GL*C floats */, int lir, int rg) {
   typedef fs_colfold<K, C, WG, FV> S;
   static_assert(CPT == S::CPT, "chunks per thread");
-  constexpr int G = WG / L;
+  constexpr int GL = L < 64 ? WG / 64 : WG / L;
+  float acc[NVL * V];
+#pragma unroll
+  for (int e = 0; e < NVL * V; ++e) acc[e] = acc_in[e];
+  if constexpr (L < 64) {
+#pragma unroll
+    for (int m = L; m < 64; m <<= 1) {
+#pragma unroll
+      for (int e = 0; e < NVL * V; ++e) {
+        const float other = fs_shfl_xor(acc[e], m);
+        // both partners compute op(lower, upper): identical bits in both
+        const bool upper = (fs_lane_id() & m) != 0;
+        acc[e] = fs_red_op<KIND>(upper ? other : acc[e], upper ? acc[e] : other);
+      }
+    }
+  }
+  const int slot = L < 64 ? (int)threadIdx.x / 64 : rg;
+  const bool writer = L < 64 ? (fs_lane_id() < L) : true;
   __syncthreads();  // the LDS area may still be read by the previous fold
+  if (writer) {
 #pragma unroll
-  for (int j = 0; j < NVL; ++j) {
-    const int vi = j * L + lir;
-    if (vi < NV) {
+    for (int j = 0; j < NVL; ++j) {
+      const int vi = j * L + lir;
+      if (vi < NV) {
 #pragma unroll
-      for (int k = 0; k < V; ++k) lds[rg * C + vi * V + k] = acc[j * V + k];
+        for (int k = 0; k < V; ++k) lds[slot * C + vi * V + k] = acc[j * V + k];
+      }
     }
   }
   __syncthreads();
@@ -424,7 +452,7 @@ FS_DEV void fs_colred_fold_wg(const float (&acc)[NVL * V], float (&vals)[CPT][FV
 #pragma unroll
       for (int f = 0; f < FV; ++f) {
         float a = lds[col0 + f];
-        for (int g = 1; g < G; ++g) a = fs_red_op<KIND>(a, lds[g * C + col0 + f]);
+        for (int g = 1; g < GL; ++g) a = fs_red_op<KIND>(a, lds[g * C + col0 + f]);
         vals[i][f] = a;
       }
     }
@@ -449,7 +477,7 @@ FS_DEV bool fs_colred_fold_grid(float (&vals)[CPT][FV], float* part, fs_u32* tic
   typedef fs_colfold<K, C, WG, FV> S;
   static_assert(CPT == S::CPT, "chunks per thread");
   constexpr int KC = K * C;
-  constexpr int FB = 8;  // loads in flight per chunk
+  constexpr int FB = 16;  // loads in flight per chunk
   fs_u32 idx = blockIdx.x, n = gridDim.x;
   const int t = (int)threadIdx.x;
   while (n > 1) {

@@ -2,6 +2,7 @@
 #include <algorithm>
 #include <functional>
 #include <set>
+#include <cstdlib>
 
 #include "fs_internal.h"
 
@@ -124,6 +125,8 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   if (l_min > 1024 && !tileable) FS_FAIL(FS_ERR_UNSUPPORTED, "rows of %d columns are too long for one workgroup", C);
   if (tileable) l_min = std::min(l_min, 256);
   int L = rowred ? std::min(64, l_max) : std::min(256, l_max);
+  // looping (column-reduction) kernels want more bytes in flight per lane: 16 elements per lane
+  if (colred) L = std::min(L, std::max(1, pow2_ceil((NV * V + 15) / 16)));
   L = std::max(L, l_min);
   // small problems: more lanes per row until the device has ~8 wavefronts per CU
   while ((int64_t)R * L / 64 < 2048 && L < l_max) L *= 2;
@@ -139,7 +142,8 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
 
   int WG;
   const int64_t total_waves = std::max<int64_t>(1, (int64_t)R * CT * L / 64);
-  if (colred || total_waves > 1024) WG = std::max(256, L);
+  if (colred) WG = std::max(512, L);
+  else if (total_waves > 1024) WG = std::max(256, L);
   else WG = std::max(64, L);
   if (opt.has_hint && opt.hint.wg_threads > 0) {
     const int h = opt.hint.wg_threads;
@@ -160,9 +164,13 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   // order and a fresh wavefront issues its loads at once, which measures faster on this device
   // than persistent workgroups looping with a grid stride.  Column reductions keep a bounded
   // grid because every workgroup leaves a partial to fold.
-  int cap = colred ? 1024 : (1 << 30);
+  int cap = colred ? 256 : (1 << 30);
   if (opt.has_hint && opt.hint.max_workgroups > 0) cap = opt.hint.max_workgroups;
   s.grid = std::max(1, std::min(s.n_iters, cap));
+  s.U = 1;  // (two tiles per trip measured no faster than one with 16 elements per lane)
+  if (const char* env = getenv("FS_DEBUG_UNROLL")) s.U = std::max(1, atoi(env));
+  // two fold levels at most: the smallest fan-in whose square covers the grid
+  s.fan_in = s.grid <= 64 ? 8 : s.grid <= 256 ? 16 : 32;
 
   // LDS plan (Section 5.1).  Size requirements: cross-wave row-reduction partials (the "direct
   // allocation" for a non-root Reduce) and the column-partial fold area.  Space sharing: all row
@@ -171,7 +179,7 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   // reductions in turn.
   int lds = 0;
   if (rowred && L > 64) lds += 2 * s.G * (L / 64) * gp->max_batched_reduces * 4;
-  if (colred) lds += s.G * C * 4 + 16;
+  if (colred) lds += (L < 64 ? WG / 64 : s.G) * C * 4 + 16;
   // [1,C] inputs shared by all rows of a workgroup: with one trip per workgroup they are staged in
   // LDS by the whole workgroup when several rows share them and the budget allows
   int n_rowv = 0;

@@ -79,6 +79,7 @@ struct Schedule {
   int E = 4;        // elements per lane = NVL * V
   int WG = 256;     // workgroup size
   int G = 4;        // row-groups per workgroup = WG / L
+  int U = 1;        // row tiles per loop trip in looping kernels (loads of all U issued first)
   int CT = 1;       // column tiles per row (> 1 only for groups without reductions: very long rows)
   int n_iters = 0;  // ceil(R * CT / G): loop trips over the whole grid
   int grid = 0;     // workgroups (`blocks` of Section 4.1)
@@ -109,7 +110,7 @@ struct GroupPlan {
 
 struct PlanOptions {
   uint32_t mode = FS_MODE_STITCHED;
-  int lds_budget = 32768;
+  int lds_budget = 65536;
   fs_sched_hint hint = {0, 0, 0, 0};
   bool has_hint = false;
 };

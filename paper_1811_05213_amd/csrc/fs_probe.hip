@@ -27,7 +27,7 @@ struct fs_selftest_kinds {
 __global__ void __launch_bounds__(256) fs_device_selftest_kernel(const void* in, void* out, float* part, fs_u32* tickets, int R) {
   constexpr int V = 8, NVL = 2, L = 128, NV = 200, WG = 256, G = WG / L, C = NV * V, E = NVL * V;
   __shared__ float lds_rr[2 * G * 2 * 2];
-  __shared__ float lds_col[G * C];
+  __shared__ float lds_col[(L < 64 ? WG / 64 : G) * C];
   __shared__ fs_u32 flag;
   const int tid = threadIdx.x, lir = tid & (L - 1), rg = tid / L;
   float ca[E], cb[E];

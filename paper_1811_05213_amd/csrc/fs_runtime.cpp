@@ -133,7 +133,7 @@ fs_status fs_plan_create(const fs_graph_desc* desc, fs_plan** out_plan) {
     return st;
   }
   plan->opt.mode = desc->mode;
-  plan->opt.lds_budget = desc->lds_budget_bytes > 0 ? desc->lds_budget_bytes : 32768;
+  plan->opt.lds_budget = desc->lds_budget_bytes > 0 ? desc->lds_budget_bytes : 65536;
   if (desc->hint) {
     plan->opt.hint = *desc->hint;
     plan->opt.has_hint = true;
