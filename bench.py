@@ -70,9 +70,10 @@ def time_plan(runs, steps, warmup):
 
 
 def time_copy_probe(nbytes, reps=20):
+    """GB/s (read + write) of the library's plain copy kernel moving nbytes -> nbytes, rotating buffers."""
     import torch
     from paper_1811_05213_amd import copy_probe
-    n_sets = 4
+    n_sets = max(3, min(24, (3 << 30) // (2 * nbytes)))
     srcs = [torch.empty(nbytes, dtype=torch.uint8, device="cuda:0").random_(0, 255) for _ in range(n_sets)]
     dsts = [torch.empty(nbytes, dtype=torch.uint8, device="cuda:0") for _ in range(n_sets)]
     stream = torch.cuda.current_stream().cuda_stream
@@ -174,6 +175,9 @@ def main():
     log("headline", json.dumps(head))
     extras = {}
     copy_gbs = time_copy_probe(1 << 29)
+    # the same number of bytes as the headline workload moves, as a plain copy: the practical ceiling at that size
+    same = max(1 << 20, (head["min_hbm_bytes"] // 2) // 4096 * 4096)
+    copy_same_gbs = time_copy_probe(same, reps=200 if same < (1 << 28) else 20)
     if not args.no_extras:
         for cfg in (1, 2, 3, 4, 5):
             if cfg == args.workload:
@@ -181,6 +185,10 @@ def main():
             steps = {1: 400, 2: 400, 3: 30, 4: 200, 5: 50}[cfg]
             extras[f"cfg{cfg}"] = measure_workload(cfg, steps, max(4, steps // 10))
             log(f"cfg{cfg}", json.dumps(extras[f"cfg{cfg}"]))
+        # the same stitched kernels on more rows: where the launch stops dominating (row sweep end points)
+        for cfg, rows in ((1, 65536), (2, 262144)):
+            extras[f"cfg{cfg}_rows{rows}"] = measure_workload(cfg, 50, 5, with_unfused=False, rows=rows)
+            log(f"cfg{cfg}_rows{rows}", json.dumps(extras[f"cfg{cfg}_rows{rows}"]))
     cpu = None if args.no_cpu else cpu_baseline(args.workload)
 
     ms = head["stitched"]["ms"]
@@ -208,6 +216,7 @@ def main():
                      "algorithmic_bytes_per_launch": head["min_hbm_bytes"], "avg_launch_us": ms * 1e3},
         "cpu_baseline": cpu,
         "copy_probe_gbs": copy_gbs,
+        "copy_probe_same_bytes_gbs": copy_same_gbs,
         "other_workloads": extras,
     }
     print(json.dumps(line), flush=True)

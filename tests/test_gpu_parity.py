@@ -216,6 +216,27 @@ def test_elementwise20_predicate_bit_exact():
     np.testing.assert_array_equal(out_u[2], ref[2])
 
 
+def test_ragged_rows_with_staged_vectors_and_bf16():
+    # LayerNorm chain on C not a multiple of the lane tiling (ragged vector indices), bf16 in/out:
+    # exercises the LDS-staged per-column vectors with clamped lanes
+    for rows, cols in ((300, 1000), (64, 520), (1000, 72)):
+        g = layernorm_gelu_graph(rows, cols)
+        x = RNG.standard_normal((rows, cols)).astype(np.float32)
+        ins = [f32_to_bf16_bits(x)] + [RNG.normal(m, s, (1, cols)).astype(np.float32) for m, s in ((1, .1), (0, .1), (0, .02))]
+        both_modes(g, ins, f"layernorm {rows}x{cols}")
+
+
+def test_unrolled_row_loop(monkeypatch):
+    # looping (column-reduction) kernels with two and three row tiles per trip
+    g, ins, name = workload(4, 5000)
+    ref = oracle.run(g, ins, THREADS)
+    for u in ("2", "3"):
+        monkeypatch.setenv("FS_DEBUG_UNROLL", u)
+        out = run_graph(g, ins, hint={"max_workgroups": 7})
+        check_all(g, out, ref, f"{name} unroll {u}")
+    monkeypatch.delenv("FS_DEBUG_UNROLL")
+
+
 # ------------------------------------------------------------------ determinism and schedule invariance
 def test_run_to_run_bit_identical():
     for cfg, rows in ((4, 70001), (1, 5000), (5, None)):
