@@ -233,6 +233,7 @@ struct Emitter {
     os << "  (void)lir; (void)rg; (void)R; (void)C; (void)G; (void)CT;\n";
     if (xwave) os << "  __shared__ float lds_rr[2 * G * " << WPR << " * " << KB << "];\n  int parity = 0;\n";
     if (K > 0) os << "  __shared__ float lds_col[(L < 64 ? WG / 64 : G) * C];\n  __shared__ fs_u32 lds_flag;\n";
+    if (s.tile_transpose) os << "  __shared__ float lds_tile[C * (G + 1)];\n";
     if (s.stage_rowv) {
       int n_rowv = 0;
       for (const ExtTensor& e : gp.ext_in) n_rowv += e.kind == KIND_ROWV;
@@ -388,7 +389,10 @@ struct Emitter {
       if (n.opcode == FS_TRANSPOSE) {
         const ExtTensor* e = find_out(m);
         const std::string arr = as_array(n.in[0], std::to_string(loc(m)));
-        if (e)
+        if (e && s.tile_transpose)
+          os << "    fs_store_tile_transposed<" << e->dtype << ", " << tmpl_row() << ", WG, C>(" << arr << ", lds_tile, a.p[" << e->arg
+             << "], R, row - rg, lir, rg);\n";
+        else if (e)
           os << "    fs_store_row_transposed<" << e->dtype << ", " << tmpl_row() << ">(" << arr << ", a.p[" << e->arg << "], R, row, lir, vbase, rok);\n";
         continue;
       }

@@ -125,11 +125,15 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   if (l_min > 1024 && !tileable) FS_FAIL(FS_ERR_UNSUPPORTED, "rows of %d columns are too long for one workgroup", C);
   if (tileable) l_min = std::min(l_min, 256);
   int L = rowred ? std::min(64, l_max) : std::min(256, l_max);
+  // a transposed root leaves as runs of G = WG/L consecutive elements: at least 16 rows per workgroup
+  bool has_transposed = false;
+  for (const ExtTensor& e : gp->ext_out) has_transposed |= e.transposed;
+  if (has_transposed && !rowred) L = std::min(L, std::max(l_min, 16));
   // looping (column-reduction) kernels want more bytes in flight per lane: 16 elements per lane
   if (colred) L = std::min(L, std::max(1, pow2_ceil((NV * V + 15) / 16)));
   L = std::max(L, l_min);
   // small problems: more lanes per row until the device has ~8 wavefronts per CU
-  while ((int64_t)R * L / 64 < 2048 && L < l_max) L *= 2;
+  while ((int64_t)R * L / 64 < 2048 && L < l_max && !(has_transposed && !rowred)) L *= 2;
   if (opt.has_hint && opt.hint.lanes_per_row > 0) {
     const int h = opt.hint.lanes_per_row;
     if ((h & (h - 1)) == 0 && h >= l_min && h <= 1024) L = h;
@@ -143,7 +147,7 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   int WG;
   const int64_t total_waves = std::max<int64_t>(1, (int64_t)R * CT * L / 64);
   if (colred) WG = std::max(512, L);
-  else if (total_waves > 1024) WG = std::max(256, L);
+  else if (total_waves > 1024 || has_transposed) WG = std::max(256, L);
   else WG = std::max(64, L);
   if (opt.has_hint && opt.hint.wg_threads > 0) {
     const int h = opt.hint.wg_threads;
@@ -185,6 +189,11 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   int n_rowv = 0;
   for (const ExtTensor& e : gp->ext_in) n_rowv += e.kind == KIND_ROWV;
   s.stage_rowv = false;
+  s.tile_transpose = false;
+  if (has_transposed && CT == 1 && s.G >= 4 && lds + C * (s.G + 1) * 4 <= opt.lds_budget) {
+    s.tile_transpose = true;
+    lds += C * (s.G + 1) * 4;
+  }
   const int slot_bytes = s.NVL * s.L * V * 4;
   if (n_rowv > 0 && CT == 1 && s.grid >= s.n_iters && s.G >= 4 && R > 1 && lds + n_rowv * slot_bytes <= opt.lds_budget) {
     s.stage_rowv = true;

@@ -87,6 +87,7 @@ struct Schedule {
   int lds_bytes = 0;
   int fan_in = 32;  // column-reduction tree fan-in
   bool stage_rowv = false;  // [1,C] inputs are staged once per workgroup in LDS
+  bool tile_transpose = false;  // transposed roots leave through a padded LDS tile
 };
 
 struct GroupPlan {

@@ -297,3 +297,27 @@ def test_run_argument_errors():
     r.launch()  # still usable afterwards
     check_all(g, r.results(), oracle.run(g, ins, THREADS), "after argument errors")
     plan.destroy()
+
+
+def test_transposes_through_lds_tile_and_direct():
+    # tile path (several shapes, ragged rows/cols, bf16 and u8 payloads) and the direct path (forced by a tiny LDS budget)
+    for rows, cols, dt in ((512, 256, "f32"), (130, 72, "f32"), (1000, 36, "f32"), (77, 200, "bf16"), (64, 4100, "f32"), (300, 1, "f32"), (1, 300, "f32")):
+        g = Graph()
+        x = g.input(rows, cols, dt)
+        y = g.unary("neg", x)
+        t = g.transpose(y)
+        g.set_outputs([t, y])
+        v = RNG.standard_normal((rows, cols)).astype(np.float32)
+        ins = [f32_to_bf16_bits(v) if dt == "bf16" else v]
+        for budget in (0, 64):
+            ref = oracle.run(g, ins, THREADS)
+            out = run_graph(g, ins, lds_budget_bytes=budget)
+            check_all(g, out, ref, f"transpose {rows}x{cols} {dt} budget {budget}")
+            np.testing.assert_array_equal(out[0], out[1].T)
+    # a predicate tensor, transposed
+    g = Graph()
+    a, b = g.input(90, 40), g.input(90, 40)
+    g.set_outputs([g.transpose(g.cmp("gt", a, b))])
+    ins = [RNG.standard_normal((90, 40)).astype(np.float32) for _ in range(2)]
+    out = run_graph(g, ins)
+    np.testing.assert_array_equal(out[0], (ins[0] > ins[1]).astype(np.uint8).T)
