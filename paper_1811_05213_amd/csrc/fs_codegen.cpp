@@ -57,10 +57,23 @@ struct Emitter {
     return buf;
   }
 
-  int source_of(int o) const {  // the tensor behind an operand, looking through a broadcast
-    const fs_node& n = g.nodes[o];
-    return (n.opcode == FS_BCAST_ROWVEC || n.opcode == FS_BCAST_COLVEC) ? n.in[0] : o;
+  // the tensor behind an operand: looks through a broadcast, and through transposes that are
+  // members of the group (they only flip the orientation flag; the registers are the producer's)
+  int source_of(int o) const {
+    const fs_node* n = &g.nodes[o];
+    if (n->opcode == FS_BCAST_ROWVEC || n->opcode == FS_BCAST_COLVEC) {
+      o = n->in[0];
+      n = &g.nodes[o];
+    }
+    while (n->opcode == FS_TRANSPOSE && in_set[o] && in_set[n->in[0]]) {
+      o = n->in[0];
+      n = &g.nodes[o];
+    }
+    return o;
   }
+  // a member transpose of an in-group value has no registers of its own
+  bool is_alias(int m) const { return g.nodes[m].opcode == FS_TRANSPOSE && in_set[g.nodes[m].in[0]]; }
+  bool is_col_reduce(int m) const { return std::find(gp.col_reduces.begin(), gp.col_reduces.end(), m) != gp.col_reduces.end(); }
 
   const ExtTensor* find_out(int node) const {
     for (const ExtTensor& e : gp.ext_out)
@@ -147,6 +160,7 @@ struct Emitter {
 
   // an array holding operand `o` as a full slice (needed by max/min reductions / transposed stores)
   std::string as_array(int o, const std::string& tag) {
+    o = source_of(o) == o || !op_is_free(g.nodes[o].opcode) ? source_of(o) : o;
     const fs_node& n = g.nodes[o];
     if ((!op_is_free(n.opcode) || n.opcode == FS_INPUT) && !folded[o]) {
       const Kind k = gp.kind.at(o);
@@ -159,8 +173,18 @@ struct Emitter {
   }
 
   void emit_store(const ExtTensor& e, const std::string& indent) {
-    const std::string nm = name(e.node, gp.kind.at(e.node));
-    if (e.transposed) return;  // emitted with the node
+    const int holder = source_of(e.node);  // an aliasing transpose stores its producer's registers
+    const std::string nm = name(holder, gp.kind.at(holder));
+    if (e.transposed) {
+      // the value leaves in the flipped orientation: through a padded LDS tile when the plan has one
+      if (gp.s.tile_transpose)
+        os << indent << "fs_store_tile_transposed<" << e.dtype << ", " << tmpl_row() << ", WG, C>(" << nm << ", lds_tile, a.p[" << e.arg
+           << "], R, row - rg, lir, rg);\n";
+      else
+        os << indent << "fs_store_row_transposed<" << e.dtype << ", " << tmpl_row() << ">(" << nm << ", a.p[" << e.arg
+           << "], R, row, lir, vbase, rok);\n";
+      return;
+    }
     if (e.kind == KIND_FULL)
       os << indent << "fs_store_row<" << e.dtype << ", " << tmpl_row() << ", " << (e.streaming ? "true" : "false") << ">(" << nm << ", a.p["
          << e.arg << "], row0, lir, vbase, rok);\n";
@@ -198,7 +222,7 @@ struct Emitter {
     const Schedule& s = gp.s;
     for (int m : gp.members) in_set[m] = 1;
     count_uses();
-    const int R = gp.R, C = gp.C;
+    const int C = gp.C;
     const int NP = (int)(gp.ext_in.size() + gp.ext_out.size());
     const int K = (int)gp.col_reduces.size();
     const int WPR = s.L > 64 ? s.L / 64 : 1;
@@ -374,7 +398,7 @@ struct Emitter {
         continue;
       }
       ++i;
-      if (n.opcode == FS_REDUCE_COL && R > 1) {
+      if (is_col_reduce(m)) {
         const std::string ca = "ca" + std::to_string(loc(m));
         if (folded[n.in[0]]) {
           const fs_node& mn = g.nodes[n.in[0]];
@@ -387,13 +411,12 @@ struct Emitter {
         continue;
       }
       if (n.opcode == FS_TRANSPOSE) {
-        const ExtTensor* e = find_out(m);
-        const std::string arr = as_array(n.in[0], std::to_string(loc(m)));
-        if (e && s.tile_transpose)
-          os << "    fs_store_tile_transposed<" << e->dtype << ", " << tmpl_row() << ", WG, C>(" << arr << ", lds_tile, a.p[" << e->arg
-             << "], R, row - rg, lir, rg);\n";
-        else if (e)
-          os << "    fs_store_row_transposed<" << e->dtype << ", " << tmpl_row() << ">(" << arr << ", a.p[" << e->arg << "], R, row, lir, vbase, rok);\n";
+        // no arithmetic: an in-group operand is aliased; an operand from memory is copied (it was loaded as it lies)
+        if (!is_alias(m)) {
+          os << "    float " << name(m, KIND_FULL) << "[E];\n    _Pragma(\"unroll\") for (int e = 0; e < E; ++e) " << name(m, KIND_FULL)
+             << "[e] = " << ref(n.in[0]) << ";\n";
+        }
+        if (const ExtTensor* e = find_out(m)) emit_store(*e, "    ");
         continue;
       }
       const Kind k = gp.kind.at(m);

@@ -36,20 +36,20 @@ struct Analyser {
     if (rows == 1 && cols == C) return KIND_ROWV;
     return KIND_NONE;
   }
-  Kind classify(const fs_node& n) const { return classify(n.rows, n.cols); }
+  // t: the tensor lives in the transposed orientation of the work space (its [r,c] is the work
+  // space's [c,r]).  A [C,1] tensor of that orientation is one value per work-space column and has
+  // the memory layout of a [1,C] tensor, so vectors need no data movement at all.
+  Kind classify(const fs_node& n, bool t) const { return t ? classify(n.cols, n.rows) : classify(n.rows, n.cols); }
 
-  // A member whose value only exists after the grid-wide fold / is only stored transposed.
-  bool is_deferred(int id) const {
-    const fs_node& n = g.nodes[id];
-    return (n.opcode == FS_REDUCE_COL && R > 1) || n.opcode == FS_TRANSPOSE;
-  }
-  // A row reduction that needs lanes to exchange values (C == 1 degenerates to a copy).
-  bool is_cross_lane_reduce(int id) const { return g.nodes[id].opcode == FS_REDUCE_ROW && C > 1; }
-
-  // What a consumer expecting kind `want` sees when it reads operand node `o`.
-  bool resolve(int o, Kind want, Resolved* r) const {
+  int source_of(int o) const {
     const fs_node& n = g.nodes[o];
-    if (classify(n) != want) return false;
+    return (n.opcode == FS_BCAST_ROWVEC || n.opcode == FS_BCAST_COLVEC) ? n.in[0] : o;
+  }
+
+  // What a consumer working in orientation t and expecting kind `want` sees when it reads operand `o`.
+  bool resolve(int o, Kind want, bool t, Resolved* r) const {
+    const fs_node& n = g.nodes[o];
+    if (classify(n, t) != want) return false;
     if (n.opcode == FS_CONST) {
       r->literal = true;
       return true;
@@ -61,11 +61,11 @@ struct Analyser {
         r->literal = true;
         return true;
       }
-      const Kind kx = classify(xn);
+      const Kind kx = classify(xn, t);
       if (kx == KIND_NONE) return false;
       // a broadcast either widens a vector to the full work space or is the identity
-      const bool ok = kx == want || (want == KIND_FULL && kx == (n.opcode == FS_BCAST_ROWVEC ? KIND_ROWV : KIND_COLV));
-      if (!ok) return false;
+      const Kind vec = ((n.opcode == FS_BCAST_ROWVEC) != t) ? KIND_ROWV : KIND_COLV;
+      if (!(kx == want || (want == KIND_FULL && kx == vec))) return false;
       r->node = x;
       r->kind = kx;
       return true;
@@ -230,48 +230,75 @@ fs_status analyse_group(const Graph& g, const std::vector<int>& members, const s
   Analyser a(g, gp);
   for (int m : gp.members) a.in_set[m] = 1;
 
-  // work space: the largest extents seen (a transposed root contributes its operand's shape)
+  // Orientation of every member.  A transpose inside a group moves no data: it flips the flag,
+  // and everything downstream is computed in the producer's register layout (the paper inlines
+  // such shape modulation by thread composition, Section 4.3).  Only a value that LEAVES the
+  // kernel in the flipped orientation is stored transposed.
+  std::map<int, bool>& tf = gp.tflag;
+  for (int m : gp.members) {
+    const fs_node& n = g.nodes[m];
+    bool t = n.opcode == FS_TRANSPOSE;  // operands outside the group are read as they lie in memory
+    for (int k = 0; k < n.num_in; ++k) {
+      const int src = a.source_of(n.in[k]);
+      if (a.in_set[src]) {
+        t = (n.opcode == FS_TRANSPOSE) ? !tf[src] : tf[src];
+        break;
+      }
+    }
+    tf[m] = t;
+  }
+  // work space: the largest extents seen, every shape taken in its orientation
   int R = 1, C = 1;
   for (int m : gp.members) {
     const fs_node& n = g.nodes[m];
-    if (n.opcode != FS_TRANSPOSE) R = std::max(R, n.rows), C = std::max(C, n.cols);
+    const bool t = tf[m], t_op = n.opcode == FS_TRANSPOSE ? !t : t;
+    R = std::max(R, t ? n.cols : n.rows), C = std::max(C, t ? n.rows : n.cols);
     for (int k = 0; k < n.num_in; ++k) {
       const fs_node& o = g.nodes[n.in[k]];
-      R = std::max(R, o.rows), C = std::max(C, o.cols);
+      R = std::max(R, t_op ? o.cols : o.rows), C = std::max(C, t_op ? o.rows : o.cols);
     }
   }
   a.R = gp.R = R;
   a.C = gp.C = C;
 
+  auto is_reduce = [&](int id) { return g.nodes[id].opcode == FS_REDUCE_ROW || g.nodes[id].opcode == FS_REDUCE_COL; };
+  // reductions by their direction in the work space (a row reduction of a flipped tensor runs down the columns)
+  auto reduces_rows = [&](int id) { return is_reduce(id) && gp.kind[id] == KIND_COLV && C > 1; };   // lanes exchange values
+  auto reduces_cols = [&](int id) { return is_reduce(id) && gp.kind[id] == KIND_ROWV && R > 1; };   // finished by the grid fold
+
   for (int m : gp.members) {
     const fs_node& n = g.nodes[m];
-    Kind result_kind = a.classify(n);
+    const bool t = tf[m], t_op = n.opcode == FS_TRANSPOSE ? !t : t;
+    const Kind result_kind = a.classify(n, t);
     Kind operand_kind = result_kind;
-    if (n.opcode == FS_REDUCE_ROW || n.opcode == FS_REDUCE_COL || n.opcode == FS_TRANSPOSE) {
-      operand_kind = KIND_FULL;
-      if (n.opcode == FS_TRANSPOSE) result_kind = KIND_FULL;  // lives in the operand's layout, stored transposed
-    }
-    if (result_kind == KIND_NONE)
+    if (is_reduce(m) || n.opcode == FS_TRANSPOSE) operand_kind = KIND_FULL;
+    if (result_kind == KIND_NONE || (n.opcode == FS_TRANSPOSE && result_kind != KIND_FULL))
       FS_FAIL(FS_ERR_UNSUPPORTED, "node %d [%d,%d] does not fit the group's work space [%d,%d]", m, n.rows, n.cols, R, C);
     gp.kind[m] = result_kind;
-    int lvl = result_kind == KIND_ROWV && !a.is_deferred(m) ? -1 : 0;
+    const bool deferred = reduces_cols(m);
+    int lvl = result_kind == KIND_ROWV && !deferred ? -1 : 0;
     for (int k = 0; k < n.num_in; ++k) {
       Resolved r;
-      if (!a.resolve(n.in[k], operand_kind, &r))
+      if (!a.resolve(n.in[k], operand_kind, t_op, &r))
         FS_FAIL(FS_ERR_UNSUPPORTED, "node %d: operand %d does not fit the group's work space [%d,%d]", m, n.in[k], R, C);
       if (r.literal) continue;
       if (a.in_set[r.node]) {
-        if (a.is_deferred(r.node))
+        if (tf[r.node] != t_op) FS_FAIL(FS_ERR_UNSUPPORTED, "node %d mixes orientations", m);
+        if (reduces_cols(r.node))
           FS_FAIL(FS_ERR_UNSUPPORTED, "node %d consumes node %d, whose value only exists after the whole grid has run", m, r.node);
-        lvl = std::max(lvl, gp.level[r.node] + (a.is_cross_lane_reduce(r.node) ? 1 : 0));
+        lvl = std::max(lvl, gp.level[r.node] + (reduces_rows(r.node) ? 1 : 0));
       } else {
+        // tensors from memory: a full tensor can only be read in the orientation it is stored in
+        if (r.kind == KIND_FULL && t_op) FS_FAIL(FS_ERR_UNSUPPORTED, "node %d would need a transposing load of node %d", m, r.node);
+        for (const ExtTensor& e : gp.ext_in)
+          if (e.node == r.node && e.kind != r.kind) FS_FAIL(FS_ERR_UNSUPPORTED, "node %d is read in two orientations", r.node);
         add_ext_in(gp, r.node, r.kind, g.nodes[r.node].dtype);
         gp.kind[r.node] = r.kind;
       }
     }
     gp.level[m] = lvl;
-    if (a.is_cross_lane_reduce(m)) gp.row_reduces.push_back(m);
-    if (n.opcode == FS_REDUCE_COL && R > 1) gp.col_reduces.push_back(m);
+    if (reduces_rows(m)) gp.row_reduces.push_back(m);
+    if (reduces_cols(m)) gp.col_reduces.push_back(m);
 
     // does the value leave the kernel?
     bool leaves = g.output_index[m] >= 0;
@@ -286,10 +313,13 @@ fs_status analyse_group(const Graph& g, const std::vector<int>& members, const s
     if (leaves) {
       ExtTensor e;
       e.node = m;
-      e.kind = n.opcode == FS_REDUCE_COL && R > 1 ? KIND_ROWV : result_kind;
+      e.kind = result_kind;
       e.dtype = n.dtype;
-      e.transposed = n.opcode == FS_TRANSPOSE;
-      e.deferred = n.opcode == FS_REDUCE_COL && R > 1;
+      e.transposed = t && result_kind == KIND_FULL && R > 1 && C > 1;
+      e.deferred = deferred;
+      if (t && result_kind == KIND_FULL && !e.transposed && (R > 1 || C > 1)) {
+        // a flipped vector-shaped work space ([R,1] <-> [1,R]) has the same memory layout: plain store
+      }
       gp.ext_out.push_back(e);
     }
   }
@@ -412,7 +442,13 @@ struct Former {
       for (size_t a = 0; a < members.size() && !changed; ++a) {
         if (!valid[a]) continue;
         for (size_t b = a + 1; b < members.size() && !changed; ++b) {
-          if (!valid[b] || plan[a].R != plan[b].R || plan[a].C != plan[b].C) continue;
+          if (!valid[b]) continue;
+          // work spaces must nest: equal, or one of them is a vector ([R,1] / [1,C]) of the other
+          auto fits = [](int x, int y) { return x == y || x == 1 || y == 1; };
+          // ... or do so after a flip (a transpose inside the merged group reorients one side)
+          const bool straight = fits(plan[a].R, plan[b].R) && fits(plan[a].C, plan[b].C);
+          const bool flipped = fits(plan[a].R, plan[b].C) && fits(plan[a].C, plan[b].R);
+          if (!straight && !flipped) continue;
           if (members[a].size() + members[b].size() > 96) continue;
           // profitable?
           bool share_full = false;

@@ -95,6 +95,7 @@ struct GroupPlan {
   int R = 0, C = 0;          // work space
   std::map<int, Kind> kind;  // members and external tensors -> kind
   std::map<int, int> level;  // members -> stage (number of row reductions upstream)
+  std::map<int, bool> tflag; // members -> lives in the transposed orientation of the work space
   std::vector<ExtTensor> ext_in, ext_out;
   std::vector<int> row_reduces;  // REDUCE_ROW members that need a cross-lane exchange
   std::vector<int> col_reduces;  // REDUCE_COL members finished by the grid-wide fold

@@ -321,3 +321,28 @@ def test_transposes_through_lds_tile_and_direct():
     ins = [RNG.standard_normal((90, 40)).astype(np.float32) for _ in range(2)]
     out = run_graph(g, ins)
     np.testing.assert_array_equal(out[0], (ins[0] > ins[1]).astype(np.uint8).T)
+
+
+def test_transposes_inside_a_group():
+    """A transpose between fused ops moves no data: consumers run in the producer's layout."""
+    for rows, cols in ((130, 72), (64, 64), (512, 256), (33, 1000)):
+        g = Graph()
+        x = g.input(rows, cols)
+        kv = g.input(cols, 1)            # per-row vector of the transposed space
+        rv = g.input(1, rows)            # per-column vector of the transposed space
+        y = g.unary("tanh", x)
+        t = g.transpose(y)               # [cols, rows]
+        u = g.binary("mul", t, g.bcast_colvec(kv, rows))
+        w = g.binary("add", u, g.bcast_rowvec(rv, cols))
+        rsum = g.reduce_row("sum", w)    # [cols,1]: runs down the work space's columns (grid fold)
+        csum = g.reduce_col("max", w)    # [1,rows]: a row reduction of the work space
+        z = g.binary("sub", w, g.bcast_rowvec(csum, cols))
+        back = g.transpose(z)            # [rows, cols] again: plain store
+        g.set_outputs([w, rsum, csum, z, back])
+        ins = [RNG.standard_normal((rows, cols)).astype(np.float32), RNG.standard_normal((cols, 1)).astype(np.float32),
+               RNG.standard_normal((1, rows)).astype(np.float32)]
+        p = fs.Plan(g)
+        assert p.stats()["num_groups"] == 1, "one stitched kernel despite two transposes"
+        p.destroy()
+        ref, out_s, _ = both_modes(g, ins, f"in-group transposes {rows}x{cols}")
+        np.testing.assert_array_equal(out_s[4], out_s[3].T)
