@@ -146,7 +146,15 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
 
   int WG;
   const int64_t total_waves = std::max<int64_t>(1, (int64_t)R * CT * L / 64);
-  if (colred) WG = std::max(512, L);
+  if (colred) {
+    // large workgroups (few partials, many rows per trip) as long as every CU still gets a workgroup
+    WG = std::max(64, L);
+    for (int w = 512; w >= 128; w /= 2)
+      if (w >= L && (int64_t)R * L / w >= 256) {
+        WG = w;
+        break;
+      }
+  }
   else if (total_waves > 1024 || has_transposed) WG = std::max(256, L);
   else WG = std::max(64, L);
   if (opt.has_hint && opt.hint.wg_threads > 0) {
@@ -360,6 +368,15 @@ fs_status analyse_group(const Graph& g, const std::vector<int>& members, const s
 // -------------------------------------------------------------------------------------------
 namespace {
 
+// Performance feedback to the fusion decision (the role of the schedule planner's feedback edge,
+// Section 2.2): a column reduction finished inside a kernel costs a ticketed grid-wide fold, a few
+// microseconds of latency.  That is hidden behind the streaming of a large group, but for a
+// launch-bound group it is dearer than the launch it saves, so small groups do not take one in.
+bool worth_fusing(const GroupPlan& merged) {
+  constexpr uint64_t kFoldWorthBytes = 16ull << 20;
+  return merged.col_reduces.empty() || merged.members.size() == 1 || merged.s.grid == 1 || merged.min_hbm_bytes >= kFoldWorthBytes;
+}
+
 struct Former {
   const Graph& g;
   const PlanOptions& opt;
@@ -468,6 +485,7 @@ struct Former {
           std::vector<int> merged = members[a];
           merged.insert(merged.end(), members[b].begin(), members[b].end());
           if (analyse_group(g, merged, group_of, (int)a, opt, &merged_plan) != FS_OK) continue;
+          if (!worth_fusing(merged_plan)) continue;
           for (int m : members[b]) group_of[m] = (int)a;
           members[a] = merged;
           members[b].clear();
@@ -571,6 +589,7 @@ fs_status form_groups(const Graph& g, const fs_graph_desc* desc, const PlanOptio
         merged.push_back(id);
         if ((int)merged.size() > 96) continue;
         if (analyse_group(g, merged, f.group_of, grp, opt, &scratch) != FS_OK) continue;
+        if (!worth_fusing(scratch)) continue;
         joined = grp;
         break;
       }

@@ -341,8 +341,12 @@ def test_transposes_inside_a_group():
         g.set_outputs([w, rsum, csum, z, back])
         ins = [RNG.standard_normal((rows, cols)).astype(np.float32), RNG.standard_normal((cols, 1)).astype(np.float32),
                RNG.standard_normal((1, rows)).astype(np.float32)]
-        p = fs.Plan(g)
-        assert p.stats()["num_groups"] == 1, "one stitched kernel despite two transposes"
+        one = [0] * len(g.nodes)      # the caller's fusion plan: everything in one kernel
+        p = fs.Plan(g, group_of_node=one)
+        assert p.stats()["num_groups"] == 1 and p.group_info(0)["num_col_reduces"] == 1
         p.destroy()
-        ref, out_s, _ = both_modes(g, ins, f"in-group transposes {rows}x{cols}")
-        np.testing.assert_array_equal(out_s[4], out_s[3].T)
+        ref = oracle.run(g, ins, THREADS)
+        out = run_graph(g, ins, group_of_node=one)
+        check_all(g, out, ref, f"in-group transposes {rows}x{cols}, one kernel")
+        np.testing.assert_array_equal(out[4], out[3].T)
+        both_modes(g, ins, f"in-group transposes {rows}x{cols}")   # the library's own grouping, and per-op
