@@ -20,6 +20,7 @@
 //     rounds).
 #include <algorithm>
 #include <cstring>
+#include <set>
 #include <sstream>
 
 #include "fs_internal.h"
@@ -218,6 +219,140 @@ struct Emitter {
     }
   }
 
+  // ---- rows walked in column chunks (Schedule::chunked) ----------------------------------------
+  // [R,C] and [1,C] members (and tensors from memory) that `targets` depend on without crossing a
+  // row reduction: what one pass over the row has to load and recompute.
+  void needed_for(const std::vector<int>& targets, std::set<int>* mem, std::set<int>* ext) {
+    std::vector<int> stack(targets);
+    while (!stack.empty()) {
+      const int id = stack.back();
+      stack.pop_back();
+      const fs_node& n = g.nodes[id];
+      for (int k = 0; k < n.num_in; ++k) {
+        if (g.nodes[n.in[k]].opcode == FS_CONST) continue;
+        const int src = source_of(n.in[k]);
+        if (g.nodes[src].opcode == FS_CONST) continue;
+        const Kind kd = gp.kind.at(src);
+        if (kd == KIND_COLV) continue;  // one value per row: exists before the pass starts
+        if (!in_set[src]) ext->insert(src);
+        else if (mem->insert(src).second) stack.push_back(src);
+      }
+    }
+  }
+
+  void emit_exchange(const std::vector<int>& batch, bool xwave, int WPR, int KB, const std::string& ind) {
+    for (int b : batch)
+      os << ind << "q" << loc(b) << " = fs_segment_allreduce<" << g.nodes[b].attr_i << ", (L < 64 ? L : 64)>(q" << loc(b) << ");\n";
+    if (xwave) {
+      os << ind << "{\n" << ind << "  const fs_xwave<" << KB << ", " << WPR << "> xw{lds_rr + (parity * G + rg) * " << WPR * KB
+         << ", lir >> 6, (tid & 63) == 0};\n";
+      for (size_t k = 0; k < batch.size(); ++k) os << ind << "  xw.put(" << k << ", q" << loc(batch[k]) << ");\n";
+      os << ind << "  fs_lds_barrier();\n";
+      for (size_t k = 0; k < batch.size(); ++k)
+        os << ind << "  q" << loc(batch[k]) << " = xw.get<" << g.nodes[batch[k]].attr_i << ">(" << k << ");\n";
+      os << ind << "  parity ^= 1;\n" << ind << "}\n";
+    }
+    for (int b : batch) {
+      const fs_node& bn = g.nodes[b];
+      const std::string q = "q" + std::to_string(loc(b));
+      os << ind << "const float " << name(b, KIND_COLV) << " = " << rounded(b, bn.attr_i == FS_RED_MEAN ? q + " / (float)C" : q) << ";\n";
+      if (const ExtTensor* e = find_out(b)) emit_store(*e, ind);
+    }
+  }
+
+  // One pass over the row: loads, the members of `mem` in id order, then `tail` per chunk.
+  // Passes alternate their direction: a pass starts with the chunks its predecessor touched
+  // last, the ones most likely still in the L2.
+  int n_passes = 0;
+  template <class Tail>
+  void emit_pass(const std::set<int>& mem, const std::set<int>& ext, bool store_outputs, Tail tail) {
+    if (n_passes++ % 2 == 0) os << "    for (int ch = 0; ch < CT; ++ch) {\n";
+    else os << "    for (int ch = CT - 1; ch >= 0; --ch) {\n";
+    os << "      const int vbase = ch * (NVL * L);\n";
+    for (const ExtTensor& e : gp.ext_in) {
+      if (!ext.count(e.node)) continue;
+      os << "      float " << name(e.node, e.kind) << "[E];\n";
+      if (e.kind == KIND_FULL)
+        os << "      fs_load_row<" << e.dtype << ", " << tmpl_row() << ", false>(" << name(e.node, e.kind) << ", a.p[" << e.arg
+           << "], row0, lir, vbase);\n";
+      else
+        os << "      fs_load_row<" << e.dtype << ", " << tmpl_row() << ">(" << name(e.node, e.kind) << ", a.p[" << e.arg << "], 0, lir, vbase);\n";
+    }
+    for (int m : gp.members) {
+      if (!mem.count(m) || folded[m]) continue;
+      const fs_node& n = g.nodes[m];
+      const Kind k = gp.kind.at(m);
+      if (!is_alias(m))
+        os << "      float " << name(m, k) << "[E];\n      _Pragma(\"unroll\") for (int e = 0; e < E; ++e) " << name(m, k) << "[e] = "
+           << (n.opcode == FS_TRANSPOSE ? ref(n.in[0]) : rounded(m, expr(m))) << ";\n";
+      if (!store_outputs) continue;
+      if (const ExtTensor* e = find_out(m)) {
+        if (k == KIND_ROWV)
+          os << "      if (row == 0) fs_store_row<" << e->dtype << ", " << tmpl_row() << ">(" << name(source_of(m), k) << ", a.p[" << e->arg
+             << "], 0, lir, vbase, true);\n";
+        else
+          emit_store(*e, "      ");
+      }
+    }
+    tail();
+    os << "    }\n";
+  }
+
+  void run_chunked(bool xwave, int WPR, int KB) {
+    auto is_rr = [&](int m) { return std::find(gp.row_reduces.begin(), gp.row_reduces.end(), m) != gp.row_reduces.end(); };
+    int max_level = 0;
+    for (int m : gp.members) max_level = std::max(max_level, gp.level.at(m));
+    os << "  for (int it = (int)blockIdx.x; it < a.n_iters; it += (int)gridDim.x) {\n";
+    os << "    const long row = it, row0 = row * C;\n    constexpr bool rok = true;\n    constexpr int vbase = 0;  // (outside the passes)\n"
+       << "    (void)row0; (void)rok; (void)vbase;\n";
+    for (const ExtTensor& e : gp.ext_in)
+      if (e.kind == KIND_COLV) os << "    const float " << name(e.node, KIND_COLV) << " = fs_load1<" << e.dtype << ">(a.p[" << e.arg << "], row);\n";
+    const std::string col_ok = "(!RAGGED || (vbase + (e / V) * L + lir) < NV)";
+    for (int lvl = 0; lvl <= max_level + 1; ++lvl) {
+      // per-row values of this stage (they depend on earlier reductions only)
+      for (int m : gp.members) {
+        if (gp.level.at(m) != lvl || gp.kind.at(m) != KIND_COLV || is_rr(m) || folded[m]) continue;
+        os << "    const float " << name(m, KIND_COLV) << " = " << rounded(m, expr(m)) << ";\n";
+        if (const ExtTensor* e = find_out(m))
+          os << "    if (lir == 0) fs_store1<" << e->dtype << ">(a.p[" << e->arg << "], row, " << name(m, KIND_COLV) << ");\n";
+      }
+      std::vector<int> batch;
+      for (int m : gp.row_reduces)
+        if (gp.level.at(m) == lvl) batch.push_back(m);
+      if (batch.empty()) continue;
+      std::set<int> mem, ext;
+      needed_for(batch, &mem, &ext);
+      for (int b : batch) os << "    float q" << loc(b) << " = fs_red_identity<" << g.nodes[b].attr_i << ">();\n";
+      emit_pass(mem, ext, false, [&]() {
+        for (int b : batch) {
+          const fs_node& bn = g.nodes[b];
+          const std::string q = "q" + std::to_string(loc(b));
+          if (folded[bn.in[0]]) {
+            const fs_node& mn = g.nodes[bn.in[0]];
+            os << "      _Pragma(\"unroll\") for (int e = 0; e < E; ++e) " << q << " = " << col_ok << " ? __builtin_fmaf(" << ref(mn.in[0])
+               << ", " << ref(mn.in[1]) << ", " << q << ") : " << q << ";\n";
+          } else {
+            os << "      {\n";
+            const std::string arr = as_array(bn.in[0], std::to_string(loc(b)));
+            os << "      " << q << " = fs_red_op<" << bn.attr_i << ">(" << q << ", fs_lane_reduce<" << bn.attr_i << ", " << tmpl_row() << ">(" << arr
+               << ", lir, vbase));\n      }\n";
+          }
+        }
+      });
+      emit_exchange(batch, xwave, WPR, KB, "    ");
+    }
+    // last pass: everything that leaves the kernel as an [R,C] or [1,C] tensor
+    std::vector<int> roots;
+    for (const ExtTensor& e : gp.ext_out)
+      if (e.kind != KIND_COLV) roots.push_back(e.node);
+    if (!roots.empty()) {
+      std::set<int> mem(roots.begin(), roots.end()), ext;
+      needed_for(roots, &mem, &ext);
+      emit_pass(mem, ext, true, []() {});
+    }
+    os << "  }\n}\n";
+  }
+
   void run(const std::string& kname) {
     const Schedule& s = gp.s;
     for (int m : gp.members) in_set[m] = 1;
@@ -256,6 +391,10 @@ struct Emitter {
     os << "  const long R = a.R;\n";
     os << "  (void)lir; (void)rg; (void)R; (void)C; (void)G; (void)CT;\n";
     if (xwave) os << "  __shared__ float lds_rr[2 * G * " << WPR << " * " << KB << "];\n  int parity = 0;\n";
+    if (s.chunked) {
+      run_chunked(xwave, WPR, KB);
+      return;
+    }
     if (K > 0) os << "  __shared__ float lds_col[(L < 64 ? WG / 64 : G) * C];\n  __shared__ fs_u32 lds_flag;\n";
     if (s.tile_transpose) os << "  __shared__ float lds_tile[C * (G + 1)];\n";
     if (s.stage_rowv) {

@@ -314,11 +314,11 @@ template <int KIND> FS_DEV float fs_red_op(float a, float b) {
 
 // Serial reduction of the lane's own E elements (masked columns contribute the identity).
 template <int KIND, int V, int NVL, int L, int NV, bool RAGGED>
-FS_DEV float fs_lane_reduce(const float (&v)[NVL * V], int lir) {
+FS_DEV float fs_lane_reduce(const float (&v)[NVL * V], int lir, int vbase = 0) {
   float acc = fs_red_identity<KIND>();
 #pragma unroll
   for (int j = 0; j < NVL; ++j) {
-    const bool ok = !RAGGED || (j * L + lir) < NV;
+    const bool ok = !RAGGED || (vbase + j * L + lir) < NV;
 #pragma unroll
     for (int k = 0; k < V; ++k) acc = fs_red_op<KIND>(acc, ok ? v[j * V + k] : fs_red_identity<KIND>());
   }

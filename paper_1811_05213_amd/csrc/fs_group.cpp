@@ -122,25 +122,35 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   // Groups without reductions do not need a whole row in one workgroup: very long rows are cut
   // into column tiles, each handled like a row of its own.
   const bool tileable = !rowred && !colred;
-  if (l_min > 1024 && !tileable) FS_FAIL(FS_ERR_UNSUPPORTED, "rows of %d columns are too long for one workgroup", C);
-  if (tileable) l_min = std::min(l_min, 256);
-  int L = rowred ? std::min(64, l_max) : std::min(256, l_max);
-  // a transposed root leaves as runs of G = WG/L consecutive elements: at least 16 rows per workgroup
   bool has_transposed = false;
   for (const ExtTensor& e : gp->ext_out) has_transposed |= e.transposed;
+  // Row reductions over rows that do not fit the registers of one workgroup: the workgroup walks
+  // its row in column chunks, once per stage, recomputing what each stage needs.
+  const bool chunked = l_min > 1024 && rowred && !colred && !has_transposed;
+  if (l_min > 1024 && !tileable && !chunked)
+    FS_FAIL(FS_ERR_UNSUPPORTED, "rows of %d columns are too long for one workgroup in a group with %s", C,
+            colred ? "column reductions" : "transposed outputs");
+  if (tileable) l_min = std::min(l_min, 256);
+  if (chunked) l_min = 1024;  // (measured: the largest workgroup keeps the fewest rows in flight, so re-reads hit the caches more often)
+  int L = rowred ? std::min(64, l_max) : std::min(256, l_max);
+  // a transposed root leaves as runs of G = WG/L consecutive elements: at least 16 rows per workgroup
   if (has_transposed && !rowred) L = std::min(L, std::max(l_min, 16));
   // looping (column-reduction) kernels want more bytes in flight per lane: 16 elements per lane
   if (colred) L = std::min(L, std::max(1, pow2_ceil((NV * V + 15) / 16)));
   L = std::max(L, l_min);
   // small problems: more lanes per row until the device has ~8 wavefronts per CU
-  while ((int64_t)R * L / 64 < 2048 && L < l_max && !(has_transposed && !rowred)) L *= 2;
+  while ((int64_t)R * L / 64 < 2048 && L < l_max && !(has_transposed && !rowred) && !chunked) L *= 2;
   if (opt.has_hint && opt.hint.lanes_per_row > 0) {
     const int h = opt.hint.lanes_per_row;
-    if ((h & (h - 1)) == 0 && h >= l_min && h <= 1024) L = h;
+    if ((h & (h - 1)) == 0 && h >= (chunked ? 64 : l_min) && h <= 1024) L = h;
   }
   int NVL = (NV + L - 1) / L, CT = 1;
   if (NVL * V > ecap && tileable) {
     NVL = std::max(1, ecap / V);
+    CT = (NV + NVL * L - 1) / (NVL * L);
+  }
+  if (chunked) {
+    NVL = std::max(1, 16 / V);
     CT = (NV + NVL * L - 1) / (NVL * L);
   }
 
@@ -157,7 +167,8 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   }
   else if (total_waves > 1024 || has_transposed) WG = std::max(256, L);
   else WG = std::max(64, L);
-  if (opt.has_hint && opt.hint.wg_threads > 0) {
+  if (chunked) WG = L;  // one row per workgroup
+  if (opt.has_hint && opt.hint.wg_threads > 0 && !chunked) {
     const int h = opt.hint.wg_threads;
     if (h % 64 == 0 && h >= L && h <= 1024) WG = h;
   }
@@ -171,7 +182,8 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   s.WG = WG;
   s.G = WG / L;
   s.ragged = (int64_t)CT * NVL * L != NV;
-  s.n_iters = (int)(((int64_t)R * CT + s.G - 1) / s.G);
+  s.chunked = chunked;
+  s.n_iters = chunked ? R : (int)(((int64_t)R * CT + s.G - 1) / s.G);
   // Streaming groups launch one workgroup per row tile: the hardware hands tiles out in memory
   // order and a fresh wavefront issues its loads at once, which measures faster on this device
   // than persistent workgroups looping with a grid stride.  Column reductions keep a bounded
@@ -352,7 +364,10 @@ fs_status analyse_group(const Graph& g, const std::vector<int>& members, const s
   for (const ExtTensor& e : gp.ext_in) gp.min_hbm_bytes += (uint64_t)g.nodes[e.node].rows * g.nodes[e.node].cols * dtype_size(e.dtype);
   for (const ExtTensor& e : gp.ext_out) gp.min_hbm_bytes += (uint64_t)g.nodes[e.node].rows * g.nodes[e.node].cols * dtype_size(e.dtype);
 
-  return choose_schedule(g, opt, &gp);
+  const fs_status st = choose_schedule(g, opt, &gp);
+  if (st == FS_OK && gp.s.chunked)  // every stage reads the row again: keep it in the caches
+    for (ExtTensor& e : gp.ext_in) e.streaming = false;
+  return st;
 }
 
 // -------------------------------------------------------------------------------------------

@@ -272,5 +272,14 @@ def test_ragged_and_degenerate_shapes_plan():
         gi = p.group_info(0)
         assert gi["elems_per_lane"] * gi["lanes_per_row"] >= cols
         p.destroy()
-    # rows too long for one workgroup's registers are refused cleanly
-    assert _status(softmax_graph(2, 1 << 20)) == "FS_ERR_UNSUPPORTED"
+    # rows too long for one workgroup's registers are walked in chunks (one row per workgroup, recomputation per stage)
+    p = fs.Plan(softmax_graph(2, 1 << 20))
+    gi = p.group_info(0)
+    assert p.stats()["num_launches"] == 1 and gi["elems_per_lane"] * gi["lanes_per_row"] < (1 << 20) and gi["rows_per_iter"] == 1
+    src = p.group_source(0)
+    assert src.count("const int vbase = ch * (NVL * L);") == 3  # max pass, sum pass, output pass
+    p.destroy()
+    # ... but not together with a column reduction in the same kernel: refused cleanly
+    g = multi_reduce_graph(4, 1 << 17)
+    assert _status(g, group_of_node=[0 if n.op not in ("input", "const", "bcast_rowvec", "bcast_colvec") else -1 for n in g.nodes]) \
+        == "FS_ERR_UNSUPPORTED"

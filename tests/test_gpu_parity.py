@@ -134,6 +134,21 @@ def test_row_reduce_across_wavefronts():
         both_modes(g, [RNG.standard_normal((rows, cols)).astype(np.float32)], f"softmax {rows}x{cols}")
 
 
+def test_rows_longer_than_a_workgroup_holds():
+    # one workgroup per row walks it in column chunks, once per stage, recomputing what the stage needs
+    for rows, cols in [(3, 100001), (2, 1 << 18), (1100, 40000)]:
+        g = softmax_graph(rows, cols)
+        p = fs.Plan(g)
+        gi = p.group_info(0)
+        assert p.stats()["num_launches"] == 1 and gi["elems_per_lane"] * gi["lanes_per_row"] < cols
+        p.destroy()
+        both_modes(g, [RNG.standard_normal((rows, cols)).astype(np.float32)], f"softmax {rows}x{cols}")
+    for rows, cols in [(5, 65544), (7, 40001)]:
+        g = layernorm_gelu_graph(rows, cols)
+        ins = [f32_to_bf16_bits(RNG.standard_normal(s).astype(np.float32)) for s in ((rows, cols), (1, cols), (1, cols), (1, cols))]
+        both_modes(g, ins, f"layernorm+gelu {rows}x{cols}")
+
+
 def test_broadcasts_and_transpose():
     rows, cols = 130, 72
     g = Graph()
