@@ -111,6 +111,7 @@ def measure_workload(cfg, steps, warmup, with_unfused=True, rows=None):
             out["frac_of_peak"] = out["gbs"] / HBM_PEAK_GBS
             out["groups"] = [plan.group_info(i) for i in range(min(st["num_groups"], 4))]
             out["kernel"] = plan.group_kernel_name(0)
+            out["kernels"] = [plan.group_kernel_name(i) for i in range(st["num_groups"])]
         del runs
         plan.destroy()
         torch.cuda.empty_cache()
