@@ -157,7 +157,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
-    ap.add_argument("--workload", type=int, default=2, help="BASELINE.json config number (1-5) for the headline line")
+    ap.add_argument("--workload", type=int, default=2, help="BASELINE.json config number (1-5; 6-7 are extra backward-pass subgraphs) for the headline line")
     ap.add_argument("--no-extras", action="store_true", help="skip the other four workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     args = ap.parse_args()
@@ -180,10 +180,10 @@ def main():
     same = max(1 << 20, (head["min_hbm_bytes"] // 2) // 4096 * 4096)
     copy_same_gbs = time_copy_probe(same, reps=200 if same < (1 << 28) else 20)
     if not args.no_extras:
-        for cfg in (1, 2, 3, 4, 5):
+        for cfg in (1, 2, 3, 4, 5, 6, 7):  # 6, 7: backward-pass subgraphs (LayerNorm, softmax), not benchmark configurations
             if cfg == args.workload:
                 continue
-            steps = {1: 400, 2: 400, 3: 30, 4: 200, 5: 50}[cfg]
+            steps = {1: 400, 2: 400, 3: 30, 4: 200, 5: 50, 6: 100, 7: 100}[cfg]
             extras[f"cfg{cfg}"] = measure_workload(cfg, steps, max(4, steps // 10))
             log(f"cfg{cfg}", json.dumps(extras[f"cfg{cfg}"]))
         # the same stitched kernels on more rows: where the launch stops dominating (row sweep end points)

@@ -183,10 +183,19 @@ def test_vector_valued_members_and_constants():
 
 # ------------------------------------------------------------------ the five workloads
 @pytest.mark.parametrize("cfg,rows", [(1, 256), (1, 33), (1, 5000), (2, 512), (2, 77), (3, 256), (3, 1001), (4, 512), (4, 5000),
-                                      (4, 70001), (5, None), (5, 100)])
+                                      (4, 70001), (5, None), (5, 100), (6, 777), (6, 4096), (7, 1000)])
 def test_workloads_test_sizes(cfg, rows):
     g, ins, name = workload(cfg, rows)
     both_modes(g, ins, name)
+
+
+def test_backward_subgraphs_are_one_kernel():
+    # LayerNorm backward: four row reductions in three stages and two column reductions, one launch
+    for cfg in (6, 7):
+        g, _, _ = workload(cfg, 2048)
+        p = fs.Plan(g)
+        assert p.stats()["num_launches"] == 1
+        p.destroy()
 
 
 def test_layernorm_decomposed_gelu_variant():

@@ -276,6 +276,34 @@ def test_layernorm_pins():
     np.testing.assert_allclose(xn_s, xn_o, rtol=1e-4, atol=1e-5)
 
 
+def test_backward_graphs_vs_torch_autograd():
+    # the LayerNorm-backward and softmax-backward subgraphs against torch's fp64 autograd of the forward ops
+    from workloads import layernorm_grad_graph, softmax_grad_graph
+    R, C = 24, 96
+    x = RNG.standard_normal((R, C)).astype(np.float32) * 2 + 0.5
+    dy = RNG.standard_normal((R, C)).astype(np.float32)
+    gamma = RNG.normal(1, 0.1, (1, C)).astype(np.float32)
+    dx, dgamma, dbeta = run1(layernorm_grad_graph(R, C), [x, dy, gamma])
+    xt = torch.from_numpy(x).double().requires_grad_()
+    gt = torch.from_numpy(gamma[0]).double().requires_grad_()
+    bt = torch.zeros(C, dtype=torch.float64, requires_grad=True)
+    torch.nn.functional.layer_norm(xt, (C,), gt, bt, 1e-5).backward(torch.from_numpy(dy).double())
+    np.testing.assert_allclose(dx, xt.grad.numpy(), rtol=2e-5, atol=2e-6)
+    np.testing.assert_allclose(dgamma[0], gt.grad.numpy(), rtol=2e-5, atol=2e-5)
+    np.testing.assert_allclose(dbeta[0], bt.grad.numpy(), rtol=2e-5, atol=2e-5)
+    # dx is orthogonal to the constant vector and to xhat (the two projections the formula removes)
+    assert np.abs(dx.astype(np.float64).sum(1)).max() < 1e-4
+
+    z = RNG.standard_normal((R, C)).astype(np.float32)
+    zt = torch.from_numpy(z).double().requires_grad_()
+    yt = torch.softmax(zt, dim=1)
+    yt.backward(torch.from_numpy(dy).double())
+    y32 = yt.detach().float().numpy()
+    (dz,) = run1(softmax_grad_graph(R, C), [y32, dy])
+    np.testing.assert_allclose(dz, zt.grad.numpy(), rtol=1e-4, atol=1e-7)
+    assert np.abs(dz.astype(np.float64).sum(1)).max() < 1e-6  # softmax gradients sum to zero over a row
+
+
 def test_multi_reduce_pins():
     R, C = 64, 16
     g = multi_reduce_graph(R, C)

@@ -314,8 +314,58 @@ def random_dag_inputs(g: Graph, cfg: int = 5) -> List[np.ndarray]:
 
 
 # ---------------------------------------------------------------------------------------------
+# ---------------------------------------------------------------------------------------------
+# Backward-pass patterns (row reductions and column reductions in one subgraph).  Not among the
+# five configurations of the headline benchmark: a second family for the same stitcher.
+# cfg 6: LayerNorm backward: dx, dgamma, dbeta from x, dy, gamma
+# cfg 7: softmax backward: dx = y * (dy - rowsum(dy * y))
+# ---------------------------------------------------------------------------------------------
+def layernorm_grad_graph(rows: int = 16384, cols: int = 1024, eps: float = 1e-5) -> Graph:
+    g = Graph()
+    x = g.input(rows, cols, "f32", "x")
+    dy = g.input(rows, cols, "f32", "dy")
+    gamma = g.input(1, cols, "f32", "gamma")
+    mu = g.reduce_row("mean", x, name="mu")
+    xc = g.binary("sub", x, g.bcast_colvec(mu, cols), name="xc")
+    var = g.reduce_row("mean", g.binary("mul", xc, xc), name="var")
+    rstd = g.unary("rsqrt", g.binary("add", var, g.const(eps, rows, 1)), name="rstd")
+    xhat = g.binary("mul", xc, g.bcast_colvec(rstd, cols), name="xhat")
+    dbeta = g.reduce_col("sum", dy, name="dbeta")
+    dgamma = g.reduce_col("sum", g.binary("mul", dy, xhat), name="dgamma")
+    gy = g.binary("mul", dy, g.bcast_rowvec(gamma, rows), name="gy")
+    m1 = g.reduce_row("mean", gy, name="m1")
+    m2 = g.reduce_row("mean", g.binary("mul", gy, xhat), name="m2")
+    t = g.binary("sub", gy, g.bcast_colvec(m1, cols))
+    t = g.binary("sub", t, g.binary("mul", xhat, g.bcast_colvec(m2, cols)))
+    dx = g.binary("mul", t, g.bcast_colvec(rstd, cols), name="dx")
+    g.set_outputs([dx, dgamma, dbeta])
+    return g
+
+
+def layernorm_grad_inputs(rows: int = 16384, cols: int = 1024) -> List[np.ndarray]:
+    return [_draw(np.random.default_rng(_seed(6, 0)), "normal", rows, cols, 0.0, 1.0),
+            _draw(np.random.default_rng(_seed(6, 1)), "normal", rows, cols, 0.0, 1.0),
+            _draw(np.random.default_rng(_seed(6, 2)), "normal", 1, cols, 1.0, 0.1)]
+
+
+def softmax_grad_graph(rows: int = 16384, cols: int = 1024) -> Graph:
+    g = Graph()
+    y = g.input(rows, cols, "f32", "y")
+    dy = g.input(rows, cols, "f32", "dy")
+    s = g.reduce_row("sum", g.binary("mul", dy, y), name="s")
+    dx = g.binary("mul", y, g.binary("sub", dy, g.bcast_colvec(s, cols)), name="dx")
+    g.set_outputs([dx])
+    return g
+
+
+def softmax_grad_inputs(rows: int = 16384, cols: int = 1024) -> List[np.ndarray]:
+    # y: positive rows of mean 1/cols (the scale of a softmax output; exact normalisation is not needed here)
+    y = _draw(np.random.default_rng(_seed(7, 0)), "uniform", rows, cols, 0.0, 2.0 / cols)
+    return [y, _draw(np.random.default_rng(_seed(7, 1)), "normal", rows, cols, 0.0, 1.0)]
+
+
 def workload(cfg: int, rows: int | None = None) -> Tuple[Graph, List[np.ndarray], str]:
-    """(graph, inputs, name) of workload cfg in 1..5; `rows` shrinks cfg 1-4 to a test size."""
+    """(graph, inputs, name) of workload cfg in 1..7 (1-5: the benchmark's; 6-7: backward patterns); `rows` resizes it."""
     if cfg == 1:
         r = rows or 256
         return softmax_graph(r, 1024), softmax_inputs(r, 1024), f"softmax_f32_{r}x1024"
@@ -331,6 +381,12 @@ def workload(cfg: int, rows: int | None = None) -> Tuple[Graph, List[np.ndarray]
     if cfg == 5:
         g = random_dag_graph(rows=rows or 512)
         return g, random_dag_inputs(g), f"random_dag200_{rows or 512}xk"
+    if cfg == 6:
+        r = rows or 16384
+        return layernorm_grad_graph(r, 1024), layernorm_grad_inputs(r, 1024), f"layernorm_grad_f32_{r}x1024"
+    if cfg == 7:
+        r = rows or 16384
+        return softmax_grad_graph(r, 1024), softmax_grad_inputs(r, 1024), f"softmax_grad_f32_{r}x1024"
     raise ValueError(cfg)
 
 
