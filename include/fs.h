@@ -122,6 +122,8 @@ typedef struct {
 #define FS_MODE_UNFUSED 1u  /* one launch per compute node, every intermediate in HBM; the
                                comparison executor for launch count and HBM traffic
                                (the role of the per-op baseline in Section 6.3) */
+#define FS_MODE_NO_PERFLIB 2u /* flag, may be or-ed in: ignore the performance library and keep the
+                                 schedules of the analytic rules */
 
 /*
  * Optional schedule override, applied to every group it is legal for (0 = let the
@@ -226,6 +228,44 @@ fs_status fs_plan_group_source(const fs_plan* plan, int32_t group, const char** 
 
 /* Name of the kernel symbol of one group (for matching profiler output). */
 fs_status fs_plan_group_kernel_name(const fs_plan* plan, int32_t group, const char** out_name);
+
+/*
+ * Schedule tuning with the performance library (Sections 4.3 and 4.4).
+ *
+ * The library is a persistent key-value store of measured kernel times: key = one generated
+ * kernel (its structure and every schedule constant: lanes per row, elements per lane,
+ * workgroup size) under one launch (rows, loop trips, grid); value = microseconds.  It lives
+ * in the text file named by the environment variable FS_PERF_LIBRARY, else in perflib.tsv beside
+ * the shared library.  fs_plan_create consults it for every group unless the caller passes a
+ * schedule hint or FS_MODE_NO_PERFLIB: it enumerates the group's candidate schedules, looks
+ * each candidate's kernel up and keeps the fastest recorded one.
+ *
+ * fs_plan_tune is the measure-on-miss half: for every group of `plan`, in launch order, it
+ * builds each candidate schedule's kernel, and for every key the library does not hold yet it
+ * runs that kernel on the caller's buffers `reps` times (HIP events on `hip_stream`, the
+ * last-level cache flushed before each timed launch when the group moves more than 1 MiB),
+ * and inserts the median.  It does not change `plan`: create the plan again to use what was
+ * learned.  Unlike fs_plan_run it SYNCHRONISES and ALLOCATES (private scratch for the
+ * candidates' partials and a flush buffer, freed before it returns); the outputs and the
+ * workspace hold the results of a normal run afterwards.  inputs / outputs / workspace as for
+ * fs_plan_run.  reps <= 0 means 9.  report may be NULL.
+ */
+typedef struct {
+  int32_t groups;           /* groups visited */
+  int32_t candidates;       /* candidate kernels considered (the current schedules included) */
+  int32_t measured;         /* of those, measured now and inserted */
+  int32_t hits;             /* of those, already in the library */
+  int32_t improvable;       /* groups for which some candidate is recorded faster than the current schedule */
+  int32_t reserved;
+  double current_usec;      /* sum over groups of the recorded time of the plan's current schedules */
+  double best_usec;         /* sum over groups of the fastest recorded candidate */
+} fs_tune_report;
+
+/* The performance-library key of one group's kernel under its launch (owned by the plan). */
+fs_status fs_plan_group_perf_key(const fs_plan* plan, int32_t group, const char** out_key);
+
+fs_status fs_plan_tune(fs_plan* plan, const void* const* inputs, void* const* outputs, void* workspace,
+                       size_t workspace_bytes, void* hip_stream, int32_t reps, fs_tune_report* report);
 
 /*
  * fs_copy_probe: a plain streaming copy of `bytes` bytes (multiple of 16) from src

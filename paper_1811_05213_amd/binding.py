@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libfs.so")
 FS_ABI_VERSION = 1
 FS_MODE_STITCHED = 0
 FS_MODE_UNFUSED = 1
+FS_MODE_NO_PERFLIB = 2
 
 STATUS_NAMES = ["FS_OK", "FS_ERR_INVALID_ARG", "FS_ERR_BAD_GRAPH", "FS_ERR_SHAPE", "FS_ERR_DTYPE", "FS_ERR_UNSUPPORTED",
                 "FS_ERR_LDS_BUDGET", "FS_ERR_WORKSPACE", "FS_ERR_COMPILE", "FS_ERR_HIP", "FS_ERR_OOM"]
@@ -60,6 +61,14 @@ class fs_group_info(ctypes.Structure):
         return {n: getattr(self, n) for n, _ in self._fields_}
 
 
+class fs_tune_report(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("groups", "candidates", "measured", "hits", "improvable", "reserved")] + \
+               [("current_usec", ctypes.c_double), ("best_usec", ctypes.c_double)]
+
+    def as_dict(self):
+        return {n: getattr(self, n) for n, _ in self._fields_ if n != "reserved"}
+
+
 class FsError(RuntimeError):
     def __init__(self, status: int, message: str):
         super().__init__(f"{STATUS_NAMES[status] if 0 <= status < len(STATUS_NAMES) else status}: {message}")
@@ -88,11 +97,14 @@ def lib() -> ctypes.CDLL:
         L.fs_plan_node_groups.argtypes = [vp, i32p, ctypes.c_int32]
         L.fs_plan_group_source.argtypes = [vp, ctypes.c_int32, ctypes.POINTER(ctypes.c_char_p)]
         L.fs_plan_group_kernel_name.argtypes = [vp, ctypes.c_int32, ctypes.POINTER(ctypes.c_char_p)]
+        L.fs_plan_group_perf_key.argtypes = [vp, ctypes.c_int32, ctypes.POINTER(ctypes.c_char_p)]
         L.fs_copy_probe.argtypes = [vp, vp, ctypes.c_size_t, vp]
+        L.fs_plan_tune.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), vp, ctypes.c_size_t, vp, ctypes.c_int32,
+                                   ctypes.POINTER(fs_tune_report)]
         L.fs_last_error.restype = ctypes.c_char_p
         for name in ("fs_plan_create", "fs_plan_destroy", "fs_plan_workspace_bytes", "fs_plan_run",
                      "fs_plan_workspace_init", "fs_plan_stats", "fs_plan_group_info", "fs_plan_node_groups",
-                     "fs_plan_group_source", "fs_plan_group_kernel_name", "fs_copy_probe"):
+                     "fs_plan_group_source", "fs_plan_group_kernel_name", "fs_copy_probe", "fs_plan_tune", "fs_plan_group_perf_key"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -191,6 +203,11 @@ class Plan:
         _check(lib().fs_plan_group_kernel_name(self._h, group, ctypes.byref(s)))
         return s.value.decode()
 
+    def group_perf_key(self, group: int) -> str:
+        s = ctypes.c_char_p()
+        _check(lib().fs_plan_group_perf_key(self._h, group, ctypes.byref(s)))
+        return s.value.decode()
+
     def workspace_init(self, workspace_ptr: int, workspace_bytes: int, stream: int = 0) -> None:
         _check(lib().fs_plan_workspace_init(self._h, workspace_ptr, workspace_bytes, stream))
 
@@ -198,6 +215,13 @@ class Plan:
             stream: int = 0) -> None:
         ins, outs = self.pointer_tables(input_ptrs, output_ptrs)
         _check(lib().fs_plan_run(self._h, ins, outs, workspace_ptr, workspace_bytes, stream))
+
+    def tune(self, input_ptrs: Sequence[int], output_ptrs: Sequence[int], workspace_ptr: int, workspace_bytes: int,
+             stream: int = 0, reps: int = 0) -> dict:
+        ins, outs = self.pointer_tables(input_ptrs, output_ptrs)
+        rep = fs_tune_report()
+        _check(lib().fs_plan_tune(self._h, ins, outs, workspace_ptr, workspace_bytes, stream, reps, ctypes.byref(rep)))
+        return rep.as_dict()
 
     @staticmethod
     def pointer_tables(input_ptrs: Sequence[int], output_ptrs: Sequence[int]):

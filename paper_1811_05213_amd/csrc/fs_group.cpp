@@ -371,6 +371,62 @@ fs_status analyse_group(const Graph& g, const std::vector<int>& members, const s
 }
 
 // -------------------------------------------------------------------------------------------
+// Schedule tuning (Section 4.3): candidates and the library-driven choice.
+// -------------------------------------------------------------------------------------------
+std::vector<fs_sched_hint> candidate_hints(const GroupPlan& base) {
+  const Schedule& s = base.s;
+  std::vector<fs_sched_hint> out;
+  if (s.chunked) return out;  // one row per 1024-lane workgroup: nothing to vary
+  std::vector<int> Ls, WGs, caps;
+  for (int L : {s.L / 2, s.L, s.L * 2})
+    if (L >= 1 && L <= 1024) Ls.push_back(L);
+  for (int WG : {s.WG / 2, s.WG, s.WG * 2})
+    if (WG >= 64 && WG <= 1024) WGs.push_back(WG);
+  caps.push_back(0);
+  if (!base.col_reduces.empty() && s.grid > 1)  // every workgroup leaves a partial: the grid is a real trade-off
+    for (int c : {s.grid / 2, s.grid * 2})
+      if (c >= 1 && c <= 2048) caps.push_back(c);
+  for (int L : Ls)
+    for (int WG : WGs)
+      for (int cap : caps) {
+        if (WG < L) continue;
+        if (L == s.L && WG == s.WG && cap == 0) continue;  // the base schedule itself
+        out.push_back(fs_sched_hint{L, WG, cap, 0});
+      }
+  return out;
+}
+
+bool choose_from_library(const Graph& g, const std::vector<int>& members, const std::vector<int>& group_of, int self_group,
+                         const PlanOptions& opt, GroupPlan* gp) {
+  // a candidate has to beat the analytic schedule by more than the noise of the measurement
+  constexpr double kMargin = 0.97;
+  double best = 0.0;
+  const bool base_known = perflib_lookup(perf_key(*gp), &best);
+  best *= kMargin;
+  bool changed = false;
+  GroupPlan cand;
+  const std::vector<fs_sched_hint> hints = candidate_hints(*gp);
+  for (const fs_sched_hint& h : hints) {
+    PlanOptions o = opt;
+    o.hint = h;
+    o.has_hint = true;
+    if (analyse_group(g, members, group_of, self_group, o, &cand) != FS_OK) continue;
+    if (cand.s.L != h.lanes_per_row || cand.s.WG != h.wg_threads) continue;  // the hint was not legal for this group
+    if (generate_kernel(g, &cand, self_group) != FS_OK) continue;
+    double us = 0.0;
+    if (!perflib_lookup(perf_key(cand), &us)) continue;
+    // an unmeasured base schedule is not displaced: only compare within the library
+    if (!base_known) continue;
+    if (us < best) {
+      best = us;
+      *gp = cand;
+      changed = true;
+    }
+  }
+  return changed;
+}
+
+// -------------------------------------------------------------------------------------------
 // Group formation.
 //
 // Unfused mode: one group per compute node.  Caller-given plan: checked, not changed.

@@ -112,6 +112,7 @@ struct GroupPlan {
   uint64_t min_hbm_bytes = 0;
   // generated kernel
   std::string kernel_name, source;
+  std::string perf_key;  // filled on demand by fs_plan_group_perf_key
 };
 
 struct PlanOptions {
@@ -140,6 +141,20 @@ fs_status generate_kernel(const Graph& g, GroupPlan* gp, int group_index);
 fs_status compile_kernel(const std::string& source, const std::string& name, std::vector<char>* code);
 
 const char* device_header_source();  // text of fs_device.h, embedded at build time
+
+// ---- schedule tuning and the performance library (Sections 4.3, 4.4) ---------------------------
+// Schedules worth trying for a group besides the one the analytic rules picked (`base`): the
+// neighbourhood of the base schedule in lanes per row, workgroup size and grid.
+std::vector<fs_sched_hint> candidate_hints(const GroupPlan& base);
+// Library key of one kernel under one launch, lookups and inserts (persistent, see fs_perflib.cpp).
+std::string perf_key(const GroupPlan& gp);
+size_t perflib_size();
+bool perflib_lookup(const std::string& key, double* usec);
+bool perflib_insert(const std::string& key, double usec, const std::string& note);
+// Re-plans `members` under every candidate schedule, looks the kernels up in the library and
+// replaces *gp by the fastest recorded one.  Returns true when *gp changed.
+bool choose_from_library(const Graph& g, const std::vector<int>& members, const std::vector<int>& group_of, int self_group,
+                         const PlanOptions& opt, GroupPlan* gp);
 
 }  // namespace fs
 

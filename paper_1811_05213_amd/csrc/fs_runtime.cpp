@@ -7,6 +7,7 @@
 #include <sys/stat.h>
 #include <unistd.h>
 
+#include <algorithm>
 #include <cstdlib>
 #include <cstring>
 #include <fstream>
@@ -132,7 +133,8 @@ fs_status fs_plan_create(const fs_graph_desc* desc, fs_plan** out_plan) {
     delete plan;
     return st;
   }
-  plan->opt.mode = desc->mode;
+  plan->opt.mode = desc->mode & FS_MODE_UNFUSED;
+  const bool use_library = !(desc->mode & FS_MODE_NO_PERFLIB) && !desc->hint && perflib_size() > 0;
   plan->opt.lds_budget = desc->lds_budget_bytes > 0 ? desc->lds_budget_bytes : 65536;
   if (desc->hint) {
     plan->opt.hint = *desc->hint;
@@ -162,6 +164,8 @@ fs_status fs_plan_create(const fs_graph_desc* desc, fs_plan** out_plan) {
       delete plan;
       return st;
     }
+    // schedule tuning: the fastest candidate the performance library knows (Sections 4.3, 4.4)
+    if (use_library) choose_from_library(g, ordered[gi], plan->group_of, (int)gi, plan->opt, &plan->groups[gi]);
   }
 
   // workspace: [tickets][tensors crossing group boundaries][column-reduction partials]
@@ -250,6 +254,29 @@ static fs_status load_on_device(fs_plan* plan, int device, fs_plan::Loaded** out
   return FS_OK;
 }
 
+namespace fs {
+// kernarg block: { void* p[NP]; float* part; u32* tickets; int R; int n_iters; }
+hipError_t launch_group(const GroupPlan& gp, void* function, void* const* tensors, void* part, void* tickets, hipStream_t stream) {
+  alignas(8) char buf[8 * 48 + 32];
+  size_t n = 0;
+  auto push_ptr = [&](void* p) {
+    memcpy(buf + n, &p, 8);
+    n += 8;
+  };
+  const size_t np = gp.ext_in.size() + gp.ext_out.size();
+  for (size_t k = 0; k < np; ++k) push_ptr(tensors[k]);
+  push_ptr(part);
+  push_ptr(tickets);
+  const int R = gp.R, iters = gp.s.n_iters;
+  memcpy(buf + n, &R, 4);
+  memcpy(buf + n + 4, &iters, 4);
+  n += 8;
+  size_t size = n;
+  void* config[] = {HIP_LAUNCH_PARAM_BUFFER_POINTER, buf, HIP_LAUNCH_PARAM_BUFFER_SIZE, &size, HIP_LAUNCH_PARAM_END};
+  return hipModuleLaunchKernel((hipFunction_t)function, (unsigned)gp.s.grid, 1, 1, (unsigned)gp.s.WG, 1, 1, 0, stream, nullptr, config);
+}
+}  // namespace fs
+
 static fs_status check_workspace(const fs_plan* plan, const void* workspace, size_t workspace_bytes) {
   if (plan->workspace_bytes == 0) return FS_OK;
   if (!workspace) FS_FAIL(FS_ERR_WORKSPACE, "workspace is NULL but the plan needs %zu bytes", plan->workspace_bytes);
@@ -297,25 +324,12 @@ fs_status fs_plan_run(fs_plan* plan, const void* const* inputs, void* const* out
 
   for (size_t gi = 0; gi < plan->groups.size(); ++gi) {
     const GroupPlan& gp = plan->groups[gi];
-    // kernarg block: { void* p[NP]; float* part; u32* tickets; int R; int n_iters; }
-    alignas(8) char buf[8 * 48 + 32];
+    void* tensors[48];
     size_t n = 0;
-    auto push_ptr = [&](void* p) {
-      memcpy(buf + n, &p, 8);
-      n += 8;
-    };
-    for (const ExtTensor& t : gp.ext_in) push_ptr(tensor_ptr(t.node));
-    for (const ExtTensor& t : gp.ext_out) push_ptr(tensor_ptr(t.node));
-    push_ptr(gp.part_bytes ? (void*)(ws + gp.part_offset) : nullptr);
-    push_ptr(gp.n_tickets ? (void*)(ws + gp.ticket_offset) : nullptr);
-    const int R = gp.R, iters = gp.s.n_iters;
-    memcpy(buf + n, &R, 4);
-    memcpy(buf + n + 4, &iters, 4);
-    n += 8;
-    size_t size = n;
-    void* config[] = {HIP_LAUNCH_PARAM_BUFFER_POINTER, buf, HIP_LAUNCH_PARAM_BUFFER_SIZE, &size, HIP_LAUNCH_PARAM_END};
-    e = hipModuleLaunchKernel((hipFunction_t)ld->functions[gi], (unsigned)gp.s.grid, 1, 1, (unsigned)gp.s.WG, 1, 1, 0,
-                              (hipStream_t)hip_stream, nullptr, config);
+    for (const ExtTensor& t : gp.ext_in) tensors[n++] = tensor_ptr(t.node);
+    for (const ExtTensor& t : gp.ext_out) tensors[n++] = tensor_ptr(t.node);
+    e = launch_group(gp, ld->functions[gi], tensors, gp.part_bytes ? (void*)(ws + gp.part_offset) : nullptr,
+                     gp.n_tickets ? (void*)(ws + gp.ticket_offset) : nullptr, (hipStream_t)hip_stream);
     if (e != hipSuccess) FS_FAIL(FS_ERR_HIP, "launch of group %zu (%s): %s", gi, gp.kernel_name.c_str(), hipGetErrorString(e));
   }
   return FS_OK;
@@ -372,6 +386,185 @@ fs_status fs_plan_group_kernel_name(const fs_plan* plan, int32_t group, const ch
   if (!plan || !out_name) FS_FAIL(FS_ERR_INVALID_ARG, "NULL argument");
   if (group < 0 || group >= (int)plan->groups.size()) FS_FAIL(FS_ERR_INVALID_ARG, "group %d out of range", group);
   *out_name = plan->groups[group].kernel_name.c_str();
+  return FS_OK;
+}
+
+fs_status fs_plan_group_perf_key(const fs_plan* plan, int32_t group, const char** out_key) {
+  if (!plan || !out_key) FS_FAIL(FS_ERR_INVALID_ARG, "NULL argument");
+  if (group < 0 || group >= (int)plan->groups.size()) FS_FAIL(FS_ERR_INVALID_ARG, "group %d out of range", group);
+  GroupPlan& gp = const_cast<fs_plan*>(plan)->groups[group];
+  if (gp.perf_key.empty()) gp.perf_key = perf_key(gp);
+  *out_key = gp.perf_key.c_str();
+  return FS_OK;
+}
+
+// ---- schedule tuning: measure-on-miss into the performance library (Sections 4.3, 4.4) ----------
+namespace {
+
+struct TuneScratch {  // everything fs_plan_tune allocates, released on every exit path
+  void* flush = nullptr;
+  void* scratch = nullptr;
+  hipModule_t module = nullptr;
+  std::vector<hipEvent_t> events;
+  ~TuneScratch() {
+    (void)hipDeviceSynchronize();  // nothing below may still be in use by a launch
+    if (module) (void)hipModuleUnload(module);
+    if (scratch) (void)hipFree(scratch);
+    if (flush) (void)hipFree(flush);
+    for (hipEvent_t e : events) (void)hipEventDestroy(e);
+  }
+};
+
+}  // namespace
+
+fs_status fs_plan_tune(fs_plan* plan, const void* const* inputs, void* const* outputs, void* workspace,
+                       size_t workspace_bytes, void* hip_stream, int32_t reps, fs_tune_report* report) {
+  if (!plan || !outputs) FS_FAIL(FS_ERR_INVALID_ARG, "NULL argument");
+  const Graph& g = plan->graph;
+  if (!g.input_ids.empty() && !inputs) FS_FAIL(FS_ERR_INVALID_ARG, "inputs is NULL");
+  for (size_t k = 0; k < g.input_ids.size(); ++k)
+    if (!inputs[k] || ((uintptr_t)inputs[k] & 15)) FS_FAIL(FS_ERR_INVALID_ARG, "inputs[%zu] is NULL or not 16-byte aligned", k);
+  for (size_t k = 0; k < g.outputs.size(); ++k)
+    if (!outputs[k] || ((uintptr_t)outputs[k] & 15)) FS_FAIL(FS_ERR_INVALID_ARG, "outputs[%zu] is NULL or not 16-byte aligned", k);
+  fs_status st = check_workspace(plan, workspace, workspace_bytes);
+  if (st != FS_OK) return st;
+  if (reps <= 0) reps = 9;
+  if (reps > 101) reps = 101;
+  hipStream_t stream = (hipStream_t)hip_stream;
+  int device = 0;
+  hipError_t e = hipGetDevice(&device);
+  if (e != hipSuccess) FS_FAIL(FS_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e));
+  fs_plan::Loaded* ld = nullptr;
+  st = load_on_device(plan, device, &ld);
+  if (st != FS_OK) return st;
+#define FS_HIP(call)                                                                 \
+  do {                                                                               \
+    const hipError_t e_ = (call);                                                    \
+    if (e_ != hipSuccess) FS_FAIL(FS_ERR_HIP, "%s: %s", #call, hipGetErrorString(e_)); \
+  } while (0)
+
+  char* ws = (char*)workspace;
+  auto tensor_ptr = [&](int node) -> void* {
+    if (g.input_index[node] >= 0) return const_cast<void*>(inputs[g.input_index[node]]);
+    if (g.output_index[node] >= 0) return outputs[g.output_index[node]];
+    return ws + plan->ws_tensor_offset.at(node);
+  };
+
+  TuneScratch res;
+  constexpr size_t kFlushBytes = 256ull << 20;  // one pass over 2 x 256 MiB evicts the last-level cache
+  res.events.resize(2 * (size_t)reps);
+  for (hipEvent_t& ev : res.events) {
+    ev = nullptr;
+    FS_HIP(hipEventCreate(&ev));
+  }
+  fs_tune_report rep = {};
+  PlanOptions base_opt = plan->opt;
+  base_opt.has_hint = false;
+
+  for (size_t gi = 0; gi < plan->groups.size(); ++gi) {
+    const GroupPlan& base = plan->groups[gi];
+    void* tensors[48];
+    size_t nt = 0;
+    for (const ExtTensor& t : base.ext_in) tensors[nt++] = tensor_ptr(t.node);
+    for (const ExtTensor& t : base.ext_out) tensors[nt++] = tensor_ptr(t.node);
+    void* base_part = base.part_bytes ? (void*)(ws + base.part_offset) : nullptr;
+    void* base_tickets = base.n_tickets ? (void*)(ws + base.ticket_offset) : nullptr;
+
+    // the current schedule first, then its neighbourhood (distinct kernels only)
+    std::vector<GroupPlan> cands;
+    cands.push_back(base);
+    std::set<std::string> keys{perf_key(base)};
+    for (const fs_sched_hint& h : candidate_hints(base)) {
+      PlanOptions o = base_opt;
+      o.hint = h;
+      o.has_hint = true;
+      GroupPlan c;
+      if (analyse_group(g, base.members, plan->group_of, (int)gi, o, &c) != FS_OK) continue;
+      if (c.s.L != h.lanes_per_row || c.s.WG != h.wg_threads) continue;
+      if (generate_kernel(g, &c, (int)gi) != FS_OK) continue;
+      if (!keys.insert(perf_key(c)).second) continue;
+      cands.push_back(std::move(c));
+    }
+    const bool cold = base.min_hbm_bytes > (1ull << 20);
+    if (cold && !res.flush) FS_HIP(hipMalloc(&res.flush, 2 * kFlushBytes));
+
+    double cur_us = 0.0, best_us = 0.0;
+    for (size_t k = 0; k < cands.size(); ++k) {
+      const GroupPlan& c = cands[k];
+      const std::string key = perf_key(c);
+      double us = 0.0;
+      ++rep.candidates;
+      if (perflib_lookup(key, &us)) {
+        ++rep.hits;
+      } else {
+        void* fn = ld->functions[gi];
+        void* part = base_part;
+        void* tickets = base_tickets;
+        if (k > 0) {
+          std::vector<char> code;
+          st = compile_kernel(std::string(device_header_source()) + "\n" + c.source, c.kernel_name, &code);
+          if (st != FS_OK) return st;
+          FS_HIP(hipModuleLoadData(&res.module, code.data()));
+          hipFunction_t f;
+          FS_HIP(hipModuleGetFunction(&f, res.module, c.kernel_name.c_str()));
+          fn = (void*)f;
+          const size_t tbytes = align_up((size_t)c.n_tickets * 4, 256);
+          if (tbytes + c.part_bytes > 0) {
+            FS_HIP(hipMalloc(&res.scratch, tbytes + c.part_bytes));
+            if (tbytes) {
+              const int ze = launch_zero_u32(res.scratch, tbytes / 4, stream);
+              if (ze != 0) FS_FAIL(FS_ERR_HIP, "fill kernel launch: %s", hipGetErrorString((hipError_t)ze));
+            }
+            tickets = c.n_tickets ? res.scratch : nullptr;
+            part = c.part_bytes ? (void*)((char*)res.scratch + tbytes) : nullptr;
+          } else {
+            part = tickets = nullptr;
+          }
+        }
+        for (int w = 0; w < 2; ++w) FS_HIP(launch_group(c, fn, tensors, part, tickets, stream));
+        // a cold launch is timed on its own; launches that live in the caches anyway are timed in runs of 20
+        const int inner = cold ? 1 : 20;
+        for (int r = 0; r < reps; ++r) {
+          if (cold) {
+            const int ce = launch_copy_probe(res.flush, (char*)res.flush + kFlushBytes, kFlushBytes, stream);
+            if (ce != 0) FS_FAIL(FS_ERR_HIP, "flush launch: %s", hipGetErrorString((hipError_t)ce));
+          }
+          FS_HIP(hipEventRecord(res.events[2 * r], stream));
+          for (int i = 0; i < inner; ++i) FS_HIP(launch_group(c, fn, tensors, part, tickets, stream));
+          FS_HIP(hipEventRecord(res.events[2 * r + 1], stream));
+        }
+        FS_HIP(hipStreamSynchronize(stream));
+        std::vector<float> ms((size_t)reps);
+        for (int r = 0; r < reps; ++r) FS_HIP(hipEventElapsedTime(&ms[r], res.events[2 * r], res.events[2 * r + 1]));
+        std::sort(ms.begin(), ms.end());
+        us = (double)ms[(size_t)reps / 2] * 1e3 / inner;
+        char note[160];
+        snprintf(note, sizeof(note), "%zu nodes on [%d,%d]: %d lanes/row, %d elements/lane, workgroup %d, grid %d, %s", c.members.size(), c.R,
+                 c.C, c.s.L, c.s.E, c.s.WG, c.s.grid, cold ? "cold caches" : "warm caches");
+        if (!perflib_insert(key, us, note)) FS_FAIL(FS_ERR_INVALID_ARG, "the performance library file cannot be written");
+        ++rep.measured;
+        if (res.module) {
+          (void)hipModuleUnload(res.module);
+          res.module = nullptr;
+        }
+        if (res.scratch) {
+          (void)hipFree(res.scratch);
+          res.scratch = nullptr;
+        }
+      }
+      if (k == 0) cur_us = best_us = us;
+      else if (us < best_us) best_us = us;
+    }
+    rep.current_usec += cur_us;
+    rep.best_usec += best_us;
+    if (best_us < cur_us) ++rep.improvable;
+    ++rep.groups;
+    // leave this group's results as a normal run would, for the groups that follow
+    FS_HIP(launch_group(base, ld->functions[gi], tensors, base_part, base_tickets, stream));
+  }
+  FS_HIP(hipStreamSynchronize(stream));
+#undef FS_HIP
+  if (report) *report = rep;
   return FS_OK;
 }
 

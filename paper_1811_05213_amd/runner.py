@@ -59,6 +59,12 @@ class DeviceRun:
         self.plan.run([t.data_ptr() for t in self.inputs], [t.data_ptr() for t in self.outputs],
                       self.workspace.data_ptr() if self.ws_bytes else 0, self.ws_bytes, stream)
 
+    def tune(self, reps: int = 0) -> dict:
+        """fs_plan_tune on this run's buffers: fills the performance library for the plan's groups."""
+        stream = torch.cuda.current_stream(self.device).cuda_stream
+        return self.plan.tune([t.data_ptr() for t in self.inputs], [t.data_ptr() for t in self.outputs],
+                              self.workspace.data_ptr() if self.ws_bytes else 0, self.ws_bytes, stream, reps)
+
     def prepare(self):
         """Freeze the pointer tables and the stream; returns a zero-argument launcher for timing loops."""
         ins, outs = self.plan.pointer_tables([t.data_ptr() for t in self.inputs], [t.data_ptr() for t in self.outputs])

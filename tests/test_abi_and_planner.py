@@ -283,3 +283,48 @@ def test_ragged_and_degenerate_shapes_plan():
     g = multi_reduce_graph(4, 1 << 17)
     assert _status(g, group_of_node=[0 if n.op not in ("input", "const", "bcast_rowvec", "bcast_colvec") else -1 for n in g.nodes]) \
         == "FS_ERR_UNSUPPORTED"
+
+
+def test_performance_library_drives_the_schedule(tmp_path, monkeypatch):
+    # schedule tuning = enumerate the candidates, look each kernel up in the library, keep the fastest recorded one
+    lib_file = tmp_path / "perflib.tsv"
+    monkeypatch.setenv("FS_PERF_LIBRARY", str(lib_file))
+    g = softmax_graph(300, 1000)
+    p0 = fs.Plan(g)
+    base = p0.group_info(0)
+    k0 = p0.group_perf_key(0)
+    assert k0.startswith(p0.group_kernel_name(0) + ":R300:")
+    hinted = fs.Plan(g, hint={"lanes_per_row": base["lanes_per_row"] * 2, "wg_threads": base["wg_threads"]})
+    k1 = hinted.group_perf_key(0)
+    assert k1 != k0 and hinted.group_info(0)["lanes_per_row"] == 2 * base["lanes_per_row"]
+
+    # only the candidate is recorded: an unmeasured base schedule is not displaced
+    lib_file.write_text(f"# test library\n{k1}\t5.0\n")
+    p = fs.Plan(g)
+    assert p.group_perf_key(0) == k0
+    p.destroy()
+    # both recorded, the candidate faster: it is chosen ...
+    lib_file.write_text(f"{k0}\t10.0\n{k1}\t5.0\n")
+    p = fs.Plan(g)
+    assert p.group_perf_key(0) == k1 and p.group_info(0)["lanes_per_row"] == 2 * base["lanes_per_row"]
+    p.destroy()
+    # ... unless the caller opts out, or passes a hint of its own
+    p = fs.Plan(g, mode=fs.FS_MODE_NO_PERFLIB)
+    assert p.group_perf_key(0) == k0
+    p.destroy()
+    p = fs.Plan(g, hint={"wg_threads": base["wg_threads"]})
+    assert p.group_info(0)["lanes_per_row"] == base["lanes_per_row"]
+    p.destroy()
+    # a candidate inside the measurement noise (3 %) does not displace the analytic schedule
+    lib_file.write_text(f"{k0}\t10.0\n{k1}\t9.8\n")
+    p = fs.Plan(g)
+    assert p.group_perf_key(0) == k0
+    p.destroy()
+    # a later record overrides an earlier one; malformed lines are skipped
+    with open(lib_file, "a") as f:
+        f.write(f"garbage line\n{k1}\t5.0\n{k1}\t50.0\n")
+    p = fs.Plan(g)
+    assert p.group_perf_key(0) == k0
+    p.destroy()
+    p0.destroy()
+    hinted.destroy()

@@ -374,3 +374,27 @@ def test_transposes_inside_a_group():
         check_all(g, out, ref, f"in-group transposes {rows}x{cols}, one kernel")
         np.testing.assert_array_equal(out[4], out[3].T)
         both_modes(g, ins, f"in-group transposes {rows}x{cols}")   # the library's own grouping, and per-op
+
+
+def test_tuning_fills_the_library_and_tuned_plans_match_the_oracle(tmp_path, monkeypatch):
+    # measure-on-miss: every candidate schedule of every group is timed once and recorded; a second pass only hits
+    monkeypatch.setenv("FS_PERF_LIBRARY", str(tmp_path / "perflib.tsv"))
+    for cfg, rows in ((1, 300), (4, 3000), (6, 512), (5, 64)):
+        g, ins, name = workload(cfg, rows)
+        ref = oracle.run(g, ins, THREADS)
+        plan = fs.Plan(g)
+        r = DeviceRun(plan)
+        r.set_inputs(ins)
+        rep = r.tune(reps=3)
+        assert rep["groups"] == plan.stats()["num_groups"]
+        # (groups with the same structure share their keys: the second one already hits)
+        assert rep["measured"] + rep["hits"] == rep["candidates"] > rep["groups"] and rep["measured"] > rep["hits"]
+        assert 0 < rep["best_usec"] <= rep["current_usec"]
+        check_all(g, r.results(), ref, name + " after tuning")  # the buffers hold a normal run's results
+        rep2 = r.tune(reps=3)
+        assert rep2["measured"] == 0 and rep2["hits"] == rep2["candidates"] == rep["candidates"]
+        plan.destroy()
+        out = run_graph(g, ins)  # planned again: now with the library's schedules
+        check_all(g, out, ref, name + " tuned plan")
+    text = (tmp_path / "perflib.tsv").read_text()
+    assert text.count("\t") >= 10 and "lanes/row" in text
