@@ -366,7 +366,8 @@ struct Emitter {
     // Per-column values ([1,C] tensors) are loaded into registers once per workgroup when the
     // workgroup loops over many rows; with one trip per workgroup (or column tiles) they are
     // simply read where the loop body needs them.
-    const bool rowv_in_loop = s.CT > 1 || s.grid >= s.n_iters;
+    const bool ctile = s.col_tiled;  // column reductions by column tiles: a workgroup keeps its tile, RB workgroups share the rows
+    const bool rowv_in_loop = !ctile && (s.CT > 1 || s.grid >= s.n_iters);
 
     // fixed local numbering: external inputs first, then members
     for (const ExtTensor& e : gp.ext_in) loc(e.node);
@@ -395,7 +396,12 @@ struct Emitter {
       run_chunked(xwave, WPR, KB);
       return;
     }
-    if (K > 0) os << "  __shared__ float lds_col[(L < 64 ? WG / 64 : G) * C];\n  __shared__ fs_u32 lds_flag;\n";
+    // CW columns are folded together: the whole row, or one column tile
+    os << "  constexpr int CW = " << (ctile ? "NVL * L * V" : "C") << ", NVF = CW / V, RB = " << s.RB << ";\n";
+    if (ctile) os << "  const int tile = (int)blockIdx.x % CT, rb = (int)blockIdx.x / CT, vbase = tile * (NVL * L);\n";
+    else os << "  const int tile = 0, rb = (int)blockIdx.x;\n";
+    os << "  (void)tile; (void)rb; (void)CW; (void)NVF; (void)RB;\n";
+    if (K > 0) os << "  __shared__ float lds_col[(L < 64 ? WG / 64 : G) * CW];\n  __shared__ fs_u32 lds_flag;\n";
     if (s.tile_transpose) os << "  __shared__ float lds_tile[C * (G + 1)];\n";
     if (s.stage_rowv) {
       int n_rowv = 0;
@@ -435,7 +441,7 @@ struct Emitter {
              << "], 0, lir, " << vb << ", true);\n";
       }
     };
-    if (!rowv_in_loop) emit_rowv("  ", "0", "blockIdx.x == 0 && rg == 0");
+    if (!rowv_in_loop) emit_rowv("  ", ctile ? "vbase" : "0", "rb == 0 && rg == 0");
     for (int k = 0; k < K; ++k) {
       const int m = gp.col_reduces[k];
       os << "  float ca" << loc(m) << "[E];\n  _Pragma(\"unroll\") for (int e = 0; e < E; ++e) ca" << loc(m) << "[e] = fs_red_identity<"
@@ -446,7 +452,9 @@ struct Emitter {
     // A looping kernel handles U row tiles per trip: the loads of all U tiles are issued first,
     // then the U bodies run one after the other (more bytes in flight per wavefront).
     const int U = (rowv_in_loop || s.CT > 1) ? 1 : std::max(1, s.U);
-    if (U == 1) {
+    if (ctile) {
+      os << "  for (int it = rb; it < a.n_iters; it += RB) {\n";
+    } else if (U == 1) {
       os << "  for (int it = (int)blockIdx.x; it < a.n_iters; it += (int)gridDim.x) {\n";
     } else {
       os << "  for (int it0 = (int)blockIdx.x * " << U << "; it0 < a.n_iters; it0 += (int)gridDim.x * " << U << ") {\n";
@@ -454,7 +462,9 @@ struct Emitter {
     for (int u = 0; u < U; ++u) {
       const std::string x = U == 1 ? "" : "_" + std::to_string(u);
       if (U > 1) os << "    const int it" << x << " = it0 + " << u << ";\n";
-      if (s.CT == 1) {
+      if (ctile) {
+        os << "    const long row = (long)it * G + rg;\n";
+      } else if (s.CT == 1) {
         os << "    const long row" << x << " = (long)it" << x << " * G + rg;\n    constexpr int vbase" << x << " = 0;\n";
       } else {
         os << "    const long unit = (long)it * G + rg;\n    const long row = unit / CT;\n    const int vbase = (int)(unit % CT) * (NVL * L);\n";
@@ -573,24 +583,25 @@ struct Emitter {
 
     // ---- epilogue: finish the column reductions ----
     if (K > 0) {
-      const int FV = C % 4 == 0 ? 4 : C % 2 == 0 ? 2 : 1;
-      os << "  {\n    constexpr int FV = " << FV << ";\n    typedef fs_colfold<" << K << ", C, WG, FV> S;\n    float cv[S::CPT][FV];\n";
+      const int CW = ctile ? s.NVL * s.L * s.V : C;
+      const int FV = CW % 4 == 0 ? 4 : CW % 2 == 0 ? 2 : 1;
+      os << "  {\n    constexpr int FV = " << FV << ";\n    typedef fs_colfold<" << K << ", CW, WG, FV> S;\n    float cv[S::CPT][FV];\n";
       for (int k = 0; k < K; ++k) {
         const int m = gp.col_reduces[k];
-        os << "    fs_colred_fold_wg<" << g.nodes[m].attr_i << ", " << k << ", " << K << ", V, NVL, L, NV, C, WG, FV>(ca" << loc(m)
+        os << "    fs_colred_fold_wg<" << g.nodes[m].attr_i << ", " << k << ", " << K << ", V, NVL, L, NVF, CW, WG, FV>(ca" << loc(m)
            << ", cv, lds_col, lir, rg);\n";
       }
-      os << "    if (fs_colred_fold_grid<" << K << ", C, WG, FV, " << s.fan_in << ", " << kname
-         << "_kinds>(cv, a.part, a.tickets, &lds_flag)) {\n";
+      os << "    if (fs_colred_fold_grid<" << K << ", CW, WG, FV, " << s.fan_in << ", " << kname << "_kinds>(cv, a.part + (long)tile * "
+         << s.part_stride_floats << "L, a.tickets + tile * " << s.ticket_stride << ", &lds_flag, (fs_u32)rb, (fs_u32)RB)) {\n";
       os << "      _Pragma(\"unroll\") for (int i = 0; i < S::CPT; ++i) {\n        const int c = tid + i * WG;\n"
-         << "        if (c < S::NCH) {\n          const int k = c / S::CH, col0 = (c % S::CH) * FV;\n";
+         << "        if (c < S::NCH) {\n          const int k = c / S::CH, col0 = tile * CW + (c % S::CH) * FV;\n";
       for (int k = 0; k < K; ++k) {
         const int m = gp.col_reduces[k];
         const ExtTensor* e = find_out(m);
         if (!e) continue;
         const fs_node& n = g.nodes[m];
-        os << "          if (k == " << k << ") { _Pragma(\"unroll\") for (int f = 0; f < FV; ++f) fs_store1<" << e->dtype << ">(a.p[" << e->arg
-           << "], col0 + f, cv[i][f]" << (n.attr_i == FS_RED_MEAN ? " / (float)a.R" : "") << "); }\n";
+        os << "          if (k == " << k << ") { _Pragma(\"unroll\") for (int f = 0; f < FV; ++f) if (col0 + f < C) fs_store1<" << e->dtype
+           << ">(a.p[" << e->arg << "], col0 + f, cv[i][f]" << (n.attr_i == FS_RED_MEAN ? " / (float)a.R" : "") << "); }\n";
       }
       os << "        }\n      }\n    }\n  }\n";
     }

@@ -504,6 +504,8 @@ FS_DEV void fs_colred_fold_wg(const float (&acc_in)[NVL * V], float (&vals)[CPT]
 //   part     workspace, sum over levels of n_level*K*C floats
 //   tickets  workspace, one zero-initialised u32 per fan-in group per level; left zero on exit
 //   flag     one u32 of LDS
+//   idx, n   this workgroup's index among the n workgroups that fold together (the whole grid,
+//            or the workgroups of one column tile)
 // Returns true in exactly one workgroup, whose `vals` then hold the final values.
 //
 // Visibility across the 8 XCDs (each has its own L2) is obtained without device-scope fences,
@@ -514,12 +516,11 @@ FS_DEV void fs_colred_fold_wg(const float (&acc_in)[NVL * V], float (&vals)[CPT]
 // The F loads of a chunk are independent and issued in batches, so a fold costs a few memory
 // round trips, not F of them; they are combined in index order, whichever workgroup folds.
 template <int K, int C, int WG, int FV, int F, typename KINDS, int CPT>
-FS_DEV bool fs_colred_fold_grid(float (&vals)[CPT][FV], float* part, fs_u32* tickets, fs_u32* flag) {
+FS_DEV bool fs_colred_fold_grid(float (&vals)[CPT][FV], float* part, fs_u32* tickets, fs_u32* flag, fs_u32 idx, fs_u32 n) {
   typedef fs_colfold<K, C, WG, FV> S;
   static_assert(CPT == S::CPT, "chunks per thread");
   constexpr int KC = K * C;
   constexpr int FB = 16;  // loads in flight per chunk
-  fs_u32 idx = blockIdx.x, n = gridDim.x;
   const int t = (int)threadIdx.x;
   while (n > 1) {
     {

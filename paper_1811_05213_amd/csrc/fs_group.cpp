@@ -127,36 +127,47 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   // Row reductions over rows that do not fit the registers of one workgroup: the workgroup walks
   // its row in column chunks, once per stage, recomputing what each stage needs.
   const bool chunked = l_min > 1024 && rowred && !colred && !has_transposed;
-  if (l_min > 1024 && !tileable && !chunked)
+  // Column reductions alone do not need whole rows either: column tiles, each with its own fold.
+  const bool col_tiled = l_min > 1024 && colred && !rowred && !has_transposed;
+  if (l_min > 1024 && !tileable && !chunked && !col_tiled)
     FS_FAIL(FS_ERR_UNSUPPORTED, "rows of %d columns are too long for one workgroup in a group with %s", C,
-            colred ? "column reductions" : "transposed outputs");
+            colred ? "row and column reductions" : "transposed outputs");
   if (tileable) l_min = std::min(l_min, 256);
-  if (chunked) l_min = 1024;  // (measured: the largest workgroup keeps the fewest rows in flight, so re-reads hit the caches more often)
+  if (chunked) l_min = 1024;
+  if (col_tiled) l_min = std::min(256, l_max);  // (measured: the largest workgroup keeps the fewest rows in flight, so re-reads hit the caches more often)
   int L = rowred ? std::min(64, l_max) : std::min(256, l_max);
   // a transposed root leaves as runs of G = WG/L consecutive elements: at least 16 rows per workgroup
   if (has_transposed && !rowred) L = std::min(L, std::max(l_min, 16));
   // looping (column-reduction) kernels want more bytes in flight per lane: 16 elements per lane
   if (colred) L = std::min(L, std::max(1, pow2_ceil((NV * V + 15) / 16)));
   L = std::max(L, l_min);
+  if (col_tiled) L = l_min;
   // small problems: more lanes per row until the device has ~8 wavefronts per CU
-  while ((int64_t)R * L / 64 < 2048 && L < l_max && !(has_transposed && !rowred) && !chunked) L *= 2;
+  while ((int64_t)R * L / 64 < 2048 && L < l_max && !(has_transposed && !rowred) && !chunked && !col_tiled) L *= 2;
   if (opt.has_hint && opt.hint.lanes_per_row > 0) {
     const int h = opt.hint.lanes_per_row;
-    if ((h & (h - 1)) == 0 && h >= (chunked ? 64 : l_min) && h <= 1024) L = h;
+    if ((h & (h - 1)) == 0 && h >= ((chunked || col_tiled) ? 64 : l_min) && h <= 1024) L = h;
   }
   int NVL = (NV + L - 1) / L, CT = 1;
   if (NVL * V > ecap && tileable) {
     NVL = std::max(1, ecap / V);
     CT = (NV + NVL * L - 1) / (NVL * L);
   }
-  if (chunked) {
+  if (chunked || col_tiled) {
     NVL = std::max(1, 16 / V);
     CT = (NV + NVL * L - 1) / (NVL * L);
   }
 
   int WG;
   const int64_t total_waves = std::max<int64_t>(1, (int64_t)R * CT * L / 64);
-  if (colred) {
+  if (col_tiled) {
+    WG = std::max(64, L);
+    for (int w = 512; w >= 128; w /= 2)
+      if (w >= L && (int64_t)R * L / w >= 8) {
+        WG = w;
+        break;
+      }
+  } else if (colred) {
     // large workgroups (few partials, many rows per trip) as long as every CU still gets a workgroup
     WG = std::max(64, L);
     for (int w = 512; w >= 128; w /= 2)
@@ -183,7 +194,8 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   s.G = WG / L;
   s.ragged = (int64_t)CT * NVL * L != NV;
   s.chunked = chunked;
-  s.n_iters = chunked ? R : (int)(((int64_t)R * CT + s.G - 1) / s.G);
+  s.col_tiled = col_tiled;
+  s.n_iters = chunked ? R : col_tiled ? (R + s.G - 1) / s.G : (int)(((int64_t)R * CT + s.G - 1) / s.G);
   // Streaming groups launch one workgroup per row tile: the hardware hands tiles out in memory
   // order and a fresh wavefront issues its loads at once, which measures faster on this device
   // than persistent workgroups looping with a grid stride.  Column reductions keep a bounded
@@ -191,10 +203,15 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   int cap = colred ? 256 : (1 << 30);
   if (opt.has_hint && opt.hint.max_workgroups > 0) cap = opt.hint.max_workgroups;
   s.grid = std::max(1, std::min(s.n_iters, cap));
+  s.RB = s.grid;
+  if (col_tiled) {  // RB workgroups per column tile, about `cap` workgroups in all
+    s.RB = std::max(1, std::min(s.n_iters, std::max(1, cap / CT)));
+    s.grid = s.RB * CT;
+  }
   s.U = 1;  // (two tiles per trip measured no faster than one with 16 elements per lane)
   if (const char* env = getenv("FS_DEBUG_UNROLL")) s.U = std::max(1, atoi(env));
   // two fold levels at most: the smallest fan-in whose square covers the grid
-  s.fan_in = s.grid <= 64 ? 8 : s.grid <= 256 ? 16 : 32;
+  s.fan_in = s.RB <= 64 ? 8 : s.RB <= 256 ? 16 : 32;
 
   // LDS plan (Section 5.1).  Size requirements: cross-wave row-reduction partials (the "direct
   // allocation" for a non-root Reduce) and the column-partial fold area.  Space sharing: all row
@@ -203,7 +220,8 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   // reductions in turn.
   int lds = 0;
   if (rowred && L > 64) lds += 2 * s.G * (L / 64) * gp->max_batched_reduces * 4;
-  if (colred) lds += (L < 64 ? WG / 64 : s.G) * C * 4 + 16;
+  const int fold_width = col_tiled ? NVL * L * V : C;  // columns one workgroup folds
+  if (colred) lds += (L < 64 ? WG / 64 : s.G) * fold_width * 4 + 16;
   // [1,C] inputs shared by all rows of a workgroup: with one trip per workgroup they are staged in
   // LDS by the whole workgroup when several rows share them and the budget allows
   int n_rowv = 0;
@@ -226,16 +244,19 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   // grid-wide fold scratch
   gp->n_tickets = 0;
   gp->part_bytes = 0;
+  s.part_stride_floats = 0;
+  s.ticket_stride = 0;
   if (colred) {
-    const size_t kc = gp->col_reduces.size() * (size_t)C;
-    size_t floats = 0;
-    int n = s.grid;
+    const size_t kc = gp->col_reduces.size() * (size_t)fold_width;
+    int n = s.RB;
     while (n > 1) {
-      floats += (size_t)n * kc;
+      s.part_stride_floats += (size_t)n * kc;
       n = (n + s.fan_in - 1) / s.fan_in;
-      gp->n_tickets += n;
+      s.ticket_stride += n;
     }
-    gp->part_bytes = floats * 4;
+    const int tiles = col_tiled ? CT : 1;
+    gp->n_tickets = s.ticket_stride * tiles;
+    gp->part_bytes = s.part_stride_floats * tiles * 4;
   }
   (void)g;
   return FS_OK;

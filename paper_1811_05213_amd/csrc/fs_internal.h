@@ -92,6 +92,12 @@ struct Schedule {
   // column chunks once per stage, and each stage recomputes the elementwise values it needs from
   // the inputs instead of keeping them (space traded for recomputation, Section 5.1.2).
   bool chunked = false;
+  // Column reductions over rows too wide for one workgroup: CT column tiles, each folded by its own
+  // RB = grid / CT workgroups (tile = block % CT).  Strides of one tile's scratch in the workspace:
+  bool col_tiled = false;
+  int RB = 0;
+  size_t part_stride_floats = 0;
+  int ticket_stride = 0;
 };
 
 struct GroupPlan {

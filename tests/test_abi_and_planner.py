@@ -279,6 +279,14 @@ def test_ragged_and_degenerate_shapes_plan():
     src = p.group_source(0)
     assert src.count("const int vbase = ch * (NVL * L);") == 3  # max pass, sum pass, output pass
     p.destroy()
+    # column reductions over wide rows run by column tiles
+    gw = Graph()
+    xw = gw.input(100, 50000)
+    gw.set_outputs([gw.reduce_col("sum", xw)])
+    p = fs.Plan(gw)
+    gi = p.group_info(0)
+    assert gi["grid"] % -(-50000 // (gi["elems_per_lane"] * gi["lanes_per_row"])) == 0 and "tile * CW" in p.group_source(0)
+    p.destroy()
     # ... but not together with a column reduction in the same kernel: refused cleanly
     g = multi_reduce_graph(4, 1 << 17)
     assert _status(g, group_of_node=[0 if n.op not in ("input", "const", "bcast_rowvec", "bcast_colvec") else -1 for n in g.nodes]) \

@@ -124,6 +124,26 @@ def test_row_and_col_reductions(kind):
         both_modes(g, [RNG.standard_normal((rows, cols)).astype(np.float32)], f"reduce {kind} {rows}x{cols}")
 
 
+def test_column_reductions_over_wide_rows():
+    # wider than one workgroup's registers: column tiles, each with its own partials, tickets and fold
+    for rows, cols in [(1000, 12288), (300, 100001), (5, 20000), (4097, 16384)]:
+        g = Graph()
+        x = g.input(rows, cols)
+        g.set_outputs([g.reduce_col("sum", x), g.reduce_col("max", g.binary("mul", x, x)), g.reduce_col("mean", x)])
+        p = fs.Plan(g)
+        gi = p.group_info(0)
+        assert gi["elems_per_lane"] * gi["lanes_per_row"] < cols
+        if rows >= 300:  # (small launch-bound groups keep column folds apart)
+            assert p.stats()["num_launches"] == 1 and gi["num_col_reduces"] == 3
+        p.destroy()
+        both_modes(g, [RNG.standard_normal((rows, cols)).astype(np.float32)], f"wide column reductions {rows}x{cols}")
+    # LayerNorm backward with a wide hidden dimension: the planner separates what cannot share a kernel
+    g, ins, name = workload(6, 64)
+    from workloads import layernorm_grad_graph, layernorm_grad_inputs
+    g = layernorm_grad_graph(48, 16384)
+    both_modes(g, layernorm_grad_inputs(48, 16384), "layernorm backward 48x16384")
+
+
 def test_row_reduce_across_wavefronts():
     # rows long enough to be spread over 2..16 wavefronts with an LDS fold, ragged tails included
     for rows, cols in [(9, 4096), (3, 20000), (2, 16385), (5, 32768)]:  # 32768 = the longest row one workgroup holds
