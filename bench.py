@@ -115,6 +115,17 @@ def measure_workload(cfg, steps, warmup, with_unfused=True, rows=None):
         del runs
         plan.destroy()
         torch.cuda.empty_cache()
+    if cfg == 5:
+        # the same DAG grouped by the layered planner exactly as the paper states it (Section 3.2)
+        from paper_1811_05213_amd import FS_MODE_LAYERED
+        plan = Plan(g, mode=FS_MODE_LAYERED)
+        runs = build_sets(plan, g, ins, "cuda:0", target)
+        ms, _ = time_plan(runs, steps, warmup)
+        out["layered_planner"] = {"ms": ms, "launches": plan.stats()["num_launches"],
+                                  "launched_hbm_bytes": plan.stats()["launched_hbm_bytes"]}
+        del runs
+        plan.destroy()
+        torch.cuda.empty_cache()
     if with_unfused:
         out["speedup_vs_unfused"] = out["unfused"]["ms"] / out["stitched"]["ms"]
         out["launch_ratio"] = out["stitched"]["launches"] / out["unfused"]["launches"]

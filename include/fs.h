@@ -122,6 +122,11 @@ typedef struct {
 #define FS_MODE_UNFUSED 1u  /* one launch per compute node, every intermediate in HBM; the
                                comparison executor for launch count and HBM traffic
                                (the role of the per-op baseline in Section 6.3) */
+#define FS_MODE_LAYERED 4u /* flag, may be or-ed in: form groups with the layered planner exactly as
+                              Section 3.2 describes it (Work/Span layers, intra-layer ElementwiseFusion,
+                              Algorithm 1 from every fusion root) instead of the default planner, which
+                              visits nodes in the same order but joins a node to any consistent user
+                              group and then merges sibling groups across layers */
 #define FS_MODE_NO_PERFLIB 2u /* flag, may be or-ed in: ignore the performance library and keep the
                                  schedules of the analytic rules */
 
@@ -222,6 +227,11 @@ fs_status fs_plan_group_info(const fs_plan* plan, int32_t group, fs_group_info* 
 
 /* The group each node was assigned to (-1 for INPUT/CONST/BCAST_*). out has room for num_nodes entries. */
 fs_status fs_plan_node_groups(const fs_plan* plan, int32_t* out, int32_t num_nodes);
+
+/* Work/Span analysis (Section 3.1): the span of every node: 0 for a node no live node consumes,
+ * else 1 + the largest span of its users; -1 for INPUT/CONST/BCAST_* and dead nodes.  Nodes of
+ * equal span are one layer.  out has room for num_nodes entries. */
+fs_status fs_plan_node_spans(const fs_plan* plan, int32_t* out, int32_t num_nodes);
 
 /* The generated HIP source of one group's kernel (owned by the plan; valid until destroy). */
 fs_status fs_plan_group_source(const fs_plan* plan, int32_t group, const char** out_src);

@@ -17,6 +17,7 @@ FS_ABI_VERSION = 1
 FS_MODE_STITCHED = 0
 FS_MODE_UNFUSED = 1
 FS_MODE_NO_PERFLIB = 2
+FS_MODE_LAYERED = 4
 
 STATUS_NAMES = ["FS_OK", "FS_ERR_INVALID_ARG", "FS_ERR_BAD_GRAPH", "FS_ERR_SHAPE", "FS_ERR_DTYPE", "FS_ERR_UNSUPPORTED",
                 "FS_ERR_LDS_BUDGET", "FS_ERR_WORKSPACE", "FS_ERR_COMPILE", "FS_ERR_HIP", "FS_ERR_OOM"]
@@ -95,6 +96,7 @@ def lib() -> ctypes.CDLL:
         L.fs_plan_stats.argtypes = [vp, i32p, i32p, u64p, u64p]
         L.fs_plan_group_info.argtypes = [vp, ctypes.c_int32, ctypes.POINTER(fs_group_info)]
         L.fs_plan_node_groups.argtypes = [vp, i32p, ctypes.c_int32]
+        L.fs_plan_node_spans.argtypes = [vp, i32p, ctypes.c_int32]
         L.fs_plan_group_source.argtypes = [vp, ctypes.c_int32, ctypes.POINTER(ctypes.c_char_p)]
         L.fs_plan_group_kernel_name.argtypes = [vp, ctypes.c_int32, ctypes.POINTER(ctypes.c_char_p)]
         L.fs_plan_group_perf_key.argtypes = [vp, ctypes.c_int32, ctypes.POINTER(ctypes.c_char_p)]
@@ -104,7 +106,7 @@ def lib() -> ctypes.CDLL:
         L.fs_last_error.restype = ctypes.c_char_p
         for name in ("fs_plan_create", "fs_plan_destroy", "fs_plan_workspace_bytes", "fs_plan_run",
                      "fs_plan_workspace_init", "fs_plan_stats", "fs_plan_group_info", "fs_plan_node_groups",
-                     "fs_plan_group_source", "fs_plan_group_kernel_name", "fs_copy_probe", "fs_plan_tune", "fs_plan_group_perf_key"):
+                     "fs_plan_group_source", "fs_plan_group_kernel_name", "fs_copy_probe", "fs_plan_tune", "fs_plan_group_perf_key", "fs_plan_node_spans"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -191,6 +193,12 @@ class Plan:
         n = len(self.graph.nodes)
         out = (ctypes.c_int32 * n)()
         _check(lib().fs_plan_node_groups(self._h, out, n))
+        return list(out)
+
+    def node_spans(self) -> List[int]:
+        n = len(self.graph.nodes)
+        out = (ctypes.c_int32 * n)()
+        _check(lib().fs_plan_node_spans(self._h, out, n))
         return list(out)
 
     def group_source(self, group: int) -> str:

@@ -43,7 +43,7 @@ fs_status build_graph(const fs_graph_desc* desc, Graph* g) {
     FS_FAIL(FS_ERR_INVALID_ARG, "abi_version %u, library speaks %u", desc->abi_version, FS_ABI_VERSION);
   if (desc->num_nodes <= 0 || !desc->nodes) FS_FAIL(FS_ERR_INVALID_ARG, "no nodes");
   if (desc->num_outputs <= 0 || !desc->outputs) FS_FAIL(FS_ERR_INVALID_ARG, "no outputs");
-  if ((desc->mode & ~(uint32_t)(FS_MODE_UNFUSED | FS_MODE_NO_PERFLIB)) != 0) FS_FAIL(FS_ERR_INVALID_ARG, "unknown mode %u", desc->mode);
+  if ((desc->mode & ~(uint32_t)(FS_MODE_UNFUSED | FS_MODE_NO_PERFLIB | FS_MODE_LAYERED)) != 0) FS_FAIL(FS_ERR_INVALID_ARG, "unknown mode %u", desc->mode);
   if (desc->lds_budget_bytes < 0 || desc->lds_budget_bytes > 65536)
     FS_FAIL(FS_ERR_INVALID_ARG, "lds_budget_bytes %d outside [0, 65536]", desc->lds_budget_bytes);
 

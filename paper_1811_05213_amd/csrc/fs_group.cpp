@@ -589,6 +589,102 @@ struct Former {
     }
   }
 
+  // ---- Work/Span analysis (Section 3.1) --------------------------------------------------------
+  // span = 0 for a node nothing live consumes (a root); otherwise 1 + the largest span among its
+  // users (broadcasts are looked through: they are inlined, not instructions of their own).
+  // Nodes of equal span form a layer and do not depend on each other.
+  std::vector<int> spans() const {
+    std::vector<int> span(g.n(), -1);
+    for (int id = g.n() - 1; id >= 0; --id) {
+      if (!live[id] || op_is_free(g.nodes[id].opcode)) continue;
+      std::vector<int> us;
+      real_users(id, &us);
+      int sp = 0;
+      for (int u : us) sp = std::max(sp, span[u] + 1);
+      span[id] = sp;
+    }
+    return span;
+  }
+
+  static bool is_elementwise(int op) { return op_is_unary(op) || op_is_binary(op) || op == FS_CMP || op == FS_SELECT; }
+
+  // ---- the layered planner: Section 3.2 as written ----------------------------------------------
+  // For every layer from the roots upwards: (1) intra-layer ElementwiseFusion of the layer's still
+  // unassigned elementwise nodes (schedule-compatible, fused footprint under the threshold);
+  // (2) for every fusion root of the layer, Algorithm 1: walk the layers above it, fuse a node
+  // when SchdConsistent holds, otherwise put it in `giveup`.
+  void plan_layered() {
+    constexpr uint64_t kFootprintThreshold = 16ull << 20;
+    const std::vector<int> span = spans();
+    int max_span = -1;
+    for (int sp : span) max_span = std::max(max_span, sp);
+    std::vector<std::vector<int>> layer(max_span + 1);
+    for (int id = 0; id < g.n(); ++id)
+      if (span[id] >= 0) layer[span[id]].push_back(id);
+    GroupPlan scratch;
+    for (int s = 0; s <= max_span; ++s) {
+      // (1) ElementwiseFusion among the unassigned nodes of this layer
+      std::vector<int> roots;  // group ids created in this layer
+      for (int id : layer[s]) {
+        if (group_of[id] >= 0) continue;
+        int joined = -1;
+        if (is_elementwise(g.nodes[id].opcode)) {
+          for (int grp : roots) {
+            if (!is_elementwise(g.nodes[members[grp][0]].opcode)) continue;
+            std::vector<int> merged = members[grp];
+            merged.push_back(id);
+            if (analyse_group(g, merged, group_of, grp, opt, &scratch) != FS_OK) continue;
+            if (scratch.min_hbm_bytes > kFootprintThreshold) continue;
+            joined = grp;
+            break;
+          }
+        }
+        if (joined < 0) {
+          joined = (int)members.size();
+          members.push_back({});
+          roots.push_back(joined);
+        }
+        group_of[id] = joined;
+        members[joined].push_back(id);
+      }
+      // (2) Algorithm 1 from every fusion root of this layer
+      for (int grp : roots) {
+        std::set<int> giveup;
+        for (int l = s + 1; l <= max_span; ++l) {
+          for (int hlo : layer[l]) {
+            if (group_of[hlo] >= 0) continue;
+            std::vector<int> us;
+            real_users(hlo, &us);
+            bool user_gave_up = false, user_fused = false;
+            for (int u : us) {
+              user_gave_up |= giveup.count(u) != 0;
+              user_fused |= group_of[u] == grp;
+            }
+            bool ok = !user_gave_up && user_fused;  // SchdConsistent, tests 1 and 2
+            if (ok) {
+              // (exact form of test 1 for users that already belong to other fused computations)
+              for (int u : us) {
+                const int h = group_of[u];
+                if (h >= 0 && h != grp && reaches(h, grp)) ok = false;
+              }
+            }
+            if (ok) {  // test 3: an optimised schedule (and LDS plan) for the fused computation exists
+              std::vector<int> merged = members[grp];
+              merged.push_back(hlo);
+              ok = (int)merged.size() <= 96 && analyse_group(g, merged, group_of, grp, opt, &scratch) == FS_OK && worth_fusing(scratch);
+            }
+            if (ok) {
+              group_of[hlo] = grp;
+              members[grp].push_back(hlo);
+            } else {
+              giveup.insert(hlo);
+            }
+          }
+        }
+      }
+    }
+  }
+
   fs_status topo_order(std::vector<std::vector<int>>* ordered) const {
     const int NG = (int)members.size();
     std::vector<std::set<int>> succ(NG);
@@ -651,6 +747,8 @@ fs_status form_groups(const Graph& g, const fs_graph_desc* desc, const PlanOptio
       f.group_of[id] = it->second;
       f.members[it->second].push_back(id);
     }
+  } else if (opt.layered) {
+    f.plan_layered();
   } else {
     for (int id = N - 1; id >= 0; --id) {
       if (!f.live[id] || op_is_free(g.nodes[id].opcode)) continue;
@@ -696,6 +794,13 @@ fs_status form_groups(const Graph& g, const fs_graph_desc* desc, const PlanOptio
   }
   *group_of = f.group_of;
   return f.topo_order(ordered);
+}
+
+void work_span(const Graph& g, std::vector<int>* span) {
+  PlanOptions opt;
+  Former f(g, opt);
+  f.mark_live();
+  *span = f.spans();
 }
 
 }  // namespace fs

@@ -126,6 +126,7 @@ struct PlanOptions {
   int lds_budget = 65536;
   fs_sched_hint hint = {0, 0, 0, 0};
   bool has_hint = false;
+  bool layered = false;  // group with the layered planner of Section 3.2 instead of the default one
 };
 
 // Analyse a candidate member set: work space, kinds, stages, external tensors, schedule, LDS plan.
@@ -138,6 +139,9 @@ fs_status analyse_group(const Graph& g, const std::vector<int>& members, const s
 // Assign every compute node to a group.  group_of[node] = group id or -1 for free nodes.
 fs_status form_groups(const Graph& g, const fs_graph_desc* desc, const PlanOptions& opt, std::vector<int>* group_of,
                       std::vector<std::vector<int>>* groups_in_launch_order);
+
+// Work/Span analysis (Section 3.1): span per node, -1 for inlined and dead nodes.
+void work_span(const Graph& g, std::vector<int>* span);
 
 // Emit the HIP source of one group's kernel (Section 5.2, Algorithm 2 realised as a
 // straight-line body over hand-written device building blocks).

@@ -134,6 +134,7 @@ fs_status fs_plan_create(const fs_graph_desc* desc, fs_plan** out_plan) {
     return st;
   }
   plan->opt.mode = desc->mode & FS_MODE_UNFUSED;
+  plan->opt.layered = (desc->mode & FS_MODE_LAYERED) != 0;
   const bool use_library = !(desc->mode & FS_MODE_NO_PERFLIB) && !desc->hint && perflib_size() > 0;
   plan->opt.lds_budget = desc->lds_budget_bytes > 0 ? desc->lds_budget_bytes : 65536;
   if (desc->hint) {
@@ -372,6 +373,15 @@ fs_status fs_plan_node_groups(const fs_plan* plan, int32_t* out, int32_t num_nod
   if (!plan || !out) FS_FAIL(FS_ERR_INVALID_ARG, "NULL argument");
   if (num_nodes != plan->graph.n()) FS_FAIL(FS_ERR_INVALID_ARG, "num_nodes %d, plan has %d", num_nodes, plan->graph.n());
   for (int i = 0; i < num_nodes; ++i) out[i] = plan->group_of[i];
+  return FS_OK;
+}
+
+fs_status fs_plan_node_spans(const fs_plan* plan, int32_t* out, int32_t num_nodes) {
+  if (!plan || !out) FS_FAIL(FS_ERR_INVALID_ARG, "NULL argument");
+  if (num_nodes != plan->graph.n()) FS_FAIL(FS_ERR_INVALID_ARG, "num_nodes %d, plan has %d", num_nodes, plan->graph.n());
+  std::vector<int> span;
+  work_span(plan->graph, &span);
+  for (int i = 0; i < num_nodes; ++i) out[i] = span[i];
   return FS_OK;
 }
 

@@ -336,3 +336,55 @@ def test_performance_library_drives_the_schedule(tmp_path, monkeypatch):
     p.destroy()
     p0.destroy()
     hinted.destroy()
+
+
+def test_work_span_and_layered_planner():
+    # Work/Span: roots have span 0, everything else 1 + the largest span of its users; a layer has no internal dependences
+    g = random_dag_graph()
+    p = fs.Plan(g, mode=fs.FS_MODE_LAYERED)
+    span = p.node_spans()
+    free = ("input", "const", "bcast_rowvec", "bcast_colvec")
+    users = {i: [] for i in range(len(g.nodes))}
+
+    def real_users(i):
+        out = []
+        for u in users[i]:
+            out += real_users(u) if g.nodes[u].op in free else [u]
+        return out
+    for i, n in enumerate(g.nodes):
+        for o in n.ins:
+            users[o].append(i)
+    live = [s >= 0 for s in span]
+    for i, n in enumerate(g.nodes):
+        if n.op in free:
+            assert span[i] == -1
+            continue
+        if not live[i]:
+            continue
+        us = [u for u in real_users(i) if live[u]]
+        assert span[i] == (1 + max(span[u] for u in us) if us else 0)
+        for o in n.ins:
+            assert g.nodes[o].op in free or span[o] > span[i]
+    assert all(span[o] >= 0 for o in g.outputs) and min(span[o] for o in g.outputs) == 0
+    # the layered plan is a valid plan: every live compute node in exactly one group, launch order respects dependences
+    grp = p.node_groups()
+    for i, n in enumerate(g.nodes):
+        if n.op not in free and live[i]:
+            assert grp[i] >= 0
+            for o in n.ins:
+                src = o
+                while g.nodes[src].op in ("bcast_rowvec", "bcast_colvec"):
+                    src = g.nodes[src].ins[0]
+                if g.nodes[src].op not in free:
+                    assert grp[src] <= grp[i]
+    d = fs.Plan(g)
+    # the default planner (exact cycle test, any user's group, sibling merging across layers) needs far fewer launches
+    assert d.stats()["num_launches"] < p.stats()["num_launches"] <= len(g.compute_ids())
+    assert d.node_spans() == span
+    p.destroy()
+    d.destroy()
+    # on the chain-like workloads both planners find the single kernel
+    for g2 in (softmax_graph(300, 1000), layernorm_gelu_graph(77, 1024), elementwise20_graph(64, 1024)):
+        p = fs.Plan(g2, mode=fs.FS_MODE_LAYERED)
+        assert p.stats()["num_launches"] == 1
+        p.destroy()

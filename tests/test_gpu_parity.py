@@ -418,3 +418,11 @@ def test_tuning_fills_the_library_and_tuned_plans_match_the_oracle(tmp_path, mon
         check_all(g, out, ref, name + " tuned plan")
     text = (tmp_path / "perflib.tsv").read_text()
     assert text.count("\t") >= 10 and "lanes/row" in text
+
+
+def test_layered_planner_results_match_the_oracle():
+    for cfg, rows in ((5, None), (6, 300), (4, 3000)):
+        g, ins, name = workload(cfg, rows)
+        ref = oracle.run(g, ins, THREADS)
+        out = run_graph(g, ins, mode=fs.FS_MODE_LAYERED)
+        check_all(g, out, ref, name + " layered planner")
