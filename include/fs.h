@@ -143,7 +143,8 @@ typedef struct {
   int32_t lanes_per_row;
   int32_t wg_threads;
   int32_t max_workgroups;
-  int32_t reserved;
+  int32_t tiles_per_trip; /* looping kernels: row tiles handled per loop trip (1..4), the loads of all of
+                             them issued before the first is used */
 } fs_sched_hint;
 
 typedef struct {

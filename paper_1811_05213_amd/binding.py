@@ -42,7 +42,7 @@ class fs_node(ctypes.Structure):
 
 class fs_sched_hint(ctypes.Structure):
     _fields_ = [("lanes_per_row", ctypes.c_int32), ("wg_threads", ctypes.c_int32),
-                ("max_workgroups", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+                ("max_workgroups", ctypes.c_int32), ("tiles_per_trip", ctypes.c_int32)]
 
 
 class fs_graph_desc(ctypes.Structure):
@@ -156,7 +156,8 @@ class Plan:
         desc.lds_budget_bytes = lds_budget_bytes
         h = None
         if hint:
-            h = fs_sched_hint(hint.get("lanes_per_row", 0), hint.get("wg_threads", 0), hint.get("max_workgroups", 0), 0)
+            h = fs_sched_hint(hint.get("lanes_per_row", 0), hint.get("wg_threads", 0), hint.get("max_workgroups", 0),
+                              hint.get("tiles_per_trip", 0))
             desc.hint = ctypes.pointer(h)
         self._h = ctypes.c_void_p()
         self._run = lib().fs_plan_run

@@ -209,7 +209,7 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
     s.grid = s.RB * CT;
   }
   s.U = 1;  // (two tiles per trip measured no faster than one with 16 elements per lane)
-  if (const char* env = getenv("FS_DEBUG_UNROLL")) s.U = std::max(1, atoi(env));
+  if (opt.has_hint && opt.hint.tiles_per_trip >= 1 && opt.hint.tiles_per_trip <= 4) s.U = opt.hint.tiles_per_trip;
   // two fold levels at most: the smallest fan-in whose square covers the grid
   s.fan_in = s.RB <= 64 ? 8 : s.RB <= 256 ? 16 : 32;
 
@@ -414,6 +414,8 @@ std::vector<fs_sched_hint> candidate_hints(const GroupPlan& base) {
         if (L == s.L && WG == s.WG && cap == 0) continue;  // the base schedule itself
         out.push_back(fs_sched_hint{L, WG, cap, 0});
       }
+  // looping kernels: two row tiles per trip with the base shape
+  if (s.grid < s.n_iters && s.CT == 1 && s.U == 1) out.push_back(fs_sched_hint{s.L, s.WG, 0, 2});
   return out;
 }
 

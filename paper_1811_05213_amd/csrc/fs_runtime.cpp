@@ -141,7 +141,7 @@ fs_status fs_plan_create(const fs_graph_desc* desc, fs_plan** out_plan) {
     plan->opt.hint = *desc->hint;
     plan->opt.has_hint = true;
     const fs_sched_hint& h = plan->opt.hint;
-    if (h.lanes_per_row < 0 || h.wg_threads < 0 || h.max_workgroups < 0) {
+    if (h.lanes_per_row < 0 || h.wg_threads < 0 || h.max_workgroups < 0 || h.tiles_per_trip < 0) {
       delete plan;
       FS_FAIL(FS_ERR_INVALID_ARG, "negative schedule hint");
     }
@@ -402,7 +402,9 @@ fs_status fs_plan_group_kernel_name(const fs_plan* plan, int32_t group, const ch
 fs_status fs_plan_group_perf_key(const fs_plan* plan, int32_t group, const char** out_key) {
   if (!plan || !out_key) FS_FAIL(FS_ERR_INVALID_ARG, "NULL argument");
   if (group < 0 || group >= (int)plan->groups.size()) FS_FAIL(FS_ERR_INVALID_ARG, "group %d out of range", group);
-  GroupPlan& gp = const_cast<fs_plan*>(plan)->groups[group];
+  fs_plan* p = const_cast<fs_plan*>(plan);
+  std::lock_guard<std::mutex> lk(p->mu);
+  GroupPlan& gp = p->groups[group];
   if (gp.perf_key.empty()) gp.perf_key = perf_key(gp);
   *out_key = gp.perf_key.c_str();
   return FS_OK;

@@ -270,15 +270,13 @@ def test_ragged_rows_with_staged_vectors_and_bf16():
         both_modes(g, ins, f"layernorm {rows}x{cols}")
 
 
-def test_unrolled_row_loop(monkeypatch):
+def test_unrolled_row_loop():
     # looping (column-reduction) kernels with two and three row tiles per trip
     g, ins, name = workload(4, 5000)
     ref = oracle.run(g, ins, THREADS)
-    for u in ("2", "3"):
-        monkeypatch.setenv("FS_DEBUG_UNROLL", u)
-        out = run_graph(g, ins, hint={"max_workgroups": 7})
+    for u in (2, 3):
+        out = run_graph(g, ins, hint={"max_workgroups": 7, "tiles_per_trip": u})
         check_all(g, out, ref, f"{name} unroll {u}")
-    monkeypatch.delenv("FS_DEBUG_UNROLL")
 
 
 # ------------------------------------------------------------------ determinism and schedule invariance
