@@ -20,6 +20,7 @@
 //     rounds).
 #include <algorithm>
 #include <cstring>
+#include <functional>
 #include <set>
 #include <sstream>
 
@@ -268,7 +269,9 @@ struct Emitter {
   void emit_pass(const std::set<int>& mem, const std::set<int>& ext, bool store_outputs, Tail tail) {
     if (n_passes++ % 2 == 0) os << "    for (int ch = 0; ch < CT; ++ch) {\n";
     else os << "    for (int ch = CT - 1; ch >= 0; --ch) {\n";
-    os << "      const int vbase = ch * (NVL * L);\n";
+    // (inside a pass the chunk's own sizes shadow the body's: the building blocks read them by name)
+    os << "      constexpr int NVL = NVLC, E = NVLC * V;\n      constexpr bool RAGGED = RAGC;\n"
+       << "      const int vbase = RESV + ch * (NVL * L);\n      (void)RAGGED;\n";
     for (const ExtTensor& e : gp.ext_in) {
       if (!ext.count(e.node)) continue;
       os << "      float " << name(e.node, e.kind) << "[E];\n";
@@ -298,6 +301,25 @@ struct Emitter {
     os << "    }\n";
   }
 
+  // inside a pass: fold the chunk's elements into the running lane partials q<b> of the stage's reductions
+  void emit_chunk_accumulate(const std::vector<int>& batch) {
+    const std::string col_ok = "(!RAGGED || (vbase + (e / V) * L + lir) < NV)";
+    for (int b : batch) {
+      const fs_node& bn = g.nodes[b];
+      const std::string q = "q" + std::to_string(loc(b));
+      if (folded[bn.in[0]]) {
+        const fs_node& mn = g.nodes[bn.in[0]];
+        os << "      _Pragma(\"unroll\") for (int e = 0; e < E; ++e) " << q << " = " << col_ok << " ? __builtin_fmaf(" << ref(mn.in[0]) << ", "
+           << ref(mn.in[1]) << ", " << q << ") : " << q << ";\n";
+      } else {
+        os << "      {\n";
+        const std::string arr = as_array(bn.in[0], std::to_string(loc(b)));
+        os << "      " << q << " = fs_red_op<" << bn.attr_i << ">(" << q << ", fs_lane_reduce<" << bn.attr_i << ", " << tmpl_row() << ">(" << arr
+           << ", lir, vbase));\n      }\n";
+      }
+    }
+  }
+
   void run_chunked(bool xwave, int WPR, int KB) {
     auto is_rr = [&](int m) { return std::find(gp.row_reduces.begin(), gp.row_reduces.end(), m) != gp.row_reduces.end(); };
     int max_level = 0;
@@ -307,7 +329,6 @@ struct Emitter {
        << "    (void)row0; (void)rok; (void)vbase;\n";
     for (const ExtTensor& e : gp.ext_in)
       if (e.kind == KIND_COLV) os << "    const float " << name(e.node, KIND_COLV) << " = fs_load1<" << e.dtype << ">(a.p[" << e.arg << "], row);\n";
-    const std::string col_ok = "(!RAGGED || (vbase + (e / V) * L + lir) < NV)";
     for (int lvl = 0; lvl <= max_level + 1; ++lvl) {
       // per-row values of this stage (they depend on earlier reductions only)
       for (int m : gp.members) {
@@ -323,22 +344,7 @@ struct Emitter {
       std::set<int> mem, ext;
       needed_for(batch, &mem, &ext);
       for (int b : batch) os << "    float q" << loc(b) << " = fs_red_identity<" << g.nodes[b].attr_i << ">();\n";
-      emit_pass(mem, ext, false, [&]() {
-        for (int b : batch) {
-          const fs_node& bn = g.nodes[b];
-          const std::string q = "q" + std::to_string(loc(b));
-          if (folded[bn.in[0]]) {
-            const fs_node& mn = g.nodes[bn.in[0]];
-            os << "      _Pragma(\"unroll\") for (int e = 0; e < E; ++e) " << q << " = " << col_ok << " ? __builtin_fmaf(" << ref(mn.in[0])
-               << ", " << ref(mn.in[1]) << ", " << q << ") : " << q << ";\n";
-          } else {
-            os << "      {\n";
-            const std::string arr = as_array(bn.in[0], std::to_string(loc(b)));
-            os << "      " << q << " = fs_red_op<" << bn.attr_i << ">(" << q << ", fs_lane_reduce<" << bn.attr_i << ", " << tmpl_row() << ">(" << arr
-               << ", lir, vbase));\n      }\n";
-          }
-        }
-      });
+      emit_pass(mem, ext, false, [&]() { emit_chunk_accumulate(batch); });
       emit_exchange(batch, xwave, WPR, KB, "    ");
     }
     // last pass: everything that leaves the kernel as an [R,C] or [1,C] tensor
@@ -393,8 +399,12 @@ struct Emitter {
     os << "  (void)lir; (void)rg; (void)R; (void)C; (void)G; (void)CT;\n";
     if (xwave) os << "  __shared__ float lds_rr[2 * G * " << WPR << " * " << KB << "];\n  int parity = 0;\n";
     if (s.chunked) {
-      run_chunked(xwave, WPR, KB);
-      return;
+      os << "  constexpr int NVLC = " << s.NVLC << ", RESV = " << s.RESV << ";\n  constexpr bool RAGC = " << (s.ragged_chunks ? "true" : "false")
+         << ";\n";
+      if (!s.resident) {
+        run_chunked(xwave, WPR, KB);
+        return;
+      }
     }
     // CW columns are folded together: the whole row, or one column tile
     os << "  constexpr int CW = " << (ctile ? "NVL * L * V" : "C") << ", NVF = CW / V, RB = " << s.RB << ";\n";
@@ -464,7 +474,7 @@ struct Emitter {
       if (U > 1) os << "    const int it" << x << " = it0 + " << u << ";\n";
       if (ctile) {
         os << "    const long row = (long)it * G + rg;\n";
-      } else if (s.CT == 1) {
+      } else if (s.CT == 1 || s.resident) {
         os << "    const long row" << x << " = (long)it" << x << " * G + rg;\n    constexpr int vbase" << x << " = 0;\n";
       } else {
         os << "    const long unit = (long)it * G + rg;\n    const long row = unit / CT;\n    const int vbase = (int)(unit % CT) * (NVL * L);\n";
@@ -482,7 +492,25 @@ struct Emitter {
         }
       }
     }
-    if (rowv_in_loop) emit_rowv("    ", "vbase", "row == 0 && rok");
+    // With more than 32 elements per lane the per-column values are loaded where they are first
+    // needed, not at the top of the body: the row itself already takes half of the register file.
+    const bool late_rowv = rowv_in_loop && s.E > 32;
+    bool rowv_done = !rowv_in_loop;
+    if (rowv_in_loop && !late_rowv) {
+      emit_rowv("    ", "vbase", "row == 0 && rok");
+      rowv_done = true;
+    }
+    std::function<bool(int)> uses_rowv = [&](int m) {
+      const fs_node& n = g.nodes[m];
+      for (int k = 0; k < n.num_in; ++k) {
+        if (g.nodes[n.in[k]].opcode == FS_CONST) continue;
+        const int src = source_of(n.in[k]);
+        if (g.nodes[src].opcode == FS_CONST) continue;
+        if (gp.kind.at(src) == KIND_ROWV) return true;
+        if (in_set[src] && folded[src] && uses_rowv(src)) return true;
+      }
+      return false;
+    };
 
     // members in stage order; the row reductions of a stage come last and share one exchange
     std::vector<int> order;
@@ -510,6 +538,10 @@ struct Emitter {
     while (i < order.size()) {
       const int m = order[i];
       const fs_node& n = g.nodes[m];
+      if (!rowv_done && uses_rowv(m)) {
+        emit_rowv("    ", "vbase", "row == 0 && rok");
+        rowv_done = true;
+      }
       if (is_rr(m)) {
         // batch: every row reduction of this stage
         std::vector<int> batch;
@@ -527,7 +559,15 @@ struct Emitter {
             const std::string arr = as_array(bn.in[0], std::to_string(loc(b)));
             os << "    float " << q << " = fs_lane_reduce<" << bn.attr_i << ", " << tmpl_row() << ">(" << arr << ", lir);\n";
           }
-          os << "    " << q << " = fs_segment_allreduce<" << bn.attr_i << ", (L < 64 ? L : 64)>(" << q << ");\n";
+        }
+        if (s.resident) {  // the part of the row that is not resident: walked in chunks, recomputed from the inputs
+          std::set<int> mem, ext;
+          needed_for(batch, &mem, &ext);
+          emit_pass(mem, ext, false, [&]() { emit_chunk_accumulate(batch); });
+        }
+        for (int b : batch) {
+          const std::string q = "q" + std::to_string(loc(b));
+          os << "    " << q << " = fs_segment_allreduce<" << g.nodes[b].attr_i << ", (L < 64 ? L : 64)>(" << q << ");\n";
         }
         if (xwave) {
           os << "    {\n      const fs_xwave<" << KB << ", " << WPR << "> xw{lds_rr + (parity * G + rg) * " << WPR * KB
@@ -578,6 +618,17 @@ struct Emitter {
       if (const ExtTensor* e = find_out(m)) emit_store(*e, "    ");
     }
       if (U > 1) os << "    }\n";
+    }
+    if (!rowv_done) emit_rowv("    ", "vbase", "row == 0 && rok");
+    if (s.resident) {  // last pass over the non-resident part: everything that leaves as an [R,C] or [1,C] tensor
+      std::vector<int> roots;
+      for (const ExtTensor& e : gp.ext_out)
+        if (e.kind != KIND_COLV) roots.push_back(e.node);
+      if (!roots.empty()) {
+        std::set<int> mem(roots.begin(), roots.end()), ext;
+        needed_for(roots, &mem, &ext);
+        emit_pass(mem, ext, true, []() {});
+      }
     }
     os << "  }\n";
 

@@ -124,6 +124,16 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   const bool tileable = !rowred && !colred;
   bool has_transposed = false;
   for (const ExtTensor& e : gp->ext_out) has_transposed |= e.transposed;
+  // A row that no longer fits 32 elements per lane of a 1024-lane workgroup may still fit 64: one
+  // workgroup per CU then, but the row is read once instead of once per stage.  Beyond that, the
+  // first 64 elements per lane stay resident and only the rest of the row is walked in chunks.
+  bool resident = false;
+  if (rowred && !colred && !has_transposed && l_min > 1024 && opt.wide_level > 0) {
+    const int e64 = std::max(64, V);
+    const int l64 = pow2_ceil((NV + e64 / V - 1) / (e64 / V));
+    if (l64 <= 1024 && opt.wide_level >= 2) ecap = e64, l_min = l64;
+    else resident = true;
+  }
   // Row reductions over rows that do not fit the registers of one workgroup: the workgroup walks
   // its row in column chunks, once per stage, recomputing what each stage needs.
   const bool chunked = l_min > 1024 && rowred && !colred && !has_transposed;
@@ -153,9 +163,12 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
     NVL = std::max(1, ecap / V);
     CT = (NV + NVL * L - 1) / (NVL * L);
   }
+  int NVLC = 0, RESV = 0;
   if (chunked || col_tiled) {
-    NVL = std::max(1, 16 / V);
-    CT = (NV + NVL * L - 1) / (NVL * L);
+    NVLC = std::max(1, 16 / V);
+    NVL = resident ? std::max(1, (opt.wide_level >= 2 ? 48 : 32) / V) : NVLC;  // (64 resident elements plus a chunk in flight spill)
+    RESV = resident ? NVL * L : 0;
+    CT = (NV - RESV + NVLC * L - 1) / (NVLC * L);
   }
 
   int WG;
@@ -192,7 +205,11 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   s.E = s.NVL * V;
   s.WG = WG;
   s.G = WG / L;
-  s.ragged = (int64_t)CT * NVL * L != NV;
+  s.ragged = resident ? false : (int64_t)CT * NVL * L != NV;
+  s.resident = resident;
+  s.NVLC = NVLC;
+  s.RESV = RESV;
+  s.ragged_chunks = chunked && (int64_t)RESV + (int64_t)CT * NVLC * L != NV;
   s.chunked = chunked;
   s.col_tiled = col_tiled;
   s.n_iters = chunked ? R : col_tiled ? (R + s.G - 1) / s.G : (int)(((int64_t)R * CT + s.G - 1) / s.G);

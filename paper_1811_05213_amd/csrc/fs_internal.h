@@ -92,6 +92,11 @@ struct Schedule {
   // column chunks once per stage, and each stage recomputes the elementwise values it needs from
   // the inputs instead of keeping them (space traded for recomputation, Section 5.1.2).
   bool chunked = false;
+  // ... optionally with the first RESV vectors of the row resident in registers for the whole
+  // body (64 elements per lane), so only the rest is walked, NVLC vectors per lane per chunk.
+  bool resident = false;
+  int NVLC = 0, RESV = 0;
+  bool ragged_chunks = false;
   // Column reductions over rows too wide for one workgroup: CT column tiles, each folded by its own
   // RB = grid / CT workgroups (tile = block % CT).  Strides of one tile's scratch in the workspace:
   bool col_tiled = false;
@@ -126,6 +131,10 @@ struct PlanOptions {
   int lds_budget = 65536;
   fs_sched_hint hint = {0, 0, 0, 0};
   bool has_hint = false;
+  // How much of a row longer than 32 elements per lane may stay in registers: 2 = up to 64 elements
+  // per lane (or 48 resident ones plus chunks), 1 = 32 resident ones plus chunks, 0 = chunks only.
+  // Plan creation steps down while the compiled kernel spills.
+  int wide_level = 2;
   bool layered = false;  // group with the layered planner of Section 3.2 instead of the default one
 };
 

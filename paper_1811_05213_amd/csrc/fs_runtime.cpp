@@ -113,6 +113,25 @@ fs_status compile_kernel(const std::string& source, const std::string& name, std
   return FS_OK;
 }
 
+// Largest scratch (register spill) size among the kernels of a code object, read from its
+// metadata note: the msgpack integer that follows each ".private_segment_fixed_size" key.
+long code_object_scratch_bytes(const std::vector<char>& code) {
+  static const char key[] = ".private_segment_fixed_size";
+  const size_t klen = sizeof(key) - 1;
+  long worst = 0;
+  for (size_t i = 0; i + klen + 5 <= code.size(); ++i) {
+    if (code[i] != '.' || memcmp(code.data() + i, key, klen) != 0) continue;
+    const unsigned char* p = (const unsigned char*)code.data() + i + klen;
+    long v = -1;
+    if (p[0] <= 0x7f) v = p[0];
+    else if (p[0] == 0xcc) v = p[1];
+    else if (p[0] == 0xcd) v = ((long)p[1] << 8) | p[2];
+    else if (p[0] == 0xce) v = ((long)p[1] << 24) | ((long)p[2] << 16) | ((long)p[3] << 8) | p[4];
+    if (v > worst) worst = v;
+  }
+  return worst;
+}
+
 }  // namespace fs
 
 using namespace fs;
@@ -164,6 +183,25 @@ fs_status fs_plan_create(const fs_graph_desc* desc, fs_plan** out_plan) {
     if (st != FS_OK) {
       delete plan;
       return st;
+    }
+    // A row held with more than 32 elements per lane leaves little room for anything else: when
+    // the compiled kernel spills, the group is planned again with the row walked in chunks.
+    GroupPlan& gp = plan->groups[gi];
+    for (int level = plan->opt.wide_level - 1; level >= 0 && gp.s.E > 16 && (gp.s.E > 32 || gp.s.resident) && !gp.row_reduces.empty(); --level) {
+      std::vector<char> code;
+      st = compile_kernel(std::string(device_header_source()) + "\n" + gp.source, gp.kernel_name, &code);
+      if (st == FS_OK && code_object_scratch_bytes(code) > 0) {
+        PlanOptions narrow = plan->opt;
+        narrow.wide_level = level;
+        st = analyse_group(g, ordered[gi], plan->group_of, (int)gi, narrow, &gp);
+        if (st == FS_OK) st = generate_kernel(g, &gp, (int)gi);
+      } else {
+        level = -1;  // fits (or failed): stop
+      }
+      if (st != FS_OK) {
+        delete plan;
+        return st;
+      }
     }
     // schedule tuning: the fastest candidate the performance library knows (Sections 4.3, 4.4)
     if (use_library) choose_from_library(g, ordered[gi], plan->group_of, (int)gi, plan->opt, &plan->groups[gi]);

@@ -279,6 +279,14 @@ def test_ragged_and_degenerate_shapes_plan():
     src = p.group_source(0)
     assert src.count("const int vbase = ch * (NVL * L);") == 3  # max pass, sum pass, output pass
     p.destroy()
+    # between 32768 and 65536 columns a softmax row still fits the registers (64 elements per lane); LayerNorm+GeLU with its
+    # three per-column vectors would spill there, which plan creation detects from the compiled kernel: chunks again
+    p = fs.Plan(softmax_graph(4, 65536))
+    assert p.group_info(0)["elems_per_lane"] == 64 and "ch" not in re.findall(r"for \(int (\w+) = ", p.group_source(0))
+    p.destroy()
+    p = fs.Plan(layernorm_gelu_graph(4, 65536))
+    assert p.group_info(0)["elems_per_lane"] == 16 and "ch" in re.findall(r"for \(int (\w+) = ", p.group_source(0))
+    p.destroy()
     # column reductions over wide rows run by column tiles
     gw = Graph()
     xw = gw.input(100, 50000)
