@@ -439,7 +439,7 @@ std::vector<fs_sched_hint> candidate_hints(const GroupPlan& base) {
 bool choose_from_library(const Graph& g, const std::vector<int>& members, const std::vector<int>& group_of, int self_group,
                          const PlanOptions& opt, GroupPlan* gp) {
   // a candidate has to beat the analytic schedule by more than the noise of the measurement
-  constexpr double kMargin = 0.97;
+  constexpr double kMargin = 0.95;
   double best = 0.0;
   const bool base_known = perflib_lookup(perf_key(*gp), &best);
   best *= kMargin;

@@ -331,8 +331,8 @@ def test_performance_library_drives_the_schedule(tmp_path, monkeypatch):
     p = fs.Plan(g, hint={"wg_threads": base["wg_threads"]})
     assert p.group_info(0)["lanes_per_row"] == base["lanes_per_row"]
     p.destroy()
-    # a candidate inside the measurement noise (3 %) does not displace the analytic schedule
-    lib_file.write_text(f"{k0}\t10.0\n{k1}\t9.8\n")
+    # a candidate inside the measurement noise (5 %) does not displace the analytic schedule
+    lib_file.write_text(f"{k0}\t10.0\n{k1}\t9.6\n")
     p = fs.Plan(g)
     assert p.group_perf_key(0) == k0
     p.destroy()
