@@ -430,3 +430,15 @@ def test_layered_planner_results_match_the_oracle():
         ref = oracle.run(g, ins, THREADS)
         out = run_graph(g, ins, mode=fs.FS_MODE_LAYERED)
         check_all(g, out, ref, name + " layered planner")
+
+
+@pytest.mark.parametrize("seed,rows,ks", [(11, 33, (8, 24)), (12, 200, (36, 100)), (13, 512, (64, 128, 256)), (14, 1000, (4, 1024)),
+                                          (15, 77, (130, 2)), (16, 2048, (512,))])
+def test_random_dags_other_seeds_and_shapes(seed, rows, ks):
+    # the benchmark's DAG generator with other seeds, row counts and column widths (ragged, tiny and wide), three planners
+    g = random_dag_graph(num_nodes=120, rows=rows, ks=ks, seed=seed)
+    ins = random_dag_inputs(g)
+    ref = oracle.run(g, ins, THREADS)
+    for mode, label in ((fs.FS_MODE_STITCHED, "stitched"), (fs.FS_MODE_LAYERED, "layered"), (fs.FS_MODE_UNFUSED, "unfused")):
+        out = run_graph(g, ins, mode=mode)
+        check_all(g, out, ref, f"random dag seed {seed} rows {rows} ks {ks} {label}")
