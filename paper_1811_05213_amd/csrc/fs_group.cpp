@@ -219,6 +219,7 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   // grid because every workgroup leaves a partial to fold.
   int cap = colred ? 256 : (1 << 30);
   if (opt.has_hint && opt.hint.max_workgroups > 0) cap = opt.hint.max_workgroups;
+  cap = std::min(cap, (int)(0x7fffffff / WG));  // a launch holds fewer than 2^31 lanes: beyond that the workgroups loop
   s.grid = std::max(1, std::min(s.n_iters, cap));
   s.RB = s.grid;
   if (col_tiled) {  // RB workgroups per column tile, about `cap` workgroups in all

@@ -346,6 +346,18 @@ def test_performance_library_drives_the_schedule(tmp_path, monkeypatch):
     hinted.destroy()
 
 
+def test_huge_row_counts_stay_inside_the_launch_limits():
+    # one workgroup per row tile until a launch would hold 2^31 lanes; then the workgroups loop over tiles
+    g = Graph()
+    x = g.input(1 << 28, 4)
+    g.set_outputs([g.unary("exp", x)])
+    p = fs.Plan(g)
+    gi = p.group_info(0)
+    tiles = -(-(1 << 28) // gi["rows_per_iter"])
+    assert gi["grid"] * gi["wg_threads"] < 2 ** 31 and gi["grid"] <= tiles
+    p.destroy()
+
+
 def test_work_span_and_layered_planner():
     # Work/Span: roots have span 0, everything else 1 + the largest span of its users; a layer has no internal dependences
     g = random_dag_graph()

@@ -255,6 +255,37 @@ def test_full_size_elementwise20_on_sampled_rows():
     assert all(np.isfinite(o).all() for o in out)
 
 
+def test_tensors_beyond_two_to_the_31_elements_on_sampled_rows():
+    # 2.16e9 elements (8.7 GB) per tensor: element indices and byte offsets past 32 bits.  The input is drawn on the
+    # device (seeded); the oracle evaluates a sample of rows, which is exact because every op here is row-independent.
+    import torch
+    rows, cols = (1 << 21) + 3, 1032
+
+    def build(r):
+        g = Graph()
+        x = g.input(r, cols)
+        y = g.binary("mul", g.unary("tanh", x), x)
+        g.set_outputs([y, g.reduce_row("sum", y), g.binary("sub", y, g.bcast_colvec(g.reduce_row("max", x), cols))])
+        return g
+    g = build(rows)
+    plan = fs.Plan(g)
+    assert plan.stats()["num_launches"] == 1
+    r = DeviceRun(plan)
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(181105213)
+    x = torch.empty((rows, cols), dtype=torch.float32, device="cuda:0").uniform_(-2, 2, generator=gen)
+    r.set_device_inputs([x])
+    r.launch()
+    torch.cuda.synchronize()
+    pick = np.unique(np.concatenate([[0, 1, (1 << 20) - 1, 1 << 20, (1 << 21) - 1, 1 << 21, rows - 1], RNG.integers(0, rows, 300)]))
+    idx = torch.from_numpy(pick).to("cuda:0")
+    xs = x[idx].cpu().numpy()
+    ref = oracle.run(build(len(pick)), [xs], THREADS)
+    got = [t[idx].cpu().numpy() for t in r.outputs]
+    check_all(build(len(pick)), got, ref, "2^31+ elements, sampled rows")
+    plan.destroy()
+
+
 def test_elementwise20_predicate_bit_exact():
     rows = 300
     g = elementwise20_graph(rows, 1024)
