@@ -411,13 +411,18 @@ struct Emitter {
     if (ctile) os << "  const int tile = (int)blockIdx.x % CT, rb = (int)blockIdx.x / CT, vbase = tile * (NVL * L);\n";
     else os << "  const int tile = 0, rb = (int)blockIdx.x;\n";
     os << "  (void)tile; (void)rb; (void)CW; (void)NVF; (void)RB;\n";
-    if (K > 0) os << "  __shared__ float lds_col[(L < 64 ? WG / 64 : G) * CW];\n  __shared__ fs_u32 lds_flag;\n";
-    if (s.tile_transpose) os << "  __shared__ float lds_tile[C * (G + 1)];\n";
-    if (s.stage_rowv) {
-      int n_rowv = 0;
-      for (const ExtTensor& e : gp.ext_in) n_rowv += e.kind == KIND_ROWV;
-      os << "  constexpr int SLOT = NVL * L * V;\n  __shared__ float lds_rowv[" << n_rowv << " * SLOT];\n";
+    // One LDS pool, shared by lifetime: the row loop's buffers (transpose tile, staged [1,C]
+    // operands) and the epilogue's column-fold area never live at the same time.
+    int n_rowv = 0;
+    for (const ExtTensor& e : gp.ext_in) n_rowv += e.kind == KIND_ROWV;
+    if (K > 0 || s.tile_transpose || s.stage_rowv) {
+      os << "  constexpr int SLOT = NVL * L * V, TILE_FLOATS = " << (s.tile_transpose ? "C * (G + 1)" : "0") << ", LOOP_FLOATS = TILE_FLOATS + "
+         << (s.stage_rowv ? n_rowv : 0) << " * SLOT, FOLD_FLOATS = " << (K > 0 ? "(L < 64 ? WG / 64 : G) * CW" : "0") << ";\n";
+      os << "  __shared__ float lds_pool[LOOP_FLOATS > FOLD_FLOATS ? LOOP_FLOATS : FOLD_FLOATS];\n";
+      os << "  float* const lds_tile = lds_pool; float* const lds_rowv = lds_pool + TILE_FLOATS; float* const lds_col = lds_pool;\n";
+      os << "  (void)lds_tile; (void)lds_rowv; (void)lds_col; (void)SLOT;\n";
     }
+    if (K > 0) os << "  __shared__ fs_u32 lds_flag;\n";
 
     // ---- per-column values ----
     auto emit_rowv = [&](const std::string& ind, const std::string& vb, const std::string& store_cond) {

@@ -239,25 +239,35 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   // reductions of the kernel reuse one ping-pong pair of slots instead of one buffer each (the
   // Reduce.2-reuses-Reduce.1 case of Section 5.1.3); the column fold area is shared by all column
   // reductions in turn.
-  int lds = 0;
-  if (rowred && L > 64) lds += 2 * s.G * (L / 64) * gp->max_batched_reduces * 4;
+  // Space sharing by lifetime (the idea of Section 5.1.3 applied to the kernel's two phases): what
+  // the row loop uses (transpose tile, staged [1,C] operands) is dead when the epilogue folds the
+  // column partials, so both live in one pool of max(loop bytes, fold bytes).
+  int fixed = 0, loop_bytes = 0, fold_bytes = 0;
+  if (rowred && L > 64) fixed += 2 * s.G * (L / 64) * gp->max_batched_reduces * 4;
   const int fold_width = col_tiled ? NVL * L * V : C;  // columns one workgroup folds
-  if (colred) lds += (L < 64 ? WG / 64 : s.G) * fold_width * 4 + 16;
+  if (colred) {
+    fixed += 16;
+    fold_bytes = (L < 64 ? WG / 64 : s.G) * fold_width * 4;
+  }
+  auto total = [&]() { return fixed + std::max(loop_bytes, fold_bytes); };
   // [1,C] inputs shared by all rows of a workgroup: with one trip per workgroup they are staged in
   // LDS by the whole workgroup when several rows share them and the budget allows
   int n_rowv = 0;
   for (const ExtTensor& e : gp->ext_in) n_rowv += e.kind == KIND_ROWV;
   s.stage_rowv = false;
   s.tile_transpose = false;
-  if (has_transposed && CT == 1 && s.G >= 4 && lds + C * (s.G + 1) * 4 <= opt.lds_budget) {
+  const int tile_bytes = C * (s.G + 1) * 4;
+  if (has_transposed && CT == 1 && s.G >= 4 && fixed + std::max(loop_bytes + tile_bytes, fold_bytes) <= opt.lds_budget) {
     s.tile_transpose = true;
-    lds += C * (s.G + 1) * 4;
+    loop_bytes += tile_bytes;
   }
   const int slot_bytes = s.NVL * s.L * V * 4;
-  if (n_rowv > 0 && CT == 1 && s.grid >= s.n_iters && s.G >= 4 && R > 1 && lds + n_rowv * slot_bytes <= opt.lds_budget) {
+  if (n_rowv > 0 && CT == 1 && s.grid >= s.n_iters && s.G >= 4 && R > 1 &&
+      fixed + std::max(loop_bytes + n_rowv * slot_bytes, fold_bytes) <= opt.lds_budget) {
     s.stage_rowv = true;
-    lds += n_rowv * slot_bytes;
+    loop_bytes += n_rowv * slot_bytes;
   }
+  const int lds = total();
   s.lds_bytes = lds;
   if (lds > opt.lds_budget)
     FS_FAIL(FS_ERR_LDS_BUDGET, "group needs %d bytes of LDS, budget is %d", lds, opt.lds_budget);
