@@ -497,26 +497,63 @@ struct Emitter {
         }
       }
     }
-    // With more than 32 elements per lane the per-column values are loaded where they are first
-    // needed, not at the top of the body: the row itself already takes half of the register file.
-    const bool late_rowv = rowv_in_loop && s.E > 32;
+    // Inside the loop body every per-column value is made available right before its first use,
+    // one tensor at a time (a [1,C] operand costs E registers from its load to its last use; three
+    // of them loaded at the top of a LayerNorm body with 32 elements per lane spill).  Staged
+    // operands are written to LDS up front; only their reads into registers are lazy.
+    std::set<int> rowv_ready;
+    const bool lazy_rowv = rowv_in_loop && getenv("FS_EAGER_ROWV") == nullptr;
     bool rowv_done = !rowv_in_loop;
-    if (rowv_in_loop && !late_rowv) {
+    if (rowv_in_loop && !lazy_rowv) {
       emit_rowv("    ", "vbase", "row == 0 && rok");
       rowv_done = true;
     }
-    std::function<bool(int)> uses_rowv = [&](int m) {
+    if (lazy_rowv && s.stage_rowv) {
+      int k = 0;
+      for (const ExtTensor& e : gp.ext_in)
+        if (e.kind == KIND_ROWV) os << "    fs_stage_rowvec<" << e.dtype << ", V, L, C, WG>(lds_rowv + " << (k++) << " * SLOT, a.p[" << e.arg << "]);\n";
+      os << "    __syncthreads();\n";
+    }
+    std::function<void(int)> ensure_rowv = [&](int src) {
+      if (!lazy_rowv || rowv_ready.count(src)) return;
+      rowv_ready.insert(src);
+      const std::string nm = name(src, KIND_ROWV);
+      if (!in_set[src]) {
+        int k = 0;
+        for (const ExtTensor& e : gp.ext_in) {
+          if (e.kind != KIND_ROWV) continue;
+          if (e.node == src) {
+            os << "    float " << nm << "[E];\n";
+            if (s.stage_rowv) os << "    fs_read_staged<" << tmpl_row() << ">(" << nm << ", lds_rowv + " << k << " * SLOT, lir);\n";
+            else os << "    fs_load_row<" << e.dtype << ", " << tmpl_row() << ">(" << nm << ", a.p[" << e.arg << "], 0, lir, vbase);\n";
+          }
+          ++k;
+        }
+        return;
+      }
+      // a [1,C] member: its own operands first
+      const fs_node& n = g.nodes[src];
+      for (int k = 0; k < n.num_in; ++k) {
+        if (g.nodes[n.in[k]].opcode == FS_CONST) continue;
+        const int o = source_of(n.in[k]);
+        if (g.nodes[o].opcode != FS_CONST && gp.kind.at(o) == KIND_ROWV) ensure_rowv(o);
+      }
+      if (folded[src]) return;
+      os << "    float " << nm << "[E];\n    _Pragma(\"unroll\") for (int e = 0; e < E; ++e) " << nm << "[e] = " << rounded(src, expr(src)) << ";\n";
+      if (const ExtTensor* e = find_out(src))
+        os << "    if (row == 0 && rok) fs_store_row<" << e->dtype << ", " << tmpl_row() << ">(" << nm << ", a.p[" << e->arg
+           << "], 0, lir, vbase, true);\n";
+    };
+    std::function<void(int)> ensure_rowv_operands = [&](int m) {
       const fs_node& n = g.nodes[m];
       for (int k = 0; k < n.num_in; ++k) {
         if (g.nodes[n.in[k]].opcode == FS_CONST) continue;
-        const int src = source_of(n.in[k]);
-        if (g.nodes[src].opcode == FS_CONST) continue;
-        if (gp.kind.at(src) == KIND_ROWV) return true;
-        if (in_set[src] && folded[src] && uses_rowv(src)) return true;
+        const int o = source_of(n.in[k]);
+        if (g.nodes[o].opcode == FS_CONST) continue;
+        if (gp.kind.at(o) == KIND_ROWV) ensure_rowv(o);
+        else if (in_set[o] && folded[o]) ensure_rowv_operands(o);
       }
-      return false;
     };
-
     // members in stage order; the row reductions of a stage come last and share one exchange
     std::vector<int> order;
     for (int m : gp.members)
@@ -543,9 +580,12 @@ struct Emitter {
     while (i < order.size()) {
       const int m = order[i];
       const fs_node& n = g.nodes[m];
-      if (!rowv_done && uses_rowv(m)) {
-        emit_rowv("    ", "vbase", "row == 0 && rok");
-        rowv_done = true;
+      if (lazy_rowv) {
+        if (is_rr(m)) {  // the whole batch of this stage is emitted at once
+          for (size_t k = i; k < order.size() && is_rr(order[k]) && gp.level.at(order[k]) == gp.level.at(m); ++k) ensure_rowv_operands(order[k]);
+        } else {
+          ensure_rowv_operands(m);
+        }
       }
       if (is_rr(m)) {
         // batch: every row reduction of this stage
@@ -624,7 +664,10 @@ struct Emitter {
     }
       if (U > 1) os << "    }\n";
     }
-    if (!rowv_done) emit_rowv("    ", "vbase", "row == 0 && rok");
+    if (lazy_rowv)  // [1,C] members nothing in the body consumed (outputs only)
+      for (int m : gp.members)
+        if (gp.level.at(m) < 0) ensure_rowv(m);
+    (void)rowv_done;
     if (s.resident) {  // last pass over the non-resident part: everything that leaves as an [R,C] or [1,C] tensor
       std::vector<int> roots;
       for (const ExtTensor& e : gp.ext_out)

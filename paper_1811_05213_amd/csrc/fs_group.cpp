@@ -10,6 +10,11 @@ namespace fs {
 
 namespace {
 
+int pow2_floor(int x) {
+  int p = 1;
+  while (p * 2 <= x) p *= 2;
+  return p;
+}
 int pow2_ceil(int x) {
   int p = 1;
   while (p < x) p <<= 1;
@@ -101,11 +106,11 @@ void add_ext_in(GroupPlan& gp, int node, Kind k, int dtype) {
 static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPlan* gp) {
   Schedule& s = gp->s;
   const int R = gp->R, C = gp->C;
-  int max_es = 0, n_full = 0;
+  int max_es = 0;
   for (const ExtTensor& e : gp->ext_in)
-    if (e.kind == KIND_FULL) max_es = std::max(max_es, dtype_size(e.dtype)), ++n_full;
+    if (e.kind == KIND_FULL) max_es = std::max(max_es, dtype_size(e.dtype));
   for (const ExtTensor& e : gp->ext_out)
-    if (e.kind == KIND_FULL) max_es = std::max(max_es, dtype_size(e.dtype)), ++n_full;
+    if (e.kind == KIND_FULL) max_es = std::max(max_es, dtype_size(e.dtype));
   if (max_es == 0) max_es = 4;
   int V = 16 / max_es;
   while (C % V) V /= 2;
@@ -113,26 +118,40 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   const bool rowred = !gp->row_reduces.empty();
   const bool colred = !gp->col_reduces.empty();
 
-  // elements of one [R,C] value a lane may hold
-  int ecap = rowred ? 32 : 8;
-  if (n_full > 4) ecap /= 2;
+  // Elements of one [R,C] value a lane may hold.  With row reductions the row stays in registers
+  // across the stages together with everything else that is live: the other [R,C] inputs and the
+  // lane's slices of the [1,C] operands (E registers each).  128 registers per lane keep four
+  // wavefronts per SIMD in flight; 32 elements per lane is the most that pays even when it fits.
+  int n_live = 1;
+  for (const ExtTensor& e : gp->ext_in) n_live += e.kind == KIND_FULL || e.kind == KIND_ROWV;
+  int ecap = rowred ? std::max(8, std::min(32, pow2_floor(128 / n_live))) : 8;
   ecap = std::max(ecap, V);
-  int l_min = pow2_ceil((NV + ecap / V - 1) / (ecap / V));
+  // lanes per row are a power of two: when half as many lanes would hold the row with at most
+  // 1.5 x a cap below 32, take them (5120 bf16 columns under a cap of 16: 256 lanes x 24 elements,
+  // not 512 x 16 with 37 % of the lanes idle)
+  auto lanes_for = [&](int e) {
+    const int l = pow2_ceil((NV + e / V - 1) / (e / V));
+    if (rowred && l >= 2 && e < 32 && ((NV + l / 2 - 1) / (l / 2)) * V * 2 <= e * 3) return l / 2;
+    return l;
+  };
+  int l_min = lanes_for(ecap);
   const int l_max = std::min(1024, pow2_ceil(NV));
   // Groups without reductions do not need a whole row in one workgroup: very long rows are cut
   // into column tiles, each handled like a row of its own.
   const bool tileable = !rowred && !colred;
   bool has_transposed = false;
   for (const ExtTensor& e : gp->ext_out) has_transposed |= e.transposed;
-  // A row that no longer fits 32 elements per lane of a 1024-lane workgroup may still fit 64: one
-  // workgroup per CU then, but the row is read once instead of once per stage.  Beyond that, the
-  // first 64 elements per lane stay resident and only the rest of the row is walked in chunks.
+  // Rows too long for that: first more elements per lane (32, then 64: one workgroup per CU, but the
+  // row is still read once instead of once per stage); beyond that the first 48 (or 32) elements
+  // per lane stay resident and the rest of the row is walked in chunks; last, chunks only.  Plan
+  // creation steps `wide_level` down while the compiled kernel spills.
   bool resident = false;
-  if (rowred && !colred && !has_transposed && l_min > 1024 && opt.wide_level > 0) {
-    const int e64 = std::max(64, V);
-    const int l64 = pow2_ceil((NV + e64 / V - 1) / (e64 / V));
-    if (l64 <= 1024 && opt.wide_level >= 2) ecap = e64, l_min = l64;
-    else resident = true;
+  if (rowred && l_min > 1024) {
+    const int e32 = std::max(32, V), e64 = std::max(64, V);
+    const bool may_chunk = !colred && !has_transposed;
+    if (ecap < e32 && lanes_for(e32) <= 1024 && (opt.wide_level >= 1 || !may_chunk)) ecap = e32, l_min = lanes_for(e32);
+    else if (may_chunk && opt.wide_level >= 2 && lanes_for(e64) <= 1024) ecap = e64, l_min = lanes_for(e64);
+    else if (may_chunk && opt.wide_level >= 1) resident = true;
   }
   // Row reductions over rows that do not fit the registers of one workgroup: the workgroup walks
   // its row in column chunks, once per stage, recomputing what each stage needs.
@@ -218,6 +237,21 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   // than persistent workgroups looping with a grid stride.  Column reductions keep a bounded
   // grid because every workgroup leaves a partial to fold.
   int cap = colred ? 256 : (1 << 30);
+  // Exception: [1,C] operands that cannot be shared through LDS (fewer than 4 rows per workgroup)
+  // are read again from L2 for every row of a one-shot grid.  When those reads outweigh the row's
+  // own traffic (LayerNorm with gamma, beta and a bias over rows of 4096+ elements: 12 bytes per
+  // column against 4), the workgroups loop instead, 16 wavefronts per CU, and keep their slices of
+  // the operands in registers (measured on [8192,4096] bf16: 35.3 -> 29.4 us).
+  if (!colred && !chunked && CT == 1 && s.G < 4 && R > 1) {
+    int64_t rowv_bytes = 0, full_bytes = 0;
+    for (const ExtTensor& e : gp->ext_in) {  // bytes per column
+      if (e.kind == KIND_ROWV) rowv_bytes += dtype_size(e.dtype);
+      if (e.kind == KIND_FULL) full_bytes += dtype_size(e.dtype);
+    }
+    for (const ExtTensor& e : gp->ext_out)
+      if (e.kind == KIND_FULL) full_bytes += dtype_size(e.dtype);
+    if (rowv_bytes * 2 >= full_bytes * 3) cap = std::max(256, 262144 / WG);
+  }
   if (opt.has_hint && opt.hint.max_workgroups > 0) cap = opt.hint.max_workgroups;
   cap = std::min(cap, (int)(0x7fffffff / WG));  // a launch holds fewer than 2^31 lanes: beyond that the workgroups loop
   s.grid = std::max(1, std::min(s.n_iters, cap));

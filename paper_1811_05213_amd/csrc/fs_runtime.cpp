@@ -187,7 +187,7 @@ fs_status fs_plan_create(const fs_graph_desc* desc, fs_plan** out_plan) {
     // A row held with more than 32 elements per lane leaves little room for anything else: when
     // the compiled kernel spills, the group is planned again with the row walked in chunks.
     GroupPlan& gp = plan->groups[gi];
-    for (int level = plan->opt.wide_level - 1; level >= 0 && gp.s.E > 16 && (gp.s.E > 32 || gp.s.resident) && !gp.row_reduces.empty(); --level) {
+    for (int level = plan->opt.wide_level - 1; level >= 0 && (gp.s.E >= 32 || gp.s.resident) && !gp.row_reduces.empty(); --level) {
       std::vector<char> code;
       st = compile_kernel(std::string(device_header_source()) + "\n" + gp.source, gp.kernel_name, &code);
       if (st == FS_OK && code_object_scratch_bytes(code) > 0) {
