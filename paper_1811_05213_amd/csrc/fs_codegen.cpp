@@ -180,8 +180,8 @@ struct Emitter {
     if (e.transposed) {
       // the value leaves in the flipped orientation: through a padded LDS tile when the plan has one
       if (gp.s.tile_transpose)
-        os << indent << "fs_store_tile_transposed<" << e.dtype << ", " << tmpl_row() << ", WG, C>(" << nm << ", lds_tile, a.p[" << e.arg
-           << "], R, row - rg, lir, rg);\n";
+        os << indent << "fs_store_tile_transposed<" << e.dtype << ", " << tmpl_row() << ", WG, TCW, C>(" << nm << ", lds_tile, a.p[" << e.arg
+           << "], R, row - rg, lir, rg, vbase);\n";
       else
         os << indent << "fs_store_row_transposed<" << e.dtype << ", " << tmpl_row() << ">(" << nm << ", a.p[" << e.arg
            << "], R, row, lir, vbase, rok);\n";
@@ -416,7 +416,8 @@ struct Emitter {
     int n_rowv = 0;
     for (const ExtTensor& e : gp.ext_in) n_rowv += e.kind == KIND_ROWV;
     if (K > 0 || s.tile_transpose || s.stage_rowv) {
-      os << "  constexpr int SLOT = NVL * L * V, TILE_FLOATS = " << (s.tile_transpose ? "C * (G + 1)" : "0") << ", LOOP_FLOATS = TILE_FLOATS + "
+      os << "  constexpr int TCW = " << (s.tiled_transpose ? "NVL * L * V" : "C") << ";  // columns of one transpose tile\n";
+      os << "  constexpr int SLOT = NVL * L * V, TILE_FLOATS = " << (s.tile_transpose ? "TCW * (G + 1)" : "0") << ", LOOP_FLOATS = TILE_FLOATS + "
          << (s.stage_rowv ? n_rowv : 0) << " * SLOT, FOLD_FLOATS = " << (K > 0 ? "(L < 64 ? WG / 64 : G) * CW" : "0") << ";\n";
       os << "  __shared__ float lds_pool[LOOP_FLOATS > FOLD_FLOATS ? LOOP_FLOATS : FOLD_FLOATS];\n";
       os << "  float* const lds_tile = lds_pool; float* const lds_rowv = lds_pool + TILE_FLOATS; float* const lds_col = lds_pool;\n";
@@ -479,6 +480,9 @@ struct Emitter {
       if (U > 1) os << "    const int it" << x << " = it0 + " << u << ";\n";
       if (ctile) {
         os << "    const long row = (long)it * G + rg;\n";
+      } else if (s.tiled_transpose) {
+        // 2-D tiles: consecutive workgroups take consecutive column tiles of the same G rows
+        os << "    const long row = (long)(it / CT) * G + rg;\n    const int vbase = (it % CT) * (NVL * L);\n";
       } else if (s.CT == 1 || s.resident) {
         os << "    const long row" << x << " = (long)it" << x << " * G + rg;\n    constexpr int vbase" << x << " = 0;\n";
       } else {

@@ -258,19 +258,20 @@ template <int DT> FS_DEV void fs_store1_fwd(void* base, long i, float x) {
   static_cast<typename fs_elem<DT>::type*>(base)[i] = fs_from_f32<DT>(x);
 }
 
-// Transposing store of a G x C tile (one row per row-group, in registers) through a padded LDS
-// tile: rows tile_row0 .. tile_row0+G-1 of the [R,C] value become G consecutive elements of each
-// of the C rows of the [C,R] output, so global stores are runs of G elements instead of single
-// elements R apart.  LDS holds C x (G+1) floats (the +1 keeps the column-wise writes of the four
-// row-groups of a wavefront on distinct banks).  Every lane of the workgroup must call it.
-template <int DT, int V, int NVL, int L, int NV, bool RAGGED, int WG, int C>
-FS_DEV void fs_store_tile_transposed(const float (&src)[NVL * V], float* lds, void* base, long R, long tile_row0, int lir, int rg) {
+// Transposing store of a G x TC tile (one row per row-group, in registers) through a padded LDS
+// tile: rows tile_row0 .. tile_row0+G-1 and columns col0 .. col0+TC-1 of the [R,CTOT] value become
+// G consecutive elements of each of TC rows of the [CTOT,R] output, so global stores are runs of G
+// elements instead of single elements R apart.  LDS holds TC x (G+1) floats (the +1 keeps the
+// column-wise writes of the row-groups of a wavefront on distinct banks).  vbase = col0 / V is the
+// tile's first vector in the row.  Every lane of the workgroup must call it.
+template <int DT, int V, int NVL, int L, int NV, bool RAGGED, int WG, int TC, int CTOT>
+FS_DEV void fs_store_tile_transposed(const float (&src)[NVL * V], float* lds, void* base, long R, long tile_row0, int lir, int rg, int vbase) {
   constexpr int G = WG / L, P = G + 1;
   __syncthreads();  // the tile may still be read by its previous use
 #pragma unroll
   for (int j = 0; j < NVL; ++j) {
     const int vi = j * L + lir;
-    if (!RAGGED || vi < NV) {
+    if (!RAGGED || vbase + vi < NV) {
 #pragma unroll
       for (int k = 0; k < V; ++k) lds[(vi * V + k) * P + rg] = src[j * V + k];
     }
@@ -279,18 +280,21 @@ FS_DEV void fs_store_tile_transposed(const float (&src)[NVL * V], float* lds, vo
   constexpr int RUN = (G % 4 == 0) ? 4 : 1;
   constexpr int RPC = G / RUN;  // runs per output row
   const bool vec_ok = RUN == 4 && (R % 4) == 0;
-  for (int i = (int)threadIdx.x; i < C * RPC; i += WG) {
+  const int col0 = vbase * V;
+  for (int i = (int)threadIdx.x; i < TC * RPC; i += WG) {
     const int c = i / RPC, g0 = (i % RPC) * RUN;
     const long r = tile_row0 + g0;
+    if (col0 + c >= CTOT) continue;
     float tmp[RUN];
 #pragma unroll
     for (int q = 0; q < RUN; ++q) tmp[q] = lds[c * P + g0 + q];
+    const long o = (long)(col0 + c) * R + r;
     if (RUN == 4 && vec_ok && r + 3 < R) {
-      fs_store_vec<DT, RUN>(tmp, base, (long)c * R + r);
+      fs_store_vec<DT, RUN>(tmp, base, o);
     } else {
 #pragma unroll
       for (int q = 0; q < RUN; ++q)
-        if (r + q < R) fs_store1_fwd<DT>(base, (long)c * R + r + q, tmp[q]);
+        if (r + q < R) fs_store1_fwd<DT>(base, o + q, tmp[q]);
     }
   }
 }

@@ -162,6 +162,8 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
     FS_FAIL(FS_ERR_UNSUPPORTED, "rows of %d columns are too long for one workgroup in a group with %s", C,
             colred ? "row and column reductions" : "transposed outputs");
   if (tileable) l_min = std::min(l_min, 256);
+  // wide transposes: 2-D tiles through LDS
+  const bool tiled_transpose = has_transposed && tileable && C > 256 && R > 1;
   if (chunked) l_min = 1024;
   if (col_tiled) l_min = std::min(256, l_max);  // (measured: the largest workgroup keeps the fewest rows in flight, so re-reads hit the caches more often)
   int L = rowred ? std::min(64, l_max) : std::min(256, l_max);
@@ -171,15 +173,29 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   if (colred) L = std::min(L, std::max(1, pow2_ceil((NV * V + 15) / 16)));
   L = std::max(L, l_min);
   if (col_tiled) L = l_min;
+  // tile = tt_rows rows (128 bytes of the narrowest transposed output: the length of a run in the
+  // transposed tensor) by 1024 / tt_rows lanes x one 16-byte vector; measured best among 14 shapes
+  int tt_rows = 64;
+  if (tiled_transpose) {
+    int es = 4;
+    for (const ExtTensor& e : gp->ext_out)
+      if (e.transposed) es = std::min(es, dtype_size(e.dtype));
+    tt_rows = std::max(16, std::min(64, 128 / es));
+    L = std::min(1024 / tt_rows, l_max);
+  }
   // small problems: more lanes per row until the device has ~8 wavefronts per CU
   while ((int64_t)R * L / 64 < 2048 && L < l_max && !(has_transposed && !rowred) && !chunked && !col_tiled) L *= 2;
-  if (opt.has_hint && opt.hint.lanes_per_row > 0) {
+  if (opt.has_hint && opt.hint.lanes_per_row > 0 && !tiled_transpose) {
     const int h = opt.hint.lanes_per_row;
     if ((h & (h - 1)) == 0 && h >= ((chunked || col_tiled) ? 64 : l_min) && h <= 1024) L = h;
   }
   int NVL = (NV + L - 1) / L, CT = 1;
   if (NVL * V > ecap && tileable) {
     NVL = std::max(1, ecap / V);
+    CT = (NV + NVL * L - 1) / (NVL * L);
+  }
+  if (tiled_transpose) {
+    NVL = 1;
     CT = (NV + NVL * L - 1) / (NVL * L);
   }
   int NVLC = 0, RESV = 0;
@@ -211,7 +227,8 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   else if (total_waves > 1024 || has_transposed) WG = std::max(256, L);
   else WG = std::max(64, L);
   if (chunked) WG = L;  // one row per workgroup
-  if (opt.has_hint && opt.hint.wg_threads > 0 && !chunked) {
+  if (tiled_transpose) WG = std::max(64, L * std::min(tt_rows, std::max(4, pow2_ceil(R))));
+  if (opt.has_hint && opt.hint.wg_threads > 0 && !chunked && !tiled_transpose) {
     const int h = opt.hint.wg_threads;
     if (h % 64 == 0 && h >= L && h <= 1024) WG = h;
   }
@@ -231,7 +248,9 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   s.ragged_chunks = chunked && (int64_t)RESV + (int64_t)CT * NVLC * L != NV;
   s.chunked = chunked;
   s.col_tiled = col_tiled;
-  s.n_iters = chunked ? R : col_tiled ? (R + s.G - 1) / s.G : (int)(((int64_t)R * CT + s.G - 1) / s.G);
+  s.tiled_transpose = tiled_transpose;
+  s.n_iters = chunked ? R : col_tiled ? (R + s.G - 1) / s.G : tiled_transpose ? (int)((int64_t)CT * ((R + s.G - 1) / s.G))
+                                                                             : (int)(((int64_t)R * CT + s.G - 1) / s.G);
   // Streaming groups launch one workgroup per row tile: the hardware hands tiles out in memory
   // order and a fresh wavefront issues its loads at once, which measures faster on this device
   // than persistent workgroups looping with a grid stride.  Column reductions keep a bounded
@@ -290,8 +309,8 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   for (const ExtTensor& e : gp->ext_in) n_rowv += e.kind == KIND_ROWV;
   s.stage_rowv = false;
   s.tile_transpose = false;
-  const int tile_bytes = C * (s.G + 1) * 4;
-  if (has_transposed && CT == 1 && s.G >= 4 && fixed + std::max(loop_bytes + tile_bytes, fold_bytes) <= opt.lds_budget) {
+  const int tile_bytes = (tiled_transpose ? NVL * L * V : C) * (s.G + 1) * 4;
+  if (has_transposed && (CT == 1 || tiled_transpose) && s.G >= 4 && fixed + std::max(loop_bytes + tile_bytes, fold_bytes) <= opt.lds_budget) {
     s.tile_transpose = true;
     loop_bytes += tile_bytes;
   }

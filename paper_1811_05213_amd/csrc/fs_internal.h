@@ -88,6 +88,10 @@ struct Schedule {
   int fan_in = 32;  // column-reduction tree fan-in
   bool stage_rowv = false;  // [1,C] inputs are staged once per workgroup in LDS
   bool tile_transpose = false;  // transposed roots leave through a padded LDS tile
+  // Reduction-free groups with transposed roots over wide rows: 2-D tiles.  A workgroup owns G
+  // consecutive rows of one column tile of NVL*L*V columns (unit = column tile fastest), so both
+  // the reads and the transposed writes are runs of consecutive elements.
+  bool tiled_transpose = false;
   // Rows too long for the registers of one workgroup, with row reductions: the row is walked in CT
   // column chunks once per stage, and each stage recomputes the elementwise values it needs from
   // the inputs instead of keeping them (space traded for recomputation, Section 5.1.2).

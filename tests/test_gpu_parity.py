@@ -402,6 +402,31 @@ def test_transposes_through_lds_tile_and_direct():
     np.testing.assert_array_equal(out[0], (ins[0] > ins[1]).astype(np.uint8).T)
 
 
+def test_wide_transposes_in_2d_tiles():
+    # reduction-free groups with transposed roots over more than 256 columns: 2-D tiles through LDS (ragged in both directions,
+    # bf16 and u8 payloads, several roots, per-column and per-row operands)
+    for rows, cols, dt in ((300, 5000, "f32"), (5, 300, "f32"), (3, 70001, "f32"), (7000, 258, "bf16"), (1031, 1030, "f32"), (64, 4100, "f32")):
+        g = Graph()
+        x = g.input(rows, cols, dt)
+        b = g.input(1, cols)
+        w = g.input(rows, 1)
+        xf = g.unary("convert", x, "f32") if dt != "f32" else x
+        y = g.binary("mul", g.binary("add", xf, g.bcast_rowvec(b, rows)), g.bcast_colvec(w, cols))
+        yo = g.unary("convert", y, dt) if dt != "f32" else y
+        t = g.transpose(yo)
+        m = g.transpose(g.cmp("gt", y, xf))
+        g.set_outputs([t, yo, m, g.transpose(g.unary("neg", xf))])
+        p = fs.Plan(g)
+        assert p.stats()["num_launches"] == 1 and p.group_info(0)["lds_bytes"] > 0 and "it % CT" in p.group_source(0)
+        p.destroy()
+        v = RNG.standard_normal((rows, cols)).astype(np.float32)
+        ins = [f32_to_bf16_bits(v) if dt == "bf16" else v, RNG.standard_normal((1, cols)).astype(np.float32),
+               RNG.standard_normal((rows, 1)).astype(np.float32)]
+        ref, out_s, _ = both_modes(g, ins, f"tiled transpose {rows}x{cols} {dt}")
+        np.testing.assert_array_equal(out_s[0], out_s[1].T)
+        np.testing.assert_array_equal(out_s[2], ref[2])
+
+
 def test_transposes_inside_a_group():
     """A transpose between fused ops moves no data: consumers run in the producer's layout."""
     for rows, cols in ((130, 72), (64, 64), (512, 256), (33, 1000)):
