@@ -426,27 +426,14 @@ struct Emitter {
     if (K > 0) os << "  __shared__ fs_u32 lds_flag;\n";
 
     // ---- per-column values ----
+    // (looping kernels: loaded once per workgroup, before the loop; LDS staging only exists in one-trip kernels)
     auto emit_rowv = [&](const std::string& ind, const std::string& vb, const std::string& store_cond) {
-      if (s.stage_rowv) {
-        int k = 0;
-        for (const ExtTensor& e : gp.ext_in)
-          if (e.kind == KIND_ROWV)
-            os << ind << "fs_stage_rowvec<" << e.dtype << ", V, L, C, WG>(lds_rowv + " << (k++) << " * SLOT, a.p[" << e.arg << "]);\n";
-        os << ind << "__syncthreads();\n";
-        k = 0;
-        for (const ExtTensor& e : gp.ext_in)
-          if (e.kind == KIND_ROWV) {
-            os << ind << "float " << name(e.node, KIND_ROWV) << "[E];\n";
-            os << ind << "fs_read_staged<" << tmpl_row() << ">(" << name(e.node, KIND_ROWV) << ", lds_rowv + " << (k++) << " * SLOT, lir);\n";
-          }
-      } else {
-        for (const ExtTensor& e : gp.ext_in)
-          if (e.kind == KIND_ROWV) {
-            os << ind << "float " << name(e.node, KIND_ROWV) << "[E];\n";
-            os << ind << "fs_load_row<" << e.dtype << ", " << tmpl_row() << ">(" << name(e.node, KIND_ROWV) << ", a.p[" << e.arg << "], 0, lir, " << vb
-               << ");\n";
-          }
-      }
+      for (const ExtTensor& e : gp.ext_in)
+        if (e.kind == KIND_ROWV) {
+          os << ind << "float " << name(e.node, KIND_ROWV) << "[E];\n";
+          os << ind << "fs_load_row<" << e.dtype << ", " << tmpl_row() << ">(" << name(e.node, KIND_ROWV) << ", a.p[" << e.arg << "], 0, lir, " << vb
+             << ");\n";
+        }
       for (int m : gp.members) {
         if (gp.level.at(m) >= 0 || folded[m]) continue;
         const std::string nm = name(m, KIND_ROWV);
@@ -506,12 +493,7 @@ struct Emitter {
     // of them loaded at the top of a LayerNorm body with 32 elements per lane spill).  Staged
     // operands are written to LDS up front; only their reads into registers are lazy.
     std::set<int> rowv_ready;
-    const bool lazy_rowv = rowv_in_loop && getenv("FS_EAGER_ROWV") == nullptr;
-    bool rowv_done = !rowv_in_loop;
-    if (rowv_in_loop && !lazy_rowv) {
-      emit_rowv("    ", "vbase", "row == 0 && rok");
-      rowv_done = true;
-    }
+    const bool lazy_rowv = rowv_in_loop;
     if (lazy_rowv && s.stage_rowv) {
       int k = 0;
       for (const ExtTensor& e : gp.ext_in)
@@ -671,7 +653,6 @@ struct Emitter {
     if (lazy_rowv)  // [1,C] members nothing in the body consumed (outputs only)
       for (int m : gp.members)
         if (gp.level.at(m) < 0) ensure_rowv(m);
-    (void)rowv_done;
     if (s.resident) {  // last pass over the non-resident part: everything that leaves as an [R,C] or [1,C] tensor
       std::vector<int> roots;
       for (const ExtTensor& e : gp.ext_out)
