@@ -185,7 +185,9 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
     L = std::min(1024 / tt_rows, l_max);
   }
   // small problems: more lanes per row until the device has ~8 wavefronts per CU
-  while ((int64_t)R * L / 64 < 2048 && L < l_max && !(has_transposed && !rowred) && !chunked && !col_tiled) L *= 2;
+  // (a row that will be cut into column tiles anyway is not a small problem)
+  const bool col_tiles_anyway = tileable && (int64_t)NV * V > (int64_t)L * ecap;
+  while ((int64_t)R * L / 64 < 2048 && L < l_max && !(has_transposed && !rowred) && !chunked && !col_tiled && !col_tiles_anyway) L *= 2;
   if (opt.has_hint && opt.hint.lanes_per_row > 0 && !tiled_transpose) {
     const int h = opt.hint.lanes_per_row;
     if ((h & (h - 1)) == 0 && h >= ((chunked || col_tiled) ? 64 : l_min) && h <= 1024) L = h;
