@@ -418,10 +418,10 @@ struct Emitter {
     if (K > 0 || s.tile_transpose || s.stage_rowv) {
       os << "  constexpr int TCW = " << (s.tiled_transpose ? "NVL * L * V" : "C") << ";  // columns of one transpose tile\n";
       os << "  constexpr int SLOT = NVL * L * V, TILE_FLOATS = " << (s.tile_transpose ? "TCW * (G + 1)" : "0") << ", LOOP_FLOATS = TILE_FLOATS + "
-         << (s.stage_rowv ? n_rowv : 0) << " * SLOT, FOLD_FLOATS = " << (K > 0 ? "(L < 64 ? WG / 64 : G) * CW" : "0") << ";\n";
+         << (s.stage_rowv ? n_rowv : 0) << " * SLOT, PC = " << std::max(1, s.fold_piece) << ", FOLD_FLOATS = " << (K > 0 ? "(L < 64 ? WG / 64 : G) * PC" : "0") << ";\n";
       os << "  __shared__ float lds_pool[LOOP_FLOATS > FOLD_FLOATS ? LOOP_FLOATS : FOLD_FLOATS];\n";
       os << "  float* const lds_tile = lds_pool; float* const lds_rowv = lds_pool + TILE_FLOATS; float* const lds_col = lds_pool;\n";
-      os << "  (void)lds_tile; (void)lds_rowv; (void)lds_col; (void)SLOT;\n";
+      os << "  (void)lds_tile; (void)lds_rowv; (void)lds_col; (void)SLOT; (void)PC;\n";
     }
     if (K > 0) os << "  __shared__ fs_u32 lds_flag;\n";
 
@@ -672,7 +672,7 @@ struct Emitter {
       os << "  {\n    constexpr int FV = " << FV << ";\n    typedef fs_colfold<" << K << ", CW, WG, FV> S;\n    float cv[S::CPT][FV];\n";
       for (int k = 0; k < K; ++k) {
         const int m = gp.col_reduces[k];
-        os << "    fs_colred_fold_wg<" << g.nodes[m].attr_i << ", " << k << ", " << K << ", V, NVL, L, NVF, CW, WG, FV>(ca" << loc(m)
+        os << "    fs_colred_fold_wg<" << g.nodes[m].attr_i << ", " << k << ", " << K << ", V, NVL, L, NVF, CW, WG, FV, PC>(ca" << loc(m)
            << ", cv, lds_col, lir, rg);\n";
       }
       os << "    if (fs_colred_fold_grid<" << K << ", CW, WG, FV, " << s.fan_in << ", " << kname << "_kinds>(cv, a.part + (long)tile * "

@@ -453,12 +453,14 @@ FS_DEV float fs_shfl_xor(float v, int mask) {
 // Stage 1, in-workgroup fold of reduction number KIDX.  acc: the lane's per-column accumulators
 // in the row layout.  Fills the chunks of `vals` that belong to reduction KIDX.  When several
 // row-groups share a wavefront (L < 64) they are folded inside the wavefront first (lanes l,
-// l+L, l+2L, ... own the same columns), so the LDS area holds one row of C floats per wavefront
-// (GL = WG/64 rows), not one per row-group.
-template <int KIND, int KIDX, int K, int V, int NVL, int L, int NV, int C, int WG, int FV, int CPT>
-FS_DEV void fs_colred_fold_wg(const float (&acc_in)[NVL * V], float (&vals)[CPT][FV], float* lds /* GL*C floats */, int lir, int rg) {
+// l+L, l+2L, ... own the same columns), so the LDS area holds one row per wavefront (GL = WG/64
+// rows), not one per row-group.  The C columns go through the area PC columns at a time (PC a
+// multiple of 8, or C itself): wide rows need no more LDS than narrow ones, only more barriers.
+template <int KIND, int KIDX, int K, int V, int NVL, int L, int NV, int C, int WG, int FV, int PC, int CPT>
+FS_DEV void fs_colred_fold_wg(const float (&acc_in)[NVL * V], float (&vals)[CPT][FV], float* lds /* GL*PC floats */, int lir, int rg) {
   typedef fs_colfold<K, C, WG, FV> S;
   static_assert(CPT == S::CPT, "chunks per thread");
+  static_assert(PC == C || PC % 8 == 0, "piece width");
   constexpr int GL = L < 64 ? WG / 64 : WG / L;
   float acc[NVL * V];
 #pragma unroll
@@ -477,28 +479,30 @@ FS_DEV void fs_colred_fold_wg(const float (&acc_in)[NVL * V], float (&vals)[CPT]
   }
   const int slot = L < 64 ? (int)threadIdx.x / 64 : rg;
   const bool writer = L < 64 ? (fs_lane_id() < L) : true;
-  __syncthreads();  // the LDS area may still be read by the previous fold
-  if (writer) {
+  for (int p0 = 0; p0 < C; p0 += PC) {
+    __syncthreads();  // the LDS area may still be read by the previous piece or fold
+    if (writer) {
 #pragma unroll
-    for (int j = 0; j < NVL; ++j) {
-      const int vi = j * L + lir;
-      if (vi < NV) {
+      for (int j = 0; j < NVL; ++j) {
+        const int vi = j * L + lir, col = vi * V - p0;
+        if (vi < NV && col >= 0 && col < PC) {
 #pragma unroll
-        for (int k = 0; k < V; ++k) lds[slot * C + vi * V + k] = acc[j * V + k];
+          for (int k = 0; k < V; ++k) lds[slot * PC + col + k] = acc[j * V + k];
+        }
       }
     }
-  }
-  __syncthreads();
+    __syncthreads();
 #pragma unroll
-  for (int i = 0; i < S::CPT; ++i) {
-    const int c = (int)threadIdx.x + i * WG;
-    if (c >= KIDX * S::CH && c < (KIDX + 1) * S::CH) {
-      const int col0 = (c - KIDX * S::CH) * FV;
+    for (int i = 0; i < S::CPT; ++i) {
+      const int c = (int)threadIdx.x + i * WG;
+      const int col0 = (c - KIDX * S::CH) * FV - p0;
+      if (c >= KIDX * S::CH && c < (KIDX + 1) * S::CH && col0 >= 0 && col0 < PC) {
 #pragma unroll
-      for (int f = 0; f < FV; ++f) {
-        float a = lds[col0 + f];
-        for (int g = 1; g < GL; ++g) a = fs_red_op<KIND>(a, lds[g * C + col0 + f]);
-        vals[i][f] = a;
+        for (int f = 0; f < FV; ++f) {
+          float a = lds[col0 + f];
+          for (int g = 1; g < GL; ++g) a = fs_red_op<KIND>(a, lds[g * PC + col0 + f]);
+          vals[i][f] = a;
+        }
       }
     }
   }

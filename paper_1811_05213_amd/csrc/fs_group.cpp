@@ -124,6 +124,7 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   // wavefronts per SIMD in flight; 32 elements per lane is the most that pays even when it fits.
   int n_live = 1;
   for (const ExtTensor& e : gp->ext_in) n_live += e.kind == KIND_FULL || e.kind == KIND_ROWV;
+  n_live += (int)gp->col_reduces.size();  // a column accumulator per element
   int ecap = rowred ? std::max(8, std::min(32, pow2_floor(128 / n_live))) : 8;
   if (colred && !rowred) ecap = 32 / max_es;  // 32 bytes per lane per tile (bf16 sums: 30.2 -> 25.4 us on [65536,1024])
   ecap = std::max(ecap, V);
@@ -220,12 +221,14 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
       }
   } else if (colred) {
     // large workgroups (few partials, many rows per trip) as long as every CU still gets a workgroup
+    // and the in-workgroup fold area (one row of C floats per wavefront or row-group) fits the budget
     WG = std::max(64, L);
     for (int w = 512; w >= 128; w /= 2)
       if (w >= L && (int64_t)R * L / w >= 256) {
         WG = w;
         break;
       }
+    if (rowred && L >= 256) WG = std::max(WG, std::min(1024, 4 * L));  // rows across several wavefronts: 16 wavefronts per CU
   }
   else if (total_waves > 1024 || has_transposed) WG = std::max(256, L);
   else WG = std::max(64, L);
@@ -301,9 +304,14 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   int fixed = 0, loop_bytes = 0, fold_bytes = 0;
   if (rowred && L > 64) fixed += 2 * s.G * (L / 64) * gp->max_batched_reduces * 4;
   const int fold_width = col_tiled ? NVL * L * V : C;  // columns one workgroup folds
+  s.fold_piece = fold_width;
   if (colred) {
+    // the fold area takes at most half of the budget: wide rows pass through it in pieces
     fixed += 16;
-    fold_bytes = (L < 64 ? WG / 64 : s.G) * fold_width * 4;
+    const int fold_rows = L < 64 ? WG / 64 : s.G;
+    const int piece_cap = std::max(8, (opt.lds_budget / 2 / (fold_rows * 4)) / 8 * 8);
+    if (fold_width > piece_cap) s.fold_piece = piece_cap;
+    fold_bytes = fold_rows * s.fold_piece * 4;
   }
   auto total = [&]() { return fixed + std::max(loop_bytes, fold_bytes); };
   // [1,C] inputs shared by all rows of a workgroup: with one trip per workgroup they are staged in

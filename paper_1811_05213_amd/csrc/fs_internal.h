@@ -86,6 +86,7 @@ struct Schedule {
   bool ragged = false;  // some lane's vector index can fall beyond NV
   int lds_bytes = 0;
   int fan_in = 32;  // column-reduction tree fan-in
+  int fold_piece = 0;  // columns that pass through the in-workgroup fold area at a time
   bool stage_rowv = false;  // [1,C] inputs are staged once per workgroup in LDS
   bool tile_transpose = false;  // transposed roots leave through a padded LDS tile
   // Reduction-free groups with transposed roots over wide rows: 2-D tiles.  A workgroup owns G

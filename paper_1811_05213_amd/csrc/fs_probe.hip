@@ -59,8 +59,8 @@ __global__ void __launch_bounds__(256) fs_device_selftest_kernel(const void* in,
   constexpr int FV = 4;
   typedef fs_colfold<2, C, WG, FV> S;
   float cv[S::CPT][FV];
-  fs_colred_fold_wg<FS_K_SUM, 0, 2, V, NVL, L, NV, C, WG, FV>(ca, cv, lds_col, lir, rg);
-  fs_colred_fold_wg<FS_K_MAX, 1, 2, V, NVL, L, NV, C, WG, FV>(cb, cv, lds_col, lir, rg);
+  fs_colred_fold_wg<FS_K_SUM, 0, 2, V, NVL, L, NV, C, WG, FV, C>(ca, cv, lds_col, lir, rg);
+  fs_colred_fold_wg<FS_K_MAX, 1, 2, V, NVL, L, NV, C, WG, FV, C>(cb, cv, lds_col, lir, rg);
   if (fs_colred_fold_grid<2, C, WG, FV, 32, fs_selftest_kinds>(cv, part, tickets, &flag, blockIdx.x, gridDim.x))
     for (int i = 0; i < S::CPT; ++i)
       if (tid + i * WG < S::NCH) fs_store1<FS_DT_F32>(out, (tid + i * WG) * FV, cv[i][0] + cv[i][3]);

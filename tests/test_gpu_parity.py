@@ -142,6 +142,15 @@ def test_column_reductions_over_wide_rows():
     from workloads import layernorm_grad_graph, layernorm_grad_inputs
     g = layernorm_grad_graph(48, 16384)
     both_modes(g, layernorm_grad_inputs(48, 16384), "layernorm backward 48x16384")
+    # row and column reductions over wide rows in one kernel: the in-workgroup column fold passes through LDS in pieces
+    for rows, cols in ((3000, 4096), (700, 8200), (1500, 16384), (300, 30000)):
+        g = layernorm_grad_graph(rows, cols)
+        p = fs.Plan(g)
+        assert p.stats()["num_launches"] == 1 and p.group_info(0)["lds_bytes"] <= 40000
+        p.destroy()
+        both_modes(g, layernorm_grad_inputs(rows, cols), f"layernorm backward {rows}x{cols}")
+    g = multi_reduce_graph(2000, 8192)
+    both_modes(g, multi_reduce_inputs(2000, 8192), "multi reduce 2000x8192")
 
 
 def test_row_reduce_across_wavefronts():
