@@ -1,0 +1,159 @@
+"""Shape survey: common fused patterns over a range of shapes, each as ONE stitched plan on one MI355X.
+
+    python -m paper_1811_05213_amd.survey [--steps 30] [--filter softmax]
+
+For every case it prints the schedule the planner chose (launches, lanes per row, elements per lane,
+workgroup size, grid, LDS bytes) and the measured time per launch, effective HBM GB/s (minimal bytes:
+every plan input read once, every plan output written once) and the fraction of the 8 TB/s peak.
+Buffers rotate through >= 2 GiB so the last-level cache cannot serve them.  Inputs are seeded
+synthetic normals; this is a timing tool (parity lives in tests/).
+"""
+from __future__ import annotations
+
+import argparse
+import sys
+
+import numpy as np
+
+from workloads import (Graph, f32_to_bf16_bits, layernorm_gelu_graph, layernorm_grad_graph, min_hbm_bytes, softmax_graph,
+                       softmax_grad_graph)
+
+
+def _f32(g, x, dt):
+    return g.unary("convert", x, "f32") if dt != "f32" else x
+
+
+def _out(g, y, dt):
+    return g.unary("convert", y, dt) if dt != "f32" else y
+
+
+def rmsnorm(r, c, dt="bf16"):
+    g = Graph()
+    x, w = g.input(r, c, dt), g.input(1, c)
+    xf = _f32(g, x, dt)
+    rs = g.unary("rsqrt", g.binary("add", g.reduce_row("mean", g.binary("mul", xf, xf)), g.const(1e-6, r, 1)))
+    g.set_outputs([_out(g, g.binary("mul", g.binary("mul", xf, g.bcast_colvec(rs, c)), g.bcast_rowvec(w, r)), dt)])
+    return g
+
+
+def bias_gelu(r, c, dt="bf16"):
+    g = Graph()
+    x, b = g.input(r, c, dt), g.input(1, c)
+    g.set_outputs([_out(g, g.unary("gelu_tanh", g.binary("add", _f32(g, x, dt), g.bcast_rowvec(b, r))), dt)])
+    return g
+
+
+def add_layernorm(r, c, dt="bf16"):
+    g = Graph()
+    x, res, gam, bet = g.input(r, c, dt), g.input(r, c, dt), g.input(1, c), g.input(1, c)
+    h = g.binary("add", _f32(g, x, dt), _f32(g, res, dt))
+    hc = g.binary("sub", h, g.bcast_colvec(g.reduce_row("mean", h), c))
+    rstd = g.unary("rsqrt", g.binary("add", g.reduce_row("mean", g.binary("mul", hc, hc)), g.const(1e-5, r, 1)))
+    y = g.binary("add", g.binary("mul", g.binary("mul", hc, g.bcast_colvec(rstd, c)), g.bcast_rowvec(gam, r)), g.bcast_rowvec(bet, r))
+    g.set_outputs([_out(g, h, dt), _out(g, y, dt)])
+    return g
+
+
+def masked_softmax(r, c, dt="bf16"):
+    g = Graph()
+    x, m = g.input(r, c, dt), g.input(r, c, dt)
+    z = g.binary("add", g.binary("mul", _f32(g, x, dt), g.const(0.125, r, c)), _f32(g, m, dt))
+    e = g.unary("exp", g.binary("sub", z, g.bcast_colvec(g.reduce_row("max", z), c)))
+    g.set_outputs([_out(g, g.binary("div", e, g.bcast_colvec(g.reduce_row("sum", e), c)), dt)])
+    return g
+
+
+def adam(r, c):
+    g = Graph()
+    p, gr, m, v = (g.input(r, c) for _ in range(4))
+    k = lambda val: g.const(val, r, c)
+    m2 = g.binary("add", g.binary("mul", m, k(0.9)), g.binary("mul", gr, k(0.1)))
+    v2 = g.binary("add", g.binary("mul", v, k(0.999)), g.binary("mul", g.binary("mul", gr, gr), k(0.001)))
+    upd = g.binary("div", m2, g.binary("add", g.unary("sqrt", v2), k(1e-8)))
+    g.set_outputs([g.binary("sub", p, g.binary("mul", upd, k(1e-3))), m2, v2])
+    return g
+
+
+def colsum(r, c, dt="f32"):
+    g = Graph()
+    g.set_outputs([g.reduce_col("sum", _f32(g, g.input(r, c, dt), dt))])
+    return g
+
+
+def bias_grad(r, c):
+    g = Graph()
+    x, dy = g.input(r, c), g.input(r, c)
+    t = g.binary("mul", dy, g.unary("tanh", x))
+    g.set_outputs([t, g.reduce_col("sum", t)])
+    return g
+
+
+def transpose(r, c, dt="f32"):
+    g = Graph()
+    g.set_outputs([g.transpose(g.input(r, c, dt))])
+    return g
+
+
+def cases():
+    out = []
+    for r, c in [(4096, 4096), (16384, 2048), (65536, 128), (8192, 8192), (2048, 32768), (1 << 20, 64), (4096, 65536), (2048, 131072)]:
+        out.append(("softmax f32", softmax_graph(r, c), r, c))
+    for r, c in [(32768, 768), (16384, 1024), (8192, 4096), (8192, 8192), (4096, 16384)]:
+        out.append(("layernorm+gelu bf16", layernorm_gelu_graph(r, c), r, c))
+        out.append(("rmsnorm bf16", rmsnorm(r, c), r, c))
+    for r, c in [(16384, 1024), (8192, 4096)]:
+        out.append(("add+layernorm bf16", add_layernorm(r, c), r, c))
+        out.append(("masked softmax bf16", masked_softmax(r, c), r, c))
+    for r, c in [(8192, 28672), (65536, 1024)]:
+        out.append(("bias+gelu bf16", bias_gelu(r, c), r, c))
+    for r, c in [(16384, 4096), (1, 1 << 26)]:
+        out.append(("adam f32", adam(r, c), r, c))
+    for r, c in [(1 << 20, 64), (65536, 1024), (16384, 4096), (1024, 65536)]:
+        out.append(("column sum f32", colsum(r, c), r, c))
+    out.append(("column sum bf16", colsum(65536, 1024, "bf16"), 65536, 1024))
+    out.append(("bias grad f32", bias_grad(16384, 4096), 16384, 4096))
+    for r, c in [(8192, 8192), (65536, 1024), (1024, 65536)]:
+        out.append(("transpose f32", transpose(r, c), r, c))
+    out.append(("transpose bf16", transpose(16384, 4096, "bf16"), 16384, 4096))
+    for r, c in [(16384, 1024), (8192, 4096), (4096, 8192)]:
+        out.append(("layernorm backward f32", layernorm_grad_graph(r, c), r, c))
+    out.append(("softmax backward f32", softmax_grad_graph(8192, 4096), 8192, 4096))
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--filter", default="")
+    args = ap.parse_args()
+    import torch
+    if not torch.cuda.is_available():
+        print("survey: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    from bench import build_sets, time_plan
+    from . import Plan
+    rng = np.random.default_rng(181105213)
+    print("%-24s %9s x %-9s %2s  %5s %3s %5s %7s %6s | %9s %7s %6s" % ("pattern", "rows", "cols", "k", "L", "E", "WG", "grid", "LDS", "us", "GB/s", "% peak"))
+    for name, g, r, c in cases():
+        if args.filter and args.filter not in name:
+            continue
+        ins = []
+        for i in g.input_ids():
+            n = g.nodes[i]
+            a = rng.standard_normal((n.rows, n.cols), dtype=np.float32)
+            ins.append(f32_to_bf16_bits(a) if n.dtype == "bf16" else a)
+        plan = Plan(g)
+        gi = plan.group_info(0)
+        runs = build_sets(plan, g, ins, "cuda:0", 2 << 30)
+        ms, _ = time_plan(runs, args.steps, 5)
+        gbs = min_hbm_bytes(g) / ms / 1e6
+        print("%-24s %9d x %-9d %2d  %5d %3d %5d %7d %6d | %9.1f %7.0f %6.1f" % (
+            name, r, c, plan.stats()["num_launches"], gi["lanes_per_row"], gi["elems_per_lane"], gi["wg_threads"], gi["grid"],
+            gi["lds_bytes"], ms * 1e3, gbs, gbs / 80.0), flush=True)
+        del runs
+        plan.destroy()
+        torch.cuda.empty_cache()
+
+
+if __name__ == "__main__":
+    main()
