@@ -22,14 +22,14 @@ def summarize(path: str, filters=()) -> str:
         args = [f"%{f}%" for f in filters]
     rows = list(c.execute(
         "select name, count(*), avg(duration)/1000.0, min(duration)/1000.0, max(duration)/1000.0, sum(duration)/1000.0, "
-        f"avg(grid_x), avg(workgroup_x), max(static_lds_size), max(scratch_size) from kernels {where} group by name order by 6 desc limit 40", args))
+        f"avg(grid_x), avg(workgroup_x), max(static_lds_size), max(scratch_size) from kernels {where} group by name order by 6 desc limit 60", args))
     out.append("%-56s %6s %9s %9s %9s %12s %9s %5s %6s %7s" % ("kernel", "calls", "avg_us", "min_us", "max_us", "total_us", "grid_thr", "wg", "lds", "scratch"))
     for r in rows:
         out.append("%-56s %6d %9.2f %9.2f %9.2f %12.1f %9d %5d %6d %7d" % (r[0][:56], *r[1:]))
     try:
         cw = where.replace("name like", "kernel_name like")
         rows = list(c.execute("select kernel_name, counter_name, count(*), avg(value), min(value), max(value) from counters_collection "
-                              f"{cw} group by kernel_name, counter_name order by 1, 2 limit 80", args))
+                              f"{cw} group by kernel_name, counter_name order by 1, 2 limit 600", args))
     except sqlite3.Error:
         rows = []
     if rows:
