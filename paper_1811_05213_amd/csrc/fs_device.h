@@ -479,6 +479,34 @@ FS_DEV void fs_colred_fold_wg(const float (&acc_in)[NVL * V], float (&vals)[CPT]
   }
   const int slot = L < 64 ? (int)threadIdx.x / 64 : rg;
   const bool writer = L < 64 ? (fs_lane_id() < L) : true;
+  if constexpr (PC >= C) {  // the whole row at once
+    __syncthreads();  // the LDS area may still be read by the previous fold
+    if (writer) {
+#pragma unroll
+      for (int j = 0; j < NVL; ++j) {
+        const int vi = j * L + lir;
+        if (vi < NV) {
+#pragma unroll
+          for (int k = 0; k < V; ++k) lds[slot * C + vi * V + k] = acc[j * V + k];
+        }
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < S::CPT; ++i) {
+      const int c = (int)threadIdx.x + i * WG;
+      if (c >= KIDX * S::CH && c < (KIDX + 1) * S::CH) {
+        const int col0 = (c - KIDX * S::CH) * FV;
+#pragma unroll
+        for (int f = 0; f < FV; ++f) {
+          float a = lds[col0 + f];
+          for (int g = 1; g < GL; ++g) a = fs_red_op<KIND>(a, lds[g * C + col0 + f]);
+          vals[i][f] = a;
+        }
+      }
+    }
+    return;
+  }
   for (int p0 = 0; p0 < C; p0 += PC) {
     __syncthreads();  // the LDS area may still be read by the previous piece or fold
     if (writer) {
