@@ -113,12 +113,14 @@ fs_status compile_kernel(const std::string& source, const std::string& name, std
   return FS_OK;
 }
 
-// Largest scratch (register spill) size among the kernels of a code object, read from its
-// metadata note: the msgpack integer that follows each ".private_segment_fixed_size" key.
-long code_object_scratch_bytes(const std::vector<char>& code) {
+// Scratch (register spill) bytes of every kernel of a code object, read from its metadata note:
+// the msgpack integer after each ".private_segment_fixed_size" key, attributed to the kernel whose
+// ".name" key precedes it in the same map (the keys of a kernel's map are sorted).
+std::map<std::string, long> code_object_scratch_bytes(const std::vector<char>& code) {
   static const char key[] = ".private_segment_fixed_size";
-  const size_t klen = sizeof(key) - 1;
-  long worst = 0;
+  static const char name_key[] = ".name";
+  const size_t klen = sizeof(key) - 1, nlen = sizeof(name_key) - 1;
+  std::map<std::string, long> out;
   for (size_t i = 0; i + klen + 5 <= code.size(); ++i) {
     if (code[i] != '.' || memcmp(code.data() + i, key, klen) != 0) continue;
     const unsigned char* p = (const unsigned char*)code.data() + i + klen;
@@ -127,9 +129,20 @@ long code_object_scratch_bytes(const std::vector<char>& code) {
     else if (p[0] == 0xcc) v = p[1];
     else if (p[0] == 0xcd) v = ((long)p[1] << 8) | p[2];
     else if (p[0] == 0xce) v = ((long)p[1] << 24) | ((long)p[2] << 16) | ((long)p[3] << 8) | p[4];
-    if (v > worst) worst = v;
+    if (v < 0) continue;
+    // the closest ".name" before the key, followed by a msgpack string
+    for (size_t j = i; j-- > 0 && i - j < 4096;) {
+      if (code[j] != '.' || memcmp(code.data() + j, name_key, nlen) != 0) continue;
+      const unsigned char* q = (const unsigned char*)code.data() + j + nlen;
+      size_t len = 0, skip = 0;
+      if ((q[0] & 0xe0) == 0xa0) len = q[0] & 0x1f, skip = 1;
+      else if (q[0] == 0xd9) len = q[1], skip = 2;
+      else break;
+      out[std::string((const char*)q + skip, len)] = v;
+      break;
+    }
   }
-  return worst;
+  return out;
 }
 
 }  // namespace fs
@@ -184,27 +197,56 @@ fs_status fs_plan_create(const fs_graph_desc* desc, fs_plan** out_plan) {
       delete plan;
       return st;
     }
-    // A row held with more than 32 elements per lane leaves little room for anything else: when
-    // the compiled kernel spills, the group is planned again with the row walked in chunks.
-    GroupPlan& gp = plan->groups[gi];
-    for (int level = plan->opt.wide_level - 1; level >= 0 && (gp.s.E >= 32 || gp.s.resident) && !gp.row_reduces.empty(); --level) {
-      std::vector<char> code;
-      st = compile_kernel(std::string(device_header_source()) + "\n" + gp.source, gp.kernel_name, &code);
-      if (st == FS_OK && code_object_scratch_bytes(code) > 0) {
-        PlanOptions narrow = plan->opt;
-        narrow.wide_level = level;
-        st = analyse_group(g, ordered[gi], plan->group_of, (int)gi, narrow, &gp);
-        if (st == FS_OK) st = generate_kernel(g, &gp, (int)gi);
-      } else {
-        level = -1;  // fits (or failed): stop
-      }
-      if (st != FS_OK) {
-        delete plan;
-        return st;
-      }
-    }
     // schedule tuning: the fastest candidate the performance library knows (Sections 4.3, 4.4)
     if (use_library) choose_from_library(g, ordered[gi], plan->group_of, (int)gi, plan->opt, &plan->groups[gi]);
+  }
+
+  // One translation unit per plan: the building blocks once, then every distinct kernel body.
+  // Spill feedback: a kernel whose code object reports scratch memory is planned again with less
+  // register pressure -- rows held beyond 32 elements per lane step down towards chunks, otherwise
+  // the workgroup is halved (the register file is shared by fewer wavefronts) -- and the unit is
+  // compiled again; a few rounds at most.
+  std::vector<PlanOptions> group_opt(plan->groups.size(), plan->opt);
+  for (int round = 0;; ++round) {
+    std::string tu = device_header_source();
+    std::set<std::string> seen;
+    for (const GroupPlan& gp : plan->groups)
+      if (seen.insert(gp.kernel_name).second) tu += "\n" + gp.source;
+    st = compile_kernel(tu, "fs_plan", &plan->code);
+    if (st != FS_OK) {
+      delete plan;
+      return st;
+    }
+    if (round == 4) break;
+    const std::map<std::string, long> scratch = code_object_scratch_bytes(plan->code);
+    bool changed = false;
+    for (size_t gi = 0; gi < plan->groups.size(); ++gi) {
+      GroupPlan& gp = plan->groups[gi];
+      auto it = scratch.find(gp.kernel_name);
+      if (it == scratch.end() || it->second == 0) continue;
+      // the next milder plan that actually differs from the current one
+      PlanOptions o = group_opt[gi];
+      GroupPlan again;
+      bool found = false;
+      while (!found && !gp.row_reduces.empty() && (gp.s.E >= 32 || gp.s.resident) && o.wide_level > 0) {
+        --o.wide_level;
+        found = analyse_group(g, ordered[gi], plan->group_of, (int)gi, o, &again) == FS_OK &&
+                generate_kernel(g, &again, (int)gi) == FS_OK && again.kernel_name != gp.kernel_name;
+      }
+      if (!found && gp.s.WG >= 2 * std::max(64, gp.s.L) && !gp.s.chunked && !gp.s.tiled_transpose) {
+        o = group_opt[gi];
+        if (!o.has_hint) o.hint = fs_sched_hint{0, 0, 0, 0};
+        o.has_hint = true;
+        o.hint.wg_threads = gp.s.WG / 2;
+        found = analyse_group(g, ordered[gi], plan->group_of, (int)gi, o, &again) == FS_OK &&
+                generate_kernel(g, &again, (int)gi) == FS_OK && again.kernel_name != gp.kernel_name;
+      }
+      if (!found) continue;
+      group_opt[gi] = o;
+      gp = again;
+      changed = true;
+    }
+    if (!changed) break;
   }
 
   // workspace: [tickets][tensors crossing group boundaries][column-reduction partials]
@@ -239,16 +281,6 @@ fs_status fs_plan_create(const fs_graph_desc* desc, fs_plan** out_plan) {
   plan->launched_hbm_bytes = 0;
   for (const GroupPlan& gp : plan->groups) plan->launched_hbm_bytes += gp.min_hbm_bytes;
 
-  // one translation unit per plan: the building blocks once, then every distinct kernel body
-  std::string tu = device_header_source();
-  std::set<std::string> seen;
-  for (const GroupPlan& gp : plan->groups)
-    if (seen.insert(gp.kernel_name).second) tu += "\n" + gp.source;
-  st = compile_kernel(tu, "fs_plan", &plan->code);
-  if (st != FS_OK) {
-    delete plan;
-    return st;
-  }
   *out_plan = plan;
   return FS_OK;
 }
