@@ -358,6 +358,19 @@ def test_huge_row_counts_stay_inside_the_launch_limits():
     p.destroy()
 
 
+def test_spill_feedback_relieves_register_pressure():
+    # row norm + two column sums over 8192 fp32 columns: 32 elements per lane of x, its square and two accumulators do not fit
+    # the 128 registers of a 1024-lane workgroup; plan creation sees the scratch in the compiled code object and halves the workgroup
+    p = fs.Plan(multi_reduce_graph(8192, 8192))
+    gi = p.group_info(0)
+    assert p.stats()["num_launches"] == 1 and gi["wg_threads"] == 512 and gi["elems_per_lane"] == 32
+    p.destroy()
+    # LayerNorm + GeLU over 28672 bf16 columns: 32 elements per lane spill, so the row is walked in chunks instead
+    p = fs.Plan(layernorm_gelu_graph(64, 28672))
+    assert p.group_info(0)["elems_per_lane"] == 16 and "int ch =" in p.group_source(0)
+    p.destroy()
+
+
 def test_work_span_and_layered_planner():
     # Work/Span: roots have span 0, everything else 1 + the largest span of its users; a layer has no internal dependences
     g = random_dag_graph()
