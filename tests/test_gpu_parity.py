@@ -507,3 +507,17 @@ def test_random_dags_other_seeds_and_shapes(seed, rows, ks):
     for mode, label in ((fs.FS_MODE_STITCHED, "stitched"), (fs.FS_MODE_LAYERED, "layered"), (fs.FS_MODE_UNFUSED, "unfused")):
         out = run_graph(g, ins, mode=mode)
         check_all(g, out, ref, f"random dag seed {seed} rows {rows} ks {ks} {label}")
+
+
+@pytest.mark.parametrize("seed,rows,cols", [(1, 37, 72), (2, 300, 1000), (3, 64, 64), (4, 1000, 36), (5, 5, 3000), (6, 129, 258),
+                                            (7, 2048, 128), (8, 16, 4100), (9, 513, 520), (10, 70, 9000), (11, 4099, 8), (12, 260, 264)])
+def test_random_graphs_with_every_op_class(seed, rows, cols):
+    # ~130-node DAGs mixing all unary ops, comparisons and selects, bf16 round trips, row and column reductions of every kind,
+    # transposes and both broadcasts; three planners against the oracle
+    from graphgen import random_graph, random_inputs
+    g = random_graph(seed, rows, cols)
+    ins = random_inputs(g, seed)
+    ref = oracle.run(g, ins, THREADS)
+    for mode, label in ((fs.FS_MODE_STITCHED, "stitched"), (fs.FS_MODE_LAYERED, "layered"), (fs.FS_MODE_UNFUSED, "unfused")):
+        out = run_graph(g, ins, mode=mode)
+        check_all(g, out, ref, f"random graph seed {seed} {rows}x{cols} {label}")
