@@ -121,11 +121,13 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   // Elements of one [R,C] value a lane may hold.  With row reductions the row stays in registers
   // across the stages together with everything else that is live: the other [R,C] inputs and the
   // lane's slices of the [1,C] operands (E registers each).  128 registers per lane keep four
-  // wavefronts per SIMD in flight; 32 elements per lane is the most that pays even when it fits.
+  // wavefronts per SIMD in flight; 16 elements per lane is the most that pays even when more would
+  // fit (measured over 26 row-reduction cases: 16 beats 32 by 3-10 %: more wavefronts per row, more
+  // rows in flight); rows too long for that take 32 and 64 below.
   int n_live = 1;
   for (const ExtTensor& e : gp->ext_in) n_live += e.kind == KIND_FULL || e.kind == KIND_ROWV;
   n_live += (int)gp->col_reduces.size();  // a column accumulator per element
-  int ecap = rowred ? std::max(8, std::min(32, pow2_floor(128 / n_live))) : 8;
+  int ecap = rowred ? std::max(8, std::min(16, pow2_floor(128 / n_live))) : 8;
   if (colred && !rowred) ecap = 32 / max_es;  // 32 bytes per lane per tile (bf16 sums: 30.2 -> 25.4 us on [65536,1024])
   ecap = std::max(ecap, V);
   // lanes per row are a power of two: when half as many lanes would hold the row with at most

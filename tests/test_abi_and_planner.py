@@ -359,11 +359,12 @@ def test_huge_row_counts_stay_inside_the_launch_limits():
 
 
 def test_spill_feedback_relieves_register_pressure():
-    # row norm + two column sums over 8192 fp32 columns: 32 elements per lane of x, its square and two accumulators do not fit
-    # the 128 registers of a 1024-lane workgroup; plan creation sees the scratch in the compiled code object and halves the workgroup
-    p = fs.Plan(multi_reduce_graph(8192, 8192))
+    # LayerNorm backward over 8192 fp32 columns: x, dy, gamma and two column accumulators at 16 elements per lane do not fit the
+    # 128 registers a lane has in a 1024-lane workgroup; plan creation sees the scratch in the compiled code object and halves it
+    from workloads import layernorm_grad_graph
+    p = fs.Plan(layernorm_grad_graph(4096, 8192))
     gi = p.group_info(0)
-    assert p.stats()["num_launches"] == 1 and gi["wg_threads"] == 512 and gi["elems_per_lane"] == 32
+    assert p.stats()["num_launches"] == 1 and gi["lanes_per_row"] == 512 and gi["wg_threads"] == 512
     p.destroy()
     # LayerNorm + GeLU over 28672 bf16 columns: 32 elements per lane spill, so the row is walked in chunks instead
     p = fs.Plan(layernorm_gelu_graph(64, 28672))
