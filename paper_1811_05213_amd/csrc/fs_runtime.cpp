@@ -223,7 +223,9 @@ fs_status fs_plan_create(const fs_graph_desc* desc, fs_plan** out_plan) {
     for (size_t gi = 0; gi < plan->groups.size(); ++gi) {
       GroupPlan& gp = plan->groups[gi];
       auto it = scratch.find(gp.kernel_name);
-      if (it == scratch.end() || it->second == 0) continue;
+      // (a few spilled registers cost nothing measurable, and whether a borderline kernel gets them varies with what the
+      // run-time compiler compiled before in the same process; hundreds of bytes are what ruins a kernel)
+      if (it == scratch.end() || it->second <= 128) continue;
       // the next milder plan that actually differs from the current one
       PlanOptions o = group_opt[gi];
       GroupPlan again;
@@ -241,6 +243,9 @@ fs_status fs_plan_create(const fs_graph_desc* desc, fs_plan** out_plan) {
         found = analyse_group(g, ordered[gi], plan->group_of, (int)gi, o, &again) == FS_OK &&
                 generate_kernel(g, &again, (int)gi) == FS_OK && again.kernel_name != gp.kernel_name;
       }
+      if (getenv("FS_LOG_PLAN"))
+        fprintf(stderr, "fs: group %zu kernel %s spills %ld bytes (%d lanes/row, %d elements/lane, workgroup %d): %s\n", gi, gp.kernel_name.c_str(),
+                it->second, gp.s.L, gp.s.E, gp.s.WG, found ? "planned again" : "kept");
       if (!found) continue;
       group_opt[gi] = o;
       gp = again;

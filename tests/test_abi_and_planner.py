@@ -280,12 +280,13 @@ def test_ragged_and_degenerate_shapes_plan():
     assert src.count("const int vbase = RESV + ch * (NVL * L);") == 3  # max pass, sum pass, output pass
     p.destroy()
     # between 32768 and 65536 columns a softmax row still fits the registers (64 elements per lane); LayerNorm+GeLU with its
-    # three per-column vectors would spill there, which plan creation detects from the compiled kernel: chunks again
+    # three per-column vectors would spill hundreds of bytes there, which plan creation detects from the compiled kernel: the
+    # row is walked in chunks instead (with or without a resident part)
     p = fs.Plan(softmax_graph(4, 65536))
     assert p.group_info(0)["elems_per_lane"] == 64 and "ch" not in re.findall(r"for \(int (\w+) = ", p.group_source(0))
     p.destroy()
     p = fs.Plan(layernorm_gelu_graph(4, 65536))
-    assert p.group_info(0)["elems_per_lane"] == 16 and "ch" in re.findall(r"for \(int (\w+) = ", p.group_source(0))
+    assert p.group_info(0)["elems_per_lane"] <= 32 and "ch" in re.findall(r"for \(int (\w+) = ", p.group_source(0))
     p.destroy()
     # column reductions over wide rows run by column tiles
     gw = Graph()
@@ -359,16 +360,20 @@ def test_huge_row_counts_stay_inside_the_launch_limits():
 
 
 def test_spill_feedback_relieves_register_pressure():
-    # LayerNorm backward over 8192 fp32 columns: x, dy, gamma and two column accumulators at 16 elements per lane do not fit the
-    # 128 registers a lane has in a 1024-lane workgroup; plan creation sees the scratch in the compiled code object and halves it
+    # plan creation reads every kernel's scratch size from the compiled code object; a kernel that spills hundreds of bytes is
+    # planned again with a milder row form or half the workgroup.  LayerNorm + GeLU over 65536 bf16 columns would hold 64
+    # elements per lane plus three per-column operands (~800 bytes of scratch): it ends up walking the row in chunks instead
+    p = fs.Plan(layernorm_gelu_graph(4, 65536))
+    assert p.group_info(0)["elems_per_lane"] <= 32 and "int ch =" in p.group_source(0)
+    p.destroy()
+    # the same row without the operands fits: softmax keeps all 64 elements per lane in registers
+    p = fs.Plan(softmax_graph(4, 65536))
+    assert p.group_info(0)["elems_per_lane"] == 64 and "int ch =" not in p.group_source(0)
+    p.destroy()
+    # LayerNorm backward over 8192 columns stays one kernel (a handful of spilled registers, under 128 bytes, is tolerated)
     from workloads import layernorm_grad_graph
     p = fs.Plan(layernorm_grad_graph(4096, 8192))
-    gi = p.group_info(0)
-    assert p.stats()["num_launches"] == 1 and gi["lanes_per_row"] == 512 and gi["wg_threads"] == 512
-    p.destroy()
-    # LayerNorm + GeLU over 28672 bf16 columns: 32 elements per lane spill, so the row is walked in chunks instead
-    p = fs.Plan(layernorm_gelu_graph(64, 28672))
-    assert p.group_info(0)["elems_per_lane"] == 16 and "int ch =" in p.group_source(0)
+    assert p.stats()["num_launches"] == 1 and p.group_info(0)["wg_threads"] in (512, 1024)
     p.destroy()
 
 
