@@ -23,6 +23,16 @@
  *     holding 0 or 1.  Every device tensor pointer must be 16-byte aligned.
  *   - A plan is immutable after fs_plan_create.  fs_plan_run may be called
  *     concurrently on one plan only with distinct workspaces.
+ *
+ * Environment (all optional)
+ *   FS_KERNEL_CACHE        directory of the compiled-kernel cache (default: kcache/
+ *                          beside the shared library); kernels are keyed by source,
+ *                          compile options and compiler version
+ *   FS_PERF_LIBRARY        file of the performance library (see fs_plan_tune)
+ *   FS_LOG_PLAN            when set, plan creation reports on stderr every kernel it
+ *                          plans again because the compiled code spills registers
+ *   FS_DUMP_FAILED_SOURCE  file that receives the generated source when its
+ *                          compilation fails
  */
 #ifndef FS_H_
 #define FS_H_
