@@ -427,3 +427,14 @@ def test_work_span_and_layered_planner():
         p = fs.Plan(g2, mode=fs.FS_MODE_LAYERED)
         assert p.stats()["num_launches"] == 1
         p.destroy()
+
+
+def test_survey_patterns_are_single_kernels():
+    # every pattern of the shape survey (softmax variants, norms, optimizer update, column sums, transposes, backward passes)
+    # from 64 to 131072 columns plans as ONE stitched kernel
+    from paper_1811_05213_amd import survey
+    for name, g, rows, cols in survey.cases():
+        p = fs.Plan(g)
+        assert p.stats()["num_launches"] == 1, (name, rows, cols)
+        assert p.stats()["launched_hbm_bytes"] == p.stats()["min_hbm_bytes"] == min_hbm_bytes(g)
+        p.destroy()
