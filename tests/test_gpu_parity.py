@@ -521,3 +521,21 @@ def test_random_graphs_with_every_op_class(seed, rows, cols):
     for mode, label in ((fs.FS_MODE_STITCHED, "stitched"), (fs.FS_MODE_LAYERED, "layered"), (fs.FS_MODE_UNFUSED, "unfused")):
         out = run_graph(g, ins, mode=mode)
         check_all(g, out, ref, f"random graph seed {seed} {rows}x{cols} {label}")
+
+
+def test_gpu_matches_the_stored_small_cases():
+    # the tiny hand-checkable cases of tests/golden/oracle_small_cases.json (written by the oracle alone), on the GPU
+    import json
+    import os
+    import sys
+    here = os.path.dirname(os.path.abspath(__file__))
+    sys.path.insert(0, os.path.join(here, "golden"))
+    import make_oracle_fixtures as mk
+    stored = json.load(open(os.path.join(here, "golden", "oracle_small_cases.json")))
+    for name, g, ins in mk.cases():
+        ref = []
+        for o, hexes, shape in zip(g.outputs, stored[name]["outputs_hex"], stored[name]["output_shapes"]):
+            v = np.array([int(h, 16) for h in hexes], dtype=np.uint32).view(np.float32).reshape(shape)
+            ref.append(f32_to_bf16_bits(v) if g.nodes[o].dtype == "bf16" else v)
+        for mode in (fs.FS_MODE_STITCHED, fs.FS_MODE_UNFUSED):
+            check_all(g, run_graph(g, ins, mode=mode), ref, f"stored case {name} mode {mode}")

@@ -7,6 +7,8 @@ routines (softmax, layer_norm, gelu).  A planted mistake (dropped term, swapped 
 wrong reduce axis, wrong rounding) fails at least one test below.
 """
 import math
+import os
+import sys
 
 import numpy as np
 import pytest
@@ -396,8 +398,43 @@ def test_random_dag_vs_numpy_and_order_independence():
         np.testing.assert_array_equal(a, b)
 
 
+def _paper_figures():
+    out = {}
+    with open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "paper_figures.txt")) as f:
+        for line in f:
+            line = line.split("#")[0].split()
+            if len(line) == 2:
+                out[line[0]] = float(line[1])
+    return out
+
+
 def test_e2e_formula_fixture():
-    # Section 6.4 formula 1 + FusableRatio (1 - 1/FusionSpeedup) with the printed geomean 1.74 and a
-    # fusable ratio inside the printed 20-50 % range reproduces the printed ~13 % end-to-end figure.
-    pred = 1 + 0.3 * (1 - 1 / 1.74)
-    assert pred == pytest.approx(1.128, abs=1e-3)
+    # Section 6.4: predicted end-to-end speedup = 1 + FusableRatio (1 - 1/FusionSpeedup).  With the printed geomean fusion
+    # speedup and a fusable ratio inside the printed range the formula reproduces the printed ~13 % end-to-end figure, and over
+    # the printed ranges it stays inside the printed 5-20 % band's order of magnitude.
+    fig = _paper_figures()
+    pred = 1 + 0.3 * (1 - 1 / fig["fusion_speedup_geomean"])
+    assert pred == pytest.approx(1 + fig["e2e_speedup_geomean_pct"] / 100, abs=3e-3)
+    lo = 1 + fig["fusable_ratio_min_pct"] / 100 * (1 - 1 / fig["fusion_speedup_min"])
+    hi = 1 + fig["fusable_ratio_max_pct"] / 100 * (1 - 1 / fig["fusion_speedup_max"])
+    assert 1.0 < lo < 1 + fig["e2e_speedup_min_pct"] / 100 < 1 + fig["e2e_speedup_max_pct"] / 100 < hi < 1.5
+
+
+def test_oracle_reproduces_its_stored_small_cases():
+    # tests/golden/oracle_small_cases.json was written by tests/golden/make_oracle_fixtures.py (oracle only): the oracle must
+    # keep producing exactly those bits, and the softmax case is redone here by hand in fp64
+    import json
+    import math
+    sys.path.insert(0, os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden"))
+    import make_oracle_fixtures as mk
+    stored = json.load(open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "oracle_small_cases.json")))
+    for name, g, ins in mk.cases():
+        res = oracle.run(g, ins, 1)
+        for r, hexes, shape in zip(res, stored[name]["outputs_hex"], stored[name]["output_shapes"]):
+            got = (bf16_bits_to_f32(r) if r.dtype == np.uint16 else r.astype(np.float32)).view(np.uint32).ravel()
+            assert list(r.shape) == shape and [format(int(v), "08x") for v in got] == hexes, name
+    row = [0.0, 1.0, 2.0, 3.0]
+    e = [math.exp(v - 3.0) for v in row]
+    want = np.array([v / sum(e) for v in e], dtype=np.float64)
+    got = np.array([int(h, 16) for h in stored["softmax_2x4"]["outputs_hex"][0][:4]], dtype=np.uint32).view(np.float32)
+    np.testing.assert_allclose(got, want, rtol=2e-7)
