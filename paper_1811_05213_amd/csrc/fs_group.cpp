@@ -168,8 +168,8 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   if (tileable) l_min = std::min(l_min, 256);
   // wide transposes: 2-D tiles through LDS
   const bool tiled_transpose = has_transposed && tileable && C > 256 && R > 1;
-  if (chunked) l_min = 1024;
-  if (col_tiled) l_min = std::min(256, l_max);  // (measured: the largest workgroup keeps the fewest rows in flight, so re-reads hit the caches more often)
+  if (chunked) l_min = 1024;  // (measured: the largest workgroup keeps the fewest rows in flight, so re-reads hit the caches more often)
+  if (col_tiled) l_min = std::min(256, l_max);
   int L = rowred ? std::min(64, l_max) : std::min(256, l_max);
   // a transposed root leaves as runs of G = WG/L consecutive elements: at least 16 rows per workgroup
   if (has_transposed && !rowred) L = std::min(L, std::max(l_min, 16));
