@@ -565,6 +565,13 @@ namespace {
 // launch-bound group it is dearer than the launch it saves, so small groups do not take one in.
 bool worth_fusing(const GroupPlan& merged) {
   constexpr uint64_t kFoldWorthBytes = 16ull << 20;
+  // A transposed root that cannot leave through an LDS tile (rows spread over a whole workgroup)
+  // is written element by element, R elements apart: an order of magnitude slower than handing
+  // the value to a kernel of its own that transposes in 2-D tiles (softmax + transpose of
+  // [8192,4096]: 408 us fused, 95 us as two kernels); launch-bound groups keep it (one launch less).
+  if (merged.members.size() > 1 && !merged.s.tile_transpose && !merged.s.tiled_transpose && merged.min_hbm_bytes >= kFoldWorthBytes)
+    for (const ExtTensor& e : merged.ext_out)
+      if (e.transposed) return false;
   return merged.col_reduces.empty() || merged.members.size() == 1 || merged.s.grid == 1 || merged.min_hbm_bytes >= kFoldWorthBytes;
 }
 
