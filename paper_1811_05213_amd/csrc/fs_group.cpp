@@ -171,6 +171,11 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   if (chunked) l_min = 1024;  // (measured: the largest workgroup keeps the fewest rows in flight, so re-reads hit the caches more often)
   if (col_tiled) l_min = std::min(256, l_max);
   int L = rowred ? std::min(64, l_max) : std::min(256, l_max);
+  // Very narrow rows: a row of at most 32 bytes belongs to one lane (no cross-lane step at all;
+  // [4M,3] L2-normalise: 34.8 -> 17.6 us); rows that can only be read element by element (odd
+  // widths) get at least two elements per lane.
+  if (rowred && !colred && C * max_es <= 32) L = 1;
+  else if (rowred && !colred && V == 1 && NV >= 4) L = std::min(L, pow2_ceil(NV) / 2);
   // a transposed root leaves as runs of G = WG/L consecutive elements: at least 16 rows per workgroup
   if (has_transposed && !rowred) L = std::min(L, std::max(l_min, 16));
   // looping (column-reduction) kernels want more bytes in flight per lane: 16 elements per lane
