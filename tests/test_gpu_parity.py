@@ -411,6 +411,20 @@ def test_transposes_through_lds_tile_and_direct():
     np.testing.assert_array_equal(out[0], (ins[0] > ins[1]).astype(np.uint8).T)
 
 
+def test_very_narrow_rows():
+    # rows of a few elements: one lane per row (no cross-lane step), odd widths with scalar accesses, per-column operands
+    for rows, cols in ((100003, 3), (50000, 7), (30000, 13), (70000, 2), (65537, 8), (40000, 6), (9, 5)):
+        g = Graph()
+        x, w = g.input(rows, cols), g.input(1, cols)
+        xs = g.binary("mul", x, g.bcast_rowvec(w, rows))
+        n = g.unary("rsqrt", g.binary("add", g.reduce_row("sum", g.binary("mul", xs, xs)), g.const(1e-6, rows, 1)))
+        y = g.binary("mul", xs, g.bcast_colvec(n, cols))
+        g.set_outputs([y, g.reduce_row("max", y), g.reduce_row("mean", x)])
+        ins = [RNG.standard_normal((rows, cols)).astype(np.float32), RNG.uniform(0.5, 2, (1, cols)).astype(np.float32)]
+        both_modes(g, ins, f"narrow rows {rows}x{cols}")
+        both_modes(softmax_graph(rows, cols), [ins[0]], f"narrow softmax {rows}x{cols}")
+
+
 def test_wide_transposes_in_2d_tiles():
     # reduction-free groups with transposed roots over more than 256 columns: 2-D tiles through LDS (ragged in both directions,
     # bf16 and u8 payloads, several roots, per-column and per-row operands)
