@@ -266,8 +266,9 @@ struct Emitter {
   // last, the ones most likely still in the L2.
   int n_passes = 0;
   template <class Tail>
-  void emit_pass(const std::set<int>& mem, const std::set<int>& ext, bool store_outputs, Tail tail) {
-    if (n_passes++ % 2 == 0) os << "    for (int ch = 0; ch < CT; ++ch) {\n";
+  void emit_pass(const std::set<int>& mem, const std::set<int>& ext, bool store_outputs, Tail tail, const std::string& loop = "") {
+    if (!loop.empty()) os << "    " << loop << " {\n";
+    else if (n_passes++ % 2 == 0) os << "    for (int ch = 0; ch < CT; ++ch) {\n";
     else os << "    for (int ch = CT - 1; ch >= 0; --ch) {\n";
     // (inside a pass the chunk's own sizes shadow the body's: the building blocks read them by name)
     os << "      constexpr int NVL = NVLC, E = NVLC * V;\n      constexpr bool RAGGED = RAGC;\n"
@@ -359,6 +360,66 @@ struct Emitter {
     os << "  }\n}\n";
   }
 
+  // ---- a few very long rows, only reduced: one workgroup per row segment (Schedule::split_rows) ----
+  // Every workgroup folds its segment's chunks into lane partials, the workgroup's lanes are
+  // folded as for any row reduction, and the S segment results of a row meet through the ticketed
+  // fold of the column reductions (a "vector" of one float per reduction).  The workgroup that
+  // folds last also evaluates the per-row values that depend on the results, and stores.
+  void run_split_rows(const std::string& kname, int WPR, int KB) {
+    const Schedule& s = gp.s;
+    const int K = (int)gp.row_reduces.size();
+    auto is_rr = [&](int m) { return std::find(gp.row_reduces.begin(), gp.row_reduces.end(), m) != gp.row_reduces.end(); };
+    os << "  constexpr int S = " << s.S << ", CPS = " << s.CPS << ";\n";
+    os << "  __shared__ fs_u32 lds_flag;\n  __shared__ float lds_vals[" << K << "];\n";
+    os << "  const long row = (int)blockIdx.x / S, row0 = row * C;\n  const int seg = (int)blockIdx.x % S;\n"
+       << "  constexpr bool rok = true;\n  constexpr int vbase = 0;\n  (void)row0; (void)rok; (void)vbase;\n";
+    for (const ExtTensor& e : gp.ext_in)
+      if (e.kind == KIND_COLV) os << "  const float " << name(e.node, KIND_COLV) << " = fs_load1<" << e.dtype << ">(a.p[" << e.arg << "], row);\n";
+    // per-row values that need no reduction result
+    for (int m : gp.members)
+      if (gp.level.at(m) == 0 && gp.kind.at(m) == KIND_COLV && !is_rr(m) && !folded[m])
+        os << "  const float " << name(m, KIND_COLV) << " = " << rounded(m, expr(m)) << ";\n";
+    std::set<int> mem, ext;
+    needed_for(gp.row_reduces, &mem, &ext);
+    for (int b : gp.row_reduces) os << "  float q" << loc(b) << " = fs_red_identity<" << g.nodes[b].attr_i << ">();\n";
+    os << "  {\n    const int ch_end = (seg + 1) * CPS < CT ? (seg + 1) * CPS : CT;\n";
+    emit_pass(mem, ext, false, [&]() { emit_chunk_accumulate(gp.row_reduces); }, "for (int ch = seg * CPS; ch < ch_end; ++ch)");
+    os << "  }\n";
+    // fold the workgroup's lanes (the results are not rounded or divided yet: that happens once, at the end)
+    for (int b : gp.row_reduces)
+      os << "  q" << loc(b) << " = fs_segment_allreduce<" << g.nodes[b].attr_i << ", (L < 64 ? L : 64)>(q" << loc(b) << ");\n";
+    if (s.L > 64) {
+      os << "  {\n    const fs_xwave<" << KB << ", " << WPR << "> xw{lds_rr, lir >> 6, (tid & 63) == 0};\n";
+      for (int k = 0; k < K; ++k) os << "    xw.put(" << k << ", q" << loc(gp.row_reduces[k]) << ");\n";
+      os << "    fs_lds_barrier();\n";
+      for (int k = 0; k < K; ++k)
+        os << "    q" << loc(gp.row_reduces[k]) << " = xw.get<" << g.nodes[gp.row_reduces[k]].attr_i << ">(" << k << ");\n";
+      os << "  }\n";
+    }
+    os << "  typedef fs_colfold<" << K << ", 1, WG, 1> SF;\n  float cv[SF::CPT][1];\n  cv[0][0] = 0.0f;\n";
+    for (int k = 0; k < K; ++k) os << "  if (tid == " << k << ") cv[0][0] = q" << loc(gp.row_reduces[k]) << ";\n";
+    os << "  if (fs_colred_fold_grid<" << K << ", 1, WG, 1, " << s.fan_in << ", " << kname << "_kinds>(cv, a.part + row * " << s.part_stride_floats
+       << "L, a.tickets + row * " << s.ticket_stride << ", &lds_flag, (fs_u32)seg, (fs_u32)S)) {\n";
+    os << "    if (tid < " << K << ") lds_vals[tid] = cv[0][0];\n    __syncthreads();\n    if (tid == 0) {\n";
+    // thread 0 of the last workgroup: the results, what depends on them, and the stores
+    std::vector<int> order;
+    for (int m : gp.members)
+      if (gp.kind.at(m) == KIND_COLV && !folded[m] && (is_rr(m) || gp.level.at(m) >= 1)) order.push_back(m);
+    std::stable_sort(order.begin(), order.end(), [&](int x, int y) { return gp.level.at(x) < gp.level.at(y); });
+    for (int m : order) {
+      if (is_rr(m)) {
+        const int k = (int)(std::find(gp.row_reduces.begin(), gp.row_reduces.end(), m) - gp.row_reduces.begin());
+        const std::string q = "lds_vals[" + std::to_string(k) + "]";
+        os << "      const float " << name(m, KIND_COLV) << " = " << rounded(m, g.nodes[m].attr_i == FS_RED_MEAN ? q + " / (float)C" : q) << ";\n";
+      } else {
+        os << "      const float " << name(m, KIND_COLV) << " = " << rounded(m, expr(m)) << ";\n";
+      }
+    }
+    for (const ExtTensor& e : gp.ext_out)
+      os << "      fs_store1<" << e.dtype << ">(a.p[" << e.arg << "], row, " << name(source_of(e.node), KIND_COLV) << ");\n";
+    os << "    }\n  }\n}\n";
+  }
+
   void run(const std::string& kname) {
     const Schedule& s = gp.s;
     for (int m : gp.members) in_set[m] = 1;
@@ -381,13 +442,15 @@ struct Emitter {
 
     os << "// work space [R," << C << "], " << s.L << " lanes/row, " << s.E << " elements/lane, workgroup " << s.WG << "\n";
     os << "struct " << kname << "_args { void* p[" << NP << "]; float* part; fs_u32* tickets; int R; int n_iters; };\n";
-    if (K > 0) {
+    // the reductions that are folded across workgroups: column reductions, or the row reductions of split rows
+    const std::vector<int>& folded_across = s.split_rows ? gp.row_reduces : gp.col_reduces;
+    if (!folded_across.empty()) {
       os << "struct " << kname << "_kinds {\n  static FS_DEV float op(int k, float a, float b) { switch (k) {";
-      for (int k = 0; k < K; ++k)
-        os << " case " << k << ": return fs_red_op<" << g.nodes[gp.col_reduces[k]].attr_i << ">(a, b);";
+      for (size_t k = 0; k < folded_across.size(); ++k)
+        os << " case " << k << ": return fs_red_op<" << g.nodes[folded_across[k]].attr_i << ">(a, b);";
       os << " } return a; }\n  static FS_DEV float identity(int k) { switch (k) {";
-      for (int k = 0; k < K; ++k)
-        os << " case " << k << ": return fs_red_identity<" << g.nodes[gp.col_reduces[k]].attr_i << ">();";
+      for (size_t k = 0; k < folded_across.size(); ++k)
+        os << " case " << k << ": return fs_red_identity<" << g.nodes[folded_across[k]].attr_i << ">();";
       os << " } return 0.0f; }\n};\n";
     }
     os << "extern \"C\" __global__ void __launch_bounds__(" << s.WG << ") " << kname << "(const " << kname << "_args a) {\n";
@@ -401,6 +464,10 @@ struct Emitter {
     if (s.chunked) {
       os << "  constexpr int NVLC = " << s.NVLC << ", RESV = " << s.RESV << ";\n  constexpr bool RAGC = " << (s.ragged_chunks ? "true" : "false")
          << ";\n";
+      if (s.split_rows) {
+        run_split_rows(kname, WPR, KB);
+        return;
+      }
       if (!s.resident) {
         run_chunked(xwave, WPR, KB);
         return;

@@ -145,12 +145,20 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   const bool tileable = !rowred && !colred;
   bool has_transposed = false;
   for (const ExtTensor& e : gp->ext_out) has_transposed |= e.transposed;
+  // A few very long rows whose reductions are all the group produces: splitting each row over many
+  // workgroups beats any single-workgroup form ([4, 4M] row sums: 263 us on 4 CUs).
+  bool split_rows = false;
+  if (rowred && !colred && !has_transposed && R <= 128 && (int64_t)C * max_es >= (1 << 18) && (int64_t)R * C * max_es >= (1 << 20)) {
+    split_rows = true;
+    for (const ExtTensor& e : gp->ext_out) split_rows &= e.kind == KIND_COLV;
+    for (int m : gp->row_reduces) split_rows &= gp->level.at(m) == 0;
+  }
   // Rows too long for that: first more elements per lane (32, then 64: one workgroup per CU, but the
   // row is still read once instead of once per stage); beyond that the first 48 (or 32) elements
   // per lane stay resident and the rest of the row is walked in chunks; last, chunks only.  Plan
   // creation steps `wide_level` down while the compiled kernel spills.
   bool resident = false;
-  if (rowred && l_min > 1024) {
+  if (rowred && l_min > 1024 && !split_rows) {
     const int e32 = std::max(32, V), e64 = std::max(64, V);
     const bool may_chunk = !colred && !has_transposed;
     if (ecap < e32 && lanes_for(e32) <= 1024 && (opt.wide_level >= 1 || !may_chunk)) ecap = e32, l_min = lanes_for(e32);
@@ -159,7 +167,7 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   }
   // Row reductions over rows that do not fit the registers of one workgroup: the workgroup walks
   // its row in column chunks, once per stage, recomputing what each stage needs.
-  const bool chunked = l_min > 1024 && rowred && !colred && !has_transposed;
+  const bool chunked = (l_min > 1024 && rowred && !colred && !has_transposed) || split_rows;
   // Column reductions alone do not need whole rows either: column tiles, each with its own fold.
   const bool col_tiled = l_min > 1024 && colred && !rowred && !has_transposed;
   if (l_min > 1024 && !tileable && !chunked && !col_tiled)
@@ -168,7 +176,8 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   if (tileable) l_min = std::min(l_min, 256);
   // wide transposes: 2-D tiles through LDS
   const bool tiled_transpose = has_transposed && tileable && C > 256 && R > 1;
-  if (chunked) l_min = 1024;  // (measured: the largest workgroup keeps the fewest rows in flight, so re-reads hit the caches more often)
+  if (split_rows) l_min = 256;
+  else if (chunked) l_min = 1024;  // (measured: the largest workgroup keeps the fewest rows in flight, so re-reads hit the caches more often)
   if (col_tiled) l_min = std::min(256, l_max);
   int L = rowred ? std::min(64, l_max) : std::min(256, l_max);
   // Very narrow rows: a row of at most 32 bytes belongs to one lane (no cross-lane step at all;
@@ -196,7 +205,8 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   // (a row that will be cut into column tiles anyway is not a small problem)
   const bool col_tiles_anyway = tileable && (int64_t)NV * V > (int64_t)L * ecap;
   while ((int64_t)R * L / 64 < 2048 && L < l_max && !(has_transposed && !rowred) && !chunked && !col_tiled && !col_tiles_anyway) L *= 2;
-  if (opt.has_hint && opt.hint.lanes_per_row > 0 && !tiled_transpose) {
+  if (split_rows) L = 256;
+  if (opt.has_hint && opt.hint.lanes_per_row > 0 && !tiled_transpose && !split_rows) {
     const int h = opt.hint.lanes_per_row;
     if ((h & (h - 1)) == 0 && h >= ((chunked || col_tiled) ? 64 : l_min) && h <= 1024) L = h;
   }
@@ -262,7 +272,16 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   s.chunked = chunked;
   s.col_tiled = col_tiled;
   s.tiled_transpose = tiled_transpose;
-  s.n_iters = chunked ? R : col_tiled ? (R + s.G - 1) / s.G : tiled_transpose ? (int)((int64_t)CT * ((R + s.G - 1) / s.G))
+  s.split_rows = split_rows;
+  s.S = 1;
+  s.CPS = CT;
+  if (split_rows) {  // at least 2 chunks per workgroup, about `target` workgroups in all
+    const int target = opt.has_hint && opt.hint.max_workgroups > 0 ? opt.hint.max_workgroups : 512;
+    s.S = std::max(1, std::min((CT + 1) / 2, std::max(1, target / R)));
+    s.CPS = (CT + s.S - 1) / s.S;
+    s.S = (CT + s.CPS - 1) / s.CPS;  // no empty segment
+  }
+  s.n_iters = split_rows ? R * s.S : chunked ? R : col_tiled ? (R + s.G - 1) / s.G : tiled_transpose ? (int)((int64_t)CT * ((R + s.G - 1) / s.G))
                                                                              : (int)(((int64_t)R * CT + s.G - 1) / s.G);
   // Streaming groups launch one workgroup per row tile: the hardware hands tiles out in memory
   // order and a fresh wavefront issues its loads at once, which measures faster on this device
@@ -288,6 +307,10 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   cap = std::min(cap, (int)(0x7fffffff / WG));  // a launch holds fewer than 2^31 lanes: beyond that the workgroups loop
   s.grid = std::max(1, std::min(s.n_iters, cap));
   s.RB = s.grid;
+  if (split_rows) {
+    s.grid = R * s.S;
+    s.RB = s.S;
+  }
   if (col_tiled) {  // RB workgroups per column tile, about `cap` workgroups in all
     s.RB = std::max(1, std::min(s.n_iters, std::max(1, cap / CT)));
     s.grid = s.RB * CT;
@@ -310,6 +333,7 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   // column partials, so both live in one pool of max(loop bytes, fold bytes).
   int fixed = 0, loop_bytes = 0, fold_bytes = 0;
   if (rowred && L > 64) fixed += 2 * s.G * (L / 64) * gp->max_batched_reduces * 4;
+  if (split_rows) fixed += 16 + (int)gp->row_reduces.size() * 4;
   const int fold_width = col_tiled ? NVL * L * V : C;  // columns one workgroup folds
   s.fold_piece = fold_width;
   if (colred) {
@@ -348,6 +372,17 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   gp->part_bytes = 0;
   s.part_stride_floats = 0;
   s.ticket_stride = 0;
+  if (split_rows) {  // per row: S partials of one float per reduction
+    const size_t k = gp->row_reduces.size();
+    int n = s.S;
+    while (n > 1) {
+      s.part_stride_floats += (size_t)n * k;
+      n = (n + s.fan_in - 1) / s.fan_in;
+      s.ticket_stride += n;
+    }
+    gp->n_tickets = s.ticket_stride * R;
+    gp->part_bytes = s.part_stride_floats * R * 4;
+  }
   if (colred) {
     const size_t kc = gp->col_reduces.size() * (size_t)fold_width;
     int n = s.RB;

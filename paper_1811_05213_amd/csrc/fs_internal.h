@@ -93,6 +93,11 @@ struct Schedule {
   // consecutive rows of one column tile of NVL*L*V columns (unit = column tile fastest), so both
   // the reads and the transposed writes are runs of consecutive elements.
   bool tiled_transpose = false;
+  // A few very long rows that are only reduced (every result an [R,1] value): each row is cut into
+  // S segments of CPS chunks, one workgroup per segment, and the segments' partial results are
+  // folded across workgroups with the ticket scheme of the column reductions.
+  bool split_rows = false;
+  int S = 1, CPS = 0;
   // Rows too long for the registers of one workgroup, with row reductions: the row is walked in CT
   // column chunks once per stage, and each stage recomputes the elementwise values it needs from
   // the inputs instead of keeping them (space traded for recomputation, Section 5.1.2).

@@ -429,6 +429,27 @@ def test_work_span_and_layered_planner():
         p.destroy()
 
 
+def test_few_long_rows_are_split_over_workgroups():
+    # [R,1]-only results over a handful of very long rows: one workgroup per row segment, about 512 in all, a per-row fold
+    def norms(rows, cols, keep_full=False):
+        g = Graph()
+        x = g.input(rows, cols)
+        outs = [g.unary("sqrt", g.reduce_row("sum", g.binary("mul", x, x))), g.reduce_row("max", x)]
+        if keep_full:
+            outs.append(g.unary("neg", x))
+        g.set_outputs(outs)
+        return g
+    p = fs.Plan(norms(4, 1 << 22))
+    gi = p.group_info(0)
+    assert p.stats()["num_launches"] == 1 and gi["grid"] == 512 and gi["wg_threads"] == 256 and gi["scratch_bytes"] > 0
+    assert "constexpr int S = 128" in p.group_source(0)
+    assert fs.Plan(norms(4, 1 << 22), hint={"max_workgroups": 64}).group_info(0)["grid"] == 64
+    # an [R,C] output, many rows, or rows a workgroup holds in registers: the ordinary forms
+    assert fs.Plan(norms(4, 1 << 22, keep_full=True)).group_info(0)["grid"] == 4
+    assert fs.Plan(norms(4096, 1 << 18)).group_info(0)["grid"] == 4096
+    assert fs.Plan(norms(4, 1 << 14)).group_info(0)["grid"] == 4
+
+
 def test_survey_patterns_are_single_kernels():
     # every pattern of the shape survey (softmax variants, norms, optimizer update, column sums, transposes, backward passes)
     # from 64 to 131072 columns plans as ONE stitched kernel

@@ -425,6 +425,31 @@ def test_very_narrow_rows():
         both_modes(softmax_graph(rows, cols), [ins[0]], f"narrow softmax {rows}x{cols}")
 
 
+def test_few_very_long_rows_reduced_by_segments():
+    # a handful of rows of millions of elements whose only results are per-row values: every row is cut into segments, one
+    # workgroup each, and the segment results meet through the ticketed fold (several reductions, values before and after
+    # them, a per-row and a per-column operand, bf16 payload, ragged last chunk and last segment)
+    from paper_1811_05213_amd import Plan
+    for rows, cols, dt in ((4, (1 << 22) + 3, "f32"), (1, 3000001, "f32"), (7, 1 << 20, "bf16"), (64, 262144 + 8, "f32"), (3, 2100000, "f32")):
+        g = Graph()
+        x = g.input(rows, cols, dt)
+        w = g.input(rows, 1)
+        b = g.input(1, cols)
+        xf = g.unary("convert", x, "f32") if dt != "f32" else x
+        xs = g.binary("add", g.binary("mul", xf, g.bcast_colvec(g.unary("tanh", w), cols)), g.bcast_rowvec(b, rows))
+        ss = g.reduce_row("sum", g.binary("mul", xs, xs))
+        mx = g.reduce_row("max", xs)
+        mean = g.reduce_row("mean", xf)
+        norm = g.unary("sqrt", ss)
+        g.set_outputs([norm, mx, g.binary("div", mean, g.binary("add", norm, w)), g.reduce_row("min", xs)])
+        p = Plan(g)
+        assert p.stats()["num_launches"] == 1 and p.group_info(0)["grid"] > rows, (rows, cols, p.group_info(0))
+        xv = (0.5 + RNG.standard_normal((rows, cols))).astype(np.float32)  # a mean well away from zero: no cancellation
+        ins = [f32_to_bf16_bits(xv) if dt == "bf16" else xv, RNG.uniform(0.5, 2, (rows, 1)).astype(np.float32), (0.1 * RNG.standard_normal((1, cols))).astype(np.float32)]
+        both_modes(g, ins, f"segmented rows {rows}x{cols} {dt}")
+        both_modes(g, ins, f"segmented rows again {rows}x{cols} {dt}")  # the tickets are left at zero
+
+
 def test_wide_transposes_in_2d_tiles():
     # reduction-free groups with transposed roots over more than 256 columns: 2-D tiles through LDS (ragged in both directions,
     # bf16 and u8 payloads, several roots, per-column and per-row operands)
