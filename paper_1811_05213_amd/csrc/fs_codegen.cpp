@@ -379,11 +379,16 @@ struct Emitter {
     for (int m : gp.members)
       if (gp.level.at(m) == 0 && gp.kind.at(m) == KIND_COLV && !is_rr(m) && !folded[m])
         os << "  const float " << name(m, KIND_COLV) << " = " << rounded(m, expr(m)) << ";\n";
+    // one pass over the segment: the reductions' operands, and what leaves the kernel as [R,C] or [1,C]
+    // tensors (all of it computed before any reduction result)
+    std::vector<int> targets(gp.row_reduces);
     std::set<int> mem, ext;
-    needed_for(gp.row_reduces, &mem, &ext);
+    for (const ExtTensor& e : gp.ext_out)
+      if (e.kind != KIND_COLV) targets.push_back(e.node), mem.insert(e.node);
+    needed_for(targets, &mem, &ext);
     for (int b : gp.row_reduces) os << "  float q" << loc(b) << " = fs_red_identity<" << g.nodes[b].attr_i << ">();\n";
     os << "  {\n    const int ch_end = (seg + 1) * CPS < CT ? (seg + 1) * CPS : CT;\n";
-    emit_pass(mem, ext, false, [&]() { emit_chunk_accumulate(gp.row_reduces); }, "for (int ch = seg * CPS; ch < ch_end; ++ch)");
+    emit_pass(mem, ext, true, [&]() { emit_chunk_accumulate(gp.row_reduces); }, "for (int ch = seg * CPS; ch < ch_end; ++ch)");
     os << "  }\n";
     // fold the workgroup's lanes (the results are not rounded or divided yet: that happens once, at the end)
     for (int b : gp.row_reduces)
@@ -416,7 +421,8 @@ struct Emitter {
       }
     }
     for (const ExtTensor& e : gp.ext_out)
-      os << "      fs_store1<" << e.dtype << ">(a.p[" << e.arg << "], row, " << name(source_of(e.node), KIND_COLV) << ");\n";
+      if (e.kind == KIND_COLV)
+        os << "      fs_store1<" << e.dtype << ">(a.p[" << e.arg << "], row, " << name(source_of(e.node), KIND_COLV) << ");\n";
     os << "    }\n  }\n}\n";
   }
 

@@ -145,12 +145,15 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   const bool tileable = !rowred && !colred;
   bool has_transposed = false;
   for (const ExtTensor& e : gp->ext_out) has_transposed |= e.transposed;
-  // A few very long rows whose reductions are all the group produces: splitting each row over many
-  // workgroups beats any single-workgroup form ([4, 4M] row sums: 263 us on 4 CUs).
-  bool split_rows = false;
-  if (rowred && !colred && !has_transposed && R <= 128 && (int64_t)C * max_es >= (1 << 18) && (int64_t)R * C * max_es >= (1 << 20)) {
-    split_rows = true;
-    for (const ExtTensor& e : gp->ext_out) split_rows &= e.kind == KIND_COLV;
+  // A few very long rows occupy as many CUs as there are rows ([4, 4M] row sums: 263 us on 4 CUs).
+  // When every row reduction of the group is in its first stage and everything else that leaves the
+  // group is either a per-row value or computed before any reduction result, each row is split
+  // over many workgroups; other such groups are better cut into kernels of that form and
+  // reduction-free ones (worth_fusing).
+  const bool few_long_rows = rowred && !colred && !has_transposed && R <= 128 && (int64_t)C * max_es >= (1 << 18) && (int64_t)R * C * max_es >= (1 << 20);
+  bool split_rows = few_long_rows;
+  if (split_rows) {
+    for (const ExtTensor& e : gp->ext_out) split_rows &= e.kind == KIND_COLV || gp->level.at(e.node) == 0;
     for (int m : gp->row_reduces) split_rows &= gp->level.at(m) == 0;
   }
   // Rows too long for that: first more elements per lane (32, then 64: one workgroup per CU, but the
@@ -273,6 +276,7 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   s.col_tiled = col_tiled;
   s.tiled_transpose = tiled_transpose;
   s.split_rows = split_rows;
+  s.few_long_rows = few_long_rows;
   s.S = 1;
   s.CPS = CT;
   if (split_rows) {  // at least 2 chunks per workgroup, about `target` workgroups in all
@@ -612,6 +616,12 @@ bool worth_fusing(const GroupPlan& merged) {
   if (merged.members.size() > 1 && !merged.s.tile_transpose && !merged.s.tiled_transpose && merged.min_hbm_bytes >= kFoldWorthBytes)
     for (const ExtTensor& e : merged.ext_out)
       if (e.transposed) return false;
+  // A handful of very long rows: one workgroup per row leaves most of the device idle, so such a
+  // group, if its rows do not fit one workgroup's registers either, is only formed when its rows can
+  // be split over workgroups.  Softmax of [8, 1M]: 286 us as
+  // one kernel on 8 CUs, 38 us as three kernels that each fill the device; [32, 256K]: 73 -> 37 us;
+  // from 64 rows on the single kernel is as fast or faster ([128, 64K]: 20 against 35 us).
+  if (merged.members.size() > 1 && merged.s.few_long_rows && !merged.s.split_rows && merged.s.chunked && merged.R <= 32) return false;
   return merged.col_reduces.empty() || merged.members.size() == 1 || merged.s.grid == 1 || merged.min_hbm_bytes >= kFoldWorthBytes;
 }
 

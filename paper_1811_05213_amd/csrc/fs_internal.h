@@ -96,6 +96,7 @@ struct Schedule {
   // A few very long rows that are only reduced (every result an [R,1] value): each row is cut into
   // S segments of CPS chunks, one workgroup per segment, and the segments' partial results are
   // folded across workgroups with the ticket scheme of the column reductions.
+  bool few_long_rows = false;
   bool split_rows = false;
   int S = 1, CPS = 0;
   // Rows too long for the registers of one workgroup, with row reductions: the row is walked in CT

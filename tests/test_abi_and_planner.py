@@ -273,7 +273,7 @@ def test_ragged_and_degenerate_shapes_plan():
         assert gi["elems_per_lane"] * gi["lanes_per_row"] >= cols
         p.destroy()
     # rows too long for one workgroup's registers are walked in chunks (one row per workgroup, recomputation per stage)
-    p = fs.Plan(softmax_graph(2, 1 << 20))
+    p = fs.Plan(softmax_graph(40, 1 << 20))
     gi = p.group_info(0)
     assert p.stats()["num_launches"] == 1 and gi["elems_per_lane"] * gi["lanes_per_row"] < (1 << 20) and gi["rows_per_iter"] == 1
     src = p.group_source(0)
@@ -435,8 +435,10 @@ def test_few_long_rows_are_split_over_workgroups():
         g = Graph()
         x = g.input(rows, cols)
         outs = [g.unary("sqrt", g.reduce_row("sum", g.binary("mul", x, x))), g.reduce_row("max", x)]
-        if keep_full:
+        if keep_full == "before":
             outs.append(g.unary("neg", x))
+        if keep_full == "after":
+            outs.append(g.binary("div", x, g.bcast_colvec(outs[0], cols)))
         g.set_outputs(outs)
         return g
     p = fs.Plan(norms(4, 1 << 22))
@@ -444,10 +446,19 @@ def test_few_long_rows_are_split_over_workgroups():
     assert p.stats()["num_launches"] == 1 and gi["grid"] == 512 and gi["wg_threads"] == 256 and gi["scratch_bytes"] > 0
     assert "constexpr int S = 128" in p.group_source(0)
     assert fs.Plan(norms(4, 1 << 22), hint={"max_workgroups": 64}).group_info(0)["grid"] == 64
-    # an [R,C] output, many rows, or rows a workgroup holds in registers: the ordinary forms
-    assert fs.Plan(norms(4, 1 << 22, keep_full=True)).group_info(0)["grid"] == 4
+    # an [R,C] output computed before any reduction result is stored by the segment workgroups
+    p = fs.Plan(norms(4, 1 << 22, keep_full="before"))
+    assert p.stats()["num_launches"] == 1 and p.group_info(0)["grid"] == 512 and "fs_store_row" in p.group_source(0)
+    # one that depends on a reduction, many rows, or rows a workgroup holds in registers: the ordinary forms
+    p = fs.Plan(norms(40, 1 << 20, keep_full="after"))
+    assert p.stats()["num_launches"] == 1 and p.group_info(0)["grid"] == 40
     assert fs.Plan(norms(4096, 1 << 18)).group_info(0)["grid"] == 4096
     assert fs.Plan(norms(4, 1 << 14)).group_info(0)["grid"] == 4
+    # up to 32 such rows, groups that cannot take this form are not formed: a softmax becomes max | exp and sum (stores the
+    # exponentials) | divide, three launches that each fill the device instead of one on 2 CUs
+    p = fs.Plan(softmax_graph(2, 1 << 20))
+    assert p.stats()["num_launches"] == 3 and [p.group_info(i)["grid"] for i in range(2)] == [256, 256]
+    assert "fs_store_row" in p.group_source(1) and "constexpr int S = 128" in p.group_source(1)
 
 
 def test_survey_patterns_are_single_kernels():

@@ -164,8 +164,9 @@ def test_row_reduce_across_wavefronts():
 
 
 def test_rows_longer_than_a_workgroup_holds():
-    # one workgroup per row walks it in column chunks, once per stage, recomputing what the stage needs
-    for rows, cols in [(3, 100001), (2, 1 << 18), (1100, 40000), (300, 65536), (7, 50001), (5, 131072 + 4 * 77)]:
+    # one workgroup per row walks it in column chunks, once per stage, recomputing what the stage needs (more than 32 rows
+    # where the rows are beyond 256 KiB: fewer are cut into kernels that split the rows)
+    for rows, cols in [(35, 100001), (33, 1 << 18), (1100, 40000), (300, 65536), (7, 50001), (34, 131072 + 4 * 77)]:
         g = softmax_graph(rows, cols)
         p = fs.Plan(g)
         gi = p.group_info(0)
@@ -448,6 +449,24 @@ def test_few_very_long_rows_reduced_by_segments():
         ins = [f32_to_bf16_bits(xv) if dt == "bf16" else xv, RNG.uniform(0.5, 2, (rows, 1)).astype(np.float32), (0.1 * RNG.standard_normal((1, cols))).astype(np.float32)]
         both_modes(g, ins, f"segmented rows {rows}x{cols} {dt}")
         both_modes(g, ins, f"segmented rows again {rows}x{cols} {dt}")  # the tickets are left at zero
+    # [R,C] and [1,C] results that need no reduction result are stored by the segment workgroups
+    for rows, cols in ((3, 700001), (20, 70000)):
+        g = Graph()
+        x, b = g.input(rows, cols), g.input(1, cols)
+        xs = g.binary("mul", x, g.bcast_rowvec(b, rows))
+        g.set_outputs([g.unary("tanh", xs), g.reduce_row("max", xs), g.unary("abs", b), g.unary("rsqrt", g.reduce_row("sum", g.binary("mul", xs, xs)))])
+        p = Plan(g)
+        assert "fs_store_row" in p.group_source(0) and p.group_info(0)["grid"] > rows
+        ins = [RNG.standard_normal((rows, cols)).astype(np.float32), RNG.uniform(-2, 2, (1, cols)).astype(np.float32)]
+        both_modes(g, ins, f"segmented rows with full outputs {rows}x{cols}")
+    # groups that cannot take that form over up to 32 such rows are cut into ones that can: softmax and LayerNorm+GeLU
+    for rows, cols in ((8, (1 << 20) + 5), (1, 1 << 21), (32, 70000)):
+        g = softmax_graph(rows, cols)
+        assert Plan(g).stats()["num_launches"] == 3
+        both_modes(g, [RNG.standard_normal((rows, cols)).astype(np.float32)], f"few long rows softmax {rows}x{cols}")
+    g = layernorm_gelu_graph(3, 300000)
+    assert Plan(g).stats()["num_launches"] > 1
+    both_modes(g, layernorm_gelu_inputs(3, 300000), "few long rows LayerNorm+GeLU")
 
 
 def test_wide_transposes_in_2d_tiles():
