@@ -360,8 +360,9 @@ struct Emitter {
     os << "  }\n}\n";
   }
 
-  // ---- a few very long rows, only reduced: one workgroup per row segment (Schedule::split_rows) ----
-  // Every workgroup folds its segment's chunks into lane partials, the workgroup's lanes are
+  // ---- a few very long rows: one workgroup per row segment (Schedule::split_rows) ----------------
+  // Every workgroup walks its segment's chunks once, storing what leaves the kernel as [R,C] or
+  // [1,C] tensors and folding the reductions' operands into lane partials; the workgroup's lanes are
   // folded as for any row reduction, and the S segment results of a row meet through the ticketed
   // fold of the column reductions (a "vector" of one float per reduction).  The workgroup that
   // folds last also evaluates the per-row values that depend on the results, and stores.

@@ -93,9 +93,11 @@ struct Schedule {
   // consecutive rows of one column tile of NVL*L*V columns (unit = column tile fastest), so both
   // the reads and the transposed writes are runs of consecutive elements.
   bool tiled_transpose = false;
-  // A few very long rows that are only reduced (every result an [R,1] value): each row is cut into
-  // S segments of CPS chunks, one workgroup per segment, and the segments' partial results are
-  // folded across workgroups with the ticket scheme of the column reductions.
+  // A few very long rows (few_long_rows) leave most CUs idle with one workgroup per row.  When all
+  // row reductions are in the first stage and every other result is an [R,1] value or needs no
+  // reduction result (split_rows), each row is cut into S segments of CPS chunks, one workgroup per
+  // segment, and the segments' partial results are folded across workgroups with the ticket scheme
+  // of the column reductions.
   bool few_long_rows = false;
   bool split_rows = false;
   int S = 1, CPS = 0;
