@@ -441,7 +441,7 @@ struct Emitter {
     // workgroup loops over many rows; with one trip per workgroup (or column tiles) they are
     // simply read where the loop body needs them.
     const bool ctile = s.col_tiled;  // column reductions by column tiles: a workgroup keeps its tile, RB workgroups share the rows
-    const bool rowv_in_loop = !ctile && (s.CT > 1 || s.grid >= s.n_iters);
+    const bool rowv_in_loop = !ctile && (s.CT > 1 || s.grid >= s.n_iters || s.stage_rowv);
 
     // fixed local numbering: external inputs first, then members
     for (const ExtTensor& e : gp.ext_in) loc(e.node);
@@ -500,7 +500,7 @@ struct Emitter {
     if (K > 0) os << "  __shared__ fs_u32 lds_flag;\n";
 
     // ---- per-column values ----
-    // (looping kernels: loaded once per workgroup, before the loop; LDS staging only exists in one-trip kernels)
+    // (looping kernels without LDS staging: loaded into registers once per workgroup, before the loop)
     auto emit_rowv = [&](const std::string& ind, const std::string& vb, const std::string& store_cond) {
       for (const ExtTensor& e : gp.ext_in)
         if (e.kind == KIND_ROWV) {
@@ -519,6 +519,15 @@ struct Emitter {
       }
     };
     if (!rowv_in_loop) emit_rowv("  ", ctile ? "vbase" : "0", "rb == 0 && rg == 0");
+    // staged [1,C] operands of a looping kernel: written to LDS once, before the loop
+    const bool stage_before_loop = s.stage_rowv && s.grid < s.n_iters;
+    auto emit_staging = [&](const std::string& ind) {
+      int k = 0;
+      for (const ExtTensor& e : gp.ext_in)
+        if (e.kind == KIND_ROWV) os << ind << "fs_stage_rowvec<" << e.dtype << ", V, L, C, WG>(lds_rowv + " << (k++) << " * SLOT, a.p[" << e.arg << "]);\n";
+      os << ind << "__syncthreads();\n";
+    };
+    if (stage_before_loop) emit_staging("  ");
     for (int k = 0; k < K; ++k) {
       const int m = gp.col_reduces[k];
       os << "  float ca" << loc(m) << "[E];\n  _Pragma(\"unroll\") for (int e = 0; e < E; ++e) ca" << loc(m) << "[e] = fs_red_identity<"
@@ -568,12 +577,7 @@ struct Emitter {
     // operands are written to LDS up front; only their reads into registers are lazy.
     std::set<int> rowv_ready;
     const bool lazy_rowv = rowv_in_loop;
-    if (lazy_rowv && s.stage_rowv) {
-      int k = 0;
-      for (const ExtTensor& e : gp.ext_in)
-        if (e.kind == KIND_ROWV) os << "    fs_stage_rowvec<" << e.dtype << ", V, L, C, WG>(lds_rowv + " << (k++) << " * SLOT, a.p[" << e.arg << "]);\n";
-      os << "    __syncthreads();\n";
-    }
+    if (lazy_rowv && s.stage_rowv && !stage_before_loop) emit_staging("    ");
     std::function<void(int)> ensure_rowv = [&](int src) {
       if (!lazy_rowv || rowv_ready.count(src)) return;
       rowv_ready.insert(src);

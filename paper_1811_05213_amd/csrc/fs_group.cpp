@@ -252,6 +252,28 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   }
   else if (total_waves > 1024 || has_transposed) WG = std::max(256, L);
   else WG = std::max(64, L);
+  // Rows across several wavefronts whose [1,C] operands outweigh the row's own traffic (LayerNorm
+  // with gamma, beta and a bias over bf16 rows: 12 bytes per column against 4): re-reading the
+  // operands for every row costs L2 bandwidth, keeping them in registers costs occupancy (48 of 84
+  // registers).  When they fit the LDS budget, 4 rows share a workgroup that stages them once and
+  // loops, 32 wavefronts per CU (LayerNorm+GeLU bf16 [8192,4096]: 35.3 us re-reading, 31.2 us from
+  // registers, 27.6 us staged; [16384,2048]: 29.3 -> 26.5 us).
+  bool staged_loop = false;
+  if (rowred && !colred && !chunked && !has_transposed && CT == 1 && L >= 128 && R > 1) {
+    int64_t rowv_bytes = 0, full_bytes = 0;
+    int n_rowv_in = 0;
+    for (const ExtTensor& e : gp->ext_in) {  // bytes per column
+      if (e.kind == KIND_ROWV) rowv_bytes += dtype_size(e.dtype), ++n_rowv_in;
+      if (e.kind == KIND_FULL) full_bytes += dtype_size(e.dtype);
+    }
+    for (const ExtTensor& e : gp->ext_out)
+      if (e.kind == KIND_FULL) full_bytes += dtype_size(e.dtype);
+    const int wg = std::min(1024, 4 * L);
+    if (rowv_bytes * 2 >= full_bytes * 3 && (int64_t)n_rowv_in * NVL * L * V * 4 + 1024 <= opt.lds_budget && (int64_t)R * L / wg >= 2 * (524288 / wg)) {  // at least two trips
+      staged_loop = true;
+      WG = wg;
+    }
+  }
   if (chunked) WG = L;  // one row per workgroup
   if (tiled_transpose) WG = std::max(64, L * std::min(tt_rows, std::max(4, pow2_ceil(R))));
   if (opt.has_hint && opt.hint.wg_threads > 0 && !chunked && !tiled_transpose) {
@@ -297,7 +319,9 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   // own traffic (LayerNorm with gamma, beta and a bias over rows of 4096+ elements: 12 bytes per
   // column against 4), the workgroups loop instead, 16 wavefronts per CU, and keep their slices of
   // the operands in registers (measured on [8192,4096] bf16: 35.3 -> 29.4 us).
-  if (!colred && !chunked && CT == 1 && s.G < 4 && R > 1) {
+  if (staged_loop && s.G >= 2) {
+    cap = std::max(256, 524288 / WG);
+  } else if (!colred && !chunked && CT == 1 && s.G < 4 && R > 1) {
     int64_t rowv_bytes = 0, full_bytes = 0;
     for (const ExtTensor& e : gp->ext_in) {  // bytes per column
       if (e.kind == KIND_ROWV) rowv_bytes += dtype_size(e.dtype);
@@ -349,8 +373,8 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
     fold_bytes = fold_rows * s.fold_piece * 4;
   }
   auto total = [&]() { return fixed + std::max(loop_bytes, fold_bytes); };
-  // [1,C] inputs shared by all rows of a workgroup: with one trip per workgroup they are staged in
-  // LDS by the whole workgroup when several rows share them and the budget allows
+  // [1,C] inputs shared by all rows of a workgroup are staged in LDS by the whole workgroup (once,
+  // before the loop, when the workgroup loops) when several rows share them and the budget allows
   int n_rowv = 0;
   for (const ExtTensor& e : gp->ext_in) n_rowv += e.kind == KIND_ROWV;
   s.stage_rowv = false;
@@ -361,7 +385,7 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
     loop_bytes += tile_bytes;
   }
   const int slot_bytes = s.NVL * s.L * V * 4;
-  if (n_rowv > 0 && CT == 1 && s.grid >= s.n_iters && s.G >= 4 && R > 1 &&
+  if (n_rowv > 0 && CT == 1 && (s.G >= 4 || (staged_loop && s.G >= 2)) && R > 1 &&
       fixed + std::max(loop_bytes + n_rowv * slot_bytes, fold_bytes) <= opt.lds_budget) {
     s.stage_rowv = true;
     loop_bytes += n_rowv * slot_bytes;
