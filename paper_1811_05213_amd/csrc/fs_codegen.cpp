@@ -160,6 +160,22 @@ struct Emitter {
 
   static std::string tmpl_row() { return "V, NVL, L, NV, RAGGED"; }
 
+  // The last stage of a row-reduction body (everything after the last exchange: normalise, scale,
+  // activation, stores) can be emitted vector by vector: the same statements inside a loop over
+  // the lane's NVL vectors, each touching the V elements of vector j only.  Operands that are read
+  // where they are used (staged or reloaded [1,C] tensors) and the values on their way to a store
+  // are then live for one vector at a time instead of the whole slice (LayerNorm+bias+GeLU with
+  // 16 elements per lane: 66 -> 61 registers, i.e. 8 instead of 7 wavefronts per SIMD).
+  bool strip = false;
+  std::ostringstream pre;  // while `strip`: array declarations and per-row scalars, placed before the loop
+  std::string eloop() const {
+    return strip ? "_Pragma(\"unroll\") for (int e = j * V; e < (j + 1) * V; ++e) " : "_Pragma(\"unroll\") for (int e = 0; e < E; ++e) ";
+  }
+  void declare(const std::string& nm, const std::string& ind) { (strip ? pre : os) << ind << "float " << nm << "[E];\n"; }
+  // row-slice calls: whole slice, or vector j of it
+  std::string vec_fn(const char* fn) const { return std::string(fn) + (strip ? "_vec" : ""); }
+  std::string vec_arg() const { return strip ? ", j" : ""; }
+
   // an array holding operand `o` as a full slice (needed by max/min reductions / transposed stores)
   std::string as_array(int o, const std::string& tag) {
     o = source_of(o) == o || !op_is_free(g.nodes[o].opcode) ? source_of(o) : o;
@@ -188,10 +204,10 @@ struct Emitter {
       return;
     }
     if (e.kind == KIND_FULL)
-      os << indent << "fs_store_row<" << e.dtype << ", " << tmpl_row() << ", " << (e.streaming ? "true" : "false") << ">(" << nm << ", a.p["
-         << e.arg << "], row0, lir, vbase, rok);\n";
+      os << indent << vec_fn("fs_store_row") << "<" << e.dtype << ", " << tmpl_row() << ", " << (e.streaming ? "true" : "false") << ">(" << nm
+         << ", a.p[" << e.arg << "], row0, lir, vbase, rok" << vec_arg() << ");\n";
     else if (e.kind == KIND_COLV)
-      os << indent << "if (rok && lir == 0 && vbase == 0) fs_store1<" << e.dtype << ">(a.p[" << e.arg << "], row, " << nm << ");\n";
+      (strip ? pre : os) << indent << "if (rok && lir == 0 && vbase == 0) fs_store1<" << e.dtype << ">(a.p[" << e.arg << "], row, " << nm << ");\n";
   }
 
   void count_uses() {
@@ -587,9 +603,12 @@ struct Emitter {
         for (const ExtTensor& e : gp.ext_in) {
           if (e.kind != KIND_ROWV) continue;
           if (e.node == src) {
-            os << "    float " << nm << "[E];\n";
-            if (s.stage_rowv) os << "    fs_read_staged<" << tmpl_row() << ">(" << nm << ", lds_rowv + " << k << " * SLOT, lir);\n";
-            else os << "    fs_load_row<" << e.dtype << ", " << tmpl_row() << ">(" << nm << ", a.p[" << e.arg << "], 0, lir, vbase);\n";
+            declare(nm, "    ");
+            if (s.stage_rowv)
+              os << "    " << vec_fn("fs_read_staged") << "<" << tmpl_row() << ">(" << nm << ", lds_rowv + " << k << " * SLOT, lir" << vec_arg() << ");\n";
+            else
+              os << "    " << vec_fn("fs_load_row") << "<" << e.dtype << ", " << tmpl_row() << ">(" << nm << ", a.p[" << e.arg << "], 0, lir, vbase"
+                 << vec_arg() << ");\n";
           }
           ++k;
         }
@@ -603,10 +622,11 @@ struct Emitter {
         if (g.nodes[o].opcode != FS_CONST && gp.kind.at(o) == KIND_ROWV) ensure_rowv(o);
       }
       if (folded[src]) return;
-      os << "    float " << nm << "[E];\n    _Pragma(\"unroll\") for (int e = 0; e < E; ++e) " << nm << "[e] = " << rounded(src, expr(src)) << ";\n";
+      declare(nm, "    ");
+      os << "    " << eloop() << nm << "[e] = " << rounded(src, expr(src)) << ";\n";
       if (const ExtTensor* e = find_out(src))
-        os << "    if (row == 0 && rok) fs_store_row<" << e->dtype << ", " << tmpl_row() << ">(" << nm << ", a.p[" << e->arg
-           << "], 0, lir, vbase, true);\n";
+        os << "    if (row == 0 && rok) " << vec_fn("fs_store_row") << "<" << e->dtype << ", " << tmpl_row() << ">(" << nm << ", a.p[" << e->arg
+           << "], 0, lir, vbase, true" << vec_arg() << ");\n";
     };
     std::function<void(int)> ensure_rowv_operands = [&](int m) {
       const fs_node& n = g.nodes[m];
@@ -629,6 +649,15 @@ struct Emitter {
       return (int)is_rr(x) < (int)is_rr(y);
     });
     const std::string col_ok = "(!RAGGED || ((e / V) * L + lir) < NV)";
+    // the statements after the last exchange are emitted vector by vector (see `strip`) when the
+    // lane holds several vectors and they are plain elementwise work and stores
+    size_t tail_start = 0;
+    for (size_t k = 0; k < order.size(); ++k)
+      if (is_rr(order[k])) tail_start = k + 1;
+    bool strip_tail = tail_start > 0 && tail_start < order.size() && s.NVL >= 2 && U == 1 && !s.resident && !s.tile_transpose && !s.tiled_transpose;
+    for (const ExtTensor& e : gp.ext_out) strip_tail &= !e.transposed;
+    for (size_t k = tail_start; k < order.size() && strip_tail; ++k) strip_tail &= g.nodes[order[k]].opcode != FS_TRANSPOSE;
+    std::ostringstream before_strip;
 
     for (int u = 0; u < U; ++u) {
       if (U > 1) {
@@ -642,6 +671,12 @@ struct Emitter {
       }
       size_t i = 0;
     while (i < order.size()) {
+      if (i == tail_start && strip_tail) {
+        strip = true;
+        pre.str("");
+        before_strip.str("");
+        before_strip.swap(os);
+      }
       const int m = order[i];
       const fs_node& n = g.nodes[m];
       if (lazy_rowv) {
@@ -700,32 +735,37 @@ struct Emitter {
         const std::string ca = "ca" + std::to_string(loc(m));
         if (folded[n.in[0]]) {
           const fs_node& mn = g.nodes[n.in[0]];
-          os << "    _Pragma(\"unroll\") for (int e = 0; e < E; ++e) " << ca << "[e] = rok ? __builtin_fmaf(" << ref(mn.in[0]) << ", "
-             << ref(mn.in[1]) << ", " << ca << "[e]) : " << ca << "[e];\n";
+          os << "    " << eloop() << ca << "[e] = rok ? __builtin_fmaf(" << ref(mn.in[0]) << ", " << ref(mn.in[1]) << ", " << ca << "[e]) : " << ca
+             << "[e];\n";
         } else {
-          os << "    _Pragma(\"unroll\") for (int e = 0; e < E; ++e) " << ca << "[e] = rok ? fs_red_op<" << n.attr_i << ">(" << ca << "[e], "
-             << ref(n.in[0]) << ") : " << ca << "[e];\n";
+          os << "    " << eloop() << ca << "[e] = rok ? fs_red_op<" << n.attr_i << ">(" << ca << "[e], " << ref(n.in[0]) << ") : " << ca << "[e];\n";
         }
         continue;
       }
       if (n.opcode == FS_TRANSPOSE) {
         // no arithmetic: an in-group operand is aliased; an operand from memory is copied (it was loaded as it lies)
         if (!is_alias(m)) {
-          os << "    float " << name(m, KIND_FULL) << "[E];\n    _Pragma(\"unroll\") for (int e = 0; e < E; ++e) " << name(m, KIND_FULL)
-             << "[e] = " << ref(n.in[0]) << ";\n";
+          declare(name(m, KIND_FULL), "    ");
+          os << "    " << eloop() << name(m, KIND_FULL) << "[e] = " << ref(n.in[0]) << ";\n";
         }
         if (const ExtTensor* e = find_out(m)) emit_store(*e, "    ");
         continue;
       }
       const Kind k = gp.kind.at(m);
       if (k == KIND_COLV) {
-        os << "    const float " << name(m, k) << " = " << rounded(m, expr(m)) << ";\n";
+        (strip ? pre : os) << "    const float " << name(m, k) << " = " << rounded(m, expr(m)) << ";\n";
       } else {
-        os << "    float " << name(m, k) << "[E];\n    _Pragma(\"unroll\") for (int e = 0; e < E; ++e) " << name(m, k) << "[e] = "
-           << rounded(m, expr(m)) << ";\n";
+        declare(name(m, k), "    ");
+        os << "    " << eloop() << name(m, k) << "[e] = " << rounded(m, expr(m)) << ";\n";
       }
       if (const ExtTensor* e = find_out(m)) emit_store(*e, "    ");
     }
+      if (strip) {
+        strip = false;
+        const std::string body = os.str();
+        os.swap(before_strip);
+        os << pre.str() << "    _Pragma(\"unroll\") for (int j = 0; j < NVL; ++j) {\n" << body << "    }\n";
+      }
       if (U > 1) os << "    }\n";
     }
     if (lazy_rowv)  // [1,C] members nothing in the body consumed (outputs only)

@@ -164,24 +164,30 @@ template <int DT, int V, bool NT = false> FS_DEV void fs_store_vec(const float* 
 // per row; RAGGED says some of those vector indices can fall beyond NV: they are clamped too.
 // Nothing here branches, so all loads of a body are issued back to back and waited for once;
 // lanes outside the tensor hold duplicates that are never stored and never reduced.
+// (the _vec forms handle vector j of the slice alone: a body that is emitted vector by vector
+// keeps fewer registers live)
+template <int DT, int V, int NVL, int L, int NV, bool RAGGED, bool NT = false>
+FS_DEV void fs_load_row_vec(float (&dst)[NVL * V], const void* base, long row_elem0, int lir, int vbase, int j) {
+  int vi = vbase + j * L + lir;
+  if (RAGGED) vi = vi < NV ? vi : NV - 1;
+  fs_load_vec<DT, V, NT>(&dst[j * V], base, row_elem0 + (long)vi * V);
+}
 template <int DT, int V, int NVL, int L, int NV, bool RAGGED, bool NT = false>
 FS_DEV void fs_load_row(float (&dst)[NVL * V], const void* base, long row_elem0, int lir, int vbase) {
 #pragma unroll
-  for (int j = 0; j < NVL; ++j) {
-    int vi = vbase + j * L + lir;
-    if (RAGGED) vi = vi < NV ? vi : NV - 1;
-    fs_load_vec<DT, V, NT>(&dst[j * V], base, row_elem0 + (long)vi * V);
-  }
+  for (int j = 0; j < NVL; ++j) fs_load_row_vec<DT, V, NVL, L, NV, RAGGED, NT>(dst, base, row_elem0, lir, vbase, j);
 }
 
 template <int DT, int V, int NVL, int L, int NV, bool RAGGED, bool NT = false>
+FS_DEV void fs_store_row_vec(const float (&src)[NVL * V], void* base, long row_elem0, int lir, int vbase, bool rok, int j) {
+  const int vi = vbase + j * L + lir;
+  const bool ok = rok && (!RAGGED || vi < NV);
+  if (ok) fs_store_vec<DT, V, NT>(&src[j * V], base, row_elem0 + (long)vi * V);
+}
+template <int DT, int V, int NVL, int L, int NV, bool RAGGED, bool NT = false>
 FS_DEV void fs_store_row(const float (&src)[NVL * V], void* base, long row_elem0, int lir, int vbase, bool rok) {
 #pragma unroll
-  for (int j = 0; j < NVL; ++j) {
-    const int vi = vbase + j * L + lir;
-    const bool ok = rok && (!RAGGED || vi < NV);
-    if (ok) fs_store_vec<DT, V, NT>(&src[j * V], base, row_elem0 + (long)vi * V);
-  }
+  for (int j = 0; j < NVL; ++j) fs_store_row_vec<DT, V, NVL, L, NV, RAGGED, NT>(src, base, row_elem0, lir, vbase, rok, j);
 }
 
 // Transposing store of the lane's slice of row `row` of a [R,C] value into a [C,R] tensor.
@@ -227,31 +233,30 @@ template <int DT, int V, int L, int C, int WG> FS_DEV void fs_stage_rowvec(float
 }
 // The lane's slice of a staged vector (same element ownership as fs_load_row).
 template <int V, int NVL, int L, int NV, bool RAGGED>
-FS_DEV void fs_read_staged(float (&dst)[NVL * V], const float* lds, int lir) {
+FS_DEV void fs_read_staged_vec(float (&dst)[NVL * V], const float* lds, int lir, int j) {
   if constexpr (V % 4 == 0) {
     constexpr int Q = V / 4;
     typedef float f4 __attribute__((ext_vector_type(4)));
 #pragma unroll
-    for (int j = 0; j < NVL; ++j) {
+    for (int q = 0; q < Q; ++q) {
+      const f4 x = *reinterpret_cast<const f4*>(lds + ((j * Q + q) * L + lir) * 4);
 #pragma unroll
-      for (int q = 0; q < Q; ++q) {
-        const f4 x = *reinterpret_cast<const f4*>(lds + ((j * Q + q) * L + lir) * 4);
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          const float xk = x[k];
-          dst[j * V + q * 4 + k] = xk;
-        }
+      for (int k = 0; k < 4; ++k) {
+        const float xk = x[k];
+        dst[j * V + q * 4 + k] = xk;
       }
     }
   } else {
+    int vi = j * L + lir;
+    if (RAGGED) vi = vi < NV ? vi : NV - 1;
 #pragma unroll
-    for (int j = 0; j < NVL; ++j) {
-      int vi = j * L + lir;
-      if (RAGGED) vi = vi < NV ? vi : NV - 1;
-#pragma unroll
-      for (int k = 0; k < V; ++k) dst[j * V + k] = lds[vi * V + k];
-    }
+    for (int k = 0; k < V; ++k) dst[j * V + k] = lds[vi * V + k];
   }
+}
+template <int V, int NVL, int L, int NV, bool RAGGED>
+FS_DEV void fs_read_staged(float (&dst)[NVL * V], const float* lds, int lir) {
+#pragma unroll
+  for (int j = 0; j < NVL; ++j) fs_read_staged_vec<V, NVL, L, NV, RAGGED>(dst, lds, lir, j);
 }
 
 template <int DT> FS_DEV void fs_store1_fwd(void* base, long i, float x) {
