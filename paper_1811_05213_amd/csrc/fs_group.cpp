@@ -252,14 +252,18 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   }
   else if (total_waves > 1024 || has_transposed) WG = std::max(256, L);
   else WG = std::max(64, L);
-  // Rows across several wavefronts whose [1,C] operands outweigh the row's own traffic (LayerNorm
-  // with gamma, beta and a bias over bf16 rows: 12 bytes per column against 4): re-reading the
-  // operands for every row costs L2 bandwidth, keeping them in registers costs occupancy (48 of 84
-  // registers).  When they fit the LDS budget, 4 rows share a workgroup that stages them once and
-  // loops, 32 wavefronts per CU (LayerNorm+GeLU bf16 [8192,4096]: 35.3 us re-reading, 31.2 us from
-  // registers, 27.6 us staged; [16384,2048]: 29.3 -> 26.5 us).
+  // Rows whose [1,C] operands outweigh the row's own traffic (LayerNorm with gamma, beta and a bias
+  // over bf16 rows: 12 bytes per column against 4).  Re-reading the operands for every row, or for
+  // every few rows of a one-trip workgroup, costs L2 bandwidth; keeping them in registers costs
+  // occupancy (48 of 84 registers).  When they fit the LDS budget and there is work for more than
+  // two rounds of resident workgroups, the workgroups loop instead, 32 wavefronts per CU, and stage
+  // the operands in LDS once, before the loop.  LayerNorm+GeLU bf16 [8192,4096]: 35.3 us re-reading,
+  // 31.2 us from registers, 27.6 us staged; [16384,2048]: 29.3 -> 26.5 us; [16384,1024]: 14.7 ->
+  // 13.1 us (one trip: staged once per 4 rows); no gain without such operands (softmax: 3-7 % slower),
+  // nor for one-wavefront rows with fewer than 16 elements per lane or a half-empty last vector
+  // ([16384,512]: 9.2 -> 9.7 us, [32768,768]: 22.6 -> 24.1 us), which keep the one-trip form.
   bool staged_loop = false;
-  if (rowred && !colred && !chunked && !has_transposed && CT == 1 && L >= 128 && R > 1) {
+  if (rowred && !colred && !chunked && !has_transposed && CT == 1 && R > 1) {
     int64_t rowv_bytes = 0, full_bytes = 0;
     int n_rowv_in = 0;
     for (const ExtTensor& e : gp->ext_in) {  // bytes per column
@@ -268,8 +272,11 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
     }
     for (const ExtTensor& e : gp->ext_out)
       if (e.kind == KIND_FULL) full_bytes += dtype_size(e.dtype);
-    const int wg = std::min(1024, 4 * L);
-    if (rowv_bytes * 2 >= full_bytes * 3 && (int64_t)n_rowv_in * NVL * L * V * 4 + 1024 <= opt.lds_budget && (int64_t)R * L / wg >= 2 * (524288 / wg)) {  // at least two trips
+    const int wg = L >= 128 ? std::min(1024, 4 * L) : 1024;
+    // (one-wavefront rows: beyond ~8 rounds of resident workgroups the one-trip form catches up and
+    // passes: [65536,1024] 48.9 against 49.5 us, [262144,1024] 203 against 210 us)
+    const bool full_slices = L >= 128 || (NVL * V >= 16 && (int64_t)NVL * L == NV && (int64_t)R * L <= 8 * 524288);
+    if (full_slices && rowv_bytes * 2 >= full_bytes * 3 && (int64_t)n_rowv_in * NVL * L * V * 4 + 1024 <= opt.lds_budget && (int64_t)R * L / wg >= 2 * (524288 / wg)) {
       staged_loop = true;
       WG = wg;
     }
