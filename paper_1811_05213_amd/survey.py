@@ -94,6 +94,13 @@ def transpose(r, c, dt="f32"):
     return g
 
 
+def row_norms(r, c):
+    g = Graph()
+    x = g.input(r, c)
+    g.set_outputs([g.unary("sqrt", g.reduce_row("sum", g.binary("mul", x, x))), g.reduce_row("max", x)])
+    return g
+
+
 def cases():
     out = []
     for r, c in [(4096, 4096), (16384, 2048), (65536, 128), (8192, 8192), (2048, 32768), (1 << 20, 64), (4096, 65536), (2048, 131072)]:
@@ -118,6 +125,10 @@ def cases():
     for r, c in [(16384, 1024), (8192, 4096), (4096, 8192)]:
         out.append(("layernorm backward f32", layernorm_grad_graph(r, c), r, c))
     out.append(("softmax backward f32", softmax_grad_graph(8192, 4096), 8192, 4096))
+    # a handful of very long rows: rows split over workgroups (norms), or cut into such kernels (softmax: 3 launches)
+    for r, c in [(4, 1 << 22), (1, 1 << 26), (96, 1 << 19)]:
+        out.append(("row L2 norm + max f32", row_norms(r, c), r, c))
+    out.append(("softmax f32", softmax_graph(8, 1 << 20), 8, 1 << 20))
     return out
 
 

@@ -463,10 +463,14 @@ def test_few_long_rows_are_split_over_workgroups():
 
 def test_survey_patterns_are_single_kernels():
     # every pattern of the shape survey (softmax variants, norms, optimizer update, column sums, transposes, backward passes)
-    # from 64 to 131072 columns plans as ONE stitched kernel
+    # from 64 to 131072 columns plans as ONE stitched kernel (the softmax over 8 rows of a million columns is the one
+    # exception: cut into three kernels that each fill the device)
     from paper_1811_05213_amd import survey
     for name, g, rows, cols in survey.cases():
         p = fs.Plan(g)
-        assert p.stats()["num_launches"] == 1, (name, rows, cols)
-        assert p.stats()["launched_hbm_bytes"] == p.stats()["min_hbm_bytes"] == min_hbm_bytes(g)
+        if rows <= 32 and cols >= (1 << 20) and "softmax" in name:
+            assert p.stats()["num_launches"] == 3, (name, rows, cols)
+        else:
+            assert p.stats()["num_launches"] == 1, (name, rows, cols)
+            assert p.stats()["launched_hbm_bytes"] == p.stats()["min_hbm_bytes"] == min_hbm_bytes(g)
         p.destroy()
