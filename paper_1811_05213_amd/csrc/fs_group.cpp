@@ -588,6 +588,13 @@ std::vector<fs_sched_hint> candidate_hints(const GroupPlan& base) {
       }
   // looping kernels: the other number of row tiles per trip with the base shape
   if (s.grid < s.n_iters && s.CT == 1) out.push_back(fs_sched_hint{s.L, s.WG, 0, s.U == 1 ? 2 : 1});
+  // row-reduction groups with [1,C] operands staged in LDS: one trip per workgroup against looping
+  // workgroups that stage once (32 wavefronts per CU), whichever the base is not
+  if (s.stage_rowv && base.col_reduces.empty() && s.CT == 1 && s.L <= 256) {
+    const int wg_loop = s.L >= 128 ? std::min(1024, 4 * s.L) : 1024, wg_once = std::max(256, 4 * s.L);
+    if (s.grid >= s.n_iters) out.push_back(fs_sched_hint{s.L, wg_loop, 524288 / wg_loop, 0});
+    else if (wg_once <= 1024) out.push_back(fs_sched_hint{s.L, wg_once, 1 << 20, 0});
+  }
   return out;
 }
 

@@ -573,7 +573,7 @@ fs_status fs_plan_tune(fs_plan* plan, const void* const* inputs, void* const* ou
       cands.push_back(std::move(c));
     }
     const bool cold = base.min_hbm_bytes > (1ull << 20);
-    if (cold && !res.flush) FS_HIP(hipMalloc(&res.flush, 2 * kFlushBytes));
+    if (!res.flush) FS_HIP(hipMalloc(&res.flush, 2 * kFlushBytes));
 
     double cur_us = 0.0, best_us = 0.0;
     for (size_t k = 0; k < cands.size(); ++k) {
@@ -607,6 +607,13 @@ fs_status fs_plan_tune(fs_plan* plan, const void* const* inputs, void* const* ou
           } else {
             part = tickets = nullptr;
           }
+        }
+        // The device needs tens of milliseconds of work to reach its steady clocks, and it has idled
+        // while this candidate was compiled: ~35 ms of copies first (a kernel measured right after an
+        // idle period reads 5-10 % slow, more than most differences between candidates).
+        for (int w = 0; w < 200; ++w) {
+          const int ce = launch_copy_probe(res.flush, (char*)res.flush + kFlushBytes, kFlushBytes, stream);
+          if (ce != 0) FS_FAIL(FS_ERR_HIP, "warm-up launch: %s", hipGetErrorString((hipError_t)ce));
         }
         for (int w = 0; w < 2; ++w) FS_HIP(launch_group(c, fn, tensors, part, tickets, stream));
         // a cold launch is timed on its own; launches that live in the caches anyway are timed in runs of 20
