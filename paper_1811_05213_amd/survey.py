@@ -156,7 +156,7 @@ def main():
         plan = Plan(g)
         gi = plan.group_info(0)
         runs = build_sets(plan, g, ins, "cuda:0", 2 << 30)
-        ms, _ = time_plan(runs, args.steps, 5)
+        ms, _ = time_plan(runs, args.steps, 5, min_warm_ms=50.0)  # steady clocks first
         gbs = min_hbm_bytes(g) / ms / 1e6
         print("%-24s %9d x %-9d %2d  %5d %3d %5d %7d %6d | %9.1f %7.0f %6.1f" % (
             name, r, c, plan.stats()["num_launches"], gi["lanes_per_row"], gi["elems_per_lane"], gi["wg_threads"], gi["grid"],
