@@ -252,8 +252,8 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   }
   else if (total_waves > 1024 || has_transposed) WG = std::max(256, L);
   else WG = std::max(64, L);
-  // Rows whose [1,C] operands outweigh the row's own traffic (LayerNorm with gamma, beta and a bias
-  // over bf16 rows: 12 bytes per column against 4).  Re-reading the operands for every row, or for
+  // Rows with [1,C] operands, above all operands that outweigh the row's own traffic (LayerNorm with
+  // gamma, beta and a bias over bf16 rows: 12 bytes per column against 4).  Re-reading the operands for every row, or for
   // every few rows of a one-trip workgroup, costs L2 bandwidth; keeping them in registers costs
   // occupancy (48 of 84 registers).  When they fit the LDS budget and there is work for more than
   // two rounds of resident workgroups, the workgroups loop instead, 32 wavefronts per CU, and stage
@@ -275,8 +275,13 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
     const int wg = L >= 128 ? std::min(1024, 4 * L) : 1024;
     // (one-wavefront rows: beyond ~8 rounds of resident workgroups the one-trip form catches up and
     // passes: [65536,1024] 48.9 against 49.5 us, [262144,1024] 203 against 210 us)
-    const bool full_slices = L >= 128 || (NVL * V >= 16 && (int64_t)NVL * L == NV && (int64_t)R * L <= 8 * 524288);
-    if (full_slices && rowv_bytes * 2 >= full_bytes * 3 && (int64_t)n_rowv_in * NVL * L * V * 4 + 1024 <= opt.lds_budget && (int64_t)R * L / wg >= 2 * (524288 / wg)) {
+    const bool full_slices = NVL * V >= 16 && (int64_t)NVL * L == NV && (int64_t)R * L <= 8 * 524288;
+    // rows across several wavefronts gain with any [1,C] operand (RMSNorm bf16 [8192,4096]: 24.5 ->
+    // 23.6 us, residual+LayerNorm: 50.5 -> 45.8 us); one-wavefront rows only with heavy ones
+    // (up to ~4 rounds of work: at [32768,2048] the one-trip form is 2-5 % faster again)
+    const bool heavy = rowv_bytes * 2 >= full_bytes * 3;
+    const bool pays = L >= 128 ? heavy || (n_rowv_in > 0 && (int64_t)R * L <= 4 * 524288) : full_slices && heavy;
+    if (pays && (int64_t)n_rowv_in * NVL * L * V * 4 + 1024 <= opt.lds_budget && (int64_t)R * L / wg >= 2 * (524288 / wg)) {
       staged_loop = true;
       WG = wg;
     }
