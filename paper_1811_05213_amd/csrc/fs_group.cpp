@@ -186,6 +186,17 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   // Very narrow rows: a row of at most 32 bytes belongs to one lane (no cross-lane step at all;
   // [4M,3] L2-normalise: 34.8 -> 17.6 us); rows that can only be read element by element (odd
   // widths) get at least two elements per lane.
+  // A row that leaves part of a wavefront's last vector slots empty (768 bf16 columns: 96 vectors
+  // on 64 lanes x 2) is better served by fewer lanes that it fills exactly, several rows per
+  // wavefront (32 lanes x 3: LayerNorm+GeLU bf16 [32768,768] 24.0 -> 20.9 us).
+  // Below a quarter of the slots empty it does not pay (softmax fp32 [32768,640]: 27.7 us on 64 lanes
+  // x 3 vectors with 17 % empty, 29.4 us on 32 x 5).
+  if (rowred && !colred && L > l_min && l_min >= 1) {
+    const auto waste = [&](int lanes) { return (int64_t)((NV + lanes - 1) / lanes) * lanes - NV; };
+    if (waste(L) * 4 >= NV + waste(L))
+      for (int l = L; l >= l_min; l /= 2)
+        if (waste(l) < waste(L)) L = l;
+  }
   if (rowred && !colred && C * max_es <= 32) L = 1;
   else if (rowred && !colred && V == 1 && NV >= 4) L = std::min(L, pow2_ceil(NV) / 2);
   // a transposed root leaves as runs of G = WG/L consecutive elements: at least 16 rows per workgroup
@@ -272,7 +283,7 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
     }
     for (const ExtTensor& e : gp->ext_out)
       if (e.kind == KIND_FULL) full_bytes += dtype_size(e.dtype);
-    const int wg = L >= 128 ? std::min(1024, 4 * L) : 1024;
+    const int wg = L >= 128 ? std::min(1024, 4 * L) : std::max(256, std::min(1024, 16 * L));  // 4 rows, or 16 one-wavefront rows, per trip
     // (one-wavefront rows: beyond ~8 rounds of resident workgroups the one-trip form catches up and
     // passes: [65536,1024] 48.9 against 49.5 us, [262144,1024] 203 against 210 us)
     const bool full_slices = NVL * V >= 16 && (int64_t)NVL * L == NV && (int64_t)R * L <= 8 * 524288;
