@@ -147,7 +147,9 @@ typedef struct {
  * says how many lanes cooperate on one row (a power of two, 1..1024, the analogue
  * of reduce_warps in Section 4.4); wg_threads is the workgroup size (multiple of 64,
  * <= 1024).  max_workgroups = 1 gives the always-valid single-block schedule of
- * Section 4.3.
+ * Section 4.3.  For a group over a handful of very long rows that are split over
+ * workgroups, max_workgroups is the number of row segments in all (lanes_per_row and
+ * wg_threads are fixed at 256 there).
  */
 typedef struct {
   int32_t lanes_per_row;
