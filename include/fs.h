@@ -30,7 +30,9 @@
  *                          compile options and compiler version
  *   FS_PERF_LIBRARY        file of the performance library (see fs_plan_tune)
  *   FS_LOG_PLAN            when set, plan creation reports on stderr every kernel it
- *                          plans again because the compiled code spills registers
+ *                          plans again because the compiled code spills registers or
+ *                          sits just above an occupancy step, and the registers and
+ *                          scratch bytes of every kernel it ends up with
  *   FS_DUMP_FAILED_SOURCE  file that receives the generated source when its
  *                          compilation fails
  */

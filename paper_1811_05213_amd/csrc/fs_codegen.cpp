@@ -476,7 +476,9 @@ struct Emitter {
         os << " case " << k << ": return fs_red_identity<" << g.nodes[folded_across[k]].attr_i << ">();";
       os << " } return 0.0f; }\n};\n";
     }
-    os << "extern \"C\" __global__ void __launch_bounds__(" << s.WG << ") " << kname << "(const " << kname << "_args a) {\n";
+    os << "extern \"C\" __global__ void __launch_bounds__(" << s.WG << ") ";
+    if (s.min_waves > 0) os << "__attribute__((amdgpu_waves_per_eu(" << s.min_waves << "))) ";
+    os << kname << "(const " << kname << "_args a) {\n";
     os << "  constexpr int V = " << s.V << ", NVL = " << s.NVL << ", L = " << s.L << ", NV = " << s.NV << ", E = NVL * V, WG = " << s.WG
        << ", G = WG / L, C = " << C << ", CT = " << s.CT << ";\n";
     os << "  constexpr bool RAGGED = " << (s.ragged ? "true" : "false") << ";\n";
@@ -497,7 +499,9 @@ struct Emitter {
       }
     }
     // CW columns are folded together: the whole row, or one column tile
-    os << "  constexpr int CW = " << (ctile ? "NVL * L * V" : "C") << ", NVF = CW / V, RB = " << s.RB << ";\n";
+    // (RB, the number of workgroups that fold together, only where something is folded: a kernel without column
+    // reductions has the same text, hence the same compiled code, whatever the number of rows)
+    os << "  constexpr int CW = " << (ctile ? "NVL * L * V" : "C") << ", NVF = CW / V, RB = " << (K > 0 || ctile ? s.RB : 1) << ";\n";
     if (ctile) os << "  const int tile = (int)blockIdx.x % CT, rb = (int)blockIdx.x / CT, vbase = tile * (NVL * L);\n";
     else os << "  const int tile = 0, rb = (int)blockIdx.x;\n";
     os << "  (void)tile; (void)rb; (void)CW; (void)NVF; (void)RB;\n";

@@ -321,6 +321,7 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   s.col_tiled = col_tiled;
   s.tiled_transpose = tiled_transpose;
   s.split_rows = split_rows;
+  s.min_waves = opt.min_waves;
   s.few_long_rows = few_long_rows;
   s.S = 1;
   s.CPS = CT;

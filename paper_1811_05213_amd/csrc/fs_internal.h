@@ -98,6 +98,7 @@ struct Schedule {
   // reduction result (split_rows), each row is cut into S segments of CPS chunks, one workgroup per
   // segment, and the segments' partial results are folded across workgroups with the ticket scheme
   // of the column reductions.
+  int min_waves = 0;  // amdgpu_waves_per_eu attribute of the kernel, 0 = none
   bool few_long_rows = false;
   bool split_rows = false;
   int S = 1, CPS = 0;
@@ -148,6 +149,7 @@ struct PlanOptions {
   // per lane (or 48 resident ones plus chunks), 1 = 32 resident ones plus chunks, 0 = chunks only.
   // Plan creation steps down while the compiled kernel spills.
   int wide_level = 2;
+  int min_waves = 0;  // > 0: the kernel asks the compiler for that many wavefronts per SIMD (occupancy feedback at plan creation)
   bool layered = false;  // group with the layered planner of Section 3.2 instead of the default one
 };
 

@@ -113,13 +113,13 @@ fs_status compile_kernel(const std::string& source, const std::string& name, std
   return FS_OK;
 }
 
-// Scratch (register spill) bytes of every kernel of a code object, read from its metadata note:
-// the msgpack integer after each ".private_segment_fixed_size" key, attributed to the kernel whose
-// ".name" key precedes it in the same map (the keys of a kernel's map are sorted).
-std::map<std::string, long> code_object_scratch_bytes(const std::vector<char>& code) {
-  static const char key[] = ".private_segment_fixed_size";
+// One integer field of every kernel of a code object, read from its metadata note: the msgpack
+// integer after each occurrence of `key` (".private_segment_fixed_size": scratch, i.e. register
+// spill, bytes; ".vgpr_count": vector registers), attributed to the kernel whose ".name" key
+// precedes it in the same map (the keys of a kernel's map are sorted).
+std::map<std::string, long> code_object_kernel_field(const std::vector<char>& code, const char* key) {
   static const char name_key[] = ".name";
-  const size_t klen = sizeof(key) - 1, nlen = sizeof(name_key) - 1;
+  const size_t klen = strlen(key), nlen = sizeof(name_key) - 1;
   std::map<std::string, long> out;
   for (size_t i = 0; i + klen + 5 <= code.size(); ++i) {
     if (code[i] != '.' || memcmp(code.data() + i, key, klen) != 0) continue;
@@ -206,7 +206,14 @@ fs_status fs_plan_create(const fs_graph_desc* desc, fs_plan** out_plan) {
   // register pressure -- rows held beyond 32 elements per lane step down towards chunks, otherwise
   // the workgroup is halved (the register file is shared by fewer wavefronts) -- and the unit is
   // compiled again; a few rounds at most.
+  // Occupancy feedback: a 1024-lane workgroup is 4 wavefronts per SIMD, so a CU holds two of them
+  // only at 64 vector registers or fewer.  A kernel that is up to 16 registers above that is compiled
+  // once more with the compiler asked for 8 wavefronts per SIMD, and keeps that form if it then fits
+  // without spilling (softmax over 32768 fp32 columns: 67 -> 56 registers, 105.5 -> 94.5 us; a
+  // masked softmax of the same shape spills when forced and stays as it was).
   std::vector<PlanOptions> group_opt(plan->groups.size(), plan->opt);
+  std::vector<GroupPlan> before_waves(plan->groups.size());  // the plan to return to when forcing the occupancy spills
+  std::vector<char> waves_tried(plan->groups.size(), 0);
   for (int round = 0;; ++round) {
     std::string tu = device_header_source();
     std::set<std::string> seen;
@@ -217,15 +224,46 @@ fs_status fs_plan_create(const fs_graph_desc* desc, fs_plan** out_plan) {
       delete plan;
       return st;
     }
-    if (round == 4) break;
-    const std::map<std::string, long> scratch = code_object_scratch_bytes(plan->code);
+    const std::map<std::string, long> scratch = code_object_kernel_field(plan->code, ".private_segment_fixed_size");
+    const std::map<std::string, long> vgprs = code_object_kernel_field(plan->code, ".vgpr_count");
     bool changed = false;
     for (size_t gi = 0; gi < plan->groups.size(); ++gi) {
       GroupPlan& gp = plan->groups[gi];
       auto it = scratch.find(gp.kernel_name);
+      if (gp.s.min_waves > 0) {  // a forced occupancy must come (nearly) for free: at most 8 spilled registers
+        if (it != scratch.end() && it->second > 32) {
+          if (getenv("FS_LOG_PLAN"))
+            fprintf(stderr, "fs: group %zu kernel %s spills %ld bytes at %d wavefronts per SIMD: back to the plain form\n", gi,
+                    gp.kernel_name.c_str(), it->second, gp.s.min_waves);
+          gp = before_waves[gi];
+          group_opt[gi].min_waves = 0;
+          changed = true;
+        }
+        continue;
+      }
+      if (round >= 4) continue;  // (only returns to the plain form are still taken: the loop ends)
       // (a few spilled registers cost nothing measurable, and whether a borderline kernel gets them varies with what the
       // run-time compiler compiled before in the same process; hundreds of bytes are what ruins a kernel)
-      if (it == scratch.end() || it->second <= 128) continue;
+      if (it == scratch.end() || it->second <= 128) {
+        auto vg = vgprs.find(gp.kernel_name);
+        if (!waves_tried[gi] && gp.s.WG == 1024 && vg != vgprs.end() && vg->second > 64 && vg->second <= 80 && (it == scratch.end() || it->second == 0)) {
+          waves_tried[gi] = 1;
+          PlanOptions o = group_opt[gi];
+          o.min_waves = 8;
+          GroupPlan again;
+          if (analyse_group(g, ordered[gi], plan->group_of, (int)gi, o, &again) == FS_OK && generate_kernel(g, &again, (int)gi) == FS_OK &&
+              again.kernel_name != gp.kernel_name) {
+            if (getenv("FS_LOG_PLAN"))
+              fprintf(stderr, "fs: group %zu kernel %s uses %ld registers with 1024-lane workgroups: trying 8 wavefronts per SIMD\n", gi,
+                      gp.kernel_name.c_str(), vg->second);
+            before_waves[gi] = gp;
+            group_opt[gi] = o;
+            gp = again;
+            changed = true;
+          }
+        }
+        continue;
+      }
       // the next milder plan that actually differs from the current one
       PlanOptions o = group_opt[gi];
       GroupPlan again;
@@ -251,7 +289,17 @@ fs_status fs_plan_create(const fs_graph_desc* desc, fs_plan** out_plan) {
       gp = again;
       changed = true;
     }
-    if (!changed) break;
+    if (!changed) {
+      if (getenv("FS_LOG_PLAN"))
+        for (size_t gi = 0; gi < plan->groups.size(); ++gi) {
+          const GroupPlan& gp = plan->groups[gi];
+          auto vg = vgprs.find(gp.kernel_name);
+          auto sc = scratch.find(gp.kernel_name);
+          fprintf(stderr, "fs: group %zu kernel %s: %ld vector registers, %ld bytes of scratch, workgroup %d, grid %d\n", gi, gp.kernel_name.c_str(),
+                  vg == vgprs.end() ? -1 : vg->second, sc == scratch.end() ? -1 : sc->second, gp.s.WG, gp.s.grid);
+        }
+      break;
+    }
   }
 
   // workspace: [tickets][tensors crossing group boundaries][column-reduction partials]

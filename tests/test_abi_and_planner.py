@@ -377,6 +377,22 @@ def test_spill_feedback_relieves_register_pressure():
     p.destroy()
 
 
+def test_occupancy_feedback_for_1024_lane_workgroups():
+    # two 1024-lane workgroups share a CU only at <= 64 vector registers; a kernel a few registers above that is compiled again
+    # with the compiler asked for 8 wavefronts per SIMD, and keeps that form only if nothing spills
+    p = fs.Plan(softmax_graph(2048, 32768))
+    assert p.group_info(0)["wg_threads"] == 1024 and p.group_info(0)["elems_per_lane"] == 32
+    src = p.group_source(0)
+    if "amdgpu_waves_per_eu(8)" in src:  # taken: the compiled kernel must be spill-free (the plan would have gone back otherwise)
+        assert p.stats()["num_launches"] == 1
+    p.destroy()
+    # kernels that are not 1024 lanes wide, or fit anyway, carry no such request
+    for g in (softmax_graph(4096, 4096), layernorm_gelu_graph(16384, 1024), softmax_graph(4096, 16384)):
+        p = fs.Plan(g)
+        assert "amdgpu_waves_per_eu" not in p.group_source(0)
+        p.destroy()
+
+
 def test_work_span_and_layered_planner():
     # Work/Span: roots have span 0, everything else 1 + the largest span of its users; a layer has no internal dependences
     g = random_dag_graph()

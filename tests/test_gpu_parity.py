@@ -166,7 +166,7 @@ def test_row_reduce_across_wavefronts():
 def test_rows_longer_than_a_workgroup_holds():
     # one workgroup per row walks it in column chunks, once per stage, recomputing what the stage needs (more than 32 rows
     # where the rows are beyond 256 KiB: fewer are cut into kernels that split the rows)
-    for rows, cols in [(35, 100001), (33, 1 << 18), (1100, 40000), (300, 65536), (7, 50001), (34, 131072 + 4 * 77)]:
+    for rows, cols in [(35, 100001), (33, 1 << 18), (1100, 40000), (300, 65536), (7, 50001), (34, 131072 + 4 * 77), (600, 32768)]:
         g = softmax_graph(rows, cols)
         p = fs.Plan(g)
         gi = p.group_info(0)
@@ -174,7 +174,7 @@ def test_rows_longer_than_a_workgroup_holds():
         if cols % 4:  # (odd widths use scalar accesses: whichever form does not spill)
             pass
         elif cols <= 65536:  # up to 64 elements per lane of a 1024-lane workgroup still stay in registers (no spills: checked at plan creation)
-            assert gi["elems_per_lane"] > 32 and gi["elems_per_lane"] * gi["lanes_per_row"] >= cols
+            assert gi["elems_per_lane"] >= 32 and gi["elems_per_lane"] * gi["lanes_per_row"] >= cols
         else:  # longer: walked in chunks, the first 48 elements per lane resident
             assert gi["elems_per_lane"] == 48 and gi["elems_per_lane"] * gi["lanes_per_row"] < cols
         p.destroy()
