@@ -22,7 +22,7 @@ def summarize(path: str, filters=()) -> str:
         args = [f"%{f}%" for f in filters]
     rows = list(c.execute(
         "select name, count(*), avg(duration)/1000.0, min(duration)/1000.0, max(duration)/1000.0, sum(duration)/1000.0, "
-        f"avg(grid_x), avg(workgroup_x), max(static_lds_size), max(scratch_size) from kernels {where} group by name order by 6 desc limit 60", args))
+        f"avg(grid_x), avg(workgroup_x), max(static_lds_size), max(scratch_size) from kernels {where} group by name order by 6 desc limit 400", args))
     out.append("%-56s %6s %9s %9s %9s %12s %9s %5s %6s %7s" % ("kernel", "calls", "avg_us", "min_us", "max_us", "total_us", "grid_thr", "wg", "lds", "scratch"))
     for r in rows:
         out.append("%-56s %6d %9.2f %9.2f %9.2f %12.1f %9d %5d %6d %7d" % (r[0][:56], *r[1:]))
