@@ -317,6 +317,35 @@ def test_ragged_rows_with_staged_vectors_and_bf16():
         both_modes(g, ins, f"layernorm {rows}x{cols}")
 
 
+def test_looping_workgroups_with_operands_staged_once():
+    # row-reduction groups with per-column operands whose workgroups loop and stage the operands in LDS once, before the loop:
+    # row counts that are no multiple of the rows per trip (masked rows in the last trip), one-wavefront rows (16 rows per
+    # trip), rows across 4 wavefronts, exact-fit lane counts (768 bf16 columns: 32 lanes x 3 vectors), a light operand
+    from paper_1811_05213_amd import Plan, survey
+    for rows, cols in ((16391, 1024), (8197, 4096), (32771, 768)):
+        g = layernorm_gelu_graph(rows, cols)
+        p = Plan(g)
+        gi = p.group_info(0)
+        assert gi["grid"] * gi["rows_per_iter"] < rows and "fs_stage_rowvec" in p.group_source(0), (rows, cols, gi)
+        p.destroy()
+        x = RNG.standard_normal((rows, cols)).astype(np.float32)
+        ins = [f32_to_bf16_bits(x)] + [RNG.normal(m, s, (1, cols)).astype(np.float32) for m, s in ((1, .1), (0, .1), (0, .02))]
+        both_modes(g, ins, f"looping layernorm {rows}x{cols}")
+    g = survey.rmsnorm(8195, 2048)
+    p = Plan(g)
+    assert p.group_info(0)["grid"] * p.group_info(0)["rows_per_iter"] < 8195
+    p.destroy()
+    ins = [f32_to_bf16_bits(RNG.standard_normal((8195, 2048)).astype(np.float32)), RNG.normal(1, .1, (1, 2048)).astype(np.float32)]
+    both_modes(g, ins, "looping rmsnorm 8195x2048")
+    # the same schedule forced onto a small problem by hint: more workgroups than row tiles, workgroups without a trip
+    g = layernorm_gelu_graph(50, 1024)
+    x = RNG.standard_normal((50, 1024)).astype(np.float32)
+    ins = [f32_to_bf16_bits(x)] + [RNG.normal(m, s, (1, 1024)).astype(np.float32) for m, s in ((1, .1), (0, .1), (0, .02))]
+    ref = oracle.run(g, ins, THREADS)
+    for hint in ({"wg_threads": 1024, "max_workgroups": 2}, {"wg_threads": 1024, "max_workgroups": 512}, {"wg_threads": 256, "max_workgroups": 3}):
+        check_all(g, run_graph(g, ins, hint=hint), ref, f"looping layernorm 50x1024 {hint}")
+
+
 def test_unrolled_row_loop():
     # looping (column-reduction) kernels with two and three row tiles per trip
     g, ins, name = workload(4, 5000)
