@@ -310,7 +310,8 @@ def test_elementwise20_predicate_bit_exact():
 def test_ragged_rows_with_staged_vectors_and_bf16():
     # LayerNorm chain on C not a multiple of the lane tiling (ragged vector indices), bf16 in/out:
     # exercises the LDS-staged per-column vectors with clamped lanes
-    for rows, cols in ((300, 1000), (64, 520), (1000, 72)):
+    # (768, 384 and 192 bf16 columns: the lane count the row fills exactly, several rows per wavefront with 24 elements per lane)
+    for rows, cols in ((300, 1000), (64, 520), (1000, 72), (5000, 768), (3001, 384), (7000, 192)):
         g = layernorm_gelu_graph(rows, cols)
         x = RNG.standard_normal((rows, cols)).astype(np.float32)
         ins = [f32_to_bf16_bits(x)] + [RNG.normal(m, s, (1, cols)).astype(np.float32) for m, s in ((1, .1), (0, .1), (0, .02))]
