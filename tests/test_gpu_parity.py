@@ -497,6 +497,17 @@ def test_few_very_long_rows_reduced_by_segments():
     g = layernorm_gelu_graph(3, 300000)
     assert Plan(g).stats()["num_launches"] > 1
     both_modes(g, layernorm_gelu_inputs(3, 300000), "few long rows LayerNorm+GeLU")
+    # the layered planner takes the same cut; a caller's own plan (the whole softmax as one group) is honoured and runs as
+    # one kernel that walks each row in chunks
+    g = softmax_graph(4, 300001)
+    x = RNG.standard_normal((4, 300001)).astype(np.float32)
+    ref = oracle.run(g, [x], THREADS)
+    check_all(g, run_graph(g, [x], mode=fs.FS_MODE_LAYERED), ref, "few long rows softmax, layered planner")
+    one = [0 if n.op not in ("input", "const", "bcast_rowvec", "bcast_colvec") else -1 for n in g.nodes]
+    p = Plan(g, group_of_node=one)
+    assert p.stats()["num_launches"] == 1 and p.group_info(0)["grid"] == 4
+    p.destroy()
+    check_all(g, run_graph(g, [x], group_of_node=one), ref, "few long rows softmax, caller's single group")
 
 
 def test_wide_transposes_in_2d_tiles():
