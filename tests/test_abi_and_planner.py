@@ -97,6 +97,26 @@ def test_validation_errors():
     assert _status(g) == "FS_ERR_BAD_GRAPH"
 
 
+def test_degenerate_graphs_are_refused():
+    # empty tensors, no outputs, an input as an output: distinct statuses, nothing planned
+    for r, c in ((0, 8), (8, 0), (-1, 4)):
+        g = Graph()
+        x = g.input(4, 8)
+        y = g.unary("neg", x)
+        g.set_outputs([y])
+        for n in (x, y):
+            g.nodes[n].rows, g.nodes[n].cols = r, c
+        assert _status(g) == "FS_ERR_SHAPE"
+    g = Graph()
+    g.input(4, 8)
+    g.set_outputs([])
+    assert _status(g) == "FS_ERR_INVALID_ARG"
+    g = Graph()
+    x = g.input(4, 8)
+    g.set_outputs([x])
+    assert _status(g) == "FS_ERR_BAD_GRAPH"
+
+
 def test_invalid_arguments(built_lib):
     desc = binding.fs_graph_desc()
     h = ctypes.c_void_p()
