@@ -372,6 +372,35 @@ def test_run_to_run_bit_identical():
         plan.destroy()
 
 
+def test_workspace_reuse_with_new_inputs():
+    # the same plan and the same workspace (partials, tickets, tensors between groups) run on changing inputs: nothing of an
+    # earlier run may be picked up by a later one (partials of the grid-wide folds are read with device-coherent loads, tickets
+    # return to zero).  Column reductions, rows split over workgroups, the 200-node DAG, the few-long-rows softmax (3 kernels).
+    cases = [workload(4, 70001)[:2], workload(6, 3000)[:2], workload(5)[:2], (softmax_graph(4, 300001), None)]
+    g = Graph()
+    x = g.input(3, 2100000)
+    g.set_outputs([g.unary("sqrt", g.reduce_row("sum", g.binary("mul", x, x))), g.reduce_row("max", x)])
+    cases.append((g, None))
+    for g, ins in cases:
+        plan = fs.Plan(g)
+        r = DeviceRun(plan)
+        for trial in range(4):
+            rng = np.random.default_rng(9000 + trial)
+            cur = []
+            for k, i in enumerate(g.input_ids()):
+                n = g.nodes[i]
+                if ins is not None and trial == 0:
+                    cur.append(ins[k])
+                    continue
+                a = rng.standard_normal((n.rows, n.cols)).astype(np.float32)  # (fresh draws of the distribution the graphs are built for)
+                cur.append(f32_to_bf16_bits(a) if n.dtype == "bf16" else a)
+            r.set_inputs(cur)
+            r.launch()
+            r.launch()
+            check_all(g, r.results(), oracle.run(g, cur, THREADS), f"workspace reuse, trial {trial}")
+        plan.destroy()
+
+
 @pytest.mark.parametrize("cfg,rows", [(1, 300), (2, 300), (4, 3000), (3, 200)])
 def test_schedule_invariance(cfg, rows):
     """The one-block schedule (Section 4.3) and other legal schedules give the tuned schedule's result."""
