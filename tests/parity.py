@@ -1,56 +1,172 @@
 """Comparison rule shared by the GPU parity tests.
 
-fp32 outputs: |gpu - ref| <= rtol*|ref| + rtol*rms(ref) with rtol = 1e-5; bf16 outputs the same
-with rtol = 1e-2; u8 outputs bit-exact.  The rms term keeps the relative test meaningful at
-zeros and under cancellation (differences of nearly equal values, GeLU outputs near -0).
-An fp32 output computed FROM a bf16-rounded intermediate is held to the bf16 tolerance: the two
-sides may round that intermediate to neighbouring bf16 values (fp32 -> bf16 on the GPU, fp64 -> bf16
-in the oracle, values one ulp apart across a rounding boundary), and everything downstream inherits
-that relative 2^-8.  bf16 INPUTS are exact on both sides and do not count.
+Reference of record: the CPU oracle with every node rounded to its declared dtype ("A").
+
+  u8 outputs    bit-exact.
+  fp32 outputs  |gpu - A| <= rtol*|A| + rtol*rms(A), rtol = 1e-5.
+  bf16 outputs  the same with rtol = 1e-2 (one bf16 ulp is 2^-8..2^-7 relative).
+
+The rms term keeps the relative test meaningful at zeros and under cancellation below the
+tensor's own scale.  Two refinements replace any blanket slack:
+
+1. Quantisation decisions are shared (teacher forcing).  A COMPUTED bf16 node that other nodes
+   consume is a quantiser: two correct implementations may round a value that sits on (or within
+   an fp32 ulp of) the midpoint of two bf16 neighbours to either neighbour, and whatever is
+   downstream inherits that 2^-8 relative step, amplified by cancellation, logarithms near 1, ...
+   (three seeds of the random-graph sweep failed exactly so: an fp32 sigmoid/tanh result equal to
+   a bf16 midpoint, rounded to even by the oracle, one fp32 ulp lower and hence rounded down on
+   the device, followed by a subtraction of nearly equal values).  Such nodes must therefore be
+   plan outputs of the graph under test (`expose_bf16_nodes`); the device's own bf16 values are
+   checked against the oracle at the bf16 tolerance, and are then fed to the oracle IN PLACE of
+   its own roundings, so that everything downstream is compared at its full tolerance with every
+   rounding decision upstream being the device's.  bf16 INPUTS are exact on both sides.
+
+2. Conditioning companion ("B"): the same oracle with nodes kept in fp64 and rounded at plan
+   outputs only.  Where A and B differ by more than the tolerance, the element is ill-conditioned
+   with respect to fp32 rounding itself, and no fp32 implementation can be held to the tolerance
+   there.  Those elements are counted, must stay a small fraction of the tensor, and are held to
+   |gpu - A| <= 16*|A - B| + tol instead.
 """
+from __future__ import annotations
+
+from typing import List, Optional, Sequence
+
 import numpy as np
 
-from workloads import bf16_bits_to_f32
+import oracle
+from workloads import Graph, bf16_bits_to_f32
+from workloads.graph import Node
 
 RTOL = {"f32": 1e-5, "bf16": 1e-2}
+MAX_ILL_FRACTION = 2e-3
+ILL_SLACK = 16.0
+THREADS = 16
 
 
-def check_output(gpu: np.ndarray, ref: np.ndarray, dtype: str, what: str = "", rtol_scale: float = 1.0):
+def _as_f64(a: np.ndarray, dtype: str) -> np.ndarray:
+    return (bf16_bits_to_f32(a) if dtype == "bf16" else a).astype(np.float64)
+
+
+def check_output(gpu: np.ndarray, ref: np.ndarray, dtype: str, what: str = "", ref_b: Optional[np.ndarray] = None,
+                 max_ill_fraction: float = MAX_ILL_FRACTION):
+    """One output tensor against reference A (and, when given, the conditioning companion B)."""
     assert gpu.shape == ref.shape, (what, gpu.shape, ref.shape)
     if dtype == "u8":
         bad = int((gpu != ref).sum())
         assert bad == 0, f"{what}: {bad} predicate bytes differ"
-        return {"max_err_over_tol": 0.0}
-    if dtype == "bf16":
-        gpu, ref = bf16_bits_to_f32(gpu), bf16_bits_to_f32(ref)
-    g = gpu.astype(np.float64)
-    r = ref.astype(np.float64)
+        return {"max_err_over_tol": 0.0, "ill_conditioned": 0}
+    g, r = _as_f64(gpu, dtype), _as_f64(ref, dtype)
     assert np.isfinite(g).all(), f"{what}: non-finite GPU values"
-    rtol = RTOL[dtype] * rtol_scale
+    rtol = RTOL[dtype]
     s = float(np.sqrt(np.mean(r * r)))
     tol = rtol * np.abs(r) + rtol * s + 1e-37
     err = np.abs(g - r)
+    n_ill = 0
+    if ref_b is not None:
+        gap = np.abs(_as_f64(ref_b, dtype) - r)
+        ill = gap > tol
+        n_ill = int(ill.sum())
+        if n_ill:
+            assert n_ill <= max(1.0, max_ill_fraction * ill.size), \
+                f"{what}: {n_ill} of {ill.size} elements are ill-conditioned (oracle A and B differ by more than the tolerance)"
+            tol = np.where(ill, ILL_SLACK * gap + tol, tol)
     ratio = float((err / tol).max())
     if ratio > 1.0:
         i = np.unravel_index(np.argmax(err / tol), err.shape)
         raise AssertionError(f"{what}: |gpu-ref|/tol = {ratio:.3g} at {i}: gpu {g[i]!r} ref {r[i]!r} (rms {s:.3g})")
     nrm = float(np.linalg.norm(g - r) / max(np.linalg.norm(r), 1e-300))
-    return {"max_err_over_tol": ratio, "normwise": nrm}
+    return {"max_err_over_tol": ratio, "normwise": nrm, "ill_conditioned": n_ill}
 
 
-def through_bf16(graph):
-    """For every node: does its value depend on a COMPUTED bf16 node?"""
-    dep = [False] * len(graph.nodes)
+# ------------------------------------------------------------------------------------------------
+# quantiser nodes
+# ------------------------------------------------------------------------------------------------
+def quantiser_nodes(graph: Graph) -> List[int]:
+    """Computed bf16 nodes that some other node consumes (looking through nothing: a broadcast counts)."""
+    used = set()
+    for n in graph.nodes:
+        used.update(n.ins)
+    return [i for i, n in enumerate(graph.nodes) if n.dtype == "bf16" and n.op not in ("input", "const") and i in used]
+
+
+def expose_bf16_nodes(graph: Graph) -> Graph:
+    """The same DAG with every quantiser node added to the plan outputs (after the original ones)."""
+    g = Graph(list(graph.nodes), list(graph.outputs))
+    g.set_outputs(list(graph.outputs) + [q for q in quantiser_nodes(graph) if q not in graph.outputs])
+    return g
+
+
+def forced_graph(graph: Graph, forced: Sequence[int]):
+    """The DAG in which every consumer of a node in `forced` reads a fresh bf16 INPUT instead.
+
+    Returns (g2, computed, forced_input): computed[i] is the id in g2 of node i as the oracle
+    computes it (from forced values upstream), forced_input[q] the id of the input standing in for q.
+    """
+    forced = set(forced)
+    g2 = Graph()
+    view, computed, forced_input = {}, {}, {}
     for i, n in enumerate(graph.nodes):
-        dep[i] = (n.dtype == "bf16" and n.op != "input") or any(dep[o] for o in n.ins)
-    return dep
+        c = g2._add(Node(n.op, n.dtype, n.rows, n.cols, tuple(view[o] for o in n.ins), n.attr, n.value, n.name))
+        computed[i] = view[i] = c
+        if i in forced:
+            view[i] = forced_input[i] = g2.input(n.rows, n.cols, "bf16", name=f"forced_{i}")
+    g2.set_outputs([computed[o] for o in graph.outputs])
+    return g2, computed, forced_input
 
 
-def check_all(graph, gpu_outs, ref_outs, what="", rtol_scale: float = 1.0):
+class Reference:
+    """Oracle results for one graph on one set of inputs: A, B, and per device run the forced forms."""
+
+    def __init__(self, graph: Graph, inputs: Sequence[np.ndarray], threads: int = THREADS, with_b: bool = True):
+        self.graph, self.inputs, self.threads, self.with_b = graph, list(inputs), threads, with_b
+        self.quant = quantiser_nodes(graph)
+        missing = [q for q in self.quant if q not in graph.outputs]
+        assert not missing, (f"computed bf16 nodes {missing} are consumed inside the graph but are not plan outputs: "
+                             "run the graph through expose_bf16_nodes() so their roundings can be shared")
+        self._a = self._b = None
+
+    @property
+    def a(self) -> List[np.ndarray]:
+        if self._a is None:
+            self._a = oracle.run(self.graph, self.inputs, self.threads)
+        return self._a
+
+    @property
+    def b(self) -> Optional[List[np.ndarray]]:
+        if self._b is None and self.with_b:
+            self._b = oracle.run(self.graph, self.inputs, self.threads, round_nodes=False)
+        return self._b
+
+    def __getitem__(self, k):
+        return self.a[k]
+
+    def __len__(self):
+        return len(self.graph.outputs)
+
+    def for_device(self, gpu_outs: Sequence[np.ndarray]):
+        """(A, B) to compare `gpu_outs` with: the plain ones, or the forced ones when the graph has quantisers."""
+        if not self.quant:
+            return self.a, self.b
+        g2, _, forced_input = forced_graph(self.graph, self.quant)
+        by_new_id = {forced_input[q]: gpu_outs[self.graph.outputs.index(q)] for q in self.quant}
+        originals = iter(self.inputs)
+        ins2 = [by_new_id[i] if i in by_new_id else next(originals) for i in g2.input_ids()]
+        a = oracle.run(g2, ins2, self.threads)
+        b = oracle.run(g2, ins2, self.threads, round_nodes=False) if self.with_b else None
+        return a, b
+
+
+def check_all(graph: Graph, gpu_outs, ref, what: str = "", max_ill_fraction: float = MAX_ILL_FRACTION):
+    """Every plan output of one device run against the oracle.  `ref` is a Reference (or a plain list of
+    reference-A outputs for graphs without quantiser nodes: then there is no conditioning companion)."""
+    if not isinstance(ref, Reference):
+        assert not quantiser_nodes(graph), "a graph with consumed computed bf16 nodes needs a Reference"
+        a, b = list(ref), None
+    else:
+        a, b = ref.for_device(gpu_outs)
     stats = []
-    dep = through_bf16(graph)
     for k, o in enumerate(graph.outputs):
         n = graph.nodes[o]
-        scale = rtol_scale * (RTOL["bf16"] / RTOL["f32"] if n.dtype == "f32" and dep[o] else 1.0)
-        stats.append(check_output(gpu_outs[k], ref_outs[k], n.dtype, f"{what} output {k} (node {o} {n.op} {n.name})", scale))
+        stats.append(check_output(gpu_outs[k], a[k], n.dtype, f"{what} output {k} (node {o} {n.op} {n.name})",
+                                  None if b is None else b[k], max_ill_fraction))
     return stats
