@@ -6,6 +6,7 @@ numpy.float32 bit equality for the correctly rounded ops, and torch CPU fp64 lib
 routines (softmax, layer_norm, gelu).  A planted mistake (dropped term, swapped operand,
 wrong reduce axis, wrong rounding) fails at least one test below.
 """
+import decimal
 import math
 import os
 import sys
@@ -95,6 +96,33 @@ def test_unary_brute_force(op):
             assert got[i, j] == pytest.approx(want, rel=2e-7, abs=1e-38), (op, x[i, j])
 
 
+def _dec_tanh(d):
+    e2 = (2 * d).exp()
+    return (e2 - 1) / (e2 + 1)
+
+
+DEC_UNARY = {   # 40-digit decimal arithmetic: no code in common with the C math library the oracle calls
+    "exp": lambda d: d.exp(), "log": lambda d: d.ln(), "tanh": _dec_tanh, "sigmoid": lambda d: 1 / (1 + (-d).exp()),
+    "gelu_tanh": lambda d: d / 2 * (1 + _dec_tanh((decimal.Decimal(2) / decimal.Decimal("3.14159265358979323846264338327950288")).sqrt()
+                                                  * (d + decimal.Decimal("0.044715") * d ** 3))),
+}
+
+
+@pytest.mark.parametrize("op", sorted(DEC_UNARY))
+def test_transcendentals_vs_decimal_arithmetic(op):
+    # test_unary_brute_force goes through the same libm as the oracle for exp / log / tanh; this one does not
+    decimal.getcontext().prec = 40
+    x = np.concatenate([RNG.uniform(-8, 8, 24), [0.0, 1e-6, -1e-6, 0.25, -0.25, 20.0, -20.0]]).astype(np.float32).reshape(1, -1)
+    if op == "log":
+        x = np.abs(x) + np.float32(1e-3)
+    if op == "gelu_tanh":   # below -5 the definition 0.5 z (1 + tanh u) cancels even in fp64: the oracle, which IS the definition, loses digits
+        x = np.maximum(x, np.float32(-5.0))
+    got = run1(unary_graph(op, *x.shape), [x])[0]
+    for j in range(x.shape[1]):
+        want = float(DEC_UNARY[op](decimal.Decimal(float(x[0, j]))))
+        assert got[0, j] == pytest.approx(want, rel=1.2e-7, abs=1e-38), (op, x[0, j])   # half an fp32 ulp + the cast
+
+
 def test_unary_identities():
     x = RNG.uniform(-5, 5, (4, 8)).astype(np.float32)
     t = run1(unary_graph("tanh", 4, 8), [x])[0]
@@ -147,6 +175,35 @@ def test_cmp_select_truth_table():
         pm, sel = run1(g, [a, b])
         assert pm.dtype == np.uint8 and pm[0].tolist() == w, kind
         np.testing.assert_array_equal(sel.view(np.uint32), np.where(np.array(w, bool), a, b).view(np.uint32))
+
+
+def test_u8_plan_input_through_select_truth_table():
+    # a predicate tensor that enters the plan from outside: any non-zero byte selects the first branch (bits of the
+    # chosen operand, signed zeros and all); hand-written expectations, no library routine in between
+    p = np.array([[0, 1, 2, 255, 0, 1], [1, 0, 0, 128, 7, 0]], np.uint8)
+    a = np.array([[1.5, -2.0, 3.25, -0.0, 0.0, 1e-30], [7.0, 8.0, 9.0, 10.0, -11.0, 12.0]], np.float32)
+    b = np.array([[-1.5, 2.0, -3.25, 0.0, -0.0, -1e30], [-7.0, -8.0, -9.0, -10.0, 11.0, -12.0]], np.float32)
+    want = np.array([[-1.5, -2.0, 3.25, -0.0, -0.0, 1e-30], [7.0, -8.0, -9.0, 10.0, -11.0, -12.0]], np.float32)
+    g = Graph()
+    ip, ia, ib = g.input(2, 6, "u8"), g.input(2, 6), g.input(2, 6)
+    s = g.select(ip, ia, ib)
+    g.set_outputs([s, g.select(ip, ib, ia)])
+    got, swapped = run1(g, [p, a, b])
+    np.testing.assert_array_equal(got.view(np.uint32), want.view(np.uint32))
+    np.testing.assert_array_equal(swapped.view(np.uint32), np.where(want.view(np.uint32) == a.view(np.uint32), b, a).view(np.uint32))
+    # the predicate bytes themselves pass through a transpose unchanged in meaning (normalised to 0/1)
+    g2 = Graph()
+    ip2 = g2.input(2, 6, "u8")
+    g2.set_outputs([g2.transpose(ip2)])
+    np.testing.assert_array_equal(run1(g2, [p])[0], (p.T != 0).astype(np.uint8))
+    # bf16 branches: the chosen operand's bf16 bits
+    g3 = Graph()
+    jp, ja, jb = g3.input(1, 4, "u8"), g3.input(1, 4, "bf16"), g3.input(1, 4, "bf16")
+    g3.set_outputs([g3.select(jp, ja, jb)])
+    abits = np.array([[0x3F80, 0xBF80, 0x0000, 0x8000]], np.uint16)
+    bbits = np.array([[0x4000, 0xC000, 0x8000, 0x0000]], np.uint16)
+    np.testing.assert_array_equal(run1(g3, [np.array([[1, 0, 0, 9]], np.uint8), abits, bbits])[0],
+                                  np.array([[0x3F80, 0xC000, 0x8000, 0x8000]], np.uint16))
 
 
 def test_convert_and_bf16_nodes():
