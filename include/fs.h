@@ -46,7 +46,7 @@
 extern "C" {
 #endif
 
-#define FS_ABI_VERSION 1u
+#define FS_ABI_VERSION 2u
 
 typedef struct fs_plan fs_plan; /* opaque */
 
@@ -171,7 +171,8 @@ typedef struct {
                                     node (ignored for INPUT/CONST/BCAST_* nodes, which are inlined into
                                     each consumer): the caller's fusion plan.  Ignored in FS_MODE_UNFUSED. */
   uint32_t mode;                 /* FS_MODE_* */
-  int32_t lds_budget_bytes;      /* per-workgroup LDS limit for one group; 0 => 65536 (of 160 KB per CU) */
+  int32_t lds_budget_bytes;      /* per-workgroup LDS limit for one group; 0 => 65536 (of 160 KB per CU);
+                                    at most what fs_device_limits reports for one workgroup */
   const fs_sched_hint* hint;     /* host; may be NULL */
 } fs_graph_desc;
 
@@ -205,38 +206,94 @@ typedef struct {
  */
 fs_status fs_plan_create(const fs_graph_desc* desc, fs_plan** out_plan);
 
-/* Frees the plan and unloads its code objects.  NULL is FS_OK. */
+/*
+ * fs_plan_destroy: frees the plan and unloads its code objects from every device it was loaded
+ * on (the end of the life of a fused computation's compiled form, Section 5.2).  NULL is FS_OK.
+ * No launch of the plan may still be in flight.
+ */
 fs_status fs_plan_destroy(fs_plan* plan);
 
-/* Bytes of device workspace fs_plan_run needs: tensors that cross group boundaries,
- * column-reduction partials and ticket counters.  May be 0. */
+/*
+ * fs_plan_workspace_bytes: bytes of device workspace fs_plan_run needs.  The workspace is the
+ * off-chip side of the plan's memory planning (Section 5.1 plans the on-chip side per kernel): tensors
+ * that cross group boundaries (what fusion could not keep on chip), the per-workgroup partials of
+ * two-stage column reductions and their ticket counters.  May be 0.
+ */
 fs_status fs_plan_workspace_bytes(const fs_plan* plan, size_t* bytes);
 
 /*
- * fs_plan_run: enqueue the plan's launches on `hip_stream` (a hipStream_t; NULL = the
- * null stream) of the current device.  Asynchronous: no allocation, no
- * synchronisation, no host<->device copy.
- *   inputs   host array of device pointers, one per FS_INPUT node in id order
- *   outputs  host array of device pointers, one per entry of desc.outputs, same order
- *   workspace / workspace_bytes  device buffer of >= fs_plan_workspace_bytes bytes,
- *            256-byte aligned; may be NULL when 0 bytes are needed.  The ticket
- *            counters inside it must be zero before the FIRST run on that buffer
- *            (fs_plan_workspace_init does it); every run leaves them zero again.
- * Inputs must not alias outputs or the workspace.  The first run on a device loads
- * the plan's code objects onto it.
+ * fs_plan_load: load the plan's code objects onto the CURRENT device now (hipModuleLoadData; it
+ * allocates device memory for the code and may synchronise).  fs_plan_run does this by itself on
+ * its first call on a device; a caller that wants the first fs_plan_run to be free of allocation -
+ * stream capture, a serving loop - calls fs_plan_load (or makes one warm fs_plan_run) beforehand.
+ * Idempotent per device.  FS_ERR_HIP without a usable device.
+ */
+fs_status fs_plan_load(fs_plan* plan);
+
+/*
+ * fs_plan_run: execute the fusion plan - ONE kernel launch per fused computation (Section 1: the
+ * ops of a fused computation are composed inside a single kernel, by thread composition in
+ * registers and by block composition through on-chip memory; Section 2.2: the stitched kernel) -
+ * enqueued in dependence order on `hip_stream` (a hipStream_t; NULL = the null stream) of the
+ * current device.  Asynchronous.  Once the plan is loaded on the device (fs_plan_load, or an
+ * earlier fs_plan_run) it makes no allocation, no synchronisation and no host<->device copy.
+ *   inputs   host array of device pointers, one per FS_INPUT node in id order; caller-owned,
+ *            16-byte aligned, dense row-major; read only
+ *   outputs  host array of device pointers, one per entry of desc.outputs, same order; caller-
+ *            owned, 16-byte aligned; every element is overwritten
+ *   workspace / workspace_bytes  caller-owned device buffer of >= fs_plan_workspace_bytes bytes,
+ *            256-byte aligned; may be NULL when 0 bytes are needed.  The ticket counters inside
+ *            it must be zero before the FIRST run on that buffer (fs_plan_workspace_init does
+ *            it); every run leaves them zero again.  A run that is killed half-way may leave
+ *            them non-zero: initialise again (fs_plan_workspace_check tells).
+ * Errors: FS_ERR_INVALID_ARG for a NULL or misaligned pointer and when an output's byte range
+ * overlaps an input's, another output's or the workspace's, or an input's overlaps the
+ * workspace's (inputs may alias each other: they are only read); FS_ERR_WORKSPACE for a NULL,
+ * misaligned or undersized workspace; FS_ERR_HIP when loading or a launch fails.  Nothing has
+ * been enqueued when the status is FS_ERR_INVALID_ARG or FS_ERR_WORKSPACE.
  */
 fs_status fs_plan_run(fs_plan* plan, const void* const* inputs, void* const* outputs,
                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
-/* Enqueue a fill kernel on `hip_stream` that zeroes the ticket counters of a fresh workspace. */
+/* Enqueue a fill kernel on `hip_stream` that zeroes the ticket counters of a fresh workspace
+ * (a kernel, not a memset: it may be recorded into a HIP graph). */
 fs_status fs_plan_workspace_init(fs_plan* plan, void* workspace, size_t workspace_bytes, void* hip_stream);
 
-/* Plan-level figures for the metric: groups (= launches per run in stitched mode),
- * launches per run, minimal HBM bytes of the whole plan (plan inputs once + plan
- * outputs once) and the bytes this plan's launches move (sum over groups of
- * external inputs + outputs).  Any out pointer may be NULL. */
+/*
+ * fs_plan_workspace_check: a debugging aid for the one precondition fs_plan_run cannot see from
+ * the host.  SYNCHRONISES `hip_stream`, copies the ticket counters back and returns
+ * FS_ERR_WORKSPACE when any of them is non-zero (a workspace that was never initialised, was
+ * recycled from other use, or belongs to a run that was killed inside a fold: with such tickets
+ * the last-arriver test of the grid-wide fold never fires and column-reduction outputs are not
+ * written).  FS_OK for a plan without tickets.
+ */
+fs_status fs_plan_workspace_check(fs_plan* plan, const void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * fs_plan_stats: plan-level figures for the metric.  num_groups = fused computations;
+ * num_launches = kernel launches per run (equal to num_groups: one launch per group).  Their
+ * ratio between a stitched and an unfused plan of the same DAG is the paper's fusion ratio
+ * (Section 6.3: kernels after fusion / kernels of the baseline).  min_hbm_bytes = every plan
+ * input read once + every plan output written once (the memory footprint fusion aims at,
+ * Section 4.1); unfused_hbm_bytes = what one launch per compute node moves for this DAG, every
+ * intermediate written and read back, whatever mode this plan was created in (broadcasts and
+ * constants are never materialised, Section 4.3).  Any out pointer may be NULL.
+ */
 fs_status fs_plan_stats(const fs_plan* plan, int32_t* num_groups, int32_t* num_launches,
-                        uint64_t* min_hbm_bytes, uint64_t* launched_hbm_bytes);
+                        uint64_t* min_hbm_bytes, uint64_t* unfused_hbm_bytes);
+
+/* Bytes THIS plan's launches move: the sum over its groups of external inputs + outputs (equals
+ * min_hbm_bytes for a single-group plan, unfused_hbm_bytes for an unfused one). */
+fs_status fs_plan_launched_hbm_bytes(const fs_plan* plan, uint64_t* bytes);
+
+/*
+ * The device figures the planner works with: compute units, LDS bytes one workgroup may use,
+ * lanes resident on the whole device, last-level cache bytes.  Read from the current device once
+ * per process (hipDeviceGetAttribute); without a device (planning ahead of time on a build
+ * machine) the published MI355X figures stand in and *from_device is 0.  Any out pointer may be NULL.
+ */
+fs_status fs_device_limits(int32_t* compute_units, int32_t* lds_bytes_per_workgroup, int32_t* resident_lanes,
+                           int64_t* l2_bytes, int32_t* from_device);
 
 fs_status fs_plan_group_info(const fs_plan* plan, int32_t group, fs_group_info* out_info);
 

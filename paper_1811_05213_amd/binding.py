@@ -13,7 +13,7 @@ from typing import List, Optional, Sequence
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libfs.so")
 
-FS_ABI_VERSION = 1
+FS_ABI_VERSION = 2
 FS_MODE_STITCHED = 0
 FS_MODE_UNFUSED = 1
 FS_MODE_NO_PERFLIB = 2
@@ -103,10 +103,15 @@ def lib() -> ctypes.CDLL:
         L.fs_copy_probe.argtypes = [vp, vp, ctypes.c_size_t, vp]
         L.fs_plan_tune.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), vp, ctypes.c_size_t, vp, ctypes.c_int32,
                                    ctypes.POINTER(fs_tune_report)]
+        L.fs_plan_load.argtypes = [vp]
+        L.fs_plan_workspace_check.argtypes = [vp, vp, ctypes.c_size_t, vp]
+        L.fs_plan_launched_hbm_bytes.argtypes = [vp, u64p]
+        L.fs_device_limits.argtypes = [i32p, i32p, i32p, ctypes.POINTER(ctypes.c_int64), i32p]
         L.fs_last_error.restype = ctypes.c_char_p
         for name in ("fs_plan_create", "fs_plan_destroy", "fs_plan_workspace_bytes", "fs_plan_run",
                      "fs_plan_workspace_init", "fs_plan_stats", "fs_plan_group_info", "fs_plan_node_groups",
-                     "fs_plan_group_source", "fs_plan_group_kernel_name", "fs_copy_probe", "fs_plan_tune", "fs_plan_group_perf_key", "fs_plan_node_spans"):
+                     "fs_plan_group_source", "fs_plan_group_kernel_name", "fs_copy_probe", "fs_plan_tune", "fs_plan_group_perf_key", "fs_plan_node_spans",
+                     "fs_plan_load", "fs_plan_workspace_check", "fs_plan_launched_hbm_bytes", "fs_device_limits"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -181,9 +186,17 @@ class Plan:
 
     def stats(self) -> dict:
         g, l = ctypes.c_int32(), ctypes.c_int32()
-        a, b = ctypes.c_uint64(), ctypes.c_uint64()
+        a, b, c = ctypes.c_uint64(), ctypes.c_uint64(), ctypes.c_uint64()
         _check(lib().fs_plan_stats(self._h, ctypes.byref(g), ctypes.byref(l), ctypes.byref(a), ctypes.byref(b)))
-        return {"num_groups": g.value, "num_launches": l.value, "min_hbm_bytes": a.value, "launched_hbm_bytes": b.value}
+        _check(lib().fs_plan_launched_hbm_bytes(self._h, ctypes.byref(c)))
+        return {"num_groups": g.value, "num_launches": l.value, "min_hbm_bytes": a.value, "unfused_hbm_bytes": b.value,
+                "launched_hbm_bytes": c.value}
+
+    def load(self) -> None:
+        _check(lib().fs_plan_load(self._h))
+
+    def workspace_check(self, workspace_ptr: int, workspace_bytes: int, stream: int = 0) -> None:
+        _check(lib().fs_plan_workspace_check(self._h, workspace_ptr, workspace_bytes, stream))
 
     def group_info(self, group: int) -> dict:
         info = fs_group_info()
@@ -244,6 +257,14 @@ class Plan:
         status = self._run(self._h, ins, outs, workspace_ptr, workspace_bytes, stream)
         if status != 0:
             _check(status)
+
+
+def device_limits() -> dict:
+    cu, lds, lanes, frm = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32()
+    l2 = ctypes.c_int64()
+    _check(lib().fs_device_limits(ctypes.byref(cu), ctypes.byref(lds), ctypes.byref(lanes), ctypes.byref(l2), ctypes.byref(frm)))
+    return {"compute_units": cu.value, "lds_bytes_per_workgroup": lds.value, "resident_lanes": lanes.value, "l2_bytes": l2.value,
+            "from_device": bool(frm.value)}
 
 
 def copy_probe(src_ptr: int, dst_ptr: int, nbytes: int, stream: int = 0) -> None:

@@ -44,8 +44,9 @@ fs_status build_graph(const fs_graph_desc* desc, Graph* g) {
   if (desc->num_nodes <= 0 || !desc->nodes) FS_FAIL(FS_ERR_INVALID_ARG, "no nodes");
   if (desc->num_outputs <= 0 || !desc->outputs) FS_FAIL(FS_ERR_INVALID_ARG, "no outputs");
   if ((desc->mode & ~(uint32_t)(FS_MODE_UNFUSED | FS_MODE_NO_PERFLIB | FS_MODE_LAYERED)) != 0) FS_FAIL(FS_ERR_INVALID_ARG, "unknown mode %u", desc->mode);
-  if (desc->lds_budget_bytes < 0 || desc->lds_budget_bytes > 65536)
-    FS_FAIL(FS_ERR_INVALID_ARG, "lds_budget_bytes %d outside [0, 65536]", desc->lds_budget_bytes);
+  if (desc->lds_budget_bytes < 0 || desc->lds_budget_bytes > device_limits().lds_per_workgroup)
+    FS_FAIL(FS_ERR_INVALID_ARG, "lds_budget_bytes %d outside [0, %d] (the most one workgroup may use on this device)", desc->lds_budget_bytes,
+            device_limits().lds_per_workgroup);
 
   const int N = desc->num_nodes;
   g->nodes.assign(desc->nodes, desc->nodes + N);

@@ -106,6 +106,9 @@ void add_ext_in(GroupPlan& gp, int node, Kind k, int dtype) {
 static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPlan* gp) {
   Schedule& s = gp->s;
   const int R = gp->R, C = gp->C;
+  // the machine: compute units and resident lanes as the device reports them (256 and 524288 on MI355X)
+  const int CUS = device_limits().cus;
+  const int64_t RES = device_limits().resident_lanes;
   int max_es = 0;
   for (const ExtTensor& e : gp->ext_in)
     if (e.kind == KIND_FULL) max_es = std::max(max_es, dtype_size(e.dtype));
@@ -218,7 +221,7 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   // small problems: more lanes per row until the device has ~8 wavefronts per CU
   // (a row that will be cut into column tiles anyway is not a small problem)
   const bool col_tiles_anyway = tileable && (int64_t)NV * V > (int64_t)L * ecap;
-  while ((int64_t)R * L / 64 < 2048 && L < l_max && !(has_transposed && !rowred) && !chunked && !col_tiled && !col_tiles_anyway) L *= 2;
+  while ((int64_t)R * L / 64 < 8 * CUS && L < l_max && !(has_transposed && !rowred) && !chunked && !col_tiled && !col_tiles_anyway) L *= 2;
   if (split_rows) L = 256;
   if (opt.has_hint && opt.hint.lanes_per_row > 0 && !tiled_transpose && !split_rows) {
     const int h = opt.hint.lanes_per_row;
@@ -255,13 +258,13 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
     // and the in-workgroup fold area (one row of C floats per wavefront or row-group) fits the budget
     WG = std::max(64, L);
     for (int w = 512; w >= 128; w /= 2)
-      if (w >= L && (int64_t)R * L / w >= 256) {
+      if (w >= L && (int64_t)R * L / w >= CUS) {
         WG = w;
         break;
       }
     if (rowred && L >= 256) WG = std::max(WG, std::min(1024, 4 * L));  // rows across several wavefronts: 16 wavefronts per CU
   }
-  else if (total_waves > 1024 || has_transposed) WG = std::max(256, L);
+  else if (total_waves > 4 * CUS || has_transposed) WG = std::max(256, L);
   else WG = std::max(64, L);
   // Rows with [1,C] operands, above all operands that outweigh the row's own traffic (LayerNorm with
   // gamma, beta and a bias over bf16 rows: 12 bytes per column against 4).  Re-reading the operands for every row, or for
@@ -286,13 +289,13 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
     const int wg = L >= 128 ? std::min(1024, 4 * L) : std::max(256, std::min(1024, 16 * L));  // 4 rows, or 16 one-wavefront rows, per trip
     // (one-wavefront rows: beyond ~8 rounds of resident workgroups the one-trip form catches up and
     // passes: [65536,1024] 48.9 against 49.5 us, [262144,1024] 203 against 210 us)
-    const bool full_slices = NVL * V >= 16 && (int64_t)NVL * L == NV && (int64_t)R * L <= 8 * 524288;
+    const bool full_slices = NVL * V >= 16 && (int64_t)NVL * L == NV && (int64_t)R * L <= 8 * RES;
     // rows across several wavefronts gain with any [1,C] operand (RMSNorm bf16 [8192,4096]: 24.5 ->
     // 23.6 us, residual+LayerNorm: 50.5 -> 45.8 us); one-wavefront rows only with heavy ones
     // (up to ~4 rounds of work: at [32768,2048] the one-trip form is 2-5 % faster again)
     const bool heavy = rowv_bytes * 2 >= full_bytes * 3;
-    const bool pays = L >= 128 ? heavy || (n_rowv_in > 0 && (int64_t)R * L <= 4 * 524288) : full_slices && heavy;
-    if (pays && (int64_t)n_rowv_in * NVL * L * V * 4 + 1024 <= opt.lds_budget && (int64_t)R * L / wg >= 2 * (524288 / wg)) {
+    const bool pays = L >= 128 ? heavy || (n_rowv_in > 0 && (int64_t)R * L <= 4 * RES) : full_slices && heavy;
+    if (pays && (int64_t)n_rowv_in * NVL * L * V * 4 + 1024 <= opt.lds_budget && (int64_t)R * L / wg >= 2 * (RES / wg)) {
       staged_loop = true;
       WG = wg;
     }
@@ -337,14 +340,14 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   // order and a fresh wavefront issues its loads at once, which measures faster on this device
   // than persistent workgroups looping with a grid stride.  Column reductions keep a bounded
   // grid because every workgroup leaves a partial to fold.
-  int cap = colred ? 256 : (1 << 30);
+  int cap = colred ? CUS : (1 << 30);
   // Exception: [1,C] operands that cannot be shared through LDS (fewer than 4 rows per workgroup)
   // are read again from L2 for every row of a one-shot grid.  When those reads outweigh the row's
   // own traffic (LayerNorm with gamma, beta and a bias over rows of 4096+ elements: 12 bytes per
   // column against 4), the workgroups loop instead, 16 wavefronts per CU, and keep their slices of
   // the operands in registers (measured on [8192,4096] bf16: 35.3 -> 29.4 us).
   if (staged_loop && s.G >= 2) {
-    cap = std::max(256, 524288 / WG);
+    cap = std::max(CUS, (int)(RES / WG));
   } else if (!colred && !chunked && CT == 1 && s.G < 4 && R > 1) {
     int64_t rowv_bytes = 0, full_bytes = 0;
     for (const ExtTensor& e : gp->ext_in) {  // bytes per column
@@ -353,7 +356,7 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
     }
     for (const ExtTensor& e : gp->ext_out)
       if (e.kind == KIND_FULL) full_bytes += dtype_size(e.dtype);
-    if (rowv_bytes * 2 >= full_bytes * 3) cap = std::max(256, 262144 / WG);
+    if (rowv_bytes * 2 >= full_bytes * 3) cap = std::max(CUS, (int)(RES / 2 / WG));
   }
   if (opt.has_hint && opt.hint.max_workgroups > 0) cap = opt.hint.max_workgroups;
   cap = std::min(cap, (int)(0x7fffffff / WG));  // a launch holds fewer than 2^31 lanes: beyond that the workgroups loop
@@ -609,7 +612,7 @@ std::vector<fs_sched_hint> candidate_hints(const GroupPlan& base) {
   // workgroups that stage once (32 wavefronts per CU), whichever the base is not
   if (s.stage_rowv && base.col_reduces.empty() && s.CT == 1 && s.L <= 256) {
     const int wg_loop = s.L >= 128 ? std::min(1024, 4 * s.L) : 1024, wg_once = std::max(256, 4 * s.L);
-    if (s.grid >= s.n_iters) out.push_back(fs_sched_hint{s.L, wg_loop, 524288 / wg_loop, 0});
+    if (s.grid >= s.n_iters) out.push_back(fs_sched_hint{s.L, wg_loop, (int)(device_limits().resident_lanes / wg_loop), 0});
     else if (wg_once <= 1024) out.push_back(fs_sched_hint{s.L, wg_once, 1 << 20, 0});
   }
   return out;

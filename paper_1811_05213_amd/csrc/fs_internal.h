@@ -23,6 +23,19 @@ std::string& error_buffer();
     return (status);               \
   } while (0)
 
+// ---- device figures --------------------------------------------------------------------------
+// What the planner needs to know about the machine.  Read once per process from the current
+// device; the published MI355X figures stand in when planning runs without one (kernels are
+// compiled ahead of time on machines that have no GPU).
+struct DeviceLimits {
+  int cus = 256;                      // compute units (8 XCDs x 32)
+  int lds_per_workgroup = 65536;      // LDS bytes one workgroup may allocate
+  int64_t resident_lanes = 524288;    // lanes resident on the whole device (2048 per compute unit)
+  int64_t l2_bytes = 4ll << 20;       // L2 of one XCD
+  bool from_device = false;
+};
+const DeviceLimits& device_limits();
+
 // ---- graph -----------------------------------------------------------------------------------
 inline bool op_is_free(int op) {  // never materialised, never a launch: inlined into consumers
   return op == FS_INPUT || op == FS_CONST || op == FS_BCAST_ROWVEC || op == FS_BCAST_COLVEC;
@@ -201,7 +214,7 @@ struct fs_plan {
   std::map<int, size_t> ws_tensor_offset;  // node materialised in the workspace -> byte offset
   size_t ticket_bytes = 0;                 // tickets live at the start of the workspace
   size_t workspace_bytes = 0;
-  uint64_t min_hbm_bytes = 0, launched_hbm_bytes = 0;
+  uint64_t min_hbm_bytes = 0, launched_hbm_bytes = 0, unfused_hbm_bytes = 0;
   std::vector<char> code;  // one gfx950 code object holding every kernel of the plan
   // per-device loaded code
   struct Loaded {

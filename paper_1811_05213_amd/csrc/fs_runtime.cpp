@@ -72,6 +72,29 @@ void write_file_atomic(const std::string& path, const std::vector<char>& data) {
 
 }  // namespace
 
+const DeviceLimits& device_limits() {
+  static DeviceLimits lim;
+  static std::once_flag once;
+  std::call_once(once, [] {
+    int count = 0, dev = 0;
+    if (hipGetDeviceCount(&count) != hipSuccess || count <= 0 || hipGetDevice(&dev) != hipSuccess) {
+      (void)hipGetLastError();  // no device: not an error of any later call
+      return;
+    }
+    int cus = 0, lds = 0, lanes_per_cu = 0, l2 = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return;
+    if (hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess || lds <= 0) return;
+    if (hipDeviceGetAttribute(&lanes_per_cu, hipDeviceAttributeMaxThreadsPerMultiProcessor, dev) != hipSuccess || lanes_per_cu <= 0) return;
+    if (hipDeviceGetAttribute(&l2, hipDeviceAttributeL2CacheSize, dev) != hipSuccess || l2 <= 0) l2 = 4 << 20;
+    lim.cus = cus;
+    lim.lds_per_workgroup = lds;
+    lim.resident_lanes = (int64_t)cus * lanes_per_cu;
+    lim.l2_bytes = l2;
+    lim.from_device = true;
+  });
+  return lim;
+}
+
 fs_status compile_kernel(const std::string& source, const std::string& name, std::vector<char>* code) {
   std::string key_text = source;
   for (int i = 0; i < kNumCompileOptions; ++i) key_text += kCompileOptions[i];
@@ -168,7 +191,7 @@ fs_status fs_plan_create(const fs_graph_desc* desc, fs_plan** out_plan) {
   plan->opt.mode = desc->mode & FS_MODE_UNFUSED;
   plan->opt.layered = (desc->mode & FS_MODE_LAYERED) != 0;
   const bool use_library = !(desc->mode & FS_MODE_NO_PERFLIB) && !desc->hint && perflib_size() > 0;
-  plan->opt.lds_budget = desc->lds_budget_bytes > 0 ? desc->lds_budget_bytes : 65536;
+  plan->opt.lds_budget = desc->lds_budget_bytes > 0 ? desc->lds_budget_bytes : std::min(65536, device_limits().lds_per_workgroup);
   if (desc->hint) {
     plan->opt.hint = *desc->hint;
     plan->opt.has_hint = true;
@@ -333,6 +356,19 @@ fs_status fs_plan_create(const fs_graph_desc* desc, fs_plan** out_plan) {
   for (int o : g.outputs) plan->min_hbm_bytes += (uint64_t)g.nodes[o].rows * g.nodes[o].cols * dtype_size(g.nodes[o].dtype);
   plan->launched_hbm_bytes = 0;
   for (const GroupPlan& gp : plan->groups) plan->launched_hbm_bytes += gp.min_hbm_bytes;
+  // what one launch per compute node would move: every live node as a group of its own
+  plan->unfused_hbm_bytes = 0;
+  if (plan->opt.mode == FS_MODE_UNFUSED) {
+    plan->unfused_hbm_bytes = plan->launched_hbm_bytes;
+  } else {
+    PlanOptions uo;
+    uo.mode = FS_MODE_UNFUSED;
+    uo.lds_budget = plan->opt.lds_budget;
+    GroupPlan single;
+    for (int id = 0; id < g.n(); ++id)
+      if (plan->group_of[id] >= 0 && analyse_group(g, std::vector<int>{id}, plan->group_of, 0, uo, &single) == FS_OK)
+        plan->unfused_hbm_bytes += single.min_hbm_bytes;
+  }
 
   *out_plan = plan;
   return FS_OK;
@@ -420,16 +456,67 @@ fs_status fs_plan_workspace_init(fs_plan* plan, void* workspace, size_t workspac
   return FS_OK;
 }
 
-fs_status fs_plan_run(fs_plan* plan, const void* const* inputs, void* const* outputs, void* workspace,
-                      size_t workspace_bytes, void* hip_stream) {
-  if (!plan || !outputs) FS_FAIL(FS_ERR_INVALID_ARG, "NULL argument");
+// Pointer checks shared by fs_plan_run and fs_plan_tune: NULL, alignment, and byte ranges that
+// overlap where one of the two is written (outputs against inputs, other outputs and the workspace;
+// inputs against the workspace).  Inputs may alias each other: they are only read.
+static fs_status check_buffers(const fs_plan* plan, const void* const* inputs, void* const* outputs, const void* workspace) {
+  if (!outputs) FS_FAIL(FS_ERR_INVALID_ARG, "outputs is NULL");
   const Graph& g = plan->graph;
   if (!g.input_ids.empty() && !inputs) FS_FAIL(FS_ERR_INVALID_ARG, "inputs is NULL");
   for (size_t k = 0; k < g.input_ids.size(); ++k)
     if (!inputs[k] || ((uintptr_t)inputs[k] & 15)) FS_FAIL(FS_ERR_INVALID_ARG, "inputs[%zu] is NULL or not 16-byte aligned", k);
   for (size_t k = 0; k < g.outputs.size(); ++k)
     if (!outputs[k] || ((uintptr_t)outputs[k] & 15)) FS_FAIL(FS_ERR_INVALID_ARG, "outputs[%zu] is NULL or not 16-byte aligned", k);
+  auto bytes_of = [&](int node) { return (uintptr_t)g.nodes[node].rows * (uintptr_t)g.nodes[node].cols * (uintptr_t)dtype_size(g.nodes[node].dtype); };
+  auto overlap = [](uintptr_t a, uintptr_t an, uintptr_t b, uintptr_t bn) { return a < b + bn && b < a + an; };
+  const uintptr_t ws = (uintptr_t)workspace, wsn = workspace ? plan->workspace_bytes : 0;
+  for (size_t k = 0; k < g.outputs.size(); ++k) {
+    const uintptr_t o = (uintptr_t)outputs[k], on = bytes_of(g.outputs[k]);
+    for (size_t j = 0; j < g.input_ids.size(); ++j)
+      if (overlap(o, on, (uintptr_t)inputs[j], bytes_of(g.input_ids[j]))) FS_FAIL(FS_ERR_INVALID_ARG, "outputs[%zu] overlaps inputs[%zu]", k, j);
+    for (size_t j = 0; j < k; ++j)
+      if (overlap(o, on, (uintptr_t)outputs[j], bytes_of(g.outputs[j]))) FS_FAIL(FS_ERR_INVALID_ARG, "outputs[%zu] overlaps outputs[%zu]", k, j);
+    if (wsn && overlap(o, on, ws, wsn)) FS_FAIL(FS_ERR_INVALID_ARG, "outputs[%zu] overlaps the workspace", k);
+  }
+  for (size_t j = 0; j < g.input_ids.size(); ++j)
+    if (wsn && overlap((uintptr_t)inputs[j], bytes_of(g.input_ids[j]), ws, wsn)) FS_FAIL(FS_ERR_INVALID_ARG, "inputs[%zu] overlaps the workspace", j);
+  return FS_OK;
+}
+
+fs_status fs_plan_load(fs_plan* plan) {
+  if (!plan) FS_FAIL(FS_ERR_INVALID_ARG, "plan is NULL");
+  int device = 0;
+  const hipError_t e = hipGetDevice(&device);
+  if (e != hipSuccess) FS_FAIL(FS_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e));
+  fs_plan::Loaded* ld = nullptr;
+  return load_on_device(plan, device, &ld);
+}
+
+fs_status fs_plan_workspace_check(fs_plan* plan, const void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!plan) FS_FAIL(FS_ERR_INVALID_ARG, "plan is NULL");
   fs_status st = check_workspace(plan, workspace, workspace_bytes);
+  if (st != FS_OK) return st;
+  size_t n = 0;
+  for (const GroupPlan& gp : plan->groups) n += (size_t)gp.n_tickets;
+  if (n == 0) return FS_OK;
+  hipError_t e = hipStreamSynchronize((hipStream_t)hip_stream);
+  if (e != hipSuccess) FS_FAIL(FS_ERR_HIP, "hipStreamSynchronize: %s", hipGetErrorString(e));
+  std::vector<uint32_t> host(n);
+  e = hipMemcpy(host.data(), workspace, n * 4, hipMemcpyDeviceToHost);
+  if (e != hipSuccess) FS_FAIL(FS_ERR_HIP, "hipMemcpy: %s", hipGetErrorString(e));
+  for (size_t i = 0; i < n; ++i)
+    if (host[i] != 0u)
+      FS_FAIL(FS_ERR_WORKSPACE, "ticket %zu of %zu holds %u, not 0: the workspace was never initialised, or a run on it did not finish", i, n, host[i]);
+  return FS_OK;
+}
+
+fs_status fs_plan_run(fs_plan* plan, const void* const* inputs, void* const* outputs, void* workspace,
+                      size_t workspace_bytes, void* hip_stream) {
+  if (!plan) FS_FAIL(FS_ERR_INVALID_ARG, "plan is NULL");
+  const Graph& g = plan->graph;
+  fs_status st = check_workspace(plan, workspace, workspace_bytes);
+  if (st != FS_OK) return st;
+  st = check_buffers(plan, inputs, outputs, workspace);
   if (st != FS_OK) return st;
 
   int device = 0;
@@ -460,12 +547,29 @@ fs_status fs_plan_run(fs_plan* plan, const void* const* inputs, void* const* out
 }
 
 fs_status fs_plan_stats(const fs_plan* plan, int32_t* num_groups, int32_t* num_launches, uint64_t* min_hbm_bytes,
-                        uint64_t* launched_hbm_bytes) {
+                        uint64_t* unfused_hbm_bytes) {
   if (!plan) FS_FAIL(FS_ERR_INVALID_ARG, "plan is NULL");
   if (num_groups) *num_groups = (int32_t)plan->groups.size();
   if (num_launches) *num_launches = (int32_t)plan->groups.size();
   if (min_hbm_bytes) *min_hbm_bytes = plan->min_hbm_bytes;
-  if (launched_hbm_bytes) *launched_hbm_bytes = plan->launched_hbm_bytes;
+  if (unfused_hbm_bytes) *unfused_hbm_bytes = plan->unfused_hbm_bytes;
+  return FS_OK;
+}
+
+fs_status fs_plan_launched_hbm_bytes(const fs_plan* plan, uint64_t* bytes) {
+  if (!plan || !bytes) FS_FAIL(FS_ERR_INVALID_ARG, "NULL argument");
+  *bytes = plan->launched_hbm_bytes;
+  return FS_OK;
+}
+
+fs_status fs_device_limits(int32_t* compute_units, int32_t* lds_bytes_per_workgroup, int32_t* resident_lanes, int64_t* l2_bytes,
+                           int32_t* from_device) {
+  const DeviceLimits& lim = device_limits();
+  if (compute_units) *compute_units = lim.cus;
+  if (lds_bytes_per_workgroup) *lds_bytes_per_workgroup = lim.lds_per_workgroup;
+  if (resident_lanes) *resident_lanes = (int32_t)lim.resident_lanes;
+  if (l2_bytes) *l2_bytes = lim.l2_bytes;
+  if (from_device) *from_device = lim.from_device ? 1 : 0;
   return FS_OK;
 }
 
@@ -554,14 +658,11 @@ struct TuneScratch {  // everything fs_plan_tune allocates, released on every ex
 
 fs_status fs_plan_tune(fs_plan* plan, const void* const* inputs, void* const* outputs, void* workspace,
                        size_t workspace_bytes, void* hip_stream, int32_t reps, fs_tune_report* report) {
-  if (!plan || !outputs) FS_FAIL(FS_ERR_INVALID_ARG, "NULL argument");
+  if (!plan) FS_FAIL(FS_ERR_INVALID_ARG, "plan is NULL");
   const Graph& g = plan->graph;
-  if (!g.input_ids.empty() && !inputs) FS_FAIL(FS_ERR_INVALID_ARG, "inputs is NULL");
-  for (size_t k = 0; k < g.input_ids.size(); ++k)
-    if (!inputs[k] || ((uintptr_t)inputs[k] & 15)) FS_FAIL(FS_ERR_INVALID_ARG, "inputs[%zu] is NULL or not 16-byte aligned", k);
-  for (size_t k = 0; k < g.outputs.size(); ++k)
-    if (!outputs[k] || ((uintptr_t)outputs[k] & 15)) FS_FAIL(FS_ERR_INVALID_ARG, "outputs[%zu] is NULL or not 16-byte aligned", k);
   fs_status st = check_workspace(plan, workspace, workspace_bytes);
+  if (st != FS_OK) return st;
+  st = check_buffers(plan, inputs, outputs, workspace);
   if (st != FS_OK) return st;
   if (reps <= 0) reps = 9;
   if (reps > 101) reps = 101;

@@ -24,7 +24,7 @@ tensor's own scale.  Two refinements replace any blanket slack:
 2. Conditioning companion ("B"): the same oracle with nodes kept in fp64 and rounded at plan
    outputs only.  Where A and B differ by more than the tolerance, the element is ill-conditioned
    with respect to fp32 rounding itself, and no fp32 implementation can be held to the tolerance
-   there.  Those elements are counted, must stay a small fraction of the tensor, and are held to
+   there.  Those elements are counted, must stay a small fraction of the plan's output elements, and are held to
    |gpu - A| <= 16*|A - B| + tol instead.
 """
 from __future__ import annotations
@@ -47,9 +47,9 @@ def _as_f64(a: np.ndarray, dtype: str) -> np.ndarray:
     return (bf16_bits_to_f32(a) if dtype == "bf16" else a).astype(np.float64)
 
 
-def check_output(gpu: np.ndarray, ref: np.ndarray, dtype: str, what: str = "", ref_b: Optional[np.ndarray] = None,
-                 max_ill_fraction: float = MAX_ILL_FRACTION):
-    """One output tensor against reference A (and, when given, the conditioning companion B)."""
+def check_output(gpu: np.ndarray, ref: np.ndarray, dtype: str, what: str = "", ref_b: Optional[np.ndarray] = None):
+    """One output tensor against reference A (and, when given, the conditioning companion B).
+    Returns statistics; "ill_conditioned" counts the elements the companion flagged (check_all bounds their share)."""
     assert gpu.shape == ref.shape, (what, gpu.shape, ref.shape)
     if dtype == "u8":
         bad = int((gpu != ref).sum())
@@ -67,8 +67,6 @@ def check_output(gpu: np.ndarray, ref: np.ndarray, dtype: str, what: str = "", r
         ill = gap > tol
         n_ill = int(ill.sum())
         if n_ill:
-            assert n_ill <= max(1.0, max_ill_fraction * ill.size), \
-                f"{what}: {n_ill} of {ill.size} elements are ill-conditioned (oracle A and B differ by more than the tolerance)"
             tol = np.where(ill, ILL_SLACK * gap + tol, tol)
     ratio = float((err / tol).max())
     if ratio > 1.0:
@@ -165,8 +163,13 @@ def check_all(graph: Graph, gpu_outs, ref, what: str = "", max_ill_fraction: flo
     else:
         a, b = ref.for_device(gpu_outs)
     stats = []
+    total = ill = 0
     for k, o in enumerate(graph.outputs):
         n = graph.nodes[o]
-        stats.append(check_output(gpu_outs[k], a[k], n.dtype, f"{what} output {k} (node {o} {n.op} {n.name})",
-                                  None if b is None else b[k], max_ill_fraction))
+        stats.append(check_output(gpu_outs[k], a[k], n.dtype, f"{what} output {k} (node {o} {n.op} {n.name})", None if b is None else b[k]))
+        total += n.rows * n.cols
+        ill += stats[-1]["ill_conditioned"]
+    # (a floor of a few elements: a [4,1] output whose row sums cancel is two elements, not "half the workload")
+    assert ill <= max(8.0, max_ill_fraction * total), \
+        f"{what}: {ill} of {total} output elements are ill-conditioned (oracle A and B differ by more than the tolerance): the case tests nothing"
     return stats

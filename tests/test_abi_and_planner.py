@@ -510,3 +510,79 @@ def test_survey_patterns_are_single_kernels():
             assert p.stats()["num_launches"] == 1, (name, rows, cols)
             assert p.stats()["launched_hbm_bytes"] == p.stats()["min_hbm_bytes"] == min_hbm_bytes(g)
         p.destroy()
+
+
+# ------------------------------------------------------------------ boundary: statuses that need no GPU
+def test_stats_report_the_unfused_traffic_of_the_same_dag():
+    # fs_plan_stats' fourth figure is what one launch per compute node would move, whatever mode the plan was made in
+    for g in (softmax_graph(256, 1024), layernorm_gelu_graph(512, 1024), multi_reduce_graph(4096, 512), random_dag_graph()):
+        p, u = fs.Plan(g), fs.Plan(g, mode=fs.FS_MODE_UNFUSED)
+        sp, su = p.stats(), u.stats()
+        assert sp["unfused_hbm_bytes"] == su["unfused_hbm_bytes"] == su["launched_hbm_bytes"] > sp["launched_hbm_bytes"] >= sp["min_hbm_bytes"]
+        p.destroy()
+        u.destroy()
+    # softmax by hand: max reads x, writes m; sub reads x, m, writes d; exp d -> e; sum e -> s; div e, s -> y
+    R, C = 256, 1024
+    full, vec = 4 * R * C, 4 * R
+    p = fs.Plan(softmax_graph(R, C))
+    assert p.stats()["unfused_hbm_bytes"] == (full + vec) + (full + vec + full) + 2 * full + (full + vec) + (full + vec + full)
+    p.destroy()
+
+
+def test_device_limits_without_a_device():
+    import torch
+    lim = fs.device_limits()
+    if torch.cuda.is_available():
+        assert lim["from_device"] and lim["compute_units"] > 0 and lim["lds_bytes_per_workgroup"] >= 65536
+    else:   # the published MI355X figures stand in
+        assert lim == {"compute_units": 256, "lds_bytes_per_workgroup": 65536, "resident_lanes": 524288, "l2_bytes": 4 << 20,
+                       "from_device": False}
+    # a budget above what one workgroup may use is refused, at the limit it is accepted
+    assert _status(softmax_graph(64, 1024), lds_budget_bytes=lim["lds_bytes_per_workgroup"] + 1) == "FS_ERR_INVALID_ARG"
+    assert _status(softmax_graph(64, 1024), lds_budget_bytes=lim["lds_bytes_per_workgroup"]) == "FS_OK"
+
+
+def test_run_refuses_overlapping_buffers_before_touching_the_device():
+    # Pointer checks come before any HIP call, so made-up addresses are enough.  Only calls that MUST be refused are
+    # made (an accepted call would launch on those addresses), and only where no GPU is visible.
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("host-only check: with a device present the accepted path would launch on made-up addresses")
+    g = Graph()
+    a, b = g.input(64, 256), g.input(64, 256)
+    s = g.binary("add", a, b)
+    t = g.transpose(g.binary("mul", s, a))       # two groups: the product crosses a group boundary through the workspace
+    c = g.reduce_col("sum", s)
+    g.set_outputs([s, t, c])
+    p = fs.Plan(g)
+    need = p.workspace_bytes()
+    nb = 64 * 256 * 4
+    base = 0x7000_0000_0000
+    ins, outs, ws = [base, base + 2 * nb], [base + 4 * nb, base + 6 * nb, base + 8 * nb], base + 16 * nb
+
+    def status(i, o, w=ws, wb=max(need, 256)):
+        try:
+            p.run(i, o, w, wb)
+        except fs.FsError as e:
+            return e.status_name, str(e)
+        return "FS_OK", ""
+
+    assert status([outs[0], ins[1]], outs)[0] == "FS_ERR_INVALID_ARG"                      # output 0 IS input 0
+    assert "outputs[0] overlaps inputs[0]" in status([outs[0] - nb + 16, ins[1]], outs)[1]  # partial overlap from below
+    assert "outputs[1] overlaps inputs[1]" in status([ins[0], outs[1] + nb - 16], outs)[1]  # partial overlap from above
+    assert "outputs[1] overlaps outputs[0]" in status(ins, [outs[0], outs[0] + 16, outs[2]])[1]
+    assert "outputs[2] overlaps outputs[1]" in status(ins, [outs[0], outs[1], outs[1] + nb - 16])[1]
+    if need:
+        assert "outputs[0] overlaps the workspace" in status(ins, [ws + 256, outs[1], outs[2]])[1]
+        assert "inputs[1] overlaps the workspace" in status([ins[0], ws + need - 16], outs)[1]
+        assert status(ins, outs, ws, need - 1)[0] == "FS_ERR_WORKSPACE"
+        assert status(ins, outs, ws + 64)[0] == "FS_ERR_WORKSPACE"
+    assert status([ins[0] + 4, ins[1]], outs)[0] == "FS_ERR_INVALID_ARG"                    # misaligned
+    assert status([0, ins[1]], outs)[0] == "FS_ERR_INVALID_ARG"                             # NULL
+    # inputs may alias each other (only read): not refused for that reason -> the call reaches the device query and fails THERE
+    assert status([ins[0], ins[0]], outs)[0] == "FS_ERR_HIP"
+    # loading needs a device
+    with pytest.raises(fs.FsError) as e:
+        p.load()
+    assert e.value.status_name == "FS_ERR_HIP"
+    p.destroy()

@@ -444,8 +444,29 @@ def test_run_argument_errors():
     with pytest.raises(fs.FsError) as e:
         plan.run([ptrs_in[0] + 4], ptrs_out, r.workspace.data_ptr(), need)
     assert e.value.status_name == "FS_ERR_INVALID_ARG"
+    # real device buffers that overlap: the row-norm output laid over the input, and over the workspace
+    with pytest.raises(fs.FsError) as e:
+        plan.run(ptrs_in, [ptrs_out[0], ptrs_out[1], ptrs_in[0] + 1024], r.workspace.data_ptr(), need)
+    assert e.value.status_name == "FS_ERR_INVALID_ARG" and "overlaps inputs[0]" in str(e.value)
+    with pytest.raises(fs.FsError) as e:
+        plan.run(ptrs_in, [r.workspace.data_ptr(), ptrs_out[1], ptrs_out[2]], r.workspace.data_ptr(), need)
+    assert e.value.status_name == "FS_ERR_INVALID_ARG" and "overlaps the workspace" in str(e.value)
+    plan.load()   # explicit load: the first run after it allocates nothing
+    plan.load()   # idempotent
+    plan.workspace_check(r.workspace.data_ptr(), need)   # initialised by DeviceRun: clean
     r.launch()  # still usable afterwards
     check_all(g, r.results(), Reference(g, ins), "after argument errors")
+    plan.workspace_check(r.workspace.data_ptr(), need)   # every run leaves the tickets at zero
+    # a workspace that was never initialised (recycled memory) is reported, not silently mis-folded
+    import torch
+    dirty = torch.full((max(need, 256),), 0x5A, dtype=torch.uint8, device="cuda:0")
+    with pytest.raises(fs.FsError) as e:
+        plan.workspace_check(dirty.data_ptr(), need)
+    assert e.value.status_name == "FS_ERR_WORKSPACE" and "ticket" in str(e.value)
+    plan.workspace_init(dirty.data_ptr(), need)
+    plan.workspace_check(dirty.data_ptr(), need)
+    lim = fs.device_limits()
+    assert lim["from_device"] and lim["compute_units"] >= 1 and lim["lds_bytes_per_workgroup"] >= 65536
     plan.destroy()
 
 
