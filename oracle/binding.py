@@ -95,10 +95,11 @@ def _encode(graph):
     return g, nodes, outs
 
 
-def run(graph, inputs: Sequence[np.ndarray], num_threads: int = 1, round_nodes: bool = True) -> List[np.ndarray]:
+def run(graph, inputs: Sequence[np.ndarray], num_threads: int = 1, round_nodes=True) -> List[np.ndarray]:
     """Evaluate `graph` (a workloads.Graph) on host arrays; returns one array per plan output.
 
     f32 tensors are float32 arrays, bf16 tensors are uint16 arrays of raw bits, u8 are uint8.
+    round_nodes: True / 1 the reference of record; False / 0 the fp64 companion; 2 the fp32-accumulation companion.
     """
     lib = _load()
     g, _nodes, _outs = _encode(graph)
@@ -118,7 +119,7 @@ def run(graph, inputs: Sequence[np.ndarray], num_threads: int = 1, round_nodes: 
         nd = graph.nodes[o]
         results.append(np.empty((nd.rows, nd.cols), dtype=_NP[nd.dtype]))
     out_ptrs = (ctypes.c_void_p * max(1, len(results)))(*[a.ctypes.data for a in results])
-    rc = lib.fso_run(ctypes.byref(g), in_ptrs, out_ptrs, int(num_threads), 1 if round_nodes else 0)
+    rc = lib.fso_run(ctypes.byref(g), in_ptrs, out_ptrs, int(num_threads), int(round_nodes))
     if rc != 0:
         raise RuntimeError(f"fso_run failed with code {rc}")
     return results

@@ -116,8 +116,9 @@ static double cmp_f64(int kind, double a, double b) {
   return 0.0;
 }
 
-/* sequential reduction of n values spaced `stride` apart */
-static double reduce_f64(int kind, const double* p, long n, long stride) {
+/* sequential reduction of n values spaced `stride` apart; displaced: sums are moved by
+ * 2^-24 * sum |terms| (the accumulation companion, see fso.h) */
+static double reduce_f64(int kind, const double* p, long n, long stride, int acc32) {
   double acc;
   long i;
   switch (kind) {
@@ -125,6 +126,11 @@ static double reduce_f64(int kind, const double* p, long n, long stride) {
     case FSO_MEAN:
       acc = 0.0;
       for (i = 0; i < n; ++i) acc += p[i * stride];
+      if (acc32) {
+        double mag = 0.0;
+        for (i = 0; i < n; ++i) mag += fabs(p[i * stride]);
+        acc += ldexp(mag, -24);
+      }
       return kind == FSO_MEAN ? acc / (double)n : acc;
     case FSO_MAX_:
       acc = p[0];
@@ -145,6 +151,7 @@ int fso_run(const fso_graph* g, const void* const* host_in, void* const* host_ou
   omp_set_num_threads(num_threads);
 #endif
   const int N = g->num_nodes;
+  const int acc32 = round_nodes == 2;
   int id, k;
 
   /* structural checks: topological ids, arity, shapes */
@@ -247,13 +254,13 @@ int fso_run(const fso_graph* g, const void* const* host_in, void* const* host_ou
       case FSO_REDUCE_ROW: { /* operand [R, Ca] -> [R,1] */
         const long Ca = g->nodes[n->in[0]].cols;
 #pragma omp parallel for
-        for (i = 0; i < R; ++i) out[i] = round_to(dt, reduce_f64(n->attr_i, a + i * Ca, Ca, 1));
+        for (i = 0; i < R; ++i) out[i] = round_to(dt, reduce_f64(n->attr_i, a + i * Ca, Ca, 1, acc32));
         break;
       }
       case FSO_REDUCE_COL: { /* operand [Ra, C] -> [1,C] */
         const long Ra = g->nodes[n->in[0]].rows;
 #pragma omp parallel for
-        for (j = 0; j < C; ++j) out[j] = round_to(dt, reduce_f64(n->attr_i, a + j, Ra, C));
+        for (j = 0; j < C; ++j) out[j] = round_to(dt, reduce_f64(n->attr_i, a + j, Ra, C, acc32));
         break;
       }
       default:

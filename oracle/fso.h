@@ -59,7 +59,14 @@ typedef struct {
  *   round_nodes  1: every node is rounded to its declared dtype before any consumer
  *                   reads it (the reference of record);
  *                0: nodes stay in fp64, rounding only at plan outputs (a companion
- *                   used to flag ill-conditioned elements, never the pass/fail reference).
+ *                   used to flag ill-conditioned elements, never the pass/fail reference);
+ *                2: as 1, but every sum (and the sum inside a mean) is displaced by
+ *                   2^-24 * sum |terms|: one fp32 rounding unit per term, the first-order
+ *                   size of what accumulating in fp32 can do to a sum in ANY order.  The path
+ *                   under test accumulates in fp32, in a tree order of its own; this second
+ *                   companion shows, element by element, how far that choice can move an
+ *                   output (a sum of positive terms hardly moves; a sum whose terms cancel
+ *                   moves by many times its own size).  Never the pass/fail reference either.
  * Returns 0, or a negative code: -1 bad argument, -2 bad graph, -3 out of memory.
  */
 int fso_run(const fso_graph* g, const void* const* host_in, void* const* host_out, int num_threads, int round_nodes);

@@ -29,7 +29,7 @@ std::string& error_buffer();
 // compiled ahead of time on machines that have no GPU).
 struct DeviceLimits {
   int cus = 256;                      // compute units (8 XCDs x 32)
-  int lds_per_workgroup = 65536;      // LDS bytes one workgroup may allocate
+  int lds_per_workgroup = 163840;     // LDS bytes one workgroup may allocate (all of a compute unit's 160 KB)
   int64_t resident_lanes = 524288;    // lanes resident on the whole device (2048 per compute unit)
   int64_t l2_bytes = 4ll << 20;       // L2 of one XCD
   bool from_device = false;

@@ -535,7 +535,7 @@ def test_device_limits_without_a_device():
     if torch.cuda.is_available():
         assert lim["from_device"] and lim["compute_units"] > 0 and lim["lds_bytes_per_workgroup"] >= 65536
     else:   # the published MI355X figures stand in
-        assert lim == {"compute_units": 256, "lds_bytes_per_workgroup": 65536, "resident_lanes": 524288, "l2_bytes": 4 << 20,
+        assert lim == {"compute_units": 256, "lds_bytes_per_workgroup": 163840, "resident_lanes": 524288, "l2_bytes": 4 << 20,
                        "from_device": False}
     # a budget above what one workgroup may use is refused, at the limit it is accepted
     assert _status(softmax_graph(64, 1024), lds_budget_bytes=lim["lds_bytes_per_workgroup"] + 1) == "FS_ERR_INVALID_ARG"

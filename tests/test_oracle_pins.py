@@ -271,6 +271,34 @@ def test_reductions_vs_fsum_and_numpy(kind):
         assert rc[0, c] == np.float32(py([float(t) for t in x[:, c]]))
 
 
+def test_accumulation_companion_displaces_sums_by_one_rounding_unit_per_term():
+    # round_nodes=2: sum (and the sum inside a mean) + 2^-24 * sum |terms|, then the usual rounding; max / min and
+    # everything that is not a reduction are untouched.  Closed forms first, then numpy in fp64.
+    g = Graph()
+    i = g.input(1, 4)
+    g.set_outputs([g.reduce_row("sum", i), g.reduce_row("mean", i)])
+    s, m = run1(g, [np.array([[1.0, -1.0, 0.5, 0.0]], np.float32)], round_nodes=2)
+    # sum 0.5, sum |terms| 2.5: 0.5 + 2.5 * 2^-24 lies half-way between two floats (spacing 2^-24 there) -> the even one
+    assert float(s[0, 0]) == 0.5 + 2 * 2.0 ** -24 and float(m[0, 0]) == np.float32((0.5 + 2.5 * 2.0 ** -24) / 4)
+    s, _ = run1(g, [np.array([[3.0, 3.0, 3.0, 3.0]], np.float32)], round_nodes=2)
+    assert float(s[0, 0]) == 12.0 + 2.0 ** -20    # positive terms: a relative 2^-24 = 0.75 of the spacing at 12, rounds up one step
+    x = (RNG.standard_normal((7, 1001)) * 10.0 ** RNG.integers(-2, 3, (7, 1001))).astype(np.float32)
+    g = Graph()
+    i = g.input(7, 1001)
+    g.set_outputs([g.reduce_row("sum", i), g.reduce_col("sum", i), g.reduce_row("mean", i), g.reduce_col("mean", i),
+                   g.reduce_row("max", i), g.reduce_col("min", i), g.unary("tanh", i)])
+    rs, cs, rm, cm, mx, mn, th = run1(g, [x], round_nodes=2)
+    x64 = x.astype(np.float64)
+    for axis, got_s, got_m, n in ((1, rs, rm, 1001), (0, cs, cm, 7)):
+        want = np.array([math.fsum(v) + math.fsum(abs(t) for t in v) * 2.0 ** -24 for v in (x64 if axis == 1 else x64.T)])
+        np.testing.assert_allclose(got_s.ravel(), want, rtol=1.2e-7)
+        np.testing.assert_allclose(got_m.ravel(), want / n, rtol=1.2e-7)
+    ref = run1(g, [x])
+    np.testing.assert_array_equal(mx, ref[4])
+    np.testing.assert_array_equal(mn, ref[5])
+    np.testing.assert_array_equal(th, ref[6])
+
+
 def test_softmax_pins():
     R, C = 8, 1024
     g = softmax_graph(R, C)

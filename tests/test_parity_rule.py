@@ -137,3 +137,40 @@ def test_conditioning_mask_from_the_fp64_companion():
     ref2 = Reference(g, [uu2, vv2], threads=2)
     with pytest.raises(AssertionError):
         check_all(g, [ref2.a[0]], ref2, "an eighth of the tensor ill-conditioned")
+
+
+def test_accumulation_companion_flags_cancelling_sums():
+    # tanh(row sum): for a row whose 5000 terms cancel to ~0.05 the fp32 sum is uncertain by ~1e-5 in ANY order, and tanh
+    # passes that on at slope 1, while the other rows (|sum| ~ 40) are saturated and insensitive.  The fp64-throughout
+    # companion does not see this (the summands are the same to 1e-7); the accumulation companion does.
+    rows, cols = 64, 5000
+    g = Graph()
+    x = g.input(rows, cols)
+    g.set_outputs([g.unary("tanh", g.reduce_row("sum", g.unary("tanh", x)))])
+    rng = np.random.default_rng(3)
+    xv = rng.standard_normal((rows, cols)).astype(np.float32)
+    t = np.tanh(xv.astype(np.float64)).astype(np.float32).astype(np.float64)
+    for r in (0, 1):   # make the rows' sums 0.05 by bending one element (arctanh of what is missing)
+        rest = 0.05 - (t[r].sum() - t[r, -1])
+        while abs(rest) >= 0.99:   # spread over more elements when one cannot carry it
+            xv[r, np.argmax(np.sign(rest) * -t[r])] = np.float32(2.0 * np.sign(rest))
+            t[r] = np.tanh(xv[r].astype(np.float64)).astype(np.float32)
+            rest = 0.05 - (t[r].sum() - t[r, -1])
+        xv[r, -1] = np.float32(np.arctanh(rest))
+    ref = Reference(g, [xv], threads=2)
+    assert abs(float(np.arctanh(ref.a[0][0, 0])) - 0.05) < 1e-3
+    # a device that sums in fp32 in another order (numpy's pairwise float32 sum)
+    s32 = np.tanh(xv.astype(np.float64)).astype(np.float32).sum(axis=1, dtype=np.float32, keepdims=True)
+    dev = np.tanh(s32.astype(np.float64)).astype(np.float32)
+    st = check_all(g, [dev], ref, "pairwise fp32 sum")
+    assert st[0]["ill_conditioned"] >= 2
+    assert np.abs(ref.b[0] - ref.a[0]).max() < 2e-6 < np.abs(ref.c[0] - ref.a[0])[:2].max()   # B is blind to it, C is not
+    # the flagged rows are still bounded by a multiple of the companion's gap, the others by the plain tolerance
+    bad = dev.copy()
+    bad[0, 0] += np.float32(0.05)
+    with pytest.raises(AssertionError):
+        check_all(g, [bad], ref, "far off on a flagged row")
+    bad = dev.copy()
+    bad[40, 0] -= np.float32(1e-3)
+    with pytest.raises(AssertionError):
+        check_all(g, [bad], ref, "off on a saturated row")
