@@ -255,6 +255,23 @@ fs_status fs_plan_load(fs_plan* plan);
 fs_status fs_plan_run(fs_plan* plan, const void* const* inputs, void* const* outputs,
                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * fs_plan_run_static: fs_plan_run for callers that cannot allocate or provide a workspace - code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The workspace is
+ * a static device array inside the library, FS_STATIC_SCRATCH_BYTES per GPU (held by every GPU the
+ * library runs on until the process ends); the caller still passes inputs and outputs.  The call
+ * itself makes no allocation of any kind: the plan must already be loaded on the current device
+ * (fs_plan_load, which also resolves the array's address on that device; FS_ERR_INVALID_ARG
+ * otherwise), and a plan whose fs_plan_workspace_bytes exceeds FS_STATIC_SCRATCH_BYTES is refused
+ * with FS_ERR_WORKSPACE.  All calls on one GPU share the one array, which keeps the previous
+ * call's contents: each call first zeroes its plan's ticket counters with a fill kernel on
+ * `hip_stream` (a kernel, not a memset), then enqueues the plan's launches.  Calls that overlap
+ * in time on one GPU - different streams, or different plans - race on the array: serialise them.
+ * Results are those of fs_plan_run, bit for bit.  Other errors as for fs_plan_run.
+ */
+#define FS_STATIC_SCRATCH_BYTES (8u << 20)
+fs_status fs_plan_run_static(fs_plan* plan, const void* const* inputs, void* const* outputs, void* hip_stream);
+
 /* Enqueue a fill kernel on `hip_stream` that zeroes the ticket counters of a fresh workspace
  * (a kernel, not a memset: it may be recorded into a HIP graph). */
 fs_status fs_plan_workspace_init(fs_plan* plan, void* workspace, size_t workspace_bytes, void* hip_stream);

@@ -18,6 +18,7 @@ FS_MODE_STITCHED = 0
 FS_MODE_UNFUSED = 1
 FS_MODE_NO_PERFLIB = 2
 FS_MODE_LAYERED = 4
+FS_STATIC_SCRATCH_BYTES = 8 << 20
 
 STATUS_NAMES = ["FS_OK", "FS_ERR_INVALID_ARG", "FS_ERR_BAD_GRAPH", "FS_ERR_SHAPE", "FS_ERR_DTYPE", "FS_ERR_UNSUPPORTED",
                 "FS_ERR_LDS_BUDGET", "FS_ERR_WORKSPACE", "FS_ERR_COMPILE", "FS_ERR_HIP", "FS_ERR_OOM"]
@@ -103,6 +104,8 @@ def lib() -> ctypes.CDLL:
         L.fs_copy_probe.argtypes = [vp, vp, ctypes.c_size_t, vp]
         L.fs_plan_tune.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), vp, ctypes.c_size_t, vp, ctypes.c_int32,
                                    ctypes.POINTER(fs_tune_report)]
+        L.fs_plan_run_static.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), vp]
+        L.fs_plan_run_static.restype = ctypes.c_int
         L.fs_plan_load.argtypes = [vp]
         L.fs_plan_workspace_check.argtypes = [vp, vp, ctypes.c_size_t, vp]
         L.fs_plan_launched_hbm_bytes.argtypes = [vp, u64p]
@@ -191,6 +194,10 @@ class Plan:
         _check(lib().fs_plan_launched_hbm_bytes(self._h, ctypes.byref(c)))
         return {"num_groups": g.value, "num_launches": l.value, "min_hbm_bytes": a.value, "unfused_hbm_bytes": b.value,
                 "launched_hbm_bytes": c.value}
+
+    def run_static(self, input_ptrs: Sequence[int], output_ptrs: Sequence[int], stream: int = 0) -> None:
+        ins, outs = self.pointer_tables(input_ptrs, output_ptrs)
+        _check(lib().fs_plan_run_static(self._h, ins, outs, stream))
 
     def load(self) -> None:
         _check(lib().fs_plan_load(self._h))

@@ -3,6 +3,9 @@
 // checks the header that generated kernels are prefixed with.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
+#include "fs.h"
 #include "fs_device.h"
 
 typedef unsigned int fs_uint4 __attribute__((ext_vector_type(4)));
@@ -66,7 +69,43 @@ __global__ void __launch_bounds__(256) fs_device_selftest_kernel(const void* in,
       if (tid + i * WG < S::NCH) fs_store1<FS_DT_F32>(out, (tid + i * WG) * FV, cv[i][0] + cv[i][3]);
 }
 
+// Scratch of the allocation-free entry point (fs_plan_run_static): the plan workspace of callers that
+// cannot provide one.  Every GPU the library runs on holds its own copy of this array, at its own
+// address, until the process ends.  In host code the array's name is only a handle for
+// hipGetSymbolAddress: kernels are given the per-device address that call returned, never the name.
+static __device__ __align__(256) unsigned char scratch[FS_STATIC_SCRATCH_BYTES];
+
 namespace fs {
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};
+}  // namespace
+
+size_t static_scratch_bytes() { return (size_t)FS_STATIC_SCRATCH_BYTES; }
+
+// Set-up, once per device, with that device current: the device address of the scratch array.
+int static_scratch_resolve(int device, void** out) {
+  if (device < 0 || device >= kMaxDevices) return (int)hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (!g_scratch_ptr[device]) {
+    void* p = nullptr;
+    const hipError_t e = hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return (int)e;
+    if (!p) return (int)hipErrorInvalidSymbol;
+    g_scratch_ptr[device] = p;
+  }
+  if (out) *out = g_scratch_ptr[device];
+  return 0;
+}
+
+// The address resolved earlier for `device`, or NULL.  No HIP call.
+void* static_scratch_lookup(int device) {
+  if (device < 0 || device >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  return g_scratch_ptr[device];
+}
 
 int launch_copy_probe(const void* src, void* dst, size_t bytes, hipStream_t stream) {
   const long n_vec = (long)(bytes / 16);

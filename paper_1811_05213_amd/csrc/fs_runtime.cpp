@@ -18,6 +18,9 @@
 namespace fs {
 int launch_copy_probe(const void* src, void* dst, size_t bytes, hipStream_t stream);
 int launch_zero_u32(void* p, size_t count, hipStream_t stream);
+size_t static_scratch_bytes();
+int static_scratch_resolve(int device, void** out);
+void* static_scratch_lookup(int device);
 
 namespace {
 
@@ -456,6 +459,29 @@ fs_status fs_plan_workspace_init(fs_plan* plan, void* workspace, size_t workspac
   return FS_OK;
 }
 
+// One launch per group, in launch order, on `stream`; `workspace` holds tickets, boundary tensors and partials.
+static fs_status enqueue_groups(const fs_plan* plan, const fs_plan::Loaded* ld, const void* const* inputs, void* const* outputs,
+                                void* workspace, hipStream_t stream) {
+  const Graph& g = plan->graph;
+  char* ws = (char*)workspace;
+  auto tensor_ptr = [&](int node) -> void* {
+    if (g.input_index[node] >= 0) return const_cast<void*>(inputs[g.input_index[node]]);
+    if (g.output_index[node] >= 0) return outputs[g.output_index[node]];
+    return ws + plan->ws_tensor_offset.at(node);
+  };
+  for (size_t gi = 0; gi < plan->groups.size(); ++gi) {
+    const GroupPlan& gp = plan->groups[gi];
+    void* tensors[48];
+    size_t n = 0;
+    for (const ExtTensor& t : gp.ext_in) tensors[n++] = tensor_ptr(t.node);
+    for (const ExtTensor& t : gp.ext_out) tensors[n++] = tensor_ptr(t.node);
+    const hipError_t e = launch_group(gp, ld->functions[gi], tensors, gp.part_bytes ? (void*)(ws + gp.part_offset) : nullptr,
+                                      gp.n_tickets ? (void*)(ws + gp.ticket_offset) : nullptr, stream);
+    if (e != hipSuccess) FS_FAIL(FS_ERR_HIP, "launch of group %zu (%s): %s", gi, gp.kernel_name.c_str(), hipGetErrorString(e));
+  }
+  return FS_OK;
+}
+
 // Pointer checks shared by fs_plan_run and fs_plan_tune: NULL, alignment, and byte ranges that
 // overlap where one of the two is written (outputs against inputs, other outputs and the workspace;
 // inputs against the workspace).  Inputs may alias each other: they are only read.
@@ -488,6 +514,9 @@ fs_status fs_plan_load(fs_plan* plan) {
   int device = 0;
   const hipError_t e = hipGetDevice(&device);
   if (e != hipSuccess) FS_FAIL(FS_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e));
+  // (set-up of the allocation-free entry point: this device's address of the static scratch array)
+  const int se = static_scratch_resolve(device, nullptr);
+  if (se != 0) FS_FAIL(FS_ERR_HIP, "hipGetSymbolAddress(scratch): %s", hipGetErrorString((hipError_t)se));
   fs_plan::Loaded* ld = nullptr;
   return load_on_device(plan, device, &ld);
 }
@@ -520,30 +549,39 @@ fs_status fs_plan_run(fs_plan* plan, const void* const* inputs, void* const* out
   if (st != FS_OK) return st;
 
   int device = 0;
-  hipError_t e = hipGetDevice(&device);
+  const hipError_t e = hipGetDevice(&device);
   if (e != hipSuccess) FS_FAIL(FS_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e));
   fs_plan::Loaded* ld = nullptr;
   st = load_on_device(plan, device, &ld);
   if (st != FS_OK) return st;
+  return enqueue_groups(plan, ld, inputs, outputs, workspace, (hipStream_t)hip_stream);
+}
 
-  char* ws = (char*)workspace;
-  auto tensor_ptr = [&](int node) -> void* {
-    if (g.input_index[node] >= 0) return const_cast<void*>(inputs[g.input_index[node]]);
-    if (g.output_index[node] >= 0) return outputs[g.output_index[node]];
-    return ws + plan->ws_tensor_offset.at(node);
-  };
-
-  for (size_t gi = 0; gi < plan->groups.size(); ++gi) {
-    const GroupPlan& gp = plan->groups[gi];
-    void* tensors[48];
-    size_t n = 0;
-    for (const ExtTensor& t : gp.ext_in) tensors[n++] = tensor_ptr(t.node);
-    for (const ExtTensor& t : gp.ext_out) tensors[n++] = tensor_ptr(t.node);
-    e = launch_group(gp, ld->functions[gi], tensors, gp.part_bytes ? (void*)(ws + gp.part_offset) : nullptr,
-                     gp.n_tickets ? (void*)(ws + gp.ticket_offset) : nullptr, (hipStream_t)hip_stream);
-    if (e != hipSuccess) FS_FAIL(FS_ERR_HIP, "launch of group %zu (%s): %s", gi, gp.kernel_name.c_str(), hipGetErrorString(e));
+fs_status fs_plan_run_static(fs_plan* plan, const void* const* inputs, void* const* outputs, void* hip_stream) {
+  if (!plan) FS_FAIL(FS_ERR_INVALID_ARG, "plan is NULL");
+  if (plan->workspace_bytes > static_scratch_bytes())
+    FS_FAIL(FS_ERR_WORKSPACE, "the plan needs %zu bytes of workspace, the static scratch holds %zu: use fs_plan_run with a workspace of your own",
+            plan->workspace_bytes, static_scratch_bytes());
+  int device = 0;
+  const hipError_t e = hipGetDevice(&device);
+  if (e != hipSuccess) FS_FAIL(FS_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e));
+  // look-ups only: loading a code object or resolving the symbol would allocate
+  fs_plan::Loaded* ld = nullptr;
+  {
+    std::lock_guard<std::mutex> lk(plan->mu);
+    auto it = plan->loaded.find(device);
+    if (it != plan->loaded.end()) ld = &it->second;
   }
-  return FS_OK;
+  void* ws = static_scratch_lookup(device);
+  if (!ld || !ws) FS_FAIL(FS_ERR_INVALID_ARG, "the plan is not loaded on device %d: call fs_plan_load first (this entry point allocates nothing)", device);
+  const fs_status st = check_buffers(plan, inputs, outputs, plan->workspace_bytes ? ws : nullptr);
+  if (st != FS_OK) return st;
+  // the array keeps what the previous call (of any plan) left: this plan's tickets must start at zero
+  if (plan->ticket_bytes) {
+    const int ze = launch_zero_u32(ws, plan->ticket_bytes / 4, (hipStream_t)hip_stream);
+    if (ze != 0) FS_FAIL(FS_ERR_HIP, "fill kernel launch: %s", hipGetErrorString((hipError_t)ze));
+  }
+  return enqueue_groups(plan, ld, inputs, outputs, ws, (hipStream_t)hip_stream);
 }
 
 fs_status fs_plan_stats(const fs_plan* plan, int32_t* num_groups, int32_t* num_launches, uint64_t* min_hbm_bytes,
