@@ -375,6 +375,19 @@ fs_status fs_plan_tune(fs_plan* plan, const void* const* inputs, void* const* ou
  */
 fs_status fs_copy_probe(const void* src, void* dst, size_t bytes, void* hip_stream);
 
+/*
+ * fs_copy_probe_shape: the same copy in a chosen launch shape - `vectors_in_flight` (1, 2, 4 or 8)
+ * 16-byte vectors per lane per loop trip, `workgroups` workgroups of 256 lanes that loop with a grid
+ * stride (0 = one trip per workgroup) - for finding what the fastest plain copy of a given size
+ * reaches on the device, i.e. what a kernel that moves that many bytes can be held against.
+ */
+fs_status fs_copy_probe_shape(const void* src, void* dst, size_t bytes, int32_t vectors_in_flight, int32_t workgroups,
+                              void* hip_stream);
+
+/* fs_launch_probe: enqueue an empty kernel (one wavefront) on `hip_stream`: what a launch costs when
+ * nothing is computed, the floor under the launch-bound workloads. */
+fs_status fs_launch_probe(void* hip_stream);
+
 const char* fs_last_error(void);
 
 #ifdef __cplusplus

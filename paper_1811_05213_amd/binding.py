@@ -106,6 +106,10 @@ def lib() -> ctypes.CDLL:
                                    ctypes.POINTER(fs_tune_report)]
         L.fs_plan_run_static.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), vp]
         L.fs_plan_run_static.restype = ctypes.c_int
+        L.fs_copy_probe_shape.argtypes = [vp, vp, ctypes.c_size_t, ctypes.c_int32, ctypes.c_int32, vp]
+        L.fs_copy_probe_shape.restype = ctypes.c_int
+        L.fs_launch_probe.argtypes = [vp]
+        L.fs_launch_probe.restype = ctypes.c_int
         L.fs_plan_load.argtypes = [vp]
         L.fs_plan_workspace_check.argtypes = [vp, vp, ctypes.c_size_t, vp]
         L.fs_plan_launched_hbm_bytes.argtypes = [vp, u64p]
@@ -272,6 +276,14 @@ def device_limits() -> dict:
     _check(lib().fs_device_limits(ctypes.byref(cu), ctypes.byref(lds), ctypes.byref(lanes), ctypes.byref(l2), ctypes.byref(frm)))
     return {"compute_units": cu.value, "lds_bytes_per_workgroup": lds.value, "resident_lanes": lanes.value, "l2_bytes": l2.value,
             "from_device": bool(frm.value)}
+
+
+def copy_probe_shape(src_ptr: int, dst_ptr: int, nbytes: int, vectors_in_flight: int, workgroups: int, stream: int = 0) -> None:
+    _check(lib().fs_copy_probe_shape(src_ptr, dst_ptr, nbytes, vectors_in_flight, workgroups, stream))
+
+
+def launch_probe(stream: int = 0) -> None:
+    _check(lib().fs_launch_probe(stream))
 
 
 def copy_probe(src_ptr: int, dst_ptr: int, nbytes: int, stream: int = 0) -> None:

@@ -17,7 +17,11 @@
 //     fma, unless one of the two feeds a predicate: predicates must see exactly the roundings
 //     the graph spells out;
 //   - a value that is only stored is not rounded to its dtype in registers first (the store
-//     rounds).
+//     rounds);
+//   - two per-column operands ([1,C] tensors from memory) that enter a chain of additions one
+//     after the other, (p + beta) + bias, are added to each other once per workgroup instead of
+//     once per element: p + (beta + bias).  This reassociates, so it is not done on predicate
+//     paths either; elsewhere the result moves by one rounding, as with the fma contraction.
 #include <algorithm>
 #include <cstring>
 #include <functional>
@@ -38,8 +42,22 @@ struct Emitter {
   std::vector<char> in_set;
   std::vector<int> uses;      // in-group operand slots reading each member (looking through broadcasts)
   std::vector<char> folded;   // multiply emitted inside its single consumer
+  // z = (p +- Ra) +- Rb with Ra, Rb per-column tensors from memory used nowhere else: emitted as +-p + (+-Ra +- Rb)
+  struct Comb {
+    int z, m, p;      // the outer add/sub, the inner one (absorbed: never emitted), the remaining operand (as m names it)
+    int ra, rb;       // the two [1,C] tensors
+    bool neg_a, neg_b, neg_p;
+  };
+  std::vector<Comb> combs;
+  std::map<int, int> comb_of;      // z -> index into combs
+  std::vector<char> absorbed;      // inner add/sub of a comb
+  std::map<int, int> ext_uses;     // [1,C] tensor from memory -> operand slots reading it
+  std::map<int, int> slot_of_ext;  // staged [1,C] tensor -> LDS slot
+  std::vector<int> slot_of_comb;   // comb -> LDS slot
+  int n_slots = 0;
 
-  Emitter(const Graph& g_, GroupPlan& gp_) : g(g_), gp(gp_), in_set(g_.n(), 0), uses(g_.n(), 0), folded(g_.n(), 0) {}
+  Emitter(const Graph& g_, GroupPlan& gp_)
+      : g(g_), gp(gp_), in_set(g_.n(), 0), uses(g_.n(), 0), folded(g_.n(), 0), absorbed(g_.n(), 0) {}
 
   int loc(int node) {
     auto it = local.find(node);
@@ -124,6 +142,15 @@ struct Emitter {
       case FS_ADD:
       case FS_SUB: {
         const bool sub = n.opcode == FS_SUB;
+        if (comb_of.count(id)) {
+          const Comb& c = combs[comb_of.at(id)];
+          const std::string rc = "rc" + std::to_string(loc(c.z)) + "[e]";
+          if (folded[c.p]) {
+            const fs_node& mn = g.nodes[c.p];
+            return "__builtin_fmaf(" + std::string(c.neg_p ? "-(" : "(") + ref(mn.in[0]) + "), " + ref(mn.in[1]) + ", " + rc + ")";
+          }
+          return c.neg_p ? "(" + rc + " - " + ref(c.p) + ")" : "(" + ref(c.p) + " + " + rc + ")";
+        }
         for (int side = 0; side < 2; ++side) {
           const int m = n.in[side];
           if (!folded[m]) continue;
@@ -210,12 +237,55 @@ struct Emitter {
       (strip ? pre : os) << indent << "if (rok && lir == 0 && vbase == 0) fs_store1<" << e.dtype << ">(a.p[" << e.arg << "], row, " << nm << ");\n";
   }
 
+  // the [1,C] tensor from memory behind operand `o`, or -1
+  int ext_rowv_of(int o) const {
+    if (g.nodes[o].opcode == FS_CONST) return -1;
+    const int src = source_of(o);
+    if (g.nodes[src].opcode == FS_CONST || in_set[src]) return -1;
+    auto it = gp.kind.find(src);
+    return it != gp.kind.end() && it->second == KIND_ROWV ? src : -1;
+  }
+
+  void find_combs() {
+    for (int z : gp.members) {
+      const fs_node& zn = g.nodes[z];
+      if ((zn.opcode != FS_ADD && zn.opcode != FS_SUB) || zn.dtype != FS_F32 || g.exact[z] || gp.kind.at(z) != KIND_FULL) continue;
+      for (int side = 0; side < 2; ++side) {
+        const int rb = ext_rowv_of(zn.in[side]), m = zn.in[1 - side];
+        if (rb < 0 || !in_set[m] || absorbed[m] || folded[m] || comb_of.count(m)) continue;
+        const fs_node& mn = g.nodes[m];
+        if ((mn.opcode != FS_ADD && mn.opcode != FS_SUB) || mn.dtype != FS_F32 || g.exact[m] || uses[m] != 1 || find_out(m) ||
+            gp.kind.at(m) != KIND_FULL || gp.level.at(m) != gp.level.at(z))
+          continue;
+        bool done = false;
+        for (int side2 = 0; side2 < 2 && !done; ++side2) {
+          const int ra = ext_rowv_of(mn.in[side2]), pp = mn.in[1 - side2];
+          if (ra < 0 || ra == rb || ext_uses[ra] != 1 || ext_uses[rb] != 1 || ext_rowv_of(pp) >= 0) continue;
+          // m = s1*p + t1*Ra, z = s2*m + t2*Rb  (s, t = +-1)
+          const bool msub = mn.opcode == FS_SUB, zsub = zn.opcode == FS_SUB;
+          const int s1 = (msub && side2 == 0) ? -1 : 1, t1 = (msub && side2 == 1) ? -1 : 1;   // operand `side2` is Ra
+          const int s2 = (zsub && side == 0) ? -1 : 1, t2 = (zsub && side == 1) ? -1 : 1;     // operand `side` is Rb
+          Comb c;
+          c.z = z, c.m = m, c.p = pp, c.ra = ra, c.rb = rb;
+          c.neg_p = s2 * s1 < 0, c.neg_a = s2 * t1 < 0, c.neg_b = t2 < 0;
+          comb_of[z] = (int)combs.size();
+          combs.push_back(c);
+          absorbed[m] = 1;
+          done = true;
+        }
+        if (done) break;
+      }
+    }
+  }
+
   void count_uses() {
     for (int m : gp.members) {
       const fs_node& n = g.nodes[m];
       for (int k = 0; k < n.num_in; ++k) {
         const int src = source_of(n.in[k]);
         if (in_set[src]) ++uses[src];
+        const int r = ext_rowv_of(n.in[k]);
+        if (r >= 0) ++ext_uses[r];
       }
     }
     // decide which multiplies disappear into their consumer
@@ -281,6 +351,17 @@ struct Emitter {
   // Passes alternate their direction: a pass starts with the chunks its predecessor touched
   // last, the ones most likely still in the L2.
   int n_passes = 0;
+  std::map<int, int> pass_loads;   // [R,C] input -> passes that load it (the dry run counts; see generate_kernel)
+  std::set<int> stage_written;     // staged inputs whose LDS copy has been written by an earlier pass
+  // byte offset of staged input `node`'s area inside lds_stage, or -1
+  long stage_offset(int node) const {
+    long off = 0;
+    for (int sn : gp.staged_inputs) {
+      if (sn == node) return off;
+      off += (long)gp.s.stage_chunks * gp.s.NVLC * gp.s.L * gp.s.V * dtype_size(g.nodes[sn].dtype);
+    }
+    return -1;
+  }
   template <class Tail>
   void emit_pass(const std::set<int>& mem, const std::set<int>& ext, bool store_outputs, Tail tail, const std::string& loop = "") {
     if (!loop.empty()) os << "    " << loop << " {\n";
@@ -292,10 +373,24 @@ struct Emitter {
     for (const ExtTensor& e : gp.ext_in) {
       if (!ext.count(e.node)) continue;
       os << "      float " << name(e.node, e.kind) << "[E];\n";
-      if (e.kind == KIND_FULL)
-        os << "      fs_load_row<" << e.dtype << ", " << tmpl_row() << ", false>(" << name(e.node, e.kind) << ", a.p[" << e.arg
-           << "], row0, lir, vbase);\n";
-      else
+      if (e.kind == KIND_FULL) {
+        ++pass_loads[e.node];
+        const long off = gp.s.stage_chunks > 0 ? stage_offset(e.node) : -1;
+        const std::string nm = name(e.node, e.kind);
+        const std::string from_mem = "fs_load_row<" + std::to_string(e.dtype) + ", " + tmpl_row() + ", false>(" + nm + ", a.p[" + std::to_string(e.arg) +
+                                     "], row0, lir, vbase);";
+        if (off < 0) {
+          os << "      " << from_mem << "\n";
+        } else {
+          const std::string chunk = "lds_stage + " + std::to_string(off) + " + (long)ch * " +
+                                    std::to_string((long)gp.s.NVLC * gp.s.L * gp.s.V * dtype_size(e.dtype));
+          if (stage_written.count(e.node))  // a later pass: the head of the row comes back from LDS
+            os << "      if (ch < STAGE_CHUNKS) fs_load_row_chunk_lds<" << e.dtype << ", V, NVL, L>(" << nm << ", " << chunk << ", lir);\n"
+               << "      else " << from_mem << "\n";
+          else  // the first pass that reads it: keep the head of the row
+            os << "      " << from_mem << "\n      if (ch < STAGE_CHUNKS) fs_stage_row_chunk<" << e.dtype << ", V, NVL, L>(" << chunk << ", " << nm << ", lir);\n";
+        }
+      } else
         os << "      fs_load_row<" << e.dtype << ", " << tmpl_row() << ">(" << name(e.node, e.kind) << ", a.p[" << e.arg << "], 0, lir, vbase);\n";
     }
     for (int m : gp.members) {
@@ -316,6 +411,10 @@ struct Emitter {
     }
     tail();
     os << "    }\n";
+    // (a lane reads back exactly the LDS positions it wrote itself, and a wavefront's LDS accesses complete in order:
+    // no barrier between the pass that stages and the passes that read)
+    for (const ExtTensor& e : gp.ext_in)
+      if (e.kind == KIND_FULL && ext.count(e.node) && gp.s.stage_chunks > 0 && stage_offset(e.node) >= 0) stage_written.insert(e.node);
   }
 
   // inside a pass: fold the chunk's elements into the running lane partials q<b> of the stage's reductions
@@ -458,6 +557,14 @@ struct Emitter {
     // simply read where the loop body needs them.
     const bool ctile = s.col_tiled;  // column reductions by column tiles: a workgroup keeps its tile, RB workgroups share the rows
     const bool rowv_in_loop = !ctile && (s.CT > 1 || s.grid >= s.n_iters || s.stage_rowv);
+    // per-column operands that can be added to each other once per workgroup (staged in LDS, or held in registers by
+    // a looping workgroup); where they are read again for every row there is nothing to gain
+    if (!s.chunked && !s.split_rows && !s.resident && s.CT == 1 && (s.stage_rowv || !rowv_in_loop)) find_combs();
+    std::set<int> comb_only;  // [1,C] tensors that are only read through a comb
+    for (const Comb& c : combs) comb_only.insert(c.ra), comb_only.insert(c.rb);
+    for (const ExtTensor& e : gp.ext_in)
+      if (e.kind == KIND_ROWV && !comb_only.count(e.node)) slot_of_ext[e.node] = n_slots++;
+    for (size_t k = 0; k < combs.size(); ++k) slot_of_comb.push_back(n_slots++);
 
     // fixed local numbering: external inputs first, then members
     for (const ExtTensor& e : gp.ext_in) loc(e.node);
@@ -489,6 +596,12 @@ struct Emitter {
     if (s.chunked) {
       os << "  constexpr int NVLC = " << s.NVLC << ", RESV = " << s.RESV << ";\n  constexpr bool RAGC = " << (s.ragged_chunks ? "true" : "false")
          << ";\n";
+      if (s.stage_chunks > 0 && !gp.staged_inputs.empty()) {
+        long bytes = 0;
+        for (int sn : gp.staged_inputs) bytes += (long)s.stage_chunks * s.NVLC * s.L * s.V * dtype_size(g.nodes[sn].dtype);
+        os << "  constexpr int STAGE_CHUNKS = " << s.stage_chunks << ";  // chunks of every staged input kept in LDS\n"
+           << "  __shared__ __attribute__((aligned(16))) unsigned char lds_stage[" << bytes << "];\n";
+      }
       if (s.split_rows) {
         run_split_rows(kname, WPR, KB);
         return;
@@ -507,12 +620,10 @@ struct Emitter {
     os << "  (void)tile; (void)rb; (void)CW; (void)NVF; (void)RB;\n";
     // One LDS pool, shared by lifetime: the row loop's buffers (transpose tile, staged [1,C]
     // operands) and the epilogue's column-fold area never live at the same time.
-    int n_rowv = 0;
-    for (const ExtTensor& e : gp.ext_in) n_rowv += e.kind == KIND_ROWV;
     if (K > 0 || s.tile_transpose || s.stage_rowv) {
       os << "  constexpr int TCW = " << (s.tiled_transpose ? "NVL * L * V" : "C") << ";  // columns of one transpose tile\n";
       os << "  constexpr int SLOT = NVL * L * V, TILE_FLOATS = " << (s.tile_transpose ? "TCW * (G + 1)" : "0") << ", LOOP_FLOATS = TILE_FLOATS + "
-         << (s.stage_rowv ? n_rowv : 0) << " * SLOT, PC = " << std::max(1, s.fold_piece) << ", FOLD_FLOATS = " << (K > 0 ? "(L < 64 ? WG / 64 : G) * PC" : "0") << ";\n";
+         << (s.stage_rowv ? n_slots : 0) << " * SLOT, PC = " << std::max(1, s.fold_piece) << ", FOLD_FLOATS = " << (K > 0 ? "(L < 64 ? WG / 64 : G) * PC" : "0") << ";\n";
       os << "  __shared__ float lds_pool[LOOP_FLOATS > FOLD_FLOATS ? LOOP_FLOATS : FOLD_FLOATS];\n";
       os << "  float* const lds_tile = lds_pool; float* const lds_rowv = lds_pool + TILE_FLOATS; float* const lds_col = lds_pool;\n";
       os << "  (void)lds_tile; (void)lds_rowv; (void)lds_col; (void)SLOT; (void)PC;\n";
@@ -528,6 +639,9 @@ struct Emitter {
           os << ind << "fs_load_row<" << e.dtype << ", " << tmpl_row() << ">(" << name(e.node, KIND_ROWV) << ", a.p[" << e.arg << "], 0, lir, " << vb
              << ");\n";
         }
+      for (const Comb& c : combs)
+        os << ind << "float rc" << loc(c.z) << "[E];\n" << ind << "_Pragma(\"unroll\") for (int e = 0; e < E; ++e) rc" << loc(c.z) << "[e] = "
+           << (c.neg_a ? "-" : "") << name(c.ra, KIND_ROWV) << "[e] " << (c.neg_b ? "- " : "+ ") << name(c.rb, KIND_ROWV) << "[e];\n";
       for (int m : gp.members) {
         if (gp.level.at(m) >= 0 || folded[m]) continue;
         const std::string nm = name(m, KIND_ROWV);
@@ -541,12 +655,45 @@ struct Emitter {
     if (!rowv_in_loop) emit_rowv("  ", ctile ? "vbase" : "0", "rb == 0 && rg == 0");
     // staged [1,C] operands of a looping kernel: written to LDS once, before the loop
     const bool stage_before_loop = s.stage_rowv && s.grid < s.n_iters;
-    auto emit_staging = [&](const std::string& ind) {
-      int k = 0;
+    auto ext_of = [&](int node) -> const ExtTensor& {
       for (const ExtTensor& e : gp.ext_in)
-        if (e.kind == KIND_ROWV) os << ind << "fs_stage_rowvec<" << e.dtype << ", V, L, C, WG>(lds_rowv + " << (k++) << " * SLOT, a.p[" << e.arg << "]);\n";
+        if (e.node == node) return e;
+      return gp.ext_in.front();
+    };
+    auto emit_staging = [&](const std::string& ind) {
+      for (const ExtTensor& e : gp.ext_in)
+        if (e.kind == KIND_ROWV && slot_of_ext.count(e.node))
+          os << ind << "fs_stage_rowvec<" << e.dtype << ", V, L, C, WG>(lds_rowv + " << slot_of_ext.at(e.node) << " * SLOT, a.p[" << e.arg << "]);\n";
+      for (size_t k = 0; k < combs.size(); ++k) {
+        const ExtTensor &ea = ext_of(combs[k].ra), &eb = ext_of(combs[k].rb);
+        os << ind << "fs_stage_rowvec_sum<" << ea.dtype << ", " << eb.dtype << ", " << (combs[k].neg_a ? "true" : "false") << ", "
+           << (combs[k].neg_b ? "true" : "false") << ", V, L, C, WG>(lds_rowv + " << slot_of_comb[k] << " * SLOT, a.p[" << ea.arg << "], a.p[" << eb.arg
+           << "]);\n";
+      }
       os << ind << "__syncthreads();\n";
     };
+    // Looping workgroups that stage their [1,C] operands once: the loads of the first row tile are issued BEFORE the
+    // staging, so the staging's round trip to memory and the first tile's overlap instead of following each other
+    // (every workgroup pays that chain once, at the start of the kernel, when nothing else is in flight to hide it).
+    // The tile in flight lives in variables outside the loop; `fetch` refills them at the bottom of each trip, which is
+    // the order of operations of the plain loop.
+    const bool peeled = stage_before_loop && !ctile && s.CT == 1 && !s.tiled_transpose && !s.resident && std::max(1, s.U) == 1;
+    if (peeled) {
+      os << "  long row = 0, row_ld = 0, row0 = 0;\n  bool rok = false;\n  constexpr int vbase = 0;\n  (void)row_ld; (void)row0; (void)vbase;\n";
+      for (const ExtTensor& e : gp.ext_in) {
+        if (e.kind == KIND_FULL) os << "  float " << name(e.node, KIND_FULL) << "[E];\n";
+        else if (e.kind == KIND_COLV) os << "  float " << name(e.node, KIND_COLV) << " = 0.0f;\n";
+      }
+      os << "  auto fetch = [&](int it) {\n    row = (long)it * G + rg;\n    rok = row < R;\n    row_ld = rok ? row : R - 1;\n    row0 = row_ld * C;\n";
+      for (const ExtTensor& e : gp.ext_in) {
+        if (e.kind == KIND_FULL)
+          os << "    fs_load_row<" << e.dtype << ", " << tmpl_row() << ", " << (e.streaming ? "true" : "false") << ">(" << name(e.node, KIND_FULL)
+             << ", a.p[" << e.arg << "], row0, lir, vbase);\n";
+        else if (e.kind == KIND_COLV)
+          os << "    " << name(e.node, KIND_COLV) << " = fs_load1<" << e.dtype << ">(a.p[" << e.arg << "], row_ld);\n";
+      }
+      os << "  };\n  int it = (int)blockIdx.x;\n  if (it < a.n_iters) fetch(it);\n";
+    }
     if (stage_before_loop) emit_staging("  ");
     for (int k = 0; k < K; ++k) {
       const int m = gp.col_reduces[k];
@@ -558,14 +705,16 @@ struct Emitter {
     // A looping kernel handles U row tiles per trip: the loads of all U tiles are issued first,
     // then the U bodies run one after the other (more bytes in flight per wavefront).
     const int U = (rowv_in_loop || s.CT > 1) ? 1 : std::max(1, s.U);
-    if (ctile) {
+    if (peeled) {
+      os << "  while (it < a.n_iters) {\n";
+    } else if (ctile) {
       os << "  for (int it = rb; it < a.n_iters; it += RB) {\n";
     } else if (U == 1) {
       os << "  for (int it = (int)blockIdx.x; it < a.n_iters; it += (int)gridDim.x) {\n";
     } else {
       os << "  for (int it0 = (int)blockIdx.x * " << U << "; it0 < a.n_iters; it0 += (int)gridDim.x * " << U << ") {\n";
     }
-    for (int u = 0; u < U; ++u) {
+    for (int u = 0; u < U && !peeled; ++u) {
       const std::string x = U == 1 ? "" : "_" + std::to_string(u);
       if (U > 1) os << "    const int it" << x << " = it0 + " << u << ";\n";
       if (ctile) {
@@ -603,18 +752,15 @@ struct Emitter {
       rowv_ready.insert(src);
       const std::string nm = name(src, KIND_ROWV);
       if (!in_set[src]) {
-        int k = 0;
         for (const ExtTensor& e : gp.ext_in) {
-          if (e.kind != KIND_ROWV) continue;
-          if (e.node == src) {
-            declare(nm, "    ");
-            if (s.stage_rowv)
-              os << "    " << vec_fn("fs_read_staged") << "<" << tmpl_row() << ">(" << nm << ", lds_rowv + " << k << " * SLOT, lir" << vec_arg() << ");\n";
-            else
-              os << "    " << vec_fn("fs_load_row") << "<" << e.dtype << ", " << tmpl_row() << ">(" << nm << ", a.p[" << e.arg << "], 0, lir, vbase"
-                 << vec_arg() << ");\n";
-          }
-          ++k;
+          if (e.kind != KIND_ROWV || e.node != src) continue;
+          declare(nm, "    ");
+          if (s.stage_rowv)
+            os << "    " << vec_fn("fs_read_staged") << "<" << tmpl_row() << ">(" << nm << ", lds_rowv + " << slot_of_ext.at(src) << " * SLOT, lir"
+               << vec_arg() << ");\n";
+          else
+            os << "    " << vec_fn("fs_load_row") << "<" << e.dtype << ", " << tmpl_row() << ">(" << nm << ", a.p[" << e.arg << "], 0, lir, vbase"
+               << vec_arg() << ");\n";
         }
         return;
       }
@@ -632,7 +778,25 @@ struct Emitter {
         os << "    if (row == 0 && rok) " << vec_fn("fs_store_row") << "<" << e->dtype << ", " << tmpl_row() << ">(" << nm << ", a.p[" << e->arg
            << "], 0, lir, vbase, true" << vec_arg() << ");\n";
     };
+    std::set<int> comb_ready;
     std::function<void(int)> ensure_rowv_operands = [&](int m) {
+      if (comb_of.count(m)) {  // reads its combined operand (staged) and whatever the remaining operand needs
+        const Comb& c = combs[comb_of.at(m)];
+        if (comb_ready.insert(c.z).second) {
+          const std::string nm = "rc" + std::to_string(loc(c.z));
+          declare(nm, "    ");
+          os << "    " << vec_fn("fs_read_staged") << "<" << tmpl_row() << ">(" << nm << ", lds_rowv + " << slot_of_comb[comb_of.at(m)] << " * SLOT, lir"
+             << vec_arg() << ");\n";
+        }
+        if (g.nodes[c.p].opcode != FS_CONST) {
+          const int o = source_of(c.p);
+          if (g.nodes[o].opcode != FS_CONST) {
+            if (gp.kind.at(o) == KIND_ROWV) ensure_rowv(o);
+            else if (in_set[o] && folded[o]) ensure_rowv_operands(o);
+          }
+        }
+        return;
+      }
       const fs_node& n = g.nodes[m];
       for (int k = 0; k < n.num_in; ++k) {
         if (g.nodes[n.in[k]].opcode == FS_CONST) continue;
@@ -645,7 +809,7 @@ struct Emitter {
     // members in stage order; the row reductions of a stage come last and share one exchange
     std::vector<int> order;
     for (int m : gp.members)
-      if (gp.level.at(m) >= 0 && !folded[m]) order.push_back(m);
+      if (gp.level.at(m) >= 0 && !folded[m] && !absorbed[m]) order.push_back(m);
     auto is_rr = [&](int m) { return std::find(gp.row_reduces.begin(), gp.row_reduces.end(), m) != gp.row_reduces.end(); };
     std::stable_sort(order.begin(), order.end(), [&](int x, int y) {
       const int lx = gp.level.at(x), ly = gp.level.at(y);
@@ -785,6 +949,7 @@ struct Emitter {
         emit_pass(mem, ext, true, []() {});
       }
     }
+    if (peeled) os << "    it += (int)gridDim.x;\n    if (it < a.n_iters) fetch(it);\n";
     os << "  }\n";
 
     // ---- epilogue: finish the column reductions ----
@@ -827,6 +992,26 @@ uint64_t fnv1a(const std::string& s) {
 }  // namespace
 
 fs_status generate_kernel(const Graph& g, GroupPlan* gp, int /*group_index*/) {
+  // Rows walked in chunks: a dry run counts how many passes load each [R,C] input; those that more than one pass
+  // loads keep their first chunks in the LDS the planner left over (inputs before intermediates: what a buffer
+  // saves there is HBM traffic, the bound, whereas an intermediate is recomputed from it with a few ALU operations
+  // - the order of Section 5.1.2, cheap values dropped first, with memory traffic as the cost).
+  gp->staged_inputs.clear();
+  gp->s.stage_chunks = 0;
+  long stage_bytes = 0;
+  if (gp->s.chunked && !gp->s.split_rows && gp->s.stage_avail > 0) {
+    Emitter dry(g, *gp);
+    dry.run("FSK");
+    long per_chunk = 0;
+    for (const ExtTensor& e : gp->ext_in)
+      if (e.kind == KIND_FULL && dry.pass_loads[e.node] >= 2) {
+        gp->staged_inputs.push_back(e.node);
+        per_chunk += (long)gp->s.NVLC * gp->s.L * gp->s.V * dtype_size(e.dtype);
+      }
+    if (per_chunk > 0) gp->s.stage_chunks = (int)std::min<long>(gp->s.CT, gp->s.stage_avail / per_chunk);
+    if (gp->s.stage_chunks <= 0) gp->staged_inputs.clear(), gp->s.stage_chunks = 0;
+    stage_bytes = per_chunk * gp->s.stage_chunks;
+  }
   // first pass with a placeholder name to hash the structure, second pass with the real name
   std::string text;
   {
@@ -840,6 +1025,8 @@ fs_status generate_kernel(const Graph& g, GroupPlan* gp, int /*group_index*/) {
   e.run(nm);
   gp->kernel_name = nm;
   gp->source = e.os.str();
+  // staged per-column operands that were added to each other share one LDS slot
+  gp->s.lds_bytes = gp->s.lds_planned - (gp->s.stage_rowv ? (int)e.combs.size() * gp->s.NVL * gp->s.L * gp->s.V * 4 : 0) + (int)stage_bytes;
   return FS_OK;
 }
 

@@ -190,6 +190,19 @@ FS_DEV void fs_store_row(const float (&src)[NVL * V], void* base, long row_elem0
   for (int j = 0; j < NVL; ++j) fs_store_row_vec<DT, V, NVL, L, NV, RAGGED, NT>(src, base, row_elem0, lir, vbase, rok, j);
 }
 
+// One chunk of a row kept in LDS in the tensor's own dtype (a kernel that walks a row once per stage reads the
+// chunk from memory in the first stage only).  The lane's vector j sits at chunk-local vector j*L + lir: consecutive
+// lanes touch consecutive 16-byte pieces.  What is written is what fs_load_row delivered (fp32 values that came from
+// the dtype convert back to it exactly), clamped duplicates included, so a later read sees the very same registers.
+template <int DT, int V, int NVL, int L> FS_DEV void fs_stage_row_chunk(void* lds_chunk, const float (&src)[NVL * V], int lir) {
+#pragma unroll
+  for (int j = 0; j < NVL; ++j) fs_store_vec<DT, V>(&src[j * V], lds_chunk, (long)(j * L + lir) * V);
+}
+template <int DT, int V, int NVL, int L> FS_DEV void fs_load_row_chunk_lds(float (&dst)[NVL * V], const void* lds_chunk, int lir) {
+#pragma unroll
+  for (int j = 0; j < NVL; ++j) fs_load_vec<DT, V>(&dst[j * V], lds_chunk, (long)(j * L + lir) * V);
+}
+
 // Transposing store of the lane's slice of row `row` of a [R,C] value into a [C,R] tensor.
 template <int DT, int V, int NVL, int L, int NV, bool RAGGED>
 FS_DEV void fs_store_row_transposed(const float (&src)[NVL * V], void* base, long R, long row, int lir, int vbase, bool rok) {
@@ -219,15 +232,42 @@ template <int DT, int V, int L, int C, int WG> FS_DEV void fs_stage_rowvec(float
       float tmp[4];
       fs_load_vec<DT, 4>(tmp, src, chunk * 4);
       const int vi = chunk / Q, q = chunk % Q, j = vi / L, l = vi % L;
-      float* d = lds + ((j * Q + q) * L + l) * 4;
+      typedef float f4 __attribute__((ext_vector_type(4)));
+      f4 t4;
 #pragma unroll
-      for (int k = 0; k < 4; ++k) d[k] = tmp[k];
+      for (int k = 0; k < 4; ++k) t4[k] = tmp[k];
+      *reinterpret_cast<f4*>(lds + ((j * Q + q) * L + l) * 4) = t4;  // one 128-bit LDS store
     }
   } else {
     for (int i = (int)threadIdx.x; i < C; i += WG) {
       float tmp[1];
       fs_load_vec<DT, 1>(tmp, src, i);
       lds[i] = tmp[0];
+    }
+  }
+}
+// The same for the sum (or difference) of two per-column vectors: +-a +- b is formed once, here,
+// instead of once per element of every row.
+template <int DTA, int DTB, bool NEGA, bool NEGB, int V, int L, int C, int WG> FS_DEV void fs_stage_rowvec_sum(float* lds, const void* a, const void* b) {
+  if constexpr (V % 4 == 0) {
+    constexpr int Q = V / 4;
+    for (int chunk = (int)threadIdx.x; chunk < C / 4; chunk += WG) {
+      float ta[4], tb[4];
+      fs_load_vec<DTA, 4>(ta, a, chunk * 4);
+      fs_load_vec<DTB, 4>(tb, b, chunk * 4);
+      const int vi = chunk / Q, q = chunk % Q, j = vi / L, l = vi % L;
+      typedef float f4 __attribute__((ext_vector_type(4)));
+      f4 t4;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) t4[k] = (NEGA ? -ta[k] : ta[k]) + (NEGB ? -tb[k] : tb[k]);
+      *reinterpret_cast<f4*>(lds + ((j * Q + q) * L + l) * 4) = t4;
+    }
+  } else {
+    for (int i = (int)threadIdx.x; i < C; i += WG) {
+      float ta[1], tb[1];
+      fs_load_vec<DTA, 1>(ta, a, i);
+      fs_load_vec<DTB, 1>(tb, b, i);
+      lds[i] = (NEGA ? -ta[0] : ta[0]) + (NEGB ? -tb[0] : tb[0]);
     }
   }
 }
@@ -338,25 +378,37 @@ template <int CTRL> FS_DEV float fs_dpp(float v) {
   return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
 }
 
+// DPP permute that only writes the rows of 16 lanes selected by ROW_MASK; the others receive `old`.
+template <int CTRL, int ROW_MASK> FS_DEV float fs_dpp_rows(float old, float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, old), __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xf, false));
+}
+
 // All-reduce inside aligned segments of W lanes of a wavefront (W = 1,2,4,...,64).  Every
 // lane of a segment ends with the same bits.  Steps 1..8 are DPP lane permutes inside a row
 // of 16 lanes (quad_perm, row_half_mirror, row_mirror), fused into the arithmetic
-// instruction.  Across the four rows of a wavefront the row totals are read into scalar
-// registers (v_readlane) and folded there in a fixed order.  No LDS traffic.
+// instruction.  Across the four rows of a whole wavefront two row broadcasts (lane 15 of a row
+// into the next row, lane 31 into rows 2 and 3) leave the total in lane 63, which is read into a
+// scalar register: (r3 op r2) op (r1 op r0), 6 permuting instructions and one v_readlane.  Two
+// segments of 32 lanes read their row totals into scalar registers and fold them there.  No LDS
+// traffic.
 template <int KIND, int W> FS_DEV float fs_segment_allreduce(float v) {
   if constexpr (W >= 2) v = fs_red_op<KIND>(v, fs_dpp<0xB1>(v));   // quad_perm [1,0,3,2]
   if constexpr (W >= 4) v = fs_red_op<KIND>(v, fs_dpp<0x4E>(v));   // quad_perm [2,3,0,1]
   if constexpr (W >= 8) v = fs_red_op<KIND>(v, fs_dpp<0x141>(v));  // row_half_mirror
   if constexpr (W >= 16) v = fs_red_op<KIND>(v, fs_dpp<0x140>(v)); // row_mirror
-  if constexpr (W >= 32) {
+  if constexpr (W >= 64) {
+    const float idn = fs_red_identity<KIND>();                     // (what the rows left out by the mask combine with)
+    v = fs_red_op<KIND>(v, fs_dpp_rows<0x142, 0xa>(idn, v));       // row_bcast:15 -> rows 1 and 3
+    v = fs_red_op<KIND>(v, fs_dpp_rows<0x143, 0xc>(idn, v));       // row_bcast:31 -> rows 2 and 3
+    v = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
+  } else if constexpr (W >= 32) {
     const int b = __builtin_bit_cast(int, v);
     const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 0));
     const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 16));
     const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 32));
     const float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 48));
     const float lo = fs_red_op<KIND>(r0, r1), hi = fs_red_op<KIND>(r2, r3);
-    if constexpr (W >= 64) v = fs_red_op<KIND>(lo, hi);
-    else v = (__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u)) < 32u) ? lo : hi;
+    v = (__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u)) < 32u) ? lo : hi;
   }
   return v;
 }

@@ -418,9 +418,17 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
     loop_bytes += n_rowv * slot_bytes;
   }
   const int lds = total();
-  s.lds_bytes = lds;
+  s.lds_bytes = s.lds_planned = lds;
   if (lds > opt.lds_budget)
     FS_FAIL(FS_ERR_LDS_BUDGET, "group needs %d bytes of LDS, budget is %d", lds, opt.lds_budget);
+  // Rows walked in chunks: what is left of the workgroup's LDS may hold the head of the row in its input dtype
+  // (one 1024-lane workgroup per compute unit runs such a kernel, so it may take all a workgroup is allowed
+  // unless the caller set a budget); code generation decides which inputs are worth it.
+  s.stage_avail = 0;
+  if (chunked && !split_rows) {
+    const int cap = opt.lds_budget_given ? opt.lds_budget : device_limits().lds_per_workgroup;
+    s.stage_avail = std::max(0, cap - lds - 512);
+  }
 
   // grid-wide fold scratch
   gp->n_tickets = 0;

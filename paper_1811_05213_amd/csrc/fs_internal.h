@@ -97,7 +97,8 @@ struct Schedule {
   int n_iters = 0;  // ceil(R * CT / G): loop trips over the whole grid
   int grid = 0;     // workgroups (`blocks` of Section 4.1)
   bool ragged = false;  // some lane's vector index can fall beyond NV
-  int lds_bytes = 0;
+  int lds_bytes = 0;    // static LDS of the generated kernel
+  int lds_planned = 0;  // ... as planned before code generation (an upper bound of lds_bytes)
   int fan_in = 32;  // column-reduction tree fan-in
   int fold_piece = 0;  // columns that pass through the in-workgroup fold area at a time
   bool stage_rowv = false;  // [1,C] inputs are staged once per workgroup in LDS
@@ -124,6 +125,11 @@ struct Schedule {
   bool resident = false;
   int NVLC = 0, RESV = 0;
   bool ragged_chunks = false;
+  // ... and with the first `stage_chunks` chunks of every [R,C] input that more than one pass reads kept in LDS
+  // in the input's own dtype: written by the first pass that loads them, read back by the later ones, so the
+  // row crosses HBM once instead of once per stage (Section 5.1.1: values needed by several loops of the kernel
+  // are the ones shared memory is allocated for).  stage_avail: LDS bytes the planner leaves for it.
+  int stage_avail = 0, stage_chunks = 0;
   // Column reductions over rows too wide for one workgroup: CT column tiles, each folded by its own
   // RB = grid / CT workgroups (tile = block % CT).  Strides of one tile's scratch in the workspace:
   bool col_tiled = false;
@@ -141,6 +147,7 @@ struct GroupPlan {
   std::vector<ExtTensor> ext_in, ext_out;
   std::vector<int> row_reduces;  // REDUCE_ROW members that need a cross-lane exchange
   std::vector<int> col_reduces;  // REDUCE_COL members finished by the grid-wide fold
+  std::vector<int> staged_inputs; // chunked kernels: [R,C] inputs whose first stage_chunks chunks are kept in LDS (filled by generate_kernel)
   int max_batched_reduces = 0;   // largest number of row reductions sharing one exchange
   Schedule s;
   // workspace scratch (byte offsets inside the plan workspace)
@@ -156,6 +163,7 @@ struct GroupPlan {
 struct PlanOptions {
   uint32_t mode = FS_MODE_STITCHED;
   int lds_budget = 65536;
+  bool lds_budget_given = false;  // the caller set it: rows staged in LDS stay inside it too (else they may take what the device allows)
   fs_sched_hint hint = {0, 0, 0, 0};
   bool has_hint = false;
   // How much of a row longer than 32 elements per lane may stay in registers: 2 = up to 64 elements

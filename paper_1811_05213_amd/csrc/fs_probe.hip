@@ -18,6 +18,30 @@ __global__ void __launch_bounds__(256) fs_copy_probe_kernel(const fs_uint4* __re
   if (i < n_vec) __builtin_nontemporal_store(__builtin_nontemporal_load(&src[i]), &dst[i]);
 }
 
+// The same copy with U vectors in flight per lane and a chosen grid (workgroups loop with a grid stride
+// when there are fewer of them than tiles): the shapes a streaming kernel could take, for finding the
+// fastest plain copy of a given size on the device.  Indices beyond the end are clamped for the loads
+// (never predicated, so all U loads are issued back to back) and masked at the stores.
+template <int U> __global__ void __launch_bounds__(256) fs_copy_probe_shape_kernel(const fs_uint4* __restrict__ src, fs_uint4* __restrict__ dst, long n_vec) {
+  const long stride = (long)gridDim.x * 256;
+  for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < n_vec; i += stride * U) {
+    fs_uint4 t[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const long j = i + u * stride;
+      t[u] = __builtin_nontemporal_load(&src[j < n_vec ? j : n_vec - 1]);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const long j = i + u * stride;
+      if (j < n_vec) __builtin_nontemporal_store(t[u], &dst[j]);
+    }
+  }
+}
+
+// Nothing: the cost of a launch itself.
+__global__ void fs_empty_kernel() {}
+
 __global__ void __launch_bounds__(256) fs_zero_u32_kernel(unsigned int* p, long n) {
   const long i = (long)blockIdx.x * 256 + threadIdx.x;
   if (i < n) p[i] = 0u;
@@ -113,6 +137,29 @@ int launch_copy_probe(const void* src, void* dst, size_t bytes, hipStream_t stre
   const long blocks = (n_vec + 255) / 256;
   if (blocks > 0x7fffffffL) return (int)hipErrorInvalidValue;
   hipLaunchKernelGGL(fs_copy_probe_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, (const fs_uint4*)src, (fs_uint4*)dst, n_vec);
+  return (int)hipGetLastError();
+}
+
+int launch_copy_probe_shape(const void* src, void* dst, size_t bytes, int vectors_in_flight, int workgroups, hipStream_t stream) {
+  const long n_vec = (long)(bytes / 16);
+  if (n_vec == 0) return 0;
+  const int U = vectors_in_flight;
+  if (U != 1 && U != 2 && U != 4 && U != 8) return (int)hipErrorInvalidValue;
+  long blocks = (n_vec + 256L * U - 1) / (256L * U);  // one trip per workgroup
+  if (workgroups > 0 && workgroups < blocks) blocks = workgroups;
+  if (blocks > 0x7fffffffL) return (int)hipErrorInvalidValue;
+  const dim3 grid((unsigned)blocks), wg(256);
+  switch (U) {
+    case 1: hipLaunchKernelGGL(fs_copy_probe_shape_kernel<1>, grid, wg, 0, stream, (const fs_uint4*)src, (fs_uint4*)dst, n_vec); break;
+    case 2: hipLaunchKernelGGL(fs_copy_probe_shape_kernel<2>, grid, wg, 0, stream, (const fs_uint4*)src, (fs_uint4*)dst, n_vec); break;
+    case 4: hipLaunchKernelGGL(fs_copy_probe_shape_kernel<4>, grid, wg, 0, stream, (const fs_uint4*)src, (fs_uint4*)dst, n_vec); break;
+    default: hipLaunchKernelGGL(fs_copy_probe_shape_kernel<8>, grid, wg, 0, stream, (const fs_uint4*)src, (fs_uint4*)dst, n_vec); break;
+  }
+  return (int)hipGetLastError();
+}
+
+int launch_empty(hipStream_t stream) {
+  hipLaunchKernelGGL(fs_empty_kernel, dim3(1), dim3(64), 0, stream);
   return (int)hipGetLastError();
 }
 

@@ -18,6 +18,8 @@
 namespace fs {
 int launch_copy_probe(const void* src, void* dst, size_t bytes, hipStream_t stream);
 int launch_zero_u32(void* p, size_t count, hipStream_t stream);
+int launch_copy_probe_shape(const void* src, void* dst, size_t bytes, int vectors_in_flight, int workgroups, hipStream_t stream);
+int launch_empty(hipStream_t stream);
 size_t static_scratch_bytes();
 int static_scratch_resolve(int device, void** out);
 void* static_scratch_lookup(int device);
@@ -195,6 +197,7 @@ fs_status fs_plan_create(const fs_graph_desc* desc, fs_plan** out_plan) {
   plan->opt.layered = (desc->mode & FS_MODE_LAYERED) != 0;
   const bool use_library = !(desc->mode & FS_MODE_NO_PERFLIB) && !desc->hint && perflib_size() > 0;
   plan->opt.lds_budget = desc->lds_budget_bytes > 0 ? desc->lds_budget_bytes : std::min(65536, device_limits().lds_per_workgroup);
+  plan->opt.lds_budget_given = desc->lds_budget_bytes > 0;
   if (desc->hint) {
     plan->opt.hint = *desc->hint;
     plan->opt.has_hint = true;
@@ -854,6 +857,22 @@ fs_status fs_copy_probe(const void* src, void* dst, size_t bytes, void* hip_stre
     FS_FAIL(FS_ERR_INVALID_ARG, "copy probe needs 16-byte aligned pointers and a multiple of 16 bytes");
   const int e = launch_copy_probe(src, dst, bytes, (hipStream_t)hip_stream);
   if (e != 0) FS_FAIL(FS_ERR_HIP, "copy probe launch: %s", hipGetErrorString((hipError_t)e));
+  return FS_OK;
+}
+
+fs_status fs_copy_probe_shape(const void* src, void* dst, size_t bytes, int32_t vectors_in_flight, int32_t workgroups, void* hip_stream) {
+  if (!src || !dst || (bytes & 15) || ((uintptr_t)src & 15) || ((uintptr_t)dst & 15))
+    FS_FAIL(FS_ERR_INVALID_ARG, "copy probe needs 16-byte aligned pointers and a multiple of 16 bytes");
+  if (workgroups < 0 || (vectors_in_flight != 1 && vectors_in_flight != 2 && vectors_in_flight != 4 && vectors_in_flight != 8))
+    FS_FAIL(FS_ERR_INVALID_ARG, "copy probe shape: vectors_in_flight must be 1, 2, 4 or 8 and workgroups >= 0");
+  const int e = launch_copy_probe_shape(src, dst, bytes, vectors_in_flight, workgroups, (hipStream_t)hip_stream);
+  if (e != 0) FS_FAIL(FS_ERR_HIP, "copy probe launch: %s", hipGetErrorString((hipError_t)e));
+  return FS_OK;
+}
+
+fs_status fs_launch_probe(void* hip_stream) {
+  const int e = launch_empty((hipStream_t)hip_stream);
+  if (e != 0) FS_FAIL(FS_ERR_HIP, "empty kernel launch: %s", hipGetErrorString((hipError_t)e));
   return FS_OK;
 }
 

@@ -501,7 +501,7 @@ def test_survey_patterns_are_single_kernels():
     # every pattern of the shape survey (softmax variants, norms, optimizer update, column sums, transposes, backward passes)
     # from 64 to 131072 columns plans as ONE stitched kernel (the softmax over 8 rows of a million columns is the one
     # exception: cut into three kernels that each fill the device)
-    from paper_1811_05213_amd import survey
+    from workloads import patterns as survey
     for name, g, rows, cols in survey.cases():
         p = fs.Plan(g)
         if rows <= 32 and cols >= (1 << 20) and "softmax" in name:

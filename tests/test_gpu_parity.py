@@ -324,7 +324,8 @@ def test_looping_workgroups_with_operands_staged_once():
     # row-reduction groups with per-column operands whose workgroups loop and stage the operands in LDS once, before the loop:
     # row counts that are no multiple of the rows per trip (masked rows in the last trip), one-wavefront rows (16 rows per
     # trip), rows across 4 wavefronts, exact-fit lane counts (768 bf16 columns: 32 lanes x 3 vectors), a light operand
-    from paper_1811_05213_amd import Plan, survey
+    from paper_1811_05213_amd import Plan
+    from workloads import patterns as survey
     for rows, cols in ((16391, 1024), (8197, 4096), (32771, 768)):
         g = layernorm_gelu_graph(rows, cols)
         p = Plan(g)
@@ -468,6 +469,41 @@ def test_run_argument_errors():
     lim = fs.device_limits()
     assert lim["from_device"] and lim["compute_units"] >= 1 and lim["lds_bytes_per_workgroup"] >= 65536
     plan.destroy()
+
+
+def test_plans_replay_correctly_from_a_hip_graph():
+    # fs_plan_run enqueues kernel launches only (no memset node, no allocation once the plan is loaded), so a caller may
+    # capture it.  Every replay must reproduce the eager result bit for bit, with eager work and synchronisation in
+    # between, also for plans with ticketed folds (the tickets return to zero inside each replay) and several kernels.
+    import torch
+    for cfg, rows in ((4, 3000), (5, None), (6, 700)):
+        g, ins, name = workload(cfg, rows)
+        plan = fs.Plan(g)
+        r = DeviceRun(plan)
+        r.set_inputs(ins)
+        plan.load()
+        r.launch()
+        eager = [t.clone() for t in r.outputs]
+        torch.cuda.synchronize()
+        check_all(g, r.results(), Reference(g, ins), name + " eager")
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            r.launch()
+        for rep in range(4):
+            for t in r.outputs:
+                t.zero_()
+            r2 = DeviceRun(plan)          # eager work of the same plan on other buffers between the replays
+            r2.set_inputs(ins)
+            r2.launch()
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            for k, (a, b) in enumerate(zip(r.outputs, eager)):
+                assert torch.equal(a, b), f"{name}: replay {rep} output {k} differs from the eager run"
+            for k, (a, b) in enumerate(zip(r2.outputs, eager)):
+                assert torch.equal(a, b), f"{name}: eager run between replays, output {k}"
+        del graph
+        plan.destroy()
 
 
 def test_transposes_through_lds_tile_and_direct():
@@ -696,10 +732,16 @@ SWEEP_SHAPES = [(40, 20000), (3000, 5000), (7, 70001), (1200, 4096), (2, 2), (1,
                 (4096, 260), (100, 33000), (65, 63), (1000, 1000), (12, 131080), (20000, 130), (3, 3), (8192, 512), (300, 300), (17, 9000)]
 
 
-@pytest.mark.parametrize("first", range(200, int(os.environ.get("FS_SWEEP_END", "240")), 20))
+def test_random_graph_whose_row_sums_cancel():
+    # tanh of a row sum of 5000 terms that cancel to 0.1, next to rows that sum to +-45: uncertain by ~1e-5 for any fp32
+    # sum; the accumulation companion flags such rows (about 3 % here) instead of a tolerance that is loose everywhere
+    assert _random_graph_case(261, 3000, 5000, 25) > 0
+
+
+@pytest.mark.parametrize("first", range(200, int(os.environ.get("FS_SWEEP_END", "220")), 20))
 def test_random_graph_sweep(first):
-    # seeds 200..239 (FS_SWEEP_END widens the range: 440 takes ~10x as long) over twenty shapes: tiny, ragged, wide, tall,
-    # beyond one workgroup's registers; stops at the first failure
+    # seeds 200..219 (FS_SWEEP_END widens the range: 440 is twelve times the work, ~13 minutes) over twenty shapes: tiny,
+    # ragged, wide, tall, beyond one workgroup's registers; stops at the first failure
     for seed in range(first, first + 20):
         rows, cols = SWEEP_SHAPES[seed % len(SWEEP_SHAPES)]
         print(f"seed {seed} {rows}x{cols}", flush=True)

@@ -1,22 +1,12 @@
-"""Shape survey: common fused patterns over a range of shapes, each as ONE stitched plan on one MI355X.
+"""Common fused patterns beyond the five benchmark workloads, as DAG builders (no arithmetic here: op names and shapes).
 
-    python -m paper_1811_05213_amd.survey [--steps 30] [--filter softmax]
-
-For every case it prints the schedule the planner chose (launches, lanes per row, elements per lane,
-workgroup size, grid, LDS bytes) and the measured time per launch, effective HBM GB/s (minimal bytes:
-every plan input read once, every plan output written once) and the fraction of the 8 TB/s peak.
-Buffers rotate through >= 2 GiB so the last-level cache cannot serve them.  Inputs are seeded
-synthetic normals; this is a timing tool (parity lives in tests/).
+softmax variants, normalisations, an optimizer update, column sums, a bias gradient, transposes and backward passes:
+the shapes `bench.py --survey` times and the planner tests walk through.  `cases()` lists (name, graph, rows, cols).
 """
 from __future__ import annotations
 
-import argparse
-import sys
-
-import numpy as np
-
-from workloads import (Graph, f32_to_bf16_bits, layernorm_gelu_graph, layernorm_grad_graph, min_hbm_bytes, softmax_graph,
-                       softmax_grad_graph)
+from .configs import layernorm_gelu_graph, layernorm_grad_graph, softmax_graph, softmax_grad_graph
+from .graph import Graph
 
 
 def _f32(g, x, dt):
@@ -129,42 +119,7 @@ def cases():
     for r, c in [(4, 1 << 22), (1, 1 << 26), (96, 1 << 19)]:
         out.append(("row L2 norm + max f32", row_norms(r, c), r, c))
     out.append(("softmax f32", softmax_graph(8, 1 << 20), 8, 1 << 20))
+    # rows beyond one workgroup's registers: the head of the row stays in LDS between the stages
+    out.append(("softmax f32", softmax_graph(2048, 100000), 2048, 100000))
+    out.append(("layernorm+gelu bf16", layernorm_gelu_graph(4096, 65536), 4096, 65536))
     return out
-
-
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--filter", default="")
-    args = ap.parse_args()
-    import torch
-    if not torch.cuda.is_available():
-        print("survey: no GPU visible", file=sys.stderr)
-        sys.exit(3)
-    from bench import build_sets, time_plan
-    from . import Plan
-    rng = np.random.default_rng(181105213)
-    print("%-24s %9s x %-9s %2s  %5s %3s %5s %7s %6s | %9s %7s %6s" % ("pattern", "rows", "cols", "k", "L", "E", "WG", "grid", "LDS", "us", "GB/s", "% peak"))
-    for name, g, r, c in cases():
-        if args.filter and args.filter not in name:
-            continue
-        ins = []
-        for i in g.input_ids():
-            n = g.nodes[i]
-            a = rng.standard_normal((n.rows, n.cols), dtype=np.float32)
-            ins.append(f32_to_bf16_bits(a) if n.dtype == "bf16" else a)
-        plan = Plan(g)
-        gi = plan.group_info(0)
-        runs = build_sets(plan, g, ins, "cuda:0", 2 << 30)
-        ms, _ = time_plan(runs, args.steps, 5, min_warm_ms=50.0)  # steady clocks first
-        gbs = min_hbm_bytes(g) / ms / 1e6
-        print("%-24s %9d x %-9d %2d  %5d %3d %5d %7d %6d | %9.1f %7.0f %6.1f" % (
-            name, r, c, plan.stats()["num_launches"], gi["lanes_per_row"], gi["elems_per_lane"], gi["wg_threads"], gi["grid"],
-            gi["lds_bytes"], ms * 1e3, gbs, gbs / 80.0), flush=True)
-        del runs
-        plan.destroy()
-        torch.cuda.empty_cache()
-
-
-if __name__ == "__main__":
-    main()
