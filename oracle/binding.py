@@ -17,12 +17,13 @@ _OPC = {
     "input": 0, "const": 1, "neg": 2, "abs": 3, "exp": 4, "log": 5, "tanh": 6, "sigmoid": 7, "sqrt": 8,
     "rsqrt": 9, "rcp": 10, "gelu_tanh": 11, "convert": 12, "add": 13, "sub": 14, "mul": 15, "div": 16,
     "max": 17, "min": 18, "cmp": 19, "select": 20, "bcast_rowvec": 21, "bcast_colvec": 22, "transpose": 23,
-    "reduce_row": 24, "reduce_col": 25,
+    "reduce_row": 24, "reduce_col": 25, "reshape": 26, "bitcast": 27, "concat": 28,
 }
 _DT = {"f32": 0, "bf16": 1, "u8": 2}
 _NP = {"f32": np.float32, "bf16": np.uint16, "u8": np.uint8}
 _CMP = {"gt": 0, "ge": 1, "lt": 2, "le": 3, "eq": 4, "ne": 5}
 _RED = {"sum": 0, "max": 1, "min": 2, "mean": 3}
+_AXIS = {"rows": 0, "cols": 1}
 
 
 class _Node(ctypes.Structure):
@@ -88,7 +89,7 @@ def _encode(graph):
         c.num_in = len(nd.ins)
         for k, o in enumerate(nd.ins):
             c.inp[k] = o
-        c.attr_i = _CMP[nd.attr] if nd.op == "cmp" else _RED[nd.attr] if nd.op.startswith("reduce") else 0
+        c.attr_i = _CMP[nd.attr] if nd.op == "cmp" else _RED[nd.attr] if nd.op.startswith("reduce") else _AXIS[nd.attr] if nd.op == "concat" else 0
         c.attr_f = nd.value
     outs = (ctypes.c_int32 * max(1, len(graph.outputs)))(*graph.outputs)
     g = _Graph(n, nodes, len(graph.outputs), outs)

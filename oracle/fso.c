@@ -69,6 +69,8 @@ static int arity(int op) {
   if (op >= FSO_ADD && op <= FSO_CMP) return 2;
   if (op == FSO_SELECT) return 3;
   if (op >= FSO_BCAST_ROWVEC && op <= FSO_REDUCE_COL) return 1;
+  if (op == FSO_RESHAPE || op == FSO_BITCAST) return 1;
+  if (op == FSO_CONCAT) return 2;
   return -1;
 }
 
@@ -168,6 +170,15 @@ int fso_run(const fso_graph* g, const void* const* host_in, void* const* host_ou
         case FSO_TRANSPOSE: if (a->rows != n->cols || a->cols != n->rows) return -2; break;
         case FSO_REDUCE_ROW: if (a->rows != n->rows || n->cols != 1) return -2; break;
         case FSO_REDUCE_COL: if (a->cols != n->cols || n->rows != 1) return -2; break;
+        case FSO_RESHAPE:
+        case FSO_BITCAST: if ((long)a->rows * a->cols != (long)n->rows * n->cols) return -2; break;
+        case FSO_CONCAT: {
+          const fso_node* b = &g->nodes[n->in[1]];
+          if (n->attr_i == 1) { if (a->rows != n->rows || b->rows != n->rows || a->cols + b->cols != n->cols) return -2; }
+          else if (n->attr_i == 0) { if (a->cols != n->cols || b->cols != n->cols || a->rows + b->rows != n->rows) return -2; }
+          else return -2;
+          break;
+        }
         default:
           for (k = 0; k < n->num_in; ++k) {
             const fso_node* b = &g->nodes[n->in[k]];
@@ -250,6 +261,24 @@ int fso_run(const fso_graph* g, const void* const* host_in, void* const* host_ou
 #pragma omp parallel for private(j)
         for (i = 0; i < R; ++i)
           for (j = 0; j < C; ++j) out[i * C + j] = round_to(dt, a[j * R + i]);
+        break;
+      case FSO_RESHAPE:
+      case FSO_BITCAST: /* the same row-major element sequence under another [rows, cols] split */
+#pragma omp parallel for
+        for (i = 0; i < E; ++i) out[i] = round_to(dt, a[i]);
+        break;
+      case FSO_CONCAT:
+        if (n->attr_i == 1) { /* along columns: row i is in0's row i followed by in1's row i */
+          const long Ca = g->nodes[n->in[0]].cols, Cb = g->nodes[n->in[1]].cols;
+#pragma omp parallel for private(j)
+          for (i = 0; i < R; ++i)
+            for (j = 0; j < C; ++j) out[i * C + j] = round_to(dt, j < Ca ? a[i * Ca + j] : b[i * Cb + (j - Ca)]);
+        } else { /* along rows: in0's rows, then in1's */
+          const long Ra = g->nodes[n->in[0]].rows;
+#pragma omp parallel for private(j)
+          for (i = 0; i < R; ++i)
+            for (j = 0; j < C; ++j) out[i * C + j] = round_to(dt, i < Ra ? a[i * C + j] : b[(i - Ra) * C + j]);
+        }
         break;
       case FSO_REDUCE_ROW: { /* operand [R, Ca] -> [R,1] */
         const long Ca = g->nodes[n->in[0]].cols;

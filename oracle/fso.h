@@ -34,7 +34,14 @@ enum {
   FSO_ADD = 13, FSO_SUB = 14, FSO_MUL = 15, FSO_DIV = 16, FSO_MAX = 17, FSO_MIN = 18,
   FSO_CMP = 19, FSO_SELECT = 20,
   FSO_BCAST_ROWVEC = 21, FSO_BCAST_COLVEC = 22, FSO_TRANSPOSE = 23,
-  FSO_REDUCE_ROW = 24, FSO_REDUCE_COL = 25
+  FSO_REDUCE_ROW = 24, FSO_REDUCE_COL = 25,
+  /* shape modulation beyond transpose (Section 2.1 names Reshape and Bitcast; Section 6.3 Concat).  A tensor of any
+   * rank is presented to the plan as [rows, cols] = [product of its leading dims, product of its trailing dims];
+   * RESHAPE re-splits the same row-major element sequence: out.flat[i] = in.flat[i].  BITCAST is the same map
+   * (in the source framework a Bitcast is a Reshape known not to move data; with dense row-major tensors every
+   * Reshape is).  CONCAT joins two tensors along columns (attr_i = 1: out[i, :] = in0[i, :] ++ in1[i, :]) or
+   * along rows (attr_i = 0: in0's rows, then in1's). */
+  FSO_RESHAPE = 26, FSO_BITCAST = 27, FSO_CONCAT = 28
 };
 enum { FSO_GT = 0, FSO_GE = 1, FSO_LT = 2, FSO_LE = 3, FSO_EQ = 4, FSO_NE = 5 };
 enum { FSO_SUM = 0, FSO_MAX_ = 1, FSO_MIN_ = 2, FSO_MEAN = 3 };

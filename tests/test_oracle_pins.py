@@ -523,3 +523,78 @@ def test_oracle_reproduces_its_stored_small_cases():
     want = np.array([v / sum(e) for v in e], dtype=np.float64)
     got = np.array([int(h, 16) for h in stored["softmax_2x4"]["outputs_hex"][0][:4]], dtype=np.uint32).view(np.float32)
     np.testing.assert_allclose(got, want, rtol=2e-7)
+
+
+# ------------------------------------------------------------------ reshape / bitcast / concat
+def test_reshape_and_bitcast_keep_the_row_major_sequence():
+    x = RNG.standard_normal((6, 20)).astype(np.float32)
+    g = Graph()
+    i = g.input(6, 20)
+    a = g.reshape(i, 15, 8)
+    b = g.reshape(a, 6, 20)                  # reshape o reshape^-1 = identity, bit for bit
+    c = g.reshape(i, 1, 120, op="bitcast")
+    d = g.view_nd(i, (2, 3, 4, 5), 3)        # [2,3,4,5] presented as [24, 5]
+    e = g.view_nd(d, (2, 3, 4, 5), 1)        # ... and as [2, 60]
+    g.set_outputs([a, b, c, d, e, g.unary("neg", a)])
+    ra, rb, rc, rd, re_, rn = run1(g, [x])
+    np.testing.assert_array_equal(rb.view(np.uint32), x.view(np.uint32))
+    for got, shape in ((ra, (15, 8)), (rc, (1, 120)), (rd, (24, 5)), (re_, (2, 60))):
+        assert got.shape == shape
+        # brute force over flat indices: element k of the output is element k of the input
+        for k in range(120):
+            assert got[k // shape[1], k % shape[1]] == x[k // 20, k % 20]
+    np.testing.assert_array_equal(rn, -x.reshape(15, 8))
+    # an N-D softmax: [2,3,4,5] normalised over its last dim is the 2-D softmax of the [24,5] view
+    g2 = Graph()
+    j = g2.input(6, 20)
+    v = g2.view_nd(j, (2, 3, 4, 5), 3)
+    m = g2.reduce_row("max", v)
+    ex = g2.unary("exp", g2.binary("sub", v, g2.bcast_colvec(m, 5)))
+    y = g2.binary("div", ex, g2.bcast_colvec(g2.reduce_row("sum", ex), 5))
+    g2.set_outputs([g2.reshape(y, 6, 20)])
+    got = run1(g2, [x])[0]
+    want = torch.softmax(torch.from_numpy(x).double().reshape(2, 3, 4, 5), dim=-1).reshape(6, 20).numpy()
+    np.testing.assert_allclose(got, want, rtol=3e-7)
+    # shape rule: the element count must not change
+    g3 = Graph()
+    k = g3.input(4, 4)
+    r = g3.reshape(k, 2, 8)
+    g3.nodes[r].cols = 7
+    g3.set_outputs([r])
+    with pytest.raises(RuntimeError):
+        run1(g3, [np.zeros((4, 4), np.float32)])
+
+
+def test_concat_index_rules_by_brute_force():
+    a = RNG.standard_normal((5, 3)).astype(np.float32)
+    b = RNG.standard_normal((5, 4)).astype(np.float32)
+    c = RNG.standard_normal((2, 3)).astype(np.float32)
+    g = Graph()
+    ia, ib, ic = g.input(5, 3), g.input(5, 4), g.input(2, 3)
+    cc = g.concat(ia, ib, "cols")
+    cr = g.concat(ia, ic, "rows")
+    g.set_outputs([cc, cr, g.reduce_row("sum", cc)])
+    oc, orr, rs = run1(g, [a, b, c])
+    assert oc.shape == (5, 7) and orr.shape == (7, 3)
+    for i in range(5):
+        for j in range(7):
+            assert oc[i, j] == (a[i, j] if j < 3 else b[i, j - 3])
+    for i in range(7):
+        for j in range(3):
+            assert orr[i, j] == (a[i, j] if i < 5 else c[i - 5, j])
+    want = np.array([[math.fsum(map(float, a[i])) + math.fsum(map(float, b[i]))] for i in range(5)])
+    np.testing.assert_allclose(rs, want, rtol=2e-7, atol=1e-7)
+    # bf16 payloads are copied bit for bit
+    g2 = Graph()
+    ja, jb = g2.input(1, 2, "bf16"), g2.input(1, 3, "bf16")
+    g2.set_outputs([g2.concat(ja, jb)])
+    got = run1(g2, [np.array([[0x3F80, 0x8000]], np.uint16), np.array([[0x7F7F, 0x0001, 0xC000]], np.uint16)])[0]
+    assert got.tolist() == [[0x3F80, 0x8000, 0x7F7F, 0x0001, 0xC000]]
+    # shapes that do not add up are refused
+    g3 = Graph()
+    ka, kb = g3.input(2, 2), g3.input(2, 3)
+    n = g3.concat(ka, kb)
+    g3.nodes[n].cols = 6
+    g3.set_outputs([n])
+    with pytest.raises(RuntimeError):
+        run1(g3, [np.zeros((2, 2), np.float32), np.zeros((2, 3), np.float32)])

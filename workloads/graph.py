@@ -5,7 +5,9 @@ holds no arithmetic of the method: only op *names*, shapes, dtypes and operand i
 Each binding maps the names onto the enum values of its own C header.
 
 The op vocabulary is the paper's problem statement (Section 2.1): elementwise ops,
-shape modulation (broadcasts, transpose) and reductions (sum/max/min/mean, Section 1).
+shape modulation (broadcasts, transpose, reshape / bitcast; concat, Section 6.3) and reductions
+(sum/max/min/mean, Section 1).  Tensors of any rank enter as [rows, cols] = [product of the leading
+dims, product of the trailing dims] of their row-major layout; `reshape` moves that split.
 """
 from __future__ import annotations
 
@@ -18,9 +20,9 @@ CMP_KINDS = ("gt", "ge", "lt", "le", "eq", "ne")
 REDUCE_KINDS = ("sum", "max", "min", "mean")
 DTYPES = ("f32", "bf16", "u8")
 ALL_OPS = ("input", "const") + UNARY + BINARY + ("cmp", "select", "bcast_rowvec", "bcast_colvec",
-                                                  "transpose", "reduce_row", "reduce_col")
+                                                  "transpose", "reduce_row", "reduce_col", "reshape", "bitcast", "concat")
 # nodes that are never materialised and never count as a kernel launch
-FREE_OPS = ("input", "const", "bcast_rowvec", "bcast_colvec")
+FREE_OPS = ("input", "const", "bcast_rowvec", "bcast_colvec", "reshape", "bitcast")
 
 
 @dataclass
@@ -84,6 +86,31 @@ class Graph:
     def transpose(self, a: int, name: str = "") -> int:
         n = self.nodes[a]
         return self._add(Node("transpose", n.dtype, n.cols, n.rows, (a,), name=name))
+
+    def reshape(self, a: int, rows: int, cols: int, name: str = "", op: str = "reshape") -> int:
+        """The same row-major element sequence as [rows, cols] (op "bitcast": the same map under its other name)."""
+        n = self.nodes[a]
+        assert op in ("reshape", "bitcast") and rows * cols == n.rows * n.cols, (op, rows, cols, n.rows, n.cols)
+        return self._add(Node(op, n.dtype, rows, cols, (a,), name=name))
+
+    def view_nd(self, a: int, shape: Sequence[int], split: int, name: str = "") -> int:
+        """Tensor `a` taken as an N-D tensor of `shape` and presented as [prod(shape[:split]), prod(shape[split:])]."""
+        rows = 1
+        for d in shape[:split]:
+            rows *= d
+        cols = 1
+        for d in shape[split:]:
+            cols *= d
+        return self.reshape(a, rows, cols, name=name)
+
+    def concat(self, a: int, b: int, axis: str = "cols", name: str = "") -> int:
+        na, nb = self.nodes[a], self.nodes[b]
+        assert axis in ("rows", "cols") and na.dtype == nb.dtype
+        if axis == "cols":
+            assert na.rows == nb.rows
+            return self._add(Node("concat", na.dtype, na.rows, na.cols + nb.cols, (a, b), attr="cols", name=name))
+        assert na.cols == nb.cols
+        return self._add(Node("concat", na.dtype, na.rows + nb.rows, na.cols, (a, b), attr="rows", name=name))
 
     def reduce_row(self, kind: str, a: int, dtype: str | None = None, name: str = "") -> int:
         assert kind in REDUCE_KINDS, kind
