@@ -68,9 +68,17 @@ typedef enum { FS_F32 = 0, FS_BF16 = 1, FS_U8 = 2 } fs_dtype;
 
 /*
  * Opcodes.  The four op classes of the paper's problem statement (Section 2.1):
- * elementwise, shape modulation (here: the two broadcasts and Transpose - with
- * 2-D row-major tensors Reshape/Bitcast have nothing to do), Reduction
- * (sum/max/min/mean, Section 1) and - deliberately absent - BatchMatMul.
+ * elementwise, shape modulation (the two broadcasts, Transpose, Reshape / Bitcast; Concat,
+ * which Section 6.3 names), Reduction (sum/max/min/mean, Section 1) and - deliberately
+ * absent - BatchMatMul.
+ *
+ * Tensors of any rank enter the plan as [rows, cols] = [product of the leading dims, product
+ * of the trailing dims] of their dense row-major layout; FS_RESHAPE moves that split (or
+ * regroups the element sequence in any other way that keeps the element count).  In the
+ * schedule terms of Section 4.1 / Table 1 this is the split_dim of a Row schedule: a Reshape
+ * that keeps whole rows of the consumer inside rows of the producer passes a schedule
+ * through; any other one separates two fused computations.  Here every Reshape / Bitcast is a
+ * zero-cost view at a boundary between kernels: producer and consumer address the same bytes.
  */
 typedef enum {
   FS_INPUT = 0,  /* external tensor; the k-th FS_INPUT node (in id order) is inputs[k] of fs_plan_run */
@@ -105,11 +113,26 @@ typedef enum {
   /* reductions; attr_i is an fs_reduce_kind */
   FS_REDUCE_ROW = 24,   /* in0 [R,C] -> out [R,1], reduces over the columns of each row */
   FS_REDUCE_COL = 25,   /* in0 [R,C] -> out [1,C], reduces over the rows of each column */
-  FS_NUM_OPCODES = 26
+  /* more shape modulation.  RESHAPE / BITCAST: out.flat[i] = in0.flat[i], same dtype, rows*cols unchanged;
+   * never materialised and never a launch: the result is a view of in0's buffer (in0: an FS_INPUT, a compute
+   * node or another view; not a broadcast or constant).  The two names denote the same map: in the source
+   * framework a Bitcast is a Reshape known not to move data, and with dense row-major tensors every Reshape is.
+   * As a plan output a view makes its producer write straight into the caller's buffer; a view of an FS_INPUT
+   * cannot be a plan output (nothing would be computed), nor can two members of one view family both be. */
+  FS_RESHAPE = 26,
+  FS_BITCAST = 27,
+  /* CONCAT: attr_i is an fs_concat_axis; in0 and in1 have the result's dtype.  FS_CONCAT_COLS: in0 [R,C0],
+   * in1 [R,C1] -> out [R,C0+C1], row i = in0's row i followed by in1's; FS_CONCAT_ROWS: in0 [R0,C], in1 [R1,C]
+   * -> out [R0+R1,C].  The operands are read from memory by the kernel that holds the concat (a consumer
+   * fused with it reads two tensors as one row and nothing is copied); an operand computed by the same group
+   * is materialised first. */
+  FS_CONCAT = 28,
+  FS_NUM_OPCODES = 29
 } fs_opcode;
 
 typedef enum { FS_CMP_GT = 0, FS_CMP_GE = 1, FS_CMP_LT = 2, FS_CMP_LE = 3, FS_CMP_EQ = 4, FS_CMP_NE = 5 } fs_cmp;
 typedef enum { FS_RED_SUM = 0, FS_RED_MAX = 1, FS_RED_MIN = 2, FS_RED_MEAN = 3 } fs_reduce_kind;
+typedef enum { FS_CONCAT_ROWS = 0, FS_CONCAT_COLS = 1 } fs_concat_axis;
 
 /*
  * One node of the DAG.  The node id is its index in fs_graph_desc.nodes, and the
@@ -125,7 +148,7 @@ typedef struct {
   int32_t cols;
   int32_t num_in; /* 0..3 */
   int32_t in[3];  /* operand node ids; unused entries ignored */
-  int32_t attr_i; /* fs_cmp for FS_CMP, fs_reduce_kind for FS_REDUCE_*, else 0 */
+  int32_t attr_i; /* fs_cmp for FS_CMP, fs_reduce_kind for FS_REDUCE_*, fs_concat_axis for FS_CONCAT, else 0 */
   float attr_f;   /* value of FS_CONST, else 0 */
 } fs_node;
 
@@ -166,7 +189,8 @@ typedef struct {
   int32_t num_nodes;
   const fs_node* nodes;          /* host; copied by fs_plan_create */
   int32_t num_outputs;
-  const int32_t* outputs;        /* host; node ids that are plan outputs (not INPUT/CONST/BCAST_*), distinct */
+  const int32_t* outputs;        /* host; node ids that are plan outputs (not INPUT/CONST/BCAST_*; a RESHAPE/BITCAST only
+                                    as a view of a computed value), distinct */
   const int32_t* group_of_node;  /* host; NULL => the library groups greedily.  Else one group id >= 0 per
                                     node (ignored for INPUT/CONST/BCAST_* nodes, which are inlined into
                                     each consumer): the caller's fusion plan.  Ignored in FS_MODE_UNFUSED. */

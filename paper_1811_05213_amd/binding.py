@@ -28,11 +28,12 @@ OPCODE = {
     "input": 0, "const": 1, "neg": 2, "abs": 3, "exp": 4, "log": 5, "tanh": 6, "sigmoid": 7, "sqrt": 8,
     "rsqrt": 9, "rcp": 10, "gelu_tanh": 11, "convert": 12, "add": 13, "sub": 14, "mul": 15, "div": 16,
     "max": 17, "min": 18, "cmp": 19, "select": 20, "bcast_rowvec": 21, "bcast_colvec": 22, "transpose": 23,
-    "reduce_row": 24, "reduce_col": 25,
+    "reduce_row": 24, "reduce_col": 25, "reshape": 26, "bitcast": 27, "concat": 28,
 }
 DTYPE = {"f32": 0, "bf16": 1, "u8": 2}
 CMP = {"gt": 0, "ge": 1, "lt": 2, "le": 3, "eq": 4, "ne": 5}
 RED = {"sum": 0, "max": 1, "min": 2, "mean": 3}
+AXIS = {"rows": 0, "cols": 1}
 
 
 class fs_node(ctypes.Structure):
@@ -141,7 +142,7 @@ def encode_graph(graph):
         c.num_in = len(nd.ins)
         for k, o in enumerate(nd.ins):
             c.inp[k] = o
-        c.attr_i = CMP[nd.attr] if nd.op == "cmp" else RED[nd.attr] if nd.op.startswith("reduce") else 0
+        c.attr_i = CMP[nd.attr] if nd.op == "cmp" else RED[nd.attr] if nd.op.startswith("reduce") else AXIS[nd.attr] if nd.op == "concat" else 0
         c.attr_f = nd.value
     outs = (ctypes.c_int32 * max(1, len(graph.outputs)))(*graph.outputs)
     return nodes, outs

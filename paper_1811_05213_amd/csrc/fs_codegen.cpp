@@ -365,8 +365,10 @@ struct Emitter {
   template <class Tail>
   void emit_pass(const std::set<int>& mem, const std::set<int>& ext, bool store_outputs, Tail tail, const std::string& loop = "") {
     if (!loop.empty()) os << "    " << loop << " {\n";
-    else if (n_passes++ % 2 == 0) os << "    for (int ch = 0; ch < CT; ++ch) {\n";
-    else os << "    for (int ch = CT - 1; ch >= 0; --ch) {\n";
+    // (with a resident part the registers are nearly full: the chunk loop stays rolled, one chunk - 64 bytes per lane -
+    // in flight at a time, instead of the compiler interleaving several chunks and spilling on some builds)
+    else if (n_passes++ % 2 == 0) os << "    " << (gp.s.resident ? "_Pragma(\"unroll 1\") " : "") << "for (int ch = 0; ch < CT; ++ch) {\n";
+    else os << "    " << (gp.s.resident ? "_Pragma(\"unroll 1\") " : "") << "for (int ch = CT - 1; ch >= 0; --ch) {\n";
     // (inside a pass the chunk's own sizes shadow the body's: the building blocks read them by name)
     os << "      constexpr int NVL = NVLC, E = NVLC * V;\n      constexpr bool RAGGED = RAGC;\n"
        << "      const int vbase = RESV + ch * (NVL * L);\n      (void)RAGGED;\n";
@@ -677,7 +679,9 @@ struct Emitter {
     // (every workgroup pays that chain once, at the start of the kernel, when nothing else is in flight to hide it).
     // The tile in flight lives in variables outside the loop; `fetch` refills them at the bottom of each trip, which is
     // the order of operations of the plain loop.
-    const bool peeled = stage_before_loop && !ctile && s.CT == 1 && !s.tiled_transpose && !s.resident && std::max(1, s.U) == 1;
+    bool has_concat = false;
+    for (int m : gp.members) has_concat |= g.nodes[m].opcode == FS_CONCAT;
+    const bool peeled = stage_before_loop && !ctile && s.CT == 1 && !s.tiled_transpose && !s.resident && std::max(1, s.U) == 1 && !has_concat;
     if (peeled) {
       os << "  long row = 0, row_ld = 0, row0 = 0;\n  bool rok = false;\n  constexpr int vbase = 0;\n  (void)row_ld; (void)row0; (void)vbase;\n";
       for (const ExtTensor& e : gp.ext_in) {
@@ -738,6 +742,15 @@ struct Emitter {
         } else if (e.kind == KIND_COLV) {
           os << "    const float " << name(e.node, KIND_COLV) << x << " = fs_load1<" << e.dtype << ">(a.p[" << e.arg << "], row_ld" << x << ");\n";
         }
+      }
+      // concat members: one row out of two tensors, loaded with the other inputs (U is 1 in such groups)
+      for (int m : gp.members) {
+        const fs_node& cn = g.nodes[m];
+        if (cn.opcode != FS_CONCAT) continue;
+        const ExtTensor &ea = ext_of(cn.in[0]), &eb = ext_of(cn.in[1]);
+        const long split = cn.attr_i == FS_CONCAT_COLS ? g.nodes[cn.in[0]].cols : g.nodes[cn.in[0]].rows;
+        os << "    float " << name(m, KIND_FULL) << "[E];\n    fs_load_row_concat<" << cn.dtype << ", " << tmpl_row() << ", " << cn.attr_i << ", " << split
+           << "L, " << g.nodes[cn.in[1]].cols << "L>(" << name(m, KIND_FULL) << ", a.p[" << ea.arg << "], a.p[" << eb.arg << "], row_ld, lir, vbase);\n";
       }
     }
     // Inside the loop body every per-column value is made available right before its first use,
@@ -908,6 +921,10 @@ struct Emitter {
         } else {
           os << "    " << eloop() << ca << "[e] = rok ? fs_red_op<" << n.attr_i << ">(" << ca << "[e], " << ref(n.in[0]) << ") : " << ca << "[e];\n";
         }
+        continue;
+      }
+      if (n.opcode == FS_CONCAT) {  // loaded at the top of the body
+        if (const ExtTensor* e = find_out(m)) emit_store(*e, "    ");
         continue;
       }
       if (n.opcode == FS_TRANSPOSE) {

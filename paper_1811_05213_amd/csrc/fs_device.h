@@ -178,6 +178,23 @@ FS_DEV void fs_load_row(float (&dst)[NVL * V], const void* base, long row_elem0,
   for (int j = 0; j < NVL; ++j) fs_load_row_vec<DT, V, NVL, L, NV, RAGGED, NT>(dst, base, row_elem0, lir, vbase, j);
 }
 
+// The lane's slice of a row that is the concatenation of two tensors in memory.  AXIS 1 (columns): a is [R,SPLIT],
+// b is [R,CB], the row is a's row followed by b's (SPLIT and CB are multiples of V: no vector straddles the seam).
+// AXIS 0 (rows): rows below SPLIT come from a, the others from b, both NV*V columns wide.  The source is chosen
+// by selecting the address, not by branching: every lane issues exactly one load per vector.
+template <int DT, int V, int NVL, int L, int NV, bool RAGGED, int AXIS, long SPLIT, long CB>
+FS_DEV void fs_load_row_concat(float (&dst)[NVL * V], const void* a, const void* b, long row, int lir, int vbase) {
+#pragma unroll
+  for (int j = 0; j < NVL; ++j) {
+    int vi = vbase + j * L + lir;
+    if (RAGGED) vi = vi < NV ? vi : NV - 1;
+    const long col = (long)vi * V;
+    const bool first = AXIS == 1 ? col < SPLIT : row < SPLIT;
+    const long idx = AXIS == 1 ? (first ? row * SPLIT + col : row * CB + (col - SPLIT)) : (first ? row : row - SPLIT) * ((long)NV * V) + col;
+    fs_load_vec<DT, V>(&dst[j * V], first ? a : b, idx);
+  }
+}
+
 template <int DT, int V, int NVL, int L, int NV, bool RAGGED, bool NT = false>
 FS_DEV void fs_store_row_vec(const float (&src)[NVL * V], void* base, long row_elem0, int lir, int vbase, bool rok, int j) {
   const int vi = vbase + j * L + lir;

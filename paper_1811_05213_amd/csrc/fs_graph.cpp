@@ -24,6 +24,8 @@ int op_arity(int op) {
   if (op == FS_SELECT) return 3;
   if (op == FS_BCAST_ROWVEC || op == FS_BCAST_COLVEC || op == FS_TRANSPOSE || op == FS_REDUCE_ROW || op == FS_REDUCE_COL)
     return 1;
+  if (op == FS_RESHAPE || op == FS_BITCAST) return 1;
+  if (op == FS_CONCAT) return 2;
   return -1;
 }
 
@@ -31,7 +33,7 @@ const char* op_name(int op) {
   static const char* names[FS_NUM_OPCODES] = {
       "input", "const", "neg", "abs", "exp", "log", "tanh", "sigmoid", "sqrt", "rsqrt", "rcp", "gelu_tanh", "convert",
       "add", "sub", "mul", "div", "max", "min", "cmp", "select", "bcast_rowvec", "bcast_colvec", "transpose",
-      "reduce_row", "reduce_col"};
+      "reduce_row", "reduce_col", "reshape", "bitcast", "concat"};
   return (op >= 0 && op < FS_NUM_OPCODES) ? names[op] : "?";
 }
 
@@ -101,16 +103,36 @@ fs_status build_graph(const fs_graph_desc* desc, Graph* g) {
     } else if (op == FS_BCAST_ROWVEC) {
       if (a->rows != 1 || a->cols != n.cols) FS_FAIL(FS_ERR_SHAPE, "node %d (bcast_rowvec): operand must be [1,%d]", id, n.cols);
       if (a->dtype != n.dtype) FS_FAIL(FS_ERR_DTYPE, "node %d (bcast_rowvec): dtype differs from operand", id);
-      if (op_is_free(a->opcode) && a->opcode != FS_INPUT && a->opcode != FS_CONST)
+      if (op_is_free(a->opcode) && a->opcode != FS_INPUT && a->opcode != FS_CONST && !op_is_view(a->opcode))
         FS_FAIL(FS_ERR_BAD_GRAPH, "node %d: broadcast of a broadcast", id);
     } else if (op == FS_BCAST_COLVEC) {
       if (a->cols != 1 || a->rows != n.rows) FS_FAIL(FS_ERR_SHAPE, "node %d (bcast_colvec): operand must be [%d,1]", id, n.rows);
       if (a->dtype != n.dtype) FS_FAIL(FS_ERR_DTYPE, "node %d (bcast_colvec): dtype differs from operand", id);
-      if (op_is_free(a->opcode) && a->opcode != FS_INPUT && a->opcode != FS_CONST)
+      if (op_is_free(a->opcode) && a->opcode != FS_INPUT && a->opcode != FS_CONST && !op_is_view(a->opcode))
         FS_FAIL(FS_ERR_BAD_GRAPH, "node %d: broadcast of a broadcast", id);
     } else if (op == FS_TRANSPOSE) {
       if (a->rows != n.cols || a->cols != n.rows) FS_FAIL(FS_ERR_SHAPE, "node %d (transpose): result must be [%d,%d]", id, a->cols, a->rows);
       if (a->dtype != n.dtype) FS_FAIL(FS_ERR_DTYPE, "node %d (transpose): dtype differs from operand", id);
+    } else if (op_is_view(op)) {
+      if ((int64_t)a->rows * a->cols != (int64_t)n.rows * n.cols)
+        FS_FAIL(FS_ERR_SHAPE, "node %d (%s): [%d,%d] holds another number of elements than its operand [%d,%d]", id, op_name(op), n.rows, n.cols, a->rows, a->cols);
+      if (a->dtype != n.dtype) FS_FAIL(FS_ERR_DTYPE, "node %d (%s): dtype differs from operand", id, op_name(op));
+      if (a->opcode == FS_CONST || a->opcode == FS_BCAST_ROWVEC || a->opcode == FS_BCAST_COLVEC)
+        FS_FAIL(FS_ERR_BAD_GRAPH, "node %d (%s): a view of node %d (%s), which is never materialised", id, op_name(op), n.in[0], op_name(a->opcode));
+    } else if (op == FS_CONCAT) {
+      if (n.attr_i == FS_CONCAT_COLS) {
+        if (a->rows != n.rows || b->rows != n.rows || (int64_t)a->cols + b->cols != n.cols)
+          FS_FAIL(FS_ERR_SHAPE, "node %d (concat along columns): [%d,%d] ++ [%d,%d] is not [%d,%d]", id, a->rows, a->cols, b->rows, b->cols, n.rows, n.cols);
+      } else if (n.attr_i == FS_CONCAT_ROWS) {
+        if (a->cols != n.cols || b->cols != n.cols || (int64_t)a->rows + b->rows != n.rows)
+          FS_FAIL(FS_ERR_SHAPE, "node %d (concat along rows): [%d,%d] over [%d,%d] is not [%d,%d]", id, a->rows, a->cols, b->rows, b->cols, n.rows, n.cols);
+      } else {
+        FS_FAIL(FS_ERR_BAD_GRAPH, "node %d (concat): axis %d", id, n.attr_i);
+      }
+      if (a->dtype != n.dtype || b->dtype != n.dtype) FS_FAIL(FS_ERR_DTYPE, "node %d (concat): operands must have the result dtype", id);
+      for (const fs_node* x : {a, b})
+        if (x->opcode == FS_CONST || x->opcode == FS_BCAST_ROWVEC || x->opcode == FS_BCAST_COLVEC)
+          FS_FAIL(FS_ERR_BAD_GRAPH, "node %d (concat): operands must be tensors in memory, not broadcasts or constants", id);
     } else if (op == FS_REDUCE_ROW || op == FS_REDUCE_COL) {
       if (op == FS_REDUCE_ROW && (a->rows != n.rows || n.cols != 1)) FS_FAIL(FS_ERR_SHAPE, "node %d (reduce_row): result must be [%d,1]", id, a->rows);
       if (op == FS_REDUCE_COL && (a->cols != n.cols || n.rows != 1)) FS_FAIL(FS_ERR_SHAPE, "node %d (reduce_col): result must be [1,%d]", id, a->cols);
@@ -129,12 +151,25 @@ fs_status build_graph(const fs_graph_desc* desc, Graph* g) {
       for (int k = 0; k < n.num_in; ++k) g->exact[n.in[k]] = 1;
   }
 
+  // a view's bytes are those of the node its chain of views starts from
+  g->root_of.assign(N, 0);
+  for (int id = 0; id < N; ++id) g->root_of[id] = op_is_view(g->nodes[id].opcode) ? g->root_of[g->nodes[id].in[0]] : id;
+
   g->outputs.clear();
+  std::vector<int>& family_output = g->family_output;  // root -> the plan output that lives in its family's buffer
+  family_output.assign(N, -1);
   for (int k = 0; k < desc->num_outputs; ++k) {
     const int o = desc->outputs[k];
     if (o < 0 || o >= N) FS_FAIL(FS_ERR_BAD_GRAPH, "output %d: node id %d out of range", k, o);
-    if (op_is_free(g->nodes[o].opcode)) FS_FAIL(FS_ERR_BAD_GRAPH, "output %d: node %d (%s) is never materialised", k, o, op_name(g->nodes[o].opcode));
+    const int root = g->root_of[o];
+    if (op_is_free(g->nodes[root].opcode))
+      FS_FAIL(FS_ERR_BAD_GRAPH, "output %d: node %d (%s) is never materialised%s", k, o, op_name(g->nodes[o].opcode),
+              root != o ? " (a view of a plan input computes nothing)" : "");
     if (g->output_index[o] >= 0) FS_FAIL(FS_ERR_BAD_GRAPH, "output %d: node %d listed twice", k, o);
+    if (family_output[root] >= 0)
+      FS_FAIL(FS_ERR_BAD_GRAPH, "outputs %d and %d (nodes %d and %d) are views of the same value: list one of them", family_output[root], k,
+              g->outputs[family_output[root]], o);
+    family_output[root] = k;
     g->output_index[o] = k;
     g->outputs.push_back(o);
   }

@@ -111,12 +111,19 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   const int64_t RES = device_limits().resident_lanes;
   int max_es = 0;
   for (const ExtTensor& e : gp->ext_in)
-    if (e.kind == KIND_FULL) max_es = std::max(max_es, dtype_size(e.dtype));
+    if (e.kind == KIND_FULL || e.kind == KIND_PART) max_es = std::max(max_es, dtype_size(e.dtype));
   for (const ExtTensor& e : gp->ext_out)
     if (e.kind == KIND_FULL) max_es = std::max(max_es, dtype_size(e.dtype));
   if (max_es == 0) max_es = 4;
   int V = 16 / max_es;
   while (C % V) V /= 2;
+  bool has_concat = false;
+  for (int m : gp->members)
+    if (g.nodes[m].opcode == FS_CONCAT) {
+      has_concat = true;
+      if (g.nodes[m].attr_i == FS_CONCAT_COLS)  // a vector access must not straddle the seam
+        while (g.nodes[g.nodes[m].in[0]].cols % V) V /= 2;
+    }
   const int NV = C / V;
   const bool rowred = !gp->row_reduces.empty();
   const bool colred = !gp->col_reduces.empty();
@@ -179,6 +186,8 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   if (l_min > 1024 && !tileable && !chunked && !col_tiled)
     FS_FAIL(FS_ERR_UNSUPPORTED, "rows of %d columns are too long for one workgroup in a group with %s", C,
             colred ? "row and column reductions" : "transposed outputs");
+  if (has_concat && (chunked || col_tiled))
+    FS_FAIL(FS_ERR_UNSUPPORTED, "a concat cannot be read by a kernel that walks rows of %d columns in chunks", C);
   if (tileable) l_min = std::min(l_min, 256);
   // wide transposes: 2-D tiles through LDS
   const bool tiled_transpose = has_transposed && tileable && C > 256 && R > 1;
@@ -375,6 +384,7 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   // [65536,512]).  With a row reduction in the body one tile per trip is the faster form.
   s.U = (colred && !rowred && s.grid < s.n_iters && CT == 1) ? 2 : 1;
   if (opt.has_hint && opt.hint.tiles_per_trip >= 1 && opt.hint.tiles_per_trip <= 4) s.U = opt.hint.tiles_per_trip;
+  if (has_concat) s.U = 1;
   // two fold levels at most: the smallest fan-in whose square covers the grid
   s.fan_in = s.RB <= 64 ? 8 : s.RB <= 256 ? 16 : 32;
 
@@ -511,6 +521,21 @@ fs_status analyse_group(const Graph& g, const std::vector<int>& members, const s
     const fs_node& n = g.nodes[m];
     const bool t = tf[m], t_op = n.opcode == FS_TRANSPOSE ? !t : t;
     const Kind result_kind = a.classify(n, t);
+    if (n.opcode == FS_CONCAT) {
+      // read from memory as one row out of two tensors; nothing is computed, so nothing is fused INTO a concat:
+      // an operand produced by this group would have to exist in memory first
+      if (t || result_kind != KIND_FULL) FS_FAIL(FS_ERR_UNSUPPORTED, "node %d (concat) does not fit the group's work space [%d,%d]", m, R, C);
+      for (int k = 0; k < 2; ++k) {
+        const int o = n.in[k];
+        if (a.in_set[g.root_of[o]]) FS_FAIL(FS_ERR_UNSUPPORTED, "node %d (concat): operand %d is computed by the same kernel", m, o);
+        for (const ExtTensor& e : gp.ext_in)
+          if (e.node == o && e.kind != KIND_PART) FS_FAIL(FS_ERR_UNSUPPORTED, "node %d is read both whole and as part of a concat", o);
+        add_ext_in(gp, o, KIND_PART, g.nodes[o].dtype);
+        gp.kind[o] = KIND_PART;
+      }
+      gp.kind[m] = KIND_FULL;
+      gp.level[m] = 0;
+    }
     Kind operand_kind = result_kind;
     if (is_reduce(m) || n.opcode == FS_TRANSPOSE) operand_kind = KIND_FULL;
     if (result_kind == KIND_NONE || (n.opcode == FS_TRANSPOSE && result_kind != KIND_FULL))
@@ -518,7 +543,7 @@ fs_status analyse_group(const Graph& g, const std::vector<int>& members, const s
     gp.kind[m] = result_kind;
     const bool deferred = reduces_cols(m);
     int lvl = result_kind == KIND_ROWV && !deferred ? -1 : 0;
-    for (int k = 0; k < n.num_in; ++k) {
+    for (int k = 0; k < n.num_in && n.opcode != FS_CONCAT; ++k) {
       Resolved r;
       if (!a.resolve(n.in[k], operand_kind, t_op, &r))
         FS_FAIL(FS_ERR_UNSUPPORTED, "node %d: operand %d does not fit the group's work space [%d,%d]", m, n.in[k], R, C);
@@ -529,6 +554,8 @@ fs_status analyse_group(const Graph& g, const std::vector<int>& members, const s
           FS_FAIL(FS_ERR_UNSUPPORTED, "node %d consumes node %d, whose value only exists after the whole grid has run", m, r.node);
         lvl = std::max(lvl, gp.level[r.node] + (reduces_rows(r.node) ? 1 : 0));
       } else {
+        // a view of a value this kernel computes would have to exist in memory first
+        if (a.in_set[g.root_of[r.node]]) FS_FAIL(FS_ERR_UNSUPPORTED, "node %d reads node %d, a view of a value computed by the same kernel", m, r.node);
         // tensors from memory: a full tensor can only be read in the orientation it is stored in
         if (r.kind == KIND_FULL && t_op) FS_FAIL(FS_ERR_UNSUPPORTED, "node %d would need a transposing load of node %d", m, r.node);
         for (const ExtTensor& e : gp.ext_in)
@@ -547,6 +574,7 @@ fs_status analyse_group(const Graph& g, const std::vector<int>& members, const s
       for (int u : g.users[id]) {
         const int uop = g.nodes[u].opcode;
         if (uop == FS_BCAST_ROWVEC || uop == FS_BCAST_COLVEC) scan_users(u);
+        else if (op_is_view(uop)) leaves = true;  // a view is read from memory (or is a plan output): the value must exist there
         else if (!a.in_set[u]) leaves = true;
       }
     };
@@ -716,7 +744,7 @@ struct Former {
     for (int u : g.users[id]) {
       if (!live[u]) continue;
       const int uop = g.nodes[u].opcode;
-      if (uop == FS_BCAST_ROWVEC || uop == FS_BCAST_COLVEC) real_users(u, out);
+      if (uop == FS_BCAST_ROWVEC || uop == FS_BCAST_COLVEC || op_is_view(uop)) real_users(u, out);
       else out->push_back(u);
     }
   }

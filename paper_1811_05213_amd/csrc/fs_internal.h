@@ -37,8 +37,9 @@ struct DeviceLimits {
 const DeviceLimits& device_limits();
 
 // ---- graph -----------------------------------------------------------------------------------
+inline bool op_is_view(int op) { return op == FS_RESHAPE || op == FS_BITCAST; }  // the operand's bytes under another shape
 inline bool op_is_free(int op) {  // never materialised, never a launch: inlined into consumers
-  return op == FS_INPUT || op == FS_CONST || op == FS_BCAST_ROWVEC || op == FS_BCAST_COLVEC;
+  return op == FS_INPUT || op == FS_CONST || op == FS_BCAST_ROWVEC || op == FS_BCAST_COLVEC || op_is_view(op);
 }
 inline bool op_is_unary(int op) { return op >= FS_NEG && op <= FS_CONVERT; }
 inline bool op_is_binary(int op) { return op >= FS_ADD && op <= FS_MIN; }
@@ -58,6 +59,8 @@ struct Graph {
   std::vector<int> output_index;         // node id -> index into outputs[] or -1
   std::vector<std::vector<int>> users;   // direct users of each node
   std::vector<char> exact;               // node feeds a predicate: its bits must be reproducible (no contraction)
+  std::vector<int> root_of;              // the node whose buffer a node's bytes live in: itself, or what its chain of views starts from
+  std::vector<int> family_output;        // root -> index of the plan output (the root itself or a view of it) whose buffer holds it, or -1
   int n() const { return (int)nodes.size(); }
 };
 
@@ -71,7 +74,8 @@ enum Kind : int {
   KIND_NONE = 0,
   KIND_FULL = 1,  // [R,C]: E elements per lane, in VGPRs
   KIND_COLV = 2,  // [R,1]: one value per row, replicated in the row's lanes
-  KIND_ROWV = 3   // [1,C]: one value per column, the lane's slice loaded once per workgroup
+  KIND_ROWV = 3,  // [1,C]: one value per column, the lane's slice loaded once per workgroup
+  KIND_PART = 4   // an operand of a concat member: covers part of the work space, read through that member's two-source load
 };
 
 struct ExtTensor {

@@ -341,7 +341,8 @@ fs_status fs_plan_create(const fs_graph_desc* desc, fs_plan** out_plan) {
   off = plan->ticket_bytes;
   for (GroupPlan& gp : plan->groups)
     for (const ExtTensor& e : gp.ext_out)
-      if (g.output_index[e.node] < 0 && !plan->ws_tensor_offset.count(e.node)) {
+      // (a value a plan output is a view of is written straight into the caller's buffer)
+      if (g.family_output[e.node] < 0 && !plan->ws_tensor_offset.count(e.node)) {
         plan->ws_tensor_offset[e.node] = off;
         off = align_up(off + (size_t)g.nodes[e.node].rows * g.nodes[e.node].cols * dtype_size(e.dtype), 256);
       }
@@ -356,7 +357,7 @@ fs_status fs_plan_create(const fs_graph_desc* desc, fs_plan** out_plan) {
   for (int id : g.input_ids) {
     bool used = false;  // only inputs some live node reads
     for (const GroupPlan& gp : plan->groups)
-      for (const ExtTensor& e : gp.ext_in) used |= e.node == id;
+      for (const ExtTensor& e : gp.ext_in) used |= g.root_of[e.node] == id;
     if (used) plan->min_hbm_bytes += (uint64_t)g.nodes[id].rows * g.nodes[id].cols * dtype_size(g.nodes[id].dtype);
   }
   for (int o : g.outputs) plan->min_hbm_bytes += (uint64_t)g.nodes[o].rows * g.nodes[o].cols * dtype_size(g.nodes[o].dtype);
@@ -467,10 +468,11 @@ static fs_status enqueue_groups(const fs_plan* plan, const fs_plan::Loaded* ld, 
                                 void* workspace, hipStream_t stream) {
   const Graph& g = plan->graph;
   char* ws = (char*)workspace;
-  auto tensor_ptr = [&](int node) -> void* {
-    if (g.input_index[node] >= 0) return const_cast<void*>(inputs[g.input_index[node]]);
-    if (g.output_index[node] >= 0) return outputs[g.output_index[node]];
-    return ws + plan->ws_tensor_offset.at(node);
+  auto tensor_ptr = [&](int node) -> void* {  // a view addresses the buffer of the value it is a view of
+    const int root = g.root_of[node];
+    if (g.input_index[root] >= 0) return const_cast<void*>(inputs[g.input_index[root]]);
+    if (g.family_output[root] >= 0) return outputs[g.family_output[root]];
+    return ws + plan->ws_tensor_offset.at(root);
   };
   for (size_t gi = 0; gi < plan->groups.size(); ++gi) {
     const GroupPlan& gp = plan->groups[gi];
@@ -721,10 +723,11 @@ fs_status fs_plan_tune(fs_plan* plan, const void* const* inputs, void* const* ou
   } while (0)
 
   char* ws = (char*)workspace;
-  auto tensor_ptr = [&](int node) -> void* {
-    if (g.input_index[node] >= 0) return const_cast<void*>(inputs[g.input_index[node]]);
-    if (g.output_index[node] >= 0) return outputs[g.output_index[node]];
-    return ws + plan->ws_tensor_offset.at(node);
+  auto tensor_ptr = [&](int node) -> void* {  // a view addresses the buffer of the value it is a view of
+    const int root = g.root_of[node];
+    if (g.input_index[root] >= 0) return const_cast<void*>(inputs[g.input_index[root]]);
+    if (g.family_output[root] >= 0) return outputs[g.family_output[root]];
+    return ws + plan->ws_tensor_offset.at(root);
   };
 
   TuneScratch res;

@@ -586,3 +586,124 @@ def test_run_refuses_overlapping_buffers_before_touching_the_device():
         p.load()
     assert e.value.status_name == "FS_ERR_HIP"
     p.destroy()
+
+
+# ------------------------------------------------------------------ reshape / bitcast / concat
+def _attention_scores_graph(b=2, h=3, s=64, d=32):
+    """Per-head softmax of an N-D tensor [b, s, h*s] -> view [b*s*h, s], then back, with a concat on the way in."""
+    g = Graph()
+    x = g.input(b * s, h * s)                       # [b, s, h, s] stored row-major, seen as [b*s, h*s]
+    bias = g.input(1, s)
+    v = g.view_nd(x, (b, s, h, s), 3)               # [b*s*h, s]: one softmax row per (batch, position, head)
+    z = g.binary("add", v, g.bcast_rowvec(bias, b * s * h))
+    m = g.reduce_row("max", z)
+    e = g.unary("exp", g.binary("sub", z, g.bcast_colvec(m, s)))
+    y = g.binary("div", e, g.bcast_colvec(g.reduce_row("sum", e), s))
+    out = g.reshape(y, b * s, h * s, op="bitcast")  # back to the caller's 2-D shape: a view, no copy
+    g.set_outputs([out])
+    return g
+
+
+def test_views_cost_no_launch_and_no_copy():
+    g = _attention_scores_graph()
+    p = fs.Plan(g)
+    st = p.stats()
+    assert st["num_launches"] == 1 and st["launched_hbm_bytes"] == st["min_hbm_bytes"] == min_hbm_bytes(g)
+    gi = p.group_info(0)
+    assert (gi["dom_rows"], gi["dom_cols"]) == (2 * 64 * 3, 64) and p.workspace_bytes() == 0   # the view's shape is the work space
+    groups = p.node_groups()
+    assert all(groups[i] == -1 for i, n in enumerate(g.nodes) if n.op in ("reshape", "bitcast"))
+    p.destroy()
+    u = fs.Plan(g, mode=fs.FS_MODE_UNFUSED)
+    assert u.stats()["num_launches"] == len(g.compute_ids()) == 6     # the two views are not launches
+    u.destroy()
+    # a reshape between two computations separates them (the consumer's rows are not the producer's) without a copy:
+    # the producer writes once, the consumer reads the same bytes under the other shape
+    g2 = Graph()
+    x = g2.input(128, 256)
+    a = g2.unary("tanh", x)
+    r = g2.reshape(a, 512, 64)
+    s = g2.reduce_row("sum", r)
+    g2.set_outputs([g2.binary("sub", r, g2.bcast_colvec(s, 64))])
+    p = fs.Plan(g2)
+    assert p.stats()["num_launches"] == 2 and p.workspace_bytes() >= 128 * 256 * 4
+    assert p.stats()["launched_hbm_bytes"] == 4 * 128 * 256 * 4
+    p.destroy()
+
+
+def test_view_and_concat_validation():
+    g = Graph()
+    x = g.input(4, 6)
+    r = g.reshape(x, 3, 8)
+    g.set_outputs([r])
+    assert _status(g) == "FS_ERR_BAD_GRAPH"             # a view of a plan input computes nothing
+    g = Graph()
+    x = g.input(4, 6)
+    y = g.unary("neg", x)
+    g.set_outputs([y, g.reshape(y, 3, 8)])
+    assert _status(g) == "FS_ERR_BAD_GRAPH"             # two views of one value as outputs: one buffer cannot be both
+    g = Graph()
+    x = g.input(4, 6)
+    r = g.reshape(g.unary("neg", x), 3, 8)
+    g.nodes[r].cols = 7
+    g.set_outputs([r])
+    assert _status(g) == "FS_ERR_SHAPE"
+    g = Graph()
+    x = g.input(4, 6)
+    r = g.reshape(g.unary("neg", x), 3, 8)
+    g.nodes[r].dtype = "bf16"
+    g.set_outputs([r])
+    assert _status(g) == "FS_ERR_DTYPE"
+    g = Graph()
+    v = g.input(1, 6)
+    r = g.reshape(g.bcast_rowvec(v, 4), 3, 8)
+    g.set_outputs([g.unary("neg", r)])
+    assert _status(g) == "FS_ERR_BAD_GRAPH"             # a view of a broadcast, which is never materialised
+    g = Graph()
+    a, b = g.input(4, 6), g.input(4, 2)
+    c = g.concat(a, b)
+    g.nodes[c].cols = 9
+    g.set_outputs([c])
+    assert _status(g) == "FS_ERR_SHAPE"
+    g = Graph()
+    a, b = g.input(4, 6), g.input(4, 2, "bf16")
+    c = g._add(type(g.nodes[0])("concat", "f32", 4, 8, (a, b), attr="cols"))
+    g.set_outputs([c])
+    assert _status(g) == "FS_ERR_DTYPE"
+
+
+def test_concat_is_read_as_one_row_by_its_consumers():
+    # two tensors from memory joined along columns and normalised: one kernel, nothing copied
+    g = Graph()
+    a, b = g.input(512, 96), g.input(512, 160)
+    c = g.concat(a, b)
+    m = g.reduce_row("mean", c)
+    g.set_outputs([g.binary("sub", c, g.bcast_colvec(m, 256))])
+    p = fs.Plan(g)
+    assert p.stats()["num_launches"] == 1 and p.stats()["launched_hbm_bytes"] == min_hbm_bytes(g)
+    assert "fs_load_row_concat" in p.group_source(0)
+    gi = p.group_info(0)
+    assert 96 % gi["vec_elems"] == 0
+    p.destroy()
+    # a seam at an odd column forces narrower accesses, not a wrong one
+    g = Graph()
+    a, b = g.input(64, 30), g.input(64, 34)
+    g.set_outputs([g.unary("neg", g.concat(a, b))])
+    p = fs.Plan(g)
+    assert p.group_info(0)["vec_elems"] == 2
+    p.destroy()
+    # an operand computed by the graph is materialised first: producer | concat consumer
+    g = Graph()
+    a, b = g.input(64, 32), g.input(64, 32)
+    c = g.concat(g.unary("tanh", a), b)
+    g.set_outputs([g.reduce_row("sum", c)])
+    p = fs.Plan(g)
+    assert p.stats()["num_launches"] == 2
+    p.destroy()
+    # along rows
+    g = Graph()
+    a, b = g.input(100, 64), g.input(28, 64)
+    g.set_outputs([g.reduce_row("max", g.unary("abs", g.concat(a, b, "rows")))])
+    p = fs.Plan(g)
+    assert p.stats()["num_launches"] == 1 and p.group_info(0)["dom_rows"] == 128
+    p.destroy()

@@ -764,3 +764,72 @@ def test_gpu_matches_the_stored_small_cases():
             ref.append(f32_to_bf16_bits(v) if g.nodes[o].dtype == "bf16" else v)
         for mode in (fs.FS_MODE_STITCHED, fs.FS_MODE_UNFUSED):
             check_all(g, run_graph(g, ins, mode=mode), ref, f"stored case {name} mode {mode}")
+
+
+# ------------------------------------------------------------------ reshape / bitcast / concat
+def test_views_of_nd_tensors_and_concats():
+    """Reshape / Bitcast as zero-cost views between kernels and at the plan's edges; Concat read as one row."""
+    # per-head softmax of [b, s, h, s] through views, back to the caller's 2-D shape (one kernel, no copy)
+    b, h, s = 3, 5, 72
+    g = Graph()
+    x = g.input(b * s, h * s)
+    bias = g.input(1, s)
+    v = g.view_nd(x, (b, s, h, s), 3)
+    z = g.binary("add", v, g.bcast_rowvec(bias, b * s * h))
+    e = g.unary("exp", g.binary("sub", z, g.bcast_colvec(g.reduce_row("max", z), s)))
+    y = g.binary("div", e, g.bcast_colvec(g.reduce_row("sum", e), s))
+    g.set_outputs([g.reshape(y, b * s, h * s, op="bitcast")])
+    ins = [RNG.standard_normal((b * s, h * s)).astype(np.float32), RNG.standard_normal((1, s)).astype(np.float32)]
+    p = fs.Plan(g)
+    assert p.stats()["num_launches"] == 1
+    p.destroy()
+    ref, out_s, _ = both_modes(g, ins, "per-head softmax through views")
+    assert out_s[0].shape == (b * s, h * s)
+    # a reshape between two computations: producer | consumer over the same bytes; a [1,R] vector viewed as [R,1] and
+    # broadcast along rows; the reshaped intermediate is also a plan output (the producer writes it into the caller's buffer)
+    g = Graph()
+    x = g.input(130, 264)
+    w = g.input(1, 520)
+    a = g.unary("tanh", x)
+    r = g.reshape(a, 520, 66)
+    wcol = g.reshape(w, 520, 1)
+    t = g.binary("mul", r, g.bcast_colvec(wcol, 66))
+    sm = g.reduce_row("sum", t)
+    back = g.reshape(g.binary("sub", t, g.bcast_colvec(sm, 66)), 130, 264)
+    g.set_outputs([back, r, g.reshape(sm, 1, 520)])
+    ins = [RNG.standard_normal((130, 264)).astype(np.float32), RNG.standard_normal((1, 520)).astype(np.float32)]
+    ref, out_s, out_u = both_modes(g, ins, "reshape between kernels")
+    # bf16 payload through a view; a chain of views
+    g = Graph()
+    x = g.input(64, 96, "bf16")
+    v2 = g.reshape(g.reshape(g.reshape(x, 96, 64), 1, 6144, op="bitcast"), 32, 192)
+    g.set_outputs([g.unary("neg", v2), g.reduce_row("max", g.unary("convert", v2, "f32"))])
+    both_modes(g, [f32_to_bf16_bits(RNG.standard_normal((64, 96)).astype(np.float32))], "chain of views, bf16")
+    # concat along columns feeding a normalisation (ragged tail, a seam that is not a multiple of the widest vector),
+    # along rows feeding column and row reductions, of bf16 tensors, and as a plan output of its own (a copy kernel)
+    for rows, c0, c1 in ((300, 96, 160), (77, 30, 34), (1000, 8, 1000), (5, 4100, 12)):
+        g = Graph()
+        ia, ib = g.input(rows, c0), g.input(rows, c1)
+        c = g.concat(ia, ib)
+        m = g.reduce_row("mean", c)
+        g.set_outputs([g.binary("sub", c, g.bcast_colvec(m, c0 + c1)), c])
+        ins = [RNG.standard_normal((rows, c0)).astype(np.float32), RNG.standard_normal((rows, c1)).astype(np.float32)]
+        ref, out_s, _ = both_modes(g, ins, f"concat cols {rows}x({c0}+{c1})")
+        np.testing.assert_array_equal(out_s[1], np.concatenate(ins, axis=1))
+    for r0, r1, cols, dt in ((100, 28, 64, "f32"), (1, 700, 130, "f32"), (513, 511, 256, "bf16")):
+        g = Graph()
+        ia, ib = g.input(r0, cols, dt), g.input(r1, cols, dt)
+        c = g.concat(ia, ib, "rows")
+        cf = g.unary("convert", c, "f32") if dt != "f32" else c
+        g.set_outputs([g.reduce_col("sum", cf), g.reduce_row("max", g.unary("abs", cf)), c])
+        ins = [RNG.standard_normal((r0, cols)).astype(np.float32), RNG.standard_normal((r1, cols)).astype(np.float32)]
+        if dt == "bf16":
+            ins = [f32_to_bf16_bits(a) for a in ins]
+        ref, out_s, _ = both_modes(g, ins, f"concat rows ({r0}+{r1})x{cols} {dt}")
+        np.testing.assert_array_equal(out_s[2], np.concatenate(ins, axis=0))
+    # an operand computed by the graph (materialised first), and a concat of a view
+    g = Graph()
+    ia, ib = g.input(64, 48), g.input(32, 96)
+    c = g.concat(g.unary("tanh", ia), g.reshape(ib, 64, 48))
+    g.set_outputs([g.reduce_row("sum", c), g.unary("sigmoid", c)])
+    both_modes(g, [RNG.standard_normal((64, 48)).astype(np.float32), RNG.standard_normal((32, 96)).astype(np.float32)], "concat of computed + view")
