@@ -341,6 +341,12 @@ def main():
     cpu = None if args.no_cpu else cpu_baseline(args.workload)
 
     st = head["stitched"]
+    # every workload's roofline block under the headline's (algorithmic bytes, live-measured launch time, counter traffic)
+    per_workload = {f"cfg{args.workload}": dict(head["roofline"], workload=head["workload"], launches=st["launches"],
+                                               speedup_vs_unfused=head.get("speedup_vs_unfused"))}
+    for key, w in extras.items():
+        per_workload[key] = dict(w["roofline"], workload=w["workload"], launches=w["stitched"]["launches"], speedup_vs_unfused=w.get("speedup_vs_unfused"))
+    head["roofline"] = dict(head["roofline"], workloads=per_workload)
     line = {
         "metric": "effective HBM GB/s (% of peak) per fused subgraph; fused vs unfused speedup",
         "value": head["gbs"],

@@ -674,30 +674,6 @@ struct Emitter {
       }
       os << ind << "__syncthreads();\n";
     };
-    // Looping workgroups that stage their [1,C] operands once: the loads of the first row tile are issued BEFORE the
-    // staging, so the staging's round trip to memory and the first tile's overlap instead of following each other
-    // (every workgroup pays that chain once, at the start of the kernel, when nothing else is in flight to hide it).
-    // The tile in flight lives in variables outside the loop; `fetch` refills them at the bottom of each trip, which is
-    // the order of operations of the plain loop.
-    bool has_concat = false;
-    for (int m : gp.members) has_concat |= g.nodes[m].opcode == FS_CONCAT;
-    const bool peeled = stage_before_loop && !ctile && s.CT == 1 && !s.tiled_transpose && !s.resident && std::max(1, s.U) == 1 && !has_concat;
-    if (peeled) {
-      os << "  long row = 0, row_ld = 0, row0 = 0;\n  bool rok = false;\n  constexpr int vbase = 0;\n  (void)row_ld; (void)row0; (void)vbase;\n";
-      for (const ExtTensor& e : gp.ext_in) {
-        if (e.kind == KIND_FULL) os << "  float " << name(e.node, KIND_FULL) << "[E];\n";
-        else if (e.kind == KIND_COLV) os << "  float " << name(e.node, KIND_COLV) << " = 0.0f;\n";
-      }
-      os << "  auto fetch = [&](int it) {\n    row = (long)it * G + rg;\n    rok = row < R;\n    row_ld = rok ? row : R - 1;\n    row0 = row_ld * C;\n";
-      for (const ExtTensor& e : gp.ext_in) {
-        if (e.kind == KIND_FULL)
-          os << "    fs_load_row<" << e.dtype << ", " << tmpl_row() << ", " << (e.streaming ? "true" : "false") << ">(" << name(e.node, KIND_FULL)
-             << ", a.p[" << e.arg << "], row0, lir, vbase);\n";
-        else if (e.kind == KIND_COLV)
-          os << "    " << name(e.node, KIND_COLV) << " = fs_load1<" << e.dtype << ">(a.p[" << e.arg << "], row_ld);\n";
-      }
-      os << "  };\n  int it = (int)blockIdx.x;\n  if (it < a.n_iters) fetch(it);\n";
-    }
     if (stage_before_loop) emit_staging("  ");
     for (int k = 0; k < K; ++k) {
       const int m = gp.col_reduces[k];
@@ -708,17 +684,17 @@ struct Emitter {
     // ---- the row loop ----
     // A looping kernel handles U row tiles per trip: the loads of all U tiles are issued first,
     // then the U bodies run one after the other (more bytes in flight per wavefront).
-    const int U = (rowv_in_loop || s.CT > 1) ? 1 : std::max(1, s.U);
-    if (peeled) {
-      os << "  while (it < a.n_iters) {\n";
-    } else if (ctile) {
+    // (workgroups that stage their [1,C] operands before the loop read them from LDS inside each tile's body: they
+    // may take several tiles per trip too)
+    const int U = ((rowv_in_loop && !stage_before_loop) || s.CT > 1 || ctile) ? 1 : std::max(1, s.U);
+    if (ctile) {
       os << "  for (int it = rb; it < a.n_iters; it += RB) {\n";
     } else if (U == 1) {
       os << "  for (int it = (int)blockIdx.x; it < a.n_iters; it += (int)gridDim.x) {\n";
     } else {
       os << "  for (int it0 = (int)blockIdx.x * " << U << "; it0 < a.n_iters; it0 += (int)gridDim.x * " << U << ") {\n";
     }
-    for (int u = 0; u < U && !peeled; ++u) {
+    for (int u = 0; u < U; ++u) {
       const std::string x = U == 1 ? "" : "_" + std::to_string(u);
       if (U > 1) os << "    const int it" << x << " = it0 + " << u << ";\n";
       if (ctile) {
@@ -835,12 +811,14 @@ struct Emitter {
     size_t tail_start = 0;
     for (size_t k = 0; k < order.size(); ++k)
       if (is_rr(order[k])) tail_start = k + 1;
-    bool strip_tail = tail_start > 0 && tail_start < order.size() && s.NVL >= 2 && U == 1 && !s.resident && !s.tile_transpose && !s.tiled_transpose;
+    bool strip_tail = tail_start > 0 && tail_start < order.size() && s.NVL >= 2 && !s.resident && !s.tile_transpose && !s.tiled_transpose;
     for (const ExtTensor& e : gp.ext_out) strip_tail &= !e.transposed;
     for (size_t k = tail_start; k < order.size() && strip_tail; ++k) strip_tail &= g.nodes[order[k]].opcode != FS_TRANSPOSE;
     std::ostringstream before_strip;
 
     for (int u = 0; u < U; ++u) {
+      rowv_ready.clear();  // (each tile's body is a scope of its own: what it reads lazily it declares itself)
+      comb_ready.clear();
       if (U > 1) {
         const std::string x = "_" + std::to_string(u);
         os << "    {\n    const long row = row" << x << "; const bool rok = rok" << x << "; const long row0 = row0" << x
@@ -966,7 +944,6 @@ struct Emitter {
         emit_pass(mem, ext, true, []() {});
       }
     }
-    if (peeled) os << "    it += (int)gridDim.x;\n    if (it < a.n_iters) fetch(it);\n";
     os << "  }\n";
 
     // ---- epilogue: finish the column reductions ----

@@ -547,7 +547,6 @@ fs_status fs_plan_workspace_check(fs_plan* plan, const void* workspace, size_t w
 fs_status fs_plan_run(fs_plan* plan, const void* const* inputs, void* const* outputs, void* workspace,
                       size_t workspace_bytes, void* hip_stream) {
   if (!plan) FS_FAIL(FS_ERR_INVALID_ARG, "plan is NULL");
-  const Graph& g = plan->graph;
   fs_status st = check_workspace(plan, workspace, workspace_bytes);
   if (st != FS_OK) return st;
   st = check_buffers(plan, inputs, outputs, workspace);

@@ -86,12 +86,22 @@ def check_output(gpu: np.ndarray, ref: np.ndarray, dtype: str, what: str = "", c
 # ------------------------------------------------------------------------------------------------
 # quantiser nodes
 # ------------------------------------------------------------------------------------------------
+# ops whose bf16 result is one of their bf16 operands' values (or its negation): no rounding decision is taken
+_MOVES = ("reshape", "bitcast", "concat", "transpose", "bcast_rowvec", "bcast_colvec", "neg", "abs", "max", "min", "select")
+
+
 def quantiser_nodes(graph: Graph) -> List[int]:
-    """Computed bf16 nodes that some other node consumes (looking through nothing: a broadcast counts)."""
+    """Computed bf16 nodes that round a value and that some other node consumes."""
     used = set()
     for n in graph.nodes:
         used.update(n.ins)
-    return [i for i, n in enumerate(graph.nodes) if n.dtype == "bf16" and n.op not in ("input", "const") and i in used]
+
+    def rounds(n):
+        if n.dtype != "bf16" or n.op in ("input", "const"):
+            return False
+        values = n.ins[1:] if n.op == "select" else n.ins
+        return not (n.op in _MOVES and all(graph.nodes[o].dtype == "bf16" for o in values))
+    return [i for i, n in enumerate(graph.nodes) if rounds(n) and i in used]
 
 
 def expose_bf16_nodes(graph: Graph) -> Graph:
