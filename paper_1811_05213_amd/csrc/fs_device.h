@@ -240,20 +240,24 @@ FS_DEV void fs_store_row_transposed(const float (&src)[NVL * V], void* base, lon
 // its own copy through the vector cache (which is the narrower path: 64 B/clk against 128).
 // The staged copy is laid out in the order lanes read it: the 4-float chunk q of vector
 // vi = j*L + lir sits at chunk index (j*(V/4) + q)*L + lir, so a 128-bit LDS read by
-// consecutive lanes touches consecutive 16-byte chunks (no bank conflicts).  SLOT = NVL*L*V
-// floats per vector.
+// consecutive lanes touches consecutive 16-byte chunks (no bank conflicts).  The staging pass
+// walks the LDS positions in order (thread t writes position t, t + WG, ...), so its 128-bit
+// writes are conflict-free too; what it reads from memory is then 16-byte pieces V*4 bytes
+// apart, a few KB from L2 once per workgroup.  SLOT = NVL*L*V floats per vector.
 template <int DT, int V, int L, int C, int WG> FS_DEV void fs_stage_rowvec(float* lds, const void* src) {
   if constexpr (V % 4 == 0) {
-    constexpr int Q = V / 4;
-    for (int chunk = (int)threadIdx.x; chunk < C / 4; chunk += WG) {
+    constexpr int Q = V / 4, NVS = C / V;  // 16-byte pieces per vector access, vectors per row
+    constexpr int P = ((NVS + L - 1) / L) * Q * L;  // LDS positions (16-byte pieces) of the slot, tail included
+    for (int p = (int)threadIdx.x; p < P; p += WG) {
+      const int l = p % L, jq = p / L, j = jq / Q, q = jq % Q, vi = j * L + l;
+      if (vi >= NVS) continue;
       float tmp[4];
-      fs_load_vec<DT, 4>(tmp, src, chunk * 4);
-      const int vi = chunk / Q, q = chunk % Q, j = vi / L, l = vi % L;
+      fs_load_vec<DT, 4>(tmp, src, (vi * Q + q) * 4);
       typedef float f4 __attribute__((ext_vector_type(4)));
       f4 t4;
 #pragma unroll
       for (int k = 0; k < 4; ++k) t4[k] = tmp[k];
-      *reinterpret_cast<f4*>(lds + ((j * Q + q) * L + l) * 4) = t4;  // one 128-bit LDS store
+      *reinterpret_cast<f4*>(lds + p * 4) = t4;  // one 128-bit LDS store, consecutive threads to consecutive pieces
     }
   } else {
     for (int i = (int)threadIdx.x; i < C; i += WG) {
@@ -267,17 +271,19 @@ template <int DT, int V, int L, int C, int WG> FS_DEV void fs_stage_rowvec(float
 // instead of once per element of every row.
 template <int DTA, int DTB, bool NEGA, bool NEGB, int V, int L, int C, int WG> FS_DEV void fs_stage_rowvec_sum(float* lds, const void* a, const void* b) {
   if constexpr (V % 4 == 0) {
-    constexpr int Q = V / 4;
-    for (int chunk = (int)threadIdx.x; chunk < C / 4; chunk += WG) {
+    constexpr int Q = V / 4, NVS = C / V;
+    constexpr int P = ((NVS + L - 1) / L) * Q * L;
+    for (int p = (int)threadIdx.x; p < P; p += WG) {
+      const int l = p % L, jq = p / L, j = jq / Q, q = jq % Q, vi = j * L + l;
+      if (vi >= NVS) continue;
       float ta[4], tb[4];
-      fs_load_vec<DTA, 4>(ta, a, chunk * 4);
-      fs_load_vec<DTB, 4>(tb, b, chunk * 4);
-      const int vi = chunk / Q, q = chunk % Q, j = vi / L, l = vi % L;
+      fs_load_vec<DTA, 4>(ta, a, (vi * Q + q) * 4);
+      fs_load_vec<DTB, 4>(tb, b, (vi * Q + q) * 4);
       typedef float f4 __attribute__((ext_vector_type(4)));
       f4 t4;
 #pragma unroll
       for (int k = 0; k < 4; ++k) t4[k] = (NEGA ? -ta[k] : ta[k]) + (NEGB ? -tb[k] : tb[k]);
-      *reinterpret_cast<f4*>(lds + ((j * Q + q) * L + l) * 4) = t4;
+      *reinterpret_cast<f4*>(lds + p * 4) = t4;
     }
   } else {
     for (int i = (int)threadIdx.x; i < C; i += WG) {

@@ -28,6 +28,9 @@ tensor's own scale.  Two refinements replace any blanket slack:
    by more than the tolerance, the element is ill-conditioned with respect to exactly those choices
    (a row sum whose 5000 terms cancel to 0.1, behind a function that is steep at zero, is the case
    the random-graph sweep found), and no fp32 implementation can be held to the tolerance there.
+   "More than the tolerance" is taken with a factor of four: the companions perturb by half an fp32
+   ulp per node, the device's transcendental ops are good to 1-2 ulp (log(x) for x = 1.0019: one ulp
+   of x is 1.2e-7 absolute in a tensor whose values are all ~1e-2 - another seed of the sweep).
    Those elements are counted and held to |gpu - A| <= 16*max(|A - B|, |A - C|) + tol instead; a
    plan with more than a tenth of its output elements flagged fails as a test case (it would test
    little).  The random-graph generator squashes every reduction through tanh / sigmoid, so rows
@@ -47,6 +50,10 @@ from workloads.graph import Node
 RTOL = {"f32": 1e-5, "bf16": 1e-2}
 MAX_ILL_FRACTION = 0.1
 ILL_SLACK = 16.0
+# A companion moves a value by half an fp32 ulp per node (B) or one rounding unit per term (C); the device's
+# transcendental ops are good to 1-2 ulp, i.e. up to four times B's perturbation.  An element is therefore flagged
+# as soon as four times the companions' gap would exceed the tolerance.
+ILL_THRESHOLD = 0.25
 THREADS = 16
 
 
@@ -71,7 +78,7 @@ def check_output(gpu: np.ndarray, ref: np.ndarray, dtype: str, what: str = "", c
     n_ill = 0
     if len(companions):
         gap = np.max([np.abs(_as_f64(c, dtype) - r) for c in companions], axis=0)
-        ill = gap > tol
+        ill = gap > ILL_THRESHOLD * tol
         n_ill = int(ill.sum())
         if n_ill:
             tol = np.where(ill, ILL_SLACK * gap + tol, tol)
