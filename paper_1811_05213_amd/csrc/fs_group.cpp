@@ -794,6 +794,11 @@ struct Former {
       valid[grp] = !members[grp].empty() && analyse_group(g, members[grp], group_of, grp, opt, &plan[grp]) == FS_OK;
     };
     for (size_t grp = 0; grp < members.size(); ++grp) analyse((int)grp);
+    // The scan restarts from the first pair after every merge (which merge comes first decides the result: merging
+    // is not confluent), but a pair whose merged group was analysed and refused is not analysed again until one of
+    // the two groups has changed: the analysis is the expensive part, and it depends on the two member sets only.
+    std::vector<int> version(members.size(), 0);
+    std::map<std::pair<size_t, size_t>, std::pair<int, int>> refused;
     bool changed = true;
     GroupPlan merged_plan;
     while (changed) {
@@ -824,10 +829,15 @@ struct Former {
           for (int c : successors((int)a)) cycle |= c != (int)b && reaches(c, (int)b);
           for (int c : successors((int)b)) cycle |= c != (int)a && reaches(c, (int)a);
           if (cycle) continue;
+          auto seen = refused.find({a, b});
+          if (seen != refused.end() && seen->second == std::make_pair(version[a], version[b])) continue;
           std::vector<int> merged = members[a];
           merged.insert(merged.end(), members[b].begin(), members[b].end());
-          if (analyse_group(g, merged, group_of, (int)a, opt, &merged_plan) != FS_OK) continue;
-          if (!worth_fusing(merged_plan)) continue;
+          if (analyse_group(g, merged, group_of, (int)a, opt, &merged_plan) != FS_OK || !worth_fusing(merged_plan)) {
+            refused[{a, b}] = {version[a], version[b]};
+            continue;
+          }
+          ++version[a];
           for (int m : members[b]) group_of[m] = (int)a;
           members[a] = merged;
           members[b].clear();
