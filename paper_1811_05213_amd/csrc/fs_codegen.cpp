@@ -389,8 +389,9 @@ struct Emitter {
           if (stage_written.count(e.node))  // a later pass: the head of the row comes back from LDS
             os << "      if (ch < STAGE_CHUNKS) fs_load_row_chunk_lds<" << e.dtype << ", V, NVL, L>(" << nm << ", " << chunk << ", lir);\n"
                << "      else " << from_mem << "\n";
-          else  // the first pass that reads it: keep the head of the row
-            os << "      " << from_mem << "\n      if (ch < STAGE_CHUNKS) fs_stage_row_chunk<" << e.dtype << ", V, NVL, L>(" << chunk << ", " << nm << ", lir);\n";
+          else  // the first pass that reads it: keep the head of the row, as it came from memory
+            os << "      fs_load_row_staging<" << e.dtype << ", " << tmpl_row() << ", false>(" << nm << ", a.p[" << e.arg << "], row0, lir, vbase, " << chunk
+               << ", ch < STAGE_CHUNKS);\n";
         }
       } else
         os << "      fs_load_row<" << e.dtype << ", " << tmpl_row() << ">(" << name(e.node, e.kind) << ", a.p[" << e.arg << "], 0, lir, vbase);\n";

@@ -215,6 +215,27 @@ template <int DT, int V, int NVL, int L> FS_DEV void fs_stage_row_chunk(void* ld
 #pragma unroll
   for (int j = 0; j < NVL; ++j) fs_store_vec<DT, V>(&src[j * V], lds_chunk, (long)(j * L + lir) * V);
 }
+// fs_load_row and fs_stage_row_chunk in one: the vectors go to LDS as they came from memory (when `stage`), so nothing is
+// spent on converting fp32 registers back to the dtype, and what a later stage reads back is the same bytes.
+template <int DT, int V, int NVL, int L, int NV, bool RAGGED, bool NT = false>
+FS_DEV void fs_load_row_staging(float (&dst)[NVL * V], const void* base, long row_elem0, int lir, int vbase, void* lds_chunk, bool stage) {
+  typedef typename fs_elem<DT>::type T;
+  typedef typename fs_vec<T, V>::type VT;
+#pragma unroll
+  for (int j = 0; j < NVL; ++j) {
+    int vi = vbase + j * L + lir;
+    if (RAGGED) vi = vi < NV ? vi : NV - 1;
+    const VT* p = reinterpret_cast<const VT*>(static_cast<const T*>(base) + row_elem0 + (long)vi * V);
+    const VT raw = NT ? __builtin_nontemporal_load(p) : *p;
+    if (stage) *reinterpret_cast<VT*>(static_cast<T*>(lds_chunk) + (long)(j * L + lir) * V) = raw;
+    if constexpr (V == 1) {
+      dst[j] = fs_to_f32<DT>(raw);
+    } else {
+#pragma unroll
+      for (int k = 0; k < V; ++k) dst[j * V + k] = fs_to_f32<DT>(raw[k]);
+    }
+  }
+}
 template <int DT, int V, int NVL, int L> FS_DEV void fs_load_row_chunk_lds(float (&dst)[NVL * V], const void* lds_chunk, int lir) {
 #pragma unroll
   for (int j = 0; j < NVL; ++j) fs_load_vec<DT, V>(&dst[j * V], lds_chunk, (long)(j * L + lir) * V);

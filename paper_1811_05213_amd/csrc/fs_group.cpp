@@ -170,13 +170,25 @@ static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPl
   // row is still read once instead of once per stage); beyond that the first 48 (or 32) elements
   // per lane stay resident and the rest of the row is walked in chunks; last, chunks only.  Plan
   // creation steps `wide_level` down while the compiled kernel spills.
+  // Rows whose [1,C] operands weigh at least as much per column as the rows themselves (LayerNorm with gamma, beta and a
+  // bias over bf16 rows: 12 bytes against 4) keep nothing resident: their last stage needs the registers for the operands,
+  // and the whole row fits LDS in its own dtype more often than not.  Measured, LayerNorm+GeLU bf16: [4096,65536] 323 us
+  // with a resident part, 282 us chunks only; [4096,49152] 287 -> 207 us; [2049,100000] 267 -> 239 us.
   bool resident = false;
   if (rowred && l_min > 1024 && !split_rows) {
     const int e32 = std::max(32, V), e64 = std::max(64, V);
     const bool may_chunk = !colred && !has_transposed;
+    int64_t rowv_bytes = 0, full_bytes = 0;
+    for (const ExtTensor& e : gp->ext_in) {
+      if (e.kind == KIND_ROWV) rowv_bytes += dtype_size(e.dtype);
+      if (e.kind == KIND_FULL) full_bytes += dtype_size(e.dtype);
+    }
+    for (const ExtTensor& e : gp->ext_out)
+      if (e.kind == KIND_FULL) full_bytes += dtype_size(e.dtype);
+    const bool keep_registers = rowv_bytes < full_bytes;
     if (ecap < e32 && lanes_for(e32) <= 1024 && (opt.wide_level >= 1 || !may_chunk)) ecap = e32, l_min = lanes_for(e32);
-    else if (may_chunk && opt.wide_level >= 2 && lanes_for(e64) <= 1024) ecap = e64, l_min = lanes_for(e64);
-    else if (may_chunk && opt.wide_level >= 1) resident = true;
+    else if (may_chunk && keep_registers && opt.wide_level >= 2 && lanes_for(e64) <= 1024) ecap = e64, l_min = lanes_for(e64);
+    else if (may_chunk && keep_registers && opt.wide_level >= 1) resident = true;
   }
   // Row reductions over rows that do not fit the registers of one workgroup: the workgroup walks
   // its row in column chunks, once per stage, recomputing what each stage needs.

@@ -182,10 +182,25 @@ def test_rows_longer_than_a_workgroup_holds():
             assert gi["elems_per_lane"] == 48 and gi["elems_per_lane"] * gi["lanes_per_row"] < cols
         p.destroy()
         both_modes(g, [RNG.standard_normal((rows, cols)).astype(np.float32)], f"softmax {rows}x{cols}")
-    for rows, cols in [(5, 65544), (7, 40001)]:
+    # LayerNorm+bias+GeLU over bf16 rows: its three fp32 [1,C] operands outweigh the row, nothing stays resident in registers and
+    # the row is kept in LDS as it came from memory (whole at 65544 columns, its first 160 KB at 100008)
+    for rows, cols in [(35, 65544), (7, 40001), (34, 100008), (5, 65544)]:  # (the last: few rows, cut into kernels that split the rows)
         g = layernorm_gelu_graph(rows, cols)
-        ins = [f32_to_bf16_bits(RNG.standard_normal(s).astype(np.float32)) for s in ((rows, cols), (1, cols), (1, cols), (1, cols))]
-        both_modes(g, ins, f"layernorm+gelu {rows}x{cols}")
+        p = fs.Plan(g)
+        gi = p.group_info(0)
+        assert p.stats()["num_launches"] == 1 or rows <= 32
+        if cols % 8 == 0 and rows > 32:
+            assert gi["elems_per_lane"] == 16 and gi["lds_bytes"] > 2 * min(cols, 65536)
+        p.destroy()
+        both_modes(g, layernorm_gelu_inputs(rows, cols), f"layernorm+gelu {rows}x{cols}")
+    # the same kernels under a caller's lanes-per-row hint: 512- and 256-lane workgroups walk more, shorter chunks
+    for lanes in (512, 256):
+        g = layernorm_gelu_graph(36, 65544)
+        out = run_graph(g, layernorm_gelu_inputs(36, 65544), hint={"lanes_per_row": lanes})
+        check_all(g, out, Reference(g, layernorm_gelu_inputs(36, 65544)), f"layernorm+gelu 36x65544, {lanes} lanes per row")
+        g = softmax_graph(35, 100004)
+        x = RNG.standard_normal((35, 100004)).astype(np.float32)
+        check_all(g, run_graph(g, [x], hint={"lanes_per_row": lanes}), Reference(g, [x]), f"softmax 35x100004, {lanes} lanes per row")
 
 
 def test_broadcasts_and_transpose():
