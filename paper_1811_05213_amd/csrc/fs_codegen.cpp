@@ -309,7 +309,10 @@ struct Emitter {
   // ---- rows walked in column chunks (Schedule::chunked) ----------------------------------------
   // [R,C] and [1,C] members (and tensors from memory) that `targets` depend on without crossing a
   // row reduction: what one pass over the row has to load and recompute.
-  void needed_for(const std::vector<int>& targets, std::set<int>* mem, std::set<int>* ext) {
+  // `avail`: members whose chunk is read back from LDS instead (buffered by an earlier pass): the walk stops there
+  // and lists them in `from_lds`.
+  void needed_for(const std::vector<int>& targets, std::set<int>* mem, std::set<int>* ext, const std::set<int>* avail = nullptr,
+                  std::set<int>* from_lds = nullptr) {
     std::vector<int> stack(targets);
     while (!stack.empty()) {
       const int id = stack.back();
@@ -322,6 +325,7 @@ struct Emitter {
         const Kind kd = gp.kind.at(src);
         if (kd == KIND_COLV) continue;  // one value per row: exists before the pass starts
         if (!in_set[src]) ext->insert(src);
+        else if (avail && avail->count(src)) from_lds->insert(src);
         else if (mem->insert(src).second) stack.push_back(src);
       }
     }
@@ -347,55 +351,59 @@ struct Emitter {
     }
   }
 
-  // One pass over the row: loads, the members of `mem` in id order, then `tail` per chunk.
+  // One pass over the row: loads, the members the targets need in id order, then `tail` per chunk.
   // Passes alternate their direction: a pass starts with the chunks its predecessor touched
   // last, the ones most likely still in the L2.
+  //
+  // Shared-memory planning (Section 5.1) for these kernels: a value that several passes need - an [R,C] input, or an
+  // elementwise result - may keep the first STAGE_CHUNKS chunks of the row in an LDS slot (GroupPlan::stage_slots, chosen
+  // by plan_stage_buffers below).  The first pass that loads / computes it writes the slot; later passes read it back
+  // and compute only what lies between it and their targets.  Chunks beyond STAGE_CHUNKS are recomputed from memory,
+  // as without the buffer: such a pass has two bodies, chosen per chunk.
   int n_passes = 0;
-  std::map<int, int> pass_loads;   // [R,C] input -> passes that load it (the dry run counts; see generate_kernel)
-  std::set<int> stage_written;     // staged inputs whose LDS copy has been written by an earlier pass
-  // byte offset of staged input `node`'s area inside lds_stage, or -1
+  std::map<int, int> pass_loads;     // [R,C] input -> passes that load it      } without buffers: the dry run's counts
+  std::map<int, int> pass_computes;  // [R,C] member -> passes that compute it  } (see plan_stage_buffers)
+  std::map<int, int> first_pass;     // ... and the first of them
+  std::map<int, int> pass_loads_planned;  // [R,C] input -> passes that load it where the row is buffered, with the plan's buffers in place
+  std::set<int> stage_written;       // buffered values whose slot has been written by an earlier pass
+  bool staged(int node) const { return gp.s.stage_chunks > 0 && gp.stage_slot_of.count(node) > 0; }
+  long chunk_bytes(int elem_bytes) const { return (long)gp.s.NVLC * gp.s.L * gp.s.V * elem_bytes; }
+  // byte offset of `node`'s slot inside lds_stage, or -1
   long stage_offset(int node) const {
+    auto it = gp.stage_slot_of.find(node);
+    if (it == gp.stage_slot_of.end()) return -1;
     long off = 0;
-    for (int sn : gp.staged_inputs) {
-      if (sn == node) return off;
-      off += (long)gp.s.stage_chunks * gp.s.NVLC * gp.s.L * gp.s.V * dtype_size(g.nodes[sn].dtype);
-    }
-    return -1;
+    for (int k = 0; k < it->second; ++k) off += gp.s.stage_chunks * chunk_bytes(gp.stage_slots[k].elem_bytes);
+    return off;
   }
+  std::string stage_chunk(int node) const {
+    return "lds_stage + " + std::to_string(stage_offset(node)) + " + (long)ch * " + std::to_string(chunk_bytes(dtype_size(g.nodes[node].dtype)));
+  }
+
   template <class Tail>
-  void emit_pass(const std::set<int>& mem, const std::set<int>& ext, bool store_outputs, Tail tail, const std::string& loop = "") {
-    if (!loop.empty()) os << "    " << loop << " {\n";
-    // (with a resident part the registers are nearly full: the chunk loop stays rolled, one chunk - 64 bytes per lane -
-    // in flight at a time, instead of the compiler interleaving several chunks and spilling on some builds)
-    else if (n_passes++ % 2 == 0) os << "    " << (gp.s.resident ? "_Pragma(\"unroll 1\") " : "") << "for (int ch = 0; ch < CT; ++ch) {\n";
-    else os << "    " << (gp.s.resident ? "_Pragma(\"unroll 1\") " : "") << "for (int ch = CT - 1; ch >= 0; --ch) {\n";
-    // (inside a pass the chunk's own sizes shadow the body's: the building blocks read them by name)
-    os << "      constexpr int NVL = NVLC, E = NVLC * V;\n      constexpr bool RAGGED = RAGC;\n"
-       << "      const int vbase = RESV + ch * (NVL * L);\n      (void)RAGGED;\n";
+  void emit_pass_body(const std::set<int>& mem, const std::set<int>& ext, const std::set<int>& from_lds, bool store_outputs, Tail tail) {
     for (const ExtTensor& e : gp.ext_in) {
       if (!ext.count(e.node)) continue;
       os << "      float " << name(e.node, e.kind) << "[E];\n";
       if (e.kind == KIND_FULL) {
-        ++pass_loads[e.node];
-        const long off = gp.s.stage_chunks > 0 ? stage_offset(e.node) : -1;
         const std::string nm = name(e.node, e.kind);
         const std::string from_mem = "fs_load_row<" + std::to_string(e.dtype) + ", " + tmpl_row() + ", false>(" + nm + ", a.p[" + std::to_string(e.arg) +
                                      "], row0, lir, vbase);";
-        if (off < 0) {
+        if (!staged(e.node)) {
           os << "      " << from_mem << "\n";
-        } else {
-          const std::string chunk = "lds_stage + " + std::to_string(off) + " + (long)ch * " +
-                                    std::to_string((long)gp.s.NVLC * gp.s.L * gp.s.V * dtype_size(e.dtype));
-          if (stage_written.count(e.node))  // a later pass: the head of the row comes back from LDS
-            os << "      if (ch < STAGE_CHUNKS) fs_load_row_chunk_lds<" << e.dtype << ", V, NVL, L>(" << nm << ", " << chunk << ", lir);\n"
-               << "      else " << from_mem << "\n";
-          else  // the first pass that reads it: keep the head of the row, as it came from memory
-            os << "      fs_load_row_staging<" << e.dtype << ", " << tmpl_row() << ", false>(" << nm << ", a.p[" << e.arg << "], row0, lir, vbase, " << chunk
-               << ", ch < STAGE_CHUNKS);\n";
+        } else if (stage_written.count(e.node)) {  // a later pass: the head of the row comes back from LDS
+          os << "      if (ch < STAGE_CHUNKS) fs_load_row_chunk_lds<" << e.dtype << ", V, NVL, L>(" << nm << ", " << stage_chunk(e.node) << ", lir);\n"
+             << "      else " << from_mem << "\n";
+        } else {  // the first pass that reads it: keep the head of the row, as it came from memory
+          os << "      fs_load_row_staging<" << e.dtype << ", " << tmpl_row() << ", false>(" << nm << ", a.p[" << e.arg << "], row0, lir, vbase, "
+             << stage_chunk(e.node) << ", ch < STAGE_CHUNKS);\n";
         }
       } else
         os << "      fs_load_row<" << e.dtype << ", " << tmpl_row() << ">(" << name(e.node, e.kind) << ", a.p[" << e.arg << "], 0, lir, vbase);\n";
     }
+    for (int m : from_lds)  // buffered by an earlier pass (only emitted for chunks below STAGE_CHUNKS)
+      os << "      float " << name(m, KIND_FULL) << "[E];\n      fs_load_row_chunk_lds<" << g.nodes[m].dtype << ", V, NVL, L>(" << name(m, KIND_FULL) << ", "
+         << stage_chunk(m) << ", lir);\n";
     for (int m : gp.members) {
       if (!mem.count(m) || folded[m]) continue;
       const fs_node& n = g.nodes[m];
@@ -403,6 +411,8 @@ struct Emitter {
       if (!is_alias(m))
         os << "      float " << name(m, k) << "[E];\n      _Pragma(\"unroll\") for (int e = 0; e < E; ++e) " << name(m, k) << "[e] = "
            << (n.opcode == FS_TRANSPOSE ? ref(n.in[0]) : rounded(m, expr(m))) << ";\n";
+      if (staged(m) && !stage_written.count(m))  // its first pass: the slot takes it over (from whatever it dominates)
+        os << "      if (ch < STAGE_CHUNKS) fs_stage_row_chunk<" << n.dtype << ", V, NVL, L>(" << stage_chunk(m) << ", " << name(m, k) << ", lir);\n";
       if (!store_outputs) continue;
       if (const ExtTensor* e = find_out(m)) {
         if (k == KIND_ROWV)
@@ -413,11 +423,58 @@ struct Emitter {
       }
     }
     tail();
+  }
+
+  // `targets`: what the pass is for (the stage's reductions, or the roots); `seed`: those of them the pass computes itself
+  template <class Tail>
+  void emit_pass(const std::vector<int>& targets, const std::set<int>& seed, bool store_outputs, Tail tail, const std::string& loop = "") {
+    std::set<int> avail;
+    for (int m : gp.members)
+      if (staged(m) && stage_written.count(m) && !seed.count(m)) avail.insert(m);
+    std::set<int> mem(seed), ext, mem_a(seed), ext_a, lds_a;
+    needed_for(targets, &mem, &ext);
+    if (!avail.empty()) needed_for(targets, &mem_a, &ext_a, &avail, &lds_a);
+    for (int m : mem) {
+      if (!first_pass.count(m)) first_pass[m] = n_passes;
+      if (!folded[m] && gp.kind.at(m) == KIND_FULL) ++pass_computes[m];
+    }
+    for (int x : ext)
+      if (gp.kind.at(x) == KIND_FULL) {
+        ++pass_loads[x];
+        if (!first_pass.count(x)) first_pass[x] = n_passes;
+      }
+    for (int t : targets)
+      if (!first_pass.count(t)) first_pass[t] = n_passes;
+    for (int x : lds_a.empty() ? ext : ext_a)  // what the pass loads for the chunks that are in LDS, under the current plan
+      if (gp.kind.at(x) == KIND_FULL) ++pass_loads_planned[x];
+    if (!loop.empty()) os << "    " << loop << " {\n";
+    // (with a resident part the registers are nearly full: the chunk loop stays rolled, one chunk - 64 bytes per lane -
+    // in flight at a time, instead of the compiler interleaving several chunks and spilling on some builds)
+    else if (n_passes % 2 == 0) os << "    " << (gp.s.resident ? "_Pragma(\"unroll 1\") " : "") << "for (int ch = 0; ch < CT; ++ch) {\n";
+    else os << "    " << (gp.s.resident ? "_Pragma(\"unroll 1\") " : "") << "for (int ch = CT - 1; ch >= 0; --ch) {\n";
+    ++n_passes;
+    // (inside a pass the chunk's own sizes shadow the body's: the building blocks read them by name)
+    os << "      constexpr int NVL = NVLC, E = NVLC * V;\n      constexpr bool RAGGED = RAGC;\n"
+       << "      const int vbase = RESV + ch * (NVL * L);\n      (void)RAGGED;\n";
+    if (lds_a.empty()) {
+      emit_pass_body(mem, ext, lds_a, store_outputs, tail);
+    } else if (gp.s.stage_chunks >= gp.s.CT) {  // the whole row is buffered
+      emit_pass_body(mem_a, ext_a, lds_a, store_outputs, tail);
+    } else {
+      os << "      if (ch < STAGE_CHUNKS) {\n";
+      emit_pass_body(mem_a, ext_a, lds_a, store_outputs, tail);
+      os << "      } else {\n";
+      emit_pass_body(mem, ext, std::set<int>(), store_outputs, tail);
+      os << "      }\n";
+    }
     os << "    }\n";
     // (a lane reads back exactly the LDS positions it wrote itself, and a wavefront's LDS accesses complete in order:
-    // no barrier between the pass that stages and the passes that read)
-    for (const ExtTensor& e : gp.ext_in)
-      if (e.kind == KIND_FULL && ext.count(e.node) && gp.s.stage_chunks > 0 && stage_offset(e.node) >= 0) stage_written.insert(e.node);
+    // no barrier between the pass that writes a slot and the passes that read it, nor before a value that dominates
+    // the slot's previous owner overwrites it in place)
+    for (int x : ext)
+      if (staged(x)) stage_written.insert(x);
+    for (int m : lds_a.empty() ? mem : mem_a)
+      if (staged(m) && !folded[m]) stage_written.insert(m);
   }
 
   // inside a pass: fold the chunk's elements into the running lane partials q<b> of the stage's reductions
@@ -460,21 +517,15 @@ struct Emitter {
       for (int m : gp.row_reduces)
         if (gp.level.at(m) == lvl) batch.push_back(m);
       if (batch.empty()) continue;
-      std::set<int> mem, ext;
-      needed_for(batch, &mem, &ext);
       for (int b : batch) os << "    float q" << loc(b) << " = fs_red_identity<" << g.nodes[b].attr_i << ">();\n";
-      emit_pass(mem, ext, false, [&]() { emit_chunk_accumulate(batch); });
+      emit_pass(batch, std::set<int>(), false, [&]() { emit_chunk_accumulate(batch); });
       emit_exchange(batch, xwave, WPR, KB, "    ");
     }
     // last pass: everything that leaves the kernel as an [R,C] or [1,C] tensor
     std::vector<int> roots;
     for (const ExtTensor& e : gp.ext_out)
       if (e.kind != KIND_COLV) roots.push_back(e.node);
-    if (!roots.empty()) {
-      std::set<int> mem(roots.begin(), roots.end()), ext;
-      needed_for(roots, &mem, &ext);
-      emit_pass(mem, ext, true, []() {});
-    }
+    if (!roots.empty()) emit_pass(roots, std::set<int>(roots.begin(), roots.end()), true, []() {});
     os << "  }\n}\n";
   }
 
@@ -501,13 +552,12 @@ struct Emitter {
     // one pass over the segment: the reductions' operands, and what leaves the kernel as [R,C] or [1,C]
     // tensors (all of it computed before any reduction result)
     std::vector<int> targets(gp.row_reduces);
-    std::set<int> mem, ext;
+    std::set<int> seed;
     for (const ExtTensor& e : gp.ext_out)
-      if (e.kind != KIND_COLV) targets.push_back(e.node), mem.insert(e.node);
-    needed_for(targets, &mem, &ext);
+      if (e.kind != KIND_COLV) targets.push_back(e.node), seed.insert(e.node);
     for (int b : gp.row_reduces) os << "  float q" << loc(b) << " = fs_red_identity<" << g.nodes[b].attr_i << ">();\n";
     os << "  {\n    const int ch_end = (seg + 1) * CPS < CT ? (seg + 1) * CPS : CT;\n";
-    emit_pass(mem, ext, true, [&]() { emit_chunk_accumulate(gp.row_reduces); }, "for (int ch = seg * CPS; ch < ch_end; ++ch)");
+    emit_pass(targets, seed, true, [&]() { emit_chunk_accumulate(gp.row_reduces); }, "for (int ch = seg * CPS; ch < ch_end; ++ch)");
     os << "  }\n";
     // fold the workgroup's lanes (the results are not rounded or divided yet: that happens once, at the end)
     for (int b : gp.row_reduces)
@@ -543,6 +593,178 @@ struct Emitter {
       if (e.kind == KIND_COLV)
         os << "      fs_store1<" << e.dtype << ">(a.p[" << e.arg << "], row, " << name(source_of(e.node), KIND_COLV) << ");\n";
     os << "    }\n  }\n}\n";
+  }
+
+  // ---- shared-memory planning for rows walked in chunks (Section 5.1) ----------------------------
+  // Called on a dry run (no buffers yet), whose passes counted who needs what.
+  //   size requirements (5.1.1)  candidates are the values several passes need: [R,C] inputs that more than one pass
+  //                              loads, and elementwise results whose direct users belong to more than one pass
+  //                              (multiple users, in different loops of the kernel); each would take one row in its
+  //                              own dtype.
+  //   space sharing (5.1.3)      dominance tree from the roots over the group's data flow: a candidate that dominates
+  //                              a buffered value of the same element size, and is first computed no earlier, takes
+  //                              over that value's slot - everything that still needs the old value gets it through
+  //                              the new one (softmax: exp(x - max) overwrites x; LayerNorm on fp32 rows: x - mean
+  //                              overwrites x).  Sharing costs nothing, so it is applied before anything is given up.
+  //   size shrinking (5.1.2)     while the slots of a whole row exceed the budget, candidates that need a slot of their own
+  //                              are given up - recomputed by every pass instead - in the paper's order: results of
+  //                              inexpensive ops first, then of expensive ones (exp, log, tanh, sigmoid, gelu, divide,
+  //                              sqrt, rsqrt, rcp), the one closest to the roots first within a class.  Inputs are
+  //                              never given up (recomputing them means HBM traffic, the bound): if they alone exceed
+  //                              the budget, all slots keep only the head of the row (stage_chunks < CT).
+  static bool op_is_expensive(int op) {
+    return op == FS_EXP || op == FS_LOG || op == FS_TANH || op == FS_SIGMOID || op == FS_GELU_TANH || op == FS_DIV || op == FS_SQRT ||
+           op == FS_RSQRT || op == FS_RCP;
+  }
+  static const char* op_word(int op) {
+    switch (op) {
+      case FS_INPUT: return "input";
+      case FS_NEG: return "neg";
+      case FS_ABS: return "abs";
+      case FS_EXP: return "exp";
+      case FS_LOG: return "log";
+      case FS_TANH: return "tanh";
+      case FS_SIGMOID: return "sigmoid";
+      case FS_SQRT: return "sqrt";
+      case FS_RSQRT: return "rsqrt";
+      case FS_RCP: return "rcp";
+      case FS_GELU_TANH: return "gelu";
+      case FS_CONVERT: return "convert";
+      case FS_ADD: return "add";
+      case FS_SUB: return "sub";
+      case FS_MUL: return "mul";
+      case FS_DIV: return "div";
+      case FS_MAX: return "max";
+      case FS_MIN: return "min";
+      case FS_CMP: return "cmp";
+      case FS_SELECT: return "select";
+    }
+    return "op";
+  }
+  void plan_stage_buffers(const std::set<int>& unbuffered_inputs) {
+    gp.stage_slots.clear();
+    gp.stage_slot_of.clear();
+    gp.stage_given_up.clear();
+    gp.lds_plan_text.clear();
+    gp.s.stage_chunks = 0;
+    const int ROOT = -1;
+    // data flow seen from the roots: consumer -> operand edges, a virtual root above every output
+    std::map<int, std::vector<int>> consumers;
+    for (int u : gp.members) {
+      const fs_node& n = g.nodes[u];
+      for (int k = 0; k < n.num_in; ++k) {
+        if (g.nodes[n.in[k]].opcode == FS_CONST) continue;
+        const int src = source_of(n.in[k]);
+        if (g.nodes[src].opcode == FS_CONST) continue;
+        consumers[src].push_back(u);
+      }
+    }
+    for (const ExtTensor& e : gp.ext_out) consumers[e.node].push_back(ROOT);
+    // immediate dominators (node ids are topological: consumers have larger ids, so descending order visits them first)
+    std::map<int, int> idom, depth, dist;
+    depth[ROOT] = 0, dist[ROOT] = 0;
+    std::vector<int> order;
+    for (const auto& kv : consumers) order.push_back(kv.first);
+    std::sort(order.rbegin(), order.rend());
+    auto intersect = [&](int x, int y) {
+      while (x != y) {
+        if (depth.at(x) > depth.at(y)) x = idom.at(x);
+        else y = idom.at(y);
+      }
+      return x;
+    };
+    for (int n : order) {
+      int dom = -2, d = 1 << 30;
+      for (int c : consumers[n]) {
+        if (!depth.count(c)) continue;  // (a consumer nothing reaches from the roots)
+        dom = dom == -2 ? c : intersect(dom, c);
+        d = std::min(d, dist.at(c) + 1);
+      }
+      if (dom == -2) continue;
+      idom[n] = dom, depth[n] = depth.at(dom) + 1, dist[n] = d;
+    }
+    auto dominates = [&](int b, int x) {  // b strictly above x in the dominance tree
+      if (!depth.count(b) || !depth.count(x)) return false;
+      while (depth.at(x) > depth.at(b)) x = idom.at(x);
+      return x == b && depth.at(x) == depth.at(b) && b != ROOT;
+    };
+    // candidates in the order their first pass comes (inputs before what is computed from them)
+    struct Cand { int node; bool input; int first; };
+    std::vector<Cand> cands;
+    for (const ExtTensor& e : gp.ext_in)
+      if (e.kind == KIND_FULL && pass_loads[e.node] >= 2 && !unbuffered_inputs.count(e.node)) cands.push_back({e.node, true, first_pass[e.node]});
+    for (int m : gp.members) {
+      const fs_node& n = g.nodes[m];
+      if (gp.kind.at(m) != KIND_FULL || folded[m] || find_out(m) || is_alias(m)) continue;
+      std::set<int> homes;  // the passes its direct users belong to (where each is computed first)
+      for (int u : consumers[m])
+        if (u != ROOT && first_pass.count(u)) homes.insert(first_pass.at(u));
+      if (homes.size() < 2) continue;
+      if (n.opcode == FS_CONVERT || n.opcode == FS_TRANSPOSE || n.opcode == FS_CONCAT || (n.dtype != FS_F32 && n.dtype != FS_BF16)) continue;
+      cands.push_back({m, false, first_pass[m]});
+    }
+    std::stable_sort(cands.begin(), cands.end(), [](const Cand& x, const Cand& y) { return x.first != y.first ? x.first < y.first : x.node < y.node; });
+    std::vector<int> own;  // intermediates that would need a slot of their own
+    for (const Cand& c : cands) {
+      const int eb = dtype_size(g.nodes[c.node].dtype);
+      int share = -1;
+      if (!c.input)
+        for (size_t k = 0; k < gp.stage_slots.size() && share < 0; ++k) {
+          const int prev = gp.stage_slots[k].owners.back();
+          if (gp.stage_slots[k].elem_bytes == eb && dominates(c.node, prev) && first_pass[prev] <= c.first) share = (int)k;
+        }
+      if (share >= 0) {
+        gp.stage_slots[share].owners.push_back(c.node);
+        gp.stage_slot_of[c.node] = share;
+        continue;
+      }
+      if (!c.input) own.push_back(c.node);
+      gp.stage_slot_of[c.node] = (int)gp.stage_slots.size();
+      gp.stage_slots.push_back(StageSlot{eb, {c.node}});
+    }
+    auto row_bytes = [&]() {
+      long b = 0;
+      for (const StageSlot& sl : gp.stage_slots) b += gp.s.CT * chunk_bytes(sl.elem_bytes);
+      return b;
+    };
+    // shrinking: give up own-slot intermediates while the whole row does not fit
+    std::stable_sort(own.begin(), own.end(), [&](int x, int y) {
+      const int cx = op_is_expensive(g.nodes[x].opcode), cy = op_is_expensive(g.nodes[y].opcode);
+      if (cx != cy) return cx < cy;
+      return dist.at(x) < dist.at(y);
+    });
+    for (size_t k = 0; k < own.size() && row_bytes() > gp.s.stage_avail; ++k) {
+      const int slot = gp.stage_slot_of.at(own[k]);
+      for (int o : gp.stage_slots[slot].owners) {
+        gp.stage_given_up.push_back({o, op_is_expensive(g.nodes[o].opcode) ? 2 : 1});
+        gp.stage_slot_of.erase(o);
+      }
+      gp.stage_slots.erase(gp.stage_slots.begin() + slot);
+      for (auto& kv : gp.stage_slot_of)
+        if (kv.second > slot) --kv.second;
+    }
+    long per_chunk = 0;
+    for (const StageSlot& sl : gp.stage_slots) per_chunk += chunk_bytes(sl.elem_bytes);
+    if (per_chunk > 0) gp.s.stage_chunks = (int)std::min<long>(gp.s.CT, gp.s.stage_avail / per_chunk);
+    if (gp.s.stage_chunks <= 0) {
+      gp.s.stage_chunks = 0;
+      gp.stage_slots.clear();
+      gp.stage_slot_of.clear();
+    }
+    // in words
+    std::ostringstream t;
+    t << "LDS plan: " << gp.s.stage_chunks << " of " << gp.s.CT << " chunks per row";
+    for (size_t k = 0; k < gp.stage_slots.size(); ++k) {
+      t << "; slot " << k << " (" << gp.stage_slots[k].elem_bytes << " B/element): ";
+      for (size_t o = 0; o < gp.stage_slots[k].owners.size(); ++o) {
+        const int node = gp.stage_slots[k].owners[o];
+        t << (o ? ", then " : "") << name(node, KIND_FULL) << " " << op_word(g.nodes[node].opcode) << (o ? " (dominates it)" : "");
+      }
+    }
+    for (const auto& gu : gp.stage_given_up)
+      t << "; recomputed instead: " << name(gu.first, KIND_FULL) << " " << op_word(g.nodes[gu.first].opcode)
+        << (gu.second == 2 ? " (expensive" : " (inexpensive") << ", its own slot would exceed the budget)";
+    gp.lds_plan_text = t.str();
   }
 
   void run(const std::string& kname) {
@@ -599,10 +821,11 @@ struct Emitter {
     if (s.chunked) {
       os << "  constexpr int NVLC = " << s.NVLC << ", RESV = " << s.RESV << ";\n  constexpr bool RAGC = " << (s.ragged_chunks ? "true" : "false")
          << ";\n";
-      if (s.stage_chunks > 0 && !gp.staged_inputs.empty()) {
+      if (s.stage_chunks > 0 && !gp.stage_slots.empty()) {
         long bytes = 0;
-        for (int sn : gp.staged_inputs) bytes += (long)s.stage_chunks * s.NVLC * s.L * s.V * dtype_size(g.nodes[sn].dtype);
-        os << "  constexpr int STAGE_CHUNKS = " << s.stage_chunks << ";  // chunks of every staged input kept in LDS\n"
+        for (const StageSlot& sl : gp.stage_slots) bytes += s.stage_chunks * chunk_bytes(sl.elem_bytes);
+        os << "  // " << gp.lds_plan_text << "\n";
+        os << "  constexpr int STAGE_CHUNKS = " << s.stage_chunks << ";  // chunks of every buffered value kept in LDS\n"
            << "  __shared__ __attribute__((aligned(16))) unsigned char lds_stage[" << bytes << "];\n";
       }
       if (s.split_rows) {
@@ -864,11 +1087,8 @@ struct Emitter {
             os << "    float " << q << " = fs_lane_reduce<" << bn.attr_i << ", " << tmpl_row() << ">(" << arr << ", lir);\n";
           }
         }
-        if (s.resident) {  // the part of the row that is not resident: walked in chunks, recomputed from the inputs
-          std::set<int> mem, ext;
-          needed_for(batch, &mem, &ext);
-          emit_pass(mem, ext, false, [&]() { emit_chunk_accumulate(batch); });
-        }
+        if (s.resident)  // the part of the row that is not resident: walked in chunks, recomputed from the inputs or read back from LDS
+          emit_pass(batch, std::set<int>(), false, [&]() { emit_chunk_accumulate(batch); });
         for (int b : batch) {
           const std::string q = "q" + std::to_string(loc(b));
           os << "    " << q << " = fs_segment_allreduce<" << g.nodes[b].attr_i << ", (L < 64 ? L : 64)>(" << q << ");\n";
@@ -939,11 +1159,7 @@ struct Emitter {
       std::vector<int> roots;
       for (const ExtTensor& e : gp.ext_out)
         if (e.kind != KIND_COLV) roots.push_back(e.node);
-      if (!roots.empty()) {
-        std::set<int> mem(roots.begin(), roots.end()), ext;
-        needed_for(roots, &mem, &ext);
-        emit_pass(mem, ext, true, []() {});
-      }
+      if (!roots.empty()) emit_pass(roots, std::set<int>(roots.begin(), roots.end()), true, []() {});
     }
     os << "  }\n";
 
@@ -987,25 +1203,32 @@ uint64_t fnv1a(const std::string& s) {
 }  // namespace
 
 fs_status generate_kernel(const Graph& g, GroupPlan* gp, int /*group_index*/) {
-  // Rows walked in chunks: a dry run counts how many passes load each [R,C] input; those that more than one pass
-  // loads keep their first chunks in the LDS the planner left over (inputs before intermediates: what a buffer
-  // saves there is HBM traffic, the bound, whereas an intermediate is recomputed from it with a few ALU operations
-  // - the order of Section 5.1.2, cheap values dropped first, with memory traffic as the cost).
-  gp->staged_inputs.clear();
+  // Rows walked in chunks: a dry run counts which passes load each [R,C] input and compute each elementwise result;
+  // plan_stage_buffers turns that into the kernel's LDS buffers (Section 5.1).
+  gp->stage_slots.clear();
+  gp->stage_slot_of.clear();
+  gp->stage_given_up.clear();
+  gp->lds_plan_text.clear();
   gp->s.stage_chunks = 0;
   long stage_bytes = 0;
   if (gp->s.chunked && !gp->s.split_rows && gp->s.stage_avail > 0) {
     Emitter dry(g, *gp);
     dry.run("FSK");
-    long per_chunk = 0;
-    for (const ExtTensor& e : gp->ext_in)
-      if (e.kind == KIND_FULL && dry.pass_loads[e.node] >= 2) {
-        gp->staged_inputs.push_back(e.node);
-        per_chunk += (long)gp->s.NVLC * gp->s.L * gp->s.V * dtype_size(e.dtype);
-      }
-    if (per_chunk > 0) gp->s.stage_chunks = (int)std::min<long>(gp->s.CT, gp->s.stage_avail / per_chunk);
-    if (gp->s.stage_chunks <= 0) gp->staged_inputs.clear(), gp->s.stage_chunks = 0;
-    stage_bytes = per_chunk * gp->s.stage_chunks;
+    dry.plan_stage_buffers(std::set<int>());
+    // An input whose every later use now goes through a buffered result no longer needs a slot of its own (masked
+    // softmax: once x * scale + mask is buffered, neither x nor the mask is read again): plan again without it.
+    std::set<int> unbuffered;
+    for (int round = 0; round < 8 && !gp->stage_slots.empty(); ++round) {
+      Emitter check(g, *gp);
+      check.run("FSK");
+      bool changed = false;
+      for (const StageSlot& sl : gp->stage_slots)
+        if (sl.owners.size() == 1 && !check.in_set[sl.owners[0]] && check.pass_loads_planned[sl.owners[0]] < 2)
+          changed |= unbuffered.insert(sl.owners[0]).second;
+      if (!changed) break;
+      dry.plan_stage_buffers(unbuffered);
+    }
+    for (const StageSlot& sl : gp->stage_slots) stage_bytes += gp->s.stage_chunks * dry.chunk_bytes(sl.elem_bytes);
   }
   // first pass with a placeholder name to hash the structure, second pass with the real name
   std::string text;

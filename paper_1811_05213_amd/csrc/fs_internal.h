@@ -129,10 +129,11 @@ struct Schedule {
   bool resident = false;
   int NVLC = 0, RESV = 0;
   bool ragged_chunks = false;
-  // ... and with the first `stage_chunks` chunks of every [R,C] input that more than one pass reads kept in LDS
-  // in the input's own dtype: written by the first pass that loads them, read back by the later ones, so the
-  // row crosses HBM once instead of once per stage (Section 5.1.1: values needed by several loops of the kernel
-  // are the ones shared memory is allocated for).  stage_avail: LDS bytes the planner leaves for it.
+  // ... and with the first `stage_chunks` chunks of every value that more than one pass needs and that got an LDS
+  // slot (GroupPlan::stage_slots) kept in LDS in the value's own dtype: written by the first pass that loads or
+  // computes it, read back by the later ones, so the row crosses HBM once instead of once per stage (Section 5.1.1:
+  // values needed by several loops of the kernel are the ones shared memory is allocated for).  stage_avail: LDS
+  // bytes the planner leaves for it.
   int stage_avail = 0, stage_chunks = 0;
   // Column reductions over rows too wide for one workgroup: CT column tiles, each folded by its own
   // RB = grid / CT workgroups (tile = block % CT).  Strides of one tile's scratch in the workspace:
@@ -140,6 +141,15 @@ struct Schedule {
   int RB = 0;
   size_t part_stride_floats = 0;
   int ticket_stride = 0;
+};
+
+// One LDS buffer of a kernel that walks its rows in chunks (Section 5.1): it holds the first stage_chunks chunks of one row
+// value at a time, stored in that value's dtype.  `owners` are the values that occupy it one after the other (space
+// sharing, Section 5.1.3): each later owner dominates its predecessor in the group's data flow seen from the roots, so
+// once it exists nothing needs the predecessor any more, and it overwrites it in place, lane by lane.
+struct StageSlot {
+  int elem_bytes = 0;
+  std::vector<int> owners;
 };
 
 struct GroupPlan {
@@ -151,7 +161,11 @@ struct GroupPlan {
   std::vector<ExtTensor> ext_in, ext_out;
   std::vector<int> row_reduces;  // REDUCE_ROW members that need a cross-lane exchange
   std::vector<int> col_reduces;  // REDUCE_COL members finished by the grid-wide fold
-  std::vector<int> staged_inputs; // chunked kernels: [R,C] inputs whose first stage_chunks chunks are kept in LDS (filled by generate_kernel)
+  // chunked kernels: the LDS buffers for values that several passes over the row need (filled by generate_kernel)
+  std::vector<StageSlot> stage_slots;
+  std::map<int, int> stage_slot_of;             // buffered value (input or member) -> slot
+  std::vector<std::pair<int, int>> stage_given_up;  // candidates that are recomputed instead (Section 5.1.2): (member, 1 = inexpensive op | 2 = expensive op)
+  std::string lds_plan_text;                    // the above in words (a comment in the kernel source)
   int max_batched_reduces = 0;   // largest number of row reductions sharing one exchange
   Schedule s;
   // workspace scratch (byte offsets inside the plan workspace)

@@ -322,6 +322,58 @@ def test_ragged_and_degenerate_shapes_plan():
         == "FS_ERR_UNSUPPORTED"
 
 
+def _lds_plan(graph, **kw):
+    p = fs.Plan(graph, **kw)
+    try:
+        lines = [ln.strip() for ln in p.group_source(0).splitlines() if "LDS plan:" in ln]
+        assert len(lines) == 1, lines
+        return lines[0], p.group_info(0), p.group_source(0)
+    finally:
+        p.destroy()
+
+
+def _layernorm_f32(rows, cols):
+    g = Graph()
+    x, gam, bet = g.input(rows, cols), g.input(1, cols), g.input(1, cols)
+    xc = g.binary("sub", x, g.bcast_colvec(g.reduce_row("mean", x), cols))
+    rstd = g.unary("rsqrt", g.binary("add", g.reduce_row("mean", g.binary("mul", xc, xc)), g.const(1e-5, rows, 1)))
+    g.set_outputs([g.binary("add", g.binary("mul", g.binary("mul", xc, g.bcast_colvec(rstd, cols)), g.bcast_rowvec(gam, rows)), g.bcast_rowvec(bet, rows))])
+    return g
+
+
+def test_shared_memory_planning_for_rows_walked_in_chunks():
+    # Section 5.1 for kernels that walk a row once per stage: what several passes need may keep (the head of) the row in LDS.
+    from workloads.patterns import masked_softmax
+    # space sharing (5.1.3): exp(x - max) has users in two passes (the row sum, the division), dominates x seen from the root and
+    # has x's element size: it takes over x's slot, and the last pass reads it back instead of computing exp again
+    plan, gi, src = _lds_plan(softmax_graph(2048, 100000))
+    assert re.search(r"slot 0 \(4 B/element\): v\d+ input, then v\d+ exp \(dominates it\)$", plan), plan
+    assert "slot 1" not in plan and "recomputed instead" not in plan
+    last_pass = src[src.rindex("for (int ch = 0; ch < CT; ++ch)"):]
+    buffered, recomputed = last_pass.split("} else {")
+    assert "fs_exp" not in buffered and "fs_load_row_chunk_lds" in buffered and "fs_exp" in recomputed  # (chunks beyond the LDS head: as without the buffer)
+    # x - max has one user (exp): not a candidate
+    assert " sub" not in plan
+    # LayerNorm on fp32 rows: x - mean (users: the variance pass, the last pass) overwrites x
+    plan, gi, src = _lds_plan(_layernorm_f32(512, 40000))
+    assert re.search(r"slot 0 \(4 B/element\): v\d+ input, then v\d+ sub \(dominates it\)$", plan), plan
+    # ... on bf16 rows it cannot (an fp32 result does not fit a bf16 slot lane by lane) and a slot of its own (4 B/element) beside
+    # the row exceeds the LDS: given up, i.e. recomputed by each pass (size shrinking, 5.1.2), while the input keeps the whole row
+    plan, gi, src = _lds_plan(layernorm_gelu_graph(4096, 65536))
+    assert plan.startswith("// LDS plan: 4 of 4 chunks per row; slot 0 (2 B/element): v0 input")
+    assert re.search(r"recomputed instead: v\d+ sub \(inexpensive", plan) and gi["lds_bytes"] >= 131072
+    # the order in which buffers are given up: results of inexpensive ops before those of expensive ones
+    plan, gi, src = _lds_plan(masked_softmax(512, 70000))
+    assert plan.index("add (inexpensive") < plan.index("exp (expensive") and "slot 1 (2 B/element)" in plan
+    # an input that is only read on the way to a buffered result needs no slot of its own: on fp32 rows x * scale + mask takes over
+    # x's slot in the first pass, and the mask is never read again
+    plan, gi, src = _lds_plan(masked_softmax(512, 70000, "f32"))
+    assert re.search(r"slot 0 \(4 B/element\): v\d+ input, then v\d+ add \(dominates it\), then v\d+ exp \(dominates it\)$", plan), plan
+    # a caller's LDS budget bounds the buffers: only the head of the row is kept
+    plan, gi, src = _lds_plan(softmax_graph(2048, 100000), lds_budget_bytes=70000)
+    assert plan.startswith("// LDS plan: 1 of 4 chunks per row") and gi["lds_bytes"] <= 70000
+
+
 def test_performance_library_drives_the_schedule(tmp_path, monkeypatch):
     # schedule tuning = enumerate the candidates, look each kernel up in the library, keep the fastest recorded one
     lib_file = tmp_path / "perflib.tsv"

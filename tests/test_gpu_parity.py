@@ -203,6 +203,37 @@ def test_rows_longer_than_a_workgroup_holds():
         check_all(g, run_graph(g, [x], hint={"lanes_per_row": lanes}), Reference(g, [x]), f"softmax 35x100004, {lanes} lanes per row")
 
 
+def test_lds_buffered_results_on_long_rows():
+    # rows beyond the registers with elementwise results kept in LDS between the passes (they take over the slot of the input they
+    # dominate): fp32 softmax (exp), fp32 LayerNorm (x - mean), fp32 masked softmax (x * scale + mask, then exp); rows whose head only
+    # fits the LDS run both forms of the last pass (read back below STAGE_CHUNKS, recomputed from memory beyond)
+    from workloads.patterns import masked_softmax
+    g = Graph()
+    rows, cols = 40, 40000
+    x, gam, bet = g.input(rows, cols), g.input(1, cols), g.input(1, cols)
+    xc = g.binary("sub", x, g.bcast_colvec(g.reduce_row("mean", x), cols))
+    rstd = g.unary("rsqrt", g.binary("add", g.reduce_row("mean", g.binary("mul", xc, xc)), g.const(1e-5, rows, 1)))
+    g.set_outputs([g.binary("add", g.binary("mul", g.binary("mul", xc, g.bcast_colvec(rstd, cols)), g.bcast_rowvec(gam, rows)), g.bcast_rowvec(bet, rows))])
+    p = fs.Plan(g)
+    assert "sub (dominates it)" in p.group_source(0) and "if (ch < STAGE_CHUNKS) {" in p.group_source(0)
+    p.destroy()
+    ins = [(0.5 + RNG.standard_normal((rows, cols))).astype(np.float32), RNG.normal(1, .1, (1, cols)).astype(np.float32), RNG.normal(0, .1, (1, cols)).astype(np.float32)]
+    both_modes(g, ins, "layernorm fp32 40x40000")
+    for dt in ("f32", "bf16"):
+        for rows, cols in ((36, 70000), (33, 131080)):
+            g = masked_softmax(rows, cols, dt)
+            v = [RNG.standard_normal((rows, cols)).astype(np.float32) * 4, np.where(RNG.random((rows, cols)) < 0.2, -30.0, 0.0).astype(np.float32)]
+            both_modes(g, [f32_to_bf16_bits(a) if dt == "bf16" else a for a in v], f"masked softmax {dt} {rows}x{cols}")
+    g = softmax_graph(40, 100000)
+    x = RNG.standard_normal((40, 100000)).astype(np.float32)
+    ref = Reference(g, [x])
+    for budget in (0, 70000, 20000):  # all the LDS the device allows, a head of one chunk, no room for any chunk
+        p = fs.Plan(g, lds_budget_bytes=budget)
+        assert ("exp (dominates it)" in p.group_source(0)) == (budget != 20000)
+        p.destroy()
+        check_all(g, run_graph(g, [x], lds_budget_bytes=budget), ref, f"softmax 40x100000, LDS budget {budget}")
+
+
 def test_broadcasts_and_transpose():
     rows, cols = 130, 72
     g = Graph()
