@@ -9,7 +9,10 @@ import numpy as np
 from workloads import Graph, f32_to_bf16_bits
 
 
-def random_graph(seed: int, rows: int, cols: int, num_ops: int = 40):
+def random_graph(seed: int, rows: int, cols: int, num_ops: int = 40, views: bool = False):
+    """views=True adds the shape-modulation ops: reshapes / bitcasts to another factorisation of the same elements (with
+    elementwise work and row reductions in that other shape, and the way back), and concats along columns and rows.
+    (A switch, not a change of the op mix: graphs of seeds generated without it stay what they were.)"""
     rng = np.random.default_rng(seed)
     g = Graph()
     # pools of f32 node ids by shape class
@@ -32,7 +35,48 @@ def random_graph(seed: int, rows: int, cols: int, num_ops: int = 40):
     def pick(pool):
         return pool[int(rng.integers(len(pool)))]
 
+    # the other factorisation of rows*cols elements that views lead to, and the halves that concats join
+    if cols % 2 == 0 and cols >= 2:
+        alt_shape = (rows * 2, cols // 2)
+    elif rows % 2 == 0:
+        alt_shape = (rows // 2, cols * 2)
+    else:
+        alt_shape = (1, rows * cols)
+    alt = []     # values of shape alt_shape
+    outs_extra = []
     for _ in range(num_ops):
+        if views and rng.random() < 0.18:
+            which = rng.choice(["there", "work", "back", "ccols", "crows"])
+            name = "bitcast" if rng.random() < 0.3 else "reshape"
+            if which == "there" or (which in ("work", "back") and not alt):
+                alt.append(g.reshape(bounded(pick(full)), alt_shape[0], alt_shape[1], op=name))
+            elif which == "work":  # arithmetic and a row reduction in the other shape
+                a = bounded(pick(alt))
+                b = g.input(alt_shape[0], alt_shape[1]) if rng.random() < 0.5 else pick(alt)
+                t = g.binary(rng.choice(["add", "mul", "sub"]), a, bounded(b))
+                if rng.random() < 0.5:
+                    r = g.reduce_row(rng.choice(["sum", "max", "mean"]), t)
+                    outs_extra.append(r)
+                    t = g.binary("sub", t, g.bcast_colvec(bounded(r), alt_shape[1]))
+                alt.append(t)
+            elif which == "back":
+                full.append(g.reshape(pick(alt), rows, cols, op=name))
+            elif which == "ccols" and cols >= 2:
+                c0 = int(rng.integers(1, cols))
+                if rng.random() < 0.5 and cols >= 8:
+                    c0 = max(4, (c0 // 4) * 4) if c0 >= 4 else 4  # a seam that vector accesses can respect
+                    c0 = min(c0, cols - 1)
+                left = bounded(g.input(rows, c0)) if rng.random() < 0.5 else g.input(rows, c0)
+                right = g.input(rows, cols - c0)
+                full.append(g.concat(left, right, "cols"))
+            elif which == "crows" and rows >= 2:
+                r0 = int(rng.integers(1, rows))
+                top = g.input(r0, cols)
+                bottom = g.unary("tanh", g.input(rows - r0, cols)) if rng.random() < 0.5 else g.input(rows - r0, cols)
+                full.append(g.concat(top, bottom, "rows"))
+            else:
+                full.append(g.unary("neg", bounded(pick(full))))
+            continue
         kind = rng.choice(["unary", "binary", "bcast", "cmpsel", "bf16", "rrow", "rcol", "transpose", "vec"],
                           p=[0.22, 0.22, 0.14, 0.08, 0.06, 0.1, 0.06, 0.06, 0.06])
         if kind == "unary":
@@ -85,11 +129,23 @@ def random_graph(seed: int, rows: int, cols: int, num_ops: int = 40):
         used.update(n.ins)
     free = ("input", "const", "bcast_rowvec", "bcast_colvec")
     sinks = [i for i, n in enumerate(g.nodes) if i not in used and n.op not in free]
+    sinks += [o for o in outs_extra if o not in sinks]
     # a few interior values and a predicate leave as well; one output in bf16
     extra = [int(x) for x in rng.choice(full[2:] if len(full) > 2 else full, size=min(3, max(1, len(full) - 2)), replace=False)]
     outs = list(dict.fromkeys(sinks + extra + preds[:1]))
     outs = [o for o in outs if g.nodes[o].op not in free]
-    g.set_outputs(outs)
+    # (a value and a view of it, or two views of one value, cannot both be plan outputs: they would be one buffer)
+    def root(o):
+        while g.nodes[o].op in ("reshape", "bitcast"):
+            o = g.nodes[o].ins[0]
+        return o
+    seen, kept = set(), []
+    for o in outs:
+        if root(o) in seen or g.nodes[root(o)].op in free:
+            continue
+        seen.add(root(o))
+        kept.append(o)
+    g.set_outputs(kept)
     return g
 
 

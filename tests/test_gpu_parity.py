@@ -743,11 +743,11 @@ def test_random_dags_other_seeds_and_shapes(seed, rows, ks):
         check_all(g, out, ref, f"random dag seed {seed} rows {rows} ks {ks} {label}")
 
 
-def _random_graph_case(seed, rows, cols, num_ops=40):
+def _random_graph_case(seed, rows, cols, num_ops=40, views=False):
     """One graph of tests/graphgen.py under the three planners.  Its bf16 round trips are quantisers: they are made plan
     outputs, so the oracle can take the device's own roundings for everything downstream (see tests/parity.py)."""
     from graphgen import random_graph, random_inputs
-    g = expose_bf16_nodes(random_graph(seed, rows, cols, num_ops))
+    g = expose_bf16_nodes(random_graph(seed, rows, cols, num_ops, views=views))
     ins = random_inputs(g, seed)
     ref = Reference(g, ins)
     ill = 0
@@ -799,6 +799,19 @@ def test_random_graph_sweep(first):
         rows, cols = SWEEP_SHAPES[seed % len(SWEEP_SHAPES)]
         print(f"seed {seed} {rows}x{cols}", flush=True)
         _random_graph_case(seed, rows, cols, 25 if rows * cols > 4_000_000 else 40)
+
+
+VIEW_SWEEP_SHAPES = [(65, 63), (40, 2000), (128, 96), (7, 70002), (1000, 1000), (2, 2), (300, 1), (1, 500), (4096, 260), (12, 33000), (513, 520), (64, 16384)]
+
+
+@pytest.mark.parametrize("first", range(int(os.environ.get("FS_VIEW_SWEEP_START", "1000")), int(os.environ.get("FS_VIEW_SWEEP_END", "1024")), 12))
+def test_random_graph_sweep_with_views_and_concats(first):
+    # the same generator with the shape-modulation ops switched on: reshapes / bitcasts into another factorisation of the elements,
+    # arithmetic and row reductions there, the way back, concats along columns (seams on and off vector boundaries) and rows
+    for seed in range(first, first + 12):
+        rows, cols = VIEW_SWEEP_SHAPES[seed % len(VIEW_SWEEP_SHAPES)]
+        print(f"seed {seed} {rows}x{cols} with views", flush=True)
+        _random_graph_case(seed, rows, cols, 25 if rows * cols > 2_000_000 else 35, views=True)
 
 
 def test_gpu_matches_the_stored_small_cases():
