@@ -100,7 +100,8 @@ def run(graph, inputs: Sequence[np.ndarray], num_threads: int = 1, round_nodes=T
     """Evaluate `graph` (a workloads.Graph) on host arrays; returns one array per plan output.
 
     f32 tensors are float32 arrays, bf16 tensors are uint16 arrays of raw bits, u8 are uint8.
-    round_nodes: True / 1 the reference of record; False / 0 the fp64 companion; 2 the fp32-accumulation companion.
+    round_nodes: True / 1 the reference of record; False / 0 the fp64 companion; 2 the fp32-accumulation companion;
+    3 returns no values but float64 arrays of the first-order spread of a correct fp32 implementation around the reference.
     """
     lib = _load()
     g, _nodes, _outs = _encode(graph)
@@ -118,7 +119,7 @@ def run(graph, inputs: Sequence[np.ndarray], num_threads: int = 1, round_nodes=T
     results = []
     for o in graph.outputs:
         nd = graph.nodes[o]
-        results.append(np.empty((nd.rows, nd.cols), dtype=_NP[nd.dtype]))
+        results.append(np.empty((nd.rows, nd.cols), dtype=np.float64 if int(round_nodes) == 3 else _NP[nd.dtype]))
     out_ptrs = (ctypes.c_void_p * max(1, len(results)))(*[a.ctypes.data for a in results])
     rc = lib.fso_run(ctypes.byref(g), in_ptrs, out_ptrs, int(num_threads), int(round_nodes))
     if rc != 0:

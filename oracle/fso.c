@@ -118,6 +118,44 @@ static double cmp_f64(int kind, double a, double b) {
   return 0.0;
 }
 
+/* ---- companion 3: the spread of a correct fp32 implementation around the reference, to first order ----------------
+ * Model: every correctly rounded fp32 op errs by a value uniform in +-half a spacing, spread spacing/sqrt(12), the
+ * spacing taken at its upper end 2^-23 |result|; exp, log, tanh, sigmoid, rsqrt, rcp and gelu, which a GPU builds on
+ * hardware approximations good to 1-2 spacings, have a spread of one spacing; a sum accumulated in fp32 rounds every
+ * partial sum of a balanced pairwise summation; the errors are independent, travel through each op's derivative and
+ * add in quadrature.  Inputs, constants and predicates are exact. */
+static double spacing32(double x) { return ldexp(fabs(x), -23); }
+#define FSO_SPREAD_ROUNDED 0.28867513459481287 /* 1/sqrt(12) */
+static int is_approximated(int op) {
+  return op == FSO_EXP || op == FSO_LOG || op == FSO_TANH || op == FSO_SIGMOID || op == FSO_RSQRT || op == FSO_RCP || op == FSO_GELU_TANH;
+}
+static double unary_f64(int op, double x);
+/* |f'(x)| by a central difference in fp64 (one-sided at the edge of a domain) */
+static double unary_slope(int op, double x) {
+  if (op == FSO_NEG || op == FSO_ABS || op == FSO_CONVERT) return 1.0;
+  const double h = 1e-6 * fmax(1.0, fabs(x));
+  double lo = x - h, hi = x + h;
+  if ((op == FSO_LOG || op == FSO_SQRT || op == FSO_RSQRT) && lo <= 0.0) lo = x;
+  if (op == FSO_RCP && ((lo < 0.0) != (hi < 0.0))) lo = x;
+  const double d = (unary_f64(op, hi) - unary_f64(op, lo)) / (hi - lo);
+  return isfinite(d) ? fabs(d) : 0.0;
+}
+static double local_spread(const fso_node* n, double value) {
+  if (n->dtype != FSO_F32) return 0.0; /* bf16 nodes: their rounding decisions are shared with the path under test by the tests */
+  return spacing32(value) * (is_approximated(n->opcode) ? 1.0 : FSO_SPREAD_ROUNDED);
+}
+static double quad(double a, double b) { return sqrt(a * a + b * b); }
+/* variance that rounding every partial sum of a balanced pairwise summation to fp32 adds to the total; *sum = the total */
+static double pairwise_rounding_variance(const double* p, long n, long stride, double* sum) {
+  if (n == 1) { *sum = p[0]; return 0.0; }
+  double sl, sr;
+  const long h = n / 2;
+  const double v = pairwise_rounding_variance(p, h, stride, &sl) + pairwise_rounding_variance(p + h * stride, n - h, stride, &sr);
+  *sum = sl + sr;
+  const double e = FSO_SPREAD_ROUNDED * spacing32(*sum);
+  return v + e * e;
+}
+
 /* sequential reduction of n values spaced `stride` apart; displaced: sums are moved by
  * 2^-24 * sum |terms| (the accumulation companion, see fso.h) */
 static double reduce_f64(int kind, const double* p, long n, long stride, int acc32) {
@@ -154,6 +192,7 @@ int fso_run(const fso_graph* g, const void* const* host_in, void* const* host_ou
 #endif
   const int N = g->num_nodes;
   const int acc32 = round_nodes == 2;
+  const int spread = round_nodes == 3;
   int id, k;
 
   /* structural checks: topological ids, arity, shapes */
@@ -193,7 +232,8 @@ int fso_run(const fso_graph* g, const void* const* host_in, void* const* host_ou
   /* last consumer of every node, so its buffer can be freed early */
   int* last_use = (int*)malloc(sizeof(int) * (size_t)N);
   double** val = (double**)calloc((size_t)N, sizeof(double*));
-  if (!last_use || !val) { free(last_use); free(val); return -3; }
+  double** sig = (double**)calloc((size_t)N, sizeof(double*)); /* companion 3: the spread of every node's elements */
+  if (!last_use || !val || !sig) { free(last_use); free(val); free(sig); return -3; }
   for (id = 0; id < N; ++id) last_use[id] = id;
   for (id = 0; id < N; ++id)
     for (k = 0; k < g->nodes[id].num_in; ++k) last_use[g->nodes[id].in[k]] = id;
@@ -306,12 +346,89 @@ int fso_run(const fso_graph* g, const void* const* host_in, void* const* host_ou
         }
     }
 
+    if (spread && rc == 0) { /* the same walk for the spreads: sg = spread of out, from the operands' values and spreads */
+      double* sg = (double*)calloc((size_t)E, sizeof(double));
+      if (!sg) { rc = -3; break; }
+      sig[id] = sg;
+      const double* sa = n->num_in > 0 ? sig[n->in[0]] : NULL;
+      const double* sb = n->num_in > 1 ? sig[n->in[1]] : NULL;
+      const double* sc = n->num_in > 2 ? sig[n->in[2]] : NULL;
+      switch (n->opcode) {
+        case FSO_INPUT: case FSO_CONST: case FSO_CMP: break; /* exact */
+        case FSO_SELECT:
+          for (i = 0; i < E; ++i) sg[i] = a[i] != 0.0 ? sb[i] : sc[i];
+          break;
+        case FSO_BCAST_ROWVEC:
+          for (i = 0; i < R; ++i) for (j = 0; j < C; ++j) sg[i * C + j] = sa[j];
+          break;
+        case FSO_BCAST_COLVEC:
+          for (i = 0; i < R; ++i) for (j = 0; j < C; ++j) sg[i * C + j] = sa[i];
+          break;
+        case FSO_TRANSPOSE:
+          for (i = 0; i < R; ++i) for (j = 0; j < C; ++j) sg[i * C + j] = sa[j * R + i];
+          break;
+        case FSO_RESHAPE: case FSO_BITCAST:
+          for (i = 0; i < E; ++i) sg[i] = sa[i];
+          break;
+        case FSO_CONCAT:
+          if (n->attr_i == 1) {
+            const long Ca = g->nodes[n->in[0]].cols, Cb = g->nodes[n->in[1]].cols;
+            for (i = 0; i < R; ++i) for (j = 0; j < C; ++j) sg[i * C + j] = j < Ca ? sa[i * Ca + j] : sb[i * Cb + (j - Ca)];
+          } else {
+            const long Ra = g->nodes[n->in[0]].rows;
+            for (i = 0; i < R; ++i) for (j = 0; j < C; ++j) sg[i * C + j] = i < Ra ? sa[i * C + j] : sb[(i - Ra) * C + j];
+          }
+          break;
+        case FSO_REDUCE_ROW: case FSO_REDUCE_COL: {
+          const int rowwise = n->opcode == FSO_REDUCE_ROW;
+          const long cnt = rowwise ? g->nodes[n->in[0]].cols : g->nodes[n->in[0]].rows;
+          const long outs = rowwise ? R : C, step = rowwise ? 1 : C;
+          long t;
+          for (i = 0; i < outs; ++i) {
+            const double* p = a + (rowwise ? i * cnt : i);
+            const double* q = sa + (rowwise ? i * cnt : i);
+            if (n->attr_i == FSO_SUM || n->attr_i == FSO_MEAN) {
+              double var = 0.0, total;
+              for (t = 0; t < cnt; ++t) var += q[t * step] * q[t * step];
+              double sd = sqrt(var + pairwise_rounding_variance(p, cnt, step, &total));
+              if (n->attr_i == FSO_MEAN) sd = quad(sd / (double)cnt, local_spread(n, out[i]));
+              sg[i] = sd;
+            } else { /* max / min: the spread of the element that was picked */
+              long pick = 0;
+              for (t = 1; t < cnt; ++t)
+                if (n->attr_i == FSO_MAX_ ? p[t * step] > p[pick * step] : p[t * step] < p[pick * step]) pick = t;
+              sg[i] = q[pick * step];
+            }
+          }
+          break;
+        }
+        default:
+          if (n->num_in == 1) {
+#pragma omp parallel for
+            for (i = 0; i < E; ++i) sg[i] = quad(unary_slope(n->opcode, a[i]) * sa[i], n->opcode == FSO_NEG || n->opcode == FSO_ABS ? 0.0 : local_spread(n, out[i]));
+          } else if (n->num_in == 2) {
+#pragma omp parallel for
+            for (i = 0; i < E; ++i) {
+              double sd;
+              switch (n->opcode) {
+                case FSO_ADD: case FSO_SUB: sd = quad(sa[i], sb[i]); break;
+                case FSO_MUL: sd = quad(b[i] * sa[i], a[i] * sb[i]); break;
+                case FSO_DIV: sd = quad(sa[i] / b[i], a[i] * sb[i] / (b[i] * b[i])); break;
+                case FSO_MAX: sd = a[i] >= b[i] ? sa[i] : sb[i]; break;
+                default: sd = a[i] <= b[i] ? sa[i] : sb[i]; break; /* FSO_MIN */
+              }
+              sg[i] = (n->opcode == FSO_MAX || n->opcode == FSO_MIN) ? sd : quad(sd, local_spread(n, out[i]));
+            }
+          }
+      }
+    }
+
     /* free operands whose last consumer this was */
     for (k = 0; k < n->num_in; ++k) {
       int o = n->in[k];
-      if (last_use[o] == id && val[o]) { free(val[o]); val[o] = NULL; }
+      if (last_use[o] == id && val[o]) { free(val[o]); val[o] = NULL; free(sig[o]); sig[o] = NULL; }
     }
-    if (last_use[id] == id && val[id]) { free(val[id]); val[id] = NULL; } /* dead node */
+    if (last_use[id] == id && val[id]) { free(val[id]); val[id] = NULL; free(sig[id]); sig[id] = NULL; } /* dead node */
   }
 
   /* write plan outputs in their dtype (fp64-through mode rounds here) */
@@ -322,6 +439,11 @@ int fso_run(const fso_graph* g, const void* const* host_in, void* const* host_ou
     const double* v = val[o];
     long i;
     if (!v || !host_out[k]) { rc = -1; break; }
+    if (spread) { /* companion 3 hands back the spreads, as doubles, whatever the output's dtype */
+      double* d = (double*)host_out[k];
+      for (i = 0; i < E; ++i) d[i] = sig[o] ? sig[o][i] : 0.0;
+      continue;
+    }
     if (n->dtype == FSO_F32) {
       float* d = (float*)host_out[k];
       for (i = 0; i < E; ++i) d[i] = (float)v[i];
@@ -334,8 +456,9 @@ int fso_run(const fso_graph* g, const void* const* host_in, void* const* host_ou
     }
   }
 
-  for (id = 0; id < N; ++id) free(val[id]);
+  for (id = 0; id < N; ++id) free(val[id]), free(sig[id]);
   free(val);
+  free(sig);
   free(last_use);
   return rc;
 }

@@ -74,6 +74,17 @@ typedef struct {
  *                   companion shows, element by element, how far that choice can move an
  *                   output (a sum of positive terms hardly moves; a sum whose terms cancel
  *                   moves by many times its own size).  Never the pass/fail reference either.
+ *                3: no values at all: host_out[k] receives, as DOUBLES (rows*cols of them, whatever the
+ *                   output's dtype), the first-order spread (standard deviation) of a correct fp32
+ *                   implementation's result around the reference, element by element.  Model: a correctly
+ *                   rounded fp32 op errs uniformly within half a spacing (spread spacing/sqrt(12), the
+ *                   spacing taken as 2^-23 |result|); exp, log, tanh, sigmoid, rsqrt, rcp and gelu, which
+ *                   a GPU builds on hardware approximations good to 1-2 spacings, have a spread of one
+ *                   spacing; a sum accumulated in fp32 rounds every partial sum of a balanced pairwise
+ *                   summation; errors are independent, travel through each op's derivative and add in
+ *                   quadrature; inputs, constants, predicates and bf16 roundings are exact.  Where
+ *                   companions 0 and 2 each show ONE realisation of rounding noise (which can be small at
+ *                   an element by chance), this one gives its scale.  Never the pass/fail reference.
  * Returns 0, or a negative code: -1 bad argument, -2 bad graph, -3 out of memory.
  */
 int fso_run(const fso_graph* g, const void* const* host_in, void* const* host_out, int num_threads, int round_nodes);

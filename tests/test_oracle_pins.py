@@ -299,6 +299,75 @@ def test_accumulation_companion_displaces_sums_by_one_rounding_unit_per_term():
     np.testing.assert_array_equal(th, ref[6])
 
 
+def test_spread_companion_against_numpy_float32_arithmetic():
+    # round_nodes=3 returns no values but the first-order spread of a correct fp32 implementation around the reference.  It is
+    # pinned against such implementations: numpy's own float32 arithmetic (correctly rounded + - * /, a float32 tanh, a pairwise
+    # float32 sum), whose actual deviation from the fp64 result must be of the size the spread says - within 4.5 spreads almost
+    # everywhere (it is a standard deviation), and neither far below nor far above it in the root mean square.
+    n = 20000
+    x, y, z, w = (RNG.uniform(-2, 2, (1, n)).astype(np.float32) for _ in range(4))
+    g = Graph()
+    ix, iy, iz, iw = (g.input(1, n) for _ in range(4))
+    chain = g.binary("sub", g.binary("mul", g.binary("add", g.binary("mul", ix, iy), iz), iw), g.binary("div", ix, g.binary("add", g.unary("abs", iy), g.const(1.0, 1, n))))
+    g.set_outputs([chain])
+    sd = run1(g, [x, y, z, w], round_nodes=3)[0]
+    assert sd.dtype == np.float64 and sd.shape == (1, n)
+    f32 = ((x * y + z) * w - x / (np.abs(y) + np.float32(1.0))).astype(np.float32)   # every op rounded to float32 by numpy
+    x64, y64, z64, w64 = (v.astype(np.float64) for v in (x, y, z, w))
+    err = np.abs(f32.astype(np.float64) - ((x64 * y64 + z64) * w64 - x64 / (np.abs(y64) + 1.0)))
+    ratio = err / sd
+    assert (ratio < 4.5).mean() > 0.999 and 0.3 < np.sqrt(np.mean(ratio ** 2)) < 1.5, (ratio.max(), np.sqrt(np.mean(ratio ** 2)))
+    # a difference of nearly equal tanh values: results ~1e-3 from operands ~0.5, each carrying one float32 tanh error
+    g = Graph()
+    ix, iy = g.input(1, n), g.input(1, n)
+    g.set_outputs([g.binary("sub", g.unary("tanh", ix), g.unary("tanh", iy))])
+    a = RNG.uniform(0.3, 1.0, (1, n)).astype(np.float32)
+    b = (a + RNG.uniform(-1e-3, 1e-3, (1, n)).astype(np.float32)).astype(np.float32)
+    sd = run1(g, [a, b], round_nodes=3)[0]
+    f32 = (np.tanh(a) - np.tanh(b)).astype(np.float32)          # float32 tanh: within a spacing or so of the true value
+    err = np.abs(f32.astype(np.float64) - (np.tanh(a.astype(np.float64)) - np.tanh(b.astype(np.float64))))
+    ratio = err / sd
+    assert (ratio < 4.5).mean() > 0.999 and 0.1 < np.sqrt(np.mean(ratio ** 2)) < 1.5, (ratio.max(), np.sqrt(np.mean(ratio ** 2)))
+    assert np.median(sd / np.abs(f32.astype(np.float64) + 1e-30)) > 1e-5   # ... which is far more than 1e-5 of such a result
+    # row sums of 4096 products of random sign, summed pairwise in float32 by numpy
+    rows, cols = 512, 4096
+    p, q = RNG.standard_normal((rows, cols)).astype(np.float32), RNG.standard_normal((rows, cols)).astype(np.float32)
+    g = Graph()
+    ip, iq = g.input(rows, cols), g.input(rows, cols)
+    g.set_outputs([g.reduce_row("sum", g.binary("mul", ip, iq)), g.reduce_row("mean", g.binary("mul", ip, iq))])
+    sd_sum, sd_mean = run1(g, [p, q], round_nodes=3)
+    f32 = (p * q).sum(axis=1, dtype=np.float32, keepdims=True)
+    exact = np.array([[math.fsum(float(u) * float(v) for u, v in zip(pr, qr))] for pr, qr in zip(p, q)])
+    ratio = np.abs(f32.astype(np.float64) - exact) / sd_sum
+    assert ratio.max() < 4.5 and 0.05 < np.sqrt(np.mean(ratio ** 2)) < 1.5, (ratio.max(), np.sqrt(np.mean(ratio ** 2)))
+    assert (sd_mean >= sd_sum / cols).all() and (sd_mean < 1.5 * sd_sum / cols).all()   # the sum's spread over n, plus the division's own rounding
+
+
+def test_spread_companion_structure():
+    # what is exact has no spread; data movement carries the spread with the values; max / min and select carry the spread of
+    # the element they pick
+    rows, cols = 6, 10
+    x = RNG.uniform(-1, 1, (rows, cols)).astype(np.float32)
+    y = RNG.uniform(-1, 1, (rows, cols)).astype(np.float32)
+    g = Graph()
+    ix, iy = g.input(rows, cols), g.input(rows, cols)
+    e = g.unary("exp", ix)
+    pred = g.cmp("gt", ix, iy)
+    g.set_outputs([g.unary("neg", ix), pred, g.select(pred, ix, iy), e, g.transpose(e), g.reshape(e, cols, rows), g.binary("max", e, iy),
+                   g.select(pred, e, iy), g.reduce_row("max", e), g.concat(e, iy, "cols"), g.binary("add", e, g.bcast_colvec(g.reduce_row("max", e), cols))])
+    neg, pr, sel_in, se, st, sr, smax, ssel, srmax, scat, sadd = run1(g, [x, y], round_nodes=3)
+    assert not neg.any() and not pr.any() and not sel_in.any()           # inputs, predicates, moves of inputs: exact
+    assert (se > 0).all() and (se < 1e-6).all()
+    np.testing.assert_array_equal(st, se.T)
+    np.testing.assert_array_equal(sr, se.reshape(cols, rows))
+    ev = np.exp(x.astype(np.float64))
+    np.testing.assert_array_equal(smax, np.where(ev.astype(np.float32) >= y, se, 0.0))
+    np.testing.assert_array_equal(ssel, np.where(x > y, se, 0.0))
+    np.testing.assert_array_equal(srmax[:, 0], se[np.arange(rows), np.argmax(x, axis=1)])   # exp is monotonic: the largest x
+    np.testing.assert_array_equal(scat, np.concatenate([se, np.zeros_like(se)], axis=1))
+    assert (sadd > np.maximum(se, srmax)).all() and (sadd < 1.5 * np.sqrt(se ** 2 + srmax ** 2) + 1e-7).all()   # in quadrature, plus the add's own rounding
+
+
 def test_softmax_pins():
     R, C = 8, 1024
     g = softmax_graph(R, C)

@@ -174,3 +174,33 @@ def test_accumulation_companion_flags_cancelling_sums():
     bad[40, 0] -= np.float32(1e-3)
     with pytest.raises(AssertionError):
         check_all(g, [bad], ref, "off on a saturated row")
+
+
+def test_spread_flags_what_one_realisation_of_the_noise_can_miss():
+    # max over a row of differences of nearly equal tanh values: results ~1e-4 from operands ~0.5.  Whether |A - B| at an element
+    # is large is a matter of luck (how close the fp32 roundings of the two tanh values came to their fp64 values); the spread S is
+    # not: every element of this output is flagged, and a device that is one operand spacing off passes, while it would not on a
+    # well-conditioned output, and ten times that still fails here.
+    rows, cols = 200, 64
+    g = Graph()
+    ia, ib = g.input(rows, cols), g.input(rows, cols)
+    g.set_outputs([g.reduce_row("max", g.binary("sub", g.unary("tanh", ia), g.unary("tanh", ib))), g.unary("tanh", ia)])
+    rng = np.random.default_rng(11)
+    a = rng.uniform(0.3, 1.0, (rows, cols)).astype(np.float32)
+    b = (a - rng.uniform(0, 2e-4, (rows, cols)).astype(np.float32)).astype(np.float32)
+    ref = Reference(g, [a, b], threads=2)
+    tol = 1e-5 * np.abs(ref.a[0]) + 1e-5 * float(np.sqrt(np.mean(ref.a[0].astype(np.float64) ** 2)))
+    lucky = np.abs(ref.b[0].astype(np.float64) - ref.a[0]) < 0.25 * tol
+    assert lucky.any() and (ref.s[0] > tol).all()          # B alone would leave some elements unflagged; S flags them all
+    dev = [ref.a[0].copy(), ref.a[1].copy()]
+    i = int(np.argmax(lucky))
+    dev[0][i, 0] += np.float32(6e-8)                       # one spacing of a value in [0.5, 1)
+    st = check_all(g, dev, ref, "one operand spacing off", max_ill_fraction=0.5)
+    assert st[0]["ill_conditioned"] == rows and st[1]["ill_conditioned"] == 0
+    dev[0][i, 0] += np.float32(5e-6)
+    with pytest.raises(AssertionError):
+        check_all(g, dev, ref, "far beyond the spread", max_ill_fraction=0.5)
+    dev = [ref.a[0].copy(), ref.a[1].copy()]
+    dev[1][3, 5] += np.float32(1e-4)                      # the well-conditioned output gets no slack
+    with pytest.raises(AssertionError):
+        check_all(g, dev, ref, "off on a well-conditioned output", max_ill_fraction=0.5)
