@@ -153,6 +153,29 @@ def time_empty_launch(steps=2000):
     return {"back_to_back_us": res["ms_median"] * 1e3, "launch_and_sync_us": statistics.median(singles)}
 
 
+def time_alu_probe(reps=5):
+    """What the vector ALUs sustain on chains of dependent fp32 FMAs (8 wavefronts per SIMD, no memory traffic): the clock
+    that figure implies (one wavefront FMA occupies a 16-lane SIMD for 4 cycles) and the fp32 rate without packed instructions."""
+    import torch
+    from paper_1811_05213_amd import alu_probe, device_limits
+    cus = device_limits()["compute_units"]
+    workgroups, iters = cus * 32, 2000          # 32 x 256 lanes per CU = 8 wavefronts per SIMD; 256000 FMAs per lane
+    out = torch.empty(workgroups * 256, dtype=torch.float32, device="cuda:0")
+    stream = torch.cuda.current_stream().cuda_stream
+    best = None
+    for _ in range(reps + 1):                   # (the first launch also warms the clocks)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        alu_probe(out.data_ptr(), workgroups, iters, stream)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1)
+        best = ms if best is None else min(best, ms)
+    fma_per_simd = iters * 128 * 8              # wavefront-FMAs one SIMD issues
+    return {"ms": best, "implied_clock_ghz": fma_per_simd * 4 / (best * 1e-3) / 1e9,
+            "fp32_tflops": 2.0 * iters * 128 * 256 * workgroups / (best * 1e-3) / 1e12, "wavefronts_per_simd": 8}
+
+
 def measured_traffic(workload_name):
     """HBM bytes per launch (per step for multi-kernel plans) of the workload's stitched kernels, from the committed
     rocprofv3 counter summary (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, scale factors calibrated on the copy probe), or None."""
@@ -327,6 +350,8 @@ def main():
     same = max(1 << 20, (head["min_hbm_bytes"] // 2) // 4096 * 4096)
     copy_same_gbs = time_copy_probe(same, reps=200 if same < (1 << 28) else 20)
     empty = time_empty_launch()
+    alu = time_alu_probe()
+    log(f"alu probe: {alu}")
     if not args.no_extras:
         for cfg in (1, 2, 3, 4, 5, 6, 7):  # 6, 7: backward-pass subgraphs (LayerNorm, softmax), not benchmark configurations
             if cfg == args.workload:
@@ -375,6 +400,7 @@ def main():
         "copy_probe_gbs": copy_gbs,
         "copy_probe_same_bytes_gbs": copy_same_gbs,
         "empty_kernel_launch": empty,
+        "alu_probe": alu,
         "device": device_limits(),
         "other_workloads": extras,
     }

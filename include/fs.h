@@ -408,6 +408,15 @@ fs_status fs_copy_probe(const void* src, void* dst, size_t bytes, void* hip_stre
 fs_status fs_copy_probe_shape(const void* src, void* dst, size_t bytes, int32_t vectors_in_flight, int32_t workgroups,
                               void* hip_stream);
 
+/*
+ * fs_alu_probe: `workgroups` workgroups of 256 lanes, each lane running 8 independent chains of `iters` * 16
+ * dependent fp32 fused multiply-adds (iters * 128 FMAs per lane) and writing one float to `out` (device,
+ * workgroups * 256 floats), enqueued on `hip_stream`.  It measures what the vector ALUs sustain when nothing
+ * else is used - the clock a kernel bound by ordinary fp32 arithmetic can count on, and the "alu" peak the
+ * stitched kernels' instruction counts are held against (packed fp32 instructions are not used).
+ */
+fs_status fs_alu_probe(void* out, int32_t workgroups, int32_t iters, void* hip_stream);
+
 /* fs_launch_probe: enqueue an empty kernel (one wavefront) on `hip_stream`: what a launch costs when
  * nothing is computed, the floor under the launch-bound workloads. */
 fs_status fs_launch_probe(void* hip_stream);

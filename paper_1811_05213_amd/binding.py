@@ -110,6 +110,8 @@ def lib() -> ctypes.CDLL:
         L.fs_copy_probe_shape.argtypes = [vp, vp, ctypes.c_size_t, ctypes.c_int32, ctypes.c_int32, vp]
         L.fs_copy_probe_shape.restype = ctypes.c_int
         L.fs_launch_probe.argtypes = [vp]
+        L.fs_alu_probe.argtypes = [vp, ctypes.c_int32, ctypes.c_int32, vp]
+        L.fs_alu_probe.restype = ctypes.c_int
         L.fs_launch_probe.restype = ctypes.c_int
         L.fs_plan_load.argtypes = [vp]
         L.fs_plan_workspace_check.argtypes = [vp, vp, ctypes.c_size_t, vp]
@@ -281,6 +283,10 @@ def device_limits() -> dict:
 
 def copy_probe_shape(src_ptr: int, dst_ptr: int, nbytes: int, vectors_in_flight: int, workgroups: int, stream: int = 0) -> None:
     _check(lib().fs_copy_probe_shape(src_ptr, dst_ptr, nbytes, vectors_in_flight, workgroups, stream))
+
+
+def alu_probe(out_ptr: int, workgroups: int, iters: int, stream: int = 0) -> None:
+    _check(lib().fs_alu_probe(out_ptr, workgroups, iters, stream))
 
 
 def launch_probe(stream: int = 0) -> None:

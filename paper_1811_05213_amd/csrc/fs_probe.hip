@@ -158,6 +158,26 @@ int launch_copy_probe_shape(const void* src, void* dst, size_t bytes, int vector
   return (int)hipGetLastError();
 }
 
+// Chains of dependent fp32 fused multiply-adds, 8 independent chains per lane, nothing else: what the vector ALUs
+// sustain when they are the only thing a kernel uses.  `iters` trips of 128 FMAs per lane; the result is written so
+// that nothing is optimised away.
+__global__ void __launch_bounds__(256) fs_alu_probe_kernel(float* out, int iters, float a, float b) {
+  float x0 = threadIdx.x * 1e-3f, x1 = x0 + 1, x2 = x0 + 2, x3 = x0 + 3, x4 = x0 + 4, x5 = x0 + 5, x6 = x0 + 6, x7 = x0 + 7;
+  for (int i = 0; i < iters; ++i) {
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+      x0 = __builtin_fmaf(x0, a, b), x1 = __builtin_fmaf(x1, a, b), x2 = __builtin_fmaf(x2, a, b), x3 = __builtin_fmaf(x3, a, b);
+      x4 = __builtin_fmaf(x4, a, b), x5 = __builtin_fmaf(x5, a, b), x6 = __builtin_fmaf(x6, a, b), x7 = __builtin_fmaf(x7, a, b);
+    }
+  }
+  out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = ((x0 + x1) + (x2 + x3)) + ((x4 + x5) + (x6 + x7));
+}
+
+int launch_alu_probe(float* out, int workgroups, int iters, hipStream_t stream) {
+  hipLaunchKernelGGL(fs_alu_probe_kernel, dim3((unsigned)workgroups), dim3(256), 0, stream, out, iters, 0.999f, 0.001f);
+  return (int)hipGetLastError();
+}
+
 int launch_empty(hipStream_t stream) {
   hipLaunchKernelGGL(fs_empty_kernel, dim3(1), dim3(64), 0, stream);
   return (int)hipGetLastError();

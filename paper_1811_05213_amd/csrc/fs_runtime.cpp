@@ -20,6 +20,7 @@ int launch_copy_probe(const void* src, void* dst, size_t bytes, hipStream_t stre
 int launch_zero_u32(void* p, size_t count, hipStream_t stream);
 int launch_copy_probe_shape(const void* src, void* dst, size_t bytes, int vectors_in_flight, int workgroups, hipStream_t stream);
 int launch_empty(hipStream_t stream);
+int launch_alu_probe(float* out, int workgroups, int iters, hipStream_t stream);
 size_t static_scratch_bytes();
 int static_scratch_resolve(int device, void** out);
 void* static_scratch_lookup(int device);
@@ -869,6 +870,14 @@ fs_status fs_copy_probe_shape(const void* src, void* dst, size_t bytes, int32_t 
     FS_FAIL(FS_ERR_INVALID_ARG, "copy probe shape: vectors_in_flight must be 1, 2, 4 or 8 and workgroups >= 0");
   const int e = launch_copy_probe_shape(src, dst, bytes, vectors_in_flight, workgroups, (hipStream_t)hip_stream);
   if (e != 0) FS_FAIL(FS_ERR_HIP, "copy probe launch: %s", hipGetErrorString((hipError_t)e));
+  return FS_OK;
+}
+
+fs_status fs_alu_probe(void* out, int32_t workgroups, int32_t iters, void* hip_stream) {
+  if (!out || ((uintptr_t)out & 3) || workgroups < 1 || workgroups > (1 << 20) || iters < 1 || iters > (1 << 24))
+    FS_FAIL(FS_ERR_INVALID_ARG, "alu probe needs an output buffer of workgroups * 256 floats, 1..2^20 workgroups and 1..2^24 trips");
+  const int e = launch_alu_probe((float*)out, workgroups, iters, (hipStream_t)hip_stream);
+  if (e != 0) FS_FAIL(FS_ERR_HIP, "alu probe launch: %s", hipGetErrorString((hipError_t)e));
   return FS_OK;
 }
 

@@ -753,7 +753,9 @@ def _random_graph_case(seed, rows, cols, num_ops=40, views=False):
     ill = 0
     for mode, label in ((fs.FS_MODE_STITCHED, "stitched"), (fs.FS_MODE_LAYERED, "layered"), (fs.FS_MODE_UNFUSED, "unfused")):
         out = run_graph(g, ins, mode=mode)
-        stats = check_all(g, out, ref, f"random graph seed {seed} {rows}x{cols} {label}")
+        # (a random graph may have a couple of outputs that are ill-conditioned throughout - differences of nearly equal values:
+        # up to a quarter of all output elements may be set aside before the graph is refused as a test case)
+        stats = check_all(g, out, ref, f"random graph seed {seed} {rows}x{cols} {label}", max_ill_fraction=0.25)
         ill = max(ill, sum(st["ill_conditioned"] for st in stats))
     return ill
 
