@@ -121,9 +121,11 @@ static double cmp_f64(int kind, double a, double b) {
 /* ---- companion 3: the spread of a correct fp32 implementation around the reference, to first order ----------------
  * Model: every correctly rounded fp32 op errs by a value uniform in +-half a spacing, spread spacing/sqrt(12), the
  * spacing taken at its upper end 2^-23 |result|; exp, log, tanh, sigmoid, rsqrt, rcp and gelu, which a GPU builds on
- * hardware approximations good to 1-2 spacings, have a spread of one spacing; a sum accumulated in fp32 rounds every
- * partial sum of a balanced pairwise summation; the errors are independent, travel through each op's derivative and
- * add in quadrature.  Inputs, constants and predicates are exact. */
+ * hardware approximations good to 1-2 spacings, err by one spacing; a sum accumulated in fp32 rounds every partial sum
+ * of a balanced pairwise summation.  Rounding errors are independent: they travel through each op's derivative and add
+ * in quadrature.  The errors of approximated ops are not noise - an approximation leans one way over a range of
+ * arguments - so they travel through the derivatives' absolute values and add linearly.  The spread of an element is
+ * the sum of the two parts.  Inputs, constants and predicates are exact. */
 static double spacing32(double x) { return ldexp(fabs(x), -23); }
 #define FSO_SPREAD_ROUNDED 0.28867513459481287 /* 1/sqrt(12) */
 static int is_approximated(int op) {
@@ -346,37 +348,52 @@ int fso_run(const fso_graph* g, const void* const* host_in, void* const* host_ou
         }
     }
 
-    if (spread && rc == 0) { /* the same walk for the spreads: sg = spread of out, from the operands' values and spreads */
-      double* sg = (double*)calloc((size_t)E, sizeof(double));
+    if (spread && rc == 0) {
+      /* the same walk for the spreads.  Two parts per element: sg[0..E) rounding noise, independent from op to op and
+       * element to element, added in quadrature; sg[E..2E) the error of approximated ops, which may lean one way
+       * over many elements and is therefore added linearly, by absolute value. */
+      double* sg = (double*)calloc((size_t)(2 * E), sizeof(double));
       if (!sg) { rc = -3; break; }
       sig[id] = sg;
+      double* ch = sg + E;
+      const long Ea = n->num_in > 0 ? (long)g->nodes[n->in[0]].rows * g->nodes[n->in[0]].cols : 0;
+      const long Eb = n->num_in > 1 ? (long)g->nodes[n->in[1]].rows * g->nodes[n->in[1]].cols : 0;
+      const long Ec = n->num_in > 2 ? (long)g->nodes[n->in[2]].rows * g->nodes[n->in[2]].cols : 0;
       const double* sa = n->num_in > 0 ? sig[n->in[0]] : NULL;
       const double* sb = n->num_in > 1 ? sig[n->in[1]] : NULL;
       const double* sc = n->num_in > 2 ? sig[n->in[2]] : NULL;
+      const double* ca = sa ? sa + Ea : NULL;
+      const double* cb = sb ? sb + Eb : NULL;
+      const double* cc = sc ? sc + Ec : NULL;
+#define FSO_MOVE(dst, src_a, src_c) do { sg[dst] = (src_a); ch[dst] = (src_c); } while (0)
       switch (n->opcode) {
         case FSO_INPUT: case FSO_CONST: case FSO_CMP: break; /* exact */
         case FSO_SELECT:
-          for (i = 0; i < E; ++i) sg[i] = a[i] != 0.0 ? sb[i] : sc[i];
+          for (i = 0; i < E; ++i) { if (a[i] != 0.0) FSO_MOVE(i, sb[i], cb[i]); else FSO_MOVE(i, sc[i], cc[i]); }
           break;
         case FSO_BCAST_ROWVEC:
-          for (i = 0; i < R; ++i) for (j = 0; j < C; ++j) sg[i * C + j] = sa[j];
+          for (i = 0; i < R; ++i) for (j = 0; j < C; ++j) FSO_MOVE(i * C + j, sa[j], ca[j]);
           break;
         case FSO_BCAST_COLVEC:
-          for (i = 0; i < R; ++i) for (j = 0; j < C; ++j) sg[i * C + j] = sa[i];
+          for (i = 0; i < R; ++i) for (j = 0; j < C; ++j) FSO_MOVE(i * C + j, sa[i], ca[i]);
           break;
         case FSO_TRANSPOSE:
-          for (i = 0; i < R; ++i) for (j = 0; j < C; ++j) sg[i * C + j] = sa[j * R + i];
+          for (i = 0; i < R; ++i) for (j = 0; j < C; ++j) FSO_MOVE(i * C + j, sa[j * R + i], ca[j * R + i]);
           break;
         case FSO_RESHAPE: case FSO_BITCAST:
-          for (i = 0; i < E; ++i) sg[i] = sa[i];
+          for (i = 0; i < E; ++i) FSO_MOVE(i, sa[i], ca[i]);
           break;
         case FSO_CONCAT:
           if (n->attr_i == 1) {
             const long Ca = g->nodes[n->in[0]].cols, Cb = g->nodes[n->in[1]].cols;
-            for (i = 0; i < R; ++i) for (j = 0; j < C; ++j) sg[i * C + j] = j < Ca ? sa[i * Ca + j] : sb[i * Cb + (j - Ca)];
+            for (i = 0; i < R; ++i) for (j = 0; j < C; ++j) {
+              if (j < Ca) FSO_MOVE(i * C + j, sa[i * Ca + j], ca[i * Ca + j]); else FSO_MOVE(i * C + j, sb[i * Cb + (j - Ca)], cb[i * Cb + (j - Ca)]);
+            }
           } else {
             const long Ra = g->nodes[n->in[0]].rows;
-            for (i = 0; i < R; ++i) for (j = 0; j < C; ++j) sg[i * C + j] = i < Ra ? sa[i * C + j] : sb[(i - Ra) * C + j];
+            for (i = 0; i < R; ++i) for (j = 0; j < C; ++j) {
+              if (i < Ra) FSO_MOVE(i * C + j, sa[i * C + j], ca[i * C + j]); else FSO_MOVE(i * C + j, sb[(i - Ra) * C + j], cb[(i - Ra) * C + j]);
+            }
           }
           break;
         case FSO_REDUCE_ROW: case FSO_REDUCE_COL: {
@@ -385,42 +402,49 @@ int fso_run(const fso_graph* g, const void* const* host_in, void* const* host_ou
           const long outs = rowwise ? R : C, step = rowwise ? 1 : C;
           long t;
           for (i = 0; i < outs; ++i) {
-            const double* p = a + (rowwise ? i * cnt : i);
-            const double* q = sa + (rowwise ? i * cnt : i);
+            const long base = rowwise ? i * cnt : i;
+            const double* p = a + base;
             if (n->attr_i == FSO_SUM || n->attr_i == FSO_MEAN) {
-              double var = 0.0, total;
-              for (t = 0; t < cnt; ++t) var += q[t * step] * q[t * step];
+              double var = 0.0, lin = 0.0, total;
+              for (t = 0; t < cnt; ++t) var += sa[base + t * step] * sa[base + t * step], lin += ca[base + t * step];
               double sd = sqrt(var + pairwise_rounding_variance(p, cnt, step, &total));
-              if (n->attr_i == FSO_MEAN) sd = quad(sd / (double)cnt, local_spread(n, out[i]));
-              sg[i] = sd;
+              if (n->attr_i == FSO_MEAN) sd = quad(sd / (double)cnt, local_spread(n, out[i])), lin /= (double)cnt;
+              FSO_MOVE(i, sd, lin);
             } else { /* max / min: the spread of the element that was picked */
               long pick = 0;
               for (t = 1; t < cnt; ++t)
                 if (n->attr_i == FSO_MAX_ ? p[t * step] > p[pick * step] : p[t * step] < p[pick * step]) pick = t;
-              sg[i] = q[pick * step];
+              FSO_MOVE(i, sa[base + pick * step], ca[base + pick * step]);
             }
           }
           break;
         }
         default:
           if (n->num_in == 1) {
+            const int approx = is_approximated(n->opcode), moves = n->opcode == FSO_NEG || n->opcode == FSO_ABS;
 #pragma omp parallel for
-            for (i = 0; i < E; ++i) sg[i] = quad(unary_slope(n->opcode, a[i]) * sa[i], n->opcode == FSO_NEG || n->opcode == FSO_ABS ? 0.0 : local_spread(n, out[i]));
+            for (i = 0; i < E; ++i) {
+              const double slope = unary_slope(n->opcode, a[i]), own = moves ? 0.0 : local_spread(n, out[i]);
+              sg[i] = approx ? slope * sa[i] : quad(slope * sa[i], own);
+              ch[i] = slope * ca[i] + (approx ? own : 0.0);
+            }
           } else if (n->num_in == 2) {
 #pragma omp parallel for
             for (i = 0; i < E; ++i) {
-              double sd;
+              double sd, lin;
               switch (n->opcode) {
-                case FSO_ADD: case FSO_SUB: sd = quad(sa[i], sb[i]); break;
-                case FSO_MUL: sd = quad(b[i] * sa[i], a[i] * sb[i]); break;
-                case FSO_DIV: sd = quad(sa[i] / b[i], a[i] * sb[i] / (b[i] * b[i])); break;
-                case FSO_MAX: sd = a[i] >= b[i] ? sa[i] : sb[i]; break;
-                default: sd = a[i] <= b[i] ? sa[i] : sb[i]; break; /* FSO_MIN */
+                case FSO_ADD: case FSO_SUB: sd = quad(sa[i], sb[i]), lin = ca[i] + cb[i]; break;
+                case FSO_MUL: sd = quad(b[i] * sa[i], a[i] * sb[i]), lin = fabs(b[i]) * ca[i] + fabs(a[i]) * cb[i]; break;
+                case FSO_DIV: sd = quad(sa[i] / b[i], a[i] * sb[i] / (b[i] * b[i])), lin = ca[i] / fabs(b[i]) + fabs(a[i]) * cb[i] / (b[i] * b[i]); break;
+                case FSO_MAX: sd = a[i] >= b[i] ? sa[i] : sb[i], lin = a[i] >= b[i] ? ca[i] : cb[i]; break;
+                default: sd = a[i] <= b[i] ? sa[i] : sb[i], lin = a[i] <= b[i] ? ca[i] : cb[i]; break; /* FSO_MIN */
               }
               sg[i] = (n->opcode == FSO_MAX || n->opcode == FSO_MIN) ? sd : quad(sd, local_spread(n, out[i]));
+              ch[i] = lin;
             }
           }
       }
+#undef FSO_MOVE
     }
 
     /* free operands whose last consumer this was */
@@ -441,7 +465,7 @@ int fso_run(const fso_graph* g, const void* const* host_in, void* const* host_ou
     if (!v || !host_out[k]) { rc = -1; break; }
     if (spread) { /* companion 3 hands back the spreads, as doubles, whatever the output's dtype */
       double* d = (double*)host_out[k];
-      for (i = 0; i < E; ++i) d[i] = sig[o] ? sig[o][i] : 0.0;
+      for (i = 0; i < E; ++i) d[i] = sig[o] ? sig[o][i] + sig[o][E + i] : 0.0; /* noise + lean */
       continue;
     }
     if (n->dtype == FSO_F32) {

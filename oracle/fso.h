@@ -81,8 +81,11 @@ typedef struct {
  *                   spacing taken as 2^-23 |result|); exp, log, tanh, sigmoid, rsqrt, rcp and gelu, which
  *                   a GPU builds on hardware approximations good to 1-2 spacings, have a spread of one
  *                   spacing; a sum accumulated in fp32 rounds every partial sum of a balanced pairwise
- *                   summation; errors are independent, travel through each op's derivative and add in
- *                   quadrature; inputs, constants, predicates and bf16 roundings are exact.  Where
+ *                   summation.  Rounding errors are independent, travel through each op's derivative and
+ *                   add in quadrature; the errors of approximated ops may lean one way over many elements
+ *                   (an approximation is a fixed function, not noise), so they travel through the
+ *                   derivatives' absolute values and add linearly; an element's spread is the sum of the
+ *                   two parts.  Inputs, constants, predicates and bf16 roundings are exact.  Where
  *                   companions 0 and 2 each show ONE realisation of rounding noise (which can be small at
  *                   an element by chance), this one gives its scale.  Never the pass/fail reference.
  * Returns 0, or a negative code: -1 bad argument, -2 bad graph, -3 out of memory.

@@ -303,7 +303,8 @@ def test_spread_companion_against_numpy_float32_arithmetic():
     # round_nodes=3 returns no values but the first-order spread of a correct fp32 implementation around the reference.  It is
     # pinned against such implementations: numpy's own float32 arithmetic (correctly rounded + - * /, a float32 tanh, a pairwise
     # float32 sum), whose actual deviation from the fp64 result must be of the size the spread says - within 4.5 spreads almost
-    # everywhere (it is a standard deviation), and neither far below nor far above it in the root mean square.
+    # everywhere (rounding noise enters as a standard deviation, the error of an approximated op as one spacing), and neither far
+    # below nor far above it in the root mean square.
     n = 20000
     x, y, z, w = (RNG.uniform(-2, 2, (1, n)).astype(np.float32) for _ in range(4))
     g = Graph()
@@ -365,7 +366,8 @@ def test_spread_companion_structure():
     np.testing.assert_array_equal(ssel, np.where(x > y, se, 0.0))
     np.testing.assert_array_equal(srmax[:, 0], se[np.arange(rows), np.argmax(x, axis=1)])   # exp is monotonic: the largest x
     np.testing.assert_array_equal(scat, np.concatenate([se, np.zeros_like(se)], axis=1))
-    assert (sadd > np.maximum(se, srmax)).all() and (sadd < 1.5 * np.sqrt(se ** 2 + srmax ** 2) + 1e-7).all()   # in quadrature, plus the add's own rounding
+    # the errors of two approximated results add linearly (they may lean the same way); the add's own rounding comes on top, in quadrature
+    assert (sadd >= se + srmax).all() and (sadd < se + srmax + 3e-7).all()
 
 
 def test_softmax_pins():
