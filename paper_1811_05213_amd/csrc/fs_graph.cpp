@@ -39,6 +39,160 @@ const char* op_name(int op) {
 
 static bool is_float_dtype(int dt) { return dt == FS_F32 || dt == FS_BF16; }
 
+// -------------------------------------------------------------------------------------------
+// Reshape / Bitcast between elementwise regions (Table 1: the schedule passes through a Reshape when the split
+// dimension survives).  Tensors are dense and row-major, so a Row schedule cut along dimension 0 owns a run of
+// consecutive elements whatever [rows, cols] that run is labelled with: an elementwise region - unary, binary,
+// compare and select ops whose operands are whole tensors or constants, no broadcast, no reduction, no transpose -
+// computes the same thing under either label.  For a view v = reshape(p) the region on one side is therefore
+// re-labelled with the shape of the other side and v becomes transparent (its users read p directly), so that
+// both sides can share a kernel.  Tried in this order:
+//   down  the users of v, and what follows them, are such a region ending in plan outputs: they take p's shape
+//         (p's side keeps its row structure: a softmax followed, through a reshape, by a residual add is one kernel);
+//   up    p and what it is computed from are such a region used by nothing else: they take v's shape (an activation
+//         followed, through a reshape, by a reduction over the new rows is one kernel).
+// Where a re-labelled node reads a tensor that keeps its own label (a plan input, another kernel's result), the
+// operand slot is marked flat_in: the kernel addresses it by row * C + column of its own work space, which is the
+// same element.  A concat or a transpose at the edge of a region stops the re-labelling (inside a kernel they are
+// free, alone they would cost a launch).  Node ids, dtypes and values are untouched.
+// -------------------------------------------------------------------------------------------
+static bool is_elementwise_op(int op) { return op_is_unary(op) || op_is_binary(op) || op == FS_CMP || op == FS_SELECT; }
+
+static void absorb_views(Graph* g) {
+  const int N = g->n();
+  g->flat_in.assign(N, {{0, 0, 0}});
+  g->views_absorbed = 0;
+  auto rebuild_users = [&]() {
+    // a view nothing reads any more (and that is no plan output) is dead: it does not count as a user
+    std::vector<char> live(N, 1);
+    std::vector<int> n_users(N, 0);
+    for (int id = 0; id < N; ++id)
+      for (int k = 0; k < g->nodes[id].num_in; ++k) ++n_users[g->nodes[id].in[k]];
+    for (int id = N - 1; id >= 0; --id)
+      if (op_is_view(g->nodes[id].opcode) && n_users[id] == 0 && g->output_index[id] < 0) {
+        live[id] = 0;
+        --n_users[g->nodes[id].in[0]];
+      }
+    g->users.assign(N, {});
+    for (int id = 0; id < N; ++id)
+      if (live[id])
+        for (int k = 0; k < g->nodes[id].num_in; ++k) g->users[g->nodes[id].in[k]].push_back(id);
+  };
+  auto same_shape = [&](int x, int rows, int cols) { return g->nodes[x].rows == rows && g->nodes[x].cols == cols; };
+  // may `o` stay outside a re-labelled region and be read flat by it?
+  auto flat_readable = [&](int o) {
+    const int op = g->nodes[o].opcode;
+    return op != FS_BCAST_ROWVEC && op != FS_BCAST_COLVEC && op != FS_CONCAT && op != FS_TRANSPOSE;
+  };
+  for (int v = 0; v < N; ++v) {
+    if (!op_is_view(g->nodes[v].opcode)) continue;
+    const int p = g->nodes[v].in[0];
+    const fs_node pn = g->nodes[p], vn = g->nodes[v];
+    if (op_is_free(pn.opcode) || g->users[v].empty()) continue;  // views of inputs and of views cost nothing as they are
+    if (pn.rows == vn.rows && pn.cols == vn.cols) continue;
+    std::vector<char> in_region(N, 0);
+    std::vector<int> region;
+    bool ok = true;
+    // ---- down: everything downstream of v, up to plan outputs
+    {
+      std::vector<int> stack(g->users[v].begin(), g->users[v].end());
+      while (!stack.empty() && ok) {
+        const int u = stack.back();
+        stack.pop_back();
+        if (in_region[u]) continue;
+        const fs_node& un = g->nodes[u];
+        if (!is_elementwise_op(un.opcode) || !same_shape(u, vn.rows, vn.cols)) { ok = false; break; }
+        in_region[u] = 1;
+        region.push_back(u);
+        for (int w : g->users[u]) stack.push_back(w);
+      }
+      // side inputs of the region that are elementwise work for it alone (a convert of a residual) come along
+      for (bool grew = ok; grew;) {
+        grew = false;
+        for (size_t r = 0; r < region.size(); ++r) {
+          const fs_node& rn = g->nodes[region[r]];
+          for (int k = 0; k < rn.num_in; ++k) {
+            const int o = rn.in[k];
+            if (o == v || in_region[o] || !is_elementwise_op(g->nodes[o].opcode) || !same_shape(o, vn.rows, vn.cols) || g->output_index[o] >= 0) continue;
+            bool all_inside = true, readable = true;
+            for (int w : g->users[o]) all_inside &= (bool)in_region[w];
+            for (int q = 0; q < g->nodes[o].num_in; ++q) {
+              const int oo = g->nodes[o].in[q];
+              readable &= g->nodes[oo].opcode == FS_CONST || (flat_readable(oo) && same_shape(oo, vn.rows, vn.cols));
+            }
+            if (all_inside && readable) in_region[o] = 1, region.push_back(o), grew = true;
+          }
+        }
+      }
+      for (int u : region)
+        for (int k = 0; k < g->nodes[u].num_in && ok; ++k) {
+          const int o = g->nodes[u].in[k];
+          if (o != v && !in_region[o] && g->nodes[o].opcode != FS_CONST && !(flat_readable(o) && same_shape(o, vn.rows, vn.cols))) ok = false;
+        }
+      if (ok && !region.empty()) {
+        for (int u : region) {
+          fs_node& un = g->nodes[u];
+          for (int k = 0; k < un.num_in; ++k) {
+            if (un.in[k] == v) un.in[k] = p;
+            else if (!in_region[un.in[k]]) g->flat_in[u][k] = 1;
+          }
+          un.rows = pn.rows, un.cols = pn.cols;
+        }
+        ++g->views_absorbed;
+        rebuild_users();
+        continue;
+      }
+    }
+    // ---- up: p and what it is computed from, used by nothing but this view
+    std::fill(in_region.begin(), in_region.end(), 0);
+    region.clear();
+    if (!is_elementwise_op(pn.opcode) || g->users[p].size() != 1 || g->output_index[p] >= 0) continue;
+    in_region[p] = 1;
+    region.push_back(p);
+    for (bool grew = true; grew;) {  // an operand joins once every one of its users is inside
+      grew = false;
+      for (size_t r = 0; r < region.size(); ++r) {
+        const fs_node& rn = g->nodes[region[r]];
+        for (int k = 0; k < rn.num_in; ++k) {
+          const int o = rn.in[k];
+          if (in_region[o] || !is_elementwise_op(g->nodes[o].opcode) || !same_shape(o, pn.rows, pn.cols) || g->output_index[o] >= 0) continue;
+          bool all_inside = true;
+          for (int w : g->users[o]) all_inside &= (bool)in_region[w];
+          if (all_inside) in_region[o] = 1, region.push_back(o), grew = true;
+        }
+      }
+    }
+    // drop members whose operands cannot be read flat, and whoever depends on having them inside, until it settles
+    for (bool changed = true; changed && in_region[p];) {
+      changed = false;
+      for (int u : region) {
+        if (!in_region[u]) continue;
+        bool good = true;
+        for (int k = 0; k < g->nodes[u].num_in; ++k) {
+          const int o = g->nodes[u].in[k];
+          if (!in_region[o] && g->nodes[o].opcode != FS_CONST && !(flat_readable(o) && same_shape(o, pn.rows, pn.cols))) good = false;
+        }
+        for (int w : g->users[u])
+          if (w != v && !in_region[w]) good = false;
+        if (!good) in_region[u] = 0, changed = true;
+      }
+    }
+    if (!in_region[p]) continue;
+    for (int u : region) {
+      if (!in_region[u]) continue;
+      fs_node& un = g->nodes[u];
+      for (int k = 0; k < un.num_in; ++k)
+        if (!in_region[un.in[k]]) g->flat_in[u][k] = 1;
+      un.rows = vn.rows, un.cols = vn.cols;
+    }
+    for (int u : std::vector<int>(g->users[v]))
+      for (int k = 0; k < g->nodes[u].num_in; ++k)
+        if (g->nodes[u].in[k] == v) g->nodes[u].in[k] = p;
+    ++g->views_absorbed;
+    rebuild_users();
+  }
+}
+
 fs_status build_graph(const fs_graph_desc* desc, Graph* g) {
   if (!desc) FS_FAIL(FS_ERR_INVALID_ARG, "desc is NULL");
   if (desc->abi_version != FS_ABI_VERSION)
@@ -172,6 +326,18 @@ fs_status build_graph(const fs_graph_desc* desc, Graph* g) {
     family_output[root] = k;
     g->output_index[o] = k;
     g->outputs.push_back(o);
+  }
+
+  // views between elementwise regions become transparent (operand edges and shape labels change, ids do not);
+  // what was derived from the edges is derived again
+  absorb_views(g);
+  if (g->views_absorbed > 0) {
+    g->exact.assign(N, 0);
+    for (int id = N - 1; id >= 0; --id) {
+      const fs_node& n = g->nodes[id];
+      if (n.opcode == FS_CMP || g->exact[id])
+        for (int k = 0; k < n.num_in; ++k) g->exact[n.in[k]] = 1;
+    }
   }
   return FS_OK;
 }

@@ -517,6 +517,7 @@ fs_status analyse_group(const Graph& g, const std::vector<int>& members, const s
     const bool t = tf[m], t_op = n.opcode == FS_TRANSPOSE ? !t : t;
     R = std::max(R, t ? n.cols : n.rows), C = std::max(C, t ? n.rows : n.cols);
     for (int k = 0; k < n.num_in; ++k) {
+      if (g.flat_in[m][k]) continue;  // read as an element sequence under this node's own shape: its label says nothing here
       const fs_node& o = g.nodes[n.in[k]];
       R = std::max(R, t_op ? o.cols : o.rows), C = std::max(C, t_op ? o.rows : o.cols);
     }
@@ -557,6 +558,21 @@ fs_status analyse_group(const Graph& g, const std::vector<int>& members, const s
     int lvl = result_kind == KIND_ROWV && !deferred ? -1 : 0;
     for (int k = 0; k < n.num_in && n.opcode != FS_CONCAT; ++k) {
       Resolved r;
+      if (g.flat_in[m][k]) {
+        // a tensor in memory under another [rows, cols] label: the same elements at row * C + column of this work space.
+        // It cannot come from this kernel's registers (another label means another assignment of elements to lanes).
+        const int o = n.in[k];
+        if (g.nodes[o].opcode == FS_CONST) continue;
+        if (a.in_set[o] || a.in_set[g.root_of[o]])
+          FS_FAIL(FS_ERR_UNSUPPORTED, "node %d reads node %d under another shape: it has to exist in memory first", m, o);
+        if (t_op || operand_kind != KIND_FULL || (int64_t)g.nodes[o].rows * g.nodes[o].cols != (int64_t)R * C)
+          FS_FAIL(FS_ERR_UNSUPPORTED, "node %d: operand %d (read as a flat element sequence) does not fill the work space [%d,%d]", m, o, R, C);
+        for (const ExtTensor& e : gp.ext_in)
+          if (e.node == o && e.kind != KIND_FULL) FS_FAIL(FS_ERR_UNSUPPORTED, "node %d is read in two ways", o);
+        add_ext_in(gp, o, KIND_FULL, g.nodes[o].dtype);
+        gp.kind[o] = KIND_FULL;
+        continue;
+      }
       if (!a.resolve(n.in[k], operand_kind, t_op, &r))
         FS_FAIL(FS_ERR_UNSUPPORTED, "node %d: operand %d does not fit the group's work space [%d,%d]", m, n.in[k], R, C);
       if (r.literal) continue;

@@ -5,6 +5,7 @@
 #include <cstdarg>
 #include <cstdint>
 #include <cstdio>
+#include <array>
 #include <map>
 #include <mutex>
 #include <string>
@@ -61,6 +62,10 @@ struct Graph {
   std::vector<char> exact;               // node feeds a predicate: its bits must be reproducible (no contraction)
   std::vector<int> root_of;              // the node whose buffer a node's bytes live in: itself, or what its chain of views starts from
   std::vector<int> family_output;        // root -> index of the plan output (the root itself or a view of it) whose buffer holds it, or -1
+  // flat_in[node][k]: operand k is a tensor in memory whose row-major element sequence the node reads under its own
+  // [rows, cols] (set by absorb_views: an elementwise region re-labelled with the shape on the other side of a view)
+  std::vector<std::array<unsigned char, 3>> flat_in;
+  int views_absorbed = 0;                // views that absorb_views made transparent
   int n() const { return (int)nodes.size(); }
 };
 

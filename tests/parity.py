@@ -35,10 +35,12 @@ tensor's own scale.  Two refinements replace any blanket slack:
    rounding that happened to be almost exact), while the device's own error there is not: a row maximum of differences
    of nearly equal tanh values - results ~5e-5 from operands ~1 - came out one operand spacing (6e-8, six tolerances)
    off at one element of one graph of the sweep with views, with |A - B| = 1e-9 there.  The third companion (S) is
-   therefore not a realisation but the SCALE of that noise: the oracle propagates, to first order and in quadrature,
-   a spread of spacing/sqrt(12) per correctly rounded op, one spacing per approximated op (exp, log, tanh, sigmoid,
-   rsqrt, rcp, gelu: 1-2 spacings on the device) and the accumulation term of C through every node.  An element
-   whose spread S exceeds a quarter of its tolerance is flagged like the others.
+   therefore not a realisation but the SCALE of the error: the oracle propagates, to first order, rounding noise
+   (spacing/sqrt(12) per correctly rounded op and per partial sum of a pairwise summation; independent, added in
+   quadrature) and the error of approximated ops (exp, log, tanh, sigmoid, rsqrt, rcp, gelu: 1-2 spacings on the
+   device, one in the model; an approximation leans one way over a range of arguments, so these are added linearly -
+   a row sum of 130 bounded terms was 1.01 tolerances off in another graph of that sweep) through every node.  An
+   element whose spread S exceeds a quarter of its tolerance is flagged like the others.
    Those elements are counted and held to |gpu - A| <= 16*max(|A - B|, |A - C|) + 8*S + tol instead; a
    plan with more than a tenth of its output elements flagged fails as a test case (it would test
    little).  The random-graph generator squashes every reduction through tanh / sigmoid, so rows

@@ -669,17 +669,67 @@ def test_views_cost_no_launch_and_no_copy():
     u = fs.Plan(g, mode=fs.FS_MODE_UNFUSED)
     assert u.stats()["num_launches"] == len(g.compute_ids()) == 6     # the two views are not launches
     u.destroy()
-    # a reshape between two computations separates them (the consumer's rows are not the producer's) without a copy:
-    # the producer writes once, the consumer reads the same bytes under the other shape
+    # a reshape between two computations that both have a row structure separates them (the consumer's rows are not the
+    # producer's) without a copy: the producer writes once, the consumer reads the same bytes under the other shape
     g2 = Graph()
     x = g2.input(128, 256)
-    a = g2.unary("tanh", x)
+    a = g2.binary("sub", x, g2.bcast_colvec(g2.reduce_row("max", x), 256))
     r = g2.reshape(a, 512, 64)
     s = g2.reduce_row("sum", r)
     g2.set_outputs([g2.binary("sub", r, g2.bcast_colvec(s, 64))])
     p = fs.Plan(g2)
     assert p.stats()["num_launches"] == 2 and p.workspace_bytes() >= 128 * 256 * 4
     assert p.stats()["launched_hbm_bytes"] == 4 * 128 * 256 * 4
+    p.destroy()
+
+
+def test_a_reshape_next_to_an_elementwise_region_is_fused_through():
+    # Table 1: a Row schedule passes through a Reshape.  Dense row-major tensors make an elementwise region - no broadcast, no
+    # reduction - the same computation under either shape, so it takes the shape of the other side of the view and shares its kernel.
+    # up: an activation, a reshape, then a reduction over the NEW rows: one kernel in the new shape, the input read as it lies
+    g = Graph()
+    x, y = g.input(128, 256), g.input(128, 256)
+    a = g.binary("mul", g.unary("tanh", x), y)
+    r = g.reshape(a, 512, 64)
+    s = g.reduce_row("sum", r)
+    g.set_outputs([g.binary("sub", r, g.bcast_colvec(s, 64))])
+    p = fs.Plan(g)
+    gi = p.group_info(0)
+    assert p.stats()["num_launches"] == 1 and p.workspace_bytes() == 0 and (gi["dom_rows"], gi["dom_cols"]) == (512, 64)
+    assert p.stats()["launched_hbm_bytes"] == p.stats()["min_hbm_bytes"] == 3 * 128 * 256 * 4
+    p.destroy()
+    # down: a softmax over the old rows, a bitcast, then a residual add and an activation in the new shape: one kernel in the OLD shape
+    g = Graph()
+    x, res = g.input(96, 200), g.input(300, 64)
+    e = g.unary("exp", g.binary("sub", x, g.bcast_colvec(g.reduce_row("max", x), 200)))
+    sm = g.binary("div", e, g.bcast_colvec(g.reduce_row("sum", e), 200))
+    v = g.reshape(sm, 300, 64, op="bitcast")
+    g.set_outputs([g.unary("gelu_tanh", g.binary("add", v, res))])
+    p = fs.Plan(g)
+    gi = p.group_info(0)
+    assert p.stats()["num_launches"] == 1 and p.workspace_bytes() == 0 and (gi["dom_rows"], gi["dom_cols"]) == (96, 200)
+    p.destroy()
+    # the unfused executor runs every op on its own either way
+    u = fs.Plan(g, mode=fs.FS_MODE_UNFUSED)
+    assert u.stats()["num_launches"] == len(g.compute_ids())
+    u.destroy()
+    # not through: the value is also needed under its old shape by something with a row structure, or a broadcast sits in the region
+    g = Graph()
+    x, w = g.input(128, 256), g.input(1, 256)
+    a = g.binary("mul", g.unary("tanh", x), g.bcast_rowvec(w, 128))     # a per-column operand: tied to the old columns
+    r = g.reshape(a, 512, 64)
+    g.set_outputs([g.binary("sub", r, g.bcast_colvec(g.reduce_row("sum", r), 64))])
+    p = fs.Plan(g)
+    assert p.stats()["num_launches"] == 2
+    p.destroy()
+    # a region that ends in a plan output and a view of something else: both views absorbed, still one kernel
+    g = Graph()
+    x, y = g.input(64, 96), g.input(48, 128)
+    a = g.unary("sigmoid", x)
+    b = g.binary("add", g.reshape(a, 48, 128), y)
+    g.set_outputs([g.reshape(g.unary("neg", b), 64, 96)])
+    p = fs.Plan(g)
+    assert p.stats()["num_launches"] == 1 and p.workspace_bytes() == 0
     p.destroy()
 
 

@@ -834,6 +834,44 @@ def test_gpu_matches_the_stored_small_cases():
             check_all(g, run_graph(g, ins, mode=mode), ref, f"stored case {name} mode {mode}")
 
 
+def test_kernels_fused_through_a_reshape():
+    # an elementwise region next to a view takes the shape of the other side and shares its kernel (Table 1: the Row schedule
+    # passes through a Reshape): the region's tensors are then addressed as flat element sequences of the kernel's work space
+    g = Graph()
+    x, y = g.input(128, 256), g.input(128, 256)
+    a = g.binary("mul", g.unary("tanh", x), y)
+    r = g.reshape(a, 512, 64)
+    s = g.reduce_row("sum", r)
+    g.set_outputs([g.binary("sub", r, g.bcast_colvec(s, 64))])
+    p = fs.Plan(g)
+    assert p.stats()["num_launches"] == 1
+    p.destroy()
+    both_modes(g, [RNG.standard_normal((128, 256)).astype(np.float32), (1.0 + RNG.random((128, 256))).astype(np.float32)], "activation | reshape | row reduction")
+    # softmax over the old rows, then a residual add and GeLU under the new shape; ragged sizes, a bf16 residual
+    for rows, cols, r2, c2 in ((96, 200, 300, 64), (77, 130, 10010, 1), (4096, 260, 8192, 130)):
+        g = Graph()
+        x, res = g.input(rows, cols), g.input(r2, c2, "bf16")
+        e = g.unary("exp", g.binary("sub", x, g.bcast_colvec(g.reduce_row("max", x), cols)))
+        sm = g.binary("div", e, g.bcast_colvec(g.reduce_row("sum", e), cols))
+        v = g.reshape(sm, r2, c2, op="bitcast")
+        g.set_outputs([g.unary("gelu_tanh", g.binary("add", v, g.unary("convert", res, "f32")))])
+        p = fs.Plan(g)
+        assert p.stats()["num_launches"] == 1 and p.workspace_bytes() == 0
+        p.destroy()
+        both_modes(g, [RNG.standard_normal((rows, cols)).astype(np.float32), f32_to_bf16_bits(RNG.standard_normal((r2, c2)).astype(np.float32))],
+                   f"softmax | bitcast | residual + gelu {rows}x{cols} -> {r2}x{c2}")
+    # two views around a region, outputs on both sides of them, a predicate inside the region
+    g = Graph()
+    x, y = g.input(64, 96), g.input(48, 128)
+    a = g.unary("sigmoid", x)
+    v = g.reshape(a, 48, 128)
+    b = g.binary("add", v, y)
+    pred = g.cmp("gt", v, y)
+    c = g.select(pred, b, g.unary("neg", y))
+    g.set_outputs([g.reshape(g.unary("neg", c), 64, 96), pred, b])
+    both_modes(g, [RNG.standard_normal((64, 96)).astype(np.float32), RNG.standard_normal((48, 128)).astype(np.float32)], "region between two views")
+
+
 # ------------------------------------------------------------------ reshape / bitcast / concat
 def test_views_of_nd_tensors_and_concats():
     """Reshape / Bitcast as zero-cost views between kernels and at the plan's edges; Concat read as one row."""
