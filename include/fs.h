@@ -75,10 +75,12 @@ typedef enum { FS_F32 = 0, FS_BF16 = 1, FS_U8 = 2 } fs_dtype;
  * Tensors of any rank enter the plan as [rows, cols] = [product of the leading dims, product
  * of the trailing dims] of their dense row-major layout; FS_RESHAPE moves that split (or
  * regroups the element sequence in any other way that keeps the element count).  In the
- * schedule terms of Section 4.1 / Table 1 this is the split_dim of a Row schedule: a Reshape
- * that keeps whole rows of the consumer inside rows of the producer passes a schedule
- * through; any other one separates two fused computations.  Here every Reshape / Bitcast is a
- * zero-cost view at a boundary between kernels: producer and consumer address the same bytes.
+ * schedule terms of Section 4.1 / Table 1 this is the split_dim of a Row schedule, which a Reshape
+ * passes through when the split dimension survives.  Here a Reshape / Bitcast next to an elementwise
+ * region (no broadcast, no reduction, no transpose on that side) is passed through: the region is
+ * computed under the shape of the other side and shares its kernel.  Between two computations that
+ * both have a row structure it is a zero-cost view at a boundary between kernels: producer and
+ * consumer address the same bytes.
  */
 typedef enum {
   FS_INPUT = 0,  /* external tensor; the k-th FS_INPUT node (in id order) is inputs[k] of fs_plan_run */
