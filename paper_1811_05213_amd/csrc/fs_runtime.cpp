@@ -142,33 +142,150 @@ fs_status compile_kernel(const std::string& source, const std::string& name, std
   return FS_OK;
 }
 
-// One integer field of every kernel of a code object, read from its metadata note: the msgpack
-// integer after each occurrence of `key` (".private_segment_fixed_size": scratch, i.e. register
-// spill, bytes; ".vgpr_count": vector registers), attributed to the kernel whose ".name" key
-// precedes it in the same map (the keys of a kernel's map are sorted).
+// One integer field of every kernel of a code object (".private_segment_fixed_size": scratch, i.e. register spill,
+// bytes; ".vgpr_count": vector registers), read from the code object's metadata: the ELF note named "AMDGPU" of type
+// 32 holds a msgpack map whose "amdhsa.kernels" entry is an array of one map per kernel (".name", then the fields).
+// A small msgpack reader walks it; anything malformed ends the walk and yields an empty result.
+namespace {
+struct MsgPack {
+  const unsigned char* p;
+  const unsigned char* end;
+  bool ok = true;
+  bool need(size_t n) {
+    if ((size_t)(end - p) < n) ok = false;
+    return ok;
+  }
+  uint64_t be(int n) {
+    uint64_t v = 0;
+    if (!need((size_t)n)) return 0;
+    for (int i = 0; i < n; ++i) v = (v << 8) | *p++;
+    return v;
+  }
+  // reads one value; strings and integers are reported, containers report their element count
+  enum Type { NIL, BOOL, INT, STR, ARRAY, MAP, OTHER };
+  Type next(std::string* str, int64_t* num, uint32_t* count) {
+    if (!need(1)) return OTHER;
+    const unsigned char b = *p++;
+    auto take_str = [&](uint64_t n) {
+      if (!need((size_t)n)) return OTHER;
+      if (str) str->assign((const char*)p, (size_t)n);
+      p += n;
+      return STR;
+    };
+    auto skip = [&](uint64_t n) {
+      if (need((size_t)n)) p += n;
+      return OTHER;
+    };
+    if (b <= 0x7f) { if (num) *num = b; return INT; }
+    if (b >= 0xe0) { if (num) *num = (int8_t)b; return INT; }
+    if ((b & 0xe0) == 0xa0) return take_str(b & 0x1f);
+    if ((b & 0xf0) == 0x90) { if (count) *count = b & 0x0f; return ARRAY; }
+    if ((b & 0xf0) == 0x80) { if (count) *count = b & 0x0f; return MAP; }
+    switch (b) {
+      case 0xc0: return NIL;
+      case 0xc2: case 0xc3: if (num) *num = b == 0xc3; return BOOL;
+      case 0xc4: return skip(be(1));
+      case 0xc5: return skip(be(2));
+      case 0xc6: return skip(be(4));
+      case 0xca: return skip(4);
+      case 0xcb: return skip(8);
+      case 0xcc: if (num) *num = (int64_t)be(1); else be(1); return INT;
+      case 0xcd: if (num) *num = (int64_t)be(2); else be(2); return INT;
+      case 0xce: if (num) *num = (int64_t)be(4); else be(4); return INT;
+      case 0xcf: if (num) *num = (int64_t)be(8); else be(8); return INT;
+      case 0xd0: { const int64_t v = (int8_t)be(1); if (num) *num = v; return INT; }
+      case 0xd1: { const int64_t v = (int16_t)be(2); if (num) *num = v; return INT; }
+      case 0xd2: { const int64_t v = (int32_t)be(4); if (num) *num = v; return INT; }
+      case 0xd3: { const int64_t v = (int64_t)be(8); if (num) *num = v; return INT; }
+      case 0xd9: return take_str(be(1));
+      case 0xda: return take_str(be(2));
+      case 0xdb: return take_str(be(4));
+      case 0xdc: if (count) *count = (uint32_t)be(2); else be(2); return ARRAY;
+      case 0xdd: if (count) *count = (uint32_t)be(4); else be(4); return ARRAY;
+      case 0xde: if (count) *count = (uint32_t)be(2); else be(2); return MAP;
+      case 0xdf: if (count) *count = (uint32_t)be(4); else be(4); return MAP;
+    }
+    ok = false;  // extension types do not occur in this metadata
+    return OTHER;
+  }
+  void skip_value(int depth = 0) {
+    uint32_t n = 0;
+    const Type t = next(nullptr, nullptr, &n);
+    if (!ok || depth > 32) { ok = false; return; }
+    if (t == ARRAY) for (uint32_t i = 0; i < n && ok; ++i) skip_value(depth + 1);
+    if (t == MAP) for (uint32_t i = 0; i < 2 * n && ok; ++i) skip_value(depth + 1);
+  }
+};
+
+// the msgpack metadata of an AMDGPU code object (ELF64, little endian), or an empty range
+bool amdgpu_metadata(const std::vector<char>& code, const unsigned char** begin, const unsigned char** end) {
+  const unsigned char* d = (const unsigned char*)code.data();
+  const size_t n = code.size();
+  auto rd = [&](size_t off, int bytes) {
+    uint64_t v = 0;
+    for (int i = bytes - 1; i >= 0; --i) v = (v << 8) | d[off + i];
+    return v;
+  };
+  if (n < 64 || memcmp(d, "\177ELF", 4) != 0 || d[4] != 2 || d[5] != 1) return false;
+  const uint64_t shoff = rd(0x28, 8), shentsize = rd(0x3a, 2), shnum = rd(0x3c, 2);
+  if (shentsize < 64 || shoff > n || shnum > (n - shoff) / shentsize) return false;
+  for (uint64_t k = 0; k < shnum; ++k) {
+    const size_t sh = (size_t)(shoff + k * shentsize);
+    if (rd(sh + 4, 4) != 7 /* SHT_NOTE */) continue;
+    const uint64_t off = rd(sh + 0x18, 8), size = rd(sh + 0x20, 8);
+    if (off > n || size > n - off) continue;
+    size_t q = (size_t)off;
+    const size_t stop = (size_t)(off + size);
+    while (q + 12 <= stop) {
+      const uint64_t namesz = rd(q, 4), descsz = rd(q + 4, 4), type = rd(q + 8, 4);
+      const size_t name = q + 12, desc = name + (size_t)((namesz + 3) & ~(uint64_t)3);
+      if (desc > stop || descsz > stop - desc) break;
+      if (type == 32 && namesz == 7 && memcmp(d + name, "AMDGPU", 6) == 0) {
+        *begin = d + desc;
+        *end = d + desc + descsz;
+        return true;
+      }
+      q = desc + (size_t)((descsz + 3) & ~(uint64_t)3);
+    }
+  }
+  return false;
+}
+}  // namespace
+
 std::map<std::string, long> code_object_kernel_field(const std::vector<char>& code, const char* key) {
-  static const char name_key[] = ".name";
-  const size_t klen = strlen(key), nlen = sizeof(name_key) - 1;
   std::map<std::string, long> out;
-  for (size_t i = 0; i + klen + 5 <= code.size(); ++i) {
-    if (code[i] != '.' || memcmp(code.data() + i, key, klen) != 0) continue;
-    const unsigned char* p = (const unsigned char*)code.data() + i + klen;
-    long v = -1;
-    if (p[0] <= 0x7f) v = p[0];
-    else if (p[0] == 0xcc) v = p[1];
-    else if (p[0] == 0xcd) v = ((long)p[1] << 8) | p[2];
-    else if (p[0] == 0xce) v = ((long)p[1] << 24) | ((long)p[2] << 16) | ((long)p[3] << 8) | p[4];
-    if (v < 0) continue;
-    // the closest ".name" before the key, followed by a msgpack string
-    for (size_t j = i; j-- > 0 && i - j < 4096;) {
-      if (code[j] != '.' || memcmp(code.data() + j, name_key, nlen) != 0) continue;
-      const unsigned char* q = (const unsigned char*)code.data() + j + nlen;
-      size_t len = 0, skip = 0;
-      if ((q[0] & 0xe0) == 0xa0) len = q[0] & 0x1f, skip = 1;
-      else if (q[0] == 0xd9) len = q[1], skip = 2;
-      else break;
-      out[std::string((const char*)q + skip, len)] = v;
-      break;
+  MsgPack m{nullptr, nullptr};
+  if (!amdgpu_metadata(code, &m.p, &m.end)) return out;
+  uint32_t top = 0;
+  if (m.next(nullptr, nullptr, &top) != MsgPack::MAP) return out;
+  for (uint32_t e = 0; e < top && m.ok; ++e) {
+    std::string k;
+    if (m.next(&k, nullptr, nullptr) != MsgPack::STR) return out;
+    if (k != "amdhsa.kernels") {
+      m.skip_value();
+      continue;
+    }
+    uint32_t kernels = 0;
+    if (m.next(nullptr, nullptr, &kernels) != MsgPack::ARRAY) return out;
+    for (uint32_t i = 0; i < kernels && m.ok; ++i) {
+      uint32_t fields = 0;
+      if (m.next(nullptr, nullptr, &fields) != MsgPack::MAP) return out;
+      std::string name;
+      long value = -1;
+      for (uint32_t f = 0; f < fields && m.ok; ++f) {
+        std::string fk;
+        if (m.next(&fk, nullptr, nullptr) != MsgPack::STR) return out;
+        if (fk == ".name") {
+          if (m.next(&name, nullptr, nullptr) != MsgPack::STR) return out;
+        } else if (fk == key) {
+          int64_t v = -1;
+          if (m.next(nullptr, &v, nullptr) != MsgPack::INT) return out;
+          value = (long)v;
+        } else {
+          m.skip_value();
+        }
+      }
+      if (m.ok && !name.empty() && value >= 0) out[name] = value;
     }
   }
   return out;
