@@ -621,7 +621,7 @@ fs_status analyse_group(const Graph& g, const std::vector<int>& members, const s
     }
   }
   if (gp.ext_out.empty()) FS_FAIL(FS_ERR_UNSUPPORTED, "group produces nothing");
-  if (gp.ext_in.size() + gp.ext_out.size() > 48) FS_FAIL(FS_ERR_UNSUPPORTED, "group touches too many tensors");
+  if ((int)(gp.ext_in.size() + gp.ext_out.size()) > kMaxGroupTensors) FS_FAIL(FS_ERR_UNSUPPORTED, "group touches too many tensors");
 
   // row reductions of one stage share one exchange
   std::map<int, int> per_level;
@@ -841,7 +841,7 @@ struct Former {
           const bool straight = fits(plan[a].R, plan[b].R) && fits(plan[a].C, plan[b].C);
           const bool flipped = fits(plan[a].R, plan[b].C) && fits(plan[a].C, plan[b].R);
           if (!straight && !flipped) continue;
-          if (members[a].size() + members[b].size() > 96) continue;
+          if ((int)(members[a].size() + members[b].size()) > kMaxGroupMembers) continue;
           // profitable?
           bool share_full = false;
           for (const ExtTensor& x : plan[a].ext_in)
@@ -1065,7 +1065,7 @@ fs_status form_groups(const Graph& g, const fs_graph_desc* desc, const PlanOptio
         // condition 3: schedule and LDS plan of the merged group
         std::vector<int> merged = f.members[grp];
         merged.push_back(id);
-        if ((int)merged.size() > 96) continue;
+        if ((int)merged.size() > kMaxGroupMembers) continue;
         if (analyse_group(g, merged, f.group_of, grp, opt, &scratch) != FS_OK) continue;
         if (!worth_fusing(scratch)) continue;
         joined = grp;

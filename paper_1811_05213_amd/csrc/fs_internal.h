@@ -83,6 +83,13 @@ enum Kind : int {
   KIND_PART = 4   // an operand of a concat member: covers part of the work space, read through that member's two-source load
 };
 
+// Bounds of one fused group.  kMaxGroupTensors: pointers in a kernel's argument block (8 bytes each; the block and the
+// kernel's scalar registers hold them all, and a body that touches more tensors than this is bound by their traffic,
+// not by launches).  kMaxGroupMembers: compute nodes in one generated body (code size and compile time grow with it;
+// the 200-node benchmark DAG's largest group has 46).
+constexpr int kMaxGroupTensors = 48;
+constexpr int kMaxGroupMembers = 96;
+
 struct ExtTensor {
   int node = -1;
   Kind kind = KIND_NONE;
