@@ -159,7 +159,7 @@ def time_alu_probe(reps=5):
     import torch
     from paper_1811_05213_amd import alu_probe, device_limits
     cus = device_limits()["compute_units"]
-    workgroups, iters = cus * 32, 2000          # 32 x 256 lanes per CU = 8 wavefronts per SIMD; 256000 FMAs per lane
+    workgroups, iters = cus * 32, 2000          # 32 workgroups of 256 lanes per CU: four rounds of 8 wavefronts per SIMD; 256000 FMAs per lane
     out = torch.empty(workgroups * 256, dtype=torch.float32, device="cuda:0")
     stream = torch.cuda.current_stream().cuda_stream
     best = None
@@ -171,7 +171,7 @@ def time_alu_probe(reps=5):
         torch.cuda.synchronize()
         ms = e0.elapsed_time(e1)
         best = ms if best is None else min(best, ms)
-    fma_per_simd = iters * 128 * 8              # wavefront-FMAs one SIMD issues
+    fma_per_simd = iters * 128 * (workgroups * 4) // (cus * 4)   # wavefront-FMAs one SIMD issues: 4 wavefronts per workgroup, 4 SIMDs per CU
     return {"ms": best, "implied_clock_ghz": fma_per_simd * 4 / (best * 1e-3) / 1e9,
             "fp32_tflops": 2.0 * iters * 128 * 256 * workgroups / (best * 1e-3) / 1e12, "wavefronts_per_simd": 8}
 
