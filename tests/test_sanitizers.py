@@ -35,6 +35,8 @@ def _graphs():
     out = [("softmax", softmax_graph(40, 200)), ("layernorm", layernorm_gelu_graph(33, 520)), ("ew20", elementwise20_graph(20, 64)),
            ("multi", multi_reduce_graph(300, 36)), ("lngrad", layernorm_grad_graph(50, 130)), ("dag", random_dag_graph(rows=64, ks=(8, 24, 40)))]
     out += [(f"rand{seed}", random_graph(seed, r, c)) for seed, r, c in ((1, 37, 72), (6, 129, 34), (9, 65, 63))]
+    # ... and with reshapes / bitcasts / concats, which the planner's view-absorbing pass rewrites
+    out += [(f"randv{seed}", random_graph(seed, r, c, 35, views=True)) for seed, r, c in ((1000, 65, 63), (1004, 40, 200), (1017, 12, 330), (1076, 96, 26))]
     g = Graph()
     a, b, w = g.input(24, 20), g.input(24, 12), g.input(1, 96)
     c = g.concat(a, b)
