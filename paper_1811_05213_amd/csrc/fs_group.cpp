@@ -103,386 +103,460 @@ void add_ext_in(GroupPlan& gp, int node, Kind k, int dtype) {
 // over several wavefronts and folded through LDS; small problems trade elements per lane
 // for more wavefronts so that the 256 CUs all get work.
 // -------------------------------------------------------------------------------------------
-static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPlan* gp) {
-  Schedule& s = gp->s;
-  const int R = gp->R, C = gp->C;
+namespace {
+// The decisions of one group's schedule, taken in a fixed order; every step reads what the steps before it decided.
+struct Scheduler {
+  const Graph& g;
+  const PlanOptions& opt;
+  GroupPlan* gp;
+  Schedule& s;
+  const int R, C;
   // the machine: compute units and resident lanes as the device reports them (256 and 524288 on MI355X)
-  const int CUS = device_limits().cus;
-  const int64_t RES = device_limits().resident_lanes;
-  int max_es = 0;
-  for (const ExtTensor& e : gp->ext_in)
-    if (e.kind == KIND_FULL || e.kind == KIND_PART) max_es = std::max(max_es, dtype_size(e.dtype));
-  for (const ExtTensor& e : gp->ext_out)
-    if (e.kind == KIND_FULL) max_es = std::max(max_es, dtype_size(e.dtype));
-  if (max_es == 0) max_es = 4;
-  int V = 16 / max_es;
-  while (C % V) V /= 2;
-  bool has_concat = false;
-  for (int m : gp->members)
-    if (g.nodes[m].opcode == FS_CONCAT) {
-      has_concat = true;
-      if (g.nodes[m].attr_i == FS_CONCAT_COLS)  // a vector access must not straddle the seam
-        while (g.nodes[g.nodes[m].in[0]].cols % V) V /= 2;
-    }
-  const int NV = C / V;
-  const bool rowred = !gp->row_reduces.empty();
-  const bool colred = !gp->col_reduces.empty();
+  int CUS = 0;
+  int64_t RES = 0;
+  // what the group is made of
+  int max_es = 0, V = 4, NV = 0;
+  bool has_concat = false, rowred = false, colred = false, has_transposed = false, tileable = false;
+  // the form its rows take
+  int ecap = 8, l_min = 1, l_max = 1;
+  bool few_long_rows = false, split_rows = false, resident = false, chunked = false, col_tiled = false, tiled_transpose = false;
+  // lanes, vectors, workgroup
+  int L = 64, tt_rows = 64, NVL = 1, CT = 1, NVLC = 0, RESV = 0, WG = 256;
+  bool staged_loop = false;
+  int fold_width = 0;
 
-  // Elements of one [R,C] value a lane may hold.  With row reductions the row stays in registers
-  // across the stages together with everything else that is live: the other [R,C] inputs and the
-  // lane's slices of the [1,C] operands (E registers each).  128 registers per lane keep four
-  // wavefronts per SIMD in flight; 16 elements per lane is the most that pays even when more would
-  // fit (measured over 26 row-reduction cases: 16 beats 32 by 3-10 %: more wavefronts per row, more
-  // rows in flight); rows too long for that take 32 and 64 below.
-  int n_live = 1;
-  for (const ExtTensor& e : gp->ext_in) n_live += e.kind == KIND_FULL || e.kind == KIND_ROWV;
-  n_live += (int)gp->col_reduces.size();  // a column accumulator per element
-  int ecap = rowred ? std::max(8, std::min(16, pow2_floor(128 / n_live))) : 8;
-  if (colred && !rowred) ecap = 32 / max_es;  // 32 bytes per lane per tile (bf16 sums: 30.2 -> 25.4 us on [65536,1024])
-  ecap = std::max(ecap, V);
+  Scheduler(const Graph& g_, const PlanOptions& opt_, GroupPlan* gp_) : g(g_), opt(opt_), gp(gp_), s(gp_->s), R(gp_->R), C(gp_->C) {}
+
   // lanes per row are a power of two: when half as many lanes would hold the row with at most
   // 1.5 x a cap below 32, take them (5120 bf16 columns under a cap of 16: 256 lanes x 24 elements,
   // not 512 x 16 with 37 % of the lanes idle)
-  auto lanes_for = [&](int e) {
+  int lanes_for(int e) const {
     const int l = pow2_ceil((NV + e / V - 1) / (e / V));
     if (rowred && l >= 2 && e < 32 && ((NV + l / 2 - 1) / (l / 2)) * V * 2 <= e * 3) return l / 2;
     return l;
-  };
-  int l_min = lanes_for(ecap);
-  const int l_max = std::min(1024, pow2_ceil(NV));
-  // Groups without reductions do not need a whole row in one workgroup: very long rows are cut
-  // into column tiles, each handled like a row of its own.
-  const bool tileable = !rowred && !colred;
-  bool has_transposed = false;
-  for (const ExtTensor& e : gp->ext_out) has_transposed |= e.transposed;
-  // A few very long rows occupy as many CUs as there are rows ([4, 4M] row sums: 263 us on 4 CUs).
-  // When every row reduction of the group is in its first stage and everything else that leaves the
-  // group is either a per-row value or computed before any reduction result, each row is split
-  // over many workgroups; other such groups are better cut into kernels of that form and
-  // reduction-free ones (worth_fusing).
-  const bool few_long_rows = rowred && !colred && !has_transposed && R <= 128 && (int64_t)C * max_es >= (1 << 18) && (int64_t)R * C * max_es >= (1 << 20);
-  bool split_rows = few_long_rows;
-  if (split_rows) {
-    for (const ExtTensor& e : gp->ext_out) split_rows &= e.kind == KIND_COLV || gp->level.at(e.node) == 0;
-    for (int m : gp->row_reduces) split_rows &= gp->level.at(m) == 0;
-  }
-  // Rows too long for that: first more elements per lane (32, then 64: one workgroup per CU, but the
-  // row is still read once instead of once per stage); beyond that the first 48 (or 32) elements
-  // per lane stay resident and the rest of the row is walked in chunks; last, chunks only.  Plan
-  // creation steps `wide_level` down while the compiled kernel spills.
-  // Rows whose [1,C] operands weigh at least as much per column as the rows themselves (LayerNorm with gamma, beta and a
-  // bias over bf16 rows: 12 bytes against 4) keep nothing resident: their last stage needs the registers for the operands,
-  // and the whole row fits LDS in its own dtype more often than not.  Measured, LayerNorm+GeLU bf16: [4096,65536] 323 us
-  // with a resident part, 282 us chunks only; [4096,49152] 287 -> 207 us; [2049,100000] 267 -> 239 us.
-  bool resident = false;
-  if (rowred && l_min > 1024 && !split_rows) {
-    const int e32 = std::max(32, V), e64 = std::max(64, V);
-    const bool may_chunk = !colred && !has_transposed;
-    int64_t rowv_bytes = 0, full_bytes = 0;
-    for (const ExtTensor& e : gp->ext_in) {
-      if (e.kind == KIND_ROWV) rowv_bytes += dtype_size(e.dtype);
-      if (e.kind == KIND_FULL) full_bytes += dtype_size(e.dtype);
-    }
-    for (const ExtTensor& e : gp->ext_out)
-      if (e.kind == KIND_FULL) full_bytes += dtype_size(e.dtype);
-    const bool keep_registers = rowv_bytes < full_bytes;
-    if (ecap < e32 && lanes_for(e32) <= 1024 && (opt.wide_level >= 1 || !may_chunk)) ecap = e32, l_min = lanes_for(e32);
-    else if (may_chunk && keep_registers && opt.wide_level >= 2 && lanes_for(e64) <= 1024) ecap = e64, l_min = lanes_for(e64);
-    else if (may_chunk && keep_registers && opt.wide_level >= 1) resident = true;
-  }
-  // Row reductions over rows that do not fit the registers of one workgroup: the workgroup walks
-  // its row in column chunks, once per stage, recomputing what each stage needs.
-  const bool chunked = (l_min > 1024 && rowred && !colred && !has_transposed) || split_rows;
-  // Column reductions alone do not need whole rows either: column tiles, each with its own fold.
-  const bool col_tiled = l_min > 1024 && colred && !rowred && !has_transposed;
-  if (l_min > 1024 && !tileable && !chunked && !col_tiled)
-    FS_FAIL(FS_ERR_UNSUPPORTED, "rows of %d columns are too long for one workgroup in a group with %s", C,
-            colred ? "row and column reductions" : "transposed outputs");
-  if (has_concat && (chunked || col_tiled))
-    FS_FAIL(FS_ERR_UNSUPPORTED, "a concat cannot be read by a kernel that walks rows of %d columns in chunks", C);
-  if (tileable) l_min = std::min(l_min, 256);
-  // wide transposes: 2-D tiles through LDS
-  const bool tiled_transpose = has_transposed && tileable && C > 256 && R > 1;
-  if (split_rows) l_min = 256;
-  else if (chunked) l_min = 1024;  // (measured: the largest workgroup keeps the fewest rows in flight, so re-reads hit the caches more often)
-  if (col_tiled) l_min = std::min(256, l_max);
-  int L = rowred ? std::min(64, l_max) : std::min(256, l_max);
-  // Very narrow rows: a row of at most 32 bytes belongs to one lane (no cross-lane step at all;
-  // [4M,3] L2-normalise: 34.8 -> 17.6 us); rows that can only be read element by element (odd
-  // widths) get at least two elements per lane.
-  // A row that leaves part of a wavefront's last vector slots empty (768 bf16 columns: 96 vectors
-  // on 64 lanes x 2) is better served by fewer lanes that it fills exactly, several rows per
-  // wavefront (32 lanes x 3: LayerNorm+GeLU bf16 [32768,768] 24.0 -> 20.9 us).
-  // Below a quarter of the slots empty it does not pay (softmax fp32 [32768,640]: 27.7 us on 64 lanes
-  // x 3 vectors with 17 % empty, 29.4 us on 32 x 5).
-  if (rowred && !colred && L > l_min && l_min >= 1) {
-    const auto waste = [&](int lanes) { return (int64_t)((NV + lanes - 1) / lanes) * lanes - NV; };
-    if (waste(L) * 4 >= NV + waste(L))
-      for (int l = L; l >= l_min; l /= 2)
-        if (waste(l) < waste(L)) L = l;
-  }
-  if (rowred && !colred && C * max_es <= 32) L = 1;
-  else if (rowred && !colred && V == 1 && NV >= 4) L = std::min(L, pow2_ceil(NV) / 2);
-  // a transposed root leaves as runs of G = WG/L consecutive elements: at least 16 rows per workgroup
-  if (has_transposed && !rowred) L = std::min(L, std::max(l_min, 16));
-  // looping (column-reduction) kernels want more bytes in flight per lane: 16 elements per lane
-  if (colred) L = std::min(L, std::max(1, pow2_ceil((NV * V + 15) / 16)));
-  L = std::max(L, l_min);
-  if (col_tiled) L = l_min;
-  // tile = tt_rows rows (128 bytes of the narrowest transposed output: the length of a run in the
-  // transposed tensor) by 1024 / tt_rows lanes x one 16-byte vector; measured best among 14 shapes
-  int tt_rows = 64;
-  if (tiled_transpose) {
-    int es = 4;
-    for (const ExtTensor& e : gp->ext_out)
-      if (e.transposed) es = std::min(es, dtype_size(e.dtype));
-    tt_rows = std::max(16, std::min(64, 128 / es));
-    L = std::min(1024 / tt_rows, l_max);
-  }
-  // small problems: more lanes per row until the device has ~8 wavefronts per CU
-  // (a row that will be cut into column tiles anyway is not a small problem)
-  const bool col_tiles_anyway = tileable && (int64_t)NV * V > (int64_t)L * ecap;
-  while ((int64_t)R * L / 64 < 8 * CUS && L < l_max && !(has_transposed && !rowred) && !chunked && !col_tiled && !col_tiles_anyway) L *= 2;
-  if (split_rows) L = 256;
-  if (opt.has_hint && opt.hint.lanes_per_row > 0 && !tiled_transpose && !split_rows) {
-    const int h = opt.hint.lanes_per_row;
-    if ((h & (h - 1)) == 0 && h >= ((chunked || col_tiled) ? 64 : l_min) && h <= 1024) L = h;
-  }
-  int NVL = (NV + L - 1) / L, CT = 1;
-  if (NVL * V > ecap && tileable) {
-    NVL = std::max(1, ecap / V);
-    CT = (NV + NVL * L - 1) / (NVL * L);
-  }
-  if (tiled_transpose) {
-    NVL = 1;
-    CT = (NV + NVL * L - 1) / (NVL * L);
-  }
-  int NVLC = 0, RESV = 0;
-  if (chunked || col_tiled) {
-    NVLC = std::max(1, 16 / V);
-    NVL = resident ? std::max(1, (opt.wide_level >= 2 ? 48 : 32) / V) : NVLC;  // (64 resident elements plus a chunk in flight spill)
-    RESV = resident ? NVL * L : 0;
-    CT = (NV - RESV + NVLC * L - 1) / (NVLC * L);
   }
 
-  int WG;
-  const int64_t total_waves = std::max<int64_t>(1, (int64_t)R * CT * L / 64);
-  if (col_tiled) {
-    WG = std::max(64, L);
-    for (int w = 512; w >= 128; w /= 2)
-      if (w >= L && (int64_t)R * L / w >= 8) {
-        WG = w;
-        break;
+  // element size, vector width, which reductions the group holds
+  fs_status measure_group() {
+    // the machine: compute units and resident lanes as the device reports them (256 and 524288 on MI355X)
+    CUS = device_limits().cus;
+    RES = device_limits().resident_lanes;
+    max_es = 0;
+    for (const ExtTensor& e : gp->ext_in)
+      if (e.kind == KIND_FULL || e.kind == KIND_PART) max_es = std::max(max_es, dtype_size(e.dtype));
+    for (const ExtTensor& e : gp->ext_out)
+      if (e.kind == KIND_FULL) max_es = std::max(max_es, dtype_size(e.dtype));
+    if (max_es == 0) max_es = 4;
+    V = 16 / max_es;
+    while (C % V) V /= 2;
+    has_concat = false;
+    for (int m : gp->members)
+      if (g.nodes[m].opcode == FS_CONCAT) {
+        has_concat = true;
+        if (g.nodes[m].attr_i == FS_CONCAT_COLS)  // a vector access must not straddle the seam
+          while (g.nodes[g.nodes[m].in[0]].cols % V) V /= 2;
       }
-  } else if (colred) {
-    // large workgroups (few partials, many rows per trip) as long as every CU still gets a workgroup
-    // and the in-workgroup fold area (one row of C floats per wavefront or row-group) fits the budget
-    WG = std::max(64, L);
-    for (int w = 512; w >= 128; w /= 2)
-      if (w >= L && (int64_t)R * L / w >= CUS) {
-        WG = w;
-        break;
+    NV = C / V;
+    rowred = !gp->row_reduces.empty();
+    colred = !gp->col_reduces.empty();
+    return FS_OK;
+  }
+
+  // how a row is held: registers (16, 32, 64 elements per lane), a resident part plus chunks, chunks only, split over workgroups, column tiles, 2-D transpose tiles
+  fs_status pick_row_form() {
+    // Elements of one [R,C] value a lane may hold.  With row reductions the row stays in registers
+    // across the stages together with everything else that is live: the other [R,C] inputs and the
+    // lane's slices of the [1,C] operands (E registers each).  128 registers per lane keep four
+    // wavefronts per SIMD in flight; 16 elements per lane is the most that pays even when more would
+    // fit (measured over 26 row-reduction cases: 16 beats 32 by 3-10 %: more wavefronts per row, more
+    // rows in flight); rows too long for that take 32 and 64 below.
+    int n_live = 1;
+    for (const ExtTensor& e : gp->ext_in) n_live += e.kind == KIND_FULL || e.kind == KIND_ROWV;
+    n_live += (int)gp->col_reduces.size();  // a column accumulator per element
+    ecap = rowred ? std::max(8, std::min(16, pow2_floor(128 / n_live))) : 8;
+    if (colred && !rowred) ecap = 32 / max_es;  // 32 bytes per lane per tile (bf16 sums: 30.2 -> 25.4 us on [65536,1024])
+    ecap = std::max(ecap, V);
+    l_min = lanes_for(ecap);
+    l_max = std::min(1024, pow2_ceil(NV));
+    // Groups without reductions do not need a whole row in one workgroup: very long rows are cut
+    // into column tiles, each handled like a row of its own.
+    tileable = !rowred && !colred;
+    has_transposed = false;
+    for (const ExtTensor& e : gp->ext_out) has_transposed |= e.transposed;
+    // A few very long rows occupy as many CUs as there are rows ([4, 4M] row sums: 263 us on 4 CUs).
+    // When every row reduction of the group is in its first stage and everything else that leaves the
+    // group is either a per-row value or computed before any reduction result, each row is split
+    // over many workgroups; other such groups are better cut into kernels of that form and
+    // reduction-free ones (worth_fusing).
+    few_long_rows = rowred && !colred && !has_transposed && R <= 128 && (int64_t)C * max_es >= (1 << 18) && (int64_t)R * C * max_es >= (1 << 20);
+    split_rows = few_long_rows;
+    if (split_rows) {
+      for (const ExtTensor& e : gp->ext_out) split_rows &= e.kind == KIND_COLV || gp->level.at(e.node) == 0;
+      for (int m : gp->row_reduces) split_rows &= gp->level.at(m) == 0;
+    }
+    // Rows too long for that: first more elements per lane (32, then 64: one workgroup per CU, but the
+    // row is still read once instead of once per stage); beyond that the first 48 (or 32) elements
+    // per lane stay resident and the rest of the row is walked in chunks; last, chunks only.  Plan
+    // creation steps `wide_level` down while the compiled kernel spills.
+    // Rows whose [1,C] operands weigh at least as much per column as the rows themselves (LayerNorm with gamma, beta and a
+    // bias over bf16 rows: 12 bytes against 4) keep nothing resident: their last stage needs the registers for the operands,
+    // and the whole row fits LDS in its own dtype more often than not.  Measured, LayerNorm+GeLU bf16: [4096,65536] 323 us
+    // with a resident part, 282 us chunks only; [4096,49152] 287 -> 207 us; [2049,100000] 267 -> 239 us.
+    resident = false;
+    if (rowred && l_min > 1024 && !split_rows) {
+      const int e32 = std::max(32, V), e64 = std::max(64, V);
+      const bool may_chunk = !colred && !has_transposed;
+      int64_t rowv_bytes = 0, full_bytes = 0;
+      for (const ExtTensor& e : gp->ext_in) {
+        if (e.kind == KIND_ROWV) rowv_bytes += dtype_size(e.dtype);
+        if (e.kind == KIND_FULL) full_bytes += dtype_size(e.dtype);
       }
-    if (rowred && L >= 256) WG = std::max(WG, std::min(1024, 4 * L));  // rows across several wavefronts: 16 wavefronts per CU
-  }
-  else if (total_waves > 4 * CUS || has_transposed) WG = std::max(256, L);
-  else WG = std::max(64, L);
-  // Rows with [1,C] operands, above all operands that outweigh the row's own traffic (LayerNorm with
-  // gamma, beta and a bias over bf16 rows: 12 bytes per column against 4).  Re-reading the operands for every row, or for
-  // every few rows of a one-trip workgroup, costs L2 bandwidth; keeping them in registers costs
-  // occupancy (48 of 84 registers).  When they fit the LDS budget and there is work for more than
-  // two rounds of resident workgroups, the workgroups loop instead, 32 wavefronts per CU, and stage
-  // the operands in LDS once, before the loop.  LayerNorm+GeLU bf16 [8192,4096]: 35.3 us re-reading,
-  // 31.2 us from registers, 27.6 us staged; [16384,2048]: 29.3 -> 26.5 us; [16384,1024]: 14.7 ->
-  // 13.1 us (one trip: staged once per 4 rows); no gain without such operands (softmax: 3-7 % slower),
-  // nor for one-wavefront rows with fewer than 16 elements per lane or a half-empty last vector
-  // ([16384,512]: 9.2 -> 9.7 us, [32768,768]: 22.6 -> 24.1 us), which keep the one-trip form.
-  bool staged_loop = false;
-  if (rowred && !colred && !chunked && !has_transposed && CT == 1 && R > 1) {
-    int64_t rowv_bytes = 0, full_bytes = 0;
-    int n_rowv_in = 0;
-    for (const ExtTensor& e : gp->ext_in) {  // bytes per column
-      if (e.kind == KIND_ROWV) rowv_bytes += dtype_size(e.dtype), ++n_rowv_in;
-      if (e.kind == KIND_FULL) full_bytes += dtype_size(e.dtype);
+      for (const ExtTensor& e : gp->ext_out)
+        if (e.kind == KIND_FULL) full_bytes += dtype_size(e.dtype);
+      const bool keep_registers = rowv_bytes < full_bytes;
+      if (ecap < e32 && lanes_for(e32) <= 1024 && (opt.wide_level >= 1 || !may_chunk)) ecap = e32, l_min = lanes_for(e32);
+      else if (may_chunk && keep_registers && opt.wide_level >= 2 && lanes_for(e64) <= 1024) ecap = e64, l_min = lanes_for(e64);
+      else if (may_chunk && keep_registers && opt.wide_level >= 1) resident = true;
     }
-    for (const ExtTensor& e : gp->ext_out)
-      if (e.kind == KIND_FULL) full_bytes += dtype_size(e.dtype);
-    const int wg = L >= 128 ? std::min(1024, 4 * L) : std::max(256, std::min(1024, 16 * L));  // 4 rows, or 16 one-wavefront rows, per trip
-    // (one-wavefront rows: beyond ~8 rounds of resident workgroups the one-trip form catches up and
-    // passes: [65536,1024] 48.9 against 49.5 us, [262144,1024] 203 against 210 us)
-    const bool full_slices = NVL * V >= 16 && (int64_t)NVL * L == NV && (int64_t)R * L <= 8 * RES;
-    // rows across several wavefronts gain with any [1,C] operand (RMSNorm bf16 [8192,4096]: 24.5 ->
-    // 23.6 us, residual+LayerNorm: 50.5 -> 45.8 us); one-wavefront rows only with heavy ones
-    // (up to ~4 rounds of work: at [32768,2048] the one-trip form is 2-5 % faster again)
-    const bool heavy = rowv_bytes * 2 >= full_bytes * 3;
-    const bool pays = L >= 128 ? heavy || (n_rowv_in > 0 && (int64_t)R * L <= 4 * RES) : full_slices && heavy;
-    if (pays && (int64_t)n_rowv_in * NVL * L * V * 4 + 1024 <= opt.lds_budget && (int64_t)R * L / wg >= 2 * (RES / wg)) {
-      staged_loop = true;
-      WG = wg;
-    }
-  }
-  if (chunked) WG = L;  // one row per workgroup
-  if (tiled_transpose) WG = std::max(64, L * std::min(tt_rows, std::max(4, pow2_ceil(R))));
-  if (opt.has_hint && opt.hint.wg_threads > 0 && !chunked && !tiled_transpose) {
-    const int h = opt.hint.wg_threads;
-    if (h % 64 == 0 && h >= L && h <= 1024) WG = h;
+    // Row reductions over rows that do not fit the registers of one workgroup: the workgroup walks
+    // its row in column chunks, once per stage, recomputing what each stage needs.
+    chunked = (l_min > 1024 && rowred && !colred && !has_transposed) || split_rows;
+    // Column reductions alone do not need whole rows either: column tiles, each with its own fold.
+    col_tiled = l_min > 1024 && colred && !rowred && !has_transposed;
+    if (l_min > 1024 && !tileable && !chunked && !col_tiled)
+      FS_FAIL(FS_ERR_UNSUPPORTED, "rows of %d columns are too long for one workgroup in a group with %s", C,
+              colred ? "row and column reductions" : "transposed outputs");
+    if (has_concat && (chunked || col_tiled))
+      FS_FAIL(FS_ERR_UNSUPPORTED, "a concat cannot be read by a kernel that walks rows of %d columns in chunks", C);
+    if (tileable) l_min = std::min(l_min, 256);
+    // wide transposes: 2-D tiles through LDS
+    tiled_transpose = has_transposed && tileable && C > 256 && R > 1;
+    if (split_rows) l_min = 256;
+    else if (chunked) l_min = 1024;  // (measured: the largest workgroup keeps the fewest rows in flight, so re-reads hit the caches more often)
+    if (col_tiled) l_min = std::min(256, l_max);
+    return FS_OK;
   }
 
-  s.V = V;
-  s.NV = NV;
-  s.L = L;
-  s.NVL = NVL;
-  s.CT = CT;
-  s.E = s.NVL * V;
-  s.WG = WG;
-  s.G = WG / L;
-  s.ragged = resident ? false : (int64_t)CT * NVL * L != NV;
-  s.resident = resident;
-  s.NVLC = NVLC;
-  s.RESV = RESV;
-  s.ragged_chunks = chunked && (int64_t)RESV + (int64_t)CT * NVLC * L != NV;
-  s.chunked = chunked;
-  s.col_tiled = col_tiled;
-  s.tiled_transpose = tiled_transpose;
-  s.split_rows = split_rows;
-  s.min_waves = opt.min_waves;
-  s.few_long_rows = few_long_rows;
-  s.S = 1;
-  s.CPS = CT;
-  if (split_rows) {  // at least 2 chunks per workgroup, about `target` workgroups in all
-    const int target = opt.has_hint && opt.hint.max_workgroups > 0 ? opt.hint.max_workgroups : 512;
-    s.S = std::max(1, std::min((CT + 1) / 2, std::max(1, target / R)));
-    s.CPS = (CT + s.S - 1) / s.S;
-    s.S = (CT + s.CPS - 1) / s.CPS;  // no empty segment
-  }
-  s.n_iters = split_rows ? R * s.S : chunked ? R : col_tiled ? (R + s.G - 1) / s.G : tiled_transpose ? (int)((int64_t)CT * ((R + s.G - 1) / s.G))
-                                                                             : (int)(((int64_t)R * CT + s.G - 1) / s.G);
-  // Streaming groups launch one workgroup per row tile: the hardware hands tiles out in memory
-  // order and a fresh wavefront issues its loads at once, which measures faster on this device
-  // than persistent workgroups looping with a grid stride.  Column reductions keep a bounded
-  // grid because every workgroup leaves a partial to fold.
-  int cap = colred ? CUS : (1 << 30);
-  // Exception: [1,C] operands that cannot be shared through LDS (fewer than 4 rows per workgroup)
-  // are read again from L2 for every row of a one-shot grid.  When those reads outweigh the row's
-  // own traffic (LayerNorm with gamma, beta and a bias over rows of 4096+ elements: 12 bytes per
-  // column against 4), the workgroups loop instead, 16 wavefronts per CU, and keep their slices of
-  // the operands in registers (measured on [8192,4096] bf16: 35.3 -> 29.4 us).
-  if (staged_loop && s.G >= 2) {
-    cap = std::max(CUS, (int)(RES / WG));
-  } else if (!colred && !chunked && CT == 1 && s.G < 4 && R > 1) {
-    int64_t rowv_bytes = 0, full_bytes = 0;
-    for (const ExtTensor& e : gp->ext_in) {  // bytes per column
-      if (e.kind == KIND_ROWV) rowv_bytes += dtype_size(e.dtype);
-      if (e.kind == KIND_FULL) full_bytes += dtype_size(e.dtype);
+  // lanes per row
+  fs_status pick_lanes() {
+    L = rowred ? std::min(64, l_max) : std::min(256, l_max);
+    // Very narrow rows: a row of at most 32 bytes belongs to one lane (no cross-lane step at all;
+    // [4M,3] L2-normalise: 34.8 -> 17.6 us); rows that can only be read element by element (odd
+    // widths) get at least two elements per lane.
+    // A row that leaves part of a wavefront's last vector slots empty (768 bf16 columns: 96 vectors
+    // on 64 lanes x 2) is better served by fewer lanes that it fills exactly, several rows per
+    // wavefront (32 lanes x 3: LayerNorm+GeLU bf16 [32768,768] 24.0 -> 20.9 us).
+    // Below a quarter of the slots empty it does not pay (softmax fp32 [32768,640]: 27.7 us on 64 lanes
+    // x 3 vectors with 17 % empty, 29.4 us on 32 x 5).
+    if (rowred && !colred && L > l_min && l_min >= 1) {
+      const auto waste = [&](int lanes) { return (int64_t)((NV + lanes - 1) / lanes) * lanes - NV; };
+      if (waste(L) * 4 >= NV + waste(L))
+        for (int l = L; l >= l_min; l /= 2)
+          if (waste(l) < waste(L)) L = l;
     }
-    for (const ExtTensor& e : gp->ext_out)
-      if (e.kind == KIND_FULL) full_bytes += dtype_size(e.dtype);
-    if (rowv_bytes * 2 >= full_bytes * 3) cap = std::max(CUS, (int)(RES / 2 / WG));
-  }
-  if (opt.has_hint && opt.hint.max_workgroups > 0) cap = opt.hint.max_workgroups;
-  cap = std::min(cap, (int)(0x7fffffff / WG));  // a launch holds fewer than 2^31 lanes: beyond that the workgroups loop
-  s.grid = std::max(1, std::min(s.n_iters, cap));
-  s.RB = s.grid;
-  if (split_rows) {
-    s.grid = R * s.S;
-    s.RB = s.S;
-  }
-  if (col_tiled) {  // RB workgroups per column tile, about `cap` workgroups in all
-    s.RB = std::max(1, std::min(s.n_iters, std::max(1, cap / CT)));
-    s.grid = s.RB * CT;
-  }
-  // Looping kernels that only fold columns have almost no arithmetic per trip: their rate is set by
-  // the bytes in flight, and two row tiles per trip measured 13 % faster (28.1 -> 24.5 us on
-  // [65536,512]).  With a row reduction in the body one tile per trip is the faster form.
-  s.U = (colred && !rowred && s.grid < s.n_iters && CT == 1) ? 2 : 1;
-  if (opt.has_hint && opt.hint.tiles_per_trip >= 1 && opt.hint.tiles_per_trip <= 4) s.U = opt.hint.tiles_per_trip;
-  if (has_concat) s.U = 1;
-  // two fold levels at most: the smallest fan-in whose square covers the grid
-  s.fan_in = s.RB <= 64 ? 8 : s.RB <= 256 ? 16 : 32;
-
-  // LDS plan (Section 5.1).  Size requirements: cross-wave row-reduction partials (the "direct
-  // allocation" for a non-root Reduce) and the column-partial fold area.  Space sharing: all row
-  // reductions of the kernel reuse one ping-pong pair of slots instead of one buffer each (the
-  // Reduce.2-reuses-Reduce.1 case of Section 5.1.3); the column fold area is shared by all column
-  // reductions in turn.
-  // Space sharing by lifetime (the idea of Section 5.1.3 applied to the kernel's two phases): what
-  // the row loop uses (transpose tile, staged [1,C] operands) is dead when the epilogue folds the
-  // column partials, so both live in one pool of max(loop bytes, fold bytes).
-  int fixed = 0, loop_bytes = 0, fold_bytes = 0;
-  if (rowred && L > 64) fixed += 2 * s.G * (L / 64) * gp->max_batched_reduces * 4;
-  if (split_rows) fixed += 16 + (int)gp->row_reduces.size() * 4;
-  const int fold_width = col_tiled ? NVL * L * V : C;  // columns one workgroup folds
-  s.fold_piece = fold_width;
-  if (colred) {
-    // the fold area takes at most half of the budget: wide rows pass through it in pieces
-    fixed += 16;
-    const int fold_rows = L < 64 ? WG / 64 : s.G;
-    const int piece_cap = std::max(8, (opt.lds_budget / 2 / (fold_rows * 4)) / 8 * 8);
-    if (fold_width > piece_cap) s.fold_piece = piece_cap;
-    fold_bytes = fold_rows * s.fold_piece * 4;
-  }
-  auto total = [&]() { return fixed + std::max(loop_bytes, fold_bytes); };
-  // [1,C] inputs shared by all rows of a workgroup are staged in LDS by the whole workgroup (once,
-  // before the loop, when the workgroup loops) when several rows share them and the budget allows
-  int n_rowv = 0;
-  for (const ExtTensor& e : gp->ext_in) n_rowv += e.kind == KIND_ROWV;
-  s.stage_rowv = false;
-  s.tile_transpose = false;
-  const int tile_bytes = (tiled_transpose ? NVL * L * V : C) * (s.G + 1) * 4;
-  if (has_transposed && (CT == 1 || tiled_transpose) && s.G >= 4 && fixed + std::max(loop_bytes + tile_bytes, fold_bytes) <= opt.lds_budget) {
-    s.tile_transpose = true;
-    loop_bytes += tile_bytes;
-  }
-  const int slot_bytes = s.NVL * s.L * V * 4;
-  if (n_rowv > 0 && CT == 1 && (s.G >= 4 || (staged_loop && s.G >= 2)) && R > 1 &&
-      fixed + std::max(loop_bytes + n_rowv * slot_bytes, fold_bytes) <= opt.lds_budget) {
-    s.stage_rowv = true;
-    loop_bytes += n_rowv * slot_bytes;
-  }
-  const int lds = total();
-  s.lds_bytes = s.lds_planned = lds;
-  if (lds > opt.lds_budget)
-    FS_FAIL(FS_ERR_LDS_BUDGET, "group needs %d bytes of LDS, budget is %d", lds, opt.lds_budget);
-  // Rows walked in chunks: what is left of the workgroup's LDS may hold the head of the row in its input dtype
-  // (one 1024-lane workgroup per compute unit runs such a kernel, so it may take all a workgroup is allowed
-  // unless the caller set a budget); code generation decides which inputs are worth it.
-  s.stage_avail = 0;
-  if (chunked && !split_rows) {
-    const int cap = opt.lds_budget_given ? opt.lds_budget : device_limits().lds_per_workgroup;
-    s.stage_avail = std::max(0, cap - lds - 512);
+    if (rowred && !colred && C * max_es <= 32) L = 1;
+    else if (rowred && !colred && V == 1 && NV >= 4) L = std::min(L, pow2_ceil(NV) / 2);
+    // a transposed root leaves as runs of G = WG/L consecutive elements: at least 16 rows per workgroup
+    if (has_transposed && !rowred) L = std::min(L, std::max(l_min, 16));
+    // looping (column-reduction) kernels want more bytes in flight per lane: 16 elements per lane
+    if (colred) L = std::min(L, std::max(1, pow2_ceil((NV * V + 15) / 16)));
+    L = std::max(L, l_min);
+    if (col_tiled) L = l_min;
+    // tile = tt_rows rows (128 bytes of the narrowest transposed output: the length of a run in the
+    // transposed tensor) by 1024 / tt_rows lanes x one 16-byte vector; measured best among 14 shapes
+    tt_rows = 64;
+    if (tiled_transpose) {
+      int es = 4;
+      for (const ExtTensor& e : gp->ext_out)
+        if (e.transposed) es = std::min(es, dtype_size(e.dtype));
+      tt_rows = std::max(16, std::min(64, 128 / es));
+      L = std::min(1024 / tt_rows, l_max);
+    }
+    // small problems: more lanes per row until the device has ~8 wavefronts per CU
+    // (a row that will be cut into column tiles anyway is not a small problem)
+    const bool col_tiles_anyway = tileable && (int64_t)NV * V > (int64_t)L * ecap;
+    while ((int64_t)R * L / 64 < 8 * CUS && L < l_max && !(has_transposed && !rowred) && !chunked && !col_tiled && !col_tiles_anyway) L *= 2;
+    if (split_rows) L = 256;
+    if (opt.has_hint && opt.hint.lanes_per_row > 0 && !tiled_transpose && !split_rows) {
+      const int h = opt.hint.lanes_per_row;
+      if ((h & (h - 1)) == 0 && h >= ((chunked || col_tiled) ? 64 : l_min) && h <= 1024) L = h;
+    }
+    return FS_OK;
   }
 
-  // grid-wide fold scratch
-  gp->n_tickets = 0;
-  gp->part_bytes = 0;
-  s.part_stride_floats = 0;
-  s.ticket_stride = 0;
-  if (split_rows) {  // per row: S partials of one float per reduction
-    const size_t k = gp->row_reduces.size();
-    int n = s.S;
-    while (n > 1) {
-      s.part_stride_floats += (size_t)n * k;
-      n = (n + s.fan_in - 1) / s.fan_in;
-      s.ticket_stride += n;
+  // vectors per lane, column tiles / chunks per row
+  fs_status pick_vectors() {
+    NVL = (NV + L - 1) / L, CT = 1;
+    if (NVL * V > ecap && tileable) {
+      NVL = std::max(1, ecap / V);
+      CT = (NV + NVL * L - 1) / (NVL * L);
     }
-    gp->n_tickets = s.ticket_stride * R;
-    gp->part_bytes = s.part_stride_floats * R * 4;
-  }
-  if (colred) {
-    const size_t kc = gp->col_reduces.size() * (size_t)fold_width;
-    int n = s.RB;
-    while (n > 1) {
-      s.part_stride_floats += (size_t)n * kc;
-      n = (n + s.fan_in - 1) / s.fan_in;
-      s.ticket_stride += n;
+    if (tiled_transpose) {
+      NVL = 1;
+      CT = (NV + NVL * L - 1) / (NVL * L);
     }
-    const int tiles = col_tiled ? CT : 1;
-    gp->n_tickets = s.ticket_stride * tiles;
-    gp->part_bytes = s.part_stride_floats * tiles * 4;
+    NVLC = 0, RESV = 0;
+    if (chunked || col_tiled) {
+      NVLC = std::max(1, 16 / V);
+      NVL = resident ? std::max(1, (opt.wide_level >= 2 ? 48 : 32) / V) : NVLC;  // (64 resident elements plus a chunk in flight spill)
+      RESV = resident ? NVL * L : 0;
+      CT = (NV - RESV + NVLC * L - 1) / (NVLC * L);
+    }
+    return FS_OK;
   }
-  (void)g;
-  return FS_OK;
-}
+
+  // workgroup size; whether workgroups loop with their [1,C] operands staged once
+  fs_status pick_workgroup() {
+    const int64_t total_waves = std::max<int64_t>(1, (int64_t)R * CT * L / 64);
+    if (col_tiled) {
+      WG = std::max(64, L);
+      for (int w = 512; w >= 128; w /= 2)
+        if (w >= L && (int64_t)R * L / w >= 8) {
+          WG = w;
+          break;
+        }
+    } else if (colred) {
+      // large workgroups (few partials, many rows per trip) as long as every CU still gets a workgroup
+      // and the in-workgroup fold area (one row of C floats per wavefront or row-group) fits the budget
+      WG = std::max(64, L);
+      for (int w = 512; w >= 128; w /= 2)
+        if (w >= L && (int64_t)R * L / w >= CUS) {
+          WG = w;
+          break;
+        }
+      if (rowred && L >= 256) WG = std::max(WG, std::min(1024, 4 * L));  // rows across several wavefronts: 16 wavefronts per CU
+    }
+    else if (total_waves > 4 * CUS || has_transposed) WG = std::max(256, L);
+    else WG = std::max(64, L);
+    // Rows with [1,C] operands, above all operands that outweigh the row's own traffic (LayerNorm with
+    // gamma, beta and a bias over bf16 rows: 12 bytes per column against 4).  Re-reading the operands for every row, or for
+    // every few rows of a one-trip workgroup, costs L2 bandwidth; keeping them in registers costs
+    // occupancy (48 of 84 registers).  When they fit the LDS budget and there is work for more than
+    // two rounds of resident workgroups, the workgroups loop instead, 32 wavefronts per CU, and stage
+    // the operands in LDS once, before the loop.  LayerNorm+GeLU bf16 [8192,4096]: 35.3 us re-reading,
+    // 31.2 us from registers, 27.6 us staged; [16384,2048]: 29.3 -> 26.5 us; [16384,1024]: 14.7 ->
+    // 13.1 us (one trip: staged once per 4 rows); no gain without such operands (softmax: 3-7 % slower),
+    // nor for one-wavefront rows with fewer than 16 elements per lane or a half-empty last vector
+    // ([16384,512]: 9.2 -> 9.7 us, [32768,768]: 22.6 -> 24.1 us), which keep the one-trip form.
+    staged_loop = false;
+    if (rowred && !colred && !chunked && !has_transposed && CT == 1 && R > 1) {
+      int64_t rowv_bytes = 0, full_bytes = 0;
+      int n_rowv_in = 0;
+      for (const ExtTensor& e : gp->ext_in) {  // bytes per column
+        if (e.kind == KIND_ROWV) rowv_bytes += dtype_size(e.dtype), ++n_rowv_in;
+        if (e.kind == KIND_FULL) full_bytes += dtype_size(e.dtype);
+      }
+      for (const ExtTensor& e : gp->ext_out)
+        if (e.kind == KIND_FULL) full_bytes += dtype_size(e.dtype);
+      const int wg = L >= 128 ? std::min(1024, 4 * L) : std::max(256, std::min(1024, 16 * L));  // 4 rows, or 16 one-wavefront rows, per trip
+      // (one-wavefront rows: beyond ~8 rounds of resident workgroups the one-trip form catches up and
+      // passes: [65536,1024] 48.9 against 49.5 us, [262144,1024] 203 against 210 us)
+      const bool full_slices = NVL * V >= 16 && (int64_t)NVL * L == NV && (int64_t)R * L <= 8 * RES;
+      // rows across several wavefronts gain with any [1,C] operand (RMSNorm bf16 [8192,4096]: 24.5 ->
+      // 23.6 us, residual+LayerNorm: 50.5 -> 45.8 us); one-wavefront rows only with heavy ones
+      // (up to ~4 rounds of work: at [32768,2048] the one-trip form is 2-5 % faster again)
+      const bool heavy = rowv_bytes * 2 >= full_bytes * 3;
+      const bool pays = L >= 128 ? heavy || (n_rowv_in > 0 && (int64_t)R * L <= 4 * RES) : full_slices && heavy;
+      if (pays && (int64_t)n_rowv_in * NVL * L * V * 4 + 1024 <= opt.lds_budget && (int64_t)R * L / wg >= 2 * (RES / wg)) {
+        staged_loop = true;
+        WG = wg;
+      }
+    }
+    if (chunked) WG = L;  // one row per workgroup
+    if (tiled_transpose) WG = std::max(64, L * std::min(tt_rows, std::max(4, pow2_ceil(R))));
+    if (opt.has_hint && opt.hint.wg_threads > 0 && !chunked && !tiled_transpose) {
+      const int h = opt.hint.wg_threads;
+      if (h % 64 == 0 && h >= L && h <= 1024) WG = h;
+    }
+    return FS_OK;
+  }
+
+  // the schedule record, row segments of split rows, loop trips
+  fs_status fill_schedule() {
+    s.V = V;
+    s.NV = NV;
+    s.L = L;
+    s.NVL = NVL;
+    s.CT = CT;
+    s.E = s.NVL * V;
+    s.WG = WG;
+    s.G = WG / L;
+    s.ragged = resident ? false : (int64_t)CT * NVL * L != NV;
+    s.resident = resident;
+    s.NVLC = NVLC;
+    s.RESV = RESV;
+    s.ragged_chunks = chunked && (int64_t)RESV + (int64_t)CT * NVLC * L != NV;
+    s.chunked = chunked;
+    s.col_tiled = col_tiled;
+    s.tiled_transpose = tiled_transpose;
+    s.split_rows = split_rows;
+    s.min_waves = opt.min_waves;
+    s.few_long_rows = few_long_rows;
+    s.S = 1;
+    s.CPS = CT;
+    if (split_rows) {  // at least 2 chunks per workgroup, about `target` workgroups in all
+      const int target = opt.has_hint && opt.hint.max_workgroups > 0 ? opt.hint.max_workgroups : 512;
+      s.S = std::max(1, std::min((CT + 1) / 2, std::max(1, target / R)));
+      s.CPS = (CT + s.S - 1) / s.S;
+      s.S = (CT + s.CPS - 1) / s.CPS;  // no empty segment
+    }
+    s.n_iters = split_rows ? R * s.S : chunked ? R : col_tiled ? (R + s.G - 1) / s.G : tiled_transpose ? (int)((int64_t)CT * ((R + s.G - 1) / s.G))
+                                                                               : (int)(((int64_t)R * CT + s.G - 1) / s.G);
+    return FS_OK;
+  }
+
+  // workgroups launched, row tiles per trip, fold fan-in
+  fs_status pick_grid() {
+    // Streaming groups launch one workgroup per row tile: the hardware hands tiles out in memory
+    // order and a fresh wavefront issues its loads at once, which measures faster on this device
+    // than persistent workgroups looping with a grid stride.  Column reductions keep a bounded
+    // grid because every workgroup leaves a partial to fold.
+    int cap = colred ? CUS : (1 << 30);
+    // Exception: [1,C] operands that cannot be shared through LDS (fewer than 4 rows per workgroup)
+    // are read again from L2 for every row of a one-shot grid.  When those reads outweigh the row's
+    // own traffic (LayerNorm with gamma, beta and a bias over rows of 4096+ elements: 12 bytes per
+    // column against 4), the workgroups loop instead, 16 wavefronts per CU, and keep their slices of
+    // the operands in registers (measured on [8192,4096] bf16: 35.3 -> 29.4 us).
+    if (staged_loop && s.G >= 2) {
+      cap = std::max(CUS, (int)(RES / WG));
+    } else if (!colred && !chunked && CT == 1 && s.G < 4 && R > 1) {
+      int64_t rowv_bytes = 0, full_bytes = 0;
+      for (const ExtTensor& e : gp->ext_in) {  // bytes per column
+        if (e.kind == KIND_ROWV) rowv_bytes += dtype_size(e.dtype);
+        if (e.kind == KIND_FULL) full_bytes += dtype_size(e.dtype);
+      }
+      for (const ExtTensor& e : gp->ext_out)
+        if (e.kind == KIND_FULL) full_bytes += dtype_size(e.dtype);
+      if (rowv_bytes * 2 >= full_bytes * 3) cap = std::max(CUS, (int)(RES / 2 / WG));
+    }
+    if (opt.has_hint && opt.hint.max_workgroups > 0) cap = opt.hint.max_workgroups;
+    cap = std::min(cap, (int)(0x7fffffff / WG));  // a launch holds fewer than 2^31 lanes: beyond that the workgroups loop
+    s.grid = std::max(1, std::min(s.n_iters, cap));
+    s.RB = s.grid;
+    if (split_rows) {
+      s.grid = R * s.S;
+      s.RB = s.S;
+    }
+    if (col_tiled) {  // RB workgroups per column tile, about `cap` workgroups in all
+      s.RB = std::max(1, std::min(s.n_iters, std::max(1, cap / CT)));
+      s.grid = s.RB * CT;
+    }
+    // Looping kernels that only fold columns have almost no arithmetic per trip: their rate is set by
+    // the bytes in flight, and two row tiles per trip measured 13 % faster (28.1 -> 24.5 us on
+    // [65536,512]).  With a row reduction in the body one tile per trip is the faster form.
+    s.U = (colred && !rowred && s.grid < s.n_iters && CT == 1) ? 2 : 1;
+    if (opt.has_hint && opt.hint.tiles_per_trip >= 1 && opt.hint.tiles_per_trip <= 4) s.U = opt.hint.tiles_per_trip;
+    if (has_concat) s.U = 1;
+    // two fold levels at most: the smallest fan-in whose square covers the grid
+    s.fan_in = s.RB <= 64 ? 8 : s.RB <= 256 ? 16 : 32;
+    return FS_OK;
+  }
+
+  // LDS plan of the kernel
+  fs_status plan_lds() {
+    // LDS plan (Section 5.1).  Size requirements: cross-wave row-reduction partials (the "direct
+    // allocation" for a non-root Reduce) and the column-partial fold area.  Space sharing: all row
+    // reductions of the kernel reuse one ping-pong pair of slots instead of one buffer each (the
+    // Reduce.2-reuses-Reduce.1 case of Section 5.1.3); the column fold area is shared by all column
+    // reductions in turn.
+    // Space sharing by lifetime (the idea of Section 5.1.3 applied to the kernel's two phases): what
+    // the row loop uses (transpose tile, staged [1,C] operands) is dead when the epilogue folds the
+    // column partials, so both live in one pool of max(loop bytes, fold bytes).
+    int fixed = 0, loop_bytes = 0, fold_bytes = 0;
+    if (rowred && L > 64) fixed += 2 * s.G * (L / 64) * gp->max_batched_reduces * 4;
+    if (split_rows) fixed += 16 + (int)gp->row_reduces.size() * 4;
+    fold_width = col_tiled ? NVL * L * V : C;  // columns one workgroup folds
+    s.fold_piece = fold_width;
+    if (colred) {
+      // the fold area takes at most half of the budget: wide rows pass through it in pieces
+      fixed += 16;
+      const int fold_rows = L < 64 ? WG / 64 : s.G;
+      const int piece_cap = std::max(8, (opt.lds_budget / 2 / (fold_rows * 4)) / 8 * 8);
+      if (fold_width > piece_cap) s.fold_piece = piece_cap;
+      fold_bytes = fold_rows * s.fold_piece * 4;
+    }
+    auto total = [&]() { return fixed + std::max(loop_bytes, fold_bytes); };
+    // [1,C] inputs shared by all rows of a workgroup are staged in LDS by the whole workgroup (once,
+    // before the loop, when the workgroup loops) when several rows share them and the budget allows
+    int n_rowv = 0;
+    for (const ExtTensor& e : gp->ext_in) n_rowv += e.kind == KIND_ROWV;
+    s.stage_rowv = false;
+    s.tile_transpose = false;
+    const int tile_bytes = (tiled_transpose ? NVL * L * V : C) * (s.G + 1) * 4;
+    if (has_transposed && (CT == 1 || tiled_transpose) && s.G >= 4 && fixed + std::max(loop_bytes + tile_bytes, fold_bytes) <= opt.lds_budget) {
+      s.tile_transpose = true;
+      loop_bytes += tile_bytes;
+    }
+    const int slot_bytes = s.NVL * s.L * V * 4;
+    if (n_rowv > 0 && CT == 1 && (s.G >= 4 || (staged_loop && s.G >= 2)) && R > 1 &&
+        fixed + std::max(loop_bytes + n_rowv * slot_bytes, fold_bytes) <= opt.lds_budget) {
+      s.stage_rowv = true;
+      loop_bytes += n_rowv * slot_bytes;
+    }
+    const int lds = total();
+    s.lds_bytes = s.lds_planned = lds;
+    if (lds > opt.lds_budget)
+      FS_FAIL(FS_ERR_LDS_BUDGET, "group needs %d bytes of LDS, budget is %d", lds, opt.lds_budget);
+    // Rows walked in chunks: what is left of the workgroup's LDS may hold the head of the row in its input dtype
+    // (one 1024-lane workgroup per compute unit runs such a kernel, so it may take all a workgroup is allowed
+    // unless the caller set a budget); code generation decides which inputs are worth it.
+    s.stage_avail = 0;
+    if (chunked && !split_rows) {
+      const int cap = opt.lds_budget_given ? opt.lds_budget : device_limits().lds_per_workgroup;
+      s.stage_avail = std::max(0, cap - lds - 512);
+    }
+    return FS_OK;
+  }
+
+  // workspace scratch of grid-wide folds
+  fs_status plan_scratch() {
+    // grid-wide fold scratch
+    gp->n_tickets = 0;
+    gp->part_bytes = 0;
+    s.part_stride_floats = 0;
+    s.ticket_stride = 0;
+    if (split_rows) {  // per row: S partials of one float per reduction
+      const size_t k = gp->row_reduces.size();
+      int n = s.S;
+      while (n > 1) {
+        s.part_stride_floats += (size_t)n * k;
+        n = (n + s.fan_in - 1) / s.fan_in;
+        s.ticket_stride += n;
+      }
+      gp->n_tickets = s.ticket_stride * R;
+      gp->part_bytes = s.part_stride_floats * R * 4;
+    }
+    if (colred) {
+      const size_t kc = gp->col_reduces.size() * (size_t)fold_width;
+      int n = s.RB;
+      while (n > 1) {
+        s.part_stride_floats += (size_t)n * kc;
+        n = (n + s.fan_in - 1) / s.fan_in;
+        s.ticket_stride += n;
+      }
+      const int tiles = col_tiled ? CT : 1;
+      gp->n_tickets = s.ticket_stride * tiles;
+      gp->part_bytes = s.part_stride_floats * tiles * 4;
+    }
+    return FS_OK;
+  }
+
+  fs_status run() {
+    fs_status st;
+    if ((st = measure_group()) != FS_OK) return st;
+    if ((st = pick_row_form()) != FS_OK) return st;
+    if ((st = pick_lanes()) != FS_OK) return st;
+    if ((st = pick_vectors()) != FS_OK) return st;
+    if ((st = pick_workgroup()) != FS_OK) return st;
+    if ((st = fill_schedule()) != FS_OK) return st;
+    if ((st = pick_grid()) != FS_OK) return st;
+    if ((st = plan_lds()) != FS_OK) return st;
+    return plan_scratch();
+  }
+};
+}  // namespace
+
+static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPlan* gp) { return Scheduler(g, opt, gp).run(); }
 
 fs_status analyse_group(const Graph& g, const std::vector<int>& members, const std::vector<int>& /*group_of*/,
                         int /*self_group*/, const PlanOptions& opt, GroupPlan* out) {
