@@ -925,7 +925,18 @@ struct Emitter {
         os << "    const long row = (long)it * G + rg;\n";
       } else if (s.tiled_transpose) {
         // 2-D tiles: consecutive workgroups take consecutive column tiles of the same G rows
-        os << "    const long row = (long)(it / CT) * G + rg;\n    const int vbase = (it % CT) * (NVL * L);\n";
+        if (s.tt_col_band > 0) {
+          // bands of TCB column tiles, each walked row tile by row tile; the row-tile count is a constant of this
+          // kernel so that every division below is one by a constant (a runtime divisor costs 2-3 % of a tile's time)
+          const int trt = s.n_iters / s.CT, tcb = s.tt_col_band, last = s.CT % tcb;
+          os << "    constexpr int TRT = " << trt << ", TCB = " << tcb << ", FULL_BANDS = CT / TCB, LAST_BAND = " << (last ? last : tcb) << ";\n"
+             << "    const int band = it / (TCB * TRT), in_band = it - band * (TCB * TRT);\n"
+             << "    const int rtile = band < FULL_BANDS ? in_band / TCB : in_band / LAST_BAND;\n"
+             << "    const int ctile = band * TCB + in_band - rtile * (band < FULL_BANDS ? TCB : LAST_BAND);\n"
+             << "    const long row = (long)rtile * G + rg;\n    const int vbase = ctile * (NVL * L);\n";
+        } else {
+          os << "    const long row = (long)(it / CT) * G + rg;\n    const int vbase = (it % CT) * (NVL * L);\n";
+        }
       } else if (s.CT == 1 || s.resident) {
         os << "    const long row" << x << " = (long)it" << x << " * G + rg;\n    constexpr int vbase" << x << " = 0;\n";
       } else {

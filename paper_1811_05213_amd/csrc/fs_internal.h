@@ -123,6 +123,13 @@ struct Schedule {
   // consecutive rows of one column tile of NVL*L*V columns (unit = column tile fastest), so both
   // the reads and the transposed writes are runs of consecutive elements.
   bool tiled_transpose = false;
+  // Order in which the workgroups walk those tiles.  Workgroups that run at the same time should
+  // cover a block of the tensor that is wide both ways: a band of `tt_col_band` column tiles is
+  // walked row tile by row tile (column tiles fastest inside the band) before the next band starts,
+  // so the few hundred tiles in flight read runs of tt_col_band tiles' width and write, between
+  // them, long runs of every transposed row they touch.  0 = rows of tiles in plain order (the
+  // bands would be as wide as the tensor anyway).
+  int tt_col_band = 0;
   // A few very long rows (few_long_rows) leave most CUs idle with one workgroup per row.  When all
   // row reductions are in the first stage and every other result is an [R,1] value or needs no
   // reduction result (split_rows), each row is cut into S segments of CPS chunks, one workgroup per

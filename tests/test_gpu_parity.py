@@ -648,7 +648,10 @@ def test_few_very_long_rows_reduced_by_segments():
 def test_wide_transposes_in_2d_tiles():
     # reduction-free groups with transposed roots over more than 256 columns: 2-D tiles through LDS (ragged in both directions,
     # bf16 and u8 payloads, several roots, per-column and per-row operands)
-    for rows, cols, dt in ((300, 5000, "f32"), (5, 300, "f32"), (3, 70001, "f32"), (7000, 258, "bf16"), (1031, 1030, "f32"), (64, 4100, "f32")):
+    # (tiles are walked in bands of column tiles when a row has more tiles than a band: full bands, ragged last bands of
+    # 1, 15 and 24 tiles, one and several row tiles; the narrower shapes have too few column tiles for bands)
+    for rows, cols, dt in ((300, 5000, "f32"), (5, 300, "f32"), (3, 70001, "f32"), (7000, 258, "bf16"), (1031, 1030, "f32"), (64, 4100, "f32"),
+                           (2100, 3000, "bf16")):
         g = Graph()
         x = g.input(rows, cols, dt)
         b = g.input(1, cols)
@@ -660,7 +663,9 @@ def test_wide_transposes_in_2d_tiles():
         m = g.transpose(g.cmp("gt", y, xf))
         g.set_outputs([t, yo, m, g.transpose(g.unary("neg", xf))])
         p = fs.Plan(g)
-        assert p.stats()["num_launches"] == 1 and p.group_info(0)["lds_bytes"] > 0 and "it % CT" in p.group_source(0)
+        src = p.group_source(0)
+        assert p.stats()["num_launches"] == 1 and p.group_info(0)["lds_bytes"] > 0
+        assert ("in_band" in src) == (cols > 2100) and ("it % CT" in src) != ("in_band" in src)
         p.destroy()
         v = RNG.standard_normal((rows, cols)).astype(np.float32)
         ins = [f32_to_bf16_bits(v) if dt == "bf16" else v, RNG.standard_normal((1, cols)).astype(np.float32),
