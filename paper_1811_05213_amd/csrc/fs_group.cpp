@@ -271,6 +271,8 @@ struct Scheduler {
         if (e.transposed) es = std::min(es, dtype_size(e.dtype));
       tt_rows = std::max(16, std::min(64, 128 / es));
       L = std::min(1024 / tt_rows, l_max);
+      // the tile holds one float per element: 16-element vectors (u8 alone) need narrower tiles to fit the budget
+      while (L > 4 && (int64_t)L * V * (tt_rows + 1) * 4 > opt.lds_budget) L /= 2;
     }
     // small problems: more lanes per row until the device has ~8 wavefronts per CU
     // (a row that will be cut into column tiles anyway is not a small problem)

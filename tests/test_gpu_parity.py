@@ -675,6 +675,20 @@ def test_wide_transposes_in_2d_tiles():
         np.testing.assert_array_equal(out_s[2], ref[2])
 
 
+def test_wide_transposes_of_bytes():
+    # u8 alone is read in 16-element vectors: the tile (one float per element) is narrowed until it fits the LDS budget
+    for rows, cols in ((1000, 4096), (130, 8208), (4100, 272)):
+        g = Graph()
+        g.set_outputs([g.transpose(g.input(rows, cols, "u8"))])
+        p = fs.Plan(g)
+        gi = p.group_info(0)
+        assert p.stats()["num_launches"] == 1 and gi["vec_elems"] == 16 and 0 < gi["lds_bytes"] <= 65536
+        p.destroy()
+        v = (RNG.random((rows, cols)) < 0.3).astype(np.uint8)
+        ref, out_s, _ = both_modes(g, [v], f"u8 transpose {rows}x{cols}")
+        np.testing.assert_array_equal(out_s[0], v.T)
+
+
 def test_transposes_inside_a_group():
     """A transpose between fused ops moves no data: consumers run in the producer's layout."""
     for rows, cols in ((130, 72), (64, 64), (512, 256), (33, 1000)):
