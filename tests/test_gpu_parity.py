@@ -140,6 +140,25 @@ def test_column_reductions_over_wide_rows():
         p.destroy()
         # (a mean away from zero: column sums of thousands of zero-mean terms cancel, and the rule would set such elements aside)
         both_modes(g, [(0.5 + RNG.standard_normal((rows, cols))).astype(np.float32)], f"wide column reductions {rows}x{cols}")
+    # column tiles of 64 lanes from 513 columns on; bf16 rows are read 32 elements per lane; tiles that end inside a vector
+    # and inside the row; per-column and per-row operands next to the reductions
+    for rows, cols, dt in [(3000, 4096, "bf16"), (2200, 4104, "bf16"), (4100, 1030, "f32"), (900, 6152, "bf16"), (40, 2048, "f32")]:
+        g = Graph()
+        x = g.input(rows, cols, dt)
+        b = g.input(1, cols)
+        w = g.input(rows, 1)
+        xf = g.unary("convert", x, "f32") if dt != "f32" else x
+        y = g.binary("mul", g.binary("add", xf, g.bcast_rowvec(b, rows)), g.bcast_colvec(w, cols))
+        g.set_outputs([g.reduce_col("sum", y), g.reduce_col("max", xf)])
+        p = fs.Plan(g)
+        gi = p.group_info(0)
+        if rows >= 2000:  # (the smaller ones are launch-bound and keep their folds apart)
+            assert p.stats()["num_launches"] == 1 and gi["lanes_per_row"] == 64 and gi["elems_per_lane"] == 4 * gi["vec_elems"]
+        p.destroy()
+        v = (0.5 + RNG.standard_normal((rows, cols))).astype(np.float32)
+        ins = [f32_to_bf16_bits(v) if dt == "bf16" else v, RNG.standard_normal((1, cols)).astype(np.float32),
+               (1.0 + RNG.random((rows, 1))).astype(np.float32)]
+        both_modes(g, ins, f"column tiles {rows}x{cols} {dt}")
     # LayerNorm backward with a wide hidden dimension: the planner separates what cannot share a kernel
     g, ins, name = workload(6, 64)
     from workloads import layernorm_grad_graph, layernorm_grad_inputs

@@ -66,14 +66,15 @@ def test_static_scratch_refuses_what_it_cannot_hold_and_plans_that_are_not_loade
     assert e.value.status_name == "FS_ERR_INVALID_ARG" and "fs_plan_load" in str(e.value)
     plan.destroy()
     # a workspace beyond the static array's size
+    # (one kernel per op: the 16 MiB intermediate crosses a kernel boundary and lives in the workspace)
     big = Graph()
-    x = big.input(8192, 8192)
-    big.set_outputs([big.reduce_col("sum", x), big.reduce_col("max", x)])
-    plan = fs.Plan(big)
+    x = big.input(4096, 1024)
+    big.set_outputs([big.unary("neg", big.unary("exp", x))])
+    plan = fs.Plan(big, mode=fs.FS_MODE_UNFUSED)
     assert plan.workspace_bytes() > FS_STATIC_SCRATCH_BYTES
     plan.load()
-    xs = torch.zeros((8192, 8192), dtype=torch.float32, device="cuda:0")
-    outs = [torch.empty((1, 8192), dtype=torch.float32, device="cuda:0") for _ in range(2)]
+    xs = torch.zeros((4096, 1024), dtype=torch.float32, device="cuda:0")
+    outs = [torch.empty((4096, 1024), dtype=torch.float32, device="cuda:0")]
     with pytest.raises(fs.FsError) as e:
         plan.run_static([xs.data_ptr()], [o.data_ptr() for o in outs])
     assert e.value.status_name == "FS_ERR_WORKSPACE" and "static scratch" in str(e.value)
