@@ -288,23 +288,23 @@ def survey(steps, name_filter):
     import torch
     from paper_1811_05213_amd import Plan
     from workloads import f32_to_bf16_bits, min_hbm_bytes
-    from workloads.patterns import cases
+    from workloads.patterns import cases, more_cases
     rng = np.random.default_rng(181105213)
-    print("%-24s %9s x %-9s %2s  %5s %3s %5s %7s %6s | %9s %9s %7s %6s" % ("pattern", "rows", "cols", "k", "L", "E", "WG", "grid", "LDS", "us", "median us", "GB/s", "% peak"))
-    for name, g, r, c in cases():
+    print("%-30s %9s x %-9s %2s  %5s %3s %5s %7s %6s | %9s %9s %7s %6s" % ("pattern", "rows", "cols", "k", "L", "E", "WG", "grid", "LDS", "us", "median us", "GB/s", "% peak"))
+    for name, g, r, c in cases() + more_cases():
         if name_filter and name_filter not in name:
             continue
         ins = []
         for i in g.input_ids():
             n = g.nodes[i]
             a = rng.standard_normal((n.rows, n.cols), dtype=np.float32)
-            ins.append(f32_to_bf16_bits(a) if n.dtype == "bf16" else a)
+            ins.append(f32_to_bf16_bits(a) if n.dtype == "bf16" else (a > -1.28).astype(np.uint8) if n.dtype == "u8" else a)
         plan = Plan(g)
         gi = plan.group_info(0)
         runs = build_sets(plan, g, ins, "cuda:0", 2 << 30)
         res = time_plan(runs, steps, 5)
         gbs = min_hbm_bytes(g) / res["ms_median"] / 1e6
-        print("%-24s %9d x %-9d %2d  %5d %3d %5d %7d %6d | %9.1f %9.1f %7.0f %6.1f" % (
+        print("%-30s %9d x %-9d %2d  %5d %3d %5d %7d %6d | %9.1f %9.1f %7.0f %6.1f" % (
             name, r, c, plan.stats()["num_launches"], gi["lanes_per_row"], gi["elems_per_lane"], gi["wg_threads"], gi["grid"],
             gi["lds_bytes"], res["ms"] * 1e3, res["ms_median"] * 1e3, gbs, gbs / 80.0), flush=True)
         del runs

@@ -91,6 +91,113 @@ def row_norms(r, c):
     return g
 
 
+def dropout_residual(r, c, dt="bf16"):
+    g = Graph()
+    x, res, m = g.input(r, c, dt), g.input(r, c, dt), g.input(r, c, "u8")
+    kept = g.select(m, g.binary("mul", _f32(g, x, dt), g.const(1.0 / 0.9, r, c)), g.const(0.0, r, c))
+    g.set_outputs([_out(g, g.binary("add", kept, _f32(g, res, dt)), dt)])
+    return g
+
+
+def batchnorm(r, c):
+    """Training-mode batch normalisation over the rows of [r, c]: column statistics, then the normalised tensor."""
+    g = Graph()
+    x, gam, bet = g.input(r, c), g.input(1, c), g.input(1, c)
+    mean = g.reduce_col("mean", x)
+    xc = g.binary("sub", x, g.bcast_rowvec(mean, r))
+    var = g.reduce_col("mean", g.binary("mul", xc, xc))
+    rstd = g.unary("rsqrt", g.binary("add", var, g.const(1e-5, 1, c)))
+    y = g.binary("add", g.binary("mul", g.binary("mul", xc, g.bcast_rowvec(rstd, r)), g.bcast_rowvec(gam, r)), g.bcast_rowvec(bet, r))
+    g.set_outputs([y, mean, var])
+    return g
+
+
+def heads_softmax(r, c, head, dt="bf16"):
+    """Softmax over `head` consecutive columns at a time: [r, c] viewed as [r*c/head, head] and back."""
+    g = Graph()
+    x = g.input(r, c, dt)
+    v = g.reshape(x, r * c // head, head)
+    z = _f32(g, v, dt)
+    e = g.unary("exp", g.binary("sub", z, g.bcast_colvec(g.reduce_row("max", z), head)))
+    y = _out(g, g.binary("div", e, g.bcast_colvec(g.reduce_row("sum", e), head)), dt)
+    g.set_outputs([g.reshape(y, r, c)])
+    return g
+
+
+def concat_layernorm(r, c, dt="bf16"):
+    g = Graph()
+    a, b, gam, bet = g.input(r, c // 2, dt), g.input(r, c // 2, dt), g.input(1, c), g.input(1, c)
+    h = _f32(g, g.concat(a, b, "cols"), dt)
+    hc = g.binary("sub", h, g.bcast_colvec(g.reduce_row("mean", h), c))
+    rstd = g.unary("rsqrt", g.binary("add", g.reduce_row("mean", g.binary("mul", hc, hc)), g.const(1e-5, r, 1)))
+    y = g.binary("add", g.binary("mul", g.binary("mul", hc, g.bcast_colvec(rstd, c)), g.bcast_rowvec(gam, r)), g.bcast_rowvec(bet, r))
+    g.set_outputs([_out(g, y, dt)])
+    return g
+
+
+def l2_normalise(r, c):
+    g = Graph()
+    x = g.input(r, c)
+    inv = g.unary("rsqrt", g.binary("add", g.reduce_row("sum", g.binary("mul", x, x)), g.const(1e-12, r, 1)))
+    g.set_outputs([g.binary("mul", x, g.bcast_colvec(inv, c))])
+    return g
+
+
+def bias_transpose(r, c, dt="bf16"):
+    g = Graph()
+    x, b = g.input(r, c, dt), g.input(1, c)
+    g.set_outputs([g.transpose(_out(g, g.binary("add", _f32(g, x, dt), g.bcast_rowvec(b, r)), dt))])
+    return g
+
+
+def gelu_grad(r, c, dt="bf16"):
+    """dy * d/dx gelu_tanh(x), written out in elementwise ops."""
+    g = Graph()
+    x, dy = g.input(r, c, dt), g.input(r, c, dt)
+    xf, k = _f32(g, x, dt), (lambda val: g.const(val, r, c))
+    x2 = g.binary("mul", xf, xf)
+    t = g.unary("tanh", g.binary("mul", g.binary("mul", xf, k(0.7978845608)), g.binary("add", k(1.0), g.binary("mul", x2, k(0.044715)))))
+    dt_dx = g.binary("mul", g.binary("mul", g.binary("sub", k(1.0), g.binary("mul", t, t)), k(0.7978845608)),
+                     g.binary("add", k(1.0), g.binary("mul", x2, k(3 * 0.044715))))
+    d = g.binary("add", g.binary("mul", k(0.5), g.binary("add", k(1.0), t)), g.binary("mul", g.binary("mul", k(0.5), xf), dt_dx))
+    g.set_outputs([_out(g, g.binary("mul", _f32(g, dy, dt), d), dt)])
+    return g
+
+
+def logsumexp(r, c):
+    g = Graph()
+    x = g.input(r, c)
+    m = g.reduce_row("max", x)
+    s = g.reduce_row("sum", g.unary("exp", g.binary("sub", x, g.bcast_colvec(m, c))))
+    g.set_outputs([g.binary("add", g.unary("log", s), m)])
+    return g
+
+
+def scale_rows_cols(r, c):
+    g = Graph()
+    x, a, b = g.input(r, c), g.input(r, 1), g.input(1, c)
+    g.set_outputs([g.binary("mul", g.binary("mul", x, g.bcast_colvec(a, c)), g.bcast_rowvec(b, r))])
+    return g
+
+
+def more_cases():
+    """Patterns around the shape-modulation ops, masks and column statistics (`bench.py --survey` times them after `cases()`)."""
+    out = []
+    out.append(("dropout+residual bf16/u8", dropout_residual(16384, 4096), 16384, 4096))
+    for r, c in [(65536, 256), (16384, 1024), (4096, 8192)]:
+        out.append(("batchnorm f32", batchnorm(r, c), r, c))
+    out.append(("softmax per 256-wide head bf16", heads_softmax(4096, 4096, 256), 4096, 4096))
+    out.append(("softmax per 64-wide head bf16", heads_softmax(8192, 2048, 64), 8192, 2048))
+    out.append(("concat+layernorm bf16", concat_layernorm(8192, 4096), 8192, 4096))
+    out.append(("l2 normalise f32", l2_normalise(32768, 1024), 32768, 1024))
+    out.append(("bias+transpose bf16", bias_transpose(8192, 4096), 8192, 4096))
+    out.append(("gelu backward bf16", gelu_grad(16384, 4096), 16384, 4096))
+    out.append(("logsumexp f32", logsumexp(8192, 32768), 8192, 32768))
+    out.append(("logsumexp f32", logsumexp(65536, 1024), 65536, 1024))
+    out.append(("scale rows and columns f32", scale_rows_cols(16384, 4096), 16384, 4096))
+    return out
+
+
 def cases():
     out = []
     for r, c in [(4096, 4096), (16384, 2048), (65536, 128), (8192, 8192), (2048, 32768), (1 << 20, 64), (4096, 65536), (2048, 131072)]:
