@@ -340,7 +340,10 @@ fs_status fs_device_limits(int32_t* compute_units, int32_t* lds_bytes_per_workgr
 
 fs_status fs_plan_group_info(const fs_plan* plan, int32_t group, fs_group_info* out_info);
 
-/* The group each node was assigned to (-1 for INPUT/CONST/BCAST_*). out has room for num_nodes entries. */
+/* The group each node was assigned to (-1 for INPUT/CONST/BCAST_*). out has room for num_nodes entries.
+ * In the library's own plans an elementwise value that a later kernel needs may be computed by that kernel
+ * as well (from operands that are in memory anyway) instead of being stored and read back: this reports the
+ * first kernel that computes the node, and fs_group_info's num_nodes counts such copies in each kernel. */
 fs_status fs_plan_node_groups(const fs_plan* plan, int32_t* out, int32_t num_nodes);
 
 /* Work/Span analysis (Section 3.1): the span of every node: 0 for a node no live node consumes,

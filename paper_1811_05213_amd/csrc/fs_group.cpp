@@ -584,7 +584,7 @@ struct Scheduler {
 static fs_status choose_schedule(const Graph& g, const PlanOptions& opt, GroupPlan* gp) { return Scheduler(g, opt, gp).run(); }
 
 fs_status analyse_group(const Graph& g, const std::vector<int>& members, const std::vector<int>& /*group_of*/,
-                        int /*self_group*/, const PlanOptions& opt, GroupPlan* out) {
+                        int self_group, const PlanOptions& opt, GroupPlan* out) {
   GroupPlan& gp = *out;
   gp = GroupPlan();
   gp.members = members;
@@ -702,10 +702,21 @@ fs_status analyse_group(const Graph& g, const std::vector<int>& members, const s
         const int uop = g.nodes[u].opcode;
         if (uop == FS_BCAST_ROWVEC || uop == FS_BCAST_COLVEC) scan_users(u);
         else if (op_is_view(uop)) leaves = true;  // a view is read from memory (or is a plan output): the value must exist there
-        else if (!a.in_set[u]) leaves = true;
+        else if (!opt.clones) leaves |= !a.in_set[u];
+        else {
+          // every kernel that computes u reads m from memory unless it computes m itself
+          const CloneInfo& ci = *opt.clones;
+          auto needs = [&](int h) { return h == self_group ? !a.in_set[u] : (h >= 0 && !ci.computed_in(m, h)); };
+          leaves |= needs(ci.group_of[u]);
+          auto it = ci.extra.find(u);
+          if (it != ci.extra.end())
+            for (int h : it->second) leaves |= needs(h);
+        }
       }
     };
     scan_users(m);
+    // (a copy: the first kernel that computes the value is the one that stores it)
+    if (opt.clones && opt.clones->group_of[m] != self_group) leaves = false;
     if (leaves) {
       ExtTensor e;
       e.node = m;
@@ -1181,6 +1192,134 @@ fs_status form_groups(const Graph& g, const fs_graph_desc* desc, const PlanOptio
   }
   *group_of = f.group_of;
   return f.topo_order(ordered);
+}
+
+void recompute_across_kernels(const Graph& g, const PlanOptions& opt, std::vector<int>* group_of,
+                              std::vector<std::vector<int>>* ordered, CloneInfo* ci) {
+  const int NG = (int)ordered->size();
+  ci->group_of = *group_of;
+  ci->extra.clear();
+  if (NG < 2) return;
+  PlanOptions o = opt;
+  o.clones = ci;
+  std::vector<GroupPlan> gps(NG);
+  for (int gi = 0; gi < NG; ++gi)
+    if (analyse_group(g, (*ordered)[gi], *group_of, gi, o, &gps[gi]) != FS_OK) return;  // (plan creation reports it)
+  auto elementwise = [&](int op) { return op_is_unary(op) || op_is_binary(op) || op == FS_CMP || op == FS_SELECT; };
+  auto in_list = [](const std::vector<ExtTensor>& l, int node) {
+    for (const ExtTensor& e : l)
+      if (e.node == node) return true;
+    return false;
+  };
+  for (int b = 1; b < NG; ++b) {
+    for (int round = 0; round < 16; ++round) {  // a copy may expose its own producer
+      bool changed = false;
+      const std::vector<ExtTensor> reads = gps[b].ext_in;
+      for (const ExtTensor& e : reads) {
+        const int t = e.node;
+        const fs_node& n = g.nodes[t];
+        if (e.kind != KIND_FULL || ci->group_of[t] < 0 || !elementwise(n.opcode) || ci->computed_in(t, b)) continue;
+        if (g.family_output[t] >= 0) continue;  // a plan output exists in memory anyway: reading it is as cheap as its operands
+        // every reader inside b takes it as a plain operand (not under another shape), and nobody views it
+        bool plain = true;
+        for (int u : g.users[t]) plain &= !op_is_view(g.nodes[u].opcode);
+        for (int m : (*ordered)[b])
+          for (int k = 0; k < g.nodes[m].num_in; ++k) plain &= !(g.nodes[m].in[k] == t && g.flat_in[m][k]);
+        if (!plain) continue;
+        // the value and, with it, those of its elementwise producers that exist in no memory: everything else they read has to
+        // be there already (plan inputs, values some kernel stores anyway, vectors)
+        std::vector<int> T, stack{t};
+        bool available = true;
+        while (!stack.empty() && available) {
+          const int x = stack.back();
+          stack.pop_back();
+          if (std::find(T.begin(), T.end(), x) != T.end()) continue;
+          T.push_back(x);
+          if (T.size() > 8) available = false;
+          const fs_node& xn = g.nodes[x];
+          for (int k = 0; k < xn.num_in && available; ++k) {
+            int src = xn.in[k];
+            if (g.flat_in[x][k]) available = false;
+            while (g.nodes[src].opcode == FS_BCAST_ROWVEC || g.nodes[src].opcode == FS_BCAST_COLVEC) src = g.nodes[src].in[0];
+            const fs_node& sn = g.nodes[src];
+            if (sn.opcode == FS_CONST || sn.opcode == FS_INPUT) continue;
+            const int h = ci->group_of[src];
+            if (h >= 0 && ci->computed_in(src, b)) continue;
+            if (h < 0 || h >= b) available = false;  // (a view; or not a value of an earlier kernel)
+            else if (in_list(gps[h].ext_out, src)) continue;
+            else if ((int64_t)sn.rows * sn.cols < (int64_t)n.rows * n.cols) continue;  // a vector: storing it costs next to nothing
+            else if (elementwise(sn.opcode)) stack.push_back(src);
+            else available = false;
+          }
+        }
+        if (!available) continue;
+        // every producer keeps what it still uses itself
+        CloneInfo trial = *ci;
+        std::map<int, std::vector<int>> mm;  // member lists of the kernels that change
+        mm[b] = (*ordered)[b];
+        std::sort(T.begin(), T.end());
+        for (int i = (int)T.size() - 1; i >= 0; --i) {  // consumers before producers
+          const int x = T[i], a = trial.group_of[x];
+          if (!mm.count(a)) mm[a] = (*ordered)[a];
+          std::vector<int>& ma = mm[a];
+          // it stays in its kernel while something there uses it, or while a third kernel reads it from memory
+          // (the first kernel that computes a value is the one that stores it, and that one runs before every reader)
+          bool stays = false;
+          for (int u : g.users[x]) {
+            std::vector<int> chain{u};
+            while (!chain.empty()) {
+              const int y = chain.back();
+              chain.pop_back();
+              const int yop = g.nodes[y].opcode;
+              if (yop == FS_BCAST_ROWVEC || yop == FS_BCAST_COLVEC) {
+                chain.insert(chain.end(), g.users[y].begin(), g.users[y].end());
+                continue;
+              }
+              stays |= std::find(ma.begin(), ma.end(), y) != ma.end() || op_is_view(yop);
+              auto other = [&](int h) { return h >= 0 && h != a && h != b && !trial.computed_in(x, h); };
+              stays |= other(trial.group_of[y]);
+              auto it = trial.extra.find(y);
+              if (it != trial.extra.end())
+                for (int h : it->second) stays |= other(h);
+            }
+          }
+          mm[b].push_back(x);
+          if (stays) {
+            trial.extra[x].insert(b);
+          } else {
+            ma.erase(std::find(ma.begin(), ma.end(), x));
+            trial.group_of[x] = b;
+            trial.extra[x].erase(b);
+          }
+        }
+        bool fits = (int)mm[b].size() <= kMaxGroupMembers;
+        for (auto& kv : mm) fits &= !kv.second.empty();
+        if (!fits) continue;
+        PlanOptions ot = opt;
+        ot.clones = &trial;
+        std::map<int, GroupPlan> np;
+        uint64_t before = 0, after = 0;
+        for (auto& kv : mm) {
+          fits = fits && analyse_group(g, kv.second, trial.group_of, kv.first, ot, &np[kv.first]) == FS_OK;
+          if (!fits) break;
+          before += gps[kv.first].min_hbm_bytes;
+          after += np[kv.first].min_hbm_bytes;
+        }
+        if (!fits || after >= before || !worth_fusing(np[b])) continue;
+        // a kernel that changes its form for the copy (rows no longer held in registers, another launch shape class) is not worth it
+        if (np[b].s.chunked != gps[b].s.chunked || np[b].s.split_rows != gps[b].s.split_rows || np[b].s.col_tiled != gps[b].s.col_tiled) continue;
+        for (auto& kv : mm) {
+          (*ordered)[kv.first] = kv.second;
+          gps[kv.first] = np[kv.first];
+        }
+        *ci = trial;
+        changed = true;
+        break;
+      }
+      if (!changed) break;
+    }
+  }
+  *group_of = ci->group_of;
 }
 
 void work_span(const Graph& g, std::vector<int>* span) {

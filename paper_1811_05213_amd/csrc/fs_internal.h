@@ -7,6 +7,7 @@
 #include <cstdio>
 #include <array>
 #include <map>
+#include <set>
 #include <mutex>
 #include <string>
 #include <vector>
@@ -197,6 +198,20 @@ struct GroupPlan {
   std::string perf_key;  // filled on demand by fs_plan_group_perf_key
 };
 
+// Values that more than one kernel computes.  A cheap elementwise result that a later kernel needs is
+// computed again there, from operands that exist in memory anyway, instead of passing through memory
+// itself: group_of holds the (first) kernel of every node in launch order, extra the other kernels
+// that hold a copy of it.
+struct CloneInfo {
+  std::vector<int> group_of;
+  std::map<int, std::set<int>> extra;
+  bool computed_in(int node, int grp) const {
+    if (group_of[node] == grp) return true;
+    auto it = extra.find(node);
+    return it != extra.end() && it->second.count(grp) != 0;
+  }
+};
+
 struct PlanOptions {
   uint32_t mode = FS_MODE_STITCHED;
   int lds_budget = 65536;
@@ -209,6 +224,8 @@ struct PlanOptions {
   int wide_level = 2;
   int min_waves = 0;  // > 0: the kernel asks the compiler for that many wavefronts per SIMD (occupancy feedback at plan creation)
   bool layered = false;  // group with the layered planner of Section 3.2 instead of the default one
+  // set once the groups are final: whether a value leaves a kernel then depends on which kernels compute it themselves
+  const CloneInfo* clones = nullptr;
 };
 
 // Analyse a candidate member set: work space, kinds, stages, external tensors, schedule, LDS plan.
@@ -221,6 +238,13 @@ fs_status analyse_group(const Graph& g, const std::vector<int>& members, const s
 // Assign every compute node to a group.  group_of[node] = group id or -1 for free nodes.
 fs_status form_groups(const Graph& g, const fs_graph_desc* desc, const PlanOptions& opt, std::vector<int>* group_of,
                       std::vector<std::vector<int>>* groups_in_launch_order);
+
+// After grouping: elementwise values that cross a kernel boundary are computed again by the consuming
+// kernel where that moves fewer bytes (the consumer reads the producer's operands, which exist in
+// memory anyway, instead of the value; the producer no longer stores it when nobody else reads it).
+// Adds the copies to the consumers' member lists and records them in `clones`.
+void recompute_across_kernels(const Graph& g, const PlanOptions& opt, std::vector<int>* group_of,
+                              std::vector<std::vector<int>>* groups_in_launch_order, CloneInfo* clones);
 
 // Work/Span analysis (Section 3.1): span per node, -1 for inlined and dead nodes.
 void work_span(const Graph& g, std::vector<int>* span);
@@ -254,6 +278,7 @@ struct fs_plan {
   fs::Graph graph;
   fs::PlanOptions opt;
   std::vector<int> group_of;
+  fs::CloneInfo clones;               // values computed by more than one kernel (opt.clones points here)
   std::vector<fs::GroupPlan> groups;  // in launch order
   // workspace layout
   std::map<int, size_t> ws_tensor_offset;  // node materialised in the workspace -> byte offset

@@ -337,6 +337,13 @@ fs_status fs_plan_create(const fs_graph_desc* desc, fs_plan** out_plan) {
   // group ids follow launch order
   for (size_t gi = 0; gi < ordered.size(); ++gi)
     for (int m : ordered[gi]) plan->group_of[m] = (int)gi;
+  // the library's own grouping may compute a cheap value in two kernels rather than pass it through memory
+  // (a caller's plan and the one-launch-per-op executor are taken as they are)
+  if (plan->opt.mode != FS_MODE_UNFUSED && !desc->group_of_node) {
+    recompute_across_kernels(g, plan->opt, &plan->group_of, &ordered, &plan->clones);
+    plan->opt.clones = &plan->clones;
+    plan->groups.resize(ordered.size());
+  }
   for (size_t gi = 0; gi < ordered.size(); ++gi) {
     st = analyse_group(g, ordered[gi], plan->group_of, (int)gi, plan->opt, &plan->groups[gi]);
     if (st == FS_OK) st = generate_kernel(g, &plan->groups[gi], (int)gi);

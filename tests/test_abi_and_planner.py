@@ -542,22 +542,83 @@ def test_few_long_rows_are_split_over_workgroups():
     assert p.stats()["num_launches"] == 1 and p.group_info(0)["grid"] == 40
     assert fs.Plan(norms(4096, 1 << 18)).group_info(0)["grid"] == 4096
     assert fs.Plan(norms(4, 1 << 14)).group_info(0)["grid"] == 4
-    # up to 32 such rows, groups that cannot take this form are not formed: a softmax becomes max | exp and sum (stores the
-    # exponentials) | divide, three launches that each fill the device instead of one on 2 CUs
-    p = fs.Plan(softmax_graph(2, 1 << 20))
+    # up to 32 such rows, groups that cannot take this form are not formed: a softmax becomes max | sum of the exponentials |
+    # exponentials again and divide, three launches that each fill the device instead of one on 2 CUs; the exponentials are
+    # computed by both kernels that need them rather than stored by one and read by the other (x is read three times and
+    # the result written once: four passes, not five)
+    g = softmax_graph(2, 1 << 20)
+    p = fs.Plan(g)
     assert p.stats()["num_launches"] == 3 and [p.group_info(i)["grid"] for i in range(2)] == [256, 256]
-    assert "fs_store_row" in p.group_source(1) and "constexpr int S = 128" in p.group_source(1)
+    assert "fs_store_row" not in p.group_source(1) and "constexpr int S = 128" in p.group_source(1) and "fs_exp" in p.group_source(1)
+    assert "fs_exp" in p.group_source(2) and p.group_info(2)["num_nodes"] == 3
+    assert p.stats()["launched_hbm_bytes"] == 2 * min_hbm_bytes(g) + 5 * (2 * 4)  # + the [R,1] maxima (written once, read twice) and sums (written, read)
+
+
+def _batchnorm_like(rows, cols, extra_reader=False, keep_as_output=False):
+    g = Graph()
+    x = g.input(rows, cols)
+    mean = g.reduce_col("mean", x)
+    xc = g.binary("sub", x, g.bcast_rowvec(mean, rows), name="xc")
+    var = g.reduce_col("mean", g.binary("mul", xc, xc))
+    rstd = g.unary("rsqrt", g.binary("add", var, g.const(1e-5, 1, cols)))
+    y = g.binary("mul", xc, g.bcast_rowvec(rstd, rows))
+    outs = [y, var]
+    if extra_reader:  # a third kernel that needs xc as well (it consumes var, so it cannot join the kernel that folds var)
+        outs.append(g.binary("add", g.unary("abs", xc), g.bcast_rowvec(var, rows)))
+    if keep_as_output:
+        outs.append(xc)
+    g.set_outputs(outs)
+    return g, xc
+
+
+def test_values_needed_by_two_kernels_are_computed_twice_when_that_moves_fewer_bytes():
+    rows, cols = 8192, 2048
+    full, vec = rows * cols * 4, cols * 4
+    # column statistics force three kernels; the centred values are needed by the second (variance) and the third (result):
+    # the third computes them again from x and the means instead of reading a copy the second would have to store
+    g, xc = _batchnorm_like(rows, cols)
+    p = fs.Plan(g)
+    st = p.stats()
+    assert st["num_launches"] == 3 and p.workspace_bytes() < full  # no [R,C] value passes through the workspace
+    # x read three times, y written once; the means written once and read twice, the variances written and read once
+    assert st["launched_hbm_bytes"] == 4 * full + 5 * vec
+    assert p.node_groups()[xc] == 1 and [p.group_info(k)["num_nodes"] for k in range(3)] == [1, 3, 4]
+    own = [max(k, 0) for k in p.node_groups()]
+    p.destroy()
+    # the caller's own plan is taken as it is: the value is stored by its kernel and read by the other
+    q = fs.Plan(g, group_of_node=own)
+    assert q.stats()["num_launches"] == 3 and q.stats()["launched_hbm_bytes"] == 5 * full + 4 * vec and q.workspace_bytes() > full
+    q.destroy()
+    # a third reader in the last kernel: still one copy there, nothing stored
+    g3, _ = _batchnorm_like(rows, cols, extra_reader=True)
+    p = fs.Plan(g3)
+    assert p.stats()["num_launches"] == 3 and p.stats()["launched_hbm_bytes"] == 5 * full + 5 * vec and p.workspace_bytes() < full
+    p.destroy()
+    # a plan output exists in memory anyway: the last kernel reads it (as many bytes as reading x)
+    g2, _ = _batchnorm_like(rows, cols, keep_as_output=True)
+    p = fs.Plan(g2)
+    assert p.stats()["launched_hbm_bytes"] == 5 * full + 4 * vec and p.workspace_bytes() < full
+    p.destroy()
+    # the one-launch-per-op executor is untouched
+    u = fs.Plan(g, mode=fs.FS_MODE_UNFUSED)
+    assert u.stats()["num_launches"] == len(g.compute_ids())
+    u.destroy()
 
 
 def test_survey_patterns_are_single_kernels():
     # every pattern of the shape survey (softmax variants, norms, optimizer update, column sums, transposes, backward passes)
     # from 64 to 131072 columns plans as ONE stitched kernel (the softmax over 8 rows of a million columns is the one
     # exception: cut into three kernels that each fill the device)
+    # (and batch normalisation, whose column statistics cannot be broadcast back inside the kernel that folds them:
+    # means, variances of the centred values, the normalised tensor -- x read three times and y written once)
     from workloads import patterns as survey
-    for name, g, rows, cols in survey.cases():
+    for name, g, rows, cols in survey.cases() + survey.more_cases():
         p = fs.Plan(g)
         if rows <= 32 and cols >= (1 << 20) and "softmax" in name:
             assert p.stats()["num_launches"] == 3, (name, rows, cols)
+        elif "batchnorm" in name:
+            assert p.stats()["num_launches"] == 3, (name, rows, cols)
+            assert p.stats()["launched_hbm_bytes"] == min_hbm_bytes(g) + 2 * rows * cols * 4 + 3 * cols * 4
         else:
             assert p.stats()["num_launches"] == 1, (name, rows, cols)
             assert p.stats()["launched_hbm_bytes"] == p.stats()["min_hbm_bytes"] == min_hbm_bytes(g)

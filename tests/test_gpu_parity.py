@@ -694,6 +694,47 @@ def test_wide_transposes_in_2d_tiles():
         np.testing.assert_array_equal(out_s[2], ref[2])
 
 
+def test_values_recomputed_by_the_kernels_that_need_them():
+    # an elementwise value needed on both sides of a kernel boundary is computed on both sides instead of stored and read:
+    # batch normalisation (the centred values), with a third reader and with the value kept as a plan output; a chain of
+    # producers that spans two kernels (a bf16 input's conversion, the centring) or one (the exponentials of a softmax over a
+    # handful of very long rows)
+    from workloads.patterns import batchnorm
+    for rows, cols in ((3000, 520), (20000, 1024), (700, 4100)):
+        g = batchnorm(rows, cols)
+        p = fs.Plan(g)
+        if rows * cols * 4 >= (16 << 20):  # (smaller ones are launch-bound and keep their column folds apart: other kernels)
+            assert p.stats()["num_launches"] == 3 and p.workspace_bytes() < rows * cols * 4
+        p.destroy()
+        ins = [(0.5 + RNG.standard_normal((rows, cols))).astype(np.float32), RNG.standard_normal((1, cols)).astype(np.float32),
+               RNG.standard_normal((1, cols)).astype(np.float32)]
+        both_modes(g, ins, f"batchnorm {rows}x{cols}")
+    for kw in ({"extra_reader": True}, {"keep_as_output": True}):
+        rows, cols = 5000, 1032
+        g = Graph()
+        x = g.input(rows, cols, "bf16")
+        xf = g.unary("convert", x, "f32")
+        mean = g.reduce_col("mean", xf)
+        xc = xcf = g.binary("sub", xf, g.bcast_rowvec(mean, rows))   # its producer chain (the convert) lives in the first kernel
+        var = g.reduce_col("mean", g.binary("mul", xcf, xcf))
+        y = g.binary("mul", xcf, g.bcast_rowvec(g.unary("rsqrt", g.binary("add", var, g.const(1e-5, 1, cols))), rows))
+        outs = [y, var]
+        if "extra_reader" in kw:
+            outs.append(g.binary("add", g.unary("abs", xcf), g.bcast_rowvec(var, rows)))
+        else:
+            outs.append(xc)
+        g.set_outputs(outs)
+        p = fs.Plan(g)
+        assert p.stats()["num_launches"] == 3
+        p.destroy()
+        both_modes(g, [f32_to_bf16_bits((0.5 + RNG.standard_normal((rows, cols))).astype(np.float32))], f"centred bf16 input {kw}")
+    g = softmax_graph(3, (1 << 19) + 8)
+    p = fs.Plan(g)
+    assert p.stats()["num_launches"] == 3 and p.stats()["launched_hbm_bytes"] < 4.01 * 3 * ((1 << 19) + 8) * 4
+    p.destroy()
+    both_modes(g, [RNG.standard_normal((3, (1 << 19) + 8)).astype(np.float32)], "softmax 3 x 512K")
+
+
 def test_wide_transposes_of_bytes():
     # u8 alone is read in 16-element vectors: the tile (one float per element) is narrowed until it fits the LDS budget
     for rows, cols in ((1000, 4096), (130, 8208), (4100, 272)):
