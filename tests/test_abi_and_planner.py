@@ -605,6 +605,28 @@ def test_values_needed_by_two_kernels_are_computed_twice_when_that_moves_fewer_b
     u.destroy()
 
 
+def test_recomputation_never_moves_more_bytes_than_the_same_groups_without_it():
+    # random graphs, with and without views: the library's plan against the same grouping given back as the caller's
+    # plan (which is taken as it is: every value on a kernel boundary is stored by its producer and read by its consumers)
+    import sys
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from graphgen import random_graph
+    fewer = 0
+    for seed in range(3000, 3006):
+        rows, cols = [(1000, 1000), (64, 16384), (4096, 260), (257, 1025)][seed % 4]
+        g = random_graph(seed, rows, cols, 40, views=(seed % 2 == 0))
+        p = fs.Plan(g)
+        own = [max(k, 0) for k in p.node_groups()]
+        q = fs.Plan(g, group_of_node=own)
+        a, b = p.stats(), q.stats()
+        assert a["num_launches"] == b["num_launches"] and a["launched_hbm_bytes"] <= b["launched_hbm_bytes"], (seed, a, b)
+        assert p.workspace_bytes() <= q.workspace_bytes()
+        fewer += a["launched_hbm_bytes"] < b["launched_hbm_bytes"]
+        p.destroy()
+        q.destroy()
+    assert fewer >= 2
+
+
 def test_survey_patterns_are_single_kernels():
     # every pattern of the shape survey (softmax variants, norms, optimizer update, column sums, transposes, backward passes)
     # from 64 to 131072 columns plans as ONE stitched kernel (the softmax over 8 rows of a million columns is the one
