@@ -1252,7 +1252,11 @@ void recompute_across_kernels(const Graph& g, const PlanOptions& opt, std::vecto
             else available = false;
           }
         }
-        if (!available) continue;
+        // (bytes are what is scarce, but not free of charge: at most two transcendental or division-like operations are
+        // computed a second time for one value)
+        int dear = 0;
+        for (int x : T) dear += op_is_approx(g.nodes[x].opcode) || g.nodes[x].opcode == FS_DIV || g.nodes[x].opcode == FS_SQRT;
+        if (!available || dear > 2) continue;
         // every producer keeps what it still uses itself
         CloneInfo trial = *ci;
         std::map<int, std::vector<int>> mm;  // member lists of the kernels that change
