@@ -735,6 +735,37 @@ def test_values_recomputed_by_the_kernels_that_need_them():
     both_modes(g, [RNG.standard_normal((3, (1 << 19) + 8)).astype(np.float32)], "softmax 3 x 512K")
 
 
+def test_transposes_at_the_sizes_the_survey_times():
+    # many bands of column tiles, full and ragged, over hundreds of row tiles: every element, bit for bit
+    for rows, cols, dt in ((8192, 8192, "f32"), (1024, 65536 + 384, "f32"), (16384 + 64, 4096, "bf16")):
+        g = Graph()
+        g.set_outputs([g.transpose(g.input(rows, cols, dt))])
+        p = fs.Plan(g)
+        assert "in_band" in p.group_source(0)
+        p.destroy()
+        v = RNG.standard_normal((rows, cols)).astype(np.float32)
+        x = f32_to_bf16_bits(v) if dt == "bf16" else v
+        ref, out_s, _ = both_modes(g, [x], f"transpose {rows}x{cols} {dt}")
+        got = out_s[0]
+        np.testing.assert_array_equal(got.view(x.dtype).reshape(cols, rows), x.T)
+
+
+def test_column_sums_at_the_sizes_the_survey_times():
+    # 4 to 16 column tiles with 16 to 64 workgroups each (fold fan-in 8 and 16), every output element
+    from workloads.patterns import bias_grad, colsum
+    for rows, cols, dt in ((16384, 4096, "f32"), (8192, 8192, "bf16"), (4096, 16384, "f32")):
+        g = colsum(rows, cols, dt)
+        p = fs.Plan(g)
+        gi = p.group_info(0)
+        assert p.stats()["num_launches"] == 1 and gi["lanes_per_row"] == 64 and gi["grid"] == 256
+        p.destroy()
+        v = (0.5 + RNG.standard_normal((rows, cols))).astype(np.float32)
+        both_modes(g, [f32_to_bf16_bits(v) if dt == "bf16" else v], f"column sums {rows}x{cols} {dt}")
+    g = bias_grad(16384, 4096)
+    both_modes(g, [RNG.standard_normal((16384, 4096)).astype(np.float32), (0.5 + RNG.standard_normal((16384, 4096))).astype(np.float32)],
+               "bias gradient 16384x4096")
+
+
 def test_wide_transposes_of_bytes():
     # u8 alone is read in 16-element vectors: the tile (one float per element) is narrowed until it fits the LDS budget
     for rows, cols in ((1000, 4096), (130, 8208), (4100, 272)):
