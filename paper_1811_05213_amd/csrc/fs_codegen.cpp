@@ -22,6 +22,7 @@
 //     after the other, (p + beta) + bias, are added to each other once per workgroup instead of
 //     once per element: p + (beta + bias).  This reassociates, so it is not done on predicate
 //     paths either; elsewhere the result moves by one rounding, as with the fma contraction.
+#include <cstdlib>
 #include <algorithm>
 #include <cstring>
 #include <functional>
@@ -222,10 +223,13 @@ struct Emitter {
     const std::string nm = name(holder, gp.kind.at(holder));
     if (e.transposed) {
       // the value leaves in the flipped orientation: through a padded LDS tile when the plan has one
-      if (gp.s.tile_transpose)
-        os << indent << "fs_store_tile_transposed<" << e.dtype << ", " << tmpl_row() << ", WG, TCW, C>(" << nm << ", lds_tile, a.p[" << e.arg
+      if (gp.s.tile_transpose) {
+        // tensors far larger than the caches leave with non-temporal stores, like the plain row stores
+        // (transposes of 256-512 MB: 2-5 % faster; 16 MB and u8: not)
+        const bool nt = dtype_size(e.dtype) >= 2 && (uint64_t)g.nodes[e.node].rows * g.nodes[e.node].cols * dtype_size(e.dtype) >= (32ull << 20);
+        os << indent << "fs_store_tile_transposed<" << e.dtype << ", " << tmpl_row() << ", WG, TCW, C, " << (nt ? "true" : "false") << ">(" << nm << ", lds_tile, a.p[" << e.arg
            << "], R, row - rg, lir, rg, vbase);\n";
-      else
+      } else
         os << indent << "fs_store_row_transposed<" << e.dtype << ", " << tmpl_row() << ">(" << nm << ", a.p[" << e.arg
            << "], R, row, lir, vbase, rok);\n";
       return;

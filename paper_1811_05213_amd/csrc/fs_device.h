@@ -353,7 +353,7 @@ template <int DT> FS_DEV void fs_store1_fwd(void* base, long i, float x) {
 // elements instead of single elements R apart.  LDS holds TC x (G+1) floats (the +1 keeps the
 // column-wise writes of the row-groups of a wavefront on distinct banks).  vbase = col0 / V is the
 // tile's first vector in the row.  Every lane of the workgroup must call it.
-template <int DT, int V, int NVL, int L, int NV, bool RAGGED, int WG, int TC, int CTOT>
+template <int DT, int V, int NVL, int L, int NV, bool RAGGED, int WG, int TC, int CTOT, bool NT = false>
 FS_DEV void fs_store_tile_transposed(const float (&src)[NVL * V], float* lds, void* base, long R, long tile_row0, int lir, int rg, int vbase) {
   constexpr int G = WG / L, P = G + 1;
   __syncthreads();  // the tile may still be read by its previous use
@@ -366,9 +366,11 @@ FS_DEV void fs_store_tile_transposed(const float (&src)[NVL * V], float* lds, vo
     }
   }
   __syncthreads();
-  constexpr int RUN = (G % 4 == 0) ? 4 : 1;
+  // a lane stores 16 bytes of a run: 4 floats, 8 bf16, 16 bytes of u8 (fewer where G does not divide)
+  constexpr int WANT = 16 / (int)sizeof(typename fs_elem<DT>::type);
+  constexpr int RUN = (G % WANT == 0) ? WANT : (G % 4 == 0) ? 4 : 1;
   constexpr int RPC = G / RUN;  // runs per output row
-  const bool vec_ok = RUN == 4 && (R % 4) == 0;
+  const bool vec_ok = RUN > 1 && (R % RUN) == 0;
   const int col0 = vbase * V;
   for (int i = (int)threadIdx.x; i < TC * RPC; i += WG) {
     const int c = i / RPC, g0 = (i % RPC) * RUN;
@@ -378,8 +380,8 @@ FS_DEV void fs_store_tile_transposed(const float (&src)[NVL * V], float* lds, vo
 #pragma unroll
     for (int q = 0; q < RUN; ++q) tmp[q] = lds[c * P + g0 + q];
     const long o = (long)(col0 + c) * R + r;
-    if (RUN == 4 && vec_ok && r + 3 < R) {
-      fs_store_vec<DT, RUN>(tmp, base, o);
+    if (RUN > 1 && vec_ok && r + RUN - 1 < R) {
+      fs_store_vec<DT, RUN, NT>(tmp, base, o);
     } else {
 #pragma unroll
       for (int q = 0; q < RUN; ++q)
