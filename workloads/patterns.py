@@ -195,6 +195,12 @@ def more_cases():
     out.append(("logsumexp f32", logsumexp(8192, 32768), 8192, 32768))
     out.append(("logsumexp f32", logsumexp(65536, 1024), 65536, 1024))
     out.append(("scale rows and columns f32", scale_rows_cols(16384, 4096), 16384, 4096))
+    # tensors of 4-16 MB: kernels of 4-25 us, where what happens after the last wavefront counts
+    for r in (2048, 4096):
+        out.append(("softmax f32", softmax_graph(r, 1024), r, 1024))
+    out.append(("layernorm+gelu bf16", layernorm_gelu_graph(4096, 1024), 4096, 1024))
+    out.append(("masked softmax bf16", masked_softmax(4096, 1024), 4096, 1024))
+    out.append(("adam f32", adam(2048, 2048), 2048, 2048))
     return out
 
 
