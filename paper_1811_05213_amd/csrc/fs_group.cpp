@@ -365,8 +365,12 @@ struct Scheduler {
       // 23.6 us, residual+LayerNorm: 50.5 -> 45.8 us); one-wavefront rows only with heavy ones
       // (up to ~4 rounds of work: at [32768,2048] the one-trip form is 2-5 % faster again)
       const bool heavy = rowv_bytes * 2 >= full_bytes * 3;
+      // from two rounds of resident workgroups on; from one round where heavy operands meet rows of one or two wavefronts
+      // (LayerNorm+GeLU bf16 [8192,1024]: 9.0 -> 8.0 us, [12288,1024]: 11.7 -> 10.6 us, [6000,2048]: 12.4 -> 10.3 us; rows over
+      // four wavefronts and light operands lose there: [2048,4096] 9.9 -> 10.6 us, RMSNorm [1024,8192] 6.7 -> 7.7 us)
+      const int rounds = heavy && L <= 128 ? 1 : 2;
       const bool pays = L >= 128 ? heavy || (n_rowv_in > 0 && (int64_t)R * L <= 4 * RES) : full_slices && heavy;
-      if (pays && (int64_t)n_rowv_in * NVL * L * V * 4 + 1024 <= opt.lds_budget && (int64_t)R * L / wg >= 2 * (RES / wg)) {
+      if (pays && (int64_t)n_rowv_in * NVL * L * V * 4 + 1024 <= opt.lds_budget && (int64_t)R * L / wg >= rounds * (RES / wg)) {
         staged_loop = true;
         WG = wg;
       }
