@@ -902,6 +902,18 @@ struct Emitter {
       }
       os << ind << "__syncthreads();\n";
     };
+    // rotated loop: the first trip's rows are requested before the operands are staged, the next trip's at the end of a trip
+    bool rotate = s.rotate_loop && stage_before_loop && !ctile && !s.tiled_transpose && s.CT == 1 && !s.resident && s.U <= 1;
+    for (int m : gp.members) rotate &= g.nodes[m].opcode != FS_CONCAT;
+    if (rotate) {
+      os << "  const long row_first = (long)blockIdx.x * G + rg, row_first_ld = row_first < R ? row_first : R - 1;\n";
+      for (const ExtTensor& e : gp.ext_in)
+        if (e.kind == KIND_FULL) {
+          os << "  float " << name(e.node, KIND_FULL) << "[E];\n";
+          os << "  fs_load_row<" << e.dtype << ", " << tmpl_row() << ", " << (e.streaming ? "true" : "false") << ">(" << name(e.node, KIND_FULL)
+             << ", a.p[" << e.arg << "], row_first_ld * C, lir, 0);\n";
+        }
+    }
     if (stage_before_loop) emit_staging("  ");
     for (int k = 0; k < K; ++k) {
       const int m = gp.col_reduces[k];
@@ -950,7 +962,9 @@ struct Emitter {
       os << "    const bool rok" << x << " = row" << x << " < R;\n    const long row_ld" << x << " = rok" << x << " ? row" << x
          << " : R - 1;\n    const long row0" << x << " = row_ld" << x << " * C;\n    (void)row0" << x << "; (void)vbase" << x << ";\n";
       for (const ExtTensor& e : gp.ext_in) {
-        if (e.kind == KIND_FULL) {
+        if (e.kind == KIND_FULL && rotate) {
+          // (already in registers: requested before the loop or at the end of the previous trip)
+        } else if (e.kind == KIND_FULL) {
           os << "    float " << name(e.node, KIND_FULL) << x << "[E];\n";
           os << "    fs_load_row<" << e.dtype << ", " << tmpl_row() << ", " << (e.streaming ? "true" : "false") << ">(" << name(e.node, KIND_FULL)
              << x << ", a.p[" << e.arg << "], row0" << x << ", lir, vbase" << x << ");\n";
@@ -1175,6 +1189,14 @@ struct Emitter {
       for (const ExtTensor& e : gp.ext_out)
         if (e.kind != KIND_COLV) roots.push_back(e.node);
       if (!roots.empty()) emit_pass(roots, std::set<int>(roots.begin(), roots.end()), true, []() {});
+    }
+    if (rotate) {
+      os << "    if (it + (int)gridDim.x < a.n_iters) {\n      const long rn = (long)(it + (int)gridDim.x) * G + rg, rnl = rn < R ? rn : R - 1;\n";
+      for (const ExtTensor& e : gp.ext_in)
+        if (e.kind == KIND_FULL)
+          os << "      fs_load_row<" << e.dtype << ", " << tmpl_row() << ", " << (e.streaming ? "true" : "false") << ">(" << name(e.node, KIND_FULL)
+             << ", a.p[" << e.arg << "], rnl * C, lir, 0);\n";
+      os << "    }\n";
     }
     os << "  }\n";
 

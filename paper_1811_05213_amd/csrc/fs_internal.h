@@ -119,6 +119,10 @@ struct Schedule {
   int fan_in = 32;  // column-reduction tree fan-in
   int fold_piece = 0;  // columns that pass through the in-workgroup fold area at a time
   bool stage_rowv = false;  // [1,C] inputs are staged once per workgroup in LDS
+  // Looping workgroups that stage their [1,C] operands before the loop ask for the first trip's rows before the staging
+  // and for the next trip's at the end of a trip (the same registers: the rows are dead by then), so the first memory
+  // round trip overlaps the staging.  Rows of one wavefront and a handful of trips only.
+  bool rotate_loop = false;
   bool tile_transpose = false;  // transposed roots leave through a padded LDS tile
   // Reduction-free groups with transposed roots over wide rows: 2-D tiles.  A workgroup owns G
   // consecutive rows of one column tile of NVL*L*V columns (unit = column tile fastest), so both

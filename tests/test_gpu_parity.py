@@ -392,11 +392,14 @@ def test_looping_workgroups_with_operands_staged_once():
     # trip), rows across 4 wavefronts, exact-fit lane counts (768 bf16 columns: 32 lanes x 3 vectors), a light operand
     from paper_1811_05213_amd import Plan
     from workloads import patterns as survey
-    for rows, cols in ((16391, 1024), (8197, 4096), (32771, 768)):
+    # (one-wavefront rows with up to four trips per workgroup ask for a trip's rows ahead: the first before the staging, the
+    # next at the end of a trip -- [12301,1024]: workgroups with one and with two trips, [30011,1024]: three and four)
+    for rows, cols in ((16391, 1024), (8197, 4096), (32771, 768), (12301, 1024), (30011, 1024), (40003, 1024)):
         g = layernorm_gelu_graph(rows, cols)
         p = Plan(g)
         gi = p.group_info(0)
         assert gi["grid"] * gi["rows_per_iter"] < rows and "fs_stage_rowvec" in p.group_source(0), (rows, cols, gi)
+        assert ("row_first" in p.group_source(0)) == (cols <= 1024 and rows < 40000), (rows, cols)
         p.destroy()
         x = RNG.standard_normal((rows, cols)).astype(np.float32)
         ins = [f32_to_bf16_bits(x)] + [RNG.normal(m, s, (1, cols)).astype(np.float32) for m, s in ((1, .1), (0, .1), (0, .02))]
