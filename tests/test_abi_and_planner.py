@@ -605,6 +605,50 @@ def test_values_needed_by_two_kernels_are_computed_twice_when_that_moves_fewer_b
     u.destroy()
 
 
+def test_tile_order_of_wide_transposes_and_column_tiles_of_column_reductions():
+    from workloads.patterns import colsum, transpose
+    # 2-D transpose tiles are walked in bands of column tiles: 4 KB of a row per band (8 tiles of f32, 16 of bf16), twice
+    # that with 32 row tiles or fewer; no bands where a row has no more tiles than a band
+    for rows, cols, dt, band in ((8192, 8192, "f32", 8), (1024, 65536, "f32", 16), (16384, 4096, "bf16", 16), (65536, 1024, "f32", 0)):
+        p = fs.Plan(transpose(rows, cols, dt))
+        src = p.group_source(0)
+        assert (f"TCB = {band}," in src) if band else ("in_band" not in src), (rows, cols, dt)
+        p.destroy()
+    # column reductions without row reductions: tiles of 64 lanes x 64 bytes from 513 f32 columns on, one fold per tile
+    for rows, cols, dt, elems, tiles in ((16384, 4096, "f32", 16, 4), (8192, 8192, "bf16", 32, 4), (65536, 1024, "f32", 16, 1), (65536, 512, "f32", 8, 1)):
+        p = fs.Plan(colsum(rows, cols, dt))
+        gi = p.group_info(0)
+        assert gi["lanes_per_row"] == 64 and gi["elems_per_lane"] == elems and gi["grid"] == 256, (rows, cols, gi)
+        assert (f"CT = {tiles};" in p.group_source(0)), (rows, cols)
+        p.destroy()
+
+
+def test_which_tensors_are_accessed_non_temporally():
+    # tensors of 32 MiB and more always; from 2 MiB on those no other kernel of the plan touches (a plan input one kernel
+    # reads, a plan output nothing consumes); what several kernels read, and what is smaller, stays cacheable
+    from workloads.patterns import batchnorm
+
+    def flags(plan, k):
+        src = plan.group_source(k)
+        loads = re.findall(r"fs_load_row<\d+, V, NVL, L, NV, RAGGED, (true|false)>\(\w+, a\.p\[(\d+)\]", src)
+        stores = re.findall(r"fs_store_row(?:_vec)?<\d+, V, NVL, L, NV, RAGGED, (true|false)>\(\w+, a\.p\[(\d+)\]", src)
+        return [f for f, _ in loads], [f for f, _ in stores]
+
+    p = fs.Plan(softmax_graph(4096, 1024))      # 16 MiB in, 16 MiB out, one kernel
+    assert flags(p, 0) == (["true"], ["true"])
+    p.destroy()
+    p = fs.Plan(softmax_graph(256, 1024))       # 1 MiB: too small to matter
+    assert flags(p, 0) == (["false"], ["false"])
+    p.destroy()
+    p = fs.Plan(batchnorm(4096, 1024))          # x (16 MiB) is read by all three kernels, y is written by the last
+    assert p.stats()["num_launches"] == 3
+    assert [flags(p, k) for k in range(3)] == [(["false"], []), (["false"], []), (["false"], ["true"])]
+    p.destroy()
+    p = fs.Plan(batchnorm(16384, 1024))         # 64 MiB: beyond the caches whoever reads it
+    assert [flags(p, k)[0] for k in range(3)] == [["true"]] * 3
+    p.destroy()
+
+
 def test_recomputation_never_moves_more_bytes_than_the_same_groups_without_it():
     # random graphs, with and without views: the library's plan against the same grouping given back as the caller's
     # plan (which is taken as it is: every value on a kernel boundary is stored by its producer and read by its consumers)
