@@ -299,6 +299,16 @@ struct Scheduler {
     }
     if (tiled_transpose) {
       NVL = 1;
+      // 2-byte elements: two vectors per lane make the tile's rows 512-byte runs like those of f32 tiles; the tile
+      // (one float per element) then takes 66.5 KB, which two workgroups per CU still fit -- unless the caller set a budget
+      // (bf16 transposes: [32768,8192] 198 -> 182 us, [16384,4096] 49.0 -> 46.9 us; f32 with two vectors: slower; so are
+      // bf16 tensors with few tiles either way: [65536,1024] 49.9 -> 51.5 us, [1000,30000] 37.0 -> 38.0 us, [2048,2048])
+      int es_in = 4;
+      for (const ExtTensor& e : gp->ext_in)
+        if (e.kind == KIND_FULL) es_in = std::min(es_in, dtype_size(e.dtype));
+      if (es_in == 2 && V == 8 && !opt.lds_budget_given && (int64_t)2 * L * V * (tt_rows + 1) * 4 + 1024 <= device_limits().lds_per_workgroup / 2 &&
+          NV >= 16 * L && R >= 4096 && (int64_t)R * C * 2 >= (32ll << 20))
+        NVL = 2;
       CT = (NV + NVL * L - 1) / (NVL * L);
     }
     NVLC = 0, RESV = 0;
@@ -515,7 +525,9 @@ struct Scheduler {
     s.stage_rowv = false;
     s.tile_transpose = false;
     const int tile_bytes = (tiled_transpose ? NVL * L * V : C) * (s.G + 1) * 4;
-    if (has_transposed && (CT == 1 || tiled_transpose) && s.G >= 4 && fixed + std::max(loop_bytes + tile_bytes, fold_bytes) <= opt.lds_budget) {
+    // (the wider tiles of 2-byte transposes may pass the default budget: half of what a CU has, so that two workgroups fit)
+    const int tile_cap = tiled_transpose && NVL == 2 ? device_limits().lds_per_workgroup / 2 : opt.lds_budget;
+    if (has_transposed && (CT == 1 || tiled_transpose) && s.G >= 4 && fixed + std::max(loop_bytes + tile_bytes, fold_bytes) <= tile_cap) {
       s.tile_transpose = true;
       loop_bytes += tile_bytes;
     }
@@ -527,7 +539,7 @@ struct Scheduler {
     }
     const int lds = total();
     s.lds_bytes = s.lds_planned = lds;
-    if (lds > opt.lds_budget)
+    if (lds > (s.tile_transpose ? tile_cap : opt.lds_budget))
       FS_FAIL(FS_ERR_LDS_BUDGET, "group needs %d bytes of LDS, budget is %d", lds, opt.lds_budget);
     // Rows walked in chunks: what is left of the workgroup's LDS may hold the head of the row in its input dtype
     // (one 1024-lane workgroup per compute unit runs such a kernel, so it may take all a workgroup is allowed

@@ -608,8 +608,8 @@ def test_values_needed_by_two_kernels_are_computed_twice_when_that_moves_fewer_b
 def test_tile_order_of_wide_transposes_and_column_tiles_of_column_reductions():
     from workloads.patterns import colsum, transpose
     # 2-D transpose tiles are walked in bands of column tiles: 4 KB of a row per band (8 tiles of f32, 16 of bf16), twice
-    # that with 32 row tiles or fewer; no bands where a row has no more tiles than a band
-    for rows, cols, dt, band in ((8192, 8192, "f32", 8), (1024, 65536, "f32", 16), (16384, 4096, "bf16", 16), (65536, 1024, "f32", 0)):
+    # that with 32 row tiles or fewer (a bf16 tile is 256 columns wide: two vectors per lane); no bands where a row has no more tiles than a band
+    for rows, cols, dt, band in ((8192, 8192, "f32", 8), (1024, 65536, "f32", 16), (16384, 4096, "bf16", 8), (65536, 1024, "f32", 0)):
         p = fs.Plan(transpose(rows, cols, dt))
         src = p.group_source(0)
         assert (f"TCB = {band}," in src) if band else ("in_band" not in src), (rows, cols, dt)

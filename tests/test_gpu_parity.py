@@ -751,6 +751,16 @@ def test_transposes_at_the_sizes_the_survey_times():
         ref, out_s, _ = both_modes(g, [x], f"transpose {rows}x{cols} {dt}")
         got = out_s[0]
         np.testing.assert_array_equal(got.view(x.dtype).reshape(cols, rows), x.T)
+    # bf16 tiles of large tensors are two vectors wide (512-byte rows, a 66.5 KB tile): a fused producer, rows and columns
+    # that end inside a tile
+    from workloads.patterns import bias_transpose
+    rows, cols = 8200, 4104
+    g = expose_bf16_nodes(bias_transpose(rows, cols))  # (the bf16 value also leaves as it is: its roundings are shared with the oracle)
+    p = fs.Plan(g)
+    assert p.stats()["num_launches"] == 1 and p.group_info(0)["elems_per_lane"] == 16 and p.group_info(0)["lds_bytes"] > 65536
+    p.destroy()
+    both_modes(g, [f32_to_bf16_bits(RNG.standard_normal((rows, cols)).astype(np.float32)), RNG.standard_normal((1, cols)).astype(np.float32)],
+               f"bias + transpose bf16 {rows}x{cols}")
 
 
 def test_column_sums_at_the_sizes_the_survey_times():
