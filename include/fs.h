@@ -197,8 +197,11 @@ typedef struct {
                                     node (ignored for INPUT/CONST/BCAST_* nodes, which are inlined into
                                     each consumer): the caller's fusion plan.  Ignored in FS_MODE_UNFUSED. */
   uint32_t mode;                 /* FS_MODE_* */
-  int32_t lds_budget_bytes;      /* per-workgroup LDS limit for one group; 0 => 65536 (of 160 KB per CU);
-                                    at most what fs_device_limits reports for one workgroup */
+  int32_t lds_budget_bytes;      /* per-workgroup LDS limit for one group; at most what fs_device_limits reports for
+                                    one workgroup.  0 => the library's own choice: 65536 (of 160 KB per CU) for most
+                                    kernels; up to half a CU's LDS for the transpose tile of large 2-byte tensors; all
+                                    a workgroup may use for rows walked in chunks with their head kept in LDS (one
+                                    workgroup per CU runs such a kernel).  A value given here binds all of them. */
   const fs_sched_hint* hint;     /* host; may be NULL */
 } fs_graph_desc;
 
