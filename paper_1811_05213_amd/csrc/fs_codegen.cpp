@@ -926,7 +926,11 @@ struct Emitter {
     // then the U bodies run one after the other (more bytes in flight per wavefront).
     // (workgroups that stage their [1,C] operands before the loop read them from LDS inside each tile's body: they
     // may take several tiles per trip too)
-    const int U = ((rowv_in_loop && !stage_before_loop) || s.CT > 1 || ctile) ? 1 : std::max(1, s.U);
+    // ([1,C] values computed by the kernel inside the loop body are declared, and stored by the workgroup of row 0, under the
+    // names of a single tile: such bodies take one tile per trip)
+    bool rowv_member_in_loop = false;
+    for (int m : gp.members) rowv_member_in_loop |= rowv_in_loop && gp.level.at(m) < 0;
+    const int U = ((rowv_in_loop && !stage_before_loop) || s.CT > 1 || ctile || rowv_member_in_loop) ? 1 : std::max(1, s.U);
     if (ctile) {
       os << "  for (int it = rb; it < a.n_iters; it += RB) {\n";
     } else if (U == 1) {

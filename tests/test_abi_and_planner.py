@@ -605,6 +605,21 @@ def test_values_needed_by_two_kernels_are_computed_twice_when_that_moves_fewer_b
     u.destroy()
 
 
+def test_hinted_plans_that_once_failed_to_compile():
+    # several tiles per trip asked for (by hint) around [1,C] values that the kernel computes inside its loop body: the
+    # kernel takes one tile per trip, and its code compiles (plan creation compiles every kernel, no GPU needed)
+    import sys
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from graphgen import random_graph
+    cases = [(6020, 300, 1, True, {"hint": {"lanes_per_row": 8, "wg_threads": 256, "max_workgroups": 1, "tiles_per_trip": 2}, "lds_budget_bytes": 40000, "mode": fs.FS_MODE_LAYERED}),
+             (6064, 65, 63, False, {"hint": {"lanes_per_row": 1, "wg_threads": 0, "max_workgroups": 1, "tiles_per_trip": 2}}),
+             (6098, 128, 96, False, {"hint": {"lanes_per_row": 0, "wg_threads": 256, "max_workgroups": 1, "tiles_per_trip": 4}, "lds_budget_bytes": 40000, "mode": fs.FS_MODE_LAYERED})]
+    for seed, rows, cols, views, kw in cases:
+        p = fs.Plan(random_graph(seed, rows, cols, 40, views=views), **kw)
+        assert p.stats()["num_launches"] >= 1
+        p.destroy()
+
+
 def test_tile_order_of_wide_transposes_and_column_tiles_of_column_reductions():
     from workloads.patterns import colsum, transpose
     # 2-D transpose tiles are walked in bands of column tiles: 4 KB of a row per band (8 tiles of f32, 16 of bf16), twice

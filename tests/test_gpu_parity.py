@@ -883,6 +883,26 @@ def _random_graph_case(seed, rows, cols, num_ops=40, views=False):
     return ill
 
 
+HINTED_CASES = [  # (seed, rows, cols, views, plan arguments): looping workgroups with several tiles per trip around [1,C] values the kernel computes
+    (6020, 300, 1, True, {"hint": {"lanes_per_row": 8, "wg_threads": 256, "max_workgroups": 1, "tiles_per_trip": 2}, "lds_budget_bytes": 40000, "mode": fs.FS_MODE_LAYERED}),
+    (6038, 4096, 260, True, {"hint": {"lanes_per_row": 1, "wg_threads": 0, "max_workgroups": 64, "tiles_per_trip": 4}, "lds_budget_bytes": 40000, "mode": fs.FS_MODE_LAYERED}),
+    (6064, 65, 63, False, {"hint": {"lanes_per_row": 1, "wg_threads": 0, "max_workgroups": 1, "tiles_per_trip": 2}}),
+    (6092, 20000, 130, False, {"hint": {"lanes_per_row": 8, "wg_threads": 0, "max_workgroups": 64, "tiles_per_trip": 2}, "mode": fs.FS_MODE_LAYERED}),
+    (6098, 128, 96, False, {"hint": {"lanes_per_row": 0, "wg_threads": 256, "max_workgroups": 1, "tiles_per_trip": 4}, "lds_budget_bytes": 40000, "mode": fs.FS_MODE_LAYERED}),
+]
+
+
+@pytest.mark.parametrize("seed,rows,cols,views,kw", HINTED_CASES)
+def test_random_graphs_under_hints_that_ask_for_several_tiles_per_trip(seed, rows, cols, views, kw):
+    # a [1,C] value computed inside the loop body is declared (and stored by the workgroup of row 0) under the names of a single
+    # tile: such kernels take one tile per trip whatever the hint says (these five plans once produced code that did not compile)
+    from graphgen import random_graph, random_inputs
+    g = expose_bf16_nodes(random_graph(seed, rows, cols, 40, views=views))
+    ins = random_inputs(g, seed)
+    out = run_graph(g, ins, **kw)
+    check_all(g, out, Reference(g, ins), f"random graph seed {seed} {rows}x{cols} {kw}", max_ill_fraction=0.25)
+
+
 @pytest.mark.parametrize("seed,rows,cols", [(1, 37, 72), (2, 300, 1000), (3, 64, 64), (4, 1000, 36), (5, 5, 3000), (6, 129, 258),
                                             (7, 2048, 128), (8, 16, 4100), (9, 513, 520), (10, 70, 9000), (11, 4099, 8), (12, 260, 264)])
 def test_random_graphs_with_every_op_class(seed, rows, cols):
